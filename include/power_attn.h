@@ -1,0 +1,115 @@
+/*
+ * power_attn.h -- C ABI of the MI355X (gfx950) chunked causal power-attention library.
+ *
+ * The layer (arXiv 2507.04239, Sec. 4 Eq. (7), with the sum-of-scores normalisation of
+ * Sec. 2 "Normalization" / App. E.4), per batch b and head h, for i = 0..T-1:
+ *
+ *     s_ij = scale * (q_i . k_j)            j <= i   (causal, diagonal included)
+ *     N_i  = sum_{j<=i} s_ij^p v_j          Z_i = sum_{j<=i} s_ij^p
+ *     O_i  = N_i / Z_i  (normalize != 0)    or    O_i = N_i  (normalize == 0)
+ *
+ * It is evaluated in the chunked form of Sec. 2 "Chunked form" / App. A and E: the state
+ * S_n = sum_{j < n*chunk} phi(k_j) [v_j, 1]^T over a (tiled) symmetric-power embedding phi
+ * (Lemma 4.2, Sec. 4.1.1) is accumulated chunk by chunk (update-state, App. E.2, plus the
+ * un-gated cumulative sum of App. E.3), read out with phi(q_i) (query-state, App. E.4), and
+ * combined with the attention form inside each chunk (App. E.1).  phi(q), phi(k) exist only
+ * in registers / LDS.  The backward pass (not in the paper) differentiates exactly the
+ * function above.
+ *
+ * All pointers named Q, K, V, O, Z, dO, dQ, dK, dV and `workspace` are DEVICE pointers
+ * (HIP global memory on the current device); `const pa_problem*` and the profiling
+ * arguments are HOST pointers.  Tensors are dense row-major [B, H, T, d] (Q, K, dQ, dK),
+ * [B, H, T, v] (V, O, dO, dV) in `dtype`, and [B, H, T] float32 (Z).  The caller owns
+ * every buffer; the library allocates no device memory, keeps no per-call state and only
+ * enqueues work on `hip_stream` (a hipStream_t passed as void*, NULL = the default
+ * stream); it does not synchronise.  Outputs are overwritten, never accumulated into.
+ * No function throws; all errors are return codes and nothing is launched when
+ * validation fails.
+ */
+#ifndef POWER_ATTN_H
+#define POWER_ATTN_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PA_OK = 0,
+    PA_ERR_INVALID_ARG = 1,   /* null pointer, non-positive size, T % chunk != 0, odd p with normalize, ... */
+    PA_ERR_UNSUPPORTED = 2,   /* a valid problem this build has no kernel for (see pa_problem) */
+    PA_ERR_WORKSPACE   = 3,   /* workspace is NULL or smaller than power_attn_workspace_bytes() */
+    PA_ERR_HIP         = 4    /* a HIP runtime call or kernel launch failed */
+} pa_status;
+
+typedef enum { PA_DTYPE_F32 = 0, PA_DTYPE_BF16 = 1 } pa_dtype;
+
+/* Which kernel family evaluates the problem.  AUTO picks MFMA when it applies. */
+typedef enum {
+    PA_IMPL_AUTO    = 0,
+    PA_IMPL_GENERIC = 1,  /* float32 arithmetic on the vector ALUs; any 1 <= p <= 4, d, v <= 128; both dtypes */
+    PA_IMPL_MFMA    = 2   /* bf16 MFMA with float32 accumulation; bf16 only; p = 2; see power_attn_supported() */
+} pa_impl;
+
+typedef struct {
+    int   B, H, T;      /* batch, heads, sequence length */
+    int   d;            /* query / key head size */
+    int   v;            /* value head size */
+    int   p;            /* degree of the power (Sec. 4 Eq. (7)); even when normalize != 0 */
+    int   chunk;        /* chunk size c of the chunked form; must divide T */
+    int   normalize;    /* 1: divide by the sum of the scores; 0: leave un-normalised */
+    float scale;        /* multiplies q.k before the power ("softmax scaling", App. E.1 step 2) */
+    int   dtype;        /* pa_dtype of Q, K, V, O, dO, dQ, dK, dV; accumulation is always float32 */
+    int   impl;         /* pa_impl */
+} pa_problem;
+
+/* Bytes of device scratch the calls below need for `prob` (0 on an invalid problem).
+ * for_backward = 0: power_attn_fwd; 1: power_attn_bwd. */
+size_t power_attn_workspace_bytes(const pa_problem* prob, int for_backward);
+
+/* PA_OK if `prob` is valid and a kernel family exists for it under prob->impl. */
+pa_status power_attn_supported(const pa_problem* prob);
+
+/* Forward pass.  Writes O [B,H,T,v] and Z [B,H,T] (Z_i = the row's sum of scores, saved for
+ * the backward pass; Z may be NULL when it is not wanted).  A row with Z_i == 0 gets O_i = 0
+ * when normalize != 0 (the paper is silent on it). */
+pa_status power_attn_fwd(const pa_problem* prob,
+                         const void* Q, const void* K, const void* V,
+                         void* O, float* Z,
+                         void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Backward pass: given dO = dL/dO and the forward outputs O, Z of the same problem and
+ * inputs, writes dQ, dK, dV.  (O and Z are read only when normalize != 0.)  Rows with
+ * Z_i == 0 pass no gradient. */
+pa_status power_attn_bwd(const pa_problem* prob,
+                         const void* Q, const void* K, const void* V,
+                         const void* O, const float* Z, const void* dO,
+                         void* dQ, void* dK, void* dV,
+                         void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Expanded state rows the chosen kernel family keeps per head for `prob`: C(d+p-1, p) for
+ * the generic family (Lemma 4.2), C(d/d_tile+p-1, p) * d_tile^p for the tiled one
+ * (Sec. 4.1.1).  0 on an invalid problem. */
+long long power_attn_state_rows(const pa_problem* prob);
+
+const char* power_attn_status_string(pa_status s);
+
+/* Optional per-kernel timing for benchmarks (host-side global switch, not thread-safe).
+ * Between _begin and _end every kernel the library launches is bracketed by a pair of HIP
+ * events on the launch stream; _end waits for them and returns, per kernel name, the number
+ * of launches and the summed elapsed milliseconds.  `out` is a HOST array of `max_entries`
+ * records; the number filled is returned through *n (HOST int). */
+typedef struct {
+    char   name[48];
+    int    launches;
+    float  ms_total;
+} pa_kernel_time;
+
+pa_status power_attn_profile_begin(void);
+pa_status power_attn_profile_end(pa_kernel_time* out, int max_entries, int* n);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* POWER_ATTN_H */

@@ -1,8 +1,193 @@
-# placeholder until the C-ABI library exists
+"""ctypes binding of libpower_attn.so: argument marshalling only.
+
+The functions mirror the C ABI (include/power_attn.h): ``power_attn_fwd`` and
+``power_attn_bwd`` take torch tensors that live on the GPU, pass their device pointers
+and the current HIP stream to the library, and allocate the output tensors and the
+workspace with torch.  No arithmetic of the method happens here.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_NAME = "libpower_attn.so"
+
+PA_DTYPE_F32, PA_DTYPE_BF16 = 0, 1
+PA_IMPL_AUTO, PA_IMPL_GENERIC, PA_IMPL_MFMA = 0, 1, 2
+_IMPL = {"auto": PA_IMPL_AUTO, "generic": PA_IMPL_GENERIC, "mfma": PA_IMPL_MFMA}
+
+EXPORTED_SYMBOLS = (
+    "power_attn_workspace_bytes",
+    "power_attn_supported",
+    "power_attn_fwd",
+    "power_attn_bwd",
+    "power_attn_state_rows",
+    "power_attn_status_string",
+    "power_attn_profile_begin",
+    "power_attn_profile_end",
+)
+
+
 class PowerAttnError(RuntimeError):
     pass
-def library_path(): raise PowerAttnError("not built")
-def load_library(): raise PowerAttnError("not built")
-def power_attn_fwd(*a, **k): raise PowerAttnError("not built")
-def power_attn_bwd(*a, **k): raise PowerAttnError("not built")
-def power_attn_workspace_bytes(*a, **k): raise PowerAttnError("not built")
+
+
+class PaProblem(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int), ("H", ctypes.c_int), ("T", ctypes.c_int), ("d", ctypes.c_int),
+                ("v", ctypes.c_int), ("p", ctypes.c_int), ("chunk", ctypes.c_int), ("normalize", ctypes.c_int),
+                ("scale", ctypes.c_float), ("dtype", ctypes.c_int), ("impl", ctypes.c_int)]
+
+
+class PaKernelTime(ctypes.Structure):
+    _fields_ = [("name", ctypes.c_char * 48), ("launches", ctypes.c_int), ("ms_total", ctypes.c_float)]
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return os.path.join(_HERE, _LIB_NAME)
+
+
+def load_library():
+    """Load the HIP library built in-tree; a missing library is an error (there is no
+    fallback path)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = library_path()
+    if not os.path.exists(path):
+        raise PowerAttnError(f"{path} is missing: build it with `python -c 'import __graft_entry__ as g; g.build()'`")
+    lib = ctypes.CDLL(path)
+    P = ctypes.POINTER(PaProblem)
+    vp = ctypes.c_void_p
+    lib.power_attn_workspace_bytes.restype = ctypes.c_size_t
+    lib.power_attn_workspace_bytes.argtypes = [P, ctypes.c_int]
+    lib.power_attn_supported.restype = ctypes.c_int
+    lib.power_attn_supported.argtypes = [P]
+    lib.power_attn_state_rows.restype = ctypes.c_longlong
+    lib.power_attn_state_rows.argtypes = [P]
+    lib.power_attn_fwd.restype = ctypes.c_int
+    lib.power_attn_fwd.argtypes = [P, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.power_attn_bwd.restype = ctypes.c_int
+    lib.power_attn_bwd.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.power_attn_status_string.restype = ctypes.c_char_p
+    lib.power_attn_status_string.argtypes = [ctypes.c_int]
+    lib.power_attn_profile_begin.restype = ctypes.c_int
+    lib.power_attn_profile_begin.argtypes = []
+    lib.power_attn_profile_end.restype = ctypes.c_int
+    lib.power_attn_profile_end.argtypes = [ctypes.POINTER(PaKernelTime), ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
+    _lib = lib
+    return lib
+
+
+def _check(lib, status: int, what: str):
+    if status != 0:
+        raise PowerAttnError(f"{what}: {lib.power_attn_status_string(status).decode()} (status {status})")
+
+
+def make_problem(B, H, T, d, v, p, chunk, normalize=True, scale=1.0, dtype="bf16", impl="auto") -> PaProblem:
+    return PaProblem(B, H, T, d, v, p, chunk, int(bool(normalize)), float(scale),
+                     PA_DTYPE_BF16 if dtype == "bf16" else PA_DTYPE_F32, _IMPL[impl])
+
+
+def _problem_of(Q, V, p, chunk, normalize, scale, impl) -> PaProblem:
+    import torch
+    if Q.dim() != 4 or V.dim() != 4:
+        raise PowerAttnError("tensors must be [B, H, T, d]")
+    if Q.dtype == torch.bfloat16:
+        dtype = "bf16"
+    elif Q.dtype == torch.float32:
+        dtype = "f32"
+    else:
+        raise PowerAttnError(f"unsupported dtype {Q.dtype}")
+    B, H, T, d = Q.shape
+    return make_problem(B, H, T, d, V.shape[3], p, chunk, normalize, scale, dtype, impl)
+
+
+def _dev_ptr(t, like=None, name="tensor"):
+    if not t.is_cuda:
+        raise PowerAttnError(f"{name} must be on the GPU")
+    if not t.is_contiguous():
+        raise PowerAttnError(f"{name} must be contiguous")
+    if like is not None and (t.dtype != like.dtype or t.device != like.device):
+        raise PowerAttnError(f"{name} must match the dtype and device of Q")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def power_attn_workspace_bytes(prob: PaProblem, for_backward: bool) -> int:
+    return int(load_library().power_attn_workspace_bytes(ctypes.byref(prob), int(for_backward)))
+
+
+def power_attn_state_rows(prob: PaProblem) -> int:
+    return int(load_library().power_attn_state_rows(ctypes.byref(prob)))
+
+
+def _workspace(lib, prob, for_backward, workspace, device):
+    import torch
+    need = int(lib.power_attn_workspace_bytes(ctypes.byref(prob), int(for_backward)))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=device)
+    if workspace.numel() * workspace.element_size() < need:
+        raise PowerAttnError(f"workspace holds {workspace.numel() * workspace.element_size()} bytes, {need} needed")
+    return workspace, need
+
+
+def power_attn_fwd(Q, K, V, p: int, chunk: int, normalize: bool = True, scale: float = 1.0, impl: str = "auto",
+                   workspace=None, out=None, out_z=None):
+    """Forward pass on the current stream.  Returns (O, Z): O like V, Z float32 [B, H, T]."""
+    import torch
+    lib = load_library()
+    prob = _problem_of(Q, V, p, chunk, normalize, scale, impl)
+    _check(lib, lib.power_attn_supported(ctypes.byref(prob)), "power_attn_fwd")
+    with torch.cuda.device(Q.device):
+        O = torch.empty_like(V) if out is None else out
+        Z = torch.empty(Q.shape[:3], dtype=torch.float32, device=Q.device) if out_z is None else out_z
+        workspace, need = _workspace(lib, prob, False, workspace, Q.device)
+        st = lib.power_attn_fwd(ctypes.byref(prob), _dev_ptr(Q, name="Q"), _dev_ptr(K, Q, "K"), _dev_ptr(V, Q, "V"),
+                                _dev_ptr(O, Q, "O"), ctypes.c_void_p(Z.data_ptr()),
+                                ctypes.c_void_p(workspace.data_ptr()), need, _stream())
+    _check(lib, st, "power_attn_fwd")
+    return O, Z
+
+
+def power_attn_bwd(Q, K, V, O, Z, dO, p: int, chunk: int, normalize: bool = True, scale: float = 1.0,
+                   impl: str = "auto", workspace=None, out=None):
+    """Backward pass on the current stream.  Returns (dQ, dK, dV)."""
+    import torch
+    lib = load_library()
+    prob = _problem_of(Q, V, p, chunk, normalize, scale, impl)
+    _check(lib, lib.power_attn_supported(ctypes.byref(prob)), "power_attn_bwd")
+    with torch.cuda.device(Q.device):
+        if out is None:
+            dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+        else:
+            dQ, dK, dV = out
+        workspace, need = _workspace(lib, prob, True, workspace, Q.device)
+        o_ptr = _dev_ptr(O, Q, "O") if O is not None else ctypes.c_void_p(0)
+        z_ptr = ctypes.c_void_p(Z.data_ptr()) if Z is not None else ctypes.c_void_p(0)
+        st = lib.power_attn_bwd(ctypes.byref(prob), _dev_ptr(Q, name="Q"), _dev_ptr(K, Q, "K"), _dev_ptr(V, Q, "V"),
+                                o_ptr, z_ptr, _dev_ptr(dO, Q, "dO"), _dev_ptr(dQ, Q, "dQ"), _dev_ptr(dK, Q, "dK"),
+                                _dev_ptr(dV, Q, "dV"), ctypes.c_void_p(workspace.data_ptr()), need, _stream())
+    _check(lib, st, "power_attn_bwd")
+    return dQ, dK, dV
+
+
+def profile_begin():
+    lib = load_library()
+    _check(lib, lib.power_attn_profile_begin(), "power_attn_profile_begin")
+
+
+def profile_end(max_entries: int = 64):
+    """-> {kernel name: (launches, total ms)} for the kernels launched since profile_begin()."""
+    lib = load_library()
+    arr = (PaKernelTime * max_entries)()
+    n = ctypes.c_int(0)
+    _check(lib, lib.power_attn_profile_end(arr, max_entries, ctypes.byref(n)), "power_attn_profile_end")
+    return {arr[i].name.decode(): (int(arr[i].launches), float(arr[i].ms_total)) for i in range(n.value)}

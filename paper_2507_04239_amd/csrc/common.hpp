@@ -1,0 +1,77 @@
+// Shared host/device helpers of the power-attention library (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "power_attn.h"
+
+namespace pa {
+
+typedef uint16_t bf16_t;  // raw bf16 bit pattern
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// round-to-nearest-even; NaN is kept quiet
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)0x7fc0;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+template <typename T> struct io;
+template <> struct io<float> {
+    static __device__ __forceinline__ float ld(const float* p) { return *p; }
+    static __device__ __forceinline__ void st(float* p, float x) { *p = x; }
+};
+template <> struct io<bf16_t> {
+    static __device__ __forceinline__ float ld(const bf16_t* p) { return bf16_to_f32(*p); }
+    static __device__ __forceinline__ void st(bf16_t* p, float x) { *p = f32_to_bf16(x); }
+};
+
+// ---- launch bookkeeping -------------------------------------------------------------
+// Every kernel goes through launch_end(); when profiling is on, launch_begin/launch_end
+// bracket it with events on the launch stream.
+void profile_before(const char* name, hipStream_t s);
+void profile_after(hipStream_t s);
+bool profile_enabled();
+
+struct LaunchScope {
+    hipStream_t s;
+    bool on;
+    LaunchScope(const char* name, hipStream_t stream) : s(stream), on(profile_enabled()) {
+        if (on) profile_before(name, s);
+    }
+    ~LaunchScope() {
+        if (on) profile_after(s);
+    }
+};
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// ---- kernel families ------------------------------------------------------------------
+struct Ctx {
+    pa_problem prob;
+    hipStream_t stream;
+    char* ws;
+    size_t ws_bytes;
+};
+
+// generic (vector-ALU, float32) family
+size_t generic_workspace_bytes(const pa_problem& pr, bool backward);
+long long generic_state_rows(const pa_problem& pr);
+pa_status generic_supported(const pa_problem& pr);
+pa_status generic_fwd(const Ctx& c, const void* Q, const void* K, const void* V, void* O, float* Z);
+pa_status generic_bwd(const Ctx& c, const void* Q, const void* K, const void* V, const void* O, const float* Z,
+                      const void* dO, void* dQ, void* dK, void* dV);
+
+// bf16 MFMA family (p = 2)
+size_t mfma_workspace_bytes(const pa_problem& pr, bool backward);
+long long mfma_state_rows(const pa_problem& pr);
+pa_status mfma_supported(const pa_problem& pr);
+pa_status mfma_fwd(const Ctx& c, const void* Q, const void* K, const void* V, void* O, float* Z);
+pa_status mfma_bwd(const Ctx& c, const void* Q, const void* K, const void* V, const void* O, const float* Z,
+                   const void* dO, void* dQ, void* dK, void* dV);
+
+}  // namespace pa

@@ -1,0 +1,181 @@
+// C ABI of the power-attention library: argument validation, kernel-family selection and
+// the optional per-kernel event timing.  See include/power_attn.h for the contract.
+#include <string.h>
+
+#include <string>
+#include <vector>
+
+#include "common.hpp"
+
+namespace pa {
+namespace {
+
+struct Record {
+    std::string name;
+    hipEvent_t e0, e1;
+};
+bool g_profile = false;
+std::vector<Record> g_records;
+
+pa_status validate(const pa_problem* pr) {
+    if (pr == nullptr) return PA_ERR_INVALID_ARG;
+    if (pr->B <= 0 || pr->H <= 0 || pr->T <= 0 || pr->d <= 0 || pr->v <= 0 || pr->p <= 0 || pr->chunk <= 0)
+        return PA_ERR_INVALID_ARG;
+    if (pr->T % pr->chunk != 0) return PA_ERR_INVALID_ARG;
+    if (pr->normalize != 0 && (pr->p % 2) != 0) return PA_ERR_INVALID_ARG;  // scores must be positive to normalise
+    if (pr->dtype != PA_DTYPE_F32 && pr->dtype != PA_DTYPE_BF16) return PA_ERR_INVALID_ARG;
+    if (pr->impl != PA_IMPL_AUTO && pr->impl != PA_IMPL_GENERIC && pr->impl != PA_IMPL_MFMA) return PA_ERR_INVALID_ARG;
+    if (!(pr->scale == pr->scale) || pr->scale == 0.f) return PA_ERR_INVALID_ARG;
+    return PA_OK;
+}
+
+// PA_IMPL_GENERIC / PA_IMPL_MFMA, or a negative status
+int choose(const pa_problem& pr, pa_status* why) {
+    if (pr.impl == PA_IMPL_MFMA || pr.impl == PA_IMPL_AUTO) {
+        pa_status st = mfma_supported(pr);
+        if (st == PA_OK) return PA_IMPL_MFMA;
+        if (pr.impl == PA_IMPL_MFMA) {
+            *why = st;
+            return -1;
+        }
+    }
+    pa_status st = generic_supported(pr);
+    if (st == PA_OK) return PA_IMPL_GENERIC;
+    *why = st;
+    return -1;
+}
+
+}  // namespace
+
+bool profile_enabled() { return g_profile; }
+
+void profile_before(const char* name, hipStream_t s) {
+    Record r;
+    r.name = name;
+    if (hipEventCreate(&r.e0) != hipSuccess || hipEventCreate(&r.e1) != hipSuccess) return;
+    (void)hipEventRecord(r.e0, s);
+    g_records.push_back(r);
+}
+
+void profile_after(hipStream_t s) {
+    if (!g_records.empty()) (void)hipEventRecord(g_records.back().e1, s);
+}
+
+}  // namespace pa
+
+using namespace pa;
+
+extern "C" {
+
+const char* power_attn_status_string(pa_status s) {
+    switch (s) {
+        case PA_OK: return "ok";
+        case PA_ERR_INVALID_ARG: return "invalid argument";
+        case PA_ERR_UNSUPPORTED: return "unsupported problem for the requested kernel family";
+        case PA_ERR_WORKSPACE: return "workspace missing or too small";
+        case PA_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+pa_status power_attn_supported(const pa_problem* prob) {
+    pa_status st = validate(prob);
+    if (st != PA_OK) return st;
+    pa_status why = PA_ERR_UNSUPPORTED;
+    return choose(*prob, &why) < 0 ? why : PA_OK;
+}
+
+size_t power_attn_workspace_bytes(const pa_problem* prob, int for_backward) {
+    if (validate(prob) != PA_OK) return 0;
+    pa_status why;
+    int impl = choose(*prob, &why);
+    if (impl < 0) return 0;
+    return impl == PA_IMPL_MFMA ? mfma_workspace_bytes(*prob, for_backward != 0)
+                                : generic_workspace_bytes(*prob, for_backward != 0);
+}
+
+long long power_attn_state_rows(const pa_problem* prob) {
+    if (validate(prob) != PA_OK) return 0;
+    pa_status why;
+    int impl = choose(*prob, &why);
+    if (impl < 0) return 0;
+    return impl == PA_IMPL_MFMA ? mfma_state_rows(*prob) : generic_state_rows(*prob);
+}
+
+pa_status power_attn_fwd(const pa_problem* prob, const void* Q, const void* K, const void* V, void* O, float* Z,
+                         void* workspace, size_t workspace_bytes, void* hip_stream) {
+    pa_status st = validate(prob);
+    if (st != PA_OK) return st;
+    if (Q == nullptr || K == nullptr || V == nullptr || O == nullptr) return PA_ERR_INVALID_ARG;
+    pa_status why = PA_ERR_UNSUPPORTED;
+    int impl = choose(*prob, &why);
+    if (impl < 0) return why;
+    size_t need = impl == PA_IMPL_MFMA ? mfma_workspace_bytes(*prob, false) : generic_workspace_bytes(*prob, false);
+    if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return PA_ERR_WORKSPACE;
+    if (((uintptr_t)workspace & 255u) != 0) return PA_ERR_WORKSPACE;
+    Ctx c{*prob, (hipStream_t)hip_stream, (char*)workspace, workspace_bytes};
+    return impl == PA_IMPL_MFMA ? mfma_fwd(c, Q, K, V, O, Z) : generic_fwd(c, Q, K, V, O, Z);
+}
+
+pa_status power_attn_bwd(const pa_problem* prob, const void* Q, const void* K, const void* V, const void* O,
+                         const float* Z, const void* dO, void* dQ, void* dK, void* dV, void* workspace,
+                         size_t workspace_bytes, void* hip_stream) {
+    pa_status st = validate(prob);
+    if (st != PA_OK) return st;
+    if (Q == nullptr || K == nullptr || V == nullptr || dO == nullptr || dQ == nullptr || dK == nullptr || dV == nullptr)
+        return PA_ERR_INVALID_ARG;
+    if (prob->normalize != 0 && (O == nullptr || Z == nullptr)) return PA_ERR_INVALID_ARG;
+    pa_status why = PA_ERR_UNSUPPORTED;
+    int impl = choose(*prob, &why);
+    if (impl < 0) return why;
+    size_t need = impl == PA_IMPL_MFMA ? mfma_workspace_bytes(*prob, true) : generic_workspace_bytes(*prob, true);
+    if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return PA_ERR_WORKSPACE;
+    if (((uintptr_t)workspace & 255u) != 0) return PA_ERR_WORKSPACE;
+    Ctx c{*prob, (hipStream_t)hip_stream, (char*)workspace, workspace_bytes};
+    return impl == PA_IMPL_MFMA ? mfma_bwd(c, Q, K, V, O, Z, dO, dQ, dK, dV)
+                                : generic_bwd(c, Q, K, V, O, Z, dO, dQ, dK, dV);
+}
+
+pa_status power_attn_profile_begin(void) {
+    for (auto& r : g_records) {
+        (void)hipEventDestroy(r.e0);
+        (void)hipEventDestroy(r.e1);
+    }
+    g_records.clear();
+    g_profile = true;
+    return PA_OK;
+}
+
+pa_status power_attn_profile_end(pa_kernel_time* out, int max_entries, int* n) {
+    g_profile = false;
+    if (n == nullptr || (out == nullptr && max_entries > 0)) return PA_ERR_INVALID_ARG;
+    int filled = 0;
+    pa_status st = PA_OK;
+    for (auto& r : g_records) {
+        float ms = 0.f;
+        if (hipEventSynchronize(r.e1) != hipSuccess || hipEventElapsedTime(&ms, r.e0, r.e1) != hipSuccess) {
+            st = PA_ERR_HIP;
+            continue;
+        }
+        int k = 0;
+        for (; k < filled; ++k)
+            if (r.name == out[k].name) break;
+        if (k == filled) {
+            if (filled >= max_entries) continue;
+            memset(&out[k], 0, sizeof(out[k]));
+            strncpy(out[k].name, r.name.c_str(), sizeof(out[k].name) - 1);
+            ++filled;
+        }
+        out[k].launches += 1;
+        out[k].ms_total += ms;
+    }
+    for (auto& r : g_records) {
+        (void)hipEventDestroy(r.e0);
+        (void)hipEventDestroy(r.e1);
+    }
+    g_records.clear();
+    *n = filled;
+    return st;
+}
+
+}  // extern "C"

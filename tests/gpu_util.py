@@ -1,0 +1,57 @@
+"""Helpers of the GPU parity tests: move seeded inputs to the device, run the library
+through its binding, compare with the float64 oracle."""
+import numpy as np
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}   # relative L2 error per tensor (the bar the benchmark names)
+
+
+def rel_l2(got, want):
+    want = np.asarray(want, dtype=np.float64)
+    got = np.asarray(got, dtype=np.float64)
+    den = np.linalg.norm(want)
+    return float(np.linalg.norm(got - want) / den) if den > 0 else float(np.linalg.norm(got))
+
+
+def max_over_rms(got, want):
+    want = np.asarray(want, dtype=np.float64)
+    got = np.asarray(got, dtype=np.float64)
+    rms = np.sqrt(np.mean(want ** 2))
+    return float(np.abs(got - want).max() / rms) if rms > 0 else float(np.abs(got).max())
+
+
+def to_dev(a, dtype):
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+    return t.to(torch.bfloat16) if dtype == "bf16" else t
+
+
+def to_np(t):
+    return t.detach().float().cpu().numpy()
+
+
+def run_fwd_bwd(Q, K, V, G, p, chunk, dtype, normalize=True, scale=1.0, impl="auto", backward=True):
+    """-> dict of numpy arrays O, Z (and dQ, dK, dV) computed by the HIP library."""
+    import torch
+    from paper_2507_04239_amd import power_attn_bwd, power_attn_fwd
+    tq, tk, tv = (to_dev(a, dtype) for a in (Q, K, V))
+    O, Z = power_attn_fwd(tq, tk, tv, p, chunk, normalize, scale, impl)
+    out = {"O": O, "Z": Z}
+    if backward:
+        tg = to_dev(G, dtype)
+        dQ, dK, dV = power_attn_bwd(tq, tk, tv, O, Z, tg, p, chunk, normalize, scale, impl)
+        out.update(dQ=dQ, dK=dK, dV=dV)
+    torch.cuda.synchronize()
+    return {k: to_np(t) for k, t in out.items()}
+
+
+def assert_close(got: dict, want: dict, dtype: str, what: str, factor: float = 1.0):
+    tol = TOL[dtype] * factor
+    report = {}
+    for name, w in want.items():
+        g = got[name]
+        assert np.isfinite(g).all(), f"{what}: {name} has non-finite values"
+        report[name] = (rel_l2(g, w), max_over_rms(g, w))
+    print(f"{what}: " + " ".join(f"{k}: l2={a:.2e} max/rms={b:.2e}" for k, (a, b) in report.items()), flush=True)
+    bad = {k: e for k, e in report.items() if not e[0] <= tol}
+    assert not bad, f"{what}: relative L2 error above {tol}: {bad}"
+    return report

@@ -1,0 +1,61 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every symbol the header declares,
+validates arguments and sizes workspaces without touching a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2507_04239_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.library_path()):
+        import __graft_entry__ as g
+        g.build()
+    return binding.load_library()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "power_attn.h")).read()
+    declared = set(re.findall(r"\b(power_attn_\w+)\s*\(", header))
+    assert declared == set(binding.EXPORTED_SYMBOLS)
+    for sym in declared:
+        assert getattr(lib, sym) is not None
+
+
+def test_status_strings(lib):
+    assert lib.power_attn_status_string(0) == b"ok"
+    assert b"workspace" in lib.power_attn_status_string(3)
+
+
+def test_validation_and_sizes(lib):
+    ok = binding.make_problem(1, 1, 256, 16, 16, 2, 32, dtype="f32")
+    assert lib.power_attn_supported(ctypes.byref(ok)) == 0
+    assert binding.power_attn_state_rows(ok) == 136
+    assert binding.power_attn_workspace_bytes(ok, True) > binding.power_attn_workspace_bytes(ok, False) > 0
+    bad_chunk = binding.make_problem(1, 1, 256, 16, 16, 2, 48)
+    assert lib.power_attn_supported(ctypes.byref(bad_chunk)) == 1
+    assert binding.power_attn_workspace_bytes(bad_chunk, False) == 0
+    odd_p = binding.make_problem(1, 1, 256, 16, 16, 3, 32, normalize=True)
+    assert lib.power_attn_supported(ctypes.byref(odd_p)) == 1
+    odd_p_unnorm = binding.make_problem(1, 1, 256, 16, 16, 3, 32, normalize=False)
+    assert lib.power_attn_supported(ctypes.byref(odd_p_unnorm)) == 0
+    big_p = binding.make_problem(1, 1, 256, 16, 16, 8, 32)
+    assert lib.power_attn_supported(ctypes.byref(big_p)) == 2
+    # null pointers are rejected before anything is launched (no GPU needed to see that)
+    assert lib.power_attn_fwd(ctypes.byref(ok), None, None, None, None, None, None, 0, None) == 1
+    assert lib.power_attn_fwd(None, None, None, None, None, None, None, 0, None) == 1
+    # a real-looking call with no workspace is refused with the workspace status
+    fake = ctypes.c_void_p(256)
+    assert lib.power_attn_fwd(ctypes.byref(ok), fake, fake, fake, fake, None, None, 0, None) == 3
+
+
+def test_state_rows_match_the_embedding_dimension(lib):
+    import math
+    for d, p in [(16, 2), (32, 4), (12, 3)]:
+        pr = binding.make_problem(1, 1, 64, d, d, p, 32, normalize=(p % 2 == 0), impl="generic")
+        assert binding.power_attn_state_rows(pr) == math.comb(d + p - 1, p)
