@@ -144,6 +144,8 @@ def power_attn_fwd(Q, K, V, p: int, chunk: int, normalize: bool = True, scale: f
     """Forward pass on the current stream.  Returns (O, Z): O like V, Z float32 [B, H, T]."""
     import torch
     lib = load_library()
+    for t, name in ((Q, "Q"), (K, "K"), (V, "V")):
+        _dev_ptr(t, None, name)
     prob = _problem_of(Q, V, p, chunk, normalize, scale, impl)
     _check(lib, lib.power_attn_supported(ctypes.byref(prob)), "power_attn_fwd")
     with torch.cuda.device(Q.device):
@@ -162,6 +164,8 @@ def power_attn_bwd(Q, K, V, O, Z, dO, p: int, chunk: int, normalize: bool = True
     """Backward pass on the current stream.  Returns (dQ, dK, dV)."""
     import torch
     lib = load_library()
+    for t, name in ((Q, "Q"), (K, "K"), (V, "V"), (dO, "dO")):
+        _dev_ptr(t, None, name)
     prob = _problem_of(Q, V, p, chunk, normalize, scale, impl)
     _check(lib, lib.power_attn_supported(ctypes.byref(prob)), "power_attn_bwd")
     with torch.cuda.device(Q.device):
