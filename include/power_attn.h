@@ -68,8 +68,9 @@ typedef struct {
  * for_backward = 0: power_attn_fwd; 1: power_attn_bwd. */
 size_t power_attn_workspace_bytes(const pa_problem* prob, int for_backward);
 
-/* PA_OK if `prob` is valid and a kernel family exists for it under prob->impl. */
-pa_status power_attn_supported(const pa_problem* prob);
+/* PA_OK if `prob` is valid and a kernel family exists under prob->impl for its forward
+ * (for_backward = 0) or backward (1) pass. */
+pa_status power_attn_supported(const pa_problem* prob, int for_backward);
 
 /* Forward pass.  Writes O [B,H,T,v] and Z [B,H,T] (Z_i = the row's sum of scores, saved for
  * the backward pass; Z may be NULL when it is not wanted).  A row with Z_i == 0 gets O_i = 0
@@ -94,6 +95,10 @@ pa_status power_attn_bwd(const pa_problem* prob,
 long long power_attn_state_rows(const pa_problem* prob);
 
 const char* power_attn_status_string(pa_status s);
+
+/* Text of the last HIP error that made a call return PA_ERR_HIP ("" if none); HOST string
+ * owned by the library, valid until the next failing call. */
+const char* power_attn_last_hip_error(void);
 
 /* Optional per-kernel timing for benchmarks (host-side global switch, not thread-safe).
  * Between _begin and _end every kernel the library launches is bracketed by a pair of HIP

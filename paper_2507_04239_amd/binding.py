@@ -24,6 +24,7 @@ EXPORTED_SYMBOLS = (
     "power_attn_bwd",
     "power_attn_state_rows",
     "power_attn_status_string",
+    "power_attn_last_hip_error",
     "power_attn_profile_begin",
     "power_attn_profile_end",
 )
@@ -65,7 +66,7 @@ def load_library():
     lib.power_attn_workspace_bytes.restype = ctypes.c_size_t
     lib.power_attn_workspace_bytes.argtypes = [P, ctypes.c_int]
     lib.power_attn_supported.restype = ctypes.c_int
-    lib.power_attn_supported.argtypes = [P]
+    lib.power_attn_supported.argtypes = [P, ctypes.c_int]
     lib.power_attn_state_rows.restype = ctypes.c_longlong
     lib.power_attn_state_rows.argtypes = [P]
     lib.power_attn_fwd.restype = ctypes.c_int
@@ -74,6 +75,8 @@ def load_library():
     lib.power_attn_bwd.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.power_attn_status_string.restype = ctypes.c_char_p
     lib.power_attn_status_string.argtypes = [ctypes.c_int]
+    lib.power_attn_last_hip_error.restype = ctypes.c_char_p
+    lib.power_attn_last_hip_error.argtypes = []
     lib.power_attn_profile_begin.restype = ctypes.c_int
     lib.power_attn_profile_begin.argtypes = []
     lib.power_attn_profile_end.restype = ctypes.c_int
@@ -84,7 +87,8 @@ def load_library():
 
 def _check(lib, status: int, what: str):
     if status != 0:
-        raise PowerAttnError(f"{what}: {lib.power_attn_status_string(status).decode()} (status {status})")
+        detail = lib.power_attn_last_hip_error().decode() if status == 4 else ""
+        raise PowerAttnError(f"{what}: {lib.power_attn_status_string(status).decode()} (status {status}) {detail}")
 
 
 def make_problem(B, H, T, d, v, p, chunk, normalize=True, scale=1.0, dtype="bf16", impl="auto") -> PaProblem:
@@ -147,7 +151,7 @@ def power_attn_fwd(Q, K, V, p: int, chunk: int, normalize: bool = True, scale: f
     for t, name in ((Q, "Q"), (K, "K"), (V, "V")):
         _dev_ptr(t, None, name)
     prob = _problem_of(Q, V, p, chunk, normalize, scale, impl)
-    _check(lib, lib.power_attn_supported(ctypes.byref(prob)), "power_attn_fwd")
+    _check(lib, lib.power_attn_supported(ctypes.byref(prob), 0), "power_attn_fwd")
     with torch.cuda.device(Q.device):
         O = torch.empty_like(V) if out is None else out
         Z = torch.empty(Q.shape[:3], dtype=torch.float32, device=Q.device) if out_z is None else out_z
@@ -167,7 +171,7 @@ def power_attn_bwd(Q, K, V, O, Z, dO, p: int, chunk: int, normalize: bool = True
     for t, name in ((Q, "Q"), (K, "K"), (V, "V"), (dO, "dO")):
         _dev_ptr(t, None, name)
     prob = _problem_of(Q, V, p, chunk, normalize, scale, impl)
-    _check(lib, lib.power_attn_supported(ctypes.byref(prob)), "power_attn_bwd")
+    _check(lib, lib.power_attn_supported(ctypes.byref(prob), 1), "power_attn_bwd")
     with torch.cuda.device(Q.device):
         if out is None:
             dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)

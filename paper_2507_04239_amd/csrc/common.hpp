@@ -48,6 +48,11 @@ struct LaunchScope {
     }
 };
 
+// true if the launch just issued raised no error; a failure is remembered for
+// power_attn_last_hip_error()
+bool launch_ok();
+void note_hip_error(hipError_t e, const char* where);
+
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // ---- kernel families ------------------------------------------------------------------
@@ -69,7 +74,7 @@ pa_status generic_bwd(const Ctx& c, const void* Q, const void* K, const void* V,
 // bf16 MFMA family (p = 2)
 size_t mfma_workspace_bytes(const pa_problem& pr, bool backward);
 long long mfma_state_rows(const pa_problem& pr);
-pa_status mfma_supported(const pa_problem& pr);
+pa_status mfma_supported(const pa_problem& pr, bool backward);
 pa_status mfma_fwd(const Ctx& c, const void* Q, const void* K, const void* V, void* O, float* Z);
 pa_status mfma_bwd(const Ctx& c, const void* Q, const void* K, const void* V, const void* O, const float* Z,
                    const void* dO, void* dQ, void* dK, void* dV);

@@ -558,12 +558,14 @@ size_t smem_bwd(const pa_problem& pr) {
 template <typename F>
 bool allow_smem(F* fn, size_t bytes) {
     if (bytes <= 48 * 1024) return true;
-    return hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) == hipSuccess;
+    hipError_t e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e != hipSuccess) note_hip_error(e, "hipFuncSetAttribute(max dynamic LDS)");
+    return e == hipSuccess;
 }
 
-#define PA_CHECK_LAUNCH()                              \
-    do {                                               \
-        if (hipGetLastError() != hipSuccess) return PA_ERR_HIP; \
+#define PA_CHECK_LAUNCH()                       \
+    do {                                        \
+        if (!launch_ok()) return PA_ERR_HIP;    \
     } while (0)
 
 template <typename T, int P, int KX>

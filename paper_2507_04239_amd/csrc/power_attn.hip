@@ -1,5 +1,6 @@
 // C ABI of the power-attention library: argument validation, kernel-family selection and
 // the optional per-kernel event timing.  See include/power_attn.h for the contract.
+#include <stdio.h>
 #include <string.h>
 
 #include <string>
@@ -15,6 +16,7 @@ struct Record {
     hipEvent_t e0, e1;
 };
 bool g_profile = false;
+char g_last_error[256] = "";
 std::vector<Record> g_records;
 
 pa_status validate(const pa_problem* pr) {
@@ -30,9 +32,9 @@ pa_status validate(const pa_problem* pr) {
 }
 
 // PA_IMPL_GENERIC / PA_IMPL_MFMA, or a negative status
-int choose(const pa_problem& pr, pa_status* why) {
+int choose(const pa_problem& pr, bool backward, pa_status* why) {
     if (pr.impl == PA_IMPL_MFMA || pr.impl == PA_IMPL_AUTO) {
-        pa_status st = mfma_supported(pr);
+        pa_status st = mfma_supported(pr, backward);
         if (st == PA_OK) return PA_IMPL_MFMA;
         if (pr.impl == PA_IMPL_MFMA) {
             *why = st;
@@ -48,6 +50,17 @@ int choose(const pa_problem& pr, pa_status* why) {
 }  // namespace
 
 bool profile_enabled() { return g_profile; }
+
+void note_hip_error(hipError_t e, const char* where) {
+    snprintf(g_last_error, sizeof(g_last_error), "%s: %s", where, hipGetErrorString(e));
+}
+
+bool launch_ok() {
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) return true;
+    note_hip_error(e, "kernel launch");
+    return false;
+}
 
 void profile_before(const char* name, hipStream_t s) {
     Record r;
@@ -78,17 +91,17 @@ const char* power_attn_status_string(pa_status s) {
     return "unknown status";
 }
 
-pa_status power_attn_supported(const pa_problem* prob) {
+pa_status power_attn_supported(const pa_problem* prob, int for_backward) {
     pa_status st = validate(prob);
     if (st != PA_OK) return st;
     pa_status why = PA_ERR_UNSUPPORTED;
-    return choose(*prob, &why) < 0 ? why : PA_OK;
+    return choose(*prob, for_backward != 0, &why) < 0 ? why : PA_OK;
 }
 
 size_t power_attn_workspace_bytes(const pa_problem* prob, int for_backward) {
     if (validate(prob) != PA_OK) return 0;
     pa_status why;
-    int impl = choose(*prob, &why);
+    int impl = choose(*prob, for_backward != 0, &why);
     if (impl < 0) return 0;
     return impl == PA_IMPL_MFMA ? mfma_workspace_bytes(*prob, for_backward != 0)
                                 : generic_workspace_bytes(*prob, for_backward != 0);
@@ -97,7 +110,7 @@ size_t power_attn_workspace_bytes(const pa_problem* prob, int for_backward) {
 long long power_attn_state_rows(const pa_problem* prob) {
     if (validate(prob) != PA_OK) return 0;
     pa_status why;
-    int impl = choose(*prob, &why);
+    int impl = choose(*prob, false, &why);
     if (impl < 0) return 0;
     return impl == PA_IMPL_MFMA ? mfma_state_rows(*prob) : generic_state_rows(*prob);
 }
@@ -108,11 +121,12 @@ pa_status power_attn_fwd(const pa_problem* prob, const void* Q, const void* K, c
     if (st != PA_OK) return st;
     if (Q == nullptr || K == nullptr || V == nullptr || O == nullptr) return PA_ERR_INVALID_ARG;
     pa_status why = PA_ERR_UNSUPPORTED;
-    int impl = choose(*prob, &why);
+    int impl = choose(*prob, false, &why);
     if (impl < 0) return why;
     size_t need = impl == PA_IMPL_MFMA ? mfma_workspace_bytes(*prob, false) : generic_workspace_bytes(*prob, false);
     if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return PA_ERR_WORKSPACE;
     if (((uintptr_t)workspace & 255u) != 0) return PA_ERR_WORKSPACE;
+    (void)hipGetLastError();  // errors left behind by earlier, unrelated runtime calls are not ours
     Ctx c{*prob, (hipStream_t)hip_stream, (char*)workspace, workspace_bytes};
     return impl == PA_IMPL_MFMA ? mfma_fwd(c, Q, K, V, O, Z) : generic_fwd(c, Q, K, V, O, Z);
 }
@@ -126,15 +140,18 @@ pa_status power_attn_bwd(const pa_problem* prob, const void* Q, const void* K, c
         return PA_ERR_INVALID_ARG;
     if (prob->normalize != 0 && (O == nullptr || Z == nullptr)) return PA_ERR_INVALID_ARG;
     pa_status why = PA_ERR_UNSUPPORTED;
-    int impl = choose(*prob, &why);
+    int impl = choose(*prob, true, &why);
     if (impl < 0) return why;
     size_t need = impl == PA_IMPL_MFMA ? mfma_workspace_bytes(*prob, true) : generic_workspace_bytes(*prob, true);
     if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return PA_ERR_WORKSPACE;
     if (((uintptr_t)workspace & 255u) != 0) return PA_ERR_WORKSPACE;
+    (void)hipGetLastError();
     Ctx c{*prob, (hipStream_t)hip_stream, (char*)workspace, workspace_bytes};
     return impl == PA_IMPL_MFMA ? mfma_bwd(c, Q, K, V, O, Z, dO, dQ, dK, dV)
                                 : generic_bwd(c, Q, K, V, O, Z, dO, dQ, dK, dV);
 }
+
+const char* power_attn_last_hip_error(void) { return g_last_error; }
 
 pa_status power_attn_profile_begin(void) {
     for (auto& r : g_records) {

@@ -34,18 +34,18 @@ def test_status_strings(lib):
 
 def test_validation_and_sizes(lib):
     ok = binding.make_problem(1, 1, 256, 16, 16, 2, 32, dtype="f32")
-    assert lib.power_attn_supported(ctypes.byref(ok)) == 0
+    assert lib.power_attn_supported(ctypes.byref(ok), 1) == 0
     assert binding.power_attn_state_rows(ok) == 136
     assert binding.power_attn_workspace_bytes(ok, True) > binding.power_attn_workspace_bytes(ok, False) > 0
     bad_chunk = binding.make_problem(1, 1, 256, 16, 16, 2, 48)
-    assert lib.power_attn_supported(ctypes.byref(bad_chunk)) == 1
+    assert lib.power_attn_supported(ctypes.byref(bad_chunk), 0) == 1
     assert binding.power_attn_workspace_bytes(bad_chunk, False) == 0
     odd_p = binding.make_problem(1, 1, 256, 16, 16, 3, 32, normalize=True)
-    assert lib.power_attn_supported(ctypes.byref(odd_p)) == 1
+    assert lib.power_attn_supported(ctypes.byref(odd_p), 0) == 1
     odd_p_unnorm = binding.make_problem(1, 1, 256, 16, 16, 3, 32, normalize=False)
-    assert lib.power_attn_supported(ctypes.byref(odd_p_unnorm)) == 0
+    assert lib.power_attn_supported(ctypes.byref(odd_p_unnorm), 1) == 0
     big_p = binding.make_problem(1, 1, 256, 16, 16, 8, 32)
-    assert lib.power_attn_supported(ctypes.byref(big_p)) == 2
+    assert lib.power_attn_supported(ctypes.byref(big_p), 0) == 2
     # null pointers are rejected before anything is launched (no GPU needed to see that)
     assert lib.power_attn_fwd(ctypes.byref(ok), None, None, None, None, None, None, 0, None) == 1
     assert lib.power_attn_fwd(None, None, None, None, None, None, None, 0, None) == 1
