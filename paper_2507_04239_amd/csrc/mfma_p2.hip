@@ -32,6 +32,7 @@ constexpr int NTB = DH / 8;                    // 8-wide feature blocks
 constexpr int NTILES = NTB * (NTB + 1) / 2;    // 36 tiles of 64 expanded rows
 constexpr int TILE_ELEMS = 8 * DH * 8;         // [a][v][b]
 constexpr int QBLK = 128;                      // query rows per workgroup of the chunk kernel
+constexpr int RO_PF = 8;                       // read-out steps kept in flight (72 % RO_PF == 0, even)
 
 __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
@@ -46,124 +47,164 @@ union Frag {
     uint2 h[2];
 };
 
-// ---- [BH][T][DH] -> [BH][DH][T] (bf16) -----------------------------------------------------
+// ---- token-major -> feature-major in blocks of 64 tokens -----------------------------------
+// [BH][T][DH] -> [BH][T/64][DH][64] (bf16).  Each block is 8 KB contiguous, so the readers'
+// accesses stay dense (rows of a plain [DH][T] transpose would sit a power of two apart and
+// pile onto the same memory channel).
+constexpr int TBLK = 64;
+
 __global__ __launch_bounds__(256) void k_transpose(const bf16_t* __restrict__ in, bf16_t* __restrict__ out, int T) {
-    __shared__ bf16_t tile[64][DH + 2];
-    const int bh = blockIdx.y, t0 = blockIdx.x * 64, tid = threadIdx.x;
-    const bf16_t* src = in + ((size_t)bh * T + t0) * DH;
-    for (int e = tid; e < 64 * DH; e += 256) tile[e / DH][e % DH] = src[e];
+    __shared__ bf16_t tile[TBLK][DH + 2];
+    const int bh = blockIdx.y, blk = blockIdx.x, tid = threadIdx.x;
+    const bf16_t* src = in + ((size_t)bh * T + (size_t)blk * TBLK) * DH;
+    for (int e = tid; e < TBLK * DH; e += 256) tile[e / DH][e % DH] = src[e];
     __syncthreads();
-    bf16_t* dst = out + (size_t)bh * DH * T + t0;
-    for (int e = tid; e < 64 * DH; e += 256) {
-        int f = e / 64, t = e % 64;
-        dst[(size_t)f * T + t] = tile[t][f];
-    }
+    bf16_t* dst = out + ((size_t)bh * (T / TBLK) + blk) * DH * TBLK;
+    for (int e = tid; e < TBLK * DH; e += 256) dst[e] = tile[e % TBLK][e / TBLK];
 }
 
 // ---- state scan ----------------------------------------------------------------------------
 // grid (NTILES + 1, BH), 256 threads.  Workgroup `tile` owns the 64 x DH state tile (ti, tj);
-// wave w owns its rows a in {2w, 2w+1}.  Workgroup NTILES owns Gamma.  The state is written
-// every `cs` tokens (before the tokens of that stretch are added).
-__global__ __launch_bounds__(256) void k_mfma_scan(const bf16_t* __restrict__ Kt, const bf16_t* __restrict__ Vt,
-                                                   bf16_t* __restrict__ St, bf16_t* __restrict__ Gam, int T, int cs) {
-    __shared__ __attribute__((aligned(16))) bf16_t Vs[2][DH][72];
+// wave w owns its rows a in {2w, 2w+1}.  Workgroup NTILES owns Gamma = sum k k^T (same code:
+// the A operand is k itself and the B operand comes from K instead of V).  The state is
+// written every `cs` tokens, before the tokens of that stretch are added.  Each workgroup
+// walks the sequence in stages of 64 tokens; the walk is a chain of tiny steps, so the
+// operands of SCAN_PF stages are kept in flight in registers.
+constexpr int SCAN_PF = 8;
+
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also fences global memory,
+// i.e. waits for every outstanding global load, which would drain the register ring below.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+template <bool GAMMA>
+__device__ __forceinline__ void scan_body(const bf16_t* __restrict__ Kt, const bf16_t* __restrict__ Vt,
+                                          bf16_t* __restrict__ St, bf16_t* __restrict__ Gam, int T, int cs,
+                                          bf16_t (*Vs)[DH][72]) {
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int r16 = lane & 15, g = lane >> 4;
     const int tile = blockIdx.x, bh = blockIdx.y;
     const int nstate = T / cs;
-    const bool is_gamma = tile == NTILES;
     int ti = 0, tj = 0;
-    for (int l = 0; l < tile && !is_gamma; ++l) {
-        if (++ti > tj) {
-            ++tj;
-            ti = 0;
+    if (!GAMMA) {
+        for (int l = 0; l < tile; ++l) {
+            if (++ti > tj) {
+                ++tj;
+                ti = 0;
+            }
         }
     }
     const float mult = (ti == tj) ? 1.f : 2.f;
-    // rows this lane expands (tile workgroups) / loads (Gamma workgroup)
-    const int fa = is_gamma ? 16 * w + r16 : 8 * ti + 2 * w + (r16 >> 3);
-    const int fb = 8 * tj + (r16 & 7);
-    const bf16_t* Ka = Kt + ((size_t)bh * DH + fa) * T;
-    const bf16_t* Kb = Kt + ((size_t)bh * DH + fb) * T;
-    const bf16_t* Kg = Kt + ((size_t)bh * DH + r16) * T;   // Gamma: column blocks 16cb + r16
-    const bf16_t* Vb = Vt + (size_t)bh * DH * T;
-    // V staging: thread -> (column, 16 tokens)
+    const int fa = GAMMA ? 16 * w + r16 : 8 * ti + 2 * w + (r16 >> 3);
+    const int fb = GAMMA ? fa : 8 * tj + (r16 & 7);
+    constexpr int STAGE = DH * TBLK;   // elements of one 64-token block of Kt / Vt
+    const bf16_t* Ka = Kt + (size_t)bh * DH * T + fa * TBLK + 8 * g;
+    const bf16_t* Kb = Kt + (size_t)bh * DH * T + fb * TBLK + 8 * g;
+    // B operand staging through LDS: thread -> (column, 16 tokens)
     const int vcol = tid >> 2, vpiece = tid & 3;
+    const bf16_t* Bsrc = (GAMMA ? Kt : Vt) + (size_t)bh * DH * T + vcol * TBLK + 16 * vpiece;
 
     f32x4 acc[4];
 #pragma unroll
     for (int cb = 0; cb < 4; ++cb) acc[cb] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    // Tokens at or after T - cs never feed a state that is written, so the walk stops there.
-    const int nstage = (T - cs) / 64;
-    uint4 vreg[2] = {make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0)};
-    if (!is_gamma && nstage > 0) {
-        const uint4* p = (const uint4*)(Vb + (size_t)vcol * T + 16 * vpiece);
-        vreg[0] = p[0];
-        vreg[1] = p[1];
-    }
-    for (int st = 0; st <= nstage; ++st) {
-        const int tok0 = st * 64;
-        if (tok0 % cs == 0) {
-            const int n = tok0 / cs;
-            if (!is_gamma) {
-                bf16_t* dst = St + ((size_t)(bh * nstate + n) * NTILES + tile) * TILE_ELEMS;
-                const int a = 2 * w + (g >> 1), b0 = 4 * (g & 1);
-#pragma unroll
-                for (int cb = 0; cb < 4; ++cb) {
-                    bf16x4 o;
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) o[r] = (__bf16)(acc[cb][r] * mult);
-                    *(bf16x4*)(dst + ((a * DH + 16 * cb + r16) * 8 + b0)) = o;
-                }
-            } else {
-                bf16_t* dst = Gam + (size_t)(bh * nstate + n) * DH * DH;
-#pragma unroll
-                for (int cb = 0; cb < 4; ++cb)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        dst[(16 * w + 4 * g + r) * DH + 16 * cb + r16] = f32_to_bf16(acc[cb][r]);
-            }
-        }
-        if (st == nstage) break;
-        const int buf = st & 1;
-        if (!is_gamma) {
-            *(uint4*)&Vs[buf][vcol][16 * vpiece] = vreg[0];
-            *(uint4*)&Vs[buf][vcol][16 * vpiece + 8] = vreg[1];
-            if (st + 1 < nstage) {
-                const uint4* p = (const uint4*)(Vb + (size_t)vcol * T + tok0 + 64 + 16 * vpiece);
-                vreg[0] = p[0];
-                vreg[1] = p[1];
-            }
-        }
-        __syncthreads();
-#pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            const int tk = tok0 + 32 * s + 8 * g;
-            Frag af;
-            if (!is_gamma) {
-                const uint4 ka = *(const uint4*)(Ka + tk), kb = *(const uint4*)(Kb + tk);
-                const uint32_t* pa = (const uint32_t*)&ka;
-                const uint32_t* pb = (const uint32_t*)&kb;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    af.v[2 * i] = (__bf16)(bf_lo(pa[i]) * bf_lo(pb[i]));
-                    af.v[2 * i + 1] = (__bf16)(bf_hi(pa[i]) * bf_hi(pb[i]));
-                }
-            } else {
-                af.u = *(const uint4*)(Ka + tk);
-            }
+    auto write_state = [&](int n) {
+        if (!GAMMA) {
+            bf16_t* dst = St + ((size_t)(bh * nstate + n) * NTILES + tile) * TILE_ELEMS;
+            const int a = 2 * w + (g >> 1), b0 = 4 * (g & 1);
 #pragma unroll
             for (int cb = 0; cb < 4; ++cb) {
-                Frag bfr;
-                if (!is_gamma)
-                    bfr.u = *(const uint4*)&Vs[buf][16 * cb + r16][32 * s + 8 * g];
-                else
-                    bfr.u = *(const uint4*)(Kg + (size_t)16 * cb * T + tk);
-                acc[cb] = mfma16(af.v, bfr.v, acc[cb]);
+                bf16x4 o;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) o[r] = (__bf16)(acc[cb][r] * mult);
+                *(bf16x4*)(dst + ((a * DH + 16 * cb + r16) * 8 + b0)) = o;
             }
+        } else {
+            bf16_t* dst = Gam + (size_t)(bh * nstate + n) * DH * DH;
+#pragma unroll
+            for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) dst[(16 * w + 4 * g + r) * DH + 16 * cb + r16] = f32_to_bf16(acc[cb][r]);
         }
+    };
+
+    // Tokens at or after T - cs never feed a state that is written, so the walk stops there.
+    const int nstage = (T - cs) / 64;
+    if (nstage > 0) {
+        // Register ring: slot j holds the operands of stage (st0 + j).  Every load is
+        // unconditional (indices are clamped instead of branching) so that the compiler can
+        // count the loads in flight instead of waiting for all of them.
+        // (separately named registers and macros instead of arrays and lambdas: the slot has
+        // to be a compile-time name or the ring is demoted to scratch memory)
+#define PA_SLOT(J) uint4 ka0_##J, ka1_##J, kb0_##J, kb1_##J, vr0_##J, vr1_##J;
+        PA_SLOT(0) PA_SLOT(1) PA_SLOT(2) PA_SLOT(3) PA_SLOT(4) PA_SLOT(5) PA_SLOT(6) PA_SLOT(7)
+#undef PA_SLOT
+        static_assert(SCAN_PF == 8, "the ring below is written out for 8 slots");
+#define PA_LOAD_STAGE(J, ST)                                                  \
+    {                                                                         \
+        const size_t so_ = (size_t)min((ST), nstage - 1) * STAGE;             \
+        ka0_##J = *(const uint4*)(Ka + so_);                                  \
+        ka1_##J = *(const uint4*)(Ka + so_ + 32);                             \
+        if (!GAMMA) {                                                         \
+            kb0_##J = *(const uint4*)(Kb + so_);                              \
+            kb1_##J = *(const uint4*)(Kb + so_ + 32);                         \
+        }                                                                     \
+        vr0_##J = *(const uint4*)(Bsrc + so_);                                \
+        vr1_##J = *(const uint4*)(Bsrc + so_ + 8);                            \
     }
+#define PA_HALF(J, S, KA, KB)                                                                 \
+    {                                                                                         \
+        Frag af_;                                                                             \
+        if (!GAMMA) {                                                                         \
+            const uint32_t pa_[4] = {KA.x, KA.y, KA.z, KA.w};                                 \
+            const uint32_t pb_[4] = {KB.x, KB.y, KB.z, KB.w};                                 \
+            _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                \
+                af_.v[2 * i_] = (__bf16)(bf_lo(pa_[i_]) * bf_lo(pb_[i_]));                    \
+                af_.v[2 * i_ + 1] = (__bf16)(bf_hi(pa_[i_]) * bf_hi(pb_[i_]));                \
+            }                                                                                 \
+        } else {                                                                              \
+            af_.u = KA;                                                                       \
+        }                                                                                     \
+        _Pragma("unroll") for (int cb_ = 0; cb_ < 4; ++cb_) {                                 \
+            Frag bf_;                                                                         \
+            bf_.u = *(const uint4*)&Vs[(J) & 1][16 * cb_ + r16][32 * (S) + 8 * g];            \
+            acc[cb_] = mfma16(af_.v, bf_.v, acc[cb_]);                                        \
+        }                                                                                     \
+    }
+#define PA_CONSUME(J, ST)                                                                     \
+    if ((ST) < nstage) { /* uniform; no global loads inside this branch */                    \
+        const int tok0_ = (ST) * 64;                                                          \
+        if (tok0_ % cs == 0) write_state(tok0_ / cs);                                         \
+        *(uint4*)&Vs[(J) & 1][vcol][16 * vpiece] = vr0_##J;                                   \
+        *(uint4*)&Vs[(J) & 1][vcol][16 * vpiece + 8] = vr1_##J;                               \
+        lds_barrier();                                                                        \
+        PA_HALF(J, 0, ka0_##J, kb0_##J)                                                       \
+        PA_HALF(J, 1, ka1_##J, kb1_##J)                                                       \
+    }
+#define PA_STEP(J) PA_CONSUME(J, st0 + J) PA_LOAD_STAGE(J, st0 + J + SCAN_PF)
+        PA_LOAD_STAGE(0, 0) PA_LOAD_STAGE(1, 1) PA_LOAD_STAGE(2, 2) PA_LOAD_STAGE(3, 3)
+        PA_LOAD_STAGE(4, 4) PA_LOAD_STAGE(5, 5) PA_LOAD_STAGE(6, 6) PA_LOAD_STAGE(7, 7)
+        for (int st0 = 0; st0 < nstage; st0 += SCAN_PF) {
+            PA_STEP(0) PA_STEP(1) PA_STEP(2) PA_STEP(3) PA_STEP(4) PA_STEP(5) PA_STEP(6) PA_STEP(7)
+        }
+#undef PA_STEP
+#undef PA_CONSUME
+#undef PA_HALF
+#undef PA_LOAD_STAGE
+    }
+    write_state(nstate - 1);   // tok0 = T - cs
+}
+
+__global__ __launch_bounds__(256, 2) void k_mfma_scan(const bf16_t* __restrict__ Kt, const bf16_t* __restrict__ Vt,
+                                                      bf16_t* __restrict__ St, bf16_t* __restrict__ Gam, int T, int cs) {
+    __shared__ __attribute__((aligned(16))) bf16_t Vs[2][DH][72];
+    if (blockIdx.x == NTILES)
+        scan_body<true>(Kt, Vt, St, Gam, T, cs, Vs);
+    else
+        scan_body<false>(Kt, Vt, St, Gam, T, cs, Vs);
 }
 
 // ---- chunk kernel: attention form + read-out + normalise --------------------------------------
@@ -253,7 +294,8 @@ __global__ __launch_bounds__(128) void k_mfma_fwd_chunk(const bf16_t* __restrict
 #pragma unroll
             for (int vb = 0; vb < 4; ++vb) {
                 Frag vf;
-                const bf16_t* vp = Vt + ((size_t)bh * DH + 16 * vb + r16) * T + key0 + 4 * g;
+                const bf16_t* vp = Vt + (size_t)bh * DH * T + (size_t)(key0 / TBLK) * (DH * TBLK) +
+                                   (16 * vb + r16) * TBLK + (key0 % TBLK) + 4 * g;
                 vf.h[0] = *(const uint2*)vp;
                 vf.h[1] = *(const uint2*)(vp + 16);
 #pragma unroll
@@ -280,28 +322,30 @@ __global__ __launch_bounds__(128) void k_mfma_fwd_chunk(const bf16_t* __restrict
             }
         }
         // ---- read-out: O^T += S_n^T phi(q)^T, 72 steps of 32 expanded rows -------------------------
+        // The state of this block is one linear stream (step u = 2 tile + s holds rows a = 4s + g of
+        // the tile); RO_PF steps are kept in flight in registers.
         const bf16_t* Sn = St + (size_t)(bh * nstate + n) * NTILES * TILE_ELEMS + (size_t)g * DH * 8 + r16 * 8;
+        constexpr int STEP_ELEMS = 4 * DH * 8;
+        Frag sf[RO_PF][4];
+#pragma unroll
+        for (int j = 0; j < RO_PF; ++j)
+#pragma unroll
+            for (int vb = 0; vb < 4; ++vb) sf[j][vb].u = *(const uint4*)(Sn + (size_t)j * STEP_ELEMS + 16 * vb * 8);
         int ti = 0, tj = 0;
-        Frag sf[2][4];
+        float qbv[4][8];
+        for (int u0 = 0; u0 < 2 * NTILES; u0 += RO_PF) {
 #pragma unroll
-        for (int vb = 0; vb < 4; ++vb) sf[0][vb].u = *(const uint4*)(Sn + 16 * vb * 8);
-        for (int tile = 0; tile < NTILES; ++tile) {
-            float qbv[4][8];
+            for (int j = 0; j < RO_PF; ++j) {
+                const int u = u0 + j;
+                const int s = j & 1;
+                if (s == 0) {
 #pragma unroll
-            for (int ib = 0; ib < 4; ++ib) {
-                const float4 lo = *(const float4*)&Qs[64 * wv + 16 * ib + r16][8 * tj];
-                const float4 hi = *(const float4*)&Qs[64 * wv + 16 * ib + r16][8 * tj + 4];
-                qbv[ib][0] = lo.x; qbv[ib][1] = lo.y; qbv[ib][2] = lo.z; qbv[ib][3] = lo.w;
-                qbv[ib][4] = hi.x; qbv[ib][5] = hi.y; qbv[ib][6] = hi.z; qbv[ib][7] = hi.w;
-            }
-#pragma unroll
-            for (int s = 0; s < 2; ++s) {
-                // prefetch the next step's state fragments (linear stream: step u = 2 tile + s)
-                const int u = 2 * tile + s;
-                if (u + 1 < 2 * NTILES) {
-#pragma unroll
-                    for (int vb = 0; vb < 4; ++vb)
-                        sf[(s + 1) & 1][vb].u = *(const uint4*)(Sn + (size_t)(u + 1) * 4 * DH * 8 + 16 * vb * 8);
+                    for (int ib = 0; ib < 4; ++ib) {
+                        const float4 lo = *(const float4*)&Qs[64 * wv + 16 * ib + r16][8 * tj];
+                        const float4 hi = *(const float4*)&Qs[64 * wv + 16 * ib + r16][8 * tj + 4];
+                        qbv[ib][0] = lo.x; qbv[ib][1] = lo.y; qbv[ib][2] = lo.z; qbv[ib][3] = lo.w;
+                        qbv[ib][4] = hi.x; qbv[ib][5] = hi.y; qbv[ib][6] = hi.z; qbv[ib][7] = hi.w;
+                    }
                 }
                 Frag pf[4];
 #pragma unroll
@@ -313,11 +357,19 @@ __global__ __launch_bounds__(128) void k_mfma_fwd_chunk(const bf16_t* __restrict
 #pragma unroll
                 for (int vb = 0; vb < 4; ++vb)
 #pragma unroll
-                    for (int ib = 0; ib < 4; ++ib) acc[vb][ib] = mfma16(sf[s & 1][vb].v, pf[ib].v, acc[vb][ib]);
-            }
-            if (++ti > tj) {
-                ++tj;
-                ti = 0;
+                    for (int ib = 0; ib < 4; ++ib) acc[vb][ib] = mfma16(sf[j][vb].v, pf[ib].v, acc[vb][ib]);
+                {   // unconditional (clamped) so that the compiler can count the loads in flight
+                    const int un = min(u + RO_PF, 2 * NTILES - 1);
+#pragma unroll
+                    for (int vb = 0; vb < 4; ++vb)
+                        sf[j][vb].u = *(const uint4*)(Sn + (size_t)un * STEP_ELEMS + 16 * vb * 8);
+                }
+                if (s == 1) {
+                    if (++ti > tj) {
+                        ++tj;
+                        ti = 0;
+                    }
+                }
             }
         }
     }
