@@ -64,12 +64,20 @@ __global__ __launch_bounds__(256) void k_transpose(const bf16_t* __restrict__ in
 }
 
 // ---- state scan ----------------------------------------------------------------------------
+// Fused update-state + cumulative sum over chunks (App. E.2 + E.3, no gating), used for
+//   the forward state     S_n = sum_{j <  n cs}     phi(k_j) v_j^T        (X = K, Y = V)
+//   the state gradient    R_m = sum_{i >= (m+1) cs} phi(q_i) ghat_i^T     (X = Q, Y = dO/Z, REV)
 // grid (NTILES + 1, BH), 256 threads.  Workgroup `tile` owns the 64 x DH state tile (ti, tj);
-// wave w owns its rows a in {2w, 2w+1}.  Workgroup NTILES owns Gamma = sum k k^T (same code:
-// the A operand is k itself and the B operand comes from K instead of V).  The state is
-// written every `cs` tokens, before the tokens of that stretch are added.  Each workgroup
-// walks the sequence in stages of 64 tokens; the walk is a chain of tiny steps, so the
-// operands of SCAN_PF stages are kept in flight in registers.
+// wave w owns its rows a in {2w, 2w+1}.  Workgroup NTILES owns the normaliser in its d x d
+// form: Gamma = sum k k^T, or Omega = sum gz_i q_i q_i^T for the gradient (same code: the A
+// operand is x itself, times the weight, and the B operand comes from X instead of Y).  The
+// state is written every `cs` tokens, before the tokens of that stretch are added.  Each
+// workgroup walks the sequence in stages of 64 tokens; the walk is a chain of tiny steps, so
+// the operands of SCAN_PF stages are kept in flight in registers.
+//
+// Two layouts of a 64-row tile (bf16), chosen by which contraction the reader does:
+//   "C" [a][v][b]   8 expanded rows contiguous: operand of a contraction over rows (read-out)
+//   "R" [row][v]    8 value columns contiguous: operand of a contraction over v (d phi)
 constexpr int SCAN_PF = 8;
 
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() also fences global memory,
@@ -80,14 +88,16 @@ __device__ __forceinline__ void lds_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-template <bool GAMMA>
-__device__ __forceinline__ void scan_body(const bf16_t* __restrict__ Kt, const bf16_t* __restrict__ Vt,
-                                          bf16_t* __restrict__ St, bf16_t* __restrict__ Gam, int T, int cs,
-                                          bf16_t (*Vs)[DH][72]) {
+template <bool GAMMA, bool REV, bool WC, bool WR>
+__device__ __forceinline__ void scan_body(const bf16_t* __restrict__ Xt, const bf16_t* __restrict__ Yt,
+                                          const float* __restrict__ wgt, bf16_t* __restrict__ StC,
+                                          bf16_t* __restrict__ StR, bf16_t* __restrict__ Gam, int T, int cs,
+                                          float out_scale, bf16_t (*Vs)[DH][72]) {
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int r16 = lane & 15, g = lane >> 4;
     const int tile = blockIdx.x, bh = blockIdx.y;
     const int nstate = T / cs;
+    const int nblk = T / TBLK;
     int ti = 0, tj = 0;
     if (!GAMMA) {
         for (int l = 0; l < tile; ++l) {
@@ -97,73 +107,105 @@ __device__ __forceinline__ void scan_body(const bf16_t* __restrict__ Kt, const b
             }
         }
     }
-    const float mult = (ti == tj) ? 1.f : 2.f;
+    const float mult = ((ti == tj) ? 1.f : 2.f) * out_scale;
     const int fa = GAMMA ? 16 * w + r16 : 8 * ti + 2 * w + (r16 >> 3);
     const int fb = GAMMA ? fa : 8 * tj + (r16 & 7);
-    constexpr int STAGE = DH * TBLK;   // elements of one 64-token block of Kt / Vt
-    const bf16_t* Ka = Kt + (size_t)bh * DH * T + fa * TBLK + 8 * g;
-    const bf16_t* Kb = Kt + (size_t)bh * DH * T + fb * TBLK + 8 * g;
+    constexpr int STAGE = DH * TBLK;   // elements of one 64-token block of Xt / Yt
+    const bf16_t* Xa = Xt + (size_t)bh * DH * T + fa * TBLK + 8 * g;
+    const bf16_t* Xb = Xt + (size_t)bh * DH * T + fb * TBLK + 8 * g;
+    const float* Wg = (GAMMA && REV) ? wgt + (size_t)bh * T + 8 * g : nullptr;
     // B operand staging through LDS: thread -> (column, 16 tokens)
     const int vcol = tid >> 2, vpiece = tid & 3;
-    const bf16_t* Bsrc = (GAMMA ? Kt : Vt) + (size_t)bh * DH * T + vcol * TBLK + 16 * vpiece;
+    const bf16_t* Bsrc = (GAMMA ? Xt : Yt) + (size_t)bh * DH * T + vcol * TBLK + 16 * vpiece;
 
-    f32x4 acc[4];
+    f32x4 acc[4], acct[4];   // acc: rows (a,b) x cols v;  acct: its transpose, rows v x cols (a,b)
 #pragma unroll
-    for (int cb = 0; cb < 4; ++cb) acc[cb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int cb = 0; cb < 4; ++cb) {
+        acc[cb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        acct[cb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    }
 
     auto write_state = [&](int n) {
         if (!GAMMA) {
-            bf16_t* dst = St + ((size_t)(bh * nstate + n) * NTILES + tile) * TILE_ELEMS;
-            const int a = 2 * w + (g >> 1), b0 = 4 * (g & 1);
+            if (WC) {
+                bf16_t* dst = StC + ((size_t)(bh * nstate + n) * NTILES + tile) * TILE_ELEMS;
+                const int a = 2 * w + (g >> 1), b0 = 4 * (g & 1);
 #pragma unroll
-            for (int cb = 0; cb < 4; ++cb) {
-                bf16x4 o;
+                for (int cb = 0; cb < 4; ++cb) {
+                    bf16x4 o;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) o[r] = (__bf16)(acc[cb][r] * mult);
-                *(bf16x4*)(dst + ((a * DH + 16 * cb + r16) * 8 + b0)) = o;
+                    for (int r = 0; r < 4; ++r) o[r] = (__bf16)(acc[cb][r] * mult);
+                    *(bf16x4*)(dst + ((a * DH + 16 * cb + r16) * 8 + b0)) = o;
+                }
+            }
+            if (WR) {
+                bf16_t* dst = StR + ((size_t)(bh * nstate + n) * NTILES + tile) * TILE_ELEMS;
+#pragma unroll
+                for (int cb = 0; cb < 4; ++cb) {
+                    bf16x4 o;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) o[r] = (__bf16)(acct[cb][r] * mult);
+                    *(bf16x4*)(dst + ((16 * w + r16) * DH + 16 * cb + 4 * g)) = o;
+                }
             }
         } else {
             bf16_t* dst = Gam + (size_t)(bh * nstate + n) * DH * DH;
 #pragma unroll
             for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) dst[(16 * w + 4 * g + r) * DH + 16 * cb + r16] = f32_to_bf16(acc[cb][r]);
+                for (int r = 0; r < 4; ++r)
+                    dst[(16 * w + 4 * g + r) * DH + 16 * cb + r16] = f32_to_bf16(acc[cb][r] * out_scale);
         }
     };
 
-    // Tokens at or after T - cs never feed a state that is written, so the walk stops there.
+    // Stretches at the far end never feed a state that is written, so the walk stops early.
     const int nstage = (T - cs) / 64;
     if (nstage > 0) {
-        // Register ring: slot j holds the operands of stage (st0 + j).  Every load is
+        // Register ring: slot J holds the operands of stage (st0 + J).  Every load is
         // unconditional (indices are clamped instead of branching) so that the compiler can
-        // count the loads in flight instead of waiting for all of them.
-        // (separately named registers and macros instead of arrays and lambdas: the slot has
-        // to be a compile-time name or the ring is demoted to scratch memory)
-#define PA_SLOT(J) uint4 ka0_##J, ka1_##J, kb0_##J, kb1_##J, vr0_##J, vr1_##J;
+        // count the loads in flight instead of waiting for all of them.  Separately named
+        // registers and macros instead of arrays and lambdas: the slot has to be a
+        // compile-time name or the ring is demoted to scratch memory.
+#define PA_SLOT(J) uint4 ka0_##J, ka1_##J, kb0_##J, kb1_##J, vr0_##J, vr1_##J, w00_##J, w01_##J, w10_##J, w11_##J;
         PA_SLOT(0) PA_SLOT(1) PA_SLOT(2) PA_SLOT(3) PA_SLOT(4) PA_SLOT(5) PA_SLOT(6) PA_SLOT(7)
 #undef PA_SLOT
         static_assert(SCAN_PF == 8, "the ring below is written out for 8 slots");
-#define PA_LOAD_STAGE(J, ST)                                                  \
-    {                                                                         \
-        const size_t so_ = (size_t)min((ST), nstage - 1) * STAGE;             \
-        ka0_##J = *(const uint4*)(Ka + so_);                                  \
-        ka1_##J = *(const uint4*)(Ka + so_ + 32);                             \
-        if (!GAMMA) {                                                         \
-            kb0_##J = *(const uint4*)(Kb + so_);                              \
-            kb1_##J = *(const uint4*)(Kb + so_ + 32);                         \
-        }                                                                     \
-        vr0_##J = *(const uint4*)(Bsrc + so_);                                \
-        vr1_##J = *(const uint4*)(Bsrc + so_ + 8);                            \
+#define PA_LOAD_STAGE(J, ST)                                                              \
+    {                                                                                     \
+        const int sc_ = min((ST), nstage - 1);                                            \
+        const int sidx_ = REV ? nblk - 1 - sc_ : sc_;                                     \
+        const size_t so_ = (size_t)sidx_ * STAGE;                                         \
+        ka0_##J = *(const uint4*)(Xa + so_);                                              \
+        ka1_##J = *(const uint4*)(Xa + so_ + 32);                                         \
+        if (!GAMMA) {                                                                     \
+            kb0_##J = *(const uint4*)(Xb + so_);                                          \
+            kb1_##J = *(const uint4*)(Xb + so_ + 32);                                     \
+        }                                                                                 \
+        if (GAMMA && REV) {                                                               \
+            const float* wp_ = Wg + (size_t)sidx_ * TBLK;                                 \
+            w00_##J = *(const uint4*)(wp_);                                               \
+            w01_##J = *(const uint4*)(wp_ + 4);                                           \
+            w10_##J = *(const uint4*)(wp_ + 32);                                          \
+            w11_##J = *(const uint4*)(wp_ + 36);                                          \
+        }                                                                                 \
+        vr0_##J = *(const uint4*)(Bsrc + so_);                                            \
+        vr1_##J = *(const uint4*)(Bsrc + so_ + 8);                                        \
     }
-#define PA_HALF(J, S, KA, KB)                                                                 \
+#define PA_HALF(J, S, KA, KB, W0, W1)                                                         \
     {                                                                                         \
         Frag af_;                                                                             \
+        const uint32_t pa_[4] = {KA.x, KA.y, KA.z, KA.w};                                     \
         if (!GAMMA) {                                                                         \
-            const uint32_t pa_[4] = {KA.x, KA.y, KA.z, KA.w};                                 \
             const uint32_t pb_[4] = {KB.x, KB.y, KB.z, KB.w};                                 \
             _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                \
                 af_.v[2 * i_] = (__bf16)(bf_lo(pa_[i_]) * bf_lo(pb_[i_]));                    \
                 af_.v[2 * i_ + 1] = (__bf16)(bf_hi(pa_[i_]) * bf_hi(pb_[i_]));                \
+            }                                                                                 \
+        } else if (REV) {                                                                     \
+            const uint32_t pw_[8] = {W0.x, W0.y, W0.z, W0.w, W1.x, W1.y, W1.z, W1.w};         \
+            _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                \
+                af_.v[2 * i_] = (__bf16)(bf_lo(pa_[i_]) * __uint_as_float(pw_[2 * i_]));      \
+                af_.v[2 * i_ + 1] = (__bf16)(bf_hi(pa_[i_]) * __uint_as_float(pw_[2 * i_ + 1])); \
             }                                                                                 \
         } else {                                                                              \
             af_.u = KA;                                                                       \
@@ -171,18 +213,19 @@ __device__ __forceinline__ void scan_body(const bf16_t* __restrict__ Kt, const b
         _Pragma("unroll") for (int cb_ = 0; cb_ < 4; ++cb_) {                                 \
             Frag bf_;                                                                         \
             bf_.u = *(const uint4*)&Vs[(J) & 1][16 * cb_ + r16][32 * (S) + 8 * g];            \
-            acc[cb_] = mfma16(af_.v, bf_.v, acc[cb_]);                                        \
+            if (GAMMA || WC) acc[cb_] = mfma16(af_.v, bf_.v, acc[cb_]);                       \
+            if (!GAMMA && WR) acct[cb_] = mfma16(bf_.v, af_.v, acct[cb_]);                    \
         }                                                                                     \
     }
 #define PA_CONSUME(J, ST)                                                                     \
     if ((ST) < nstage) { /* uniform; no global loads inside this branch */                    \
-        const int tok0_ = (ST) * 64;                                                          \
-        if (tok0_ % cs == 0) write_state(tok0_ / cs);                                         \
+        const int edge_ = REV ? T - (ST) * 64 : (ST) * 64;                                    \
+        if (edge_ % cs == 0) write_state(REV ? edge_ / cs - 1 : edge_ / cs);                  \
         *(uint4*)&Vs[(J) & 1][vcol][16 * vpiece] = vr0_##J;                                   \
         *(uint4*)&Vs[(J) & 1][vcol][16 * vpiece + 8] = vr1_##J;                               \
         lds_barrier();                                                                        \
-        PA_HALF(J, 0, ka0_##J, kb0_##J)                                                       \
-        PA_HALF(J, 1, ka1_##J, kb1_##J)                                                       \
+        PA_HALF(J, 0, ka0_##J, kb0_##J, w00_##J, w01_##J)                                     \
+        PA_HALF(J, 1, ka1_##J, kb1_##J, w10_##J, w11_##J)                                     \
     }
 #define PA_STEP(J) PA_CONSUME(J, st0 + J) PA_LOAD_STAGE(J, st0 + J + SCAN_PF)
         PA_LOAD_STAGE(0, 0) PA_LOAD_STAGE(1, 1) PA_LOAD_STAGE(2, 2) PA_LOAD_STAGE(3, 3)
@@ -195,16 +238,152 @@ __device__ __forceinline__ void scan_body(const bf16_t* __restrict__ Kt, const b
 #undef PA_HALF
 #undef PA_LOAD_STAGE
     }
-    write_state(nstate - 1);   // tok0 = T - cs
+    write_state(REV ? 0 : nstate - 1);
 }
 
-__global__ __launch_bounds__(256, 2) void k_mfma_scan(const bf16_t* __restrict__ Kt, const bf16_t* __restrict__ Vt,
-                                                      bf16_t* __restrict__ St, bf16_t* __restrict__ Gam, int T, int cs) {
+template <bool REV, bool WC, bool WR>
+__global__ __launch_bounds__(256, 2) void k_mfma_scan(const bf16_t* __restrict__ Xt, const bf16_t* __restrict__ Yt,
+                                                      const float* __restrict__ wgt, bf16_t* __restrict__ StC,
+                                                      bf16_t* __restrict__ StR, bf16_t* __restrict__ Gam, int T, int cs,
+                                                      float out_scale) {
     __shared__ __attribute__((aligned(16))) bf16_t Vs[2][DH][72];
     if (blockIdx.x == NTILES)
-        scan_body<true>(Kt, Vt, St, Gam, T, cs, Vs);
+        scan_body<true, REV, WC, WR>(Xt, Yt, wgt, StC, StR, Gam, T, cs, out_scale, Vs);
     else
-        scan_body<false>(Kt, Vt, St, Gam, T, cs, Vs);
+        scan_body<false, REV, WC, WR>(Xt, Yt, wgt, StC, StR, Gam, T, cs, out_scale, Vs);
+}
+
+// ---- read-out: contraction over the expanded rows (query-state, App. E.4) -----------------------
+// acc[vb][ib] (+)= S^T phi(x)^T for the 64 tokens of wave wv: 16 value columns x 16 tokens per
+// block.  `Sn` is one state in layout "C"; `Xs` holds the block's 128 rows of x (float32, already
+// scaled).  The state is one linear stream (step u = 2 tile + s holds rows a = 4s + g of the
+// tile); RO_PF steps are kept in flight in registers, loads unconditional and clamped.
+__device__ __forceinline__ void readout(f32x4 (&acc)[4][4], const bf16_t* __restrict__ Sn,
+                                        const float (*Xs)[DH + 4], int wv, int r16, int g) {
+    Sn += (size_t)g * DH * 8 + r16 * 8;
+    constexpr int STEP_ELEMS = 4 * DH * 8;
+    Frag sf[RO_PF][4];
+#pragma unroll
+    for (int j = 0; j < RO_PF; ++j)
+#pragma unroll
+        for (int vb = 0; vb < 4; ++vb) sf[j][vb].u = *(const uint4*)(Sn + (size_t)j * STEP_ELEMS + 16 * vb * 8);
+    int ti = 0, tj = 0;
+    float xbv[4][8];
+    for (int u0 = 0; u0 < 2 * NTILES; u0 += RO_PF) {
+#pragma unroll
+        for (int j = 0; j < RO_PF; ++j) {
+            const int u = u0 + j;
+            const int s = j & 1;
+            if (s == 0) {
+#pragma unroll
+                for (int ib = 0; ib < 4; ++ib) {
+                    const float4 lo = *(const float4*)&Xs[64 * wv + 16 * ib + r16][8 * tj];
+                    const float4 hi = *(const float4*)&Xs[64 * wv + 16 * ib + r16][8 * tj + 4];
+                    xbv[ib][0] = lo.x; xbv[ib][1] = lo.y; xbv[ib][2] = lo.z; xbv[ib][3] = lo.w;
+                    xbv[ib][4] = hi.x; xbv[ib][5] = hi.y; xbv[ib][6] = hi.z; xbv[ib][7] = hi.w;
+                }
+            }
+            Frag pf[4];
+#pragma unroll
+            for (int ib = 0; ib < 4; ++ib) {
+                const float xa = Xs[64 * wv + 16 * ib + r16][8 * ti + 4 * s + g];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) pf[ib].v[i] = (__bf16)(xa * xbv[ib][i]);
+            }
+#pragma unroll
+            for (int vb = 0; vb < 4; ++vb)
+#pragma unroll
+                for (int ib = 0; ib < 4; ++ib) acc[vb][ib] = mfma16(sf[j][vb].v, pf[ib].v, acc[vb][ib]);
+            {
+                const int un = min(u + RO_PF, 2 * NTILES - 1);
+#pragma unroll
+                for (int vb = 0; vb < 4; ++vb)
+                    sf[j][vb].u = *(const uint4*)(Sn + (size_t)un * STEP_ELEMS + 16 * vb * 8);
+            }
+            if (s == 1) {
+                if (++ti > tj) {
+                    ++tj;
+                    ti = 0;
+                }
+            }
+        }
+    }
+}
+
+// ---- d phi: contraction over the value columns, then the Jacobian of phi ----------------------
+// For the 64 tokens of wave wv and a state `Sn` in layout "R":
+//     A[row, token] = sum_v S[row, v] y[token, v]                      (MFMA)
+//     Dacc[token][8 ti + a] += sum_b A[(a,b)] x[8 tj + b]
+//     Dacc[token][8 tj + b] += sum_a A[(a,b)] x[8 ti + a]              (vector ALU)
+// i.e. Dacc += J_phi(x)^T (S y) for phi(x)_(ti,tj,a,b) = x[8ti+a] x[8tj+b] (the multiplicity of
+// the tile is already in S).  yf[ib][ks] are the B operands y^T (k-slots = v 32 ks + 8 g ..).
+// Dacc rows of this wave's tokens are touched by this wave only.
+__device__ __forceinline__ void dphi_contract(float (*Dacc)[DH + 4], const bf16_t* __restrict__ Sn,
+                                              const Frag (&yf)[4][2], const float (*Xs)[DH + 4], int wv, int r16,
+                                              int g) {
+    const bf16_t* Sl = Sn + (size_t)r16 * DH + 8 * g;
+    int ti = 0, tj = 0;
+    for (int tile = 0; tile < NTILES; ++tile) {
+        float u2[4][4];
+#pragma unroll
+        for (int ib = 0; ib < 4; ++ib)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) u2[ib][r] = 0.f;
+        Frag sf[4][2];
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks)
+                sf[rb][ks].u = *(const uint4*)(Sl + ((size_t)tile * 64 + 16 * rb) * DH + 32 * ks);
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb) {
+            const int a = 2 * rb + (g >> 1);
+#pragma unroll
+            for (int ib = 0; ib < 4; ++ib) {
+                f32x4 c = (f32x4){0.f, 0.f, 0.f, 0.f};
+                c = mfma16(sf[rb][0].v, yf[ib][0].v, c);
+                c = mfma16(sf[rb][1].v, yf[ib][1].v, c);
+                const int tok = 64 * wv + 16 * ib + r16;
+                const float4 xb = *(const float4*)&Xs[tok][8 * tj + 4 * (g & 1)];
+                const float xa = Xs[tok][8 * ti + a];
+                float t1 = c[0] * xb.x + c[1] * xb.y + c[2] * xb.z + c[3] * xb.w;
+                t1 += __shfl_xor(t1, 16);
+                if ((g & 1) == 0) Dacc[tok][8 * ti + a] += t1;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) u2[ib][r] += c[r] * xa;
+            }
+        }
+#pragma unroll
+        for (int ib = 0; ib < 4; ++ib) {
+            const int tok = 64 * wv + 16 * ib + r16;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                float u = u2[ib][r];
+                u += __shfl_xor(u, 32);
+                if ((g >> 1) == 0) Dacc[tok][8 * tj + 4 * (g & 1) + r] += u;
+            }
+        }
+        if (++ti > tj) {
+            ++tj;
+            ti = 0;
+        }
+    }
+}
+
+// stage `scale * X` rows [row0, row0 + 128) as float32 in LDS
+__device__ __forceinline__ void stage_rows_f32(float (*Xs)[DH + 4], const bf16_t* __restrict__ X, size_t row0,
+                                               float scale, int tid) {
+    for (int e = tid; e < QBLK * DH / 8; e += 128) {
+        const int row = e / (DH / 8), c8 = e % (DH / 8);
+        const uint4 raw = *(const uint4*)(X + (row0 + row) * DH + 8 * c8);
+        const uint32_t* pr = (const uint32_t*)&raw;
+        float* dst = &Xs[row][8 * c8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            dst[2 * i] = scale * bf_lo(pr[i]);
+            dst[2 * i + 1] = scale * bf_hi(pr[i]);
+        }
+    }
 }
 
 // ---- chunk kernel: attention form + read-out + normalise --------------------------------------
@@ -321,57 +500,7 @@ __global__ __launch_bounds__(128) void k_mfma_fwd_chunk(const bf16_t* __restrict
                 zsum[ib] += scale * (c[0] * qv.x + c[1] * qv.y + c[2] * qv.z + c[3] * qv.w);
             }
         }
-        // ---- read-out: O^T += S_n^T phi(q)^T, 72 steps of 32 expanded rows -------------------------
-        // The state of this block is one linear stream (step u = 2 tile + s holds rows a = 4s + g of
-        // the tile); RO_PF steps are kept in flight in registers.
-        const bf16_t* Sn = St + (size_t)(bh * nstate + n) * NTILES * TILE_ELEMS + (size_t)g * DH * 8 + r16 * 8;
-        constexpr int STEP_ELEMS = 4 * DH * 8;
-        Frag sf[RO_PF][4];
-#pragma unroll
-        for (int j = 0; j < RO_PF; ++j)
-#pragma unroll
-            for (int vb = 0; vb < 4; ++vb) sf[j][vb].u = *(const uint4*)(Sn + (size_t)j * STEP_ELEMS + 16 * vb * 8);
-        int ti = 0, tj = 0;
-        float qbv[4][8];
-        for (int u0 = 0; u0 < 2 * NTILES; u0 += RO_PF) {
-#pragma unroll
-            for (int j = 0; j < RO_PF; ++j) {
-                const int u = u0 + j;
-                const int s = j & 1;
-                if (s == 0) {
-#pragma unroll
-                    for (int ib = 0; ib < 4; ++ib) {
-                        const float4 lo = *(const float4*)&Qs[64 * wv + 16 * ib + r16][8 * tj];
-                        const float4 hi = *(const float4*)&Qs[64 * wv + 16 * ib + r16][8 * tj + 4];
-                        qbv[ib][0] = lo.x; qbv[ib][1] = lo.y; qbv[ib][2] = lo.z; qbv[ib][3] = lo.w;
-                        qbv[ib][4] = hi.x; qbv[ib][5] = hi.y; qbv[ib][6] = hi.z; qbv[ib][7] = hi.w;
-                    }
-                }
-                Frag pf[4];
-#pragma unroll
-                for (int ib = 0; ib < 4; ++ib) {
-                    const float qa = Qs[64 * wv + 16 * ib + r16][8 * ti + 4 * s + g];
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) pf[ib].v[i] = (__bf16)(qa * qbv[ib][i]);
-                }
-#pragma unroll
-                for (int vb = 0; vb < 4; ++vb)
-#pragma unroll
-                    for (int ib = 0; ib < 4; ++ib) acc[vb][ib] = mfma16(sf[j][vb].v, pf[ib].v, acc[vb][ib]);
-                {   // unconditional (clamped) so that the compiler can count the loads in flight
-                    const int un = min(u + RO_PF, 2 * NTILES - 1);
-#pragma unroll
-                    for (int vb = 0; vb < 4; ++vb)
-                        sf[j][vb].u = *(const uint4*)(Sn + (size_t)un * STEP_ELEMS + 16 * vb * 8);
-                }
-                if (s == 1) {
-                    if (++ti > tj) {
-                        ++tj;
-                        ti = 0;
-                    }
-                }
-            }
-        }
+        readout(acc, St + (size_t)(bh * nstate + n) * NTILES * TILE_ELEMS, Qs, wv, r16, g);
     }
 
     // ---- normalise and store ------------------------------------------------------------------
@@ -393,30 +522,381 @@ __global__ __launch_bounds__(128) void k_mfma_fwd_chunk(const bf16_t* __restrict
     }
 }
 
+// ---- backward: preparation -----------------------------------------------------------------------
+// ghat = dO / Z (bf16, [BH][T][DH]) and gz = -(dO . O) / Z (float32, [BH][T]); un-normalised:
+// ghat = dO, gz = 0.  Rows with Z == 0 give zeros.  One 16-lane group per row.
+__global__ __launch_bounds__(256) void k_mfma_bwd_prep(const bf16_t* __restrict__ dO, const bf16_t* __restrict__ O,
+                                                       const float* __restrict__ Z, bf16_t* __restrict__ Gh,
+                                                       float* __restrict__ gz, long long rows, int normalize) {
+    const long long row = (long long)blockIdx.x * 16 + (threadIdx.x >> 4);
+    const int c4 = threadIdx.x & 15;
+    if (row >= rows) return;
+    const uint2 graw = *(const uint2*)(dO + row * DH + 4 * c4);
+    float gv[4] = {bf_lo(graw.x), bf_hi(graw.x), bf_lo(graw.y), bf_hi(graw.y)};
+    float inv = 1.f, delta = 0.f;
+    if (normalize) {
+        const uint2 oraw = *(const uint2*)(O + row * DH + 4 * c4);
+        delta = gv[0] * bf_lo(oraw.x) + gv[1] * bf_hi(oraw.x) + gv[2] * bf_lo(oraw.y) + gv[3] * bf_hi(oraw.y);
+        delta += __shfl_xor(delta, 1);
+        delta += __shfl_xor(delta, 2);
+        delta += __shfl_xor(delta, 4);
+        delta += __shfl_xor(delta, 8);
+        const float z = Z[row];
+        inv = z != 0.f ? 1.f / z : 0.f;
+    }
+    bf16x4 o;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) o[i] = (__bf16)(gv[i] * inv);
+    *(bf16x4*)(Gh + row * DH + 4 * c4) = o;
+    if (c4 == 0) gz[row] = normalize ? -delta * inv : 0.f;
+}
+
+// ---- backward, queries: dQ ------------------------------------------------------------------------
+// grid (T / 128, BH), 128 threads; wave wv owns query rows [64 wv, 64 wv + 64) of the block.
+//   dq_i = scale * [ sum_{j<=i, same stretch} t_ij k_j + 2 gz_i Gamma q~_i + J_phi(q~_i)^T (S_n ghat_i) ]
+//   q~ = scale q,  s_ij = q~_i . k_j,  t_ij = 2 s_ij (ghat_i . v_j + gz_i)
+// acc[fb][ib] holds the attention-form part transposed (16 features x 16 queries); the state part
+// is accumulated in LDS (Dacc).
+__global__ __launch_bounds__(128) void k_mfma_bwd_dq(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
+                                                     const bf16_t* __restrict__ V, const bf16_t* __restrict__ Gh,
+                                                     const float* __restrict__ gz, const bf16_t* __restrict__ Kt,
+                                                     const bf16_t* __restrict__ StR, const bf16_t* __restrict__ Gam,
+                                                     bf16_t* __restrict__ dQ, int T, int cs, float scale) {
+    __shared__ __attribute__((aligned(16))) float Qs[QBLK][DH + 4];
+    __shared__ __attribute__((aligned(16))) float Dacc[QBLK][DH + 4];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int r16 = lane & 15, g = lane >> 4;
+    const int qb = blockIdx.x, bh = blockIdx.y;
+    const int i0 = qb * QBLK;
+    const int n = i0 / cs;
+    const int nstate = T / cs;
+    const size_t head_tok = (size_t)bh * T;
+
+    stage_rows_f32(Qs, Q, head_tok + i0, scale, tid);
+    for (int e = tid; e < QBLK * (DH + 4); e += 128) (&Dacc[0][0])[e] = 0.f;
+    Frag qf[4][2], gf[4][2];
+    float gzq[4];
+#pragma unroll
+    for (int ib = 0; ib < 4; ++ib) {
+        const size_t row = head_tok + i0 + 64 * wv + 16 * ib + r16;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            qf[ib][ks].u = *(const uint4*)(Q + row * DH + 32 * ks + 8 * g);
+            gf[ib][ks].u = *(const uint4*)(Gh + row * DH + 32 * ks + 8 * g);
+        }
+        gzq[ib] = gz[row];
+    }
+    f32x4 acc[4][4];
+#pragma unroll
+    for (int fb = 0; fb < 4; ++fb)
+#pragma unroll
+        for (int ib = 0; ib < 4; ++ib) acc[fb][ib] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    __syncthreads();
+
+    const int key_lo = n * cs;
+    for (int kb0 = key_lo; kb0 <= i0; kb0 += QBLK) {
+        const bool diag = kb0 == i0;
+        const int nsteps = diag ? 2 * (wv + 1) : 4;
+        for (int s = 0; s < nsteps; ++s) {
+            const int key0 = kb0 + 32 * s;
+            f32x4 sc[2][4], ec[2][4];
+#pragma unroll
+            for (int jb = 0; jb < 2; ++jb) {
+                Frag kf[2], vf[2];
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks) {
+                    kf[ks].u = *(const uint4*)(K + (head_tok + key0 + 16 * jb + r16) * DH + 32 * ks + 8 * g);
+                    vf[ks].u = *(const uint4*)(V + (head_tok + key0 + 16 * jb + r16) * DH + 32 * ks + 8 * g);
+                }
+#pragma unroll
+                for (int ib = 0; ib < 4; ++ib) {
+                    f32x4 c = (f32x4){0.f, 0.f, 0.f, 0.f};
+                    c = mfma16(kf[0].v, qf[ib][0].v, c);
+                    c = mfma16(kf[1].v, qf[ib][1].v, c);
+                    sc[jb][ib] = c;
+                    f32x4 e = (f32x4){0.f, 0.f, 0.f, 0.f};
+                    e = mfma16(vf[0].v, gf[ib][0].v, e);
+                    e = mfma16(vf[1].v, gf[ib][1].v, e);
+                    ec[jb][ib] = e;
+                }
+            }
+            Frag tf[4];
+#pragma unroll
+            for (int ib = 0; ib < 4; ++ib) {
+                const int qrow = i0 + 64 * wv + 16 * ib + r16;
+#pragma unroll
+                for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        float tv = 2.f * scale * sc[jb][ib][r] * (ec[jb][ib][r] + gzq[ib]);
+                        if (diag && key0 + 16 * jb + 4 * g + r > qrow) tv = 0.f;
+                        tf[ib].v[4 * jb + r] = (__bf16)tv;
+                    }
+            }
+#pragma unroll
+            for (int fb = 0; fb < 4; ++fb) {
+                Frag ktf;
+                const bf16_t* kp = Kt + (size_t)bh * DH * T + (size_t)(key0 / TBLK) * (DH * TBLK) +
+                                   (16 * fb + r16) * TBLK + (key0 % TBLK) + 4 * g;
+                ktf.h[0] = *(const uint2*)kp;
+                ktf.h[1] = *(const uint2*)(kp + 16);
+#pragma unroll
+                for (int ib = 0; ib < 4; ++ib) acc[fb][ib] = mfma16(ktf.v, tf[ib].v, acc[fb][ib]);
+            }
+        }
+    }
+
+    if (n > 0) {
+        // normaliser: d/dq~ of gz q~^T Gamma q~ = 2 gz Gamma q~
+        const bf16_t* Gn = Gam + (size_t)(bh * nstate + n) * DH * DH;
+#pragma unroll
+        for (int ab = 0; ab < 4; ++ab) {
+            Frag gm[2];
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) gm[ks].u = *(const uint4*)(Gn + (16 * ab + r16) * DH + 32 * ks + 8 * g);
+#pragma unroll
+            for (int ib = 0; ib < 4; ++ib) {
+                f32x4 c = (f32x4){0.f, 0.f, 0.f, 0.f};
+                c = mfma16(gm[0].v, qf[ib][0].v, c);
+                c = mfma16(gm[1].v, qf[ib][1].v, c);
+                const int tok = 64 * wv + 16 * ib + r16;
+                const float f = 2.f * gzq[ib] * scale;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) Dacc[tok][16 * ab + 4 * g + r] += f * c[r];
+            }
+        }
+        dphi_contract(Dacc, StR + (size_t)(bh * nstate + n) * NTILES * TILE_ELEMS, gf, Qs, wv, r16, g);
+    }
+#pragma unroll
+    for (int fb = 0; fb < 4; ++fb)
+#pragma unroll
+        for (int ib = 0; ib < 4; ++ib)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) Dacc[64 * wv + 16 * ib + r16][16 * fb + 4 * g + r] += acc[fb][ib][r];
+    __syncthreads();
+    for (int e = tid; e < QBLK * DH / 4; e += 128) {
+        const int row = e / (DH / 4), c4 = e % (DH / 4);
+        const float4 v4 = *(const float4*)&Dacc[row][4 * c4];
+        bf16x4 o;
+        o[0] = (__bf16)(scale * v4.x); o[1] = (__bf16)(scale * v4.y);
+        o[2] = (__bf16)(scale * v4.z); o[3] = (__bf16)(scale * v4.w);
+        *(bf16x4*)(dQ + (head_tok + i0 + row) * DH + 4 * c4) = o;
+    }
+}
+
+// ---- backward, keys / values: dK, dV ----------------------------------------------------------------
+// grid (T / 128, BH), 128 threads; wave wv owns key rows [64 wv, 64 wv + 64) of the block.
+//   dv_j = sum_{i>=j, same stretch} s_ij^2 ghat_i + R_m^T phi(k_j)
+//   dk_j = scale * sum_i t_ij q_i + 2 Omega_m k_j + J_phi(k_j)^T (R_m v_j)
+// (R and Omega already carry scale^2).  accK / accV hold the attention-form parts transposed
+// (16 features x 16 keys); the d phi part of dK is accumulated in LDS (Dacc).
+__global__ __launch_bounds__(128) void k_mfma_bwd_dkdv(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
+                                                       const bf16_t* __restrict__ V, const bf16_t* __restrict__ Gh,
+                                                       const float* __restrict__ gz, const bf16_t* __restrict__ Qt,
+                                                       const bf16_t* __restrict__ Ght, const bf16_t* __restrict__ RtC,
+                                                       const bf16_t* __restrict__ RtR, const bf16_t* __restrict__ Omg,
+                                                       bf16_t* __restrict__ dK, bf16_t* __restrict__ dV, int T, int cs,
+                                                       float scale) {
+    __shared__ __attribute__((aligned(16))) float Ks[QBLK][DH + 4];
+    __shared__ __attribute__((aligned(16))) float Dacc[QBLK][DH + 4];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int r16 = lane & 15, g = lane >> 4;
+    const int kb = blockIdx.x, bh = blockIdx.y;
+    const int j0 = kb * QBLK;
+    const int m = j0 / cs;
+    const int nstate = T / cs;
+    const size_t head_tok = (size_t)bh * T;
+
+    stage_rows_f32(Ks, K, head_tok + j0, 1.f, tid);
+    for (int e = tid; e < QBLK * (DH + 4); e += 128) (&Dacc[0][0])[e] = 0.f;
+    Frag kf[4][2], vf[4][2];   // K^T and V^T of this wave's keys as B operands
+#pragma unroll
+    for (int jb = 0; jb < 4; ++jb) {
+        const size_t row = head_tok + j0 + 64 * wv + 16 * jb + r16;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            kf[jb][ks].u = *(const uint4*)(K + row * DH + 32 * ks + 8 * g);
+            vf[jb][ks].u = *(const uint4*)(V + row * DH + 32 * ks + 8 * g);
+        }
+    }
+    f32x4 accK[4][4], accV[4][4];
+#pragma unroll
+    for (int fb = 0; fb < 4; ++fb)
+#pragma unroll
+        for (int jb = 0; jb < 4; ++jb) {
+            accK[fb][jb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+            accV[fb][jb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        }
+    __syncthreads();
+
+    const int q_hi = (m + 1) * cs;   // queries of the same stretch, from the diagonal block on
+    for (int qb0 = j0; qb0 < q_hi; qb0 += QBLK) {
+        const bool diag = qb0 == j0;
+        const int s_lo = diag ? 2 * wv : 0;    // queries before this wave's first key are masked
+        for (int s = s_lo; s < 4; ++s) {
+            const int q0 = qb0 + 32 * s;
+            f32x4 sc[2][4], ec[2][4];
+            float gzr[2][4];
+#pragma unroll
+            for (int ibq = 0; ibq < 2; ++ibq) {
+                Frag qa[2], ga[2];
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks) {
+                    qa[ks].u = *(const uint4*)(Q + (head_tok + q0 + 16 * ibq + r16) * DH + 32 * ks + 8 * g);
+                    ga[ks].u = *(const uint4*)(Gh + (head_tok + q0 + 16 * ibq + r16) * DH + 32 * ks + 8 * g);
+                }
+                const float4 gz4 = *(const float4*)(gz + head_tok + q0 + 16 * ibq + 4 * g);
+                gzr[ibq][0] = gz4.x; gzr[ibq][1] = gz4.y; gzr[ibq][2] = gz4.z; gzr[ibq][3] = gz4.w;
+#pragma unroll
+                for (int jb = 0; jb < 4; ++jb) {
+                    f32x4 c = (f32x4){0.f, 0.f, 0.f, 0.f};
+                    c = mfma16(qa[0].v, kf[jb][0].v, c);
+                    c = mfma16(qa[1].v, kf[jb][1].v, c);
+                    sc[ibq][jb] = c;
+                    f32x4 e = (f32x4){0.f, 0.f, 0.f, 0.f};
+                    e = mfma16(ga[0].v, vf[jb][0].v, e);
+                    e = mfma16(ga[1].v, vf[jb][1].v, e);
+                    ec[ibq][jb] = e;
+                }
+            }
+            Frag tf[4], af[4];
+#pragma unroll
+            for (int jb = 0; jb < 4; ++jb) {
+                const int krow = j0 + 64 * wv + 16 * jb + r16;
+#pragma unroll
+                for (int ibq = 0; ibq < 2; ++ibq)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const float sv = scale * sc[ibq][jb][r];
+                        float tv = 2.f * sv * (ec[ibq][jb][r] + gzr[ibq][r]);
+                        float av = sv * sv;
+                        if (diag && q0 + 16 * ibq + 4 * g + r < krow) {
+                            tv = 0.f;
+                            av = 0.f;
+                        }
+                        tf[jb].v[4 * ibq + r] = (__bf16)tv;
+                        af[jb].v[4 * ibq + r] = (__bf16)av;
+                    }
+            }
+            const size_t blk_off = (size_t)bh * DH * T + (size_t)(q0 / TBLK) * (DH * TBLK) + (q0 % TBLK) + 4 * g;
+#pragma unroll
+            for (int fb = 0; fb < 4; ++fb) {
+                Frag qtf, gtf;
+                const bf16_t* qp = Qt + blk_off + (16 * fb + r16) * TBLK;
+                const bf16_t* gp = Ght + blk_off + (16 * fb + r16) * TBLK;
+                qtf.h[0] = *(const uint2*)qp;
+                qtf.h[1] = *(const uint2*)(qp + 16);
+                gtf.h[0] = *(const uint2*)gp;
+                gtf.h[1] = *(const uint2*)(gp + 16);
+#pragma unroll
+                for (int jb = 0; jb < 4; ++jb) {
+                    accK[fb][jb] = mfma16(qtf.v, tf[jb].v, accK[fb][jb]);
+                    accV[fb][jb] = mfma16(gtf.v, af[jb].v, accV[fb][jb]);
+                }
+            }
+        }
+    }
+    // attention-form part of dK carries one more factor scale (d s / d k = scale q)
+#pragma unroll
+    for (int fb = 0; fb < 4; ++fb)
+#pragma unroll
+        for (int jb = 0; jb < 4; ++jb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) accK[fb][jb][r] *= scale;
+
+    if (m < nstate - 1) {
+        const bf16_t* Om = Omg + (size_t)(bh * nstate + m) * DH * DH;
+#pragma unroll
+        for (int ab = 0; ab < 4; ++ab) {
+            Frag gm[2];
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) gm[ks].u = *(const uint4*)(Om + (16 * ab + r16) * DH + 32 * ks + 8 * g);
+#pragma unroll
+            for (int jb = 0; jb < 4; ++jb) {
+                f32x4 c = (f32x4){0.f, 0.f, 0.f, 0.f};
+                c = mfma16(gm[0].v, kf[jb][0].v, c);
+                c = mfma16(gm[1].v, kf[jb][1].v, c);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) accK[ab][jb][r] += 2.f * c[r];
+            }
+        }
+        readout(accV, RtC + (size_t)(bh * nstate + m) * NTILES * TILE_ELEMS, Ks, wv, r16, g);
+        dphi_contract(Dacc, RtR + (size_t)(bh * nstate + m) * NTILES * TILE_ELEMS, vf, Ks, wv, r16, g);
+    }
+#pragma unroll
+    for (int fb = 0; fb < 4; ++fb)
+#pragma unroll
+        for (int jb = 0; jb < 4; ++jb) {
+            const size_t row = head_tok + j0 + 64 * wv + 16 * jb + r16;
+            bf16x4 o;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                Dacc[64 * wv + 16 * jb + r16][16 * fb + 4 * g + r] += accK[fb][jb][r];
+                o[r] = (__bf16)accV[fb][jb][r];
+            }
+            *(bf16x4*)(dV + row * DH + 16 * fb + 4 * g) = o;
+        }
+    __syncthreads();
+    for (int e = tid; e < QBLK * DH / 4; e += 128) {
+        const int row = e / (DH / 4), c4 = e % (DH / 4);
+        const float4 v4 = *(const float4*)&Dacc[row][4 * c4];
+        bf16x4 o;
+        o[0] = (__bf16)v4.x; o[1] = (__bf16)v4.y; o[2] = (__bf16)v4.z; o[3] = (__bf16)v4.w;
+        *(bf16x4*)(dK + (head_tok + j0 + row) * DH + 4 * c4) = o;
+    }
+}
+
 struct Layout {
     int cs, nstate;
-    size_t off_kt, off_vt, off_st, off_gam, total;
+    size_t off_kt, off_vt, off_sc, off_gam;                              // forward
+    size_t off_qt, off_gh, off_ght, off_gz, off_sr, off_rc, off_rr, off_omg;  // backward only
+    size_t total;
 };
 
 Layout make_layout(const pa_problem& pr, bool backward) {
-    Layout L;
+    Layout L{};
     L.cs = pr.chunk;
     L.nstate = pr.T / L.cs;
     const size_t BH = (size_t)pr.B * pr.H;
+    const size_t tok = BH * pr.T * DH * 2;
+    const size_t st = BH * L.nstate * (size_t)NTILES * TILE_ELEMS * 2;
+    const size_t gm = BH * L.nstate * (size_t)DH * DH * 2;
     size_t off = 0;
-    L.off_kt = off;  off = align_up(off + BH * pr.T * DH * 2, 256);
-    L.off_vt = off;  off = align_up(off + BH * pr.T * DH * 2, 256);
-    L.off_st = off;  off = align_up(off + BH * L.nstate * (size_t)NTILES * TILE_ELEMS * 2, 256);
-    L.off_gam = off; off = align_up(off + BH * L.nstate * (size_t)DH * DH * 2, 256);
-    (void)backward;
+    auto take = [&](size_t bytes) {
+        size_t o = off;
+        off = align_up(off + bytes, 256);
+        return o;
+    };
+    L.off_kt = take(tok);
+    L.off_vt = take(tok);
+    L.off_gam = take(gm);
+    if (!backward) {
+        L.off_sc = take(st);
+    } else {
+        L.off_qt = take(tok);
+        L.off_gh = take(tok);
+        L.off_ght = take(tok);
+        L.off_gz = take(BH * pr.T * sizeof(float));
+        L.off_omg = take(gm);
+        L.off_sr = take(st);
+        L.off_rc = take(st);
+        L.off_rr = take(st);
+    }
     L.total = off;
     return L;
 }
 
+#define PA_LAUNCH(NAME, ...)                   \
+    {                                          \
+        LaunchScope ls_(NAME, c.stream);       \
+        hipLaunchKernelGGL(__VA_ARGS__);       \
+    }                                          \
+    if (!launch_ok()) return PA_ERR_HIP;
+
 }  // namespace
 
 pa_status mfma_supported(const pa_problem& pr, bool backward) {
-    if (backward) return PA_ERR_UNSUPPORTED;
+    (void)backward;
     if (pr.dtype != PA_DTYPE_BF16 || pr.p != 2) return PA_ERR_UNSUPPORTED;
     if (pr.d != DH || pr.v != DH) return PA_ERR_UNSUPPORTED;
     if (pr.chunk % QBLK != 0) return PA_ERR_UNSUPPORTED;
@@ -434,31 +914,55 @@ pa_status mfma_fwd(const Ctx& c, const void* Q, const void* K, const void* V, vo
     const unsigned BH = (unsigned)(pr.B * pr.H);
     bf16_t* Kt = (bf16_t*)(c.ws + L.off_kt);
     bf16_t* Vt = (bf16_t*)(c.ws + L.off_vt);
-    bf16_t* St = (bf16_t*)(c.ws + L.off_st);
+    bf16_t* Sc = (bf16_t*)(c.ws + L.off_sc);
     bf16_t* Gam = (bf16_t*)(c.ws + L.off_gam);
-    {
-        LaunchScope ls("mfma_transpose", c.stream);
-        hipLaunchKernelGGL(k_transpose, dim3(pr.T / 64, BH), dim3(256), 0, c.stream, (const bf16_t*)K, Kt, pr.T);
-        hipLaunchKernelGGL(k_transpose, dim3(pr.T / 64, BH), dim3(256), 0, c.stream, (const bf16_t*)V, Vt, pr.T);
-    }
-    if (!launch_ok()) return PA_ERR_HIP;
-    {
-        LaunchScope ls("mfma_state_scan", c.stream);
-        hipLaunchKernelGGL(k_mfma_scan, dim3(NTILES + 1, BH), dim3(256), 0, c.stream, Kt, Vt, St, Gam, pr.T, L.cs);
-    }
-    if (!launch_ok()) return PA_ERR_HIP;
-    {
-        LaunchScope ls("mfma_fwd_chunk", c.stream);
-        hipLaunchKernelGGL(k_mfma_fwd_chunk, dim3(pr.T / QBLK, BH), dim3(128), 0, c.stream, (const bf16_t*)Q,
-                           (const bf16_t*)K, Vt, St, Gam, (bf16_t*)O, Z, pr.T, L.cs, pr.scale, pr.normalize);
-    }
-    if (!launch_ok()) return PA_ERR_HIP;
+    const dim3 tgrid(pr.T / TBLK, BH);
+    PA_LAUNCH("mfma_transpose", k_transpose, tgrid, dim3(256), 0, c.stream, (const bf16_t*)K, Kt, pr.T)
+    PA_LAUNCH("mfma_transpose", k_transpose, tgrid, dim3(256), 0, c.stream, (const bf16_t*)V, Vt, pr.T)
+    PA_LAUNCH("mfma_state_scan", (k_mfma_scan<false, true, false>), dim3(NTILES + 1, BH), dim3(256), 0, c.stream, Kt, Vt,
+              (const float*)nullptr, Sc, (bf16_t*)nullptr, Gam, pr.T, L.cs, 1.0f)
+    PA_LAUNCH("mfma_fwd_chunk", k_mfma_fwd_chunk, dim3(pr.T / QBLK, BH), dim3(128), 0, c.stream, (const bf16_t*)Q,
+              (const bf16_t*)K, Vt, Sc, Gam, (bf16_t*)O, Z, pr.T, L.cs, pr.scale, pr.normalize)
     return PA_OK;
 }
 
-pa_status mfma_bwd(const Ctx&, const void*, const void*, const void*, const void*, const float*, const void*, void*,
-                   void*, void*) {
-    return PA_ERR_UNSUPPORTED;
+pa_status mfma_bwd(const Ctx& c, const void* Q, const void* K, const void* V, const void* O, const float* Z,
+                   const void* dO, void* dQ, void* dK, void* dV) {
+    const pa_problem& pr = c.prob;
+    const Layout L = make_layout(pr, true);
+    const unsigned BH = (unsigned)(pr.B * pr.H);
+    bf16_t* Kt = (bf16_t*)(c.ws + L.off_kt);
+    bf16_t* Vt = (bf16_t*)(c.ws + L.off_vt);
+    bf16_t* Qt = (bf16_t*)(c.ws + L.off_qt);
+    bf16_t* Gh = (bf16_t*)(c.ws + L.off_gh);
+    bf16_t* Ght = (bf16_t*)(c.ws + L.off_ght);
+    float* gz = (float*)(c.ws + L.off_gz);
+    bf16_t* Gam = (bf16_t*)(c.ws + L.off_gam);
+    bf16_t* Omg = (bf16_t*)(c.ws + L.off_omg);
+    bf16_t* Sr = (bf16_t*)(c.ws + L.off_sr);
+    bf16_t* Rc = (bf16_t*)(c.ws + L.off_rc);
+    bf16_t* Rr = (bf16_t*)(c.ws + L.off_rr);
+    const long long rows = (long long)BH * pr.T;
+    const dim3 tgrid(pr.T / TBLK, BH);
+    const float s2 = pr.scale * pr.scale;
+    PA_LAUNCH("mfma_bwd_prep", k_mfma_bwd_prep, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, c.stream,
+              (const bf16_t*)dO, (const bf16_t*)O, Z, Gh, gz, rows, pr.normalize)
+    PA_LAUNCH("mfma_transpose", k_transpose, tgrid, dim3(256), 0, c.stream, (const bf16_t*)K, Kt, pr.T)
+    PA_LAUNCH("mfma_transpose", k_transpose, tgrid, dim3(256), 0, c.stream, (const bf16_t*)V, Vt, pr.T)
+    PA_LAUNCH("mfma_transpose", k_transpose, tgrid, dim3(256), 0, c.stream, (const bf16_t*)Q, Qt, pr.T)
+    PA_LAUNCH("mfma_transpose", k_transpose, tgrid, dim3(256), 0, c.stream, (const bf16_t*)Gh, Ght, pr.T)
+    // chunk states are recomputed (nothing but O and Z is saved by the forward pass), in the
+    // layout the d phi contraction reads
+    PA_LAUNCH("mfma_state_scan_bwd", (k_mfma_scan<false, false, true>), dim3(NTILES + 1, BH), dim3(256), 0, c.stream, Kt,
+              Vt, (const float*)nullptr, (bf16_t*)nullptr, Sr, Gam, pr.T, L.cs, 1.0f)
+    PA_LAUNCH("mfma_state_grad_scan", (k_mfma_scan<true, true, true>), dim3(NTILES + 1, BH), dim3(256), 0, c.stream, Qt,
+              Ght, (const float*)gz, Rc, Rr, Omg, pr.T, L.cs, s2)
+    PA_LAUNCH("mfma_bwd_dq", k_mfma_bwd_dq, dim3(pr.T / QBLK, BH), dim3(128), 0, c.stream, (const bf16_t*)Q,
+              (const bf16_t*)K, (const bf16_t*)V, Gh, gz, Kt, Sr, Gam, (bf16_t*)dQ, pr.T, L.cs, pr.scale)
+    PA_LAUNCH("mfma_bwd_dkdv", k_mfma_bwd_dkdv, dim3(pr.T / QBLK, BH), dim3(128), 0, c.stream, (const bf16_t*)Q,
+              (const bf16_t*)K, (const bf16_t*)V, Gh, gz, Qt, Ght, Rc, Rr, Omg, (bf16_t*)dK, (bf16_t*)dV, pr.T, L.cs,
+              pr.scale)
+    return PA_OK;
 }
 
 }  // namespace pa

@@ -29,3 +29,25 @@ def test_mfma_forward_full_tensors(case):
     got = run_fwd_bwd(Q, K, V, None, 2, chunk, "bf16", normalize, scale, impl="mfma", backward=False)
     O, Z = orc.fwd_bhtd(Q, K, V, 2, None, normalize, scale)
     assert_close(got, dict(O=O, Z=Z), "bf16", f"mfma fwd {case}")
+
+
+BWD_CASES = [
+    # B, H, T, chunk, normalize, scale
+    (1, 2, 512, 128, True, 1.0),
+    (1, 1, 1024, 256, True, 1.0),
+    (1, 1, 128, 128, True, 1.0),
+    (1, 2, 768, 128, True, 0.6),
+    (1, 2, 512, 128, False, 1.0),
+    (1, 1, 1536, 512, True, 1.0),
+]
+
+
+@pytest.mark.parametrize("case", BWD_CASES, ids=lambda c: "-".join(str(x) for x in c))
+def test_mfma_backward_full_tensors(case):
+    B, H, T, chunk, normalize, scale = case
+    print("case", case, flush=True)
+    Q, K, V, G = inputs.make_qkvg(B, H, T, 64, seed=4000 + BWD_CASES.index(case), dtype="bf16")
+    got = run_fwd_bwd(Q, K, V, G, 2, chunk, "bf16", normalize, scale, impl="mfma")
+    O, Z = orc.fwd_bhtd(Q, K, V, 2, None, normalize, scale)
+    dQ, dK, dV = orc.bwd_bhtd(Q, K, V, G, 2, None, normalize, scale)
+    assert_close(got, dict(O=O, Z=Z, dQ=dQ, dK=dK, dV=dV), "bf16", f"mfma fwd+bwd {case}")
