@@ -37,6 +37,7 @@ def algorithmic_flops(w):
         "bwd_dq": state + pairs * (4 * d + 2 * v + 2),
         "bwd_dkdv": state + BH * (n - 1) * c * 2 * D * v + pairs * (2 * d + 2 * v),
     }
+    f["recompute"] = 0   # the backward pass rebuilds the chunk states: executed, not credited
     f["fwd_total"] = f["update_state"] + f["fwd_chunk"]
     f["bwd_total"] = f["state_grad"] + f["bwd_dq"] + f["bwd_dkdv"]
     return f
@@ -50,6 +51,7 @@ KERNEL_ROLE = {
     "generic_bwd_dq": ("bwd_dq", PEAK_FP32_VECTOR_TFLOPS),
     "generic_bwd_dkdv": ("bwd_dkdv", PEAK_FP32_VECTOR_TFLOPS),
     "mfma_state_scan": ("update_state", PEAK_BF16_MFMA_TFLOPS),
+    "mfma_state_scan_bwd": ("recompute", PEAK_BF16_MFMA_TFLOPS),
     "mfma_fwd_chunk": ("fwd_chunk", PEAK_BF16_MFMA_TFLOPS),
     "mfma_state_grad_scan": ("state_grad", PEAK_BF16_MFMA_TFLOPS),
     "mfma_bwd_dq": ("bwd_dq", PEAK_BF16_MFMA_TFLOPS),
@@ -58,7 +60,7 @@ KERNEL_ROLE = {
 
 
 def cpu_baseline(w, sample_tokens):
-    """The float64 oracle (chunked form, forward + backward) on head 0, first `sample_tokens`
+    """The float64 oracle (chunked form, forward + backward) on one head, first `sample_tokens`
     tokens of the workload; its cost per token does not depend on the position."""
     import numpy as np
     from oracle import power_attn_oracle as orc

@@ -67,18 +67,34 @@ __global__ __launch_bounds__(256) void k_transpose(const bf16_t* __restrict__ in
 // Fused update-state + cumulative sum over chunks (App. E.2 + E.3, no gating), used for
 //   the forward state     S_n = sum_{j <  n cs}     phi(k_j) v_j^T        (X = K, Y = V)
 //   the state gradient    R_m = sum_{i >= (m+1) cs} phi(q_i) ghat_i^T     (X = Q, Y = dO/Z, REV)
-// grid (NTILES + 1, BH), 256 threads.  Workgroup `tile` owns the 64 x DH state tile (ti, tj);
-// wave w owns its rows a in {2w, 2w+1}.  Workgroup NTILES owns the normaliser in its d x d
-// form: Gamma = sum k k^T, or Omega = sum gz_i q_i q_i^T for the gradient (same code: the A
-// operand is x itself, times the weight, and the B operand comes from X instead of Y).  The
-// state is written every `cs` tokens, before the tokens of that stretch are added.  Each
-// workgroup walks the sequence in stages of 64 tokens; the walk is a chain of tiny steps, so
-// the operands of SCAN_PF stages are kept in flight in registers.
+// grid (NPAIR + 1, BH), 256 threads.  Workgroup `pair` owns the two 64 x DH state tiles
+// 2 pair, 2 pair + 1; wave w owns 32 rows (a in 4(w&1) .. +3) of tile 2 pair + (w >> 1).
+// Workgroup NPAIR owns the normaliser in its d x d form: Gamma = sum k k^T, or
+// Omega = sum gz_i q_i q_i^T for the gradient (same code: the A operand is x itself, times the
+// weight, and the B operand comes from X instead of Y; only waves 0 and 1 have rows).
+// The state is written every `cs` tokens, before the tokens of that stretch are added.
+//
+// Each workgroup walks the sequence in stages of 128 tokens.  A stage's X (as float32) and Y
+// (bf16) are staged in LDS, feature-major, and shared by the four waves; the global loads of
+// SCAN_PF further stages are in flight in registers.
 //
 // Two layouts of a 64-row tile (bf16), chosen by which contraction the reader does:
 //   "C" [a][v][b]   8 expanded rows contiguous: operand of a contraction over rows (read-out)
 //   "R" [row][v]    8 value columns contiguous: operand of a contraction over v (d phi)
-constexpr int SCAN_PF = 8;
+constexpr int NPAIR = NTILES / 2;
+constexpr int SCAN_TOK = 128;                  // tokens per stage
+constexpr int SCAN_PF = 3;                     // stages in flight in registers
+constexpr int XS_PITCH = SCAN_TOK + 4;         // floats; pitch = 4 mod 64 banks
+constexpr int YS_PITCH = SCAN_TOK + 8;         // bf16;   pitch = 4 mod 64 banks (in dwords)
+constexpr int TR_PITCH = DH + 8;               // bf16
+static_assert(NTILES % 2 == 0, "tiles are handled in pairs");
+
+struct ScanSmem {
+    float xs[2][DH][XS_PITCH];
+    bf16_t ys[2][DH][YS_PITCH];
+    float ws[2][SCAN_TOK];
+    bf16_t tr[4][32][TR_PITCH];
+};
 
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() also fences global memory,
 // i.e. waits for every outstanding global load, which would drain the register ring below.
@@ -92,165 +108,204 @@ template <bool GAMMA, bool REV, bool WC, bool WR>
 __device__ __forceinline__ void scan_body(const bf16_t* __restrict__ Xt, const bf16_t* __restrict__ Yt,
                                           const float* __restrict__ wgt, bf16_t* __restrict__ StC,
                                           bf16_t* __restrict__ StR, bf16_t* __restrict__ Gam, int T, int cs,
-                                          float out_scale, bf16_t (*Vs)[DH][72]) {
+                                          float out_scale, ScanSmem& sm) {
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int r16 = lane & 15, g = lane >> 4;
-    const int tile = blockIdx.x, bh = blockIdx.y;
+    const int bh = blockIdx.y;
     const int nstate = T / cs;
-    const int nblk = T / TBLK;
+    const int tile = GAMMA ? 0 : 2 * (int)blockIdx.x + (w >> 1);
     int ti = 0, tj = 0;
-    if (!GAMMA) {
-        for (int l = 0; l < tile; ++l) {
-            if (++ti > tj) {
-                ++tj;
-                ti = 0;
-            }
+    for (int l = 0; l < tile; ++l) {
+        if (++ti > tj) {
+            ++tj;
+            ti = 0;
         }
     }
-    const float mult = ((ti == tj) ? 1.f : 2.f) * out_scale;
-    const int fa = GAMMA ? 16 * w + r16 : 8 * ti + 2 * w + (r16 >> 3);
-    const int fb = GAMMA ? fa : 8 * tj + (r16 & 7);
-    constexpr int STAGE = DH * TBLK;   // elements of one 64-token block of Xt / Yt
-    const bf16_t* Xa = Xt + (size_t)bh * DH * T + fa * TBLK + 8 * g;
-    const bf16_t* Xb = Xt + (size_t)bh * DH * T + fb * TBLK + 8 * g;
-    const float* Wg = (GAMMA && REV) ? wgt + (size_t)bh * T + 8 * g : nullptr;
-    // B operand staging through LDS: thread -> (column, 16 tokens)
-    const int vcol = tid >> 2, vpiece = tid & 3;
-    const bf16_t* Bsrc = (GAMMA ? Xt : Yt) + (size_t)bh * DH * T + vcol * TBLK + 16 * vpiece;
+    const float mult = GAMMA ? out_scale : ((ti == tj) ? 1.f : 2.f) * out_scale;
+    // feature rows this lane expands: row block rbk in {0,1} covers tile rows 32 (w&1) + 16 rbk + r16
+    //   tiles: a = 4 (w&1) + 2 rbk + (r16 >> 3), b = r16 & 7;   Gamma: feature 32 w + 16 rbk + r16
+    const int fa0 = GAMMA ? (32 * (w & 1) + r16) : 8 * ti + 4 * (w & 1) + (r16 >> 3);
+    const int fa_step = GAMMA ? 16 : 2;
+    const int fb = 8 * tj + (r16 & 7);
+    const bool has_rows = !GAMMA || w < 2;
 
-    f32x4 acc[4], acct[4];   // acc: rows (a,b) x cols v;  acct: its transpose, rows v x cols (a,b)
+    // global -> LDS staging: thread t moves pieces t, t + 256, t + 512, t + 768 of the stage; a
+    // piece is 8 tokens of one feature (16 bytes of bf16) of X and of Y
+    const bf16_t* Xh = Xt + (size_t)bh * DH * T;
+    const bf16_t* Yh = (GAMMA ? Xt : Yt) + (size_t)bh * DH * T;
+    const float* Wh = (GAMMA && REV) ? wgt + (size_t)bh * T : nullptr;
+    int p_feat[4], p_tok[4], p_off[4];
 #pragma unroll
-    for (int cb = 0; cb < 4; ++cb) {
-        acc[cb] = (f32x4){0.f, 0.f, 0.f, 0.f};
-        acct[cb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int q = 0; q < 4; ++q) {
+        const int id = tid + 256 * q;
+        p_feat[q] = id >> 4;
+        p_tok[q] = 8 * (id & 15);                                        // token inside the stage
+        p_off[q] = (p_tok[q] >> 6) * (DH * TBLK) + p_feat[q] * TBLK + (p_tok[q] & 63);
     }
+
+    f32x4 acc[2][4];
+#pragma unroll
+    for (int rbk = 0; rbk < 2; ++rbk)
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb) acc[rbk][cb] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
     auto write_state = [&](int n) {
         if (!GAMMA) {
+            const size_t tbase = ((size_t)(bh * nstate + n) * NTILES + tile) * TILE_ELEMS;
             if (WC) {
-                bf16_t* dst = StC + ((size_t)(bh * nstate + n) * NTILES + tile) * TILE_ELEMS;
-                const int a = 2 * w + (g >> 1), b0 = 4 * (g & 1);
+                bf16_t* dst = StC + tbase;
 #pragma unroll
-                for (int cb = 0; cb < 4; ++cb) {
-                    bf16x4 o;
+                for (int rbk = 0; rbk < 2; ++rbk) {
+                    const int a = 4 * (w & 1) + 2 * rbk + (g >> 1), b0 = 4 * (g & 1);
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) o[r] = (__bf16)(acc[cb][r] * mult);
-                    *(bf16x4*)(dst + ((a * DH + 16 * cb + r16) * 8 + b0)) = o;
+                    for (int cb = 0; cb < 4; ++cb) {
+                        bf16x4 o;
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) o[r] = (__bf16)(acc[rbk][cb][r] * mult);
+                        *(bf16x4*)(dst + ((a * DH + 16 * cb + r16) * 8 + b0)) = o;
+                    }
                 }
             }
             if (WR) {
-                bf16_t* dst = StR + ((size_t)(bh * nstate + n) * NTILES + tile) * TILE_ELEMS;
+                // transpose the wave's 32 x 64 block through its private LDS patch, then store rows
 #pragma unroll
-                for (int cb = 0; cb < 4; ++cb) {
-                    bf16x4 o;
+                for (int rbk = 0; rbk < 2; ++rbk)
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) o[r] = (__bf16)(acct[cb][r] * mult);
-                    *(bf16x4*)(dst + ((16 * w + r16) * DH + 16 * cb + 4 * g)) = o;
+                    for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            sm.tr[w][16 * rbk + 4 * g + r][16 * cb + r16] = f32_to_bf16(acc[rbk][cb][r] * mult);
+                bf16_t* dst = StR + tbase + (size_t)32 * (w & 1) * DH;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int unit = lane + 64 * q;          // 32 rows x 8 units of 16 bytes
+                    const uint4 val = *(const uint4*)&sm.tr[w][unit >> 3][8 * (unit & 7)];
+                    *(uint4*)(dst + (unit >> 3) * DH + 8 * (unit & 7)) = val;
                 }
             }
-        } else {
+        } else if (has_rows) {
             bf16_t* dst = Gam + (size_t)(bh * nstate + n) * DH * DH;
 #pragma unroll
-            for (int cb = 0; cb < 4; ++cb)
+            for (int rbk = 0; rbk < 2; ++rbk)
 #pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    dst[(16 * w + 4 * g + r) * DH + 16 * cb + r16] = f32_to_bf16(acc[cb][r] * out_scale);
+                for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        dst[(32 * w + 16 * rbk + 4 * g + r) * DH + 16 * cb + r16] = f32_to_bf16(acc[rbk][cb][r] * mult);
         }
     };
 
     // Stretches at the far end never feed a state that is written, so the walk stops early.
-    const int nstage = (T - cs) / 64;
+    const int nstage = (T - cs) / SCAN_TOK;
+    const int nstage_all = T / SCAN_TOK;
     if (nstage > 0) {
-        // Register ring: slot J holds the operands of stage (st0 + J).  Every load is
+        // Register ring: slot J holds the global data of stage (st0 + J).  Every load is
         // unconditional (indices are clamped instead of branching) so that the compiler can
         // count the loads in flight instead of waiting for all of them.  Separately named
         // registers and macros instead of arrays and lambdas: the slot has to be a
         // compile-time name or the ring is demoted to scratch memory.
-#define PA_SLOT(J) uint4 ka0_##J, ka1_##J, kb0_##J, kb1_##J, vr0_##J, vr1_##J, w00_##J, w01_##J, w10_##J, w11_##J;
-        PA_SLOT(0) PA_SLOT(1) PA_SLOT(2) PA_SLOT(3) PA_SLOT(4) PA_SLOT(5) PA_SLOT(6) PA_SLOT(7)
+#define PA_SLOT(J) uint4 x0_##J, x1_##J, x2_##J, x3_##J, y0_##J, y1_##J, y2_##J, y3_##J; float wv_##J;
+        PA_SLOT(0) PA_SLOT(1) PA_SLOT(2)
 #undef PA_SLOT
-        static_assert(SCAN_PF == 8, "the ring below is written out for 8 slots");
+        static_assert(SCAN_PF == 3, "the ring below is written out for 3 slots");
 #define PA_LOAD_STAGE(J, ST)                                                              \
     {                                                                                     \
         const int sc_ = min((ST), nstage - 1);                                            \
-        const int sidx_ = REV ? nblk - 1 - sc_ : sc_;                                     \
-        const size_t so_ = (size_t)sidx_ * STAGE;                                         \
-        ka0_##J = *(const uint4*)(Xa + so_);                                              \
-        ka1_##J = *(const uint4*)(Xa + so_ + 32);                                         \
-        if (!GAMMA) {                                                                     \
-            kb0_##J = *(const uint4*)(Xb + so_);                                          \
-            kb1_##J = *(const uint4*)(Xb + so_ + 32);                                     \
-        }                                                                                 \
-        if (GAMMA && REV) {                                                               \
-            const float* wp_ = Wg + (size_t)sidx_ * TBLK;                                 \
-            w00_##J = *(const uint4*)(wp_);                                               \
-            w01_##J = *(const uint4*)(wp_ + 4);                                           \
-            w10_##J = *(const uint4*)(wp_ + 32);                                          \
-            w11_##J = *(const uint4*)(wp_ + 36);                                          \
-        }                                                                                 \
-        vr0_##J = *(const uint4*)(Bsrc + so_);                                            \
-        vr1_##J = *(const uint4*)(Bsrc + so_ + 8);                                        \
+        const int sidx_ = REV ? nstage_all - 1 - sc_ : sc_;                               \
+        const size_t so_ = (size_t)sidx_ * (2 * DH * TBLK);                               \
+        x0_##J = *(const uint4*)(Xh + so_ + p_off[0]);                                    \
+        x1_##J = *(const uint4*)(Xh + so_ + p_off[1]);                                    \
+        x2_##J = *(const uint4*)(Xh + so_ + p_off[2]);                                    \
+        x3_##J = *(const uint4*)(Xh + so_ + p_off[3]);                                    \
+        y0_##J = *(const uint4*)(Yh + so_ + p_off[0]);                                    \
+        y1_##J = *(const uint4*)(Yh + so_ + p_off[1]);                                    \
+        y2_##J = *(const uint4*)(Yh + so_ + p_off[2]);                                    \
+        y3_##J = *(const uint4*)(Yh + so_ + p_off[3]);                                    \
+        if (GAMMA && REV) wv_##J = Wh[(size_t)sidx_ * SCAN_TOK + (tid & (SCAN_TOK - 1))]; \
     }
-#define PA_HALF(J, S, KA, KB, W0, W1)                                                         \
-    {                                                                                         \
-        Frag af_;                                                                             \
-        const uint32_t pa_[4] = {KA.x, KA.y, KA.z, KA.w};                                     \
-        if (!GAMMA) {                                                                         \
-            const uint32_t pb_[4] = {KB.x, KB.y, KB.z, KB.w};                                 \
-            _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                \
-                af_.v[2 * i_] = (__bf16)(bf_lo(pa_[i_]) * bf_lo(pb_[i_]));                    \
-                af_.v[2 * i_ + 1] = (__bf16)(bf_hi(pa_[i_]) * bf_hi(pb_[i_]));                \
-            }                                                                                 \
-        } else if (REV) {                                                                     \
-            const uint32_t pw_[8] = {W0.x, W0.y, W0.z, W0.w, W1.x, W1.y, W1.z, W1.w};         \
-            _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                \
-                af_.v[2 * i_] = (__bf16)(bf_lo(pa_[i_]) * __uint_as_float(pw_[2 * i_]));      \
-                af_.v[2 * i_ + 1] = (__bf16)(bf_hi(pa_[i_]) * __uint_as_float(pw_[2 * i_ + 1])); \
-            }                                                                                 \
-        } else {                                                                              \
-            af_.u = KA;                                                                       \
-        }                                                                                     \
-        _Pragma("unroll") for (int cb_ = 0; cb_ < 4; ++cb_) {                                 \
-            Frag bf_;                                                                         \
-            bf_.u = *(const uint4*)&Vs[(J) & 1][16 * cb_ + r16][32 * (S) + 8 * g];            \
-            if (GAMMA || WC) acc[cb_] = mfma16(af_.v, bf_.v, acc[cb_]);                       \
-            if (!GAMMA && WR) acct[cb_] = mfma16(bf_.v, af_.v, acct[cb_]);                    \
-        }                                                                                     \
+#define PA_FILL_X(BUF, Q, XR)                                                             \
+    {                                                                                     \
+        float* d_ = &sm.xs[BUF][p_feat[Q]][p_tok[Q]];                                     \
+        *(float4*)d_ = make_float4(bf_lo(XR.x), bf_hi(XR.x), bf_lo(XR.y), bf_hi(XR.y));   \
+        *(float4*)(d_ + 4) = make_float4(bf_lo(XR.z), bf_hi(XR.z), bf_lo(XR.w), bf_hi(XR.w)); \
     }
-#define PA_CONSUME(J, ST)                                                                     \
+#define PA_CONSUME(J, ST, BUF)                                                                \
     if ((ST) < nstage) { /* uniform; no global loads inside this branch */                    \
-        const int edge_ = REV ? T - (ST) * 64 : (ST) * 64;                                    \
+        const int edge_ = REV ? T - (ST) * SCAN_TOK : (ST) * SCAN_TOK;                        \
         if (edge_ % cs == 0) write_state(REV ? edge_ / cs - 1 : edge_ / cs);                  \
-        *(uint4*)&Vs[(J) & 1][vcol][16 * vpiece] = vr0_##J;                                   \
-        *(uint4*)&Vs[(J) & 1][vcol][16 * vpiece + 8] = vr1_##J;                               \
+        PA_FILL_X(BUF, 0, x0_##J) PA_FILL_X(BUF, 1, x1_##J)                                   \
+        PA_FILL_X(BUF, 2, x2_##J) PA_FILL_X(BUF, 3, x3_##J)                                   \
+        *(uint4*)&sm.ys[BUF][p_feat[0]][p_tok[0]] = y0_##J;                                   \
+        *(uint4*)&sm.ys[BUF][p_feat[1]][p_tok[1]] = y1_##J;                                   \
+        *(uint4*)&sm.ys[BUF][p_feat[2]][p_tok[2]] = y2_##J;                                   \
+        *(uint4*)&sm.ys[BUF][p_feat[3]][p_tok[3]] = y3_##J;                                   \
+        if (GAMMA && REV && tid < SCAN_TOK) sm.ws[BUF][tid] = wv_##J;                         \
         lds_barrier();                                                                        \
-        PA_HALF(J, 0, ka0_##J, kb0_##J, w00_##J, w01_##J)                                     \
-        PA_HALF(J, 1, ka1_##J, kb1_##J, w10_##J, w11_##J)                                     \
+        if (has_rows) {                                                                       \
+            _Pragma("unroll") for (int s_ = 0; s_ < SCAN_TOK / 32; ++s_) {                    \
+                const int t0_ = 32 * s_ + 8 * g;                                              \
+                float xb_[8];                                                                 \
+                if (!GAMMA) {                                                                 \
+                    const float4 l_ = *(const float4*)&sm.xs[BUF][fb][t0_];                   \
+                    const float4 h_ = *(const float4*)&sm.xs[BUF][fb][t0_ + 4];               \
+                    xb_[0] = l_.x; xb_[1] = l_.y; xb_[2] = l_.z; xb_[3] = l_.w;               \
+                    xb_[4] = h_.x; xb_[5] = h_.y; xb_[6] = h_.z; xb_[7] = h_.w;               \
+                } else if (REV) {                                                             \
+                    const float4 l_ = *(const float4*)&sm.ws[BUF][t0_];                       \
+                    const float4 h_ = *(const float4*)&sm.ws[BUF][t0_ + 4];                   \
+                    xb_[0] = l_.x; xb_[1] = l_.y; xb_[2] = l_.z; xb_[3] = l_.w;               \
+                    xb_[4] = h_.x; xb_[5] = h_.y; xb_[6] = h_.z; xb_[7] = h_.w;               \
+                } else {                                                                      \
+                    _Pragma("unroll") for (int i_ = 0; i_ < 8; ++i_) xb_[i_] = 1.f;           \
+                }                                                                             \
+                Frag af_[2];                                                                  \
+                _Pragma("unroll") for (int rbk_ = 0; rbk_ < 2; ++rbk_) {                      \
+                    const float* xa_ = &sm.xs[BUF][fa0 + fa_step * rbk_][t0_];                \
+                    const float4 l_ = *(const float4*)xa_;                                    \
+                    const float4 h_ = *(const float4*)(xa_ + 4);                              \
+                    af_[rbk_].v[0] = (__bf16)(l_.x * xb_[0]); af_[rbk_].v[1] = (__bf16)(l_.y * xb_[1]); \
+                    af_[rbk_].v[2] = (__bf16)(l_.z * xb_[2]); af_[rbk_].v[3] = (__bf16)(l_.w * xb_[3]); \
+                    af_[rbk_].v[4] = (__bf16)(h_.x * xb_[4]); af_[rbk_].v[5] = (__bf16)(h_.y * xb_[5]); \
+                    af_[rbk_].v[6] = (__bf16)(h_.z * xb_[6]); af_[rbk_].v[7] = (__bf16)(h_.w * xb_[7]); \
+                }                                                                             \
+                _Pragma("unroll") for (int cb_ = 0; cb_ < 4; ++cb_) {                         \
+                    Frag bf_;                                                                 \
+                    bf_.u = *(const uint4*)&sm.ys[BUF][16 * cb_ + r16][t0_];                  \
+                    acc[0][cb_] = mfma16(af_[0].v, bf_.v, acc[0][cb_]);                       \
+                    acc[1][cb_] = mfma16(af_[1].v, bf_.v, acc[1][cb_]);                       \
+                }                                                                             \
+            }                                                                                 \
+        }                                                                                     \
     }
-#define PA_STEP(J) PA_CONSUME(J, st0 + J) PA_LOAD_STAGE(J, st0 + J + SCAN_PF)
-        PA_LOAD_STAGE(0, 0) PA_LOAD_STAGE(1, 1) PA_LOAD_STAGE(2, 2) PA_LOAD_STAGE(3, 3)
-        PA_LOAD_STAGE(4, 4) PA_LOAD_STAGE(5, 5) PA_LOAD_STAGE(6, 6) PA_LOAD_STAGE(7, 7)
-        for (int st0 = 0; st0 < nstage; st0 += SCAN_PF) {
-            PA_STEP(0) PA_STEP(1) PA_STEP(2) PA_STEP(3) PA_STEP(4) PA_STEP(5) PA_STEP(6) PA_STEP(7)
+        // The LDS buffer alternates with the stage parity; 2 * SCAN_PF stages per trip keep both
+        // the ring slot and the buffer compile-time constants.
+        PA_LOAD_STAGE(0, 0) PA_LOAD_STAGE(1, 1) PA_LOAD_STAGE(2, 2)
+        for (int st0 = 0; st0 < nstage; st0 += 2 * SCAN_PF) {
+            PA_CONSUME(0, st0 + 0, 0) PA_LOAD_STAGE(0, st0 + 3)
+            PA_CONSUME(1, st0 + 1, 1) PA_LOAD_STAGE(1, st0 + 4)
+            PA_CONSUME(2, st0 + 2, 0) PA_LOAD_STAGE(2, st0 + 5)
+            PA_CONSUME(0, st0 + 3, 1) PA_LOAD_STAGE(0, st0 + 6)
+            PA_CONSUME(1, st0 + 4, 0) PA_LOAD_STAGE(1, st0 + 7)
+            PA_CONSUME(2, st0 + 5, 1) PA_LOAD_STAGE(2, st0 + 8)
         }
-#undef PA_STEP
 #undef PA_CONSUME
-#undef PA_HALF
+#undef PA_FILL_X
 #undef PA_LOAD_STAGE
     }
     write_state(REV ? 0 : nstate - 1);
 }
 
 template <bool REV, bool WC, bool WR>
-__global__ __launch_bounds__(256, 2) void k_mfma_scan(const bf16_t* __restrict__ Xt, const bf16_t* __restrict__ Yt,
-                                                      const float* __restrict__ wgt, bf16_t* __restrict__ StC,
-                                                      bf16_t* __restrict__ StR, bf16_t* __restrict__ Gam, int T, int cs,
-                                                      float out_scale) {
-    __shared__ __attribute__((aligned(16))) bf16_t Vs[2][DH][72];
-    if (blockIdx.x == NTILES)
-        scan_body<true, REV, WC, WR>(Xt, Yt, wgt, StC, StR, Gam, T, cs, out_scale, Vs);
+__global__ __launch_bounds__(256) void k_mfma_scan(const bf16_t* __restrict__ Xt, const bf16_t* __restrict__ Yt,
+                                                   const float* __restrict__ wgt, bf16_t* __restrict__ StC,
+                                                   bf16_t* __restrict__ StR, bf16_t* __restrict__ Gam, int T, int cs,
+                                                   float out_scale) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char scan_smem_raw[];
+    ScanSmem& sm = *reinterpret_cast<ScanSmem*>(scan_smem_raw);
+    if (blockIdx.x == NPAIR)
+        scan_body<true, REV, WC, WR>(Xt, Yt, wgt, StC, StR, Gam, T, cs, out_scale, sm);
     else
-        scan_body<false, REV, WC, WR>(Xt, Yt, wgt, StC, StR, Gam, T, cs, out_scale, Vs);
+        scan_body<false, REV, WC, WR>(Xt, Yt, wgt, StC, StR, Gam, T, cs, out_scale, sm);
 }
 
 // ---- read-out: contraction over the expanded rows (query-state, App. E.4) -----------------------
@@ -523,7 +578,7 @@ __global__ __launch_bounds__(128) void k_mfma_fwd_chunk(const bf16_t* __restrict
 }
 
 // ---- backward: preparation -----------------------------------------------------------------------
-// ghat = dO / Z (bf16, [BH][T][DH]) and gz = -(dO . O) / Z (float32, [BH][T]); un-normalised:
+// ghat = dO / Z (bf16, [BH][T][DH]) and gz = -(ghat . O) (float32, [BH][T]); un-normalised:
 // ghat = dO, gz = 0.  Rows with Z == 0 give zeros.  One 16-lane group per row.
 __global__ __launch_bounds__(256) void k_mfma_bwd_prep(const bf16_t* __restrict__ dO, const bf16_t* __restrict__ O,
                                                        const float* __restrict__ Z, bf16_t* __restrict__ Gh,
@@ -532,23 +587,32 @@ __global__ __launch_bounds__(256) void k_mfma_bwd_prep(const bf16_t* __restrict_
     const int c4 = threadIdx.x & 15;
     if (row >= rows) return;
     const uint2 graw = *(const uint2*)(dO + row * DH + 4 * c4);
-    float gv[4] = {bf_lo(graw.x), bf_hi(graw.x), bf_lo(graw.y), bf_hi(graw.y)};
-    float inv = 1.f, delta = 0.f;
+    const float gv[4] = {bf_lo(graw.x), bf_hi(graw.x), bf_lo(graw.y), bf_hi(graw.y)};
+    float inv = 1.f;
     if (normalize) {
-        const uint2 oraw = *(const uint2*)(O + row * DH + 4 * c4);
-        delta = gv[0] * bf_lo(oraw.x) + gv[1] * bf_hi(oraw.x) + gv[2] * bf_lo(oraw.y) + gv[3] * bf_hi(oraw.y);
-        delta += __shfl_xor(delta, 1);
-        delta += __shfl_xor(delta, 2);
-        delta += __shfl_xor(delta, 4);
-        delta += __shfl_xor(delta, 8);
         const float z = Z[row];
         inv = z != 0.f ? 1.f / z : 0.f;
     }
     bf16x4 o;
+    float gr[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) o[i] = (__bf16)(gv[i] * inv);
+    for (int i = 0; i < 4; ++i) {
+        o[i] = (__bf16)(gv[i] * inv);
+        gr[i] = (float)o[i];
+    }
     *(bf16x4*)(Gh + row * DH + 4 * c4) = o;
-    if (c4 == 0) gz[row] = normalize ? -delta * inv : 0.f;
+    // gz is formed from the ROUNDED ghat, so that ghat . v_j + gz = ghat . (v_j - O_i) keeps its
+    // exact cancellations (a row that attends to one key only gets a zero gradient, as it must)
+    float delta = 0.f;
+    if (normalize) {
+        const uint2 oraw = *(const uint2*)(O + row * DH + 4 * c4);
+        delta = gr[0] * bf_lo(oraw.x) + gr[1] * bf_hi(oraw.x) + gr[2] * bf_lo(oraw.y) + gr[3] * bf_hi(oraw.y);
+        delta += __shfl_xor(delta, 1);
+        delta += __shfl_xor(delta, 2);
+        delta += __shfl_xor(delta, 4);
+        delta += __shfl_xor(delta, 8);
+    }
+    if (c4 == 0) gz[row] = -delta;
 }
 
 // ---- backward, queries: dQ ------------------------------------------------------------------------
@@ -886,6 +950,14 @@ Layout make_layout(const pa_problem& pr, bool backward) {
     return L;
 }
 
+// LDS beyond the default per-kernel limit has to be requested once per kernel
+template <typename F>
+bool allow_smem(F* fn, size_t bytes) {
+    hipError_t e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e != hipSuccess) note_hip_error(e, "hipFuncSetAttribute(max dynamic LDS)");
+    return e == hipSuccess;
+}
+
 #define PA_LAUNCH(NAME, ...)                   \
     {                                          \
         LaunchScope ls_(NAME, c.stream);       \
@@ -919,7 +991,8 @@ pa_status mfma_fwd(const Ctx& c, const void* Q, const void* K, const void* V, vo
     const dim3 tgrid(pr.T / TBLK, BH);
     PA_LAUNCH("mfma_transpose", k_transpose, tgrid, dim3(256), 0, c.stream, (const bf16_t*)K, Kt, pr.T)
     PA_LAUNCH("mfma_transpose", k_transpose, tgrid, dim3(256), 0, c.stream, (const bf16_t*)V, Vt, pr.T)
-    PA_LAUNCH("mfma_state_scan", (k_mfma_scan<false, true, false>), dim3(NTILES + 1, BH), dim3(256), 0, c.stream, Kt, Vt,
+    if (!allow_smem(k_mfma_scan<false, true, false>, sizeof(ScanSmem))) return PA_ERR_HIP;
+    PA_LAUNCH("mfma_state_scan", (k_mfma_scan<false, true, false>), dim3(NPAIR + 1, BH), dim3(256), sizeof(ScanSmem), c.stream, Kt, Vt,
               (const float*)nullptr, Sc, (bf16_t*)nullptr, Gam, pr.T, L.cs, 1.0f)
     PA_LAUNCH("mfma_fwd_chunk", k_mfma_fwd_chunk, dim3(pr.T / QBLK, BH), dim3(128), 0, c.stream, (const bf16_t*)Q,
               (const bf16_t*)K, Vt, Sc, Gam, (bf16_t*)O, Z, pr.T, L.cs, pr.scale, pr.normalize)
@@ -953,9 +1026,12 @@ pa_status mfma_bwd(const Ctx& c, const void* Q, const void* K, const void* V, co
     PA_LAUNCH("mfma_transpose", k_transpose, tgrid, dim3(256), 0, c.stream, (const bf16_t*)Gh, Ght, pr.T)
     // chunk states are recomputed (nothing but O and Z is saved by the forward pass), in the
     // layout the d phi contraction reads
-    PA_LAUNCH("mfma_state_scan_bwd", (k_mfma_scan<false, false, true>), dim3(NTILES + 1, BH), dim3(256), 0, c.stream, Kt,
+    if (!allow_smem(k_mfma_scan<false, false, true>, sizeof(ScanSmem)) ||
+        !allow_smem(k_mfma_scan<true, true, true>, sizeof(ScanSmem)))
+        return PA_ERR_HIP;
+    PA_LAUNCH("mfma_state_scan_bwd", (k_mfma_scan<false, false, true>), dim3(NPAIR + 1, BH), dim3(256), sizeof(ScanSmem), c.stream, Kt,
               Vt, (const float*)nullptr, (bf16_t*)nullptr, Sr, Gam, pr.T, L.cs, 1.0f)
-    PA_LAUNCH("mfma_state_grad_scan", (k_mfma_scan<true, true, true>), dim3(NTILES + 1, BH), dim3(256), 0, c.stream, Qt,
+    PA_LAUNCH("mfma_state_grad_scan", (k_mfma_scan<true, true, true>), dim3(NPAIR + 1, BH), dim3(256), sizeof(ScanSmem), c.stream, Qt,
               Ght, (const float*)gz, Rc, Rr, Omg, pr.T, L.cs, s2)
     PA_LAUNCH("mfma_bwd_dq", k_mfma_bwd_dq, dim3(pr.T / QBLK, BH), dim3(128), 0, c.stream, (const bf16_t*)Q,
               (const bf16_t*)K, (const bf16_t*)V, Gh, gz, Kt, Sr, Gam, (bf16_t*)dQ, pr.T, L.cs, pr.scale)
