@@ -36,6 +36,8 @@ def algorithmic_flops(w):
         "state_grad": state,
         "bwd_dq": state + pairs * (4 * d + 2 * v + 2),
         "bwd_dkdv": state + BH * (n - 1) * c * 2 * D * v + pairs * (2 * d + 2 * v),
+        "bwd_dk": state + pairs * 2 * d,
+        "bwd_dv": BH * (n - 1) * c * 2 * D * v + pairs * 2 * v,
     }
     f["recompute"] = 0   # the backward pass rebuilds the chunk states: executed, not credited
     f["fwd_total"] = f["update_state"] + f["fwd_chunk"]
@@ -55,7 +57,8 @@ KERNEL_ROLE = {
     "mfma_fwd_chunk": ("fwd_chunk", PEAK_BF16_MFMA_TFLOPS),
     "mfma_state_grad_scan": ("state_grad", PEAK_BF16_MFMA_TFLOPS),
     "mfma_bwd_dq": ("bwd_dq", PEAK_BF16_MFMA_TFLOPS),
-    "mfma_bwd_dkdv": ("bwd_dkdv", PEAK_BF16_MFMA_TFLOPS),
+    "mfma_bwd_dk": ("bwd_dk", PEAK_BF16_MFMA_TFLOPS),
+    "mfma_bwd_dv": ("bwd_dv", PEAK_BF16_MFMA_TFLOPS),
 }
 
 

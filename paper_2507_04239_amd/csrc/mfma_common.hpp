@@ -1,0 +1,79 @@
+// Shared definitions of the bf16 MFMA kernel family for degree p = 2 (gfx950, wave64).
+//
+// Chunked form of arXiv 2507.04239 (Sec. 2 "Chunked form", App. E) with the tiled
+// symmetric-power embedding of Sec. 4.1.1 at d_tile = 8:  the expanded row (ti, tj, a, b),
+// ti <= tj, of phi(x) is x[8 ti + a] * x[8 tj + b]; tiles off the diagonal carry the
+// multiplicity 2, which is applied once, to the state (instead of sqrt(2) on both sides).
+// Expanded operands are built in registers in MFMA operand order and never stored.
+//
+// MFMA used: v_mfma_f32_16x16x32_bf16.  Operand layout (lane l, r16 = l % 16, g = l / 16):
+//   A: row r16,   k-slots 8g..8g+7        B: column r16, k-slots 8g..8g+7
+//   C: column r16, rows 4g..4g+3 (4 floats)
+// Only the pairing of A and B k-slots matters, so k-slots are assigned to whatever order
+// the data is already in (no shuffles between the two MFMAs of the attention form).
+//
+// Two layouts of a 64-row state tile (bf16), chosen by which contraction the reader does:
+//   "C" [a][v][b]   8 expanded rows contiguous: operand of a contraction over rows (read-out)
+//   "R" [row][v]    8 value columns contiguous: operand of a contraction over v (d phi)
+#pragma once
+
+#include "common.hpp"
+
+namespace pa {
+namespace mfma {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+constexpr int DH = 64;                         // head size (d = v)
+constexpr int NTB = DH / 8;                    // 8-wide feature blocks
+constexpr int NTILES = NTB * (NTB + 1) / 2;    // 36 tiles of 64 expanded rows
+constexpr int TILE_ELEMS = 8 * DH * 8;         // elements of one state tile
+constexpr int STATE_ELEMS = NTILES * TILE_ELEMS;
+constexpr int QBLK = 128;                      // token rows per workgroup of the chunk kernels
+constexpr int TBLK = 64;                       // tokens per block of the feature-major copies
+
+__device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ float bf_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+
+union Frag {
+    bf16x8 v;
+    uint4 u;
+    uint2 h[2];
+};
+
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also fences global memory,
+// i.e. waits for every outstanding global load, which would drain a register prefetch ring.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// ---- launchers (each defined next to its kernels) ------------------------------------------
+// feature-major copy in blocks of 64 tokens: [BH][T][DH] -> [BH][T/64][DH][64]
+bool launch_transpose(hipStream_t s, const bf16_t* in, bf16_t* out, int BH, int T);
+// state scan; rev = 0: S_n from (Kt, Vt); rev = 1: R_m from (Qt, Ght) with the weights gz.
+// stC / stR may be null (layout not written); gam receives Gamma (rev = 0) or Omega (rev = 1).
+bool launch_scan(const char* name, hipStream_t s, bool rev, const bf16_t* Xt, const bf16_t* Yt, const float* wgt, bf16_t* stC,
+                 bf16_t* stR, bf16_t* gam, int BH, int T, int cs, float out_scale);
+bool launch_fwd_chunk(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* Vt, const bf16_t* stC,
+                      const bf16_t* gam, bf16_t* O, float* Z, int BH, int T, int cs, float scale, int normalize);
+bool launch_bwd_prep(hipStream_t s, const bf16_t* dO, const bf16_t* O, const float* Z, bf16_t* Gh, float* gz,
+                     long long rows, int normalize);
+bool launch_bwd_dq(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* V, const bf16_t* Gh,
+                   const float* gz, const bf16_t* Kt, const bf16_t* stR, const bf16_t* gam, bf16_t* dQ, int BH, int T,
+                   int cs, float scale);
+bool launch_bwd_dk(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* V, const bf16_t* Gh,
+                   const float* gz, const bf16_t* Qt, const bf16_t* rtR, const bf16_t* omg, bf16_t* dK, int BH, int T,
+                   int cs, float scale);
+bool launch_bwd_dv(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* Ght, const bf16_t* rtC,
+                   bf16_t* dV, int BH, int T, int cs, float scale);
+
+}  // namespace mfma
+}  // namespace pa

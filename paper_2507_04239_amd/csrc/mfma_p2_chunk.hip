@@ -1,0 +1,689 @@
+// Per-chunk kernels of the bf16 MFMA family (p = 2): forward (attention form inside the chunk +
+// query-state read-out + normalisation, App. E.1 / E.4 of arXiv 2507.04239) and the three
+// backward kernels (dQ, dK, dV).  See mfma_common.hpp for the embedding and the state layouts.
+//
+// All four share one shape: grid (T / 128, B*H), 128 threads; wave wv owns token rows
+// [64 wv, 64 wv + 64) of the block as four 16-token MFMA column blocks `ib`.  The block's own
+// rows (Q or K) sit in LDS as bf16; accumulators are transposed, acc[fb][ib] = 16 features (or
+// value columns) x 16 tokens.  Register use is kept under 256 so that two waves share a SIMD
+// and one wave's vector-ALU work (building phi, the Jacobian of phi) overlaps the other's MFMAs.
+#include "mfma_common.hpp"
+
+namespace pa {
+namespace mfma {
+namespace {
+
+constexpr int XB_PITCH = DH + 8;   // bf16 elements; 36 dwords, so 16 rows hit 16 distinct bank groups
+constexpr int RO_PF = 4;           // read-out steps kept in flight in registers (divides 72, even)
+
+typedef bf16_t XbRow[XB_PITCH];
+
+__device__ __forceinline__ float lds_bf(const bf16_t* p) { return __uint_as_float(((uint32_t)*p) << 16); }
+
+__device__ __forceinline__ void stage_rows(XbRow* Xb, const bf16_t* __restrict__ X, size_t row0, int tid) {
+    for (int e = tid; e < QBLK * DH / 8; e += 128) {
+        const int row = e >> 3, c8 = e & 7;
+        *(uint4*)&Xb[row][8 * c8] = *(const uint4*)(X + (row0 + row) * DH + 8 * c8);
+    }
+}
+
+// B (or A) operand of a 16-row block of the staged rows: features 32 ks + 8 g .. + 7 of row `row`
+__device__ __forceinline__ bf16x8 lds_frag(const XbRow* Xb, int row, int ks, int g) {
+    Frag f;
+    f.u = *(const uint4*)&Xb[row][32 * ks + 8 * g];
+    return f.v;
+}
+
+__device__ __forceinline__ bf16x8 glb_frag(const bf16_t* __restrict__ X, size_t row, int ks, int g) {
+    Frag f;
+    f.u = *(const uint4*)(X + row * DH + 32 * ks + 8 * g);
+    return f.v;
+}
+
+// A operand whose k-slots are the 8 tokens {t0 + 4g + r, t0 + 16 + 4g + r : r < 4} of feature row
+// `feat` of a feature-major copy (the k-slot order of a C-layout block fed back as a B operand)
+__device__ __forceinline__ bf16x8 tmajor_frag(const bf16_t* __restrict__ Xt_head, int feat, int t0, int g) {
+    const bf16_t* p = Xt_head + (size_t)(t0 / TBLK) * (DH * TBLK) + feat * TBLK + (t0 % TBLK) + 4 * g;
+    Frag f;
+    f.h[0] = *(const uint2*)p;
+    f.h[1] = *(const uint2*)(p + 16);
+    return f.v;
+}
+
+constexpr f32x4 ZERO4 = {0.f, 0.f, 0.f, 0.f};
+
+// ---- read-out: contraction over the expanded rows (query-state, App. E.4) -----------------------
+// acc[vb][ib] += S^T phi(xscale^(1/2) x)^T for the 64 tokens of wave wv.  `Sn` is one state in
+// layout "C", a linear stream of 72 steps (step u = 2 tile + s holds rows a = 4s + g of the
+// tile); RO_PF steps are in flight in registers, loads unconditional and clamped.
+__device__ __forceinline__ void readout(f32x4 (&acc)[4][4], const bf16_t* __restrict__ Sn, const XbRow* Xb,
+                                        float xscale, int wv, int r16, int g) {
+    Sn += (size_t)g * DH * 8 + r16 * 8;
+    constexpr int STEP_ELEMS = 4 * DH * 8;
+    Frag sf[RO_PF][4];
+#pragma unroll
+    for (int j = 0; j < RO_PF; ++j)
+#pragma unroll
+        for (int vb = 0; vb < 4; ++vb) sf[j][vb].u = *(const uint4*)(Sn + (size_t)j * STEP_ELEMS + 16 * vb * 8);
+    int ti = 0, tj = 0;
+    float xbv[4][8];
+    for (int u0 = 0; u0 < 2 * NTILES; u0 += RO_PF) {
+#pragma unroll
+        for (int j = 0; j < RO_PF; ++j) {
+            const int u = u0 + j;
+            const int s = j & 1;
+            if (s == 0 && ti == 0) {   // a new column block tj: x[8 tj .. 8 tj + 7] of each token
+#pragma unroll
+                for (int ib = 0; ib < 4; ++ib) {
+                    const uint4 raw = *(const uint4*)&Xb[64 * wv + 16 * ib + r16][8 * tj];
+                    xbv[ib][0] = bf_lo(raw.x); xbv[ib][1] = bf_hi(raw.x);
+                    xbv[ib][2] = bf_lo(raw.y); xbv[ib][3] = bf_hi(raw.y);
+                    xbv[ib][4] = bf_lo(raw.z); xbv[ib][5] = bf_hi(raw.z);
+                    xbv[ib][6] = bf_lo(raw.w); xbv[ib][7] = bf_hi(raw.w);
+                }
+            }
+            Frag pf[4];
+#pragma unroll
+            for (int ib = 0; ib < 4; ++ib) {
+                const float xa = xscale * lds_bf(&Xb[64 * wv + 16 * ib + r16][8 * ti + 4 * s + g]);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) pf[ib].v[i] = (__bf16)(xa * xbv[ib][i]);
+            }
+#pragma unroll
+            for (int vb = 0; vb < 4; ++vb)
+#pragma unroll
+                for (int ib = 0; ib < 4; ++ib) acc[vb][ib] = mfma16(sf[j][vb].v, pf[ib].v, acc[vb][ib]);
+            {
+                const int un = min(u + RO_PF, 2 * NTILES - 1);
+#pragma unroll
+                for (int vb = 0; vb < 4; ++vb)
+                    sf[j][vb].u = *(const uint4*)(Sn + (size_t)un * STEP_ELEMS + 16 * vb * 8);
+            }
+            if (s == 1) {
+                if (++ti > tj) {
+                    ++tj;
+                    ti = 0;
+                }
+            }
+        }
+    }
+}
+
+// ---- d phi: contraction over the value columns, then the Jacobian of phi ----------------------
+// For the 64 tokens of wave wv, x~ = xscale * x, and a state `Sn` in layout "R":
+//     A[(a,b), token] = sum_v S[(ti,tj,a,b), v] y[token, v]                       (MFMA)
+//     acc[8 ti + a][token] += sum_b A[(a,b)] x~[8 tj + b]        (term 1)
+//     acc[8 tj + b][token] += sum_a A[(a,b)] x~[8 ti + a]        (term 2)        (vector ALU)
+// i.e. acc += J_phi(x~)^T (S y), phi(x)_(ti,tj,a,b) = x[8ti+a] x[8tj+b] (tile multiplicity is in
+// S).  yf[ib][ks] are the B operands y^T (k-slots = value columns 32 ks + 8 g ..).
+//
+// The MFMA result block (rb, ib) holds, in lane (token r16, g), rows a = 2 rb + (g >> 1),
+// b = 4 (g & 1) + r.  Both terms are finished in registers: term 2 is summed over the tiles of a
+// column block tj and lands once per visit; term 1 is summed across the lane pair, exchanged
+// across the half-waves and added by the lane that owns feature 8 ti + a in the accumulator
+// layout (feature 16 fb + 4 g' + r').
+// Traversal order of the 36 tiles for the d phi contraction: by blocks of 2 x 2 tiles
+// (fbi, fbj) = (ti >> 1, tj >> 1), fbj outermost, so that inside one block the accumulator rows
+// both terms add to, acc[fbi] and acc[fbj], are compile-time names.  Entry = ti | tj << 8 |
+// tile index << 16; one sentinel at the end repeats the last tile.
+struct DphiOrder {
+    int v[NTILES + 1];
+};
+constexpr DphiOrder make_dphi_order() {
+    DphiOrder t{};
+    int k = 0;
+    for (int fbj = 0; fbj < 4; ++fbj)
+        for (int fbi = 0; fbi <= fbj; ++fbi)
+            for (int tj = 2 * fbj; tj < 2 * fbj + 2; ++tj)
+                for (int ti = 2 * fbi; ti < 2 * fbi + 2; ++ti)
+                    if (ti <= tj) t.v[k++] = ti | (tj << 8) | ((tj * (tj + 1) / 2 + ti) << 16);
+    t.v[k] = t.v[k - 1];
+    return t;
+}
+__constant__ DphiOrder DPHI_ORDER = make_dphi_order();
+constexpr int dphi_block_begin(int fbi, int fbj) {
+    int k = 0;
+    for (int j = 0; j < 4; ++j)
+        for (int i = 0; i <= j; ++i) {
+            if (i == fbi && j == fbj) return k;
+            k += (i == j) ? 3 : 4;
+        }
+    return k;
+}
+
+// state fragments of tile `tile`, row block rb: rows 16 rb + r16, value columns 32 ks + 8 g ..
+__device__ __forceinline__ void dphi_load_rb(Frag (&sf)[4][2], int rb, const bf16_t* __restrict__ Sl, int tile) {
+    const bf16_t* p = Sl + ((size_t)tile * 64 + 16 * rb) * DH;
+    sf[rb][0].u = *(const uint4*)p;
+    sf[rb][1].u = *(const uint4*)(p + 32);
+}
+
+template <int FBI, int FBJ>
+__device__ __forceinline__ void dphi_block(f32x4 (&acc)[4][4], Frag (&sf)[4][2], const bf16_t* __restrict__ Sl,
+                                           const Frag (&yf)[4][2], const XbRow* Xb, float xscale, int wv, int r16,
+                                           int g) {
+    constexpr int K0 = dphi_block_begin(FBI, FBJ), K1 = K0 + (FBI == FBJ ? 3 : 4);
+    float xb[4][4], u2[4][4];
+#pragma unroll 1
+    for (int k = K0; k < K1; ++k) {
+        const int code = DPHI_ORDER.v[k];
+        const int ti = code & 255, tj = (code >> 8) & 255;
+        const int next_tile = DPHI_ORDER.v[k + 1] >> 16;
+        if (ti == 2 * FBI) {   // first tile of a column block: x~[8 tj + 4 (g&1) + r]; restart term 2
+#pragma unroll
+            for (int ib = 0; ib < 4; ++ib) {
+                const uint2 raw = *(const uint2*)&Xb[64 * wv + 16 * ib + r16][8 * tj + 4 * (g & 1)];
+                xb[ib][0] = xscale * bf_lo(raw.x); xb[ib][1] = xscale * bf_hi(raw.x);
+                xb[ib][2] = xscale * bf_lo(raw.y); xb[ib][3] = xscale * bf_hi(raw.y);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) u2[ib][r] = 0.f;
+            }
+        }
+        const bool odd = (ti & 1) != 0;
+        const float m0 = (g == 2 * (ti & 1)) ? 1.f : 0.f;       // this lane owns the features of row blocks 0, 1
+        const float m1 = (g == 2 * (ti & 1) + 1) ? 1.f : 0.f;   // ... of row blocks 2, 3
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb) {
+            const float mk = (rb < 2) ? m0 : m1;
+#pragma unroll
+            for (int ib = 0; ib < 4; ++ib) {
+                f32x4 c = mfma16(sf[rb][0].v, yf[ib][0].v, ZERO4);
+                c = mfma16(sf[rb][1].v, yf[ib][1].v, c);
+                const float xa = xscale * lds_bf(&Xb[64 * wv + 16 * ib + r16][8 * ti + 2 * rb + (g >> 1)]);
+                float own = c[0] * xb[ib][0] + c[1] * xb[ib][1] + c[2] * xb[ib][2] + c[3] * xb[ib][3];
+                own += __shfl_xor(own, 16);                     // all of b; value of a = 2 rb + (g >> 1)
+                const float other = __shfl_xor(own, 32);        // value of a = 2 rb + 1 - (g >> 1)
+                const float h0 = odd ? other : own, h1 = odd ? own : other;   // a = 2 rb, 2 rb + 1 in the owner lane
+                acc[FBI][ib][2 * (rb & 1)] += mk * h0;
+                acc[FBI][ib][2 * (rb & 1) + 1] += mk * h1;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) u2[ib][r] += c[r] * xa;
+            }
+            dphi_load_rb(sf, rb, Sl, next_tile);   // ring: the slot is refilled as soon as it is consumed
+        }
+        if (ti == min(tj, 2 * FBI + 1)) {   // last tile of the column block here: land term 2
+            const float mk = ((g >> 1) == (tj & 1)) ? 1.f : 0.f;
+#pragma unroll
+            for (int ib = 0; ib < 4; ++ib)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[FBJ][ib][r] += mk * (u2[ib][r] + __shfl_xor(u2[ib][r], 32));
+        }
+    }
+}
+
+__device__ __forceinline__ void dphi(f32x4 (&acc)[4][4], const bf16_t* __restrict__ Sn, const Frag (&yf)[4][2],
+                                     const XbRow* Xb, float xscale, int wv, int r16, int g) {
+    const bf16_t* Sl = Sn + (size_t)r16 * DH + 8 * g;
+    Frag sf[4][2];
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb) dphi_load_rb(sf, rb, Sl, 0);
+    dphi_block<0, 0>(acc, sf, Sl, yf, Xb, xscale, wv, r16, g);
+    dphi_block<0, 1>(acc, sf, Sl, yf, Xb, xscale, wv, r16, g);
+    dphi_block<1, 1>(acc, sf, Sl, yf, Xb, xscale, wv, r16, g);
+    dphi_block<0, 2>(acc, sf, Sl, yf, Xb, xscale, wv, r16, g);
+    dphi_block<1, 2>(acc, sf, Sl, yf, Xb, xscale, wv, r16, g);
+    dphi_block<2, 2>(acc, sf, Sl, yf, Xb, xscale, wv, r16, g);
+    dphi_block<0, 3>(acc, sf, Sl, yf, Xb, xscale, wv, r16, g);
+    dphi_block<1, 3>(acc, sf, Sl, yf, Xb, xscale, wv, r16, g);
+    dphi_block<2, 3>(acc, sf, Sl, yf, Xb, xscale, wv, r16, g);
+    dphi_block<3, 3>(acc, sf, Sl, yf, Xb, xscale, wv, r16, g);
+}
+
+// ---- forward chunk kernel -------------------------------------------------------------------------
+// acc[vb][ib] = O^T: 16 value columns x 16 queries.
+__global__ __launch_bounds__(128, 2) void k_mfma_fwd_chunk(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
+                                                           const bf16_t* __restrict__ Vt, const bf16_t* __restrict__ StC,
+                                                           const bf16_t* __restrict__ Gam, bf16_t* __restrict__ O,
+                                                           float* __restrict__ Z, int T, int cs, float scale,
+                                                           int normalize) {
+    __shared__ __attribute__((aligned(16))) bf16_t Xb[QBLK][XB_PITCH];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int r16 = lane & 15, g = lane >> 4;
+    const int bh = blockIdx.y;
+    const int i0 = blockIdx.x * QBLK;         // first query row of the block
+    const int n = i0 / cs;                    // state entering the stretch this block lies in
+    const int nstate = T / cs;
+    const size_t head_tok = (size_t)bh * T;
+    const bf16_t* Vt_head = Vt + (size_t)bh * DH * T;
+    const float s2 = scale * scale;
+
+    stage_rows(Xb, Q, head_tok + i0, tid);
+    f32x4 acc[4][4];
+#pragma unroll
+    for (int vb = 0; vb < 4; ++vb)
+#pragma unroll
+        for (int ib = 0; ib < 4; ++ib) acc[vb][ib] = ZERO4;
+    float zsum[4] = {0.f, 0.f, 0.f, 0.f};     // per query block: partial sum of scores (this lane's k-slots)
+    __syncthreads();
+
+    // attention form over the keys of the stretch, up to the diagonal
+    for (int kb0 = n * cs; kb0 <= i0; kb0 += QBLK) {
+        const bool diag = kb0 == i0;
+        const int nsteps = diag ? 2 * (wv + 1) : 4;     // 32-key steps this wave needs
+        for (int s = 0; s < nsteps; ++s) {
+            const int key0 = kb0 + 32 * s;
+            Frag pf[4];   // P^T as B operand; k-slots: keys 4g+r of block 0, then of block 1
+#pragma unroll
+            for (int jb = 0; jb < 2; ++jb) {
+                const size_t krow = head_tok + key0 + 16 * jb + r16;
+                const bf16x8 kf0 = glb_frag(K, krow, 0, g), kf1 = glb_frag(K, krow, 1, g);
+#pragma unroll
+                for (int ib = 0; ib < 4; ++ib) {
+                    const int qrow = 64 * wv + 16 * ib + r16;
+                    f32x4 c = mfma16(kf0, lds_frag(Xb, qrow, 0, g), ZERO4);
+                    c = mfma16(kf1, lds_frag(Xb, qrow, 1, g), c);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        float pv = s2 * c[r] * c[r];
+                        if (diag && key0 + 16 * jb + 4 * g + r > i0 + qrow) pv = 0.f;
+                        zsum[ib] += pv;
+                        pf[ib].v[4 * jb + r] = (__bf16)pv;
+                    }
+                }
+            }
+#pragma unroll
+            for (int vb = 0; vb < 4; ++vb) {
+                const bf16x8 vf = tmajor_frag(Vt_head, 16 * vb + r16, key0, g);
+#pragma unroll
+                for (int ib = 0; ib < 4; ++ib) acc[vb][ib] = mfma16(vf, pf[ib].v, acc[vb][ib]);
+            }
+        }
+    }
+
+    if (n > 0) {
+        // phi(q~) . gamma = q~^T Gamma q~
+        const bf16_t* Gn = Gam + (size_t)(bh * nstate + n) * DH * DH;
+#pragma unroll 1
+        for (int ab = 0; ab < 4; ++ab) {
+            const bf16x8 gm0 = glb_frag(Gn, 16 * ab + r16, 0, g), gm1 = glb_frag(Gn, 16 * ab + r16, 1, g);
+#pragma unroll
+            for (int ib = 0; ib < 4; ++ib) {
+                const int qrow = 64 * wv + 16 * ib + r16;
+                f32x4 c = mfma16(gm0, lds_frag(Xb, qrow, 0, g), ZERO4);
+                c = mfma16(gm1, lds_frag(Xb, qrow, 1, g), c);
+                const uint2 raw = *(const uint2*)&Xb[qrow][16 * ab + 4 * g];
+                zsum[ib] += s2 * (c[0] * bf_lo(raw.x) + c[1] * bf_hi(raw.x) + c[2] * bf_lo(raw.y) + c[3] * bf_hi(raw.y));
+            }
+        }
+        readout(acc, StC + (size_t)(bh * nstate + n) * STATE_ELEMS, Xb, s2, wv, r16, g);
+    }
+
+#pragma unroll
+    for (int ib = 0; ib < 4; ++ib) {
+        float z = zsum[ib];
+        z += __shfl_xor(z, 16);
+        z += __shfl_xor(z, 32);
+        const float inv = normalize ? (z != 0.f ? 1.f / z : 0.f) : 1.f;
+        const size_t row = head_tok + i0 + 64 * wv + 16 * ib + r16;
+#pragma unroll
+        for (int vb = 0; vb < 4; ++vb) {
+            bf16x4 o;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) o[r] = (__bf16)(acc[vb][ib][r] * inv);
+            *(bf16x4*)(O + row * DH + 16 * vb + 4 * g) = o;
+        }
+        if (Z != nullptr && g == 0) Z[row] = z;
+    }
+}
+
+// ---- backward: preparation -----------------------------------------------------------------------
+// ghat = dO / Z (bf16, [BH][T][DH]) and gz = -(ghat . O) (float32, [BH][T]); un-normalised:
+// ghat = dO, gz = 0.  Rows with Z == 0 give zeros.  One 16-lane group per row.
+__global__ __launch_bounds__(256) void k_mfma_bwd_prep(const bf16_t* __restrict__ dO, const bf16_t* __restrict__ O,
+                                                       const float* __restrict__ Z, bf16_t* __restrict__ Gh,
+                                                       float* __restrict__ gz, long long rows, int normalize) {
+    const long long row = (long long)blockIdx.x * 16 + (threadIdx.x >> 4);
+    const int c4 = threadIdx.x & 15;
+    if (row >= rows) return;
+    const uint2 graw = *(const uint2*)(dO + row * DH + 4 * c4);
+    const float gv[4] = {bf_lo(graw.x), bf_hi(graw.x), bf_lo(graw.y), bf_hi(graw.y)};
+    float inv = 1.f;
+    if (normalize) {
+        const float z = Z[row];
+        inv = z != 0.f ? 1.f / z : 0.f;
+    }
+    bf16x4 o;
+    float gr[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        o[i] = (__bf16)(gv[i] * inv);
+        gr[i] = (float)o[i];
+    }
+    *(bf16x4*)(Gh + row * DH + 4 * c4) = o;
+    // gz is formed from the ROUNDED ghat, so that ghat . v_j + gz = ghat . (v_j - O_i) keeps its
+    // exact cancellations (a row that attends to one key only gets a zero gradient, as it must)
+    float delta = 0.f;
+    if (normalize) {
+        const uint2 oraw = *(const uint2*)(O + row * DH + 4 * c4);
+        delta = gr[0] * bf_lo(oraw.x) + gr[1] * bf_hi(oraw.x) + gr[2] * bf_lo(oraw.y) + gr[3] * bf_hi(oraw.y);
+        delta += __shfl_xor(delta, 1);
+        delta += __shfl_xor(delta, 2);
+        delta += __shfl_xor(delta, 4);
+        delta += __shfl_xor(delta, 8);
+    }
+    if (c4 == 0) gz[row] = -delta;
+}
+
+// ---- backward, queries: dQ ------------------------------------------------------------------------
+//   dq_i = scale * [ sum_{j<=i, same stretch} t_ij k_j + 2 gz_i Gamma q~_i + J_phi(q~_i)^T (S_n ghat_i) ]
+//   q~ = scale q,  s_ij = q~_i . k_j,  t_ij = 2 s_ij (ghat_i . v_j + gz_i)
+// acc[fb][ib] = (the bracket)^T: 16 features x 16 queries.
+__global__ __launch_bounds__(128, 2) void k_mfma_bwd_dq(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
+                                                        const bf16_t* __restrict__ V, const bf16_t* __restrict__ Gh,
+                                                        const float* __restrict__ gz, const bf16_t* __restrict__ Kt,
+                                                        const bf16_t* __restrict__ StR, const bf16_t* __restrict__ Gam,
+                                                        bf16_t* __restrict__ dQ, int T, int cs, float scale) {
+    __shared__ __attribute__((aligned(16))) bf16_t Xb[QBLK][XB_PITCH];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int r16 = lane & 15, g = lane >> 4;
+    const int bh = blockIdx.y;
+    const int i0 = blockIdx.x * QBLK;
+    const int n = i0 / cs;
+    const int nstate = T / cs;
+    const size_t head_tok = (size_t)bh * T;
+    const bf16_t* Kt_head = Kt + (size_t)bh * DH * T;
+
+    stage_rows(Xb, Q, head_tok + i0, tid);
+    Frag gf[4][2];   // ghat^T of this wave's queries as B operands
+    float gzq[4];
+#pragma unroll
+    for (int ib = 0; ib < 4; ++ib) {
+        const size_t row = head_tok + i0 + 64 * wv + 16 * ib + r16;
+        gf[ib][0].v = glb_frag(Gh, row, 0, g);
+        gf[ib][1].v = glb_frag(Gh, row, 1, g);
+        gzq[ib] = gz[row];
+    }
+    f32x4 acc[4][4];
+#pragma unroll
+    for (int fb = 0; fb < 4; ++fb)
+#pragma unroll
+        for (int ib = 0; ib < 4; ++ib) acc[fb][ib] = ZERO4;
+    __syncthreads();
+
+    for (int kb0 = n * cs; kb0 <= i0; kb0 += QBLK) {
+        const bool diag = kb0 == i0;
+        const int nsteps = diag ? 2 * (wv + 1) : 4;
+        for (int s = 0; s < nsteps; ++s) {
+            const int key0 = kb0 + 32 * s;
+            Frag tf[4];
+#pragma unroll
+            for (int jb = 0; jb < 2; ++jb) {
+                const size_t krow = head_tok + key0 + 16 * jb + r16;
+                const bf16x8 kf0 = glb_frag(K, krow, 0, g), kf1 = glb_frag(K, krow, 1, g);
+                const bf16x8 vf0 = glb_frag(V, krow, 0, g), vf1 = glb_frag(V, krow, 1, g);
+#pragma unroll
+                for (int ib = 0; ib < 4; ++ib) {
+                    const int qrow = 64 * wv + 16 * ib + r16;
+                    f32x4 c = mfma16(kf0, lds_frag(Xb, qrow, 0, g), ZERO4);
+                    c = mfma16(kf1, lds_frag(Xb, qrow, 1, g), c);
+                    f32x4 e = mfma16(vf0, gf[ib][0].v, ZERO4);
+                    e = mfma16(vf1, gf[ib][1].v, e);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        float tv = 2.f * scale * c[r] * (e[r] + gzq[ib]);
+                        if (diag && key0 + 16 * jb + 4 * g + r > i0 + qrow) tv = 0.f;
+                        tf[ib].v[4 * jb + r] = (__bf16)tv;
+                    }
+                }
+            }
+#pragma unroll
+            for (int fb = 0; fb < 4; ++fb) {
+                const bf16x8 ktf = tmajor_frag(Kt_head, 16 * fb + r16, key0, g);
+#pragma unroll
+                for (int ib = 0; ib < 4; ++ib) acc[fb][ib] = mfma16(ktf, tf[ib].v, acc[fb][ib]);
+            }
+        }
+    }
+
+    if (n > 0) {
+        // normaliser: d/dq~ of gz q~^T Gamma q~ = 2 gz Gamma q~
+        const bf16_t* Gn = Gam + (size_t)(bh * nstate + n) * DH * DH;
+#pragma unroll
+        for (int ab = 0; ab < 4; ++ab) {
+            const bf16x8 gm0 = glb_frag(Gn, 16 * ab + r16, 0, g), gm1 = glb_frag(Gn, 16 * ab + r16, 1, g);
+#pragma unroll
+            for (int ib = 0; ib < 4; ++ib) {
+                const int qrow = 64 * wv + 16 * ib + r16;
+                f32x4 c = mfma16(gm0, lds_frag(Xb, qrow, 0, g), ZERO4);
+                c = mfma16(gm1, lds_frag(Xb, qrow, 1, g), c);
+                const float f = 2.f * gzq[ib] * scale;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[ab][ib][r] += f * c[r];
+            }
+        }
+        dphi(acc, StR + (size_t)(bh * nstate + n) * STATE_ELEMS, gf, Xb, scale, wv, r16, g);
+    }
+#pragma unroll
+    for (int ib = 0; ib < 4; ++ib) {
+        const size_t row = head_tok + i0 + 64 * wv + 16 * ib + r16;
+#pragma unroll
+        for (int fb = 0; fb < 4; ++fb) {
+            bf16x4 o;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) o[r] = (__bf16)(scale * acc[fb][ib][r]);
+            *(bf16x4*)(dQ + row * DH + 16 * fb + 4 * g) = o;
+        }
+    }
+}
+
+// ---- backward, keys: dK ---------------------------------------------------------------------------
+//   dk_j = scale * sum_{i>=j, same stretch} t_ij q_i + 2 Omega_m k_j + J_phi(k_j)^T (R_m v_j)
+// (R and Omega already carry scale^2).  acc[fb][jb] = dK^T: 16 features x 16 keys.
+__global__ __launch_bounds__(128, 2) void k_mfma_bwd_dk(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
+                                                        const bf16_t* __restrict__ V, const bf16_t* __restrict__ Gh,
+                                                        const float* __restrict__ gz, const bf16_t* __restrict__ Qt,
+                                                        const bf16_t* __restrict__ RtR, const bf16_t* __restrict__ Omg,
+                                                        bf16_t* __restrict__ dK, int T, int cs, float scale) {
+    __shared__ __attribute__((aligned(16))) bf16_t Xb[QBLK][XB_PITCH];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int r16 = lane & 15, g = lane >> 4;
+    const int bh = blockIdx.y;
+    const int j0 = blockIdx.x * QBLK;
+    const int m = j0 / cs;
+    const int nstate = T / cs;
+    const size_t head_tok = (size_t)bh * T;
+    const bf16_t* Qt_head = Qt + (size_t)bh * DH * T;
+
+    stage_rows(Xb, K, head_tok + j0, tid);
+    Frag vf[4][2];   // V^T of this wave's keys as B operands
+#pragma unroll
+    for (int jb = 0; jb < 4; ++jb) {
+        const size_t row = head_tok + j0 + 64 * wv + 16 * jb + r16;
+        vf[jb][0].v = glb_frag(V, row, 0, g);
+        vf[jb][1].v = glb_frag(V, row, 1, g);
+    }
+    f32x4 acc[4][4];
+#pragma unroll
+    for (int fb = 0; fb < 4; ++fb)
+#pragma unroll
+        for (int jb = 0; jb < 4; ++jb) acc[fb][jb] = ZERO4;
+    __syncthreads();
+
+    const int q_hi = (m + 1) * cs;   // queries of the same stretch, from the diagonal block on
+    for (int qb0 = j0; qb0 < q_hi; qb0 += QBLK) {
+        const bool diag = qb0 == j0;
+        for (int s = diag ? 2 * wv : 0; s < 4; ++s) {   // queries before this wave's first key are masked
+            const int q0 = qb0 + 32 * s;
+            Frag tf[4];
+#pragma unroll
+            for (int ibq = 0; ibq < 2; ++ibq) {
+                const size_t qrow = head_tok + q0 + 16 * ibq + r16;
+                const bf16x8 qa0 = glb_frag(Q, qrow, 0, g), qa1 = glb_frag(Q, qrow, 1, g);
+                const bf16x8 ga0 = glb_frag(Gh, qrow, 0, g), ga1 = glb_frag(Gh, qrow, 1, g);
+                const float4 gz4 = *(const float4*)(gz + head_tok + q0 + 16 * ibq + 4 * g);
+                const float gzr[4] = {gz4.x, gz4.y, gz4.z, gz4.w};
+#pragma unroll
+                for (int jb = 0; jb < 4; ++jb) {
+                    const int krow = 64 * wv + 16 * jb + r16;
+                    f32x4 c = mfma16(qa0, lds_frag(Xb, krow, 0, g), ZERO4);
+                    c = mfma16(qa1, lds_frag(Xb, krow, 1, g), c);
+                    f32x4 e = mfma16(ga0, vf[jb][0].v, ZERO4);
+                    e = mfma16(ga1, vf[jb][1].v, e);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        float tv = 2.f * scale * c[r] * (e[r] + gzr[r]);
+                        if (diag && q0 + 16 * ibq + 4 * g + r < j0 + krow) tv = 0.f;
+                        tf[jb].v[4 * ibq + r] = (__bf16)tv;
+                    }
+                }
+            }
+#pragma unroll
+            for (int fb = 0; fb < 4; ++fb) {
+                const bf16x8 qtf = tmajor_frag(Qt_head, 16 * fb + r16, q0, g);
+#pragma unroll
+                for (int jb = 0; jb < 4; ++jb) acc[fb][jb] = mfma16(qtf, tf[jb].v, acc[fb][jb]);
+            }
+        }
+    }
+    // d s / d k = scale q
+#pragma unroll
+    for (int fb = 0; fb < 4; ++fb)
+#pragma unroll
+        for (int jb = 0; jb < 4; ++jb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[fb][jb][r] *= scale;
+
+    if (m < nstate - 1) {
+        const bf16_t* Om = Omg + (size_t)(bh * nstate + m) * DH * DH;
+#pragma unroll
+        for (int ab = 0; ab < 4; ++ab) {
+            const bf16x8 gm0 = glb_frag(Om, 16 * ab + r16, 0, g), gm1 = glb_frag(Om, 16 * ab + r16, 1, g);
+#pragma unroll
+            for (int jb = 0; jb < 4; ++jb) {
+                const int krow = 64 * wv + 16 * jb + r16;
+                f32x4 c = mfma16(gm0, lds_frag(Xb, krow, 0, g), ZERO4);
+                c = mfma16(gm1, lds_frag(Xb, krow, 1, g), c);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[ab][jb][r] += 2.f * c[r];
+            }
+        }
+        dphi(acc, RtR + (size_t)(bh * nstate + m) * STATE_ELEMS, vf, Xb, 1.f, wv, r16, g);
+    }
+#pragma unroll
+    for (int jb = 0; jb < 4; ++jb) {
+        const size_t row = head_tok + j0 + 64 * wv + 16 * jb + r16;
+#pragma unroll
+        for (int fb = 0; fb < 4; ++fb) {
+            bf16x4 o;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) o[r] = (__bf16)acc[fb][jb][r];
+            *(bf16x4*)(dK + row * DH + 16 * fb + 4 * g) = o;
+        }
+    }
+}
+
+// ---- backward, values: dV ---------------------------------------------------------------------------
+//   dv_j = sum_{i>=j, same stretch} s_ij^2 ghat_i + R_m^T phi(k_j)
+// acc[vb][jb] = dV^T: 16 value columns x 16 keys.
+__global__ __launch_bounds__(128, 2) void k_mfma_bwd_dv(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
+                                                        const bf16_t* __restrict__ Ght, const bf16_t* __restrict__ RtC,
+                                                        bf16_t* __restrict__ dV, int T, int cs, float scale) {
+    __shared__ __attribute__((aligned(16))) bf16_t Xb[QBLK][XB_PITCH];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int r16 = lane & 15, g = lane >> 4;
+    const int bh = blockIdx.y;
+    const int j0 = blockIdx.x * QBLK;
+    const int m = j0 / cs;
+    const int nstate = T / cs;
+    const size_t head_tok = (size_t)bh * T;
+    const bf16_t* Ght_head = Ght + (size_t)bh * DH * T;
+    const float s2 = scale * scale;
+
+    stage_rows(Xb, K, head_tok + j0, tid);
+    f32x4 acc[4][4];
+#pragma unroll
+    for (int vb = 0; vb < 4; ++vb)
+#pragma unroll
+        for (int jb = 0; jb < 4; ++jb) acc[vb][jb] = ZERO4;
+    __syncthreads();
+
+    const int q_hi = (m + 1) * cs;
+    for (int qb0 = j0; qb0 < q_hi; qb0 += QBLK) {
+        const bool diag = qb0 == j0;
+        for (int s = diag ? 2 * wv : 0; s < 4; ++s) {
+            const int q0 = qb0 + 32 * s;
+            Frag af[4];
+#pragma unroll
+            for (int ibq = 0; ibq < 2; ++ibq) {
+                const size_t qrow = head_tok + q0 + 16 * ibq + r16;
+                const bf16x8 qa0 = glb_frag(Q, qrow, 0, g), qa1 = glb_frag(Q, qrow, 1, g);
+#pragma unroll
+                for (int jb = 0; jb < 4; ++jb) {
+                    const int krow = 64 * wv + 16 * jb + r16;
+                    f32x4 c = mfma16(qa0, lds_frag(Xb, krow, 0, g), ZERO4);
+                    c = mfma16(qa1, lds_frag(Xb, krow, 1, g), c);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        float av = s2 * c[r] * c[r];
+                        if (diag && q0 + 16 * ibq + 4 * g + r < j0 + krow) av = 0.f;
+                        af[jb].v[4 * ibq + r] = (__bf16)av;
+                    }
+                }
+            }
+#pragma unroll
+            for (int vb = 0; vb < 4; ++vb) {
+                const bf16x8 gtf = tmajor_frag(Ght_head, 16 * vb + r16, q0, g);
+#pragma unroll
+                for (int jb = 0; jb < 4; ++jb) acc[vb][jb] = mfma16(gtf, af[jb].v, acc[vb][jb]);
+            }
+        }
+    }
+    if (m < nstate - 1) readout(acc, RtC + (size_t)(bh * nstate + m) * STATE_ELEMS, Xb, 1.f, wv, r16, g);
+#pragma unroll
+    for (int jb = 0; jb < 4; ++jb) {
+        const size_t row = head_tok + j0 + 64 * wv + 16 * jb + r16;
+#pragma unroll
+        for (int vb = 0; vb < 4; ++vb) {
+            bf16x4 o;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) o[r] = (__bf16)acc[vb][jb][r];
+            *(bf16x4*)(dV + row * DH + 16 * vb + 4 * g) = o;
+        }
+    }
+}
+
+}  // namespace
+
+bool launch_fwd_chunk(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* Vt, const bf16_t* stC,
+                      const bf16_t* gam, bf16_t* O, float* Z, int BH, int T, int cs, float scale, int normalize) {
+    LaunchScope ls("mfma_fwd_chunk", s);
+    hipLaunchKernelGGL(k_mfma_fwd_chunk, dim3(T / QBLK, BH), dim3(128), 0, s, Q, K, Vt, stC, gam, O, Z, T, cs, scale,
+                       normalize);
+    return launch_ok();
+}
+
+bool launch_bwd_prep(hipStream_t s, const bf16_t* dO, const bf16_t* O, const float* Z, bf16_t* Gh, float* gz,
+                     long long rows, int normalize) {
+    LaunchScope ls("mfma_bwd_prep", s);
+    hipLaunchKernelGGL(k_mfma_bwd_prep, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, s, dO, O, Z, Gh, gz, rows,
+                       normalize);
+    return launch_ok();
+}
+
+bool launch_bwd_dq(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* V, const bf16_t* Gh,
+                   const float* gz, const bf16_t* Kt, const bf16_t* stR, const bf16_t* gam, bf16_t* dQ, int BH, int T,
+                   int cs, float scale) {
+    LaunchScope ls("mfma_bwd_dq", s);
+    hipLaunchKernelGGL(k_mfma_bwd_dq, dim3(T / QBLK, BH), dim3(128), 0, s, Q, K, V, Gh, gz, Kt, stR, gam, dQ, T, cs,
+                       scale);
+    return launch_ok();
+}
+
+bool launch_bwd_dk(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* V, const bf16_t* Gh,
+                   const float* gz, const bf16_t* Qt, const bf16_t* rtR, const bf16_t* omg, bf16_t* dK, int BH, int T,
+                   int cs, float scale) {
+    LaunchScope ls("mfma_bwd_dk", s);
+    hipLaunchKernelGGL(k_mfma_bwd_dk, dim3(T / QBLK, BH), dim3(128), 0, s, Q, K, V, Gh, gz, Qt, rtR, omg, dK, T, cs,
+                       scale);
+    return launch_ok();
+}
+
+bool launch_bwd_dv(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* Ght, const bf16_t* rtC,
+                   bf16_t* dV, int BH, int T, int cs, float scale) {
+    LaunchScope ls("mfma_bwd_dv", s);
+    hipLaunchKernelGGL(k_mfma_bwd_dv, dim3(T / QBLK, BH), dim3(128), 0, s, Q, K, Ght, rtC, dV, T, cs, scale);
+    return launch_ok();
+}
+
+}  // namespace mfma
+}  // namespace pa

@@ -1,0 +1,298 @@
+// State scan of the bf16 MFMA family (p = 2): feature-major copies of the inputs, and the fused
+// update-state + cumulative sum over chunks.  See mfma_common.hpp for the embedding and layouts.
+#include "mfma_common.hpp"
+
+namespace pa {
+namespace mfma {
+namespace {
+
+// ---- token-major -> feature-major in blocks of 64 tokens -----------------------------------
+// [BH][T][DH] -> [BH][T/64][DH][64] (bf16).  Each block is 8 KB contiguous, so the readers'
+// accesses stay dense (rows of a plain [DH][T] transpose would sit a power of two apart and
+// pile onto the same memory channel).
+
+__global__ __launch_bounds__(256) void k_transpose(const bf16_t* __restrict__ in, bf16_t* __restrict__ out, int T) {
+    __shared__ bf16_t tile[TBLK][DH + 2];
+    const int bh = blockIdx.y, blk = blockIdx.x, tid = threadIdx.x;
+    const bf16_t* src = in + ((size_t)bh * T + (size_t)blk * TBLK) * DH;
+    for (int e = tid; e < TBLK * DH; e += 256) tile[e / DH][e % DH] = src[e];
+    __syncthreads();
+    bf16_t* dst = out + ((size_t)bh * (T / TBLK) + blk) * DH * TBLK;
+    for (int e = tid; e < TBLK * DH; e += 256) dst[e] = tile[e % TBLK][e / TBLK];
+}
+
+// ---- state scan ----------------------------------------------------------------------------
+// Fused update-state + cumulative sum over chunks (App. E.2 + E.3, no gating), used for
+//   the forward state     S_n = sum_{j <  n cs}     phi(k_j) v_j^T        (X = K, Y = V)
+//   the state gradient    R_m = sum_{i >= (m+1) cs} phi(q_i) ghat_i^T     (X = Q, Y = dO/Z, REV)
+// grid (NPAIR + 1, BH), 256 threads.  Workgroup `pair` owns the two 64 x DH state tiles
+// 2 pair, 2 pair + 1; wave w owns 32 rows (a in 4(w&1) .. +3) of tile 2 pair + (w >> 1).
+// Workgroup NPAIR owns the normaliser in its d x d form: Gamma = sum k k^T, or
+// Omega = sum gz_i q_i q_i^T for the gradient (same code: the A operand is x itself, times the
+// weight, and the B operand comes from X instead of Y; only waves 0 and 1 have rows).
+// The state is written every `cs` tokens, before the tokens of that stretch are added.
+//
+// Each workgroup walks the sequence in stages of 128 tokens.  A stage's X (as float32) and Y
+// (bf16) are staged in LDS, feature-major, and shared by the four waves; the global loads of
+// SCAN_PF further stages are in flight in registers.
+//
+constexpr int NPAIR = NTILES / 2;
+constexpr int SCAN_TOK = 128;                  // tokens per stage
+constexpr int SCAN_PF = 3;                     // stages in flight in registers
+constexpr int XS_PITCH = SCAN_TOK + 4;         // floats; pitch = 4 mod 64 banks
+constexpr int YS_PITCH = SCAN_TOK + 8;         // bf16;   pitch = 4 mod 64 banks (in dwords)
+constexpr int TR_PITCH = DH + 8;               // bf16
+static_assert(NTILES % 2 == 0, "tiles are handled in pairs");
+
+struct ScanSmem {
+    float xs[2][DH][XS_PITCH];
+    bf16_t ys[2][DH][YS_PITCH];
+    float ws[2][SCAN_TOK];
+    bf16_t tr[4][32][TR_PITCH];
+};
+
+template <bool GAMMA, bool REV, bool WC, bool WR>
+__device__ __forceinline__ void scan_body(const bf16_t* __restrict__ Xt, const bf16_t* __restrict__ Yt,
+                                          const float* __restrict__ wgt, bf16_t* __restrict__ StC,
+                                          bf16_t* __restrict__ StR, bf16_t* __restrict__ Gam, int T, int cs,
+                                          float out_scale, ScanSmem& sm) {
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int r16 = lane & 15, g = lane >> 4;
+    const int bh = blockIdx.y;
+    const int nstate = T / cs;
+    const int tile = GAMMA ? 0 : 2 * (int)blockIdx.x + (w >> 1);
+    int ti = 0, tj = 0;
+    for (int l = 0; l < tile; ++l) {
+        if (++ti > tj) {
+            ++tj;
+            ti = 0;
+        }
+    }
+    const float mult = GAMMA ? out_scale : ((ti == tj) ? 1.f : 2.f) * out_scale;
+    // feature rows this lane expands: row block rbk in {0,1} covers tile rows 32 (w&1) + 16 rbk + r16
+    //   tiles: a = 4 (w&1) + 2 rbk + (r16 >> 3), b = r16 & 7;   Gamma: feature 32 w + 16 rbk + r16
+    const int fa0 = GAMMA ? (32 * (w & 1) + r16) : 8 * ti + 4 * (w & 1) + (r16 >> 3);
+    const int fa_step = GAMMA ? 16 : 2;
+    const int fb = 8 * tj + (r16 & 7);
+    const bool has_rows = !GAMMA || w < 2;
+
+    // global -> LDS staging: thread t moves pieces t, t + 256, t + 512, t + 768 of the stage; a
+    // piece is 8 tokens of one feature (16 bytes of bf16) of X and of Y
+    const bf16_t* Xh = Xt + (size_t)bh * DH * T;
+    const bf16_t* Yh = (GAMMA ? Xt : Yt) + (size_t)bh * DH * T;
+    const float* Wh = (GAMMA && REV) ? wgt + (size_t)bh * T : nullptr;
+    int p_feat[4], p_tok[4], p_off[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int id = tid + 256 * q;
+        p_feat[q] = id >> 4;
+        p_tok[q] = 8 * (id & 15);                                        // token inside the stage
+        p_off[q] = (p_tok[q] >> 6) * (DH * TBLK) + p_feat[q] * TBLK + (p_tok[q] & 63);
+    }
+
+    f32x4 acc[2][4];
+#pragma unroll
+    for (int rbk = 0; rbk < 2; ++rbk)
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb) acc[rbk][cb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    auto write_state = [&](int n) {
+        if (!GAMMA) {
+            const size_t tbase = ((size_t)(bh * nstate + n) * NTILES + tile) * TILE_ELEMS;
+            if (WC) {
+                bf16_t* dst = StC + tbase;
+#pragma unroll
+                for (int rbk = 0; rbk < 2; ++rbk) {
+                    const int a = 4 * (w & 1) + 2 * rbk + (g >> 1), b0 = 4 * (g & 1);
+#pragma unroll
+                    for (int cb = 0; cb < 4; ++cb) {
+                        bf16x4 o;
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) o[r] = (__bf16)(acc[rbk][cb][r] * mult);
+                        *(bf16x4*)(dst + ((a * DH + 16 * cb + r16) * 8 + b0)) = o;
+                    }
+                }
+            }
+            if (WR) {
+                // transpose the wave's 32 x 64 block through its private LDS patch, then store rows
+#pragma unroll
+                for (int rbk = 0; rbk < 2; ++rbk)
+#pragma unroll
+                    for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            sm.tr[w][16 * rbk + 4 * g + r][16 * cb + r16] = f32_to_bf16(acc[rbk][cb][r] * mult);
+                bf16_t* dst = StR + tbase + (size_t)32 * (w & 1) * DH;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int unit = lane + 64 * q;          // 32 rows x 8 units of 16 bytes
+                    const uint4 val = *(const uint4*)&sm.tr[w][unit >> 3][8 * (unit & 7)];
+                    *(uint4*)(dst + (unit >> 3) * DH + 8 * (unit & 7)) = val;
+                }
+            }
+        } else if (has_rows) {
+            bf16_t* dst = Gam + (size_t)(bh * nstate + n) * DH * DH;
+#pragma unroll
+            for (int rbk = 0; rbk < 2; ++rbk)
+#pragma unroll
+                for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        dst[(32 * w + 16 * rbk + 4 * g + r) * DH + 16 * cb + r16] = f32_to_bf16(acc[rbk][cb][r] * mult);
+        }
+    };
+
+    // Stretches at the far end never feed a state that is written, so the walk stops early.
+    const int nstage = (T - cs) / SCAN_TOK;
+    const int nstage_all = T / SCAN_TOK;
+    if (nstage > 0) {
+        // Register ring: slot J holds the global data of stage (st0 + J).  Every load is
+        // unconditional (indices are clamped instead of branching) so that the compiler can
+        // count the loads in flight instead of waiting for all of them.  Separately named
+        // registers and macros instead of arrays and lambdas: the slot has to be a
+        // compile-time name or the ring is demoted to scratch memory.
+#define PA_SLOT(J) uint4 x0_##J, x1_##J, x2_##J, x3_##J, y0_##J, y1_##J, y2_##J, y3_##J; float wv_##J;
+        PA_SLOT(0) PA_SLOT(1) PA_SLOT(2)
+#undef PA_SLOT
+        static_assert(SCAN_PF == 3, "the ring below is written out for 3 slots");
+#define PA_LOAD_STAGE(J, ST)                                                              \
+    {                                                                                     \
+        const int sc_ = min((ST), nstage - 1);                                            \
+        const int sidx_ = REV ? nstage_all - 1 - sc_ : sc_;                               \
+        const size_t so_ = (size_t)sidx_ * (2 * DH * TBLK);                               \
+        x0_##J = *(const uint4*)(Xh + so_ + p_off[0]);                                    \
+        x1_##J = *(const uint4*)(Xh + so_ + p_off[1]);                                    \
+        x2_##J = *(const uint4*)(Xh + so_ + p_off[2]);                                    \
+        x3_##J = *(const uint4*)(Xh + so_ + p_off[3]);                                    \
+        y0_##J = *(const uint4*)(Yh + so_ + p_off[0]);                                    \
+        y1_##J = *(const uint4*)(Yh + so_ + p_off[1]);                                    \
+        y2_##J = *(const uint4*)(Yh + so_ + p_off[2]);                                    \
+        y3_##J = *(const uint4*)(Yh + so_ + p_off[3]);                                    \
+        if (GAMMA && REV) wv_##J = Wh[(size_t)sidx_ * SCAN_TOK + (tid & (SCAN_TOK - 1))]; \
+    }
+#define PA_FILL_X(BUF, Q, XR)                                                             \
+    {                                                                                     \
+        float* d_ = &sm.xs[BUF][p_feat[Q]][p_tok[Q]];                                     \
+        *(float4*)d_ = make_float4(bf_lo(XR.x), bf_hi(XR.x), bf_lo(XR.y), bf_hi(XR.y));   \
+        *(float4*)(d_ + 4) = make_float4(bf_lo(XR.z), bf_hi(XR.z), bf_lo(XR.w), bf_hi(XR.w)); \
+    }
+#define PA_CONSUME(J, ST, BUF)                                                                \
+    if ((ST) < nstage) { /* uniform; no global loads inside this branch */                    \
+        const int edge_ = REV ? T - (ST) * SCAN_TOK : (ST) * SCAN_TOK;                        \
+        if (edge_ % cs == 0) write_state(REV ? edge_ / cs - 1 : edge_ / cs);                  \
+        PA_FILL_X(BUF, 0, x0_##J) PA_FILL_X(BUF, 1, x1_##J)                                   \
+        PA_FILL_X(BUF, 2, x2_##J) PA_FILL_X(BUF, 3, x3_##J)                                   \
+        *(uint4*)&sm.ys[BUF][p_feat[0]][p_tok[0]] = y0_##J;                                   \
+        *(uint4*)&sm.ys[BUF][p_feat[1]][p_tok[1]] = y1_##J;                                   \
+        *(uint4*)&sm.ys[BUF][p_feat[2]][p_tok[2]] = y2_##J;                                   \
+        *(uint4*)&sm.ys[BUF][p_feat[3]][p_tok[3]] = y3_##J;                                   \
+        if (GAMMA && REV && tid < SCAN_TOK) sm.ws[BUF][tid] = wv_##J;                         \
+        lds_barrier();                                                                        \
+        if (has_rows) {                                                                       \
+            _Pragma("unroll") for (int s_ = 0; s_ < SCAN_TOK / 32; ++s_) {                    \
+                const int t0_ = 32 * s_ + 8 * g;                                              \
+                float xb_[8];                                                                 \
+                if (!GAMMA) {                                                                 \
+                    const float4 l_ = *(const float4*)&sm.xs[BUF][fb][t0_];                   \
+                    const float4 h_ = *(const float4*)&sm.xs[BUF][fb][t0_ + 4];               \
+                    xb_[0] = l_.x; xb_[1] = l_.y; xb_[2] = l_.z; xb_[3] = l_.w;               \
+                    xb_[4] = h_.x; xb_[5] = h_.y; xb_[6] = h_.z; xb_[7] = h_.w;               \
+                } else if (REV) {                                                             \
+                    const float4 l_ = *(const float4*)&sm.ws[BUF][t0_];                       \
+                    const float4 h_ = *(const float4*)&sm.ws[BUF][t0_ + 4];                   \
+                    xb_[0] = l_.x; xb_[1] = l_.y; xb_[2] = l_.z; xb_[3] = l_.w;               \
+                    xb_[4] = h_.x; xb_[5] = h_.y; xb_[6] = h_.z; xb_[7] = h_.w;               \
+                } else {                                                                      \
+                    _Pragma("unroll") for (int i_ = 0; i_ < 8; ++i_) xb_[i_] = 1.f;           \
+                }                                                                             \
+                Frag af_[2];                                                                  \
+                _Pragma("unroll") for (int rbk_ = 0; rbk_ < 2; ++rbk_) {                      \
+                    const float* xa_ = &sm.xs[BUF][fa0 + fa_step * rbk_][t0_];                \
+                    const float4 l_ = *(const float4*)xa_;                                    \
+                    const float4 h_ = *(const float4*)(xa_ + 4);                              \
+                    af_[rbk_].v[0] = (__bf16)(l_.x * xb_[0]); af_[rbk_].v[1] = (__bf16)(l_.y * xb_[1]); \
+                    af_[rbk_].v[2] = (__bf16)(l_.z * xb_[2]); af_[rbk_].v[3] = (__bf16)(l_.w * xb_[3]); \
+                    af_[rbk_].v[4] = (__bf16)(h_.x * xb_[4]); af_[rbk_].v[5] = (__bf16)(h_.y * xb_[5]); \
+                    af_[rbk_].v[6] = (__bf16)(h_.z * xb_[6]); af_[rbk_].v[7] = (__bf16)(h_.w * xb_[7]); \
+                }                                                                             \
+                _Pragma("unroll") for (int cb_ = 0; cb_ < 4; ++cb_) {                         \
+                    Frag bf_;                                                                 \
+                    bf_.u = *(const uint4*)&sm.ys[BUF][16 * cb_ + r16][t0_];                  \
+                    acc[0][cb_] = mfma16(af_[0].v, bf_.v, acc[0][cb_]);                       \
+                    acc[1][cb_] = mfma16(af_[1].v, bf_.v, acc[1][cb_]);                       \
+                }                                                                             \
+            }                                                                                 \
+        }                                                                                     \
+    }
+        // The LDS buffer alternates with the stage parity; 2 * SCAN_PF stages per trip keep both
+        // the ring slot and the buffer compile-time constants.
+        PA_LOAD_STAGE(0, 0) PA_LOAD_STAGE(1, 1) PA_LOAD_STAGE(2, 2)
+        for (int st0 = 0; st0 < nstage; st0 += 2 * SCAN_PF) {
+            PA_CONSUME(0, st0 + 0, 0) PA_LOAD_STAGE(0, st0 + 3)
+            PA_CONSUME(1, st0 + 1, 1) PA_LOAD_STAGE(1, st0 + 4)
+            PA_CONSUME(2, st0 + 2, 0) PA_LOAD_STAGE(2, st0 + 5)
+            PA_CONSUME(0, st0 + 3, 1) PA_LOAD_STAGE(0, st0 + 6)
+            PA_CONSUME(1, st0 + 4, 0) PA_LOAD_STAGE(1, st0 + 7)
+            PA_CONSUME(2, st0 + 5, 1) PA_LOAD_STAGE(2, st0 + 8)
+        }
+#undef PA_CONSUME
+#undef PA_FILL_X
+#undef PA_LOAD_STAGE
+    }
+    write_state(REV ? 0 : nstate - 1);
+}
+
+template <bool REV, bool WC, bool WR>
+__global__ __launch_bounds__(256) void k_mfma_scan(const bf16_t* __restrict__ Xt, const bf16_t* __restrict__ Yt,
+                                                   const float* __restrict__ wgt, bf16_t* __restrict__ StC,
+                                                   bf16_t* __restrict__ StR, bf16_t* __restrict__ Gam, int T, int cs,
+                                                   float out_scale) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char scan_smem_raw[];
+    ScanSmem& sm = *reinterpret_cast<ScanSmem*>(scan_smem_raw);
+    if (blockIdx.x == NPAIR)
+        scan_body<true, REV, WC, WR>(Xt, Yt, wgt, StC, StR, Gam, T, cs, out_scale, sm);
+    else
+        scan_body<false, REV, WC, WR>(Xt, Yt, wgt, StC, StR, Gam, T, cs, out_scale, sm);
+}
+
+}  // namespace
+
+// LDS beyond the default per-kernel limit has to be requested once per kernel
+template <typename F>
+static bool allow_smem(F* fn, size_t bytes) {
+    hipError_t e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e != hipSuccess) note_hip_error(e, "hipFuncSetAttribute(max dynamic LDS)");
+    return e == hipSuccess;
+}
+
+bool launch_transpose(hipStream_t s, const bf16_t* in, bf16_t* out, int BH, int T) {
+    LaunchScope ls("mfma_transpose", s);
+    hipLaunchKernelGGL(k_transpose, dim3(T / TBLK, BH), dim3(256), 0, s, in, out, T);
+    return launch_ok();
+}
+
+template <bool REV, bool WC, bool WR>
+static bool launch_scan_t(const char* name, hipStream_t s, const bf16_t* Xt, const bf16_t* Yt, const float* wgt,
+                          bf16_t* stC, bf16_t* stR, bf16_t* gam, int BH, int T, int cs, float out_scale) {
+    if (!allow_smem(k_mfma_scan<REV, WC, WR>, sizeof(ScanSmem))) return false;
+    LaunchScope ls(name, s);
+    hipLaunchKernelGGL((k_mfma_scan<REV, WC, WR>), dim3(NPAIR + 1, BH), dim3(256), sizeof(ScanSmem), s, Xt, Yt, wgt, stC,
+                       stR, gam, T, cs, out_scale);
+    return launch_ok();
+}
+
+bool launch_scan(const char* name, hipStream_t s, bool rev, const bf16_t* Xt, const bf16_t* Yt, const float* wgt, bf16_t* stC,
+                 bf16_t* stR, bf16_t* gam, int BH, int T, int cs, float out_scale) {
+    const bool wc = stC != nullptr, wr = stR != nullptr;
+    if (!rev) {
+        if (wc && wr) return launch_scan_t<false, true, true>(name, s, Xt, Yt, wgt, stC, stR, gam, BH, T, cs, out_scale);
+        if (wc) return launch_scan_t<false, true, false>(name, s, Xt, Yt, wgt, stC, stR, gam, BH, T, cs, out_scale);
+        return launch_scan_t<false, false, true>(name, s, Xt, Yt, wgt, stC, stR, gam, BH, T, cs, out_scale);
+    }
+    if (wc && wr) return launch_scan_t<true, true, true>(name, s, Xt, Yt, wgt, stC, stR, gam, BH, T, cs, out_scale);
+    if (wc) return launch_scan_t<true, true, false>(name, s, Xt, Yt, wgt, stC, stR, gam, BH, T, cs, out_scale);
+    return launch_scan_t<true, false, true>(name, s, Xt, Yt, wgt, stC, stR, gam, BH, T, cs, out_scale);
+}
+
+}  // namespace mfma
+}  // namespace pa
