@@ -25,7 +25,7 @@ __global__ __launch_bounds__(256) void k_transpose(const bf16_t* __restrict__ in
 // Fused update-state + cumulative sum over chunks (App. E.2 + E.3, no gating), used for
 //   the forward state     S_n = sum_{j <  n cs}     phi(k_j) v_j^T        (X = K, Y = V)
 //   the state gradient    R_m = sum_{i >= (m+1) cs} phi(q_i) ghat_i^T     (X = Q, Y = dO/Z, REV)
-// grid (NPAIR + 1, BH), 256 threads.  Workgroup `pair` owns the two 64 x DH state tiles
+// One workgroup of 256 threads per (tile pair, head).  Workgroup `pair` owns the two 64 x DH state tiles
 // 2 pair, 2 pair + 1; wave w owns 32 rows (a in 4(w&1) .. +3) of tile 2 pair + (w >> 1).
 // Workgroup NPAIR owns the normaliser in its d x d form: Gamma = sum k k^T, or
 // Omega = sum gz_i q_i q_i^T for the gradient (same code: the A operand is x itself, times the
@@ -51,16 +51,105 @@ struct ScanSmem {
     bf16_t tr[4][32][TR_PITCH];
 };
 
+// One 128-token stage of one wave: acc[rbk][cb] += phi-rows(32) x Y(64 columns), four k-steps of
+// 32 tokens.  Written as an explicit software pipeline, because a workgroup of this kernel is
+// alone on its CU (one wave per SIMD): the LDS operands of k-step s+1 are read and its A
+// operands expanded while the MFMAs of k-step s run.
+struct ScanOps {          // LDS operands of one k-step for one lane
+    float4 xal[2], xah[2];   // x[fa(rbk)][8 tokens]
+    float4 xbl, xbh;         // x[fb][8 tokens]  (or the weights / ones for the normaliser)
+    uint4 b[4];              // Y^T fragments, 4 column blocks
+};
+
+template <bool GAMMA, bool REV>
+__device__ __forceinline__ void scan_load_ops(ScanOps& o, const ScanSmem& sm, int buf, int s, int fa0, int fa_step,
+                                              int fb, int r16, int g) {
+    const int t0 = 32 * s + 8 * g;
+#pragma unroll
+    for (int rbk = 0; rbk < 2; ++rbk) {
+        const float* xa = &sm.xs[buf][fa0 + fa_step * rbk][t0];
+        o.xal[rbk] = *(const float4*)xa;
+        o.xah[rbk] = *(const float4*)(xa + 4);
+    }
+    if (!GAMMA) {
+        o.xbl = *(const float4*)&sm.xs[buf][fb][t0];
+        o.xbh = *(const float4*)&sm.xs[buf][fb][t0 + 4];
+    } else if (REV) {
+        o.xbl = *(const float4*)&sm.ws[buf][t0];
+        o.xbh = *(const float4*)&sm.ws[buf][t0 + 4];
+    } else {
+        o.xbl = make_float4(1.f, 1.f, 1.f, 1.f);
+        o.xbh = o.xbl;
+    }
+#pragma unroll
+    for (int cb = 0; cb < 4; ++cb) o.b[cb] = *(const uint4*)&sm.ys[buf][16 * cb + r16][t0];
+}
+
+__device__ __forceinline__ void scan_expand(Frag (&af)[2], const ScanOps& o) {
+#pragma unroll
+    for (int rbk = 0; rbk < 2; ++rbk) {
+        af[rbk].v[0] = (__bf16)(o.xal[rbk].x * o.xbl.x); af[rbk].v[1] = (__bf16)(o.xal[rbk].y * o.xbl.y);
+        af[rbk].v[2] = (__bf16)(o.xal[rbk].z * o.xbl.z); af[rbk].v[3] = (__bf16)(o.xal[rbk].w * o.xbl.w);
+        af[rbk].v[4] = (__bf16)(o.xah[rbk].x * o.xbh.x); af[rbk].v[5] = (__bf16)(o.xah[rbk].y * o.xbh.y);
+        af[rbk].v[6] = (__bf16)(o.xah[rbk].z * o.xbh.z); af[rbk].v[7] = (__bf16)(o.xah[rbk].w * o.xbh.w);
+    }
+}
+
+__device__ __forceinline__ void scan_mma(f32x4 (&acc)[2][4], const Frag (&af)[2], const ScanOps& o) {
+#pragma unroll
+    for (int cb = 0; cb < 4; ++cb) {
+        Frag bf;
+        bf.u = o.b[cb];
+        acc[0][cb] = mfma16(af[0].v, bf.v, acc[0][cb]);
+        acc[1][cb] = mfma16(af[1].v, bf.v, acc[1][cb]);
+    }
+}
+
+// 8 MFMAs with 3 vector-ALU instructions after each: the expansion of the next k-step rides in
+// the shadow of the matrix pipe
+__device__ __forceinline__ void scan_interleave_hint() {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+    }
+}
+
+template <bool GAMMA, bool REV>
+__device__ __forceinline__ void scan_stage(f32x4 (&acc)[2][4], const ScanSmem& sm, int buf, int fa0, int fa_step,
+                                           int fb, int r16, int g) {
+    ScanOps o0, o1;
+    Frag af0[2], af1[2];
+    scan_load_ops<GAMMA, REV>(o0, sm, buf, 0, fa0, fa_step, fb, r16, g);
+    scan_load_ops<GAMMA, REV>(o1, sm, buf, 1, fa0, fa_step, fb, r16, g);
+    scan_expand(af0, o0);
+    __builtin_amdgcn_sched_barrier(0);
+    scan_mma(acc, af0, o0);          // k-step 0
+    scan_expand(af1, o1);
+    scan_interleave_hint();
+    __builtin_amdgcn_sched_barrier(0);
+    scan_load_ops<GAMMA, REV>(o0, sm, buf, 2, fa0, fa_step, fb, r16, g);
+    scan_mma(acc, af1, o1);          // k-step 1
+    scan_expand(af0, o0);
+    scan_interleave_hint();
+    __builtin_amdgcn_sched_barrier(0);
+    scan_load_ops<GAMMA, REV>(o1, sm, buf, 3, fa0, fa_step, fb, r16, g);
+    scan_mma(acc, af0, o0);          // k-step 2
+    scan_expand(af1, o1);
+    scan_interleave_hint();
+    __builtin_amdgcn_sched_barrier(0);
+    scan_mma(acc, af1, o1);          // k-step 3
+}
+
 template <bool GAMMA, bool REV, bool WC, bool WR>
 __device__ __forceinline__ void scan_body(const bf16_t* __restrict__ Xt, const bf16_t* __restrict__ Yt,
                                           const float* __restrict__ wgt, bf16_t* __restrict__ StC,
                                           bf16_t* __restrict__ StR, bf16_t* __restrict__ Gam, int T, int cs,
-                                          float out_scale, ScanSmem& sm) {
+                                          float out_scale, ScanSmem& sm, int pair, int bh) {
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int r16 = lane & 15, g = lane >> 4;
-    const int bh = blockIdx.y;
     const int nstate = T / cs;
-    const int tile = GAMMA ? 0 : 2 * (int)blockIdx.x + (w >> 1);
+    const int tile = GAMMA ? 0 : 2 * pair + (w >> 1);
     int ti = 0, tj = 0;
     for (int l = 0; l < tile; ++l) {
         if (++ti > tj) {
@@ -188,41 +277,7 @@ __device__ __forceinline__ void scan_body(const bf16_t* __restrict__ Xt, const b
         *(uint4*)&sm.ys[BUF][p_feat[3]][p_tok[3]] = y3_##J;                                   \
         if (GAMMA && REV && tid < SCAN_TOK) sm.ws[BUF][tid] = wv_##J;                         \
         lds_barrier();                                                                        \
-        if (has_rows) {                                                                       \
-            _Pragma("unroll") for (int s_ = 0; s_ < SCAN_TOK / 32; ++s_) {                    \
-                const int t0_ = 32 * s_ + 8 * g;                                              \
-                float xb_[8];                                                                 \
-                if (!GAMMA) {                                                                 \
-                    const float4 l_ = *(const float4*)&sm.xs[BUF][fb][t0_];                   \
-                    const float4 h_ = *(const float4*)&sm.xs[BUF][fb][t0_ + 4];               \
-                    xb_[0] = l_.x; xb_[1] = l_.y; xb_[2] = l_.z; xb_[3] = l_.w;               \
-                    xb_[4] = h_.x; xb_[5] = h_.y; xb_[6] = h_.z; xb_[7] = h_.w;               \
-                } else if (REV) {                                                             \
-                    const float4 l_ = *(const float4*)&sm.ws[BUF][t0_];                       \
-                    const float4 h_ = *(const float4*)&sm.ws[BUF][t0_ + 4];                   \
-                    xb_[0] = l_.x; xb_[1] = l_.y; xb_[2] = l_.z; xb_[3] = l_.w;               \
-                    xb_[4] = h_.x; xb_[5] = h_.y; xb_[6] = h_.z; xb_[7] = h_.w;               \
-                } else {                                                                      \
-                    _Pragma("unroll") for (int i_ = 0; i_ < 8; ++i_) xb_[i_] = 1.f;           \
-                }                                                                             \
-                Frag af_[2];                                                                  \
-                _Pragma("unroll") for (int rbk_ = 0; rbk_ < 2; ++rbk_) {                      \
-                    const float* xa_ = &sm.xs[BUF][fa0 + fa_step * rbk_][t0_];                \
-                    const float4 l_ = *(const float4*)xa_;                                    \
-                    const float4 h_ = *(const float4*)(xa_ + 4);                              \
-                    af_[rbk_].v[0] = (__bf16)(l_.x * xb_[0]); af_[rbk_].v[1] = (__bf16)(l_.y * xb_[1]); \
-                    af_[rbk_].v[2] = (__bf16)(l_.z * xb_[2]); af_[rbk_].v[3] = (__bf16)(l_.w * xb_[3]); \
-                    af_[rbk_].v[4] = (__bf16)(h_.x * xb_[4]); af_[rbk_].v[5] = (__bf16)(h_.y * xb_[5]); \
-                    af_[rbk_].v[6] = (__bf16)(h_.z * xb_[6]); af_[rbk_].v[7] = (__bf16)(h_.w * xb_[7]); \
-                }                                                                             \
-                _Pragma("unroll") for (int cb_ = 0; cb_ < 4; ++cb_) {                         \
-                    Frag bf_;                                                                 \
-                    bf_.u = *(const uint4*)&sm.ys[BUF][16 * cb_ + r16][t0_];                  \
-                    acc[0][cb_] = mfma16(af_[0].v, bf_.v, acc[0][cb_]);                       \
-                    acc[1][cb_] = mfma16(af_[1].v, bf_.v, acc[1][cb_]);                       \
-                }                                                                             \
-            }                                                                                 \
-        }                                                                                     \
+        if (has_rows) scan_stage<GAMMA, REV>(acc, sm, BUF, fa0, fa_step, fb, r16, g);             \
     }
         // The LDS buffer alternates with the stage parity; 2 * SCAN_PF stages per trip keep both
         // the ring slot and the buffer compile-time constants.
@@ -246,13 +301,23 @@ template <bool REV, bool WC, bool WR>
 __global__ __launch_bounds__(256) void k_mfma_scan(const bf16_t* __restrict__ Xt, const bf16_t* __restrict__ Yt,
                                                    const float* __restrict__ wgt, bf16_t* __restrict__ StC,
                                                    bf16_t* __restrict__ StR, bf16_t* __restrict__ Gam, int T, int cs,
-                                                   float out_scale) {
+                                                   float out_scale, int nheads) {
     extern __shared__ __attribute__((aligned(16))) unsigned char scan_smem_raw[];
     ScanSmem& sm = *reinterpret_cast<ScanSmem*>(scan_smem_raw);
-    if (blockIdx.x == NPAIR)
-        scan_body<true, REV, WC, WR>(Xt, Yt, wgt, StC, StR, Gam, T, cs, out_scale, sm);
+    // Workgroups are dealt to the 8 XCDs round-robin by their linear id.  The NPAIR + 1 workgroups
+    // of one head read the same K / V stream, so the logical work items (head-major) are laid out
+    // in contiguous runs per XCD: a head's stream is then pulled into one or two L2s, not eight.
+    const int total = (NPAIR + 1) * nheads;
+    const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3;
+    const int base_cnt = total / 8, extra = total % 8;          // XCDs 0 .. extra-1 take one more
+    const int cnt = base_cnt + (xcd < extra ? 1 : 0);
+    if (q >= cnt) return;
+    const int item = xcd * base_cnt + min(xcd, extra) + q;
+    const int bh = item / (NPAIR + 1), pair = item % (NPAIR + 1);
+    if (pair == NPAIR)
+        scan_body<true, REV, WC, WR>(Xt, Yt, wgt, StC, StR, Gam, T, cs, out_scale, sm, pair, bh);
     else
-        scan_body<false, REV, WC, WR>(Xt, Yt, wgt, StC, StR, Gam, T, cs, out_scale, sm);
+        scan_body<false, REV, WC, WR>(Xt, Yt, wgt, StC, StR, Gam, T, cs, out_scale, sm, pair, bh);
 }
 
 }  // namespace
@@ -276,8 +341,9 @@ static bool launch_scan_t(const char* name, hipStream_t s, const bf16_t* Xt, con
                           bf16_t* stC, bf16_t* stR, bf16_t* gam, int BH, int T, int cs, float out_scale) {
     if (!allow_smem(k_mfma_scan<REV, WC, WR>, sizeof(ScanSmem))) return false;
     LaunchScope ls(name, s);
-    hipLaunchKernelGGL((k_mfma_scan<REV, WC, WR>), dim3(NPAIR + 1, BH), dim3(256), sizeof(ScanSmem), s, Xt, Yt, wgt, stC,
-                       stR, gam, T, cs, out_scale);
+    const int total = (NPAIR + 1) * BH;
+    hipLaunchKernelGGL((k_mfma_scan<REV, WC, WR>), dim3(8 * ((total + 7) / 8)), dim3(256), sizeof(ScanSmem), s, Xt, Yt, wgt,
+                       stC, stR, gam, T, cs, out_scale, BH);
     return launch_ok();
 }
 
