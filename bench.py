@@ -92,6 +92,8 @@ def main():
     ap.add_argument("--impl", default="auto", choices=["auto", "generic", "mfma"])
     ap.add_argument("--cpu-sample-tokens", type=int, default=32768)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--recompute-states", action="store_true",
+                    help="backward pass rebuilds the chunk states instead of reusing the forward pass's workspace")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures one GPU only (the path shards over batch and heads with no "
@@ -108,7 +110,8 @@ def main():
     tq, tk, tv, tg = (torch.from_numpy(a).to(dev).to(tdt) for a in (Q, K, V, G))
     del Q, K, V, G
     p, chunk = w["p"], w["chunk"]
-    prob = binding.make_problem(w["B"], w["H"], w["T"], w["d"], w["d"], p, chunk, True, 1.0, w["dtype"], args.impl)
+    keep = not args.recompute_states
+    prob = binding.make_problem(w["B"], w["H"], w["T"], w["d"], w["d"], p, chunk, True, 1.0, w["dtype"], args.impl, keep)
     ws_bytes = max(binding.power_attn_workspace_bytes(prob, True), binding.power_attn_workspace_bytes(prob, False))
     ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
     O = torch.empty_like(tv)
@@ -116,8 +119,8 @@ def main():
     grads = (torch.empty_like(tq), torch.empty_like(tk), torch.empty_like(tv))
 
     def step():
-        power_attn_fwd(tq, tk, tv, p, chunk, impl=args.impl, workspace=ws, out=O, out_z=Z)
-        power_attn_bwd(tq, tk, tv, O, Z, tg, p, chunk, impl=args.impl, workspace=ws, out=grads)
+        power_attn_fwd(tq, tk, tv, p, chunk, impl=args.impl, workspace=ws, out=O, out_z=Z, keep_state=keep)
+        power_attn_bwd(tq, tk, tv, O, Z, tg, p, chunk, impl=args.impl, workspace=ws, out=grads, keep_state=keep)
 
     for _ in range(args.warmup):
         step()
@@ -153,7 +156,7 @@ def main():
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": w["dtype"], "data": "synthetic",
         "config": {"workload": name, "B": w["B"], "H": w["H"], "T": w["T"], "d": w["d"], "p": p, "chunk": chunk,
-                   "normalize": True, "pass": "fwd+bwd", "impl": args.impl,
+                   "normalize": True, "pass": "fwd+bwd", "impl": args.impl, "keep_state": keep,
                    "state_rows": binding.power_attn_state_rows(prob)},
         "step_algorithmic_tflop": total_alg / 1e12,
         "step_frac_of_bf16_mfma_peak": total_alg / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS,

@@ -62,6 +62,13 @@ typedef struct {
     float scale;        /* multiplies q.k before the power ("softmax scaling", App. E.1 step 2) */
     int   dtype;        /* pa_dtype of Q, K, V, O, dO, dQ, dK, dV; accumulation is always float32 */
     int   impl;         /* pa_impl */
+    int   keep_state;   /* 0: power_attn_bwd rebuilds the chunk states itself (nothing but O and Z is
+                           saved).  1: power_attn_fwd also leaves the chunk states in `workspace` in
+                           the form the backward pass reads, and power_attn_bwd, given the SAME
+                           workspace, untouched since, and the same problem and inputs, uses them
+                           instead of rebuilding.  Both calls then need
+                           power_attn_workspace_bytes(prob, 1) bytes.  A kernel family may ignore
+                           the hint and rebuild. */
 } pa_problem;
 
 /* Bytes of device scratch the calls below need for `prob` (0 on an invalid problem).

@@ -37,7 +37,8 @@ class PowerAttnError(RuntimeError):
 class PaProblem(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int), ("H", ctypes.c_int), ("T", ctypes.c_int), ("d", ctypes.c_int),
                 ("v", ctypes.c_int), ("p", ctypes.c_int), ("chunk", ctypes.c_int), ("normalize", ctypes.c_int),
-                ("scale", ctypes.c_float), ("dtype", ctypes.c_int), ("impl", ctypes.c_int)]
+                ("scale", ctypes.c_float), ("dtype", ctypes.c_int), ("impl", ctypes.c_int),
+                ("keep_state", ctypes.c_int)]
 
 
 class PaKernelTime(ctypes.Structure):
@@ -91,12 +92,13 @@ def _check(lib, status: int, what: str):
         raise PowerAttnError(f"{what}: {lib.power_attn_status_string(status).decode()} (status {status}) {detail}")
 
 
-def make_problem(B, H, T, d, v, p, chunk, normalize=True, scale=1.0, dtype="bf16", impl="auto") -> PaProblem:
+def make_problem(B, H, T, d, v, p, chunk, normalize=True, scale=1.0, dtype="bf16", impl="auto",
+                 keep_state=False) -> PaProblem:
     return PaProblem(B, H, T, d, v, p, chunk, int(bool(normalize)), float(scale),
-                     PA_DTYPE_BF16 if dtype == "bf16" else PA_DTYPE_F32, _IMPL[impl])
+                     PA_DTYPE_BF16 if dtype == "bf16" else PA_DTYPE_F32, _IMPL[impl], int(bool(keep_state)))
 
 
-def _problem_of(Q, V, p, chunk, normalize, scale, impl) -> PaProblem:
+def _problem_of(Q, V, p, chunk, normalize, scale, impl, keep_state=False) -> PaProblem:
     import torch
     if Q.dim() != 4 or V.dim() != 4:
         raise PowerAttnError("tensors must be [B, H, T, d]")
@@ -107,7 +109,7 @@ def _problem_of(Q, V, p, chunk, normalize, scale, impl) -> PaProblem:
     else:
         raise PowerAttnError(f"unsupported dtype {Q.dtype}")
     B, H, T, d = Q.shape
-    return make_problem(B, H, T, d, V.shape[3], p, chunk, normalize, scale, dtype, impl)
+    return make_problem(B, H, T, d, V.shape[3], p, chunk, normalize, scale, dtype, impl, keep_state)
 
 
 def _dev_ptr(t, like=None, name="tensor"):
@@ -144,13 +146,17 @@ def _workspace(lib, prob, for_backward, workspace, device):
 
 
 def power_attn_fwd(Q, K, V, p: int, chunk: int, normalize: bool = True, scale: float = 1.0, impl: str = "auto",
-                   workspace=None, out=None, out_z=None):
-    """Forward pass on the current stream.  Returns (O, Z): O like V, Z float32 [B, H, T]."""
+                   workspace=None, out=None, out_z=None, keep_state: bool = False):
+    """Forward pass on the current stream.  Returns (O, Z): O like V, Z float32 [B, H, T].
+    keep_state=True needs a caller-provided workspace that is then handed, untouched, to
+    power_attn_bwd(..., keep_state=True)."""
     import torch
     lib = load_library()
     for t, name in ((Q, "Q"), (K, "K"), (V, "V")):
         _dev_ptr(t, None, name)
-    prob = _problem_of(Q, V, p, chunk, normalize, scale, impl)
+    prob = _problem_of(Q, V, p, chunk, normalize, scale, impl, keep_state)
+    if keep_state and workspace is None:
+        raise PowerAttnError("keep_state=True needs a workspace that outlives the call")
     _check(lib, lib.power_attn_supported(ctypes.byref(prob), 0), "power_attn_fwd")
     with torch.cuda.device(Q.device):
         O = torch.empty_like(V) if out is None else out
@@ -164,13 +170,15 @@ def power_attn_fwd(Q, K, V, p: int, chunk: int, normalize: bool = True, scale: f
 
 
 def power_attn_bwd(Q, K, V, O, Z, dO, p: int, chunk: int, normalize: bool = True, scale: float = 1.0,
-                   impl: str = "auto", workspace=None, out=None):
+                   impl: str = "auto", workspace=None, out=None, keep_state: bool = False):
     """Backward pass on the current stream.  Returns (dQ, dK, dV)."""
     import torch
     lib = load_library()
     for t, name in ((Q, "Q"), (K, "K"), (V, "V"), (dO, "dO")):
         _dev_ptr(t, None, name)
-    prob = _problem_of(Q, V, p, chunk, normalize, scale, impl)
+    prob = _problem_of(Q, V, p, chunk, normalize, scale, impl, keep_state)
+    if keep_state and workspace is None:
+        raise PowerAttnError("keep_state=True needs the workspace the forward pass used")
     _check(lib, lib.power_attn_supported(ctypes.byref(prob), 1), "power_attn_bwd")
     with torch.cuda.device(Q.device):
         if out is None:

@@ -9,15 +9,20 @@ using namespace mfma;
 
 struct Layout {
     int cs, nstate;
-    size_t off_kt, off_vt, off_sc, off_gam;                                   // forward
-    size_t off_qt, off_gh, off_ght, off_gz, off_sr, off_rc, off_rr, off_omg;  // backward only
+    bool keep;
+    size_t off_kt, off_vt, off_gam, off_sc, off_sr;                    // forward (sr only when states are kept)
+    size_t off_qt, off_gh, off_ght, off_gz, off_omg, off_rc, off_rr;   // backward only
     size_t total;
 };
 
+// One layout serves both passes when the states are kept: the forward part comes first and the
+// backward part is appended; the state gradient in layout "C" reuses the room of the forward
+// state in layout "C", which the backward pass no longer needs.
 Layout make_layout(const pa_problem& pr, bool backward) {
     Layout L{};
     L.cs = pr.chunk;
     L.nstate = pr.T / L.cs;
+    L.keep = pr.keep_state != 0;
     const size_t BH = (size_t)pr.B * pr.H;
     const size_t tok = BH * pr.T * DH * 2;
     const size_t st = BH * L.nstate * (size_t)STATE_ELEMS * 2;
@@ -31,16 +36,15 @@ Layout make_layout(const pa_problem& pr, bool backward) {
     L.off_kt = take(tok);
     L.off_vt = take(tok);
     L.off_gam = take(gm);
-    if (!backward) {
-        L.off_sc = take(st);
-    } else {
+    L.off_sc = take(st);
+    L.off_rc = L.off_sc;
+    if (backward || L.keep) {
+        L.off_sr = take(st);
         L.off_qt = take(tok);
         L.off_gh = take(tok);
         L.off_ght = take(tok);
         L.off_gz = take(BH * pr.T * sizeof(float));
         L.off_omg = take(gm);
-        L.off_sr = take(st);
-        L.off_rc = take(st);
         L.off_rr = take(st);
     }
     L.total = off;
@@ -75,7 +79,8 @@ pa_status mfma_fwd(const Ctx& c, const void* Q, const void* K, const void* V, vo
     bf16_t* Gam = (bf16_t*)(c.ws + L.off_gam);
     PA_TRY(launch_transpose(c.stream, (const bf16_t*)K, Kt, BH, pr.T))
     PA_TRY(launch_transpose(c.stream, (const bf16_t*)V, Vt, BH, pr.T))
-    PA_TRY(launch_scan("mfma_state_scan", c.stream, false, Kt, Vt, nullptr, Sc, nullptr, Gam, BH, pr.T, L.cs, 1.0f))
+    bf16_t* Sr = L.keep ? (bf16_t*)(c.ws + L.off_sr) : nullptr;   // kept for the backward pass
+    PA_TRY(launch_scan("mfma_state_scan", c.stream, false, Kt, Vt, nullptr, Sc, Sr, Gam, BH, pr.T, L.cs, 1.0f))
     PA_TRY(launch_fwd_chunk(c.stream, (const bf16_t*)Q, (const bf16_t*)K, Vt, Sc, Gam, (bf16_t*)O, Z, BH, pr.T, L.cs,
                             pr.scale, pr.normalize))
     return PA_OK;
@@ -100,13 +105,15 @@ pa_status mfma_bwd(const Ctx& c, const void* Q, const void* K, const void* V, co
     const bf16_t *q = (const bf16_t*)Q, *k = (const bf16_t*)K, *v = (const bf16_t*)V;
     const float s2 = pr.scale * pr.scale;
     PA_TRY(launch_bwd_prep(c.stream, (const bf16_t*)dO, (const bf16_t*)O, Z, Gh, gz, (long long)BH * pr.T, pr.normalize))
-    PA_TRY(launch_transpose(c.stream, k, Kt, BH, pr.T))
-    PA_TRY(launch_transpose(c.stream, v, Vt, BH, pr.T))
     PA_TRY(launch_transpose(c.stream, q, Qt, BH, pr.T))
     PA_TRY(launch_transpose(c.stream, Gh, Ght, BH, pr.T))
-    // chunk states are recomputed (nothing but O and Z is saved by the forward pass), in the
-    // layout the d phi contraction reads
-    PA_TRY(launch_scan("mfma_state_scan_bwd", c.stream, false, Kt, Vt, nullptr, nullptr, Sr, Gam, BH, pr.T, L.cs, 1.0f))
+    if (!L.keep) {
+        // nothing but O and Z was saved: rebuild the chunk states in the layout the d phi
+        // contraction reads
+        PA_TRY(launch_transpose(c.stream, k, Kt, BH, pr.T))
+        PA_TRY(launch_transpose(c.stream, v, Vt, BH, pr.T))
+        PA_TRY(launch_scan("mfma_state_scan_bwd", c.stream, false, Kt, Vt, nullptr, nullptr, Sr, Gam, BH, pr.T, L.cs, 1.0f))
+    }
     PA_TRY(launch_scan("mfma_state_grad_scan", c.stream, true, Qt, Ght, gz, Rc, Rr, Omg, BH, pr.T, L.cs, s2))
     PA_TRY(launch_bwd_dq(c.stream, q, k, v, Gh, gz, Kt, Sr, Gam, (bf16_t*)dQ, BH, pr.T, L.cs, pr.scale))
     PA_TRY(launch_bwd_dk(c.stream, q, k, v, Gh, gz, Qt, Rr, Omg, (bf16_t*)dK, BH, pr.T, L.cs, pr.scale))

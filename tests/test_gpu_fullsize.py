@@ -65,7 +65,7 @@ def test_headline_config3_fwd_bwd():
     w = inputs.WORKLOADS[name]
     Q, K, V, G = inputs.make_workload(name)
     print("case", name, flush=True)
-    got = run_fwd_bwd(Q, K, V, G, w["p"], w["chunk"], "bf16")
+    got = run_fwd_bwd(Q, K, V, G, w["p"], w["chunk"], "bf16", keep_state=True)   # as bench.py runs it
     for k, a in got.items():
         assert np.isfinite(a).all(), k
     # head (0, 5): every output against the chunked float64 oracle

@@ -42,12 +42,13 @@ BWD_CASES = [
 ]
 
 
+@pytest.mark.parametrize("keep_state", [False, True], ids=["recompute", "keep_state"])
 @pytest.mark.parametrize("case", BWD_CASES, ids=lambda c: "-".join(str(x) for x in c))
-def test_mfma_backward_full_tensors(case):
+def test_mfma_backward_full_tensors(case, keep_state):
     B, H, T, chunk, normalize, scale = case
-    print("case", case, flush=True)
+    print("case", case, "keep_state", keep_state, flush=True)
     Q, K, V, G = inputs.make_qkvg(B, H, T, 64, seed=4000 + BWD_CASES.index(case), dtype="bf16")
-    got = run_fwd_bwd(Q, K, V, G, 2, chunk, "bf16", normalize, scale, impl="mfma")
+    got = run_fwd_bwd(Q, K, V, G, 2, chunk, "bf16", normalize, scale, impl="mfma", keep_state=keep_state)
     O, Z = orc.fwd_bhtd(Q, K, V, 2, None, normalize, scale)
     dQ, dK, dV = orc.bwd_bhtd(Q, K, V, G, 2, None, normalize, scale)
     assert_close(got, dict(O=O, Z=Z, dQ=dQ, dK=dK, dV=dV), "bf16", f"mfma fwd+bwd {case}")
