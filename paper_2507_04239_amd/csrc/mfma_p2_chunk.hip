@@ -14,7 +14,6 @@ namespace mfma {
 namespace {
 
 constexpr int XB_PITCH = DH + 8;   // bf16 elements; 36 dwords, so 16 rows hit 16 distinct bank groups
-constexpr int RO_PF = 4;           // read-out steps kept in flight in registers (divides 72, even)
 
 typedef bf16_t XbRow[XB_PITCH];
 
@@ -52,36 +51,115 @@ __device__ __forceinline__ bf16x8 tmajor_frag(const bf16_t* __restrict__ Xt_head
 
 constexpr f32x4 ZERO4 = {0.f, 0.f, 0.f, 0.f};
 
+// ---- state streaming: global -> LDS ring of 8 KB tiles, without passing through registers ------
+// A workgroup streams one chunk state (36 tiles of 8 KB) per kernel.  The two waves would
+// otherwise both load every byte (twice the L1 / L2 traffic, and measurably less HBM bandwidth).
+// Instead each wave issues half of a tile's eight 1 KB `global_load_lds` copies (64 lanes x 16
+// bytes land contiguously at the LDS address held in M0), RING_TILES - 1 tiles ahead, and both
+// read their MFMA fragments from LDS.  One barrier per tile keeps the waves in step: after it,
+// tile t is complete and the slot of tile t - 1 is free.  The fragment reads go through inline
+// assembly on purpose: the compiler cannot tell the ring reads from the copies in flight and
+// would wait for ALL of them before every read.
+constexpr int TILE_U4 = TILE_ELEMS / 8;   // 16-byte units per tile
+constexpr int RING_RO = 4;                // ring depth of the read-out kernels (bound by HBM)
+constexpr int RING_DP = 2;                // ring depth of the d phi kernels (bound by the vector ALUs:
+                                          // a smaller ring lets a fourth workgroup share the CU)
+
+template <int RING_TILES>
+struct ChunkSmem {
+    bf16_t xb[QBLK][XB_PITCH];
+    uint4 ring[RING_TILES][TILE_U4];
+};
+
+// Cross-lane sums without the LDS pipe: v_permlane16_swap / v_permlane32_swap exchange 16-lane
+// rows (resp. 32-lane halves) between two registers.
+__device__ __forceinline__ float xor16_sum(float x) {   // x + (value in lane ^ 16), in every lane
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ void halves(float x, float& lo, float& hi) {   // lane (l & 31) of each half, in every lane
+    const auto q = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    lo = __uint_as_float(q[0]);
+    hi = __uint_as_float(q[1]);
+}
+__device__ __forceinline__ float xor32_sum(float x) {
+    float lo, hi;
+    halves(x, lo, hi);
+    return lo + hi;
+}
+
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+    return (uint32_t)(size_t)((__attribute__((address_space(3))) const void*)p);
+}
+
+__device__ __forceinline__ uint4 lds_read16(uint32_t addr) {
+    uint4 v;
+    asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(addr) : "memory");
+    return v;
+}
+
+__device__ __forceinline__ void lds_read_wait() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
+// wait until at most `n` of this wave's vector-memory operations are outstanding (they retire in order)
+template <int N>
+__device__ __forceinline__ void vm_wait() {
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 0xF) | (((N >> 4) & 0x3) << 14));
+}
+
+// Copy tile `tile` of the state `Sn` into ring slot `slot`.  SWIZZLE = false: straight copy
+// (layout "C": the consumer's fragment order is the storage order).  SWIZZLE = true (layout
+// "R", rows of 128 bytes): the 16-byte unit c of row r is stored at unit c ^ (r & 7) of the row,
+// so that the 16 rows of a fragment read spread over the banks.
+template <bool SWIZZLE, int RING_TILES>
+__device__ __forceinline__ void ring_issue(ChunkSmem<RING_TILES>& sm, int slot, const bf16_t* __restrict__ Sn, int tile, int wv,
+                                           int lane) {
+    const bf16_t* src = Sn + (size_t)tile * TILE_ELEMS;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int instr = 4 * wv + q;
+        const int unit = SWIZZLE ? (instr * 64 + (lane & ~7) + ((lane & 7) ^ (lane >> 3))) : (instr * 64 + lane);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + unit * 8),
+                                         (__attribute__((address_space(3))) void*)&sm.ring[slot][instr * 64], 16, 0, 0);
+    }
+}
+
 // ---- read-out: contraction over the expanded rows (query-state, App. E.4) -----------------------
 // acc[vb][ib] += S^T phi(xscale^(1/2) x)^T for the 64 tokens of wave wv.  `Sn` is one state in
-// layout "C", a linear stream of 72 steps (step u = 2 tile + s holds rows a = 4s + g of the
-// tile); RO_PF steps are in flight in registers, loads unconditional and clamped.
-__device__ __forceinline__ void readout(f32x4 (&acc)[4][4], const bf16_t* __restrict__ Sn, const XbRow* Xb,
-                                        float xscale, int wv, int r16, int g) {
-    Sn += (size_t)g * DH * 8 + r16 * 8;
-    constexpr int STEP_ELEMS = 4 * DH * 8;
-    Frag sf[RO_PF][4];
+// layout "C": tile (ti, tj) = two steps of 32 expanded rows, step s holding rows a = 4s + g.
+// Must be called by both waves of the workgroup (it contains barriers).
+__device__ __forceinline__ void readout(f32x4 (&acc)[4][4], const bf16_t* __restrict__ Sn, ChunkSmem<RING_RO>& sm,
+                                        float xscale, int wv, int lane) {
+    constexpr int RING_TILES = RING_RO;
+    const int r16 = lane & 15, g = lane >> 4;
+    const XbRow* Xb = sm.xb;
+    const uint32_t ring0 = lds_addr(&sm.ring[0][0]) + (uint32_t)(g * 64 + r16) * 16u;
 #pragma unroll
-    for (int j = 0; j < RO_PF; ++j)
-#pragma unroll
-        for (int vb = 0; vb < 4; ++vb) sf[j][vb].u = *(const uint4*)(Sn + (size_t)j * STEP_ELEMS + 16 * vb * 8);
+    for (int t = 0; t < RING_TILES - 1; ++t) ring_issue<false>(sm, t, Sn, t, wv, lane);
     int ti = 0, tj = 0;
     float xbv[4][8];
-    for (int u0 = 0; u0 < 2 * NTILES; u0 += RO_PF) {
+    for (int tile = 0; tile < NTILES; ++tile) {
+        vm_wait<4 * (RING_TILES - 2)>();
+        __builtin_amdgcn_s_barrier();
+        ring_issue<false>(sm, (tile + RING_TILES - 1) % RING_TILES, Sn, min(tile + RING_TILES - 1, NTILES - 1), wv, lane);
+        const uint32_t slot = ring0 + (uint32_t)(tile % RING_TILES) * (TILE_U4 * 16u);
+        Frag sf[2][4];
 #pragma unroll
-        for (int j = 0; j < RO_PF; ++j) {
-            const int u = u0 + j;
-            const int s = j & 1;
-            if (s == 0 && ti == 0) {   // a new column block tj: x[8 tj .. 8 tj + 7] of each token
+        for (int s = 0; s < 2; ++s)
 #pragma unroll
-                for (int ib = 0; ib < 4; ++ib) {
-                    const uint4 raw = *(const uint4*)&Xb[64 * wv + 16 * ib + r16][8 * tj];
-                    xbv[ib][0] = bf_lo(raw.x); xbv[ib][1] = bf_hi(raw.x);
-                    xbv[ib][2] = bf_lo(raw.y); xbv[ib][3] = bf_hi(raw.y);
-                    xbv[ib][4] = bf_lo(raw.z); xbv[ib][5] = bf_hi(raw.z);
-                    xbv[ib][6] = bf_lo(raw.w); xbv[ib][7] = bf_hi(raw.w);
-                }
+            for (int vb = 0; vb < 4; ++vb) sf[s][vb].u = lds_read16(slot + (uint32_t)(s * 256 + vb * 16) * 16u);
+        if (ti == 0) {   // a new column block tj: x[8 tj .. 8 tj + 7] of each token
+#pragma unroll
+            for (int ib = 0; ib < 4; ++ib) {
+                const uint4 raw = *(const uint4*)&Xb[64 * wv + 16 * ib + r16][8 * tj];
+                xbv[ib][0] = bf_lo(raw.x); xbv[ib][1] = bf_hi(raw.x);
+                xbv[ib][2] = bf_lo(raw.y); xbv[ib][3] = bf_hi(raw.y);
+                xbv[ib][4] = bf_lo(raw.z); xbv[ib][5] = bf_hi(raw.z);
+                xbv[ib][6] = bf_lo(raw.w); xbv[ib][7] = bf_hi(raw.w);
             }
+        }
+        lds_read_wait();
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
             Frag pf[4];
 #pragma unroll
             for (int ib = 0; ib < 4; ++ib) {
@@ -92,21 +170,14 @@ __device__ __forceinline__ void readout(f32x4 (&acc)[4][4], const bf16_t* __rest
 #pragma unroll
             for (int vb = 0; vb < 4; ++vb)
 #pragma unroll
-                for (int ib = 0; ib < 4; ++ib) acc[vb][ib] = mfma16(sf[j][vb].v, pf[ib].v, acc[vb][ib]);
-            {
-                const int un = min(u + RO_PF, 2 * NTILES - 1);
-#pragma unroll
-                for (int vb = 0; vb < 4; ++vb)
-                    sf[j][vb].u = *(const uint4*)(Sn + (size_t)un * STEP_ELEMS + 16 * vb * 8);
-            }
-            if (s == 1) {
-                if (++ti > tj) {
-                    ++tj;
-                    ti = 0;
-                }
-            }
+                for (int ib = 0; ib < 4; ++ib) acc[vb][ib] = mfma16(sf[s][vb].v, pf[ib].v, acc[vb][ib]);
+        }
+        if (++ti > tj) {
+            ++tj;
+            ti = 0;
         }
     }
+    vm_wait<0>();
 }
 
 // ---- d phi: contraction over the value columns, then the Jacobian of phi ----------------------
@@ -151,24 +222,31 @@ constexpr int dphi_block_begin(int fbi, int fbj) {
     return k;
 }
 
-// state fragments of tile `tile`, row block rb: rows 16 rb + r16, value columns 32 ks + 8 g ..
-__device__ __forceinline__ void dphi_load_rb(Frag (&sf)[4][2], int rb, const bf16_t* __restrict__ Sl, int tile) {
-    const bf16_t* p = Sl + ((size_t)tile * 64 + 16 * rb) * DH;
-    sf[rb][0].u = *(const uint4*)p;
-    sf[rb][1].u = *(const uint4*)(p + 32);
-}
-
 template <int FBI, int FBJ>
-__device__ __forceinline__ void dphi_block(f32x4 (&acc)[4][4], Frag (&sf)[4][2], const bf16_t* __restrict__ Sl,
-                                           const Frag (&yf)[4][2], const XbRow* Xb, float xscale, int wv, int r16,
-                                           int g) {
+__device__ __forceinline__ void dphi_block(f32x4 (&acc)[4][4], const bf16_t* __restrict__ Sn, ChunkSmem<RING_DP>& sm,
+                                           const Frag (&yf)[4][2], float xscale, int wv, int lane) {
+    constexpr int RING_TILES = RING_DP;
     constexpr int K0 = dphi_block_begin(FBI, FBJ), K1 = K0 + (FBI == FBJ ? 3 : 4);
+    const int r16 = lane & 15, g = lane >> 4;
+    const XbRow* Xb = sm.xb;
+    // fragment (rb, ks) of a tile in the ring: row 16 rb + r16, 16-byte unit c = 4 ks + g, swizzled
+    const uint32_t ring0 = lds_addr(&sm.ring[0][0]) + (uint32_t)((r16 >> 3) * 64 + (r16 & 7) * 8) * 16u;
+    const uint32_t u0 = (uint32_t)((g ^ (r16 & 7)) * 16), u1 = (uint32_t)(((4 + g) ^ (r16 & 7)) * 16);
     float xb[4][4], u2[4][4];
 #pragma unroll 1
     for (int k = K0; k < K1; ++k) {
         const int code = DPHI_ORDER.v[k];
         const int ti = code & 255, tj = (code >> 8) & 255;
-        const int next_tile = DPHI_ORDER.v[k + 1] >> 16;
+        vm_wait<4 * (RING_TILES - 2)>();
+        __builtin_amdgcn_s_barrier();
+        ring_issue<true>(sm, (k + RING_TILES - 1) % RING_TILES, Sn, DPHI_ORDER.v[min(k + RING_TILES - 1, NTILES)] >> 16, wv, lane);
+        const uint32_t slot = ring0 + (uint32_t)(k % RING_TILES) * (TILE_U4 * 16u);
+        Frag sf[4][2];
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb) {
+            sf[rb][0].u = lds_read16(slot + (uint32_t)(rb * 128) * 16u + u0);
+            sf[rb][1].u = lds_read16(slot + (uint32_t)(rb * 128) * 16u + u1);
+        }
         if (ti == 2 * FBI) {   // first tile of a column block: x~[8 tj + 4 (g&1) + r]; restart term 2
 #pragma unroll
             for (int ib = 0; ib < 4; ++ib) {
@@ -179,9 +257,9 @@ __device__ __forceinline__ void dphi_block(f32x4 (&acc)[4][4], Frag (&sf)[4][2],
                 for (int r = 0; r < 4; ++r) u2[ib][r] = 0.f;
             }
         }
-        const bool odd = (ti & 1) != 0;
         const float m0 = (g == 2 * (ti & 1)) ? 1.f : 0.f;       // this lane owns the features of row blocks 0, 1
         const float m1 = (g == 2 * (ti & 1) + 1) ? 1.f : 0.f;   // ... of row blocks 2, 3
+        lds_read_wait();
 #pragma unroll
         for (int rb = 0; rb < 4; ++rb) {
             const float mk = (rb < 2) ? m0 : m1;
@@ -191,42 +269,42 @@ __device__ __forceinline__ void dphi_block(f32x4 (&acc)[4][4], Frag (&sf)[4][2],
                 c = mfma16(sf[rb][1].v, yf[ib][1].v, c);
                 const float xa = xscale * lds_bf(&Xb[64 * wv + 16 * ib + r16][8 * ti + 2 * rb + (g >> 1)]);
                 float own = c[0] * xb[ib][0] + c[1] * xb[ib][1] + c[2] * xb[ib][2] + c[3] * xb[ib][3];
-                own += __shfl_xor(own, 16);                     // all of b; value of a = 2 rb + (g >> 1)
-                const float other = __shfl_xor(own, 32);        // value of a = 2 rb + 1 - (g >> 1)
-                const float h0 = odd ? other : own, h1 = odd ? own : other;   // a = 2 rb, 2 rb + 1 in the owner lane
+                own = xor16_sum(own);                           // all of b; value of a = 2 rb + (g >> 1)
+                float h0, h1;                                   // a = 2 rb (lower half-wave), 2 rb + 1 (upper)
+                halves(own, h0, h1);
                 acc[FBI][ib][2 * (rb & 1)] += mk * h0;
                 acc[FBI][ib][2 * (rb & 1) + 1] += mk * h1;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) u2[ib][r] += c[r] * xa;
             }
-            dphi_load_rb(sf, rb, Sl, next_tile);   // ring: the slot is refilled as soon as it is consumed
         }
         if (ti == min(tj, 2 * FBI + 1)) {   // last tile of the column block here: land term 2
             const float mk = ((g >> 1) == (tj & 1)) ? 1.f : 0.f;
 #pragma unroll
             for (int ib = 0; ib < 4; ++ib)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) acc[FBJ][ib][r] += mk * (u2[ib][r] + __shfl_xor(u2[ib][r], 32));
+                for (int r = 0; r < 4; ++r) acc[FBJ][ib][r] += mk * xor32_sum(u2[ib][r]);
         }
     }
 }
 
-__device__ __forceinline__ void dphi(f32x4 (&acc)[4][4], const bf16_t* __restrict__ Sn, const Frag (&yf)[4][2],
-                                     const XbRow* Xb, float xscale, int wv, int r16, int g) {
-    const bf16_t* Sl = Sn + (size_t)r16 * DH + 8 * g;
-    Frag sf[4][2];
+// Must be called by both waves of the workgroup (it contains barriers).
+__device__ __forceinline__ void dphi(f32x4 (&acc)[4][4], const bf16_t* __restrict__ Sn, ChunkSmem<RING_DP>& sm,
+                                     const Frag (&yf)[4][2], float xscale, int wv, int lane) {
+    constexpr int RING_TILES = RING_DP;
 #pragma unroll
-    for (int rb = 0; rb < 4; ++rb) dphi_load_rb(sf, rb, Sl, 0);
-    dphi_block<0, 0>(acc, sf, Sl, yf, Xb, xscale, wv, r16, g);
-    dphi_block<0, 1>(acc, sf, Sl, yf, Xb, xscale, wv, r16, g);
-    dphi_block<1, 1>(acc, sf, Sl, yf, Xb, xscale, wv, r16, g);
-    dphi_block<0, 2>(acc, sf, Sl, yf, Xb, xscale, wv, r16, g);
-    dphi_block<1, 2>(acc, sf, Sl, yf, Xb, xscale, wv, r16, g);
-    dphi_block<2, 2>(acc, sf, Sl, yf, Xb, xscale, wv, r16, g);
-    dphi_block<0, 3>(acc, sf, Sl, yf, Xb, xscale, wv, r16, g);
-    dphi_block<1, 3>(acc, sf, Sl, yf, Xb, xscale, wv, r16, g);
-    dphi_block<2, 3>(acc, sf, Sl, yf, Xb, xscale, wv, r16, g);
-    dphi_block<3, 3>(acc, sf, Sl, yf, Xb, xscale, wv, r16, g);
+    for (int k = 0; k < RING_TILES - 1; ++k) ring_issue<true>(sm, k, Sn, DPHI_ORDER.v[k] >> 16, wv, lane);
+    dphi_block<0, 0>(acc, Sn, sm, yf, xscale, wv, lane);
+    dphi_block<0, 1>(acc, Sn, sm, yf, xscale, wv, lane);
+    dphi_block<1, 1>(acc, Sn, sm, yf, xscale, wv, lane);
+    dphi_block<0, 2>(acc, Sn, sm, yf, xscale, wv, lane);
+    dphi_block<1, 2>(acc, Sn, sm, yf, xscale, wv, lane);
+    dphi_block<2, 2>(acc, Sn, sm, yf, xscale, wv, lane);
+    dphi_block<0, 3>(acc, Sn, sm, yf, xscale, wv, lane);
+    dphi_block<1, 3>(acc, Sn, sm, yf, xscale, wv, lane);
+    dphi_block<2, 3>(acc, Sn, sm, yf, xscale, wv, lane);
+    dphi_block<3, 3>(acc, Sn, sm, yf, xscale, wv, lane);
+    vm_wait<0>();
 }
 
 // ---- forward chunk kernel -------------------------------------------------------------------------
@@ -236,7 +314,8 @@ __global__ __launch_bounds__(128, 2) void k_mfma_fwd_chunk(const bf16_t* __restr
                                                            const bf16_t* __restrict__ Gam, bf16_t* __restrict__ O,
                                                            float* __restrict__ Z, int T, int cs, float scale,
                                                            int normalize) {
-    __shared__ __attribute__((aligned(16))) bf16_t Xb[QBLK][XB_PITCH];
+    __shared__ __attribute__((aligned(16))) ChunkSmem<RING_RO> sm;
+    XbRow* Xb = sm.xb;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int r16 = lane & 15, g = lane >> 4;
     const int bh = blockIdx.y;
@@ -305,14 +384,13 @@ __global__ __launch_bounds__(128, 2) void k_mfma_fwd_chunk(const bf16_t* __restr
                 zsum[ib] += s2 * (c[0] * bf_lo(raw.x) + c[1] * bf_hi(raw.x) + c[2] * bf_lo(raw.y) + c[3] * bf_hi(raw.y));
             }
         }
-        readout(acc, StC + (size_t)(bh * nstate + n) * STATE_ELEMS, Xb, s2, wv, r16, g);
+        readout(acc, StC + (size_t)(bh * nstate + n) * STATE_ELEMS, sm, s2, wv, lane);
     }
 
 #pragma unroll
     for (int ib = 0; ib < 4; ++ib) {
         float z = zsum[ib];
-        z += __shfl_xor(z, 16);
-        z += __shfl_xor(z, 32);
+        z = xor32_sum(xor16_sum(z));
         const float inv = normalize ? (z != 0.f ? 1.f / z : 0.f) : 1.f;
         const size_t row = head_tok + i0 + 64 * wv + 16 * ib + r16;
 #pragma unroll
@@ -373,7 +451,8 @@ __global__ __launch_bounds__(128, 2) void k_mfma_bwd_dq(const bf16_t* __restrict
                                                         const float* __restrict__ gz, const bf16_t* __restrict__ Kt,
                                                         const bf16_t* __restrict__ StR, const bf16_t* __restrict__ Gam,
                                                         bf16_t* __restrict__ dQ, int T, int cs, float scale) {
-    __shared__ __attribute__((aligned(16))) bf16_t Xb[QBLK][XB_PITCH];
+    __shared__ __attribute__((aligned(16))) ChunkSmem<RING_DP> sm;
+    XbRow* Xb = sm.xb;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int r16 = lane & 15, g = lane >> 4;
     const int bh = blockIdx.y;
@@ -451,7 +530,7 @@ __global__ __launch_bounds__(128, 2) void k_mfma_bwd_dq(const bf16_t* __restrict
                 for (int r = 0; r < 4; ++r) acc[ab][ib][r] += f * c[r];
             }
         }
-        dphi(acc, StR + (size_t)(bh * nstate + n) * STATE_ELEMS, gf, Xb, scale, wv, r16, g);
+        dphi(acc, StR + (size_t)(bh * nstate + n) * STATE_ELEMS, sm, gf, scale, wv, lane);
     }
 #pragma unroll
     for (int ib = 0; ib < 4; ++ib) {
@@ -474,7 +553,8 @@ __global__ __launch_bounds__(128, 2) void k_mfma_bwd_dk(const bf16_t* __restrict
                                                         const float* __restrict__ gz, const bf16_t* __restrict__ Qt,
                                                         const bf16_t* __restrict__ RtR, const bf16_t* __restrict__ Omg,
                                                         bf16_t* __restrict__ dK, int T, int cs, float scale) {
-    __shared__ __attribute__((aligned(16))) bf16_t Xb[QBLK][XB_PITCH];
+    __shared__ __attribute__((aligned(16))) ChunkSmem<RING_DP> sm;
+    XbRow* Xb = sm.xb;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int r16 = lane & 15, g = lane >> 4;
     const int bh = blockIdx.y;
@@ -557,7 +637,7 @@ __global__ __launch_bounds__(128, 2) void k_mfma_bwd_dk(const bf16_t* __restrict
                 for (int r = 0; r < 4; ++r) acc[ab][jb][r] += 2.f * c[r];
             }
         }
-        dphi(acc, RtR + (size_t)(bh * nstate + m) * STATE_ELEMS, vf, Xb, 1.f, wv, r16, g);
+        dphi(acc, RtR + (size_t)(bh * nstate + m) * STATE_ELEMS, sm, vf, 1.f, wv, lane);
     }
 #pragma unroll
     for (int jb = 0; jb < 4; ++jb) {
@@ -578,7 +658,8 @@ __global__ __launch_bounds__(128, 2) void k_mfma_bwd_dk(const bf16_t* __restrict
 __global__ __launch_bounds__(128, 2) void k_mfma_bwd_dv(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
                                                         const bf16_t* __restrict__ Ght, const bf16_t* __restrict__ RtC,
                                                         bf16_t* __restrict__ dV, int T, int cs, float scale) {
-    __shared__ __attribute__((aligned(16))) bf16_t Xb[QBLK][XB_PITCH];
+    __shared__ __attribute__((aligned(16))) ChunkSmem<RING_RO> sm;
+    XbRow* Xb = sm.xb;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int r16 = lane & 15, g = lane >> 4;
     const int bh = blockIdx.y;
@@ -628,7 +709,7 @@ __global__ __launch_bounds__(128, 2) void k_mfma_bwd_dv(const bf16_t* __restrict
             }
         }
     }
-    if (m < nstate - 1) readout(acc, RtC + (size_t)(bh * nstate + m) * STATE_ELEMS, Xb, 1.f, wv, r16, g);
+    if (m < nstate - 1) readout(acc, RtC + (size_t)(bh * nstate + m) * STATE_ELEMS, sm, 1.f, wv, lane);
 #pragma unroll
     for (int jb = 0; jb < 4; ++jb) {
         const size_t row = head_tok + j0 + 64 * wv + 16 * jb + r16;
