@@ -12,9 +12,10 @@
 // Only the pairing of A and B k-slots matters, so k-slots are assigned to whatever order
 // the data is already in (no shuffles between the two MFMAs of the attention form).
 //
-// Two layouts of a 64-row state tile (bf16), chosen by which contraction the reader does:
-//   "C" [a][v][b]   8 expanded rows contiguous: operand of a contraction over rows (read-out)
-//   "R" [row][v]    8 value columns contiguous: operand of a contraction over v (d phi)
+// A 64-row state tile (bf16) is stored as [a][v][b]: the 8 expanded rows b of one (a, v) are
+// contiguous, which is the MFMA operand of a contraction over rows (the read-out).  The
+// contraction over v (d phi in the backward pass) reads the same copy: it stages the tile in LDS
+// and lets the transposing LDS read (ds_read_b64_tr_b16) gather 8 value columns per lane.
 #pragma once
 
 #include "common.hpp"
@@ -59,18 +60,18 @@ __device__ __forceinline__ void lds_barrier() {
 // feature-major copy in blocks of 64 tokens: [BH][T][DH] -> [BH][T/64][DH][64]
 bool launch_transpose(hipStream_t s, const bf16_t* in, bf16_t* out, int BH, int T);
 // state scan; rev = 0: S_n from (Kt, Vt); rev = 1: R_m from (Qt, Ght) with the weights gz.
-// stC / stR may be null (layout not written); gam receives Gamma (rev = 0) or Omega (rev = 1).
+// gam receives Gamma (rev = 0) or Omega (rev = 1).
 bool launch_scan(const char* name, hipStream_t s, bool rev, const bf16_t* Xt, const bf16_t* Yt, const float* wgt, bf16_t* stC,
-                 bf16_t* stR, bf16_t* gam, int BH, int T, int cs, float out_scale);
+                 bf16_t* gam, int BH, int T, int cs, float out_scale);
 bool launch_fwd_chunk(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* Vt, const bf16_t* stC,
                       const bf16_t* gam, bf16_t* O, float* Z, int BH, int T, int cs, float scale, int normalize);
 bool launch_bwd_prep(hipStream_t s, const bf16_t* dO, const bf16_t* O, const float* Z, bf16_t* Gh, float* gz,
                      long long rows, int normalize);
 bool launch_bwd_dq(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* V, const bf16_t* Gh,
-                   const float* gz, const bf16_t* Kt, const bf16_t* stR, const bf16_t* gam, bf16_t* dQ, int BH, int T,
+                   const float* gz, const bf16_t* Kt, const bf16_t* stC, const bf16_t* gam, bf16_t* dQ, int BH, int T,
                    int cs, float scale);
 bool launch_bwd_dk(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* V, const bf16_t* Gh,
-                   const float* gz, const bf16_t* Qt, const bf16_t* rtR, const bf16_t* omg, bf16_t* dK, int BH, int T,
+                   const float* gz, const bf16_t* Qt, const bf16_t* rtC, const bf16_t* omg, bf16_t* dK, int BH, int T,
                    int cs, float scale);
 bool launch_bwd_dv(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* Ght, const bf16_t* rtC,
                    bf16_t* dV, int BH, int T, int cs, float scale);

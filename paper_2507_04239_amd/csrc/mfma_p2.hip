@@ -10,14 +10,13 @@ using namespace mfma;
 struct Layout {
     int cs, nstate;
     bool keep;
-    size_t off_kt, off_vt, off_gam, off_sc, off_sr;                    // forward (sr only when states are kept)
-    size_t off_qt, off_gh, off_ght, off_gz, off_omg, off_rc, off_rr;   // backward only
+    size_t off_kt, off_vt, off_gam, off_sc;                      // forward
+    size_t off_qt, off_gh, off_ght, off_gz, off_omg, off_rc;     // backward only
     size_t total;
 };
 
-// One layout serves both passes when the states are kept: the forward part comes first and the
-// backward part is appended; the state gradient in layout "C" reuses the room of the forward
-// state in layout "C", which the backward pass no longer needs.
+// One layout serves both passes: the forward part comes first and the backward part is appended,
+// so a forward pass that keeps its states leaves them where the backward pass looks for them.
 Layout make_layout(const pa_problem& pr, bool backward) {
     Layout L{};
     L.cs = pr.chunk;
@@ -37,15 +36,13 @@ Layout make_layout(const pa_problem& pr, bool backward) {
     L.off_vt = take(tok);
     L.off_gam = take(gm);
     L.off_sc = take(st);
-    L.off_rc = L.off_sc;
     if (backward || L.keep) {
-        L.off_sr = take(st);
         L.off_qt = take(tok);
         L.off_gh = take(tok);
         L.off_ght = take(tok);
         L.off_gz = take(BH * pr.T * sizeof(float));
         L.off_omg = take(gm);
-        L.off_rr = take(st);
+        L.off_rc = take(st);
     }
     L.total = off;
     return L;
@@ -79,11 +76,35 @@ pa_status mfma_fwd(const Ctx& c, const void* Q, const void* K, const void* V, vo
     bf16_t* Gam = (bf16_t*)(c.ws + L.off_gam);
     PA_TRY(launch_transpose(c.stream, (const bf16_t*)K, Kt, BH, pr.T))
     PA_TRY(launch_transpose(c.stream, (const bf16_t*)V, Vt, BH, pr.T))
-    bf16_t* Sr = L.keep ? (bf16_t*)(c.ws + L.off_sr) : nullptr;   // kept for the backward pass
-    PA_TRY(launch_scan("mfma_state_scan", c.stream, false, Kt, Vt, nullptr, Sc, Sr, Gam, BH, pr.T, L.cs, 1.0f))
+    PA_TRY(launch_scan("mfma_state_scan", c.stream, false, Kt, Vt, nullptr, Sc, Gam, BH, pr.T, L.cs, 1.0f))
     PA_TRY(launch_fwd_chunk(c.stream, (const bf16_t*)Q, (const bf16_t*)K, Vt, Sc, Gam, (bf16_t*)O, Z, BH, pr.T, L.cs,
                             pr.scale, pr.normalize))
     return PA_OK;
+}
+
+// The backward pass has two independent strands that meet only at the end: dQ needs the forward
+// state S, while dK / dV need the state gradient R, whose scan is a long chain of small steps
+// that leaves most of each CU idle.  The R strand therefore runs on a second stream (created
+// once, default priority) so that dQ's workgroups fill the CUs under the scan.
+struct SideStream {
+    hipStream_t stream = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
+    bool ok = false;
+    int device = -1;
+};
+// One side stream per process, bound to the device of the first backward call; a call on any
+// other device simply runs both strands on the caller's stream.
+static SideStream side_stream() {
+    static SideStream s;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return SideStream{};
+    if (s.device < 0) {
+        s.device = dev;
+        s.ok = hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking) == hipSuccess &&
+               hipEventCreateWithFlags(&s.fork, hipEventDisableTiming) == hipSuccess &&
+               hipEventCreateWithFlags(&s.join, hipEventDisableTiming) == hipSuccess;
+    }
+    return s.device == dev ? s : SideStream{};
 }
 
 pa_status mfma_bwd(const Ctx& c, const void* Q, const void* K, const void* V, const void* O, const float* Z,
@@ -99,25 +120,36 @@ pa_status mfma_bwd(const Ctx& c, const void* Q, const void* K, const void* V, co
     float* gz = (float*)(c.ws + L.off_gz);
     bf16_t* Gam = (bf16_t*)(c.ws + L.off_gam);
     bf16_t* Omg = (bf16_t*)(c.ws + L.off_omg);
-    bf16_t* Sr = (bf16_t*)(c.ws + L.off_sr);
+    bf16_t* Sc = (bf16_t*)(c.ws + L.off_sc);
     bf16_t* Rc = (bf16_t*)(c.ws + L.off_rc);
-    bf16_t* Rr = (bf16_t*)(c.ws + L.off_rr);
     const bf16_t *q = (const bf16_t*)Q, *k = (const bf16_t*)K, *v = (const bf16_t*)V;
     const float s2 = pr.scale * pr.scale;
-    PA_TRY(launch_bwd_prep(c.stream, (const bf16_t*)dO, (const bf16_t*)O, Z, Gh, gz, (long long)BH * pr.T, pr.normalize))
-    PA_TRY(launch_transpose(c.stream, q, Qt, BH, pr.T))
-    PA_TRY(launch_transpose(c.stream, Gh, Ght, BH, pr.T))
-    if (!L.keep) {
-        // nothing but O and Z was saved: rebuild the chunk states in the layout the d phi
-        // contraction reads
-        PA_TRY(launch_transpose(c.stream, k, Kt, BH, pr.T))
-        PA_TRY(launch_transpose(c.stream, v, Vt, BH, pr.T))
-        PA_TRY(launch_scan("mfma_state_scan_bwd", c.stream, false, Kt, Vt, nullptr, nullptr, Sr, Gam, BH, pr.T, L.cs, 1.0f))
+    const SideStream side = side_stream();
+    hipStream_t s_main = c.stream, s_side = side.ok ? side.stream : c.stream;
+
+    PA_TRY(launch_bwd_prep(s_main, (const bf16_t*)dO, (const bf16_t*)O, Z, Gh, gz, (long long)BH * pr.T, pr.normalize))
+    PA_TRY(launch_transpose(s_main, q, Qt, BH, pr.T))
+    PA_TRY(launch_transpose(s_main, Gh, Ght, BH, pr.T))
+    if (side.ok) {
+        if (hipEventRecord(side.fork, s_main) != hipSuccess || hipStreamWaitEvent(s_side, side.fork, 0) != hipSuccess)
+            return PA_ERR_HIP;
     }
-    PA_TRY(launch_scan("mfma_state_grad_scan", c.stream, true, Qt, Ght, gz, Rc, Rr, Omg, BH, pr.T, L.cs, s2))
-    PA_TRY(launch_bwd_dq(c.stream, q, k, v, Gh, gz, Kt, Sr, Gam, (bf16_t*)dQ, BH, pr.T, L.cs, pr.scale))
-    PA_TRY(launch_bwd_dk(c.stream, q, k, v, Gh, gz, Qt, Rr, Omg, (bf16_t*)dK, BH, pr.T, L.cs, pr.scale))
-    PA_TRY(launch_bwd_dv(c.stream, q, k, Ght, Rc, (bf16_t*)dV, BH, pr.T, L.cs, pr.scale))
+    // strand R (caller's stream, so that its workgroups are placed first): state-gradient scan
+    PA_TRY(launch_scan("mfma_state_grad_scan", s_main, true, Qt, Ght, gz, Rc, Omg, BH, pr.T, L.cs, s2))
+    // strand S (side stream): dQ from the forward state
+    if (!L.keep) {
+        // nothing but O and Z was saved: rebuild the chunk states
+        PA_TRY(launch_transpose(s_side, k, Kt, BH, pr.T))
+        PA_TRY(launch_transpose(s_side, v, Vt, BH, pr.T))
+        PA_TRY(launch_scan("mfma_state_scan_bwd", s_side, false, Kt, Vt, nullptr, Sc, Gam, BH, pr.T, L.cs, 1.0f))
+    }
+    PA_TRY(launch_bwd_dq(s_side, q, k, v, Gh, gz, Kt, Sc, Gam, (bf16_t*)dQ, BH, pr.T, L.cs, pr.scale))
+    PA_TRY(launch_bwd_dk(s_main, q, k, v, Gh, gz, Qt, Rc, Omg, (bf16_t*)dK, BH, pr.T, L.cs, pr.scale))
+    PA_TRY(launch_bwd_dv(s_main, q, k, Ght, Rc, (bf16_t*)dV, BH, pr.T, L.cs, pr.scale))
+    if (side.ok) {
+        if (hipEventRecord(side.join, s_side) != hipSuccess || hipStreamWaitEvent(s_main, side.join, 0) != hipSuccess)
+            return PA_ERR_HIP;
+    }
     return PA_OK;
 }
 

@@ -98,6 +98,16 @@ __device__ __forceinline__ uint4 lds_read16(uint32_t addr) {
     return v;
 }
 
+// Transposing LDS read (ds_read_b64_tr_b16).  Inside each group of 16 lanes, lane 4 j + m points
+// at 4 consecutive 16-bit elements: row j, columns 4 m .. 4 m + 3 of a 4 x 16 block.  Lane n
+// receives column n of the block, i.e. element n % 4 of the lanes n / 4 + 4 j, j = 0 .. 3.
+template <int OFF>
+__device__ __forceinline__ uint2 lds_read_tr(uint32_t addr) {
+    uint2 v;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+    return v;
+}
+
 __device__ __forceinline__ void lds_read_wait() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
 // wait until at most `n` of this wave's vector-memory operations are outstanding (they retire in order)
@@ -106,10 +116,10 @@ __device__ __forceinline__ void vm_wait() {
     __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 0xF) | (((N >> 4) & 0x3) << 14));
 }
 
-// Copy tile `tile` of the state `Sn` into ring slot `slot`.  SWIZZLE = false: straight copy
-// (layout "C": the consumer's fragment order is the storage order).  SWIZZLE = true (layout
-// "R", rows of 128 bytes): the 16-byte unit c of row r is stored at unit c ^ (r & 7) of the row,
-// so that the 16 rows of a fragment read spread over the banks.
+// Copy tile `tile` of the state `Sn` (layout [a][v][b], 16-byte units (a, v)) into ring slot
+// `slot`.  SWIZZLE = false: straight copy, for the read-out, whose fragment order is the storage
+// order.  SWIZZLE = true, for the transposing reads of d phi: unit (a, v) is stored at
+// (a, v ^ 4 (a & 1)), which puts the two rows a of one transposing read on different banks.
 template <bool SWIZZLE, int RING_TILES>
 __device__ __forceinline__ void ring_issue(ChunkSmem<RING_TILES>& sm, int slot, const bf16_t* __restrict__ Sn, int tile, int wv,
                                            int lane) {
@@ -117,7 +127,7 @@ __device__ __forceinline__ void ring_issue(ChunkSmem<RING_TILES>& sm, int slot, 
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         const int instr = 4 * wv + q;
-        const int unit = SWIZZLE ? (instr * 64 + (lane & ~7) + ((lane & 7) ^ (lane >> 3))) : (instr * 64 + lane);
+        const int unit = instr * 64 + (SWIZZLE ? (lane ^ ((instr & 1) << 2)) : lane);
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + unit * 8),
                                          (__attribute__((address_space(3))) void*)&sm.ring[slot][instr * 64], 16, 0, 0);
     }
@@ -181,7 +191,9 @@ __device__ __forceinline__ void readout(f32x4 (&acc)[4][4], const bf16_t* __rest
 }
 
 // ---- d phi: contraction over the value columns, then the Jacobian of phi ----------------------
-// For the 64 tokens of wave wv, x~ = xscale * x, and a state `Sn` in layout "R":
+// For the 64 tokens of wave wv, x~ = xscale * x, and a state `Sn` (layout [a][v][b], the same
+// copy the read-out uses; the operand of this contraction needs 8 value columns per lane, which
+// the transposing LDS read gathers from 8 units):
 //     A[(a,b), token] = sum_v S[(ti,tj,a,b), v] y[token, v]                       (MFMA)
 //     acc[8 ti + a][token] += sum_b A[(a,b)] x~[8 tj + b]        (term 1)
 //     acc[8 tj + b][token] += sum_a A[(a,b)] x~[8 ti + a]        (term 2)        (vector ALU)
@@ -229,9 +241,14 @@ __device__ __forceinline__ void dphi_block(f32x4 (&acc)[4][4], const bf16_t* __r
     constexpr int K0 = dphi_block_begin(FBI, FBJ), K1 = K0 + (FBI == FBJ ? 3 : 4);
     const int r16 = lane & 15, g = lane >> 4;
     const XbRow* Xb = sm.xb;
-    // fragment (rb, ks) of a tile in the ring: row 16 rb + r16, 16-byte unit c = 4 ks + g, swizzled
-    const uint32_t ring0 = lds_addr(&sm.ring[0][0]) + (uint32_t)((r16 >> 3) * 64 + (r16 & 7) * 8) * 16u;
-    const uint32_t u0 = (uint32_t)((g ^ (r16 & 7)) * 16), u1 = (uint32_t)(((4 + g) ^ (r16 & 7)) * 16);
+    // Fragment (rb, ks) of a tile in the ring = state rows 16 rb + r16 (a = 2 rb + (r16 >> 3),
+    // b = r16 & 7), value columns 32 ks + 8 g .. + 7, from two transposing reads (columns
+    // + 0..3, + 4..7).  As a source lane of those reads, lane (r16 = 4 j + m, g) points at the
+    // four b = 4 (m & 1) .. + 3 of unit (a = 2 rb + (m >> 1), v = 32 ks + 8 g + 4 h + j).
+    const int sj = r16 >> 2, sm1 = (r16 >> 1) & 1, sm0 = r16 & 1;
+    const uint32_t lane_lo = (uint32_t)(16 * (64 * sm1 + 8 * g + (4 * sm1) + sj) + 8 * sm0);   // h = 0, swizzled
+    const uint32_t ring_lo = lds_addr(&sm.ring[0][0]) + lane_lo;
+    const uint32_t ring_hi = lds_addr(&sm.ring[0][0]) + (lane_lo ^ 64u);                       // h = 1
     float xb[4][4], u2[4][4];
 #pragma unroll 1
     for (int k = K0; k < K1; ++k) {
@@ -240,13 +257,14 @@ __device__ __forceinline__ void dphi_block(f32x4 (&acc)[4][4], const bf16_t* __r
         vm_wait<4 * (RING_TILES - 2)>();
         __builtin_amdgcn_s_barrier();
         ring_issue<true>(sm, (k + RING_TILES - 1) % RING_TILES, Sn, DPHI_ORDER.v[min(k + RING_TILES - 1, NTILES)] >> 16, wv, lane);
-        const uint32_t slot = ring0 + (uint32_t)(k % RING_TILES) * (TILE_U4 * 16u);
+        const uint32_t slot_lo = ring_lo + (uint32_t)(k % RING_TILES) * (TILE_U4 * 16u);
+        const uint32_t slot_hi = ring_hi + (uint32_t)(k % RING_TILES) * (TILE_U4 * 16u);
         Frag sf[4][2];
-#pragma unroll
-        for (int rb = 0; rb < 4; ++rb) {
-            sf[rb][0].u = lds_read16(slot + (uint32_t)(rb * 128) * 16u + u0);
-            sf[rb][1].u = lds_read16(slot + (uint32_t)(rb * 128) * 16u + u1);
-        }
+#define PA_TR(RB, KS)                                                       \
+    sf[RB][KS].h[0] = lds_read_tr<2048 * (RB) + 512 * (KS)>(slot_lo);       \
+    sf[RB][KS].h[1] = lds_read_tr<2048 * (RB) + 512 * (KS)>(slot_hi);
+        PA_TR(0, 0) PA_TR(0, 1) PA_TR(1, 0) PA_TR(1, 1) PA_TR(2, 0) PA_TR(2, 1) PA_TR(3, 0) PA_TR(3, 1)
+#undef PA_TR
         if (ti == 2 * FBI) {   // first tile of a column block: x~[8 tj + 4 (g&1) + r]; restart term 2
 #pragma unroll
             for (int ib = 0; ib < 4; ++ib) {
@@ -449,7 +467,7 @@ __global__ __launch_bounds__(256) void k_mfma_bwd_prep(const bf16_t* __restrict_
 __global__ __launch_bounds__(128, 2) void k_mfma_bwd_dq(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
                                                         const bf16_t* __restrict__ V, const bf16_t* __restrict__ Gh,
                                                         const float* __restrict__ gz, const bf16_t* __restrict__ Kt,
-                                                        const bf16_t* __restrict__ StR, const bf16_t* __restrict__ Gam,
+                                                        const bf16_t* __restrict__ StC, const bf16_t* __restrict__ Gam,
                                                         bf16_t* __restrict__ dQ, int T, int cs, float scale) {
     __shared__ __attribute__((aligned(16))) ChunkSmem<RING_DP> sm;
     XbRow* Xb = sm.xb;
@@ -530,7 +548,7 @@ __global__ __launch_bounds__(128, 2) void k_mfma_bwd_dq(const bf16_t* __restrict
                 for (int r = 0; r < 4; ++r) acc[ab][ib][r] += f * c[r];
             }
         }
-        dphi(acc, StR + (size_t)(bh * nstate + n) * STATE_ELEMS, sm, gf, scale, wv, lane);
+        dphi(acc, StC + (size_t)(bh * nstate + n) * STATE_ELEMS, sm, gf, scale, wv, lane);
     }
 #pragma unroll
     for (int ib = 0; ib < 4; ++ib) {
@@ -551,7 +569,7 @@ __global__ __launch_bounds__(128, 2) void k_mfma_bwd_dq(const bf16_t* __restrict
 __global__ __launch_bounds__(128, 2) void k_mfma_bwd_dk(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
                                                         const bf16_t* __restrict__ V, const bf16_t* __restrict__ Gh,
                                                         const float* __restrict__ gz, const bf16_t* __restrict__ Qt,
-                                                        const bf16_t* __restrict__ RtR, const bf16_t* __restrict__ Omg,
+                                                        const bf16_t* __restrict__ RtC, const bf16_t* __restrict__ Omg,
                                                         bf16_t* __restrict__ dK, int T, int cs, float scale) {
     __shared__ __attribute__((aligned(16))) ChunkSmem<RING_DP> sm;
     XbRow* Xb = sm.xb;
@@ -637,7 +655,7 @@ __global__ __launch_bounds__(128, 2) void k_mfma_bwd_dk(const bf16_t* __restrict
                 for (int r = 0; r < 4; ++r) acc[ab][jb][r] += 2.f * c[r];
             }
         }
-        dphi(acc, RtR + (size_t)(bh * nstate + m) * STATE_ELEMS, sm, vf, 1.f, wv, lane);
+        dphi(acc, RtC + (size_t)(bh * nstate + m) * STATE_ELEMS, sm, vf, 1.f, wv, lane);
     }
 #pragma unroll
     for (int jb = 0; jb < 4; ++jb) {
@@ -742,19 +760,19 @@ bool launch_bwd_prep(hipStream_t s, const bf16_t* dO, const bf16_t* O, const flo
 }
 
 bool launch_bwd_dq(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* V, const bf16_t* Gh,
-                   const float* gz, const bf16_t* Kt, const bf16_t* stR, const bf16_t* gam, bf16_t* dQ, int BH, int T,
+                   const float* gz, const bf16_t* Kt, const bf16_t* stC, const bf16_t* gam, bf16_t* dQ, int BH, int T,
                    int cs, float scale) {
     LaunchScope ls("mfma_bwd_dq", s);
-    hipLaunchKernelGGL(k_mfma_bwd_dq, dim3(T / QBLK, BH), dim3(128), 0, s, Q, K, V, Gh, gz, Kt, stR, gam, dQ, T, cs,
+    hipLaunchKernelGGL(k_mfma_bwd_dq, dim3(T / QBLK, BH), dim3(128), 0, s, Q, K, V, Gh, gz, Kt, stC, gam, dQ, T, cs,
                        scale);
     return launch_ok();
 }
 
 bool launch_bwd_dk(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* V, const bf16_t* Gh,
-                   const float* gz, const bf16_t* Qt, const bf16_t* rtR, const bf16_t* omg, bf16_t* dK, int BH, int T,
+                   const float* gz, const bf16_t* Qt, const bf16_t* rtC, const bf16_t* omg, bf16_t* dK, int BH, int T,
                    int cs, float scale) {
     LaunchScope ls("mfma_bwd_dk", s);
-    hipLaunchKernelGGL(k_mfma_bwd_dk, dim3(T / QBLK, BH), dim3(128), 0, s, Q, K, V, Gh, gz, Qt, rtR, omg, dK, T, cs,
+    hipLaunchKernelGGL(k_mfma_bwd_dk, dim3(T / QBLK, BH), dim3(128), 0, s, Q, K, V, Gh, gz, Qt, rtC, omg, dK, T, cs,
                        scale);
     return launch_ok();
 }

@@ -41,14 +41,12 @@ constexpr int SCAN_TOK = 128;                  // tokens per stage
 constexpr int SCAN_PF = 3;                     // stages in flight in registers
 constexpr int XS_PITCH = SCAN_TOK + 4;         // floats; pitch = 4 mod 64 banks
 constexpr int YS_PITCH = SCAN_TOK + 8;         // bf16;   pitch = 4 mod 64 banks (in dwords)
-constexpr int TR_PITCH = DH + 8;               // bf16
 static_assert(NTILES % 2 == 0, "tiles are handled in pairs");
 
 struct ScanSmem {
     float xs[2][DH][XS_PITCH];
     bf16_t ys[2][DH][YS_PITCH];
     float ws[2][SCAN_TOK];
-    bf16_t tr[4][32][TR_PITCH];
 };
 
 // One 128-token stage of one wave: acc[rbk][cb] += phi-rows(32) x Y(64 columns), four k-steps of
@@ -115,6 +113,15 @@ __device__ __forceinline__ void scan_interleave_hint() {
     }
 }
 
+// x, y: two dwords each.  Lanes of an even 16-lane row r receive (x of row r, x of row r + 1),
+// lanes of an odd row r receive (y of row r - 1, y of row r), as (.x, .z) and (.y, .w) for the
+// two dwords: 8 consecutive bf16 when a lane's dwords hold 4.
+__device__ __forceinline__ uint4 pair_rows(uint2 x, uint2 y) {
+    const auto d0 = __builtin_amdgcn_permlane16_swap(x.x, y.x, false, false);
+    const auto d1 = __builtin_amdgcn_permlane16_swap(x.y, y.y, false, false);
+    return make_uint4(d0[0], d1[0], d0[1], d1[1]);
+}
+
 template <bool GAMMA, bool REV>
 __device__ __forceinline__ void scan_stage(f32x4 (&acc)[2][4], const ScanSmem& sm, int buf, int fa0, int fa_step,
                                            int fb, int r16, int g) {
@@ -141,10 +148,14 @@ __device__ __forceinline__ void scan_stage(f32x4 (&acc)[2][4], const ScanSmem& s
     scan_mma(acc, af1, o1);          // k-step 3
 }
 
-template <bool GAMMA, bool REV, bool WC, bool WR>
+// EVERY: cs == SCAN_TOK, a state is written at every stage.  The stores are then unconditional,
+// and the compiler knows how many vector-memory operations separate a stage's loads from their
+// use; behind a branch it has to assume none, and waits for all but the newest loads, i.e. also
+// for the previous stage's stores.
+template <bool GAMMA, bool REV, bool EVERY>
 __device__ __forceinline__ void scan_body(const bf16_t* __restrict__ Xt, const bf16_t* __restrict__ Yt,
                                           const float* __restrict__ wgt, bf16_t* __restrict__ StC,
-                                          bf16_t* __restrict__ StR, bf16_t* __restrict__ Gam, int T, int cs,
+                                          bf16_t* __restrict__ Gam, int T, int cs,
                                           float out_scale, ScanSmem& sm, int pair, int bh) {
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int r16 = lane & 15, g = lane >> 4;
@@ -185,49 +196,42 @@ __device__ __forceinline__ void scan_body(const bf16_t* __restrict__ Xt, const b
 #pragma unroll
         for (int cb = 0; cb < 4; ++cb) acc[rbk][cb] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
+    // Both stores below hand every lane 16 contiguous bytes: a lane's 4 accumulator rows are half
+    // of an 8-row run whose other half sits 16 lanes away, so two lanes swap halves of two
+    // column blocks (or row blocks) and each stores one complete run.
+    auto pack = [&](const f32x4& c) {
+        union {
+            bf16x4 v;
+            uint2 u;
+        } o;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) o.v[r] = (__bf16)(c[r] * mult);
+        return o.u;
+    };
     auto write_state = [&](int n) {
         if (!GAMMA) {
-            const size_t tbase = ((size_t)(bh * nstate + n) * NTILES + tile) * TILE_ELEMS;
-            if (WC) {
-                bf16_t* dst = StC + tbase;
+            // layout [a][v][b]: accumulator rows are b = 4 (g & 1) + r of a = .. + (g >> 1)
+            bf16_t* dst = StC + ((size_t)(bh * nstate + n) * NTILES + tile) * TILE_ELEMS;
 #pragma unroll
-                for (int rbk = 0; rbk < 2; ++rbk) {
-                    const int a = 4 * (w & 1) + 2 * rbk + (g >> 1), b0 = 4 * (g & 1);
+            for (int rbk = 0; rbk < 2; ++rbk) {
+                const int a = 4 * (w & 1) + 2 * rbk + (g >> 1);
 #pragma unroll
-                    for (int cb = 0; cb < 4; ++cb) {
-                        bf16x4 o;
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) o[r] = (__bf16)(acc[rbk][cb][r] * mult);
-                        *(bf16x4*)(dst + ((a * DH + 16 * cb + r16) * 8 + b0)) = o;
-                    }
-                }
-            }
-            if (WR) {
-                // transpose the wave's 32 x 64 block through its private LDS patch, then store rows
-#pragma unroll
-                for (int rbk = 0; rbk < 2; ++rbk)
-#pragma unroll
-                    for (int cb = 0; cb < 4; ++cb)
-#pragma unroll
-                        for (int r = 0; r < 4; ++r)
-                            sm.tr[w][16 * rbk + 4 * g + r][16 * cb + r16] = f32_to_bf16(acc[rbk][cb][r] * mult);
-                bf16_t* dst = StR + tbase + (size_t)32 * (w & 1) * DH;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int unit = lane + 64 * q;          // 32 rows x 8 units of 16 bytes
-                    const uint4 val = *(const uint4*)&sm.tr[w][unit >> 3][8 * (unit & 7)];
-                    *(uint4*)(dst + (unit >> 3) * DH + 8 * (unit & 7)) = val;
+                for (int cp = 0; cp < 2; ++cp) {
+                    const uint2 x = pack(acc[rbk][2 * cp]), y = pack(acc[rbk][2 * cp + 1]);
+                    const uint4 run = pair_rows(x, y);   // g even: column block 2 cp; g odd: 2 cp + 1
+                    *(uint4*)(dst + (a * DH + 16 * (2 * cp + (g & 1)) + r16) * 8) = run;
                 }
             }
         } else if (has_rows) {
+            // Gamma / Omega are symmetric: element (row, col) is stored at [col][row], where the
+            // accumulator rows 32 w + 16 rbk + 4 g + r are contiguous
             bf16_t* dst = Gam + (size_t)(bh * nstate + n) * DH * DH;
 #pragma unroll
-            for (int rbk = 0; rbk < 2; ++rbk)
-#pragma unroll
-                for (int cb = 0; cb < 4; ++cb)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        dst[(32 * w + 16 * rbk + 4 * g + r) * DH + 16 * cb + r16] = f32_to_bf16(acc[rbk][cb][r] * mult);
+            for (int cb = 0; cb < 4; ++cb) {
+                const uint2 x = pack(acc[0][cb]), y = pack(acc[1][cb]);
+                const uint4 run = pair_rows(x, y);       // g even: row block 0; g odd: row block 1
+                *(uint4*)(dst + (16 * cb + r16) * DH + 32 * w + 16 * (g & 1) + 8 * (g >> 1)) = run;
+            }
         }
     };
 
@@ -268,7 +272,7 @@ __device__ __forceinline__ void scan_body(const bf16_t* __restrict__ Xt, const b
 #define PA_CONSUME(J, ST, BUF)                                                                \
     if ((ST) < nstage) { /* uniform; no global loads inside this branch */                    \
         const int edge_ = REV ? T - (ST) * SCAN_TOK : (ST) * SCAN_TOK;                        \
-        if (edge_ % cs == 0) write_state(REV ? edge_ / cs - 1 : edge_ / cs);                  \
+        if (EVERY || edge_ % cs == 0) write_state(REV ? edge_ / cs - 1 : edge_ / cs);         \
         PA_FILL_X(BUF, 0, x0_##J) PA_FILL_X(BUF, 1, x1_##J)                                   \
         PA_FILL_X(BUF, 2, x2_##J) PA_FILL_X(BUF, 3, x3_##J)                                   \
         *(uint4*)&sm.ys[BUF][p_feat[0]][p_tok[0]] = y0_##J;                                   \
@@ -297,11 +301,11 @@ __device__ __forceinline__ void scan_body(const bf16_t* __restrict__ Xt, const b
     write_state(REV ? 0 : nstate - 1);
 }
 
-template <bool REV, bool WC, bool WR>
+template <bool REV, bool EVERY>
 __global__ __launch_bounds__(256) void k_mfma_scan(const bf16_t* __restrict__ Xt, const bf16_t* __restrict__ Yt,
                                                    const float* __restrict__ wgt, bf16_t* __restrict__ StC,
-                                                   bf16_t* __restrict__ StR, bf16_t* __restrict__ Gam, int T, int cs,
-                                                   float out_scale, int nheads) {
+                                                   bf16_t* __restrict__ Gam, int T, int cs, float out_scale,
+                                                   int nheads) {
     extern __shared__ __attribute__((aligned(16))) unsigned char scan_smem_raw[];
     ScanSmem& sm = *reinterpret_cast<ScanSmem*>(scan_smem_raw);
     // Workgroups are dealt to the 8 XCDs round-robin by their linear id.  The NPAIR + 1 workgroups
@@ -315,9 +319,9 @@ __global__ __launch_bounds__(256) void k_mfma_scan(const bf16_t* __restrict__ Xt
     const int item = xcd * base_cnt + min(xcd, extra) + q;
     const int bh = item / (NPAIR + 1), pair = item % (NPAIR + 1);
     if (pair == NPAIR)
-        scan_body<true, REV, WC, WR>(Xt, Yt, wgt, StC, StR, Gam, T, cs, out_scale, sm, pair, bh);
+        scan_body<true, REV, EVERY>(Xt, Yt, wgt, StC, Gam, T, cs, out_scale, sm, pair, bh);
     else
-        scan_body<false, REV, WC, WR>(Xt, Yt, wgt, StC, StR, Gam, T, cs, out_scale, sm, pair, bh);
+        scan_body<false, REV, EVERY>(Xt, Yt, wgt, StC, Gam, T, cs, out_scale, sm, pair, bh);
 }
 
 }  // namespace
@@ -336,28 +340,26 @@ bool launch_transpose(hipStream_t s, const bf16_t* in, bf16_t* out, int BH, int 
     return launch_ok();
 }
 
-template <bool REV, bool WC, bool WR>
+template <bool REV, bool EVERY>
 static bool launch_scan_t(const char* name, hipStream_t s, const bf16_t* Xt, const bf16_t* Yt, const float* wgt,
-                          bf16_t* stC, bf16_t* stR, bf16_t* gam, int BH, int T, int cs, float out_scale) {
-    if (!allow_smem(k_mfma_scan<REV, WC, WR>, sizeof(ScanSmem))) return false;
+                          bf16_t* stC, bf16_t* gam, int BH, int T, int cs, float out_scale) {
+    if (!allow_smem(k_mfma_scan<REV, EVERY>, sizeof(ScanSmem))) return false;
     LaunchScope ls(name, s);
     const int total = (NPAIR + 1) * BH;
-    hipLaunchKernelGGL((k_mfma_scan<REV, WC, WR>), dim3(8 * ((total + 7) / 8)), dim3(256), sizeof(ScanSmem), s, Xt, Yt, wgt,
-                       stC, stR, gam, T, cs, out_scale, BH);
+    hipLaunchKernelGGL((k_mfma_scan<REV, EVERY>), dim3(8 * ((total + 7) / 8)), dim3(256), sizeof(ScanSmem), s, Xt, Yt, wgt,
+                       stC, gam, T, cs, out_scale, BH);
     return launch_ok();
 }
 
 bool launch_scan(const char* name, hipStream_t s, bool rev, const bf16_t* Xt, const bf16_t* Yt, const float* wgt, bf16_t* stC,
-                 bf16_t* stR, bf16_t* gam, int BH, int T, int cs, float out_scale) {
-    const bool wc = stC != nullptr, wr = stR != nullptr;
+                 bf16_t* gam, int BH, int T, int cs, float out_scale) {
+    const bool every = cs == SCAN_TOK;
     if (!rev) {
-        if (wc && wr) return launch_scan_t<false, true, true>(name, s, Xt, Yt, wgt, stC, stR, gam, BH, T, cs, out_scale);
-        if (wc) return launch_scan_t<false, true, false>(name, s, Xt, Yt, wgt, stC, stR, gam, BH, T, cs, out_scale);
-        return launch_scan_t<false, false, true>(name, s, Xt, Yt, wgt, stC, stR, gam, BH, T, cs, out_scale);
+        if (every) return launch_scan_t<false, true>(name, s, Xt, Yt, wgt, stC, gam, BH, T, cs, out_scale);
+        return launch_scan_t<false, false>(name, s, Xt, Yt, wgt, stC, gam, BH, T, cs, out_scale);
     }
-    if (wc && wr) return launch_scan_t<true, true, true>(name, s, Xt, Yt, wgt, stC, stR, gam, BH, T, cs, out_scale);
-    if (wc) return launch_scan_t<true, true, false>(name, s, Xt, Yt, wgt, stC, stR, gam, BH, T, cs, out_scale);
-    return launch_scan_t<true, false, true>(name, s, Xt, Yt, wgt, stC, stR, gam, BH, T, cs, out_scale);
+    if (every) return launch_scan_t<true, true>(name, s, Xt, Yt, wgt, stC, gam, BH, T, cs, out_scale);
+    return launch_scan_t<true, false>(name, s, Xt, Yt, wgt, stC, gam, BH, T, cs, out_scale);
 }
 
 }  // namespace mfma
