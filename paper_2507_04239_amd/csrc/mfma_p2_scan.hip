@@ -2,6 +2,14 @@
 // update-state + cumulative sum over chunks.  See mfma_common.hpp for the embedding and layouts.
 #include "mfma_common.hpp"
 
+// Hooks for a cycle-counter profile of the scan's phases; a profiling harness that includes this
+// file defines them, the library build leaves them empty.
+#ifndef PA_PROBE
+#define PA_PROBE_DECL
+#define PA_PROBE(I)
+#define PA_PROBE_DUMP
+#endif
+
 namespace pa {
 namespace mfma {
 namespace {
@@ -122,9 +130,24 @@ __device__ __forceinline__ uint4 pair_rows(uint2 x, uint2 y) {
     return make_uint4(d0[0], d1[0], d0[1], d1[1]);
 }
 
-template <bool GAMMA, bool REV>
+// A state leaving the chip: four 16-byte runs per lane, at dst + run_offset(k)
+struct StateOut {
+    uint4 run[4];
+    bf16_t* dst;
+};
+template <bool GAMMA>
+__device__ __forceinline__ void store_run(const StateOut& so, int k) {
+    // state tile [a][v][b]: run k = (row block k >> 1, column-block pair k & 1); Gamma: column block k
+    const int off = GAMMA ? 16 * DH * k : (k >> 1) * (2 * DH * 8) + (k & 1) * (32 * 8);
+    *(uint4*)(so.dst + off) = so.run[k];
+}
+
+// PACED: one run of `so` is stored after each k-step.  A CU drains stores slowly (about 10 bytes
+// per clock were measured); issued back to back the four waves' 16 KB stall every wave for the
+// length of the whole compute phase, spread over it they cost nothing.
+template <bool GAMMA, bool REV, bool PACED>
 __device__ __forceinline__ void scan_stage(f32x4 (&acc)[2][4], const ScanSmem& sm, int buf, int fa0, int fa_step,
-                                           int fb, int r16, int g) {
+                                           int fb, int r16, int g, const StateOut& so) {
     ScanOps o0, o1;
     Frag af0[2], af1[2];
     scan_load_ops<GAMMA, REV>(o0, sm, buf, 0, fa0, fa_step, fb, r16, g);
@@ -134,18 +157,22 @@ __device__ __forceinline__ void scan_stage(f32x4 (&acc)[2][4], const ScanSmem& s
     scan_mma(acc, af0, o0);          // k-step 0
     scan_expand(af1, o1);
     scan_interleave_hint();
+    if (PACED) store_run<GAMMA>(so, 0);
     __builtin_amdgcn_sched_barrier(0);
     scan_load_ops<GAMMA, REV>(o0, sm, buf, 2, fa0, fa_step, fb, r16, g);
     scan_mma(acc, af1, o1);          // k-step 1
     scan_expand(af0, o0);
     scan_interleave_hint();
+    if (PACED) store_run<GAMMA>(so, 1);
     __builtin_amdgcn_sched_barrier(0);
     scan_load_ops<GAMMA, REV>(o1, sm, buf, 3, fa0, fa_step, fb, r16, g);
     scan_mma(acc, af0, o0);          // k-step 2
     scan_expand(af1, o1);
     scan_interleave_hint();
+    if (PACED) store_run<GAMMA>(so, 2);
     __builtin_amdgcn_sched_barrier(0);
     scan_mma(acc, af1, o1);          // k-step 3
+    if (PACED) store_run<GAMMA>(so, 3);
 }
 
 // EVERY: cs == SCAN_TOK, a state is written at every stage.  The stores are then unconditional,
@@ -208,30 +235,32 @@ __device__ __forceinline__ void scan_body(const bf16_t* __restrict__ Xt, const b
         for (int r = 0; r < 4; ++r) o.v[r] = (__bf16)(c[r] * mult);
         return o.u;
     };
-    auto write_state = [&](int n) {
+    // the state as it stands, packed for storing as state n
+    auto pack_state = [&](StateOut& so, int n) {
         if (!GAMMA) {
             // layout [a][v][b]: accumulator rows are b = 4 (g & 1) + r of a = .. + (g >> 1)
-            bf16_t* dst = StC + ((size_t)(bh * nstate + n) * NTILES + tile) * TILE_ELEMS;
+            so.dst = StC + ((size_t)(bh * nstate + n) * NTILES + tile) * TILE_ELEMS +
+                     ((4 * (w & 1) + (g >> 1)) * DH + 16 * (g & 1) + r16) * 8;
 #pragma unroll
-            for (int rbk = 0; rbk < 2; ++rbk) {
-                const int a = 4 * (w & 1) + 2 * rbk + (g >> 1);
+            for (int rbk = 0; rbk < 2; ++rbk)
 #pragma unroll
-                for (int cp = 0; cp < 2; ++cp) {
-                    const uint2 x = pack(acc[rbk][2 * cp]), y = pack(acc[rbk][2 * cp + 1]);
-                    const uint4 run = pair_rows(x, y);   // g even: column block 2 cp; g odd: 2 cp + 1
-                    *(uint4*)(dst + (a * DH + 16 * (2 * cp + (g & 1)) + r16) * 8) = run;
-                }
-            }
-        } else if (has_rows) {
+                for (int cp = 0; cp < 2; ++cp)   // g even: column block 2 cp; g odd: 2 cp + 1
+                    so.run[2 * rbk + cp] = pair_rows(pack(acc[rbk][2 * cp]), pack(acc[rbk][2 * cp + 1]));
+        } else {
             // Gamma / Omega are symmetric: element (row, col) is stored at [col][row], where the
             // accumulator rows 32 w + 16 rbk + 4 g + r are contiguous
-            bf16_t* dst = Gam + (size_t)(bh * nstate + n) * DH * DH;
+            so.dst = Gam + (size_t)(bh * nstate + n) * DH * DH + r16 * DH + 32 * (w & 1) + 16 * (g & 1) + 8 * (g >> 1);
 #pragma unroll
-            for (int cb = 0; cb < 4; ++cb) {
-                const uint2 x = pack(acc[0][cb]), y = pack(acc[1][cb]);
-                const uint4 run = pair_rows(x, y);       // g even: row block 0; g odd: row block 1
-                *(uint4*)(dst + (16 * cb + r16) * DH + 32 * w + 16 * (g & 1) + 8 * (g >> 1)) = run;
-            }
+            for (int cb = 0; cb < 4; ++cb)       // g even: row block 0; g odd: row block 1
+                so.run[cb] = pair_rows(pack(acc[0][cb]), pack(acc[1][cb]));
+        }
+    };
+    auto write_state = [&](int n) {
+        StateOut so;
+        pack_state(so, n);
+        if (has_rows) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) store_run<GAMMA>(so, k);
         }
     };
 
@@ -272,7 +301,11 @@ __device__ __forceinline__ void scan_body(const bf16_t* __restrict__ Xt, const b
 #define PA_CONSUME(J, ST, BUF)                                                                \
     if ((ST) < nstage) { /* uniform; no global loads inside this branch */                    \
         const int edge_ = REV ? T - (ST) * SCAN_TOK : (ST) * SCAN_TOK;                        \
-        if (EVERY || edge_ % cs == 0) write_state(REV ? edge_ / cs - 1 : edge_ / cs);         \
+        PA_PROBE(0)                                                                           \
+        StateOut so_;                                                                         \
+        if (EVERY) pack_state(so_, REV ? edge_ / cs - 1 : edge_ / cs);                        \
+        else if (edge_ % cs == 0) write_state(REV ? edge_ / cs - 1 : edge_ / cs);             \
+        PA_PROBE(1)                                                                           \
         PA_FILL_X(BUF, 0, x0_##J) PA_FILL_X(BUF, 1, x1_##J)                                   \
         PA_FILL_X(BUF, 2, x2_##J) PA_FILL_X(BUF, 3, x3_##J)                                   \
         *(uint4*)&sm.ys[BUF][p_feat[0]][p_tok[0]] = y0_##J;                                   \
@@ -280,12 +313,16 @@ __device__ __forceinline__ void scan_body(const bf16_t* __restrict__ Xt, const b
         *(uint4*)&sm.ys[BUF][p_feat[2]][p_tok[2]] = y2_##J;                                   \
         *(uint4*)&sm.ys[BUF][p_feat[3]][p_tok[3]] = y3_##J;                                   \
         if (GAMMA && REV && tid < SCAN_TOK) sm.ws[BUF][tid] = wv_##J;                         \
+        PA_PROBE(2)                                                                           \
         lds_barrier();                                                                        \
-        if (has_rows) scan_stage<GAMMA, REV>(acc, sm, BUF, fa0, fa_step, fb, r16, g);             \
+        PA_PROBE(3)                                                                           \
+        if (has_rows) scan_stage<GAMMA, REV, EVERY>(acc, sm, BUF, fa0, fa_step, fb, r16, g, so_); \
+        PA_PROBE(4)                                                                           \
     }
         // The LDS buffer alternates with the stage parity; 2 * SCAN_PF stages per trip keep both
         // the ring slot and the buffer compile-time constants.
         PA_LOAD_STAGE(0, 0) PA_LOAD_STAGE(1, 1) PA_LOAD_STAGE(2, 2)
+        PA_PROBE_DECL
         for (int st0 = 0; st0 < nstage; st0 += 2 * SCAN_PF) {
             PA_CONSUME(0, st0 + 0, 0) PA_LOAD_STAGE(0, st0 + 3)
             PA_CONSUME(1, st0 + 1, 1) PA_LOAD_STAGE(1, st0 + 4)
@@ -294,6 +331,7 @@ __device__ __forceinline__ void scan_body(const bf16_t* __restrict__ Xt, const b
             PA_CONSUME(1, st0 + 4, 0) PA_LOAD_STAGE(1, st0 + 7)
             PA_CONSUME(2, st0 + 5, 1) PA_LOAD_STAGE(2, st0 + 8)
         }
+        PA_PROBE_DUMP
 #undef PA_CONSUME
 #undef PA_FILL_X
 #undef PA_LOAD_STAGE
@@ -318,6 +356,9 @@ __global__ __launch_bounds__(256) void k_mfma_scan(const bf16_t* __restrict__ Xt
     if (q >= cnt) return;
     const int item = xcd * base_cnt + min(xcd, extra) + q;
     const int bh = item / (NPAIR + 1), pair = item % (NPAIR + 1);
+#ifdef PA_STAGGER
+    for (int i = 0; i < (int)(blockIdx.x % 32); ++i) __builtin_amdgcn_s_sleep(PA_STAGGER);
+#endif
     if (pair == NPAIR)
         scan_body<true, REV, EVERY>(Xt, Yt, wgt, StC, Gam, T, cs, out_scale, sm, pair, bh);
     else
