@@ -19,6 +19,7 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_MFMA_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_FP32_VECTOR_TFLOPS = 157.3  # MI355X fp32 vector
+PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
 
 
 def algorithmic_flops(w):
@@ -39,13 +40,37 @@ def algorithmic_flops(w):
         "bwd_dk": state + pairs * 2 * d,
         "bwd_dv": BH * (n - 1) * c * 2 * D * v + pairs * 2 * v,
     }
-    f["recompute"] = 0   # the backward pass rebuilds the chunk states: executed, not credited
+    f["recompute"] = 0   # a backward pass that rebuilds the chunk states: executed, not credited
     f["fwd_total"] = f["update_state"] + f["fwd_chunk"]
     f["bwd_total"] = f["state_grad"] + f["bwd_dq"] + f["bwd_dkdv"]
     return f
 
 
-# kernel name (as the library reports it) -> (key in algorithmic_flops, credited?, peak TFLOP/s)
+def algorithmic_bytes(w):
+    """Algorithmic HBM bytes per launch of every kernel (all heads): the n - 1 chunk states a
+    pass needs, D x (v+1) each in the storage type, written (scans) or read (per-chunk kernels)
+    once, plus the token rows the kernel reads and writes once.  Padding of the tiled embedding,
+    feature-major copies and re-reads earn nothing."""
+    B, H, T, d, p, c = w["B"], w["H"], w["T"], w["d"], w["p"], w["chunk"]
+    v = d
+    BH, n = B * H, T // c
+    e = 2 if w["dtype"] == "bf16" else 4
+    D = math.comb(d + p - 1, p)
+    states = BH * (n - 1) * D * (v + 1) * e
+    tok = BH * T * d * e                 # one [T, d] operand of every head
+    return {
+        "update_state": states + 2 * tok,            # K, V in
+        "fwd_chunk": states + 4 * tok + BH * T * 4,  # Q, K, V in; O, Z out
+        "state_grad": states + 2 * tok + BH * T * 4,  # Q, ghat, gz in
+        "bwd_dq": states + 5 * tok + BH * T * 4,     # Q, K, V, ghat, gz in; dQ out
+        "bwd_dkdv": 2 * states + 6 * tok + BH * T * 4,
+        "bwd_dk": states + 5 * tok + BH * T * 4,
+        "bwd_dv": states + 4 * tok,                  # Q, K, ghat in; dV out
+        "recompute": 0,
+    }
+
+
+# kernel name (as the library reports it) -> (key in the two models above, compute peak in TFLOP/s)
 KERNEL_ROLE = {
     "generic_state_scan": ("update_state", PEAK_FP32_VECTOR_TFLOPS),
     "generic_fwd_chunk": ("fwd_chunk", PEAK_FP32_VECTOR_TFLOPS),
@@ -62,10 +87,22 @@ KERNEL_ROLE = {
 }
 
 
-def cpu_baseline(w, sample_tokens):
-    """The float64 oracle (chunked form, forward + backward) on one head, first `sample_tokens`
-    tokens of the workload; its cost per token does not depend on the position."""
-    import numpy as np
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary of this
+    workload (a line `TRAFFIC <workload> <kernel> <bytes>`), or None."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        f = line.split()
+        if len(f) == 4 and f[0] == "TRAFFIC" and f[1] == workload and f[2] == kernel:
+            return float(f[3])
+    return None
+
+
+def cpu_baseline(w, heads):
+    """The float64 oracle (chunked form, forward + backward) on the first `heads` heads of the
+    workload, whole sequence."""
     from oracle import power_attn_oracle as orc
     from paper_2507_04239_amd import inputs
     try:
@@ -73,14 +110,16 @@ def cpu_baseline(w, sample_tokens):
         cores = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
     except Exception:
         cores = 1
-    Q, K, V, G = inputs.make_qkvg(1, 1, sample_tokens, w["d"], seed=1000 + w["position"], dtype=w["dtype"])
+    heads = max(1, min(heads, w["B"] * w["H"]))
+    Q, K, V, G = inputs.make_qkvg(1, heads, w["T"], w["d"], seed=1000 + w["position"], dtype=w["dtype"])
     t0 = time.perf_counter()
-    orc.bwd_chunked(Q[0, 0], K[0, 0], V[0, 0], G[0, 0], w["p"], w["chunk"])   # runs the forward pass inside
+    for h in range(heads):
+        orc.bwd_chunked(Q[0, h], K[0, h], V[0, h], G[0, h], w["p"], w["chunk"])   # runs the forward pass inside
     dt = time.perf_counter() - t0
-    # one head of H: a token of the whole job costs H such head-tokens
-    return {"value": sample_tokens / (dt * w["H"]), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"fwd+bwd of 1 of {w['H']} heads over the first {sample_tokens} of {w['T']} tokens "
-                      f"({dt:.1f} s), scaled by 1/{w['H']}", "seconds": dt}
+    # `heads` of the B*H heads of the job: a token of the whole job costs H head-tokens
+    return {"value": heads * w["T"] / (dt * w["H"]), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"fwd+bwd of {heads} of {w['B'] * w['H']} heads, all {w['T']} tokens ({dt:.1f} s), "
+                      f"scaled by {heads}/{w['H']}", "seconds": dt}
 
 
 def main():
@@ -90,8 +129,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default=None, help="name from paper_2507_04239_amd.inputs.WORKLOADS")
     ap.add_argument("--impl", default="auto", choices=["auto", "generic", "mfma"])
-    ap.add_argument("--cpu-sample-tokens", type=int, default=32768)
+    ap.add_argument("--cpu-sample-heads", type=int, default=2, help="heads the CPU oracle is timed on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration-mib", type=int, default=0,
+                    help="also run one plain device copy of this many MiB (a dispatch of known size, for scaling "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--recompute-states", action="store_true",
                     help="backward pass rebuilds the chunk states instead of reusing the forward pass's workspace")
     args = ap.parse_args()
@@ -132,23 +174,47 @@ def main():
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
     tokens = w["B"] * w["T"]
 
-    # per-kernel durations from HIP events recorded by the library on the launch stream
+    if args.copy_calibration_mib > 0:
+        src = torch.empty(args.copy_calibration_mib << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    # per-kernel durations from HIP events recorded by the library on the launch stream; while
+    # they are recorded the library runs its kernels back to back (no overlap between streams)
     binding.profile_begin()
     for _ in range(args.steps):
         step()
     kernels = binding.profile_end()
-    fl = algorithmic_flops(w)
+    fl, by = algorithmic_flops(w), algorithmic_bytes(w)
     per_kernel = {}
     for kname, (launches, ms_total) in kernels.items():
         per_kernel[kname] = {"launches_per_step": launches / args.steps, "avg_ms": ms_total / launches}
+        if kname in KERNEL_ROLE:
+            role, peak = KERNEL_ROLE[kname]
+            sec = ms_total / launches * 1e-3
+            per_kernel[kname].update({"tflops": fl[role] / sec / 1e12, "frac_compute_peak": fl[role] / sec / 1e12 / peak,
+                                      "hbm_gbs": by[role] / sec / 1e9, "frac_hbm_peak": by[role] / sec / 1e9 / PEAK_HBM_GBS})
+    # The dominant kernel, and the roof that bounds it: the one whose lower bound on its time is larger.
     credited = {k: v for k, v in kernels.items() if k in KERNEL_ROLE}
     dom = max(credited, key=lambda k: credited[k][1])
     role, peak = KERNEL_ROLE[dom]
     dom_ms = credited[dom][1] / credited[dom][0]
-    achieved = fl[role] / (dom_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma" if peak == PEAK_BF16_MFMA_TFLOPS else "alu", "kernel": dom, "achieved": achieved,
-                "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None,
-                "avg_kernel_ms": dom_ms, "algorithmic_flops_per_launch": fl[role]}
+    t_compute = fl[role] / (peak * 1e12)
+    t_hbm = by[role] / (PEAK_HBM_GBS * 1e9)
+    if t_hbm >= t_compute:
+        achieved = by[role] / (dom_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": achieved / PEAK_HBM_GBS, "traffic": measured_traffic(name, dom), "avg_kernel_ms": dom_ms,
+                    "algorithmic_bytes_per_launch": by[role], "algorithmic_flops_per_launch": fl[role],
+                    "frac_of_compute_peak": fl[role] / (dom_ms * 1e-3) / 1e12 / peak}
+    else:
+        achieved = fl[role] / (dom_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma" if peak == PEAK_BF16_MFMA_TFLOPS else "alu", "kernel": dom, "achieved": achieved,
+                    "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak, "traffic": measured_traffic(name, dom),
+                    "avg_kernel_ms": dom_ms, "algorithmic_flops_per_launch": fl[role],
+                    "algorithmic_bytes_per_launch": by[role]}
     total_alg = fl["fwd_total"] + fl["bwd_total"]
     out = {
         "metric": "power-attention fwd+bwd tokens/sec at p=2,d=64,T=64k; % bf16 MFMA peak",
@@ -164,7 +230,7 @@ def main():
         "kernels": per_kernel,
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, min(args.cpu_sample_tokens, w["T"]))
+        out["cpu_baseline"] = cpu_baseline(w, args.cpu_sample_heads)
     print(json.dumps(out), flush=True)
 
 

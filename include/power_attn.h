@@ -111,7 +111,10 @@ const char* power_attn_last_hip_error(void);
  * Between _begin and _end every kernel the library launches is bracketed by a pair of HIP
  * events on the launch stream; _end waits for them and returns, per kernel name, the number
  * of launches and the summed elapsed milliseconds.  `out` is a HOST array of `max_entries`
- * records; the number filled is returned through *n (HOST int). */
+ * records; the number filled is returned through *n (HOST int).  While the switch is on, the
+ * kernels of a call run back to back on the caller's stream (outside it, power_attn_bwd may run
+ * independent kernels side by side on a second stream of its own), so that every duration is
+ * the kernel's own. */
 typedef struct {
     char   name[48];
     int    launches;

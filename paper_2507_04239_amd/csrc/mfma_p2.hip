@@ -124,7 +124,8 @@ pa_status mfma_bwd(const Ctx& c, const void* Q, const void* K, const void* V, co
     bf16_t* Rc = (bf16_t*)(c.ws + L.off_rc);
     const bf16_t *q = (const bf16_t*)Q, *k = (const bf16_t*)K, *v = (const bf16_t*)V;
     const float s2 = pr.scale * pr.scale;
-    const SideStream side = side_stream();
+    SideStream side = side_stream();
+    if (profile_enabled()) side.ok = false;   // timed kernel by kernel: no overlap
     hipStream_t s_main = c.stream, s_side = side.ok ? side.stream : c.stream;
 
     PA_TRY(launch_bwd_prep(s_main, (const bf16_t*)dO, (const bf16_t*)O, Z, Gh, gz, (long long)BH * pr.T, pr.normalize))
