@@ -9,6 +9,16 @@
 // and one wave's vector-ALU work (building phi, the Jacobian of phi) overlaps the other's MFMAs.
 #include "mfma_common.hpp"
 
+// Hooks for a cycle-counter profile of the per-tile phases; a profiling harness that includes
+// this file defines them, the library build leaves them empty.
+#ifndef PA_PROBE
+#define PA_PROBE_DECL
+#define PA_PROBE_PARAM
+#define PA_PROBE_ARG
+#define PA_PROBE(I)
+#define PA_PROBE_DUMP
+#endif
+
 namespace pa {
 namespace mfma {
 namespace {
@@ -236,7 +246,7 @@ constexpr int dphi_block_begin(int fbi, int fbj) {
 
 template <int FBI, int FBJ>
 __device__ __forceinline__ void dphi_block(f32x4 (&acc)[4][4], const bf16_t* __restrict__ Sn, ChunkSmem<RING_DP>& sm,
-                                           const Frag (&yf)[4][2], float xscale, int wv, int lane) {
+                                           const Frag (&yf)[4][2], float xscale, int wv, int lane PA_PROBE_PARAM) {
     constexpr int RING_TILES = RING_DP;
     constexpr int K0 = dphi_block_begin(FBI, FBJ), K1 = K0 + (FBI == FBJ ? 3 : 4);
     const int r16 = lane & 15, g = lane >> 4;
@@ -254,8 +264,11 @@ __device__ __forceinline__ void dphi_block(f32x4 (&acc)[4][4], const bf16_t* __r
     for (int k = K0; k < K1; ++k) {
         const int code = DPHI_ORDER.v[k];
         const int ti = code & 255, tj = (code >> 8) & 255;
+        PA_PROBE(0)
         vm_wait<4 * (RING_TILES - 2)>();
+        PA_PROBE(1)
         __builtin_amdgcn_s_barrier();
+        PA_PROBE(2)
         ring_issue<true>(sm, (k + RING_TILES - 1) % RING_TILES, Sn, DPHI_ORDER.v[min(k + RING_TILES - 1, NTILES)] >> 16, wv, lane);
         const uint32_t slot_lo = ring_lo + (uint32_t)(k % RING_TILES) * (TILE_U4 * 16u);
         const uint32_t slot_hi = ring_hi + (uint32_t)(k % RING_TILES) * (TILE_U4 * 16u);
@@ -275,29 +288,39 @@ __device__ __forceinline__ void dphi_block(f32x4 (&acc)[4][4], const bf16_t* __r
                 for (int r = 0; r < 4; ++r) u2[ib][r] = 0.f;
             }
         }
-        const float m0 = (g == 2 * (ti & 1)) ? 1.f : 0.f;       // this lane owns the features of row blocks 0, 1
-        const float m1 = (g == 2 * (ti & 1) + 1) ? 1.f : 0.f;   // ... of row blocks 2, 3
+        // Row blocks rb and rb + 2 go through the cross-lane steps together.  After the 16-lane
+        // swap and one add, the 16-lane rows hold the term-1 sums over all b for
+        // a = 2 rb, 2 rb + 4, 2 rb + 1, 2 rb + 5; the 32-lane swap brings a and a + 1 together in
+        // the lanes g with (g & 1) = a >> 2, and the two lanes g >> 1 = ti & 1 own those features.
+        const float own_mask = ((g >> 1) == (ti & 1)) ? 1.f : 0.f;
         lds_read_wait();
+        PA_PROBE(3)
 #pragma unroll
-        for (int rb = 0; rb < 4; ++rb) {
-            const float mk = (rb < 2) ? m0 : m1;
+        for (int rb = 0; rb < 2; ++rb) {
 #pragma unroll
             for (int ib = 0; ib < 4; ++ib) {
-                f32x4 c = mfma16(sf[rb][0].v, yf[ib][0].v, ZERO4);
-                c = mfma16(sf[rb][1].v, yf[ib][1].v, c);
-                const float xa = xscale * lds_bf(&Xb[64 * wv + 16 * ib + r16][8 * ti + 2 * rb + (g >> 1)]);
-                float own = c[0] * xb[ib][0] + c[1] * xb[ib][1] + c[2] * xb[ib][2] + c[3] * xb[ib][3];
-                own = xor16_sum(own);                           // all of b; value of a = 2 rb + (g >> 1)
-                float h0, h1;                                   // a = 2 rb (lower half-wave), 2 rb + 1 (upper)
-                halves(own, h0, h1);
-                acc[FBI][ib][2 * (rb & 1)] += mk * h0;
-                acc[FBI][ib][2 * (rb & 1) + 1] += mk * h1;
+                f32x4 ca = mfma16(sf[rb][0].v, yf[ib][0].v, ZERO4);
+                ca = mfma16(sf[rb][1].v, yf[ib][1].v, ca);
+                f32x4 cb = mfma16(sf[rb + 2][0].v, yf[ib][0].v, ZERO4);
+                cb = mfma16(sf[rb + 2][1].v, yf[ib][1].v, cb);
+                const bf16_t* xrow = &Xb[64 * wv + 16 * ib + r16][8 * ti + 2 * rb + (g >> 1)];
+                const float xa_a = lds_bf(xrow), xa_b = lds_bf(xrow + 4);   // unscaled: xscale is applied on landing
+                const float own_a = ca[0] * xb[ib][0] + ca[1] * xb[ib][1] + ca[2] * xb[ib][2] + ca[3] * xb[ib][3];
+                const float own_b = cb[0] * xb[ib][0] + cb[1] * xb[ib][1] + cb[2] * xb[ib][2] + cb[3] * xb[ib][3];
+                const auto sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(own_a), __float_as_uint(own_b), false, false);
+                float lo, hi;
+                halves(__uint_as_float(sw[0]) + __uint_as_float(sw[1]), lo, hi);
+                acc[FBI][ib][2 * rb] += own_mask * lo;
+                acc[FBI][ib][2 * rb + 1] += own_mask * hi;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) u2[ib][r] += c[r] * xa;
+                for (int r = 0; r < 4; ++r) {
+                    u2[ib][r] += ca[r] * xa_a;
+                    u2[ib][r] += cb[r] * xa_b;
+                }
             }
         }
         if (ti == min(tj, 2 * FBI + 1)) {   // last tile of the column block here: land term 2
-            const float mk = ((g >> 1) == (tj & 1)) ? 1.f : 0.f;
+            const float mk = ((g >> 1) == (tj & 1)) ? xscale : 0.f;
 #pragma unroll
             for (int ib = 0; ib < 4; ++ib)
 #pragma unroll
@@ -312,16 +335,18 @@ __device__ __forceinline__ void dphi(f32x4 (&acc)[4][4], const bf16_t* __restric
     constexpr int RING_TILES = RING_DP;
 #pragma unroll
     for (int k = 0; k < RING_TILES - 1; ++k) ring_issue<true>(sm, k, Sn, DPHI_ORDER.v[k] >> 16, wv, lane);
-    dphi_block<0, 0>(acc, Sn, sm, yf, xscale, wv, lane);
-    dphi_block<0, 1>(acc, Sn, sm, yf, xscale, wv, lane);
-    dphi_block<1, 1>(acc, Sn, sm, yf, xscale, wv, lane);
-    dphi_block<0, 2>(acc, Sn, sm, yf, xscale, wv, lane);
-    dphi_block<1, 2>(acc, Sn, sm, yf, xscale, wv, lane);
-    dphi_block<2, 2>(acc, Sn, sm, yf, xscale, wv, lane);
-    dphi_block<0, 3>(acc, Sn, sm, yf, xscale, wv, lane);
-    dphi_block<1, 3>(acc, Sn, sm, yf, xscale, wv, lane);
-    dphi_block<2, 3>(acc, Sn, sm, yf, xscale, wv, lane);
-    dphi_block<3, 3>(acc, Sn, sm, yf, xscale, wv, lane);
+    PA_PROBE_DECL
+    dphi_block<0, 0>(acc, Sn, sm, yf, xscale, wv, lane PA_PROBE_ARG);
+    dphi_block<0, 1>(acc, Sn, sm, yf, xscale, wv, lane PA_PROBE_ARG);
+    dphi_block<1, 1>(acc, Sn, sm, yf, xscale, wv, lane PA_PROBE_ARG);
+    dphi_block<0, 2>(acc, Sn, sm, yf, xscale, wv, lane PA_PROBE_ARG);
+    dphi_block<1, 2>(acc, Sn, sm, yf, xscale, wv, lane PA_PROBE_ARG);
+    dphi_block<2, 2>(acc, Sn, sm, yf, xscale, wv, lane PA_PROBE_ARG);
+    dphi_block<0, 3>(acc, Sn, sm, yf, xscale, wv, lane PA_PROBE_ARG);
+    dphi_block<1, 3>(acc, Sn, sm, yf, xscale, wv, lane PA_PROBE_ARG);
+    dphi_block<2, 3>(acc, Sn, sm, yf, xscale, wv, lane PA_PROBE_ARG);
+    dphi_block<3, 3>(acc, Sn, sm, yf, xscale, wv, lane PA_PROBE_ARG);
+    PA_PROBE_DUMP
     vm_wait<0>();
 }
 
