@@ -26,6 +26,7 @@ namespace mfma {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 constexpr int DH = 64;                         // head size (d = v)
 constexpr int NTB = DH / 8;                    // 8-wide feature blocks
@@ -45,6 +46,7 @@ __device__ __forceinline__ float bf_hi(uint32_t u) { return __uint_as_float(u & 
 union Frag {
     bf16x8 v;
     uint4 u;
+    u32x4 q;
     uint2 h[2];
 };
 
@@ -54,6 +56,17 @@ __device__ __forceinline__ void lds_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+    return (uint32_t)(size_t)((__attribute__((address_space(3))) const void*)p);
+}
+
+
+// wait until at most `n` of this wave's vector-memory operations are outstanding (they retire in order)
+template <int N>
+__device__ __forceinline__ void vm_wait() {
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 0xF) | (((N >> 4) & 0x3) << 14));
 }
 
 // ---- launchers (each defined next to its kernels) ------------------------------------------

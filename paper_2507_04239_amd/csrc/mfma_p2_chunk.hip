@@ -98,10 +98,6 @@ __device__ __forceinline__ float xor32_sum(float x) {
     return lo + hi;
 }
 
-__device__ __forceinline__ uint32_t lds_addr(const void* p) {
-    return (uint32_t)(size_t)((__attribute__((address_space(3))) const void*)p);
-}
-
 __device__ __forceinline__ uint4 lds_read16(uint32_t addr) {
     uint4 v;
     asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(addr) : "memory");
@@ -118,12 +114,22 @@ __device__ __forceinline__ uint2 lds_read_tr(uint32_t addr) {
     return v;
 }
 
-__device__ __forceinline__ void lds_read_wait() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
-
-// wait until at most `n` of this wave's vector-memory operations are outstanding (they retire in order)
-template <int N>
-__device__ __forceinline__ void vm_wait() {
-    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 0xF) | (((N >> 4) & 0x3) << 14));
+// Wait for this wave's LDS reads.  The eight fragments they fill pass through the statement as
+// in/out registers, so that no use of them can be scheduled ahead of the wait.
+__device__ __forceinline__ void lds_read_wait(Frag& f0, Frag& f1, Frag& f2, Frag& f3, Frag& f4, Frag& f5, Frag& f6, Frag& f7) {
+    u32x4 u0 = f0.q, u1 = f1.q, u2 = f2.q, u3 = f3.q, u4 = f4.q, u5 = f5.q, u6 = f6.q, u7 = f7.q;
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(u0), "+v"(u1), "+v"(u2), "+v"(u3), "+v"(u4), "+v"(u5), "+v"(u6), "+v"(u7)
+                 :
+                 : "memory");
+    f0.q = u0;
+    f1.q = u1;
+    f2.q = u2;
+    f3.q = u3;
+    f4.q = u4;
+    f5.q = u5;
+    f6.q = u6;
+    f7.q = u7;
 }
 
 // Copy tile `tile` of the state `Sn` (layout [a][v][b], 16-byte units (a, v)) into ring slot
@@ -177,7 +183,7 @@ __device__ __forceinline__ void readout(f32x4 (&acc)[4][4], const bf16_t* __rest
                 xbv[ib][6] = bf_lo(raw.w); xbv[ib][7] = bf_hi(raw.w);
             }
         }
-        lds_read_wait();
+        lds_read_wait(sf[0][0], sf[0][1], sf[0][2], sf[0][3], sf[1][0], sf[1][1], sf[1][2], sf[1][3]);
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
             Frag pf[4];
@@ -293,7 +299,7 @@ __device__ __forceinline__ void dphi_block(f32x4 (&acc)[4][4], const bf16_t* __r
         // a = 2 rb, 2 rb + 4, 2 rb + 1, 2 rb + 5; the 32-lane swap brings a and a + 1 together in
         // the lanes g with (g & 1) = a >> 2, and the two lanes g >> 1 = ti & 1 own those features.
         const float own_mask = ((g >> 1) == (ti & 1)) ? 1.f : 0.f;
-        lds_read_wait();
+        lds_read_wait(sf[0][0], sf[0][1], sf[1][0], sf[1][1], sf[2][0], sf[2][1], sf[3][0], sf[3][1]);
         PA_PROBE(3)
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb) {
