@@ -63,7 +63,7 @@ def algorithmic_bytes(w):
         "fwd_chunk": states + 4 * tok + BH * T * 4,  # Q, K, V in; O, Z out
         "state_grad": states + 2 * tok + BH * T * 4,  # Q, ghat, gz in
         "bwd_dq": states + 5 * tok + BH * T * 4,     # Q, K, V, ghat, gz in; dQ out
-        "bwd_dkdv": 2 * states + 6 * tok + BH * T * 4,
+        "bwd_dkdv": states + 6 * tok + BH * T * 4,   # Q, K, V, ghat, gz in; dK, dV out; R once
         "bwd_dk": states + 5 * tok + BH * T * 4,
         "bwd_dv": states + 4 * tok,                  # Q, K, ghat in; dV out
         "recompute": 0,
@@ -82,6 +82,7 @@ KERNEL_ROLE = {
     "mfma_fwd_chunk": ("fwd_chunk", PEAK_BF16_MFMA_TFLOPS),
     "mfma_state_grad_scan": ("state_grad", PEAK_BF16_MFMA_TFLOPS),
     "mfma_bwd_dq": ("bwd_dq", PEAK_BF16_MFMA_TFLOPS),
+    "mfma_bwd_dkdv": ("bwd_dkdv", PEAK_BF16_MFMA_TFLOPS),
     "mfma_bwd_dk": ("bwd_dk", PEAK_BF16_MFMA_TFLOPS),
     "mfma_bwd_dv": ("bwd_dv", PEAK_BF16_MFMA_TFLOPS),
 }

@@ -86,6 +86,9 @@ bool launch_bwd_dq(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t
 bool launch_bwd_dk(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* V, const bf16_t* Gh,
                    const float* gz, const bf16_t* Qt, const bf16_t* rtC, const bf16_t* omg, bf16_t* dK, int BH, int T,
                    int cs, float scale);
+bool launch_bwd_dkdv(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* V, const bf16_t* Gh, const float* gz,
+                     const bf16_t* Qt, const bf16_t* Ght, const bf16_t* rtC, const bf16_t* omg, bf16_t* dK, bf16_t* dV, int BH,
+                     int T, int cs, float scale);
 bool launch_bwd_dv(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* Ght, const bf16_t* rtC,
                    bf16_t* dV, int BH, int T, int cs, float scale);
 

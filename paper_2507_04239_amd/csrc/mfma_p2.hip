@@ -145,8 +145,7 @@ pa_status mfma_bwd(const Ctx& c, const void* Q, const void* K, const void* V, co
         PA_TRY(launch_scan("mfma_state_scan_bwd", s_side, false, Kt, Vt, nullptr, Sc, Gam, BH, pr.T, L.cs, 1.0f))
     }
     PA_TRY(launch_bwd_dq(s_side, q, k, v, Gh, gz, Kt, Sc, Gam, (bf16_t*)dQ, BH, pr.T, L.cs, pr.scale))
-    PA_TRY(launch_bwd_dk(s_main, q, k, v, Gh, gz, Qt, Rc, Omg, (bf16_t*)dK, BH, pr.T, L.cs, pr.scale))
-    PA_TRY(launch_bwd_dv(s_main, q, k, Ght, Rc, (bf16_t*)dV, BH, pr.T, L.cs, pr.scale))
+    PA_TRY(launch_bwd_dkdv(s_main, q, k, v, Gh, gz, Qt, Ght, Rc, Omg, (bf16_t*)dK, (bf16_t*)dV, BH, pr.T, L.cs, pr.scale))
     if (side.ok) {
         if (hipEventRecord(side.join, s_side) != hipSuccess || hipStreamWaitEvent(s_main, side.join, 0) != hipSuccess)
             return PA_ERR_HIP;

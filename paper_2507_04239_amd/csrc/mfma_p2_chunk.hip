@@ -29,8 +29,8 @@ typedef bf16_t XbRow[XB_PITCH];
 
 __device__ __forceinline__ float lds_bf(const bf16_t* p) { return __uint_as_float(((uint32_t)*p) << 16); }
 
-__device__ __forceinline__ void stage_rows(XbRow* Xb, const bf16_t* __restrict__ X, size_t row0, int tid) {
-    for (int e = tid; e < QBLK * DH / 8; e += 128) {
+__device__ __forceinline__ void stage_rows(XbRow* Xb, const bf16_t* __restrict__ X, size_t row0, int tid, int nthreads = 128) {
+    for (int e = tid; e < QBLK * DH / 8; e += nthreads) {
         const int row = e >> 3, c8 = e & 7;
         *(uint4*)&Xb[row][8 * c8] = *(const uint4*)(X + (row0 + row) * DH + 8 * c8);
     }
@@ -136,91 +136,20 @@ __device__ __forceinline__ void lds_read_wait(Frag& f0, Frag& f1, Frag& f2, Frag
 // `slot`.  SWIZZLE = false: straight copy, for the read-out, whose fragment order is the storage
 // order.  SWIZZLE = true, for the transposing reads of d phi: unit (a, v) is stored at
 // (a, v ^ 4 (a & 1)), which puts the two rows a of one transposing read on different banks.
-template <bool SWIZZLE, int RING_TILES>
-__device__ __forceinline__ void ring_issue(ChunkSmem<RING_TILES>& sm, int slot, const bf16_t* __restrict__ Sn, int tile, int wv,
+// NW waves share the ring; wave `wr` of them issues 8 / NW of a tile's eight copies.
+template <bool SWIZZLE, int NW, int RING_TILES>
+__device__ __forceinline__ void ring_issue(ChunkSmem<RING_TILES>& sm, int slot, const bf16_t* __restrict__ Sn, int tile, int wr,
                                            int lane) {
     const bf16_t* src = Sn + (size_t)tile * TILE_ELEMS;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const int instr = 4 * wv + q;
+    for (int q = 0; q < 8 / NW; ++q) {
+        const int instr = (8 / NW) * wr + q;
         const int unit = instr * 64 + (SWIZZLE ? (lane ^ ((instr & 1) << 2)) : lane);
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + unit * 8),
                                          (__attribute__((address_space(3))) void*)&sm.ring[slot][instr * 64], 16, 0, 0);
     }
 }
 
-// ---- read-out: contraction over the expanded rows (query-state, App. E.4) -----------------------
-// acc[vb][ib] += S^T phi(xscale^(1/2) x)^T for the 64 tokens of wave wv.  `Sn` is one state in
-// layout "C": tile (ti, tj) = two steps of 32 expanded rows, step s holding rows a = 4s + g.
-// Must be called by both waves of the workgroup (it contains barriers).
-__device__ __forceinline__ void readout(f32x4 (&acc)[4][4], const bf16_t* __restrict__ Sn, ChunkSmem<RING_RO>& sm,
-                                        float xscale, int wv, int lane) {
-    constexpr int RING_TILES = RING_RO;
-    const int r16 = lane & 15, g = lane >> 4;
-    const XbRow* Xb = sm.xb;
-    const uint32_t ring0 = lds_addr(&sm.ring[0][0]) + (uint32_t)(g * 64 + r16) * 16u;
-#pragma unroll
-    for (int t = 0; t < RING_TILES - 1; ++t) ring_issue<false>(sm, t, Sn, t, wv, lane);
-    int ti = 0, tj = 0;
-    float xbv[4][8];
-    for (int tile = 0; tile < NTILES; ++tile) {
-        vm_wait<4 * (RING_TILES - 2)>();
-        __builtin_amdgcn_s_barrier();
-        ring_issue<false>(sm, (tile + RING_TILES - 1) % RING_TILES, Sn, min(tile + RING_TILES - 1, NTILES - 1), wv, lane);
-        const uint32_t slot = ring0 + (uint32_t)(tile % RING_TILES) * (TILE_U4 * 16u);
-        Frag sf[2][4];
-#pragma unroll
-        for (int s = 0; s < 2; ++s)
-#pragma unroll
-            for (int vb = 0; vb < 4; ++vb) sf[s][vb].u = lds_read16(slot + (uint32_t)(s * 256 + vb * 16) * 16u);
-        if (ti == 0) {   // a new column block tj: x[8 tj .. 8 tj + 7] of each token
-#pragma unroll
-            for (int ib = 0; ib < 4; ++ib) {
-                const uint4 raw = *(const uint4*)&Xb[64 * wv + 16 * ib + r16][8 * tj];
-                xbv[ib][0] = bf_lo(raw.x); xbv[ib][1] = bf_hi(raw.x);
-                xbv[ib][2] = bf_lo(raw.y); xbv[ib][3] = bf_hi(raw.y);
-                xbv[ib][4] = bf_lo(raw.z); xbv[ib][5] = bf_hi(raw.z);
-                xbv[ib][6] = bf_lo(raw.w); xbv[ib][7] = bf_hi(raw.w);
-            }
-        }
-        lds_read_wait(sf[0][0], sf[0][1], sf[0][2], sf[0][3], sf[1][0], sf[1][1], sf[1][2], sf[1][3]);
-#pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            Frag pf[4];
-#pragma unroll
-            for (int ib = 0; ib < 4; ++ib) {
-                const float xa = xscale * lds_bf(&Xb[64 * wv + 16 * ib + r16][8 * ti + 4 * s + g]);
-#pragma unroll
-                for (int i = 0; i < 8; ++i) pf[ib].v[i] = (__bf16)(xa * xbv[ib][i]);
-            }
-#pragma unroll
-            for (int vb = 0; vb < 4; ++vb)
-#pragma unroll
-                for (int ib = 0; ib < 4; ++ib) acc[vb][ib] = mfma16(sf[s][vb].v, pf[ib].v, acc[vb][ib]);
-        }
-        if (++ti > tj) {
-            ++tj;
-            ti = 0;
-        }
-    }
-    vm_wait<0>();
-}
-
-// ---- d phi: contraction over the value columns, then the Jacobian of phi ----------------------
-// For the 64 tokens of wave wv, x~ = xscale * x, and a state `Sn` (layout [a][v][b], the same
-// copy the read-out uses; the operand of this contraction needs 8 value columns per lane, which
-// the transposing LDS read gathers from 8 units):
-//     A[(a,b), token] = sum_v S[(ti,tj,a,b), v] y[token, v]                       (MFMA)
-//     acc[8 ti + a][token] += sum_b A[(a,b)] x~[8 tj + b]        (term 1)
-//     acc[8 tj + b][token] += sum_a A[(a,b)] x~[8 ti + a]        (term 2)        (vector ALU)
-// i.e. acc += J_phi(x~)^T (S y), phi(x)_(ti,tj,a,b) = x[8ti+a] x[8tj+b] (tile multiplicity is in
-// S).  yf[ib][ks] are the B operands y^T (k-slots = value columns 32 ks + 8 g ..).
-//
-// The MFMA result block (rb, ib) holds, in lane (token r16, g), rows a = 2 rb + (g >> 1),
-// b = 4 (g & 1) + r.  Both terms are finished in registers: term 2 is summed over the tiles of a
-// column block tj and lands once per visit; term 1 is summed across the lane pair, exchanged
-// across the half-waves and added by the lane that owns feature 8 ti + a in the accumulator
-// layout (feature 16 fb + 4 g' + r').
 // Traversal order of the 36 tiles for the d phi contraction: by blocks of 2 x 2 tiles
 // (fbi, fbj) = (ti >> 1, tj >> 1), fbj outermost, so that inside one block the accumulator rows
 // both terms add to, acc[fbi] and acc[fbj], are compile-time names.  Entry = ti | tj << 8 |
@@ -250,10 +179,93 @@ constexpr int dphi_block_begin(int fbi, int fbj) {
     return k;
 }
 
-template <int FBI, int FBJ>
-__device__ __forceinline__ void dphi_block(f32x4 (&acc)[4][4], const bf16_t* __restrict__ Sn, ChunkSmem<RING_DP>& sm,
-                                           const Frag (&yf)[4][2], float xscale, int wv, int lane PA_PROBE_PARAM) {
-    constexpr int RING_TILES = RING_DP;
+// ---- read-out: contraction over the expanded rows (query-state, App. E.4) -----------------------
+// acc[vb][ib] += S^T phi(xscale^(1/2) x)^T for the 64 tokens of wave wv.  `Sn` is one state in
+// layout "C": tile (ti, tj) = two steps of 32 expanded rows, step s holding rows a = 4s + g.
+// Must be called by both waves of the workgroup (it contains barriers).
+// DORDER = false: tiles in storage order from a plain ring.  DORDER = true: tiles in the order
+// of the d phi contraction from a swizzled ring, for a workgroup whose other waves do that
+// contraction on the same ring.  `wv`: which 64 tokens; `wr`: this wave's index among the NW
+// waves that share the ring.
+template <int RING_TILES, int NW, bool DORDER>
+__device__ __forceinline__ void readout(f32x4 (&acc)[4][4], const bf16_t* __restrict__ Sn, ChunkSmem<RING_TILES>& sm,
+                                        float xscale, int wv, int wr, int lane) {
+    const int r16 = lane & 15, g = lane >> 4;
+    const XbRow* Xb = sm.xb;
+    // fragment (s, vb) of a tile: unit (a = 4 s + g, v = 16 vb + r16); swizzled: v ^ 4 (a & 1)
+    const uint32_t ring0 = lds_addr(&sm.ring[0][0]) + (uint32_t)(g * 64 + (DORDER ? (r16 ^ ((g & 1) << 2)) : r16)) * 16u;
+    auto tile_of = [&](int k) { return DORDER ? (DPHI_ORDER.v[min(k, NTILES)] >> 16) : min(k, NTILES - 1); };
+#pragma unroll
+    for (int t = 0; t < RING_TILES - 1; ++t) ring_issue<DORDER, NW>(sm, t, Sn, tile_of(t), wr, lane);
+    int ti = 0, tj = 0, tj_loaded = -1;
+    float xbv[4][8];
+    for (int k = 0; k < NTILES; ++k) {
+        if (DORDER) {
+            const int code = DPHI_ORDER.v[k];
+            ti = code & 255;
+            tj = (code >> 8) & 255;
+        }
+        vm_wait<(8 / NW) * (RING_TILES - 2)>();
+        __builtin_amdgcn_s_barrier();
+        ring_issue<DORDER, NW>(sm, (k + RING_TILES - 1) % RING_TILES, Sn, tile_of(k + RING_TILES - 1), wr, lane);
+        const uint32_t slot = ring0 + (uint32_t)(k % RING_TILES) * (TILE_U4 * 16u);
+        Frag sf[2][4];
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int vb = 0; vb < 4; ++vb) sf[s][vb].u = lds_read16(slot + (uint32_t)(s * 256 + vb * 16) * 16u);
+        if (tj != tj_loaded) {   // a new column block tj: x[8 tj .. 8 tj + 7] of each token
+            tj_loaded = tj;
+#pragma unroll
+            for (int ib = 0; ib < 4; ++ib) {
+                const uint4 raw = *(const uint4*)&Xb[64 * wv + 16 * ib + r16][8 * tj];
+                xbv[ib][0] = bf_lo(raw.x); xbv[ib][1] = bf_hi(raw.x);
+                xbv[ib][2] = bf_lo(raw.y); xbv[ib][3] = bf_hi(raw.y);
+                xbv[ib][4] = bf_lo(raw.z); xbv[ib][5] = bf_hi(raw.z);
+                xbv[ib][6] = bf_lo(raw.w); xbv[ib][7] = bf_hi(raw.w);
+            }
+        }
+        lds_read_wait(sf[0][0], sf[0][1], sf[0][2], sf[0][3], sf[1][0], sf[1][1], sf[1][2], sf[1][3]);
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            Frag pf[4];
+#pragma unroll
+            for (int ib = 0; ib < 4; ++ib) {
+                const float xa = xscale * lds_bf(&Xb[64 * wv + 16 * ib + r16][8 * ti + 4 * s + g]);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) pf[ib].v[i] = (__bf16)(xa * xbv[ib][i]);
+            }
+#pragma unroll
+            for (int vb = 0; vb < 4; ++vb)
+#pragma unroll
+                for (int ib = 0; ib < 4; ++ib) acc[vb][ib] = mfma16(sf[s][vb].v, pf[ib].v, acc[vb][ib]);
+        }
+        if (!DORDER && ++ti > tj) {
+            ++tj;
+            ti = 0;
+        }
+    }
+    vm_wait<0>();
+}
+
+// ---- d phi: contraction over the value columns, then the Jacobian of phi ----------------------
+// For the 64 tokens of wave wv, x~ = xscale * x, and a state `Sn` (layout [a][v][b], the same
+// copy the read-out uses; the operand of this contraction needs 8 value columns per lane, which
+// the transposing LDS read gathers from 8 units):
+//     A[(a,b), token] = sum_v S[(ti,tj,a,b), v] y[token, v]                       (MFMA)
+//     acc[8 ti + a][token] += sum_b A[(a,b)] x~[8 tj + b]        (term 1)
+//     acc[8 tj + b][token] += sum_a A[(a,b)] x~[8 ti + a]        (term 2)        (vector ALU)
+// i.e. acc += J_phi(x~)^T (S y), phi(x)_(ti,tj,a,b) = x[8ti+a] x[8tj+b] (tile multiplicity is in
+// S).  yf[ib][ks] are the B operands y^T (k-slots = value columns 32 ks + 8 g ..).
+//
+// The MFMA result block (rb, ib) holds, in lane (token r16, g), rows a = 2 rb + (g >> 1),
+// b = 4 (g & 1) + r.  Both terms are finished in registers: term 2 is summed over the tiles of a
+// column block tj and lands once per visit; term 1 is summed across the lane pair, exchanged
+// across the half-waves and added by the lane that owns feature 8 ti + a in the accumulator
+// layout (feature 16 fb + 4 g' + r').
+template <int FBI, int FBJ, int RING_TILES, int NW>
+__device__ __forceinline__ void dphi_block(f32x4 (&acc)[4][4], const bf16_t* __restrict__ Sn, ChunkSmem<RING_TILES>& sm,
+                                           const Frag (&yf)[4][2], float xscale, int wv, int wr, int lane PA_PROBE_PARAM) {
     constexpr int K0 = dphi_block_begin(FBI, FBJ), K1 = K0 + (FBI == FBJ ? 3 : 4);
     const int r16 = lane & 15, g = lane >> 4;
     const XbRow* Xb = sm.xb;
@@ -271,11 +283,11 @@ __device__ __forceinline__ void dphi_block(f32x4 (&acc)[4][4], const bf16_t* __r
         const int code = DPHI_ORDER.v[k];
         const int ti = code & 255, tj = (code >> 8) & 255;
         PA_PROBE(0)
-        vm_wait<4 * (RING_TILES - 2)>();
+        vm_wait<(8 / NW) * (RING_TILES - 2)>();
         PA_PROBE(1)
         __builtin_amdgcn_s_barrier();
         PA_PROBE(2)
-        ring_issue<true>(sm, (k + RING_TILES - 1) % RING_TILES, Sn, DPHI_ORDER.v[min(k + RING_TILES - 1, NTILES)] >> 16, wv, lane);
+        ring_issue<true, NW>(sm, (k + RING_TILES - 1) % RING_TILES, Sn, DPHI_ORDER.v[min(k + RING_TILES - 1, NTILES)] >> 16, wr, lane);
         const uint32_t slot_lo = ring_lo + (uint32_t)(k % RING_TILES) * (TILE_U4 * 16u);
         const uint32_t slot_hi = ring_hi + (uint32_t)(k % RING_TILES) * (TILE_U4 * 16u);
         Frag sf[4][2];
@@ -335,23 +347,18 @@ __device__ __forceinline__ void dphi_block(f32x4 (&acc)[4][4], const bf16_t* __r
     }
 }
 
-// Must be called by both waves of the workgroup (it contains barriers).
-__device__ __forceinline__ void dphi(f32x4 (&acc)[4][4], const bf16_t* __restrict__ Sn, ChunkSmem<RING_DP>& sm,
-                                     const Frag (&yf)[4][2], float xscale, int wv, int lane) {
-    constexpr int RING_TILES = RING_DP;
+// Must be called by all NW waves that share the ring (it contains barriers), or run side by side
+// with waves that execute readout<.., NW, true> on the same ring.
+template <int RING_TILES, int NW>
+__device__ __forceinline__ void dphi(f32x4 (&acc)[4][4], const bf16_t* __restrict__ Sn, ChunkSmem<RING_TILES>& sm,
+                                     const Frag (&yf)[4][2], float xscale, int wv, int wr, int lane) {
 #pragma unroll
-    for (int k = 0; k < RING_TILES - 1; ++k) ring_issue<true>(sm, k, Sn, DPHI_ORDER.v[k] >> 16, wv, lane);
+    for (int k = 0; k < RING_TILES - 1; ++k) ring_issue<true, NW>(sm, k, Sn, DPHI_ORDER.v[k] >> 16, wr, lane);
     PA_PROBE_DECL
-    dphi_block<0, 0>(acc, Sn, sm, yf, xscale, wv, lane PA_PROBE_ARG);
-    dphi_block<0, 1>(acc, Sn, sm, yf, xscale, wv, lane PA_PROBE_ARG);
-    dphi_block<1, 1>(acc, Sn, sm, yf, xscale, wv, lane PA_PROBE_ARG);
-    dphi_block<0, 2>(acc, Sn, sm, yf, xscale, wv, lane PA_PROBE_ARG);
-    dphi_block<1, 2>(acc, Sn, sm, yf, xscale, wv, lane PA_PROBE_ARG);
-    dphi_block<2, 2>(acc, Sn, sm, yf, xscale, wv, lane PA_PROBE_ARG);
-    dphi_block<0, 3>(acc, Sn, sm, yf, xscale, wv, lane PA_PROBE_ARG);
-    dphi_block<1, 3>(acc, Sn, sm, yf, xscale, wv, lane PA_PROBE_ARG);
-    dphi_block<2, 3>(acc, Sn, sm, yf, xscale, wv, lane PA_PROBE_ARG);
-    dphi_block<3, 3>(acc, Sn, sm, yf, xscale, wv, lane PA_PROBE_ARG);
+#define PA_BLOCK(I, J) dphi_block<I, J, RING_TILES, NW>(acc, Sn, sm, yf, xscale, wv, wr, lane PA_PROBE_ARG);
+    PA_BLOCK(0, 0) PA_BLOCK(0, 1) PA_BLOCK(1, 1) PA_BLOCK(0, 2) PA_BLOCK(1, 2) PA_BLOCK(2, 2)
+    PA_BLOCK(0, 3) PA_BLOCK(1, 3) PA_BLOCK(2, 3) PA_BLOCK(3, 3)
+#undef PA_BLOCK
     PA_PROBE_DUMP
     vm_wait<0>();
 }
@@ -433,7 +440,7 @@ __global__ __launch_bounds__(128, 2) void k_mfma_fwd_chunk(const bf16_t* __restr
                 zsum[ib] += s2 * (c[0] * bf_lo(raw.x) + c[1] * bf_hi(raw.x) + c[2] * bf_lo(raw.y) + c[3] * bf_hi(raw.y));
             }
         }
-        readout(acc, StC + (size_t)(bh * nstate + n) * STATE_ELEMS, sm, s2, wv, lane);
+        readout<RING_RO, 2, false>(acc, StC + (size_t)(bh * nstate + n) * STATE_ELEMS, sm, s2, wv, wv, lane);
     }
 
 #pragma unroll
@@ -579,7 +586,7 @@ __global__ __launch_bounds__(128, 2) void k_mfma_bwd_dq(const bf16_t* __restrict
                 for (int r = 0; r < 4; ++r) acc[ab][ib][r] += f * c[r];
             }
         }
-        dphi(acc, StC + (size_t)(bh * nstate + n) * STATE_ELEMS, sm, gf, scale, wv, lane);
+        dphi<RING_DP, 2>(acc, StC + (size_t)(bh * nstate + n) * STATE_ELEMS, sm, gf, scale, wv, wv, lane);
     }
 #pragma unroll
     for (int ib = 0; ib < 4; ++ib) {
@@ -597,14 +604,14 @@ __global__ __launch_bounds__(128, 2) void k_mfma_bwd_dq(const bf16_t* __restrict
 // ---- backward, keys: dK ---------------------------------------------------------------------------
 //   dk_j = scale * sum_{i>=j, same stretch} t_ij q_i + 2 Omega_m k_j + J_phi(k_j)^T (R_m v_j)
 // (R and Omega already carry scale^2).  acc[fb][jb] = dK^T: 16 features x 16 keys.
-__global__ __launch_bounds__(128, 2) void k_mfma_bwd_dk(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
-                                                        const bf16_t* __restrict__ V, const bf16_t* __restrict__ Gh,
-                                                        const float* __restrict__ gz, const bf16_t* __restrict__ Qt,
-                                                        const bf16_t* __restrict__ RtC, const bf16_t* __restrict__ Omg,
-                                                        bf16_t* __restrict__ dK, int T, int cs, float scale) {
-    __shared__ __attribute__((aligned(16))) ChunkSmem<RING_DP> sm;
-    XbRow* Xb = sm.xb;
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+// Body for the 64 keys of token half `wv`; the block's K rows are already staged in sm.xb.
+template <int RING_TILES, int NW>
+__device__ __forceinline__ void dk_body(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
+                                        const bf16_t* __restrict__ Gh, const float* __restrict__ gz,
+                                        const bf16_t* __restrict__ Qt, const bf16_t* __restrict__ RtC,
+                                        const bf16_t* __restrict__ Omg, bf16_t* __restrict__ dK, int T, int cs, float scale,
+                                        ChunkSmem<RING_TILES>& sm, int wv, int wr, int lane) {
+    const XbRow* Xb = sm.xb;
     const int r16 = lane & 15, g = lane >> 4;
     const int bh = blockIdx.y;
     const int j0 = blockIdx.x * QBLK;
@@ -613,7 +620,6 @@ __global__ __launch_bounds__(128, 2) void k_mfma_bwd_dk(const bf16_t* __restrict
     const size_t head_tok = (size_t)bh * T;
     const bf16_t* Qt_head = Qt + (size_t)bh * DH * T;
 
-    stage_rows(Xb, K, head_tok + j0, tid);
     Frag vf[4][2];   // V^T of this wave's keys as B operands
 #pragma unroll
     for (int jb = 0; jb < 4; ++jb) {
@@ -626,7 +632,6 @@ __global__ __launch_bounds__(128, 2) void k_mfma_bwd_dk(const bf16_t* __restrict
     for (int fb = 0; fb < 4; ++fb)
 #pragma unroll
         for (int jb = 0; jb < 4; ++jb) acc[fb][jb] = ZERO4;
-    __syncthreads();
 
     const int q_hi = (m + 1) * cs;   // queries of the same stretch, from the diagonal block on
     for (int qb0 = j0; qb0 < q_hi; qb0 += QBLK) {
@@ -686,7 +691,7 @@ __global__ __launch_bounds__(128, 2) void k_mfma_bwd_dk(const bf16_t* __restrict
                 for (int r = 0; r < 4; ++r) acc[ab][jb][r] += 2.f * c[r];
             }
         }
-        dphi(acc, RtC + (size_t)(bh * nstate + m) * STATE_ELEMS, sm, vf, 1.f, wv, lane);
+        dphi<RING_TILES, NW>(acc, RtC + (size_t)(bh * nstate + m) * STATE_ELEMS, sm, vf, 1.f, wv, wr, lane);
     }
 #pragma unroll
     for (int jb = 0; jb < 4; ++jb) {
@@ -701,15 +706,28 @@ __global__ __launch_bounds__(128, 2) void k_mfma_bwd_dk(const bf16_t* __restrict
     }
 }
 
+__global__ __launch_bounds__(128, 2) void k_mfma_bwd_dk(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
+                                                        const bf16_t* __restrict__ V, const bf16_t* __restrict__ Gh,
+                                                        const float* __restrict__ gz, const bf16_t* __restrict__ Qt,
+                                                        const bf16_t* __restrict__ RtC, const bf16_t* __restrict__ Omg,
+                                                        bf16_t* __restrict__ dK, int T, int cs, float scale) {
+    __shared__ __attribute__((aligned(16))) ChunkSmem<RING_DP> sm;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    stage_rows(sm.xb, K, (size_t)blockIdx.y * T + blockIdx.x * QBLK, tid);
+    __syncthreads();
+    dk_body<RING_DP, 2>(Q, K, V, Gh, gz, Qt, RtC, Omg, dK, T, cs, scale, sm, wv, wv, lane);
+}
+
 // ---- backward, values: dV ---------------------------------------------------------------------------
 //   dv_j = sum_{i>=j, same stretch} s_ij^2 ghat_i + R_m^T phi(k_j)
 // acc[vb][jb] = dV^T: 16 value columns x 16 keys.
-__global__ __launch_bounds__(128, 2) void k_mfma_bwd_dv(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
-                                                        const bf16_t* __restrict__ Ght, const bf16_t* __restrict__ RtC,
-                                                        bf16_t* __restrict__ dV, int T, int cs, float scale) {
-    __shared__ __attribute__((aligned(16))) ChunkSmem<RING_RO> sm;
-    XbRow* Xb = sm.xb;
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+// Body for the 64 keys of token half `wv`; the block's K rows are already staged in sm.xb.
+template <int RING_TILES, int NW, bool DORDER>
+__device__ __forceinline__ void dv_body(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
+                                        const bf16_t* __restrict__ Ght, const bf16_t* __restrict__ RtC,
+                                        bf16_t* __restrict__ dV, int T, int cs, float scale, ChunkSmem<RING_TILES>& sm, int wv,
+                                        int wr, int lane) {
+    const XbRow* Xb = sm.xb;
     const int r16 = lane & 15, g = lane >> 4;
     const int bh = blockIdx.y;
     const int j0 = blockIdx.x * QBLK;
@@ -719,13 +737,11 @@ __global__ __launch_bounds__(128, 2) void k_mfma_bwd_dv(const bf16_t* __restrict
     const bf16_t* Ght_head = Ght + (size_t)bh * DH * T;
     const float s2 = scale * scale;
 
-    stage_rows(Xb, K, head_tok + j0, tid);
     f32x4 acc[4][4];
 #pragma unroll
     for (int vb = 0; vb < 4; ++vb)
 #pragma unroll
         for (int jb = 0; jb < 4; ++jb) acc[vb][jb] = ZERO4;
-    __syncthreads();
 
     const int q_hi = (m + 1) * cs;
     for (int qb0 = j0; qb0 < q_hi; qb0 += QBLK) {
@@ -758,7 +774,8 @@ __global__ __launch_bounds__(128, 2) void k_mfma_bwd_dv(const bf16_t* __restrict
             }
         }
     }
-    if (m < nstate - 1) readout(acc, RtC + (size_t)(bh * nstate + m) * STATE_ELEMS, sm, 1.f, wv, lane);
+    if (m < nstate - 1)
+        readout<RING_TILES, NW, DORDER>(acc, RtC + (size_t)(bh * nstate + m) * STATE_ELEMS, sm, 1.f, wv, wr, lane);
 #pragma unroll
     for (int jb = 0; jb < 4; ++jb) {
         const size_t row = head_tok + j0 + 64 * wv + 16 * jb + r16;
@@ -770,6 +787,39 @@ __global__ __launch_bounds__(128, 2) void k_mfma_bwd_dv(const bf16_t* __restrict
             *(bf16x4*)(dV + row * DH + 16 * vb + 4 * g) = o;
         }
     }
+}
+
+__global__ __launch_bounds__(128, 2) void k_mfma_bwd_dv(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
+                                                        const bf16_t* __restrict__ Ght, const bf16_t* __restrict__ RtC,
+                                                        bf16_t* __restrict__ dV, int T, int cs, float scale) {
+    __shared__ __attribute__((aligned(16))) ChunkSmem<RING_RO> sm;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    stage_rows(sm.xb, K, (size_t)blockIdx.y * T + blockIdx.x * QBLK, tid);
+    __syncthreads();
+    dv_body<RING_RO, 2, false>(Q, K, Ght, RtC, dV, T, cs, scale, sm, wv, wv, lane);
+}
+
+// ---- backward, keys and values in one pass over R ------------------------------------------------
+// dK and dV both stream the state gradient R_m of their chunk.  Here one workgroup of four waves
+// streams it once: waves 0, 1 run the dK body and waves 2, 3 the dV body for the same 128 keys,
+// all four feeding and reading one LDS ring (swizzled for the transposing reads of d phi, tiles
+// in the d phi order; the read-out does not care about either).  The two bodies execute the same
+// number of barriers.
+constexpr int RING_KV = 4;
+__global__ __launch_bounds__(256, 2) void k_mfma_bwd_dkdv(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
+                                                          const bf16_t* __restrict__ V, const bf16_t* __restrict__ Gh,
+                                                          const float* __restrict__ gz, const bf16_t* __restrict__ Qt,
+                                                          const bf16_t* __restrict__ Ght, const bf16_t* __restrict__ RtC,
+                                                          const bf16_t* __restrict__ Omg, bf16_t* __restrict__ dK,
+                                                          bf16_t* __restrict__ dV, int T, int cs, float scale) {
+    __shared__ __attribute__((aligned(16))) ChunkSmem<RING_KV> sm;
+    const int tid = threadIdx.x, lane = tid & 63, w4 = tid >> 6;
+    stage_rows(sm.xb, K, (size_t)blockIdx.y * T + blockIdx.x * QBLK, tid, 256);
+    __syncthreads();
+    if (w4 < 2)
+        dk_body<RING_KV, 4>(Q, K, V, Gh, gz, Qt, RtC, Omg, dK, T, cs, scale, sm, w4, w4, lane);
+    else
+        dv_body<RING_KV, 4, true>(Q, K, Ght, RtC, dV, T, cs, scale, sm, w4 - 2, w4, lane);
 }
 
 }  // namespace
@@ -795,6 +845,15 @@ bool launch_bwd_dq(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t
                    int cs, float scale) {
     LaunchScope ls("mfma_bwd_dq", s);
     hipLaunchKernelGGL(k_mfma_bwd_dq, dim3(T / QBLK, BH), dim3(128), 0, s, Q, K, V, Gh, gz, Kt, stC, gam, dQ, T, cs,
+                       scale);
+    return launch_ok();
+}
+
+bool launch_bwd_dkdv(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* V, const bf16_t* Gh, const float* gz,
+                     const bf16_t* Qt, const bf16_t* Ght, const bf16_t* rtC, const bf16_t* omg, bf16_t* dK, bf16_t* dV, int BH,
+                     int T, int cs, float scale) {
+    LaunchScope ls("mfma_bwd_dkdv", s);
+    hipLaunchKernelGGL(k_mfma_bwd_dkdv, dim3(T / QBLK, BH), dim3(256), 0, s, Q, K, V, Gh, gz, Qt, Ght, rtC, omg, dK, dV, T, cs,
                        scale);
     return launch_ok();
 }
