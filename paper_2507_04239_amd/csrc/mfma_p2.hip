@@ -131,6 +131,8 @@ pa_status mfma_bwd(const Ctx& c, const void* Q, const void* K, const void* V, co
     PA_TRY(launch_bwd_prep(s_main, (const bf16_t*)dO, (const bf16_t*)O, Z, Gh, gz, (long long)BH * pr.T, pr.normalize))
     PA_TRY(launch_transpose(s_main, q, Qt, BH, pr.T))
     PA_TRY(launch_transpose(s_main, Gh, Ght, BH, pr.T))
+    // The fork sits here, not right after the preparation kernel that dQ depends on: the scan's
+    // workgroups need most of a CU's LDS and must be placed before dQ's fill the CUs.
     if (side.ok) {
         if (hipEventRecord(side.fork, s_main) != hipSuccess || hipStreamWaitEvent(s_side, side.fork, 0) != hipSuccess)
             return PA_ERR_HIP;

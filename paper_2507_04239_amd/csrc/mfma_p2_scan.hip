@@ -51,11 +51,18 @@ constexpr int XS_PITCH = SCAN_TOK + 4;         // floats; pitch = 4 mod 64 banks
 constexpr int YS_PITCH = SCAN_TOK + 8;         // bf16;   pitch = 4 mod 64 banks (in dwords)
 static_assert(NTILES % 2 == 0, "tiles are handled in pairs");
 
+// The reverse scan (state gradient) runs side by side with the dQ kernel, whose workgroups need
+// LDS of their own on the same CU: there Y is single-buffered (ys[1] is not allocated), at the
+// price of a second barrier per stage.
 struct ScanSmem {
     float xs[2][DH][XS_PITCH];
-    bf16_t ys[2][DH][YS_PITCH];
     float ws[2][SCAN_TOK];
+    bf16_t ys[2][DH][YS_PITCH];
 };
+template <bool REV>
+constexpr size_t scan_smem_bytes() {
+    return REV ? sizeof(ScanSmem) - sizeof(bf16_t) * DH * YS_PITCH : sizeof(ScanSmem);
+}
 
 // One 128-token stage of one wave: acc[rbk][cb] += phi-rows(32) x Y(64 columns), four k-steps of
 // 32 tokens.  Written as an explicit software pipeline, because a workgroup of this kernel is
@@ -88,7 +95,7 @@ __device__ __forceinline__ void scan_load_ops(ScanOps& o, const ScanSmem& sm, in
         o.xbh = o.xbl;
     }
 #pragma unroll
-    for (int cb = 0; cb < 4; ++cb) o.b[cb] = *(const uint4*)&sm.ys[buf][16 * cb + r16][t0];
+    for (int cb = 0; cb < 4; ++cb) o.b[cb] = *(const uint4*)&sm.ys[REV ? 0 : buf][16 * cb + r16][t0];
 }
 
 __device__ __forceinline__ void scan_expand(Frag (&af)[2], const ScanOps& o) {
@@ -308,11 +315,12 @@ __device__ __forceinline__ void scan_body(const bf16_t* __restrict__ Xt, const b
         PA_PROBE(1)                                                                           \
         PA_FILL_X(BUF, 0, x0_##J) PA_FILL_X(BUF, 1, x1_##J)                                   \
         PA_FILL_X(BUF, 2, x2_##J) PA_FILL_X(BUF, 3, x3_##J)                                   \
-        *(uint4*)&sm.ys[BUF][p_feat[0]][p_tok[0]] = y0_##J;                                   \
-        *(uint4*)&sm.ys[BUF][p_feat[1]][p_tok[1]] = y1_##J;                                   \
-        *(uint4*)&sm.ys[BUF][p_feat[2]][p_tok[2]] = y2_##J;                                   \
-        *(uint4*)&sm.ys[BUF][p_feat[3]][p_tok[3]] = y3_##J;                                   \
         if (GAMMA && REV && tid < SCAN_TOK) sm.ws[BUF][tid] = wv_##J;                         \
+        if (REV) lds_barrier(); /* every wave is done with the Y of the stage before */       \
+        *(uint4*)&sm.ys[REV ? 0 : BUF][p_feat[0]][p_tok[0]] = y0_##J;                         \
+        *(uint4*)&sm.ys[REV ? 0 : BUF][p_feat[1]][p_tok[1]] = y1_##J;                         \
+        *(uint4*)&sm.ys[REV ? 0 : BUF][p_feat[2]][p_tok[2]] = y2_##J;                         \
+        *(uint4*)&sm.ys[REV ? 0 : BUF][p_feat[3]][p_tok[3]] = y3_##J;                         \
         PA_PROBE(2)                                                                           \
         lds_barrier();                                                                        \
         PA_PROBE(3)                                                                           \
@@ -346,6 +354,9 @@ __global__ __launch_bounds__(256) void k_mfma_scan(const bf16_t* __restrict__ Xt
                                                    int nheads) {
     extern __shared__ __attribute__((aligned(16))) unsigned char scan_smem_raw[];
     ScanSmem& sm = *reinterpret_cast<ScanSmem*>(scan_smem_raw);
+    // A scan workgroup is a long chain of dependent steps and the critical path of its pass; waves
+    // of other kernels that share the SIMD (dQ runs side by side with the reverse scan) yield to it.
+    __builtin_amdgcn_s_setprio(3);
     // Workgroups are dealt to the 8 XCDs round-robin by their linear id.  The NPAIR + 1 workgroups
     // of one head read the same K / V stream, so the logical work items (head-major) are laid out
     // in contiguous runs per XCD: a head's stream is then pulled into one or two L2s, not eight.
@@ -384,10 +395,10 @@ bool launch_transpose(hipStream_t s, const bf16_t* in, bf16_t* out, int BH, int 
 template <bool REV, bool EVERY>
 static bool launch_scan_t(const char* name, hipStream_t s, const bf16_t* Xt, const bf16_t* Yt, const float* wgt,
                           bf16_t* stC, bf16_t* gam, int BH, int T, int cs, float out_scale) {
-    if (!allow_smem(k_mfma_scan<REV, EVERY>, sizeof(ScanSmem))) return false;
+    if (!allow_smem(k_mfma_scan<REV, EVERY>, scan_smem_bytes<REV>())) return false;
     LaunchScope ls(name, s);
     const int total = (NPAIR + 1) * BH;
-    hipLaunchKernelGGL((k_mfma_scan<REV, EVERY>), dim3(8 * ((total + 7) / 8)), dim3(256), sizeof(ScanSmem), s, Xt, Yt, wgt,
+    hipLaunchKernelGGL((k_mfma_scan<REV, EVERY>), dim3(8 * ((total + 7) / 8)), dim3(256), scan_smem_bytes<REV>(), s, Xt, Yt, wgt,
                        stC, gam, T, cs, out_scale, BH);
     return launch_ok();
 }
