@@ -135,6 +135,9 @@ def main():
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (a dispatch of known size, for scaling "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--serial-kernels", action="store_true",
+                    help="run every step with the library's per-kernel events on, i.e. kernels back to back with no "
+                         "overlap between streams (for a rocprofv3 kernel trace whose averages are each kernel's own)")
     ap.add_argument("--recompute-states", action="store_true",
                     help="backward pass rebuilds the chunk states instead of reusing the forward pass's workspace")
     args = ap.parse_args()
@@ -165,6 +168,8 @@ def main():
         power_attn_fwd(tq, tk, tv, p, chunk, impl=args.impl, workspace=ws, out=O, out_z=Z, keep_state=keep)
         power_attn_bwd(tq, tk, tv, O, Z, tg, p, chunk, impl=args.impl, workspace=ws, out=grads, keep_state=keep)
 
+    if args.serial_kernels:
+        binding.profile_begin()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -173,6 +178,8 @@ def main():
         step()
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    if args.serial_kernels:
+        binding.profile_end()
     tokens = w["B"] * w["T"]
 
     if args.copy_calibration_mib > 0:
@@ -223,7 +230,7 @@ def main():
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": w["dtype"], "data": "synthetic",
         "config": {"workload": name, "B": w["B"], "H": w["H"], "T": w["T"], "d": w["d"], "p": p, "chunk": chunk,
-                   "normalize": True, "pass": "fwd+bwd", "impl": args.impl, "keep_state": keep,
+                   "normalize": True, "pass": "fwd+bwd", "impl": args.impl, "keep_state": keep, "serial_kernels": args.serial_kernels,
                    "state_rows": binding.power_attn_state_rows(prob)},
         "step_algorithmic_tflop": total_alg / 1e12,
         "step_frac_of_bf16_mfma_peak": total_alg / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS,
