@@ -52,3 +52,65 @@ def test_mfma_backward_full_tensors(case, keep_state):
     O, Z = orc.fwd_bhtd(Q, K, V, 2, None, normalize, scale)
     dQ, dK, dV = orc.bwd_bhtd(Q, K, V, G, 2, None, normalize, scale)
     assert_close(got, dict(O=O, Z=Z, dQ=dQ, dK=dK, dV=dV), "bf16", f"mfma fwd+bwd {case}")
+
+
+def test_mfma_back_to_back_steps_share_workspace():
+    """Two forward+backward steps with different inputs, queued one after the other on the same
+    workspace without host synchronisation in between: the second forward pass overwrites states
+    the first backward pass (which runs part of its kernels on a stream of the library's own)
+    still reads unless the passes are ordered correctly."""
+    import torch
+    from paper_2507_04239_amd import binding, power_attn_bwd, power_attn_fwd
+    from gpu_util import to_dev, to_np
+    B, H, T, chunk = 1, 2, 1024, 128
+    prob = binding.make_problem(B, H, T, 64, 64, 2, chunk, True, 1.0, "bf16", "mfma", True)
+    ws = torch.empty(max(binding.power_attn_workspace_bytes(prob, True), 256), dtype=torch.uint8, device="cuda:0")
+    steps = []
+    for seed in (5001, 5002, 5003):
+        Q, K, V, G = inputs.make_qkvg(B, H, T, 64, seed=seed, dtype="bf16")
+        steps.append((Q, K, V, G, [to_dev(a, "bf16") for a in (Q, K, V, G)]))
+    results = []
+    for _, _, _, _, (tq, tk, tv, tg) in steps:   # no synchronisation between the steps
+        O, Z = power_attn_fwd(tq, tk, tv, 2, chunk, impl="mfma", workspace=ws, keep_state=True)
+        dQ, dK, dV = power_attn_bwd(tq, tk, tv, O, Z, tg, 2, chunk, impl="mfma", workspace=ws, keep_state=True)
+        results.append(dict(O=O, Z=Z, dQ=dQ, dK=dK, dV=dV))
+    torch.cuda.synchronize()
+    for i, (Q, K, V, G, _) in enumerate(steps):
+        O, Z = orc.fwd_bhtd(Q, K, V, 2, None, True, 1.0)
+        dQ, dK, dV = orc.bwd_bhtd(Q, K, V, G, 2, None, True, 1.0)
+        assert_close({k: to_np(t) for k, t in results[i].items()}, dict(O=O, Z=Z, dQ=dQ, dK=dK, dV=dV), "bf16",
+                     f"mfma back-to-back step {i}")
+
+
+def test_mfma_on_a_side_stream_of_the_caller():
+    """The calls are queued on the caller's current stream, whichever that is."""
+    import torch
+    from gpu_util import to_dev, to_np
+    from paper_2507_04239_amd import power_attn_bwd, power_attn_fwd
+    Q, K, V, G = inputs.make_qkvg(1, 1, 512, 64, seed=5010, dtype="bf16")
+    tq, tk, tv, tg = (to_dev(a, "bf16") for a in (Q, K, V, G))
+    torch.cuda.synchronize()
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        O, Z = power_attn_fwd(tq, tk, tv, 2, 128, impl="mfma")
+        dQ, dK, dV = power_attn_bwd(tq, tk, tv, O, Z, tg, 2, 128, impl="mfma")
+    stream.synchronize()
+    Oo, Zo = orc.fwd_bhtd(Q, K, V, 2, None, True, 1.0)
+    dQo, dKo, dVo = orc.bwd_bhtd(Q, K, V, G, 2, None, True, 1.0)
+    assert_close({k: to_np(t) for k, t in dict(O=O, Z=Z, dQ=dQ, dK=dK, dV=dV).items()},
+                 dict(O=Oo, Z=Zo, dQ=dQo, dK=dKo, dV=dVo), "bf16", "mfma on a caller's side stream")
+
+
+def test_mfma_zero_rows():
+    """Queries that are all zero have Z = 0: O = 0 and no gradient flows through the row; zero keys
+    and values contribute nothing."""
+    Q, K, V, G = inputs.make_qkvg(1, 1, 384, 64, seed=5020, dtype="bf16")
+    Q[0, 0, 5] = 0
+    Q[0, 0, 200] = 0
+    K[0, 0, 17] = 0
+    V[0, 0, 130] = 0
+    got = run_fwd_bwd(Q, K, V, G, 2, 128, "bf16", True, 1.0, impl="mfma")
+    O, Z = orc.fwd_bhtd(Q, K, V, 2, None, True, 1.0)
+    dQ, dK, dV = orc.bwd_bhtd(Q, K, V, G, 2, None, True, 1.0)
+    assert_close(got, dict(O=O, Z=Z, dQ=dQ, dK=dK, dV=dV), "bf16", "mfma zero rows")
+    assert (got["O"][0, 0, 5] == 0).all() and (got["dQ"][0, 0, 5] == 0).all()
