@@ -116,3 +116,18 @@ def test_p4_config4_shape_reduced_batch():
     assert rel_l2(got["O"][0, 0][:2048], O_ref) <= TOL["bf16"]
     assert rel_l2(got["Z"][0, 0][:2048], Z_ref) <= TOL["bf16"]
     _check_sampled("cfg4", got, Q, K, V, G, w1, [(0, 0)], n_rows=12, n_cols=0)
+
+
+def test_d128_config5_shape_reduced_batch():
+    """bf16 fwd+bwd, p=2, d=128, chunk 256, T=32768 (config 5's head shape; one of its 128 heads)."""
+    w = dict(inputs.WORKLOADS["cfg5_bf16_p2_T32768_d128_c256"])
+    Q, K, V, G = inputs.make_qkvg(1, 1, w["T"], w["d"], seed=1005, dtype="bf16")
+    print("case cfg5 one head", flush=True)
+    got = run_fwd_bwd(Q, K, V, G, 2, w["chunk"], "bf16")
+    for k, a in got.items():
+        assert np.isfinite(a).all(), k
+    n0 = 1024   # the first four chunks, every output, against the chunked oracle (dK, dV need the whole future: not here)
+    O_ref, Z_ref = orc.fwd_chunked(Q[0, 0][:n0], K[0, 0][:n0], V[0, 0][:n0], 2, w["chunk"])
+    assert rel_l2(got["O"][0, 0][:n0], O_ref) <= TOL["bf16"]
+    assert rel_l2(got["Z"][0, 0][:n0], Z_ref) <= TOL["bf16"]
+    _check_sampled("cfg5", got, Q, K, V, G, dict(w, B=1, H=1), [(0, 0)], n_rows=12, n_cols=0)
