@@ -17,6 +17,7 @@ What it follows (arXiv 2507.04239):
     "Chunked form", App. A), update-state / query-state (Sec. 4.1 Eq. (10), App. E.2/E.4)
   * the backward pass is not in the paper; it is derived here from the definition
     of the forward pass and pinned by finite differences in the tests.
+  * gating (Sec. 2 "Gating", App. E.2 / E.3): per-timestep log-gates, see the section below.
 
 Conventions: arrays of one head are 2-D, ``Q, K: [T, d]``, ``V, G: [T, v]``.  ``scale``
 multiplies the score before the power, ``s_ij = scale * (q_i . k_j)``.  A row whose
@@ -355,27 +356,214 @@ def bwd_chunked(Q, K, V, G, p: int, chunk: int, normalize: bool = True, scale: f
 
 
 # --------------------------------------------------------------------------------------
+# Gating (Sec. 2 "Gating"; gated update-state of App. E.2, discounted cumulative sum of App. E.3)
+#
+# The paper adopts a learned gating value per timestep (and per head) and gives the operation
+# only at chunk granularity: the state is multiplied by a decay factor before the chunk's update
+# is added (App. E.2), and the cumulative sum over chunks discounts by one factor per chunk
+# (App. E.3).  The per-timestep definition both come from is the one written out here: with
+# log-gates l_t <= 0 and b_i = l_0 + ... + l_i, the pair (i, j), j <= i, carries the product of
+# the gates of the steps j+1 .. i,
+#       a_ij = s_ij^p * exp(b_i - b_j),        s_ij = scale * (q_i . k_j),
+# and everything else (sum, normalisation by the sum of the gated weights) is as before.
+# Recurrent form: S_t = g_t S_{t-1} + phi(k_t) [v_t, 1]^T,  y_t = S_t^T phi(q_t).
+# --------------------------------------------------------------------------------------
+
+def cum_log_gates(log_g) -> np.ndarray:
+    """b_i = sum_{t <= i} log g_t."""
+    return np.cumsum(np.asarray(log_g, dtype=F64))
+
+
+def _gate_matrix(b: np.ndarray) -> np.ndarray:
+    """exp(b_i - b_j) for j <= i, 0 above the diagonal."""
+    T = b.shape[0]
+    diff = b[:, None] - b[None, :]
+    mask = np.tril(np.ones((T, T), dtype=bool))
+    return np.where(mask, np.exp(np.where(mask, diff, 0.0)), 0.0)
+
+
+def fwd_quadratic_gated(Q, K, V, log_g, p: int, normalize: bool = True, scale: float = 1.0):
+    """All rows by the definition with gating.  Returns (O [T, v], Z [T])."""
+    Q = np.asarray(Q, dtype=F64); K = np.asarray(K, dtype=F64); V = np.asarray(V, dtype=F64)
+    a = _ipow(scale * (Q @ K.T), p) * _gate_matrix(cum_log_gates(log_g))
+    N = a @ V
+    Z = a.sum(axis=1)
+    return (_safe_div(N, Z[:, None]) if normalize else N), Z
+
+
+def fwd_row_gated(Q, K, V, log_g, i: int, p: int, normalize: bool = True, scale: float = 1.0):
+    """One output row by the definition with gating: (O_i [v], Z_i)."""
+    b = cum_log_gates(log_g[: i + 1])
+    q = np.asarray(Q[i], dtype=F64)
+    Kc = np.asarray(K[: i + 1], dtype=F64)
+    Vc = np.asarray(V[: i + 1], dtype=F64)
+    a = _ipow(scale * (Kc @ q), p) * np.exp(b[i] - b)
+    N = a @ Vc
+    Z = a.sum()
+    if normalize:
+        return (N / Z if Z != 0.0 else np.zeros_like(N)), Z
+    return N, Z
+
+
+def bwd_quadratic_gated(Q, K, V, log_g, G, p: int, normalize: bool = True, scale: float = 1.0):
+    """Gradient of L = sum_i G_i . O_i with respect to Q, K, V and the log-gates, straight from
+    the definition.  With e_ij = dL/da_ij:  a_ij depends on b_i with derivative a_ij and on b_j
+    with derivative -a_ij, so  dL/db_i = sum_{j<=i} e_ij a_ij - sum_{i'>=i} e_i'i a_i'i,  and
+    b_i = sum_{t<=i} l_t gives  dL/dl_t = sum_{i>=t} dL/db_i.  Returns (dQ, dK, dV, dlog_g)."""
+    Q = np.asarray(Q, dtype=F64); K = np.asarray(K, dtype=F64); V = np.asarray(V, dtype=F64)
+    O, Z = fwd_quadratic_gated(Q, K, V, log_g, p, normalize, scale)
+    Ghat, gz = _grad_row_terms(G, O, Z, normalize)
+    gate = _gate_matrix(cum_log_gates(log_g))
+    s = scale * (Q @ K.T)
+    a = _ipow(s, p) * gate                               # a_ij, j <= i
+    e = Ghat @ V.T + gz[:, None]                         # dL/da_ij
+    t = p * _ipow(s, p - 1) * gate * e                   # dL/ds_ij
+    dQ = scale * (t @ K)
+    dK = scale * (t.T @ Q)
+    dV = a.T @ Ghat
+    ea = e * a
+    db = ea.sum(axis=1) - ea.sum(axis=0)
+    dlog_g = np.cumsum(db[::-1])[::-1].copy()
+    return dQ, dK, dV, dlog_g
+
+
+def fwd_recurrent_gated(Q, K, V, log_g, p: int, normalize: bool = True, scale: float = 1.0):
+    """Gated recurrent form: S_t = g_t S_{t-1} + phi(k_t) [v_t, 1]^T,  y_t = S_t^T phi(scale q_t)."""
+    Q = np.asarray(Q, dtype=F64); K = np.asarray(K, dtype=F64); V = np.asarray(V, dtype=F64)
+    g = np.exp(np.asarray(log_g, dtype=F64))
+    T, d = Q.shape
+    v = V.shape[1]
+    S = np.zeros((dim_spow(d, p), v + 1), dtype=F64)
+    O = np.zeros((T, v), dtype=F64)
+    Z = np.zeros(T, dtype=F64)
+    for i in range(T):
+        S = g[i] * S + np.outer(spow(K[i], p), np.append(V[i], 1.0))
+        y = spow(scale * Q[i], p) @ S
+        Z[i] = y[v]
+        O[i] = (y[:v] / y[v] if y[v] != 0.0 else 0.0) if normalize else y[:v]
+    return O, Z
+
+
+def _chunk_gate_factors(b: np.ndarray, lo: int, hi: int):
+    """For the chunk [lo, hi): the decay of each query since the chunk's start, exp(b_i - B),
+    B = b_{lo-1} (0 for the first chunk); of each key until the chunk's end, exp(b_{hi-1} - b_j);
+    and across the whole chunk, exp(b_{hi-1} - B).  All are <= 1 for log-gates <= 0."""
+    B = b[lo - 1] if lo > 0 else 0.0
+    return np.exp(b[lo:hi] - B), np.exp(b[hi - 1] - b[lo:hi]), math.exp(b[hi - 1] - B)
+
+
+def fwd_chunked_gated(Q, K, V, log_g, p: int, chunk: int, normalize: bool = True, scale: float = 1.0):
+    """Chunked form with gating: the state entering a chunk is the gated sum of all earlier
+    keys as seen from the chunk's start; a query i of the chunk sees it decayed by
+    exp(b_i - B); the chunk's update weighs key j by its decay until the chunk's end, and the
+    state is multiplied by the decay across the chunk before the update is added (App. E.2,
+    E.3).  Pairs inside a chunk use the attention form with exp(b_i - b_j).  Returns (O, Z)."""
+    Q = np.asarray(Q, dtype=F64); K = np.asarray(K, dtype=F64); V = np.asarray(V, dtype=F64)
+    T, d = Q.shape
+    v = V.shape[1]
+    b = cum_log_gates(log_g)
+    Vp = np.concatenate([V, np.ones((T, 1), dtype=F64)], axis=1)
+    S = np.zeros((dim_spow(d, p), v + 1), dtype=F64)
+    O = np.zeros((T, v), dtype=F64)
+    Z = np.zeros(T, dtype=F64)
+    for lo in range(0, T, chunk):
+        hi = min(lo + chunk, T)
+        qf, kf, lam = _chunk_gate_factors(b, lo, hi)
+        Qc, Kc, Vc = Q[lo:hi] * scale, K[lo:hi], Vp[lo:hi]
+        inter = qf[:, None] * (spow(Qc, p) @ S)
+        intra = (_ipow(Qc @ Kc.T, p) * _gate_matrix(b[lo:hi])) @ Vc
+        tot = inter + intra
+        Z[lo:hi] = tot[:, v]
+        O[lo:hi] = _safe_div(tot[:, :v], tot[:, v:v + 1]) if normalize else tot[:, :v]
+        S = lam * S + spow(Kc, p).T @ (kf[:, None] * Vc)
+    return O, Z
+
+
+def bwd_chunked_gated(Q, K, V, log_g, G, p: int, chunk: int, normalize: bool = True, scale: float = 1.0):
+    """Backward of the gated chunked form (derived).  Mirrors bwd_chunked with the factors of
+    fwd_chunked_gated; the reverse sweep carries R_m, the gradient with respect to the state
+    leaving chunk m, discounted the same way.  The gradient of the log-gates is assembled from
+    the row and column sums of e_ij a_ij, which the sweeps provide as
+    q_i . dq_i / p  and  k_j . dk_j / p  (a_ij is homogeneous of degree p in q_i and in k_j).
+    Returns (dQ, dK, dV, dlog_g)."""
+    Q = np.asarray(Q, dtype=F64); K = np.asarray(K, dtype=F64); V = np.asarray(V, dtype=F64)
+    T, d = Q.shape
+    v = V.shape[1]
+    D = dim_spow(d, p)
+    b = cum_log_gates(log_g)
+    O, Z = fwd_chunked_gated(Q, K, V, log_g, p, chunk, normalize, scale)
+    Ghat, gz = _grad_row_terms(G, O, Z, normalize)
+    Gp = np.concatenate([Ghat, gz[:, None]], axis=1)
+    Vp = np.concatenate([V, np.ones((T, 1), dtype=F64)], axis=1)
+    Qs = Q * scale
+    dQs = np.zeros((T, d), dtype=F64)
+    dK = np.zeros((T, d), dtype=F64)
+    dVp = np.zeros((T, v + 1), dtype=F64)
+    bounds = [(lo, min(lo + chunk, T)) for lo in range(0, T, chunk)]
+    S = np.zeros((D, v + 1), dtype=F64)
+    for lo, hi in bounds:
+        qf, kf, lam = _chunk_gate_factors(b, lo, hi)
+        Qc, Kc, Vc, Gc = Qs[lo:hi], K[lo:hi], Vp[lo:hi], Gp[lo:hi]
+        gate = _gate_matrix(b[lo:hi])
+        s = Qc @ Kc.T
+        e = Gc @ Vc.T
+        t = p * _ipow(s, p - 1) * gate * e
+        dQs[lo:hi] += t @ Kc
+        dK[lo:hi] += t.T @ Qc
+        dVp[lo:hi] += (_ipow(s, p) * gate).T @ Gc
+        dQs[lo:hi] += qf[:, None] * spow_jacobian_transpose_apply(Qc, Gc @ S.T, p)
+        S = lam * S + spow(Kc, p).T @ (kf[:, None] * Vc)
+    R = np.zeros((D, v + 1), dtype=F64)
+    for lo, hi in reversed(bounds):
+        qf, kf, lam = _chunk_gate_factors(b, lo, hi)
+        Qc, Kc, Vc, Gc = Qs[lo:hi], K[lo:hi], Vp[lo:hi], Gp[lo:hi]
+        dVp[lo:hi] += kf[:, None] * (spow(Kc, p) @ R)
+        dK[lo:hi] += kf[:, None] * spow_jacobian_transpose_apply(Kc, Vc @ R.T, p)
+        R = lam * R + spow(Qc, p).T @ (qf[:, None] * Gc)
+    db = ((Qs * dQs).sum(axis=1) - (K * dK).sum(axis=1)) / p
+    dlog_g = np.cumsum(db[::-1])[::-1].copy()
+    return dQs * scale, dK, dVp[:, :v], dlog_g
+
+
+# --------------------------------------------------------------------------------------
 # [B, H, T, d] wrappers
 # --------------------------------------------------------------------------------------
 
-def fwd_bhtd(Q, K, V, p, chunk=None, normalize=True, scale=1.0):
-    """Forward on [B,H,T,d] arrays; ``chunk=None`` uses the attention form."""
+def fwd_bhtd(Q, K, V, p, chunk=None, normalize=True, scale=1.0, log_g=None):
+    """Forward on [B,H,T,d] arrays; ``chunk=None`` uses the attention form; ``log_g`` [B,H,T]
+    switches gating on."""
     B, H, T, _ = Q.shape
     O = np.zeros(V.shape, dtype=F64)
     Z = np.zeros((B, H, T), dtype=F64)
     for b in range(B):
         for h in range(H):
-            if chunk is None:
+            if log_g is not None:
+                if chunk is None:
+                    O[b, h], Z[b, h] = fwd_quadratic_gated(Q[b, h], K[b, h], V[b, h], log_g[b, h], p, normalize, scale)
+                else:
+                    O[b, h], Z[b, h] = fwd_chunked_gated(Q[b, h], K[b, h], V[b, h], log_g[b, h], p, chunk, normalize, scale)
+            elif chunk is None:
                 O[b, h], Z[b, h] = fwd_quadratic(Q[b, h], K[b, h], V[b, h], p, normalize, scale)
             else:
                 O[b, h], Z[b, h] = fwd_chunked(Q[b, h], K[b, h], V[b, h], p, chunk, normalize, scale)
     return O, Z
 
 
-def bwd_bhtd(Q, K, V, G, p, chunk=None, normalize=True, scale=1.0):
-    """Backward on [B,H,T,d] arrays; ``chunk=None`` uses the attention form."""
+def bwd_bhtd(Q, K, V, G, p, chunk=None, normalize=True, scale=1.0, log_g=None):
+    """Backward on [B,H,T,d] arrays; ``chunk=None`` uses the attention form.  With ``log_g``
+    [B,H,T] returns (dQ, dK, dV, dlog_g), else (dQ, dK, dV)."""
     B, H = Q.shape[:2]
     dQ = np.zeros(Q.shape, dtype=F64); dK = np.zeros(K.shape, dtype=F64); dV = np.zeros(V.shape, dtype=F64)
+    if log_g is not None:
+        dL = np.zeros(log_g.shape, dtype=F64)
+        for b in range(B):
+            for h in range(H):
+                if chunk is None:
+                    r = bwd_quadratic_gated(Q[b, h], K[b, h], V[b, h], log_g[b, h], G[b, h], p, normalize, scale)
+                else:
+                    r = bwd_chunked_gated(Q[b, h], K[b, h], V[b, h], log_g[b, h], G[b, h], p, chunk, normalize, scale)
+                dQ[b, h], dK[b, h], dV[b, h], dL[b, h] = r
+        return dQ, dK, dV, dL
     for b in range(B):
         for h in range(H):
             if chunk is None:
