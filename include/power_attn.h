@@ -69,6 +69,13 @@ typedef struct {
                            instead of rebuilding.  Both calls then need
                            power_attn_workspace_bytes(prob, 1) bytes.  A kernel family may ignore
                            the hint and rebuild. */
+    int   gated;        /* 0: the layer above (power_attn_fwd / power_attn_bwd).  1: gated
+                           (power_attn_fwd_gated / power_attn_bwd_gated): with one log-gate
+                           log g_t <= 0 per batch, head and timestep (Sec. 2 "Gating"; the decay of
+                           App. E.2 / E.3 at timestep granularity) and b_i = sum_{t<=i} log g_t, the
+                           pair (i, j) is weighted by the gates of the steps j+1 .. i:
+                               a_ij = s_ij^p exp(b_i - b_j),
+                           N_i = sum_j a_ij v_j, Z_i = sum_j a_ij. */
 } pa_problem;
 
 /* Bytes of device scratch the calls below need for `prob` (0 on an invalid problem).
@@ -95,6 +102,22 @@ pa_status power_attn_bwd(const pa_problem* prob,
                          const void* O, const float* Z, const void* dO,
                          void* dQ, void* dK, void* dV,
                          void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Gated layer (prob->gated == 1).  log_g: DEVICE float32 [B,H,T], values <= 0 (a positive
+ * value is a growth factor: accepted, but the chunked evaluation may then overflow).  The
+ * backward pass also writes dlog_g [B,H,T] float32 = dL/dlog g_t (dlog_g of the first timestep
+ * is 0: no pair straddles it).  Everything else as in the un-gated calls; the un-gated calls
+ * refuse a gated problem and vice versa (PA_ERR_INVALID_ARG). */
+pa_status power_attn_fwd_gated(const pa_problem* prob,
+                               const void* Q, const void* K, const void* V, const float* log_g,
+                               void* O, float* Z,
+                               void* workspace, size_t workspace_bytes, void* hip_stream);
+
+pa_status power_attn_bwd_gated(const pa_problem* prob,
+                               const void* Q, const void* K, const void* V, const float* log_g,
+                               const void* O, const float* Z, const void* dO,
+                               void* dQ, void* dK, void* dV, float* dlog_g,
+                               void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Expanded state rows the chosen kernel family keeps per head for `prob`: C(d+p-1, p) for
  * the generic family (Lemma 4.2), C(d/d_tile+p-1, p) * d_tile^p for the tiled one

@@ -22,6 +22,8 @@ EXPORTED_SYMBOLS = (
     "power_attn_supported",
     "power_attn_fwd",
     "power_attn_bwd",
+    "power_attn_fwd_gated",
+    "power_attn_bwd_gated",
     "power_attn_state_rows",
     "power_attn_status_string",
     "power_attn_last_hip_error",
@@ -38,7 +40,7 @@ class PaProblem(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int), ("H", ctypes.c_int), ("T", ctypes.c_int), ("d", ctypes.c_int),
                 ("v", ctypes.c_int), ("p", ctypes.c_int), ("chunk", ctypes.c_int), ("normalize", ctypes.c_int),
                 ("scale", ctypes.c_float), ("dtype", ctypes.c_int), ("impl", ctypes.c_int),
-                ("keep_state", ctypes.c_int)]
+                ("keep_state", ctypes.c_int), ("gated", ctypes.c_int)]
 
 
 class PaKernelTime(ctypes.Structure):
@@ -74,6 +76,10 @@ def load_library():
     lib.power_attn_fwd.argtypes = [P, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.power_attn_bwd.restype = ctypes.c_int
     lib.power_attn_bwd.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.power_attn_fwd_gated.restype = ctypes.c_int
+    lib.power_attn_fwd_gated.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.power_attn_bwd_gated.restype = ctypes.c_int
+    lib.power_attn_bwd_gated.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.power_attn_status_string.restype = ctypes.c_char_p
     lib.power_attn_status_string.argtypes = [ctypes.c_int]
     lib.power_attn_last_hip_error.restype = ctypes.c_char_p
@@ -93,12 +99,13 @@ def _check(lib, status: int, what: str):
 
 
 def make_problem(B, H, T, d, v, p, chunk, normalize=True, scale=1.0, dtype="bf16", impl="auto",
-                 keep_state=False) -> PaProblem:
+                 keep_state=False, gated=False) -> PaProblem:
     return PaProblem(B, H, T, d, v, p, chunk, int(bool(normalize)), float(scale),
-                     PA_DTYPE_BF16 if dtype == "bf16" else PA_DTYPE_F32, _IMPL[impl], int(bool(keep_state)))
+                     PA_DTYPE_BF16 if dtype == "bf16" else PA_DTYPE_F32, _IMPL[impl], int(bool(keep_state)),
+                     int(bool(gated)))
 
 
-def _problem_of(Q, V, p, chunk, normalize, scale, impl, keep_state=False) -> PaProblem:
+def _problem_of(Q, V, p, chunk, normalize, scale, impl, keep_state=False, gated=False) -> PaProblem:
     import torch
     if Q.dim() != 4 or V.dim() != 4:
         raise PowerAttnError("tensors must be [B, H, T, d]")
@@ -109,7 +116,7 @@ def _problem_of(Q, V, p, chunk, normalize, scale, impl, keep_state=False) -> PaP
     else:
         raise PowerAttnError(f"unsupported dtype {Q.dtype}")
     B, H, T, d = Q.shape
-    return make_problem(B, H, T, d, V.shape[3], p, chunk, normalize, scale, dtype, impl, keep_state)
+    return make_problem(B, H, T, d, V.shape[3], p, chunk, normalize, scale, dtype, impl, keep_state, gated)
 
 
 def _dev_ptr(t, like=None, name="tensor"):
@@ -145,16 +152,23 @@ def _workspace(lib, prob, for_backward, workspace, device):
     return workspace, need
 
 
+def _gate_ptr(log_g, Q, name):
+    import torch
+    if not log_g.is_cuda or not log_g.is_contiguous() or log_g.dtype != torch.float32 or tuple(log_g.shape) != tuple(Q.shape[:3]):
+        raise PowerAttnError(f"{name} must be a contiguous float32 [B, H, T] tensor on the GPU")
+    return ctypes.c_void_p(log_g.data_ptr())
+
+
 def power_attn_fwd(Q, K, V, p: int, chunk: int, normalize: bool = True, scale: float = 1.0, impl: str = "auto",
-                   workspace=None, out=None, out_z=None, keep_state: bool = False):
+                   workspace=None, out=None, out_z=None, keep_state: bool = False, log_g=None):
     """Forward pass on the current stream.  Returns (O, Z): O like V, Z float32 [B, H, T].
     keep_state=True needs a caller-provided workspace that is then handed, untouched, to
-    power_attn_bwd(..., keep_state=True)."""
+    power_attn_bwd(..., keep_state=True).  log_g (float32 [B, H, T], <= 0) switches gating on."""
     import torch
     lib = load_library()
     for t, name in ((Q, "Q"), (K, "K"), (V, "V")):
         _dev_ptr(t, None, name)
-    prob = _problem_of(Q, V, p, chunk, normalize, scale, impl, keep_state)
+    prob = _problem_of(Q, V, p, chunk, normalize, scale, impl, keep_state, log_g is not None)
     if keep_state and workspace is None:
         raise PowerAttnError("keep_state=True needs a workspace that outlives the call")
     _check(lib, lib.power_attn_supported(ctypes.byref(prob), 0), "power_attn_fwd")
@@ -162,21 +176,28 @@ def power_attn_fwd(Q, K, V, p: int, chunk: int, normalize: bool = True, scale: f
         O = torch.empty_like(V) if out is None else out
         Z = torch.empty(Q.shape[:3], dtype=torch.float32, device=Q.device) if out_z is None else out_z
         workspace, need = _workspace(lib, prob, False, workspace, Q.device)
-        st = lib.power_attn_fwd(ctypes.byref(prob), _dev_ptr(Q, name="Q"), _dev_ptr(K, Q, "K"), _dev_ptr(V, Q, "V"),
-                                _dev_ptr(O, Q, "O"), ctypes.c_void_p(Z.data_ptr()),
-                                ctypes.c_void_p(workspace.data_ptr()), need, _stream())
+        if log_g is None:
+            st = lib.power_attn_fwd(ctypes.byref(prob), _dev_ptr(Q, name="Q"), _dev_ptr(K, Q, "K"), _dev_ptr(V, Q, "V"),
+                                    _dev_ptr(O, Q, "O"), ctypes.c_void_p(Z.data_ptr()),
+                                    ctypes.c_void_p(workspace.data_ptr()), need, _stream())
+        else:
+            st = lib.power_attn_fwd_gated(ctypes.byref(prob), _dev_ptr(Q, name="Q"), _dev_ptr(K, Q, "K"),
+                                          _dev_ptr(V, Q, "V"), _gate_ptr(log_g, Q, "log_g"), _dev_ptr(O, Q, "O"),
+                                          ctypes.c_void_p(Z.data_ptr()), ctypes.c_void_p(workspace.data_ptr()), need,
+                                          _stream())
     _check(lib, st, "power_attn_fwd")
     return O, Z
 
 
 def power_attn_bwd(Q, K, V, O, Z, dO, p: int, chunk: int, normalize: bool = True, scale: float = 1.0,
-                   impl: str = "auto", workspace=None, out=None, keep_state: bool = False):
-    """Backward pass on the current stream.  Returns (dQ, dK, dV)."""
+                   impl: str = "auto", workspace=None, out=None, keep_state: bool = False, log_g=None):
+    """Backward pass on the current stream.  Returns (dQ, dK, dV), or (dQ, dK, dV, dlog_g) when
+    log_g is given."""
     import torch
     lib = load_library()
     for t, name in ((Q, "Q"), (K, "K"), (V, "V"), (dO, "dO")):
         _dev_ptr(t, None, name)
-    prob = _problem_of(Q, V, p, chunk, normalize, scale, impl, keep_state)
+    prob = _problem_of(Q, V, p, chunk, normalize, scale, impl, keep_state, log_g is not None)
     if keep_state and workspace is None:
         raise PowerAttnError("keep_state=True needs the workspace the forward pass used")
     _check(lib, lib.power_attn_supported(ctypes.byref(prob), 1), "power_attn_bwd")
@@ -188,10 +209,20 @@ def power_attn_bwd(Q, K, V, O, Z, dO, p: int, chunk: int, normalize: bool = True
         workspace, need = _workspace(lib, prob, True, workspace, Q.device)
         o_ptr = _dev_ptr(O, Q, "O") if O is not None else ctypes.c_void_p(0)
         z_ptr = ctypes.c_void_p(Z.data_ptr()) if Z is not None else ctypes.c_void_p(0)
-        st = lib.power_attn_bwd(ctypes.byref(prob), _dev_ptr(Q, name="Q"), _dev_ptr(K, Q, "K"), _dev_ptr(V, Q, "V"),
-                                o_ptr, z_ptr, _dev_ptr(dO, Q, "dO"), _dev_ptr(dQ, Q, "dQ"), _dev_ptr(dK, Q, "dK"),
-                                _dev_ptr(dV, Q, "dV"), ctypes.c_void_p(workspace.data_ptr()), need, _stream())
+        if log_g is None:
+            st = lib.power_attn_bwd(ctypes.byref(prob), _dev_ptr(Q, name="Q"), _dev_ptr(K, Q, "K"), _dev_ptr(V, Q, "V"),
+                                    o_ptr, z_ptr, _dev_ptr(dO, Q, "dO"), _dev_ptr(dQ, Q, "dQ"), _dev_ptr(dK, Q, "dK"),
+                                    _dev_ptr(dV, Q, "dV"), ctypes.c_void_p(workspace.data_ptr()), need, _stream())
+        else:
+            dlog_g = torch.empty(Q.shape[:3], dtype=torch.float32, device=Q.device)
+            st = lib.power_attn_bwd_gated(ctypes.byref(prob), _dev_ptr(Q, name="Q"), _dev_ptr(K, Q, "K"),
+                                          _dev_ptr(V, Q, "V"), _gate_ptr(log_g, Q, "log_g"), o_ptr, z_ptr,
+                                          _dev_ptr(dO, Q, "dO"), _dev_ptr(dQ, Q, "dQ"), _dev_ptr(dK, Q, "dK"),
+                                          _dev_ptr(dV, Q, "dV"), ctypes.c_void_p(dlog_g.data_ptr()),
+                                          ctypes.c_void_p(workspace.data_ptr()), need, _stream())
     _check(lib, st, "power_attn_bwd")
+    if log_g is not None:
+        return dQ, dK, dV, dlog_g
     return dQ, dK, dV
 
 

@@ -56,12 +56,30 @@ void note_hip_error(hipError_t e, const char* where);
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // ---- kernel families ------------------------------------------------------------------
+// Per-token and per-chunk decay factors derived from the log-gates (all null when the problem
+// is not gated).  With bl_i the sum of the log-gates from the start of token i's chunk up to i:
+//   bl    [BH][T]       bl_i; a pair inside a chunk carries exp(bl_i - bl_j)
+//   qfac  [BH][T]       exp(bl_i): decay of query i since the start of its chunk
+//   kfac  [BH][T]       exp(bl_end - bl_j): decay of key j until the end of its chunk
+//   lam   [BH][T/chunk] exp(bl_end): decay across the whole chunk
+//   db    [BH][T]       scratch of the backward pass: dL/db_i
+struct GateBuf {
+    float *bl = nullptr, *qfac = nullptr, *kfac = nullptr, *lam = nullptr, *db = nullptr;
+};
+
 struct Ctx {
     pa_problem prob;
     hipStream_t stream;
     char* ws;
     size_t ws_bytes;
+    GateBuf gate;
 };
+
+// gating (family-independent kernels)
+size_t gate_workspace_bytes(const pa_problem& pr, bool backward);
+GateBuf gate_buffers(const pa_problem& pr, bool backward, char* base);
+pa_status gate_prepare(const Ctx& c, const float* log_g);
+pa_status gate_gradient(const Ctx& c, const void* Q, const void* K, const void* dQ, const void* dK, float* dlog_g);
 
 // generic (vector-ALU, float32) family
 size_t generic_workspace_bytes(const pa_problem& pr, bool backward);

@@ -1,0 +1,139 @@
+// Gating (arXiv 2507.04239 Sec. 2 "Gating"; gated update-state of App. E.2, discounted
+// cumulative sum of App. E.3): the kernels every kernel family shares.  The paper states the
+// operation at chunk granularity; the per-timestep definition behind it is
+//     a_ij = s_ij^p exp(b_i - b_j),   b_i = sum_{t<=i} log g_t,   j <= i.
+// In the chunked form only sums of log-gates inside one chunk are ever needed (every factor is
+// then a decay <= 1): see GateBuf in common.hpp.  The gradient of the log-gates follows from the
+// homogeneity of the scores: dL/db_i = (q_i . dq_i - k_i . dk_i) / p, dL/dlog g_t = sum_{i>=t} dL/db_i.
+#include "common.hpp"
+
+namespace pa {
+namespace {
+
+constexpr int GT = 256;
+
+// One workgroup per (chunk, head): inclusive running sum of the chunk's log-gates, then the factors.
+__global__ __launch_bounds__(GT) void k_gate_prep(const float* __restrict__ log_g, float* __restrict__ bl,
+                                                  float* __restrict__ qfac, float* __restrict__ kfac,
+                                                  float* __restrict__ lam, int T, int chunk) {
+    __shared__ float part[GT];
+    const int n = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x;
+    const size_t base = (size_t)bh * T + (size_t)n * chunk;
+    const int per = (chunk + GT - 1) / GT;        // consecutive tokens per thread
+    const int lo = min(tid * per, chunk), hi = min(lo + per, chunk);
+    float s = 0.f;
+    for (int i = lo; i < hi; ++i) s += log_g[base + i];
+    part[tid] = s;
+    __syncthreads();
+    for (int off = 1; off < GT; off <<= 1) {      // inclusive scan of the per-thread sums
+        float add = tid >= off ? part[tid - off] : 0.f;
+        __syncthreads();
+        part[tid] += add;
+        __syncthreads();
+    }
+    const float total = part[GT - 1];
+    float run = tid > 0 ? part[tid - 1] : 0.f;
+    for (int i = lo; i < hi; ++i) {
+        run += log_g[base + i];
+        bl[base + i] = run;
+        qfac[base + i] = __expf(run);
+        kfac[base + i] = __expf(total - run);
+    }
+    if (tid == 0) lam[(size_t)bh * (T / chunk) + n] = __expf(total);
+}
+
+// dL/db_i = (q_i . dq_i - k_i . dk_i) / p; 16 lanes per row
+template <typename T>
+__global__ __launch_bounds__(256) void k_gate_db(const T* __restrict__ Q, const T* __restrict__ dQ, const T* __restrict__ K,
+                                                 const T* __restrict__ dK, float* __restrict__ db, long long rows, int d,
+                                                 float inv_p) {
+    const long long row = (long long)blockIdx.x * 16 + (threadIdx.x >> 4);
+    const int c = threadIdx.x & 15;
+    float acc = 0.f;
+    if (row < rows) {
+        const size_t o = (size_t)row * d;
+        for (int a = c; a < d; a += 16)
+            acc += io<T>::ld(Q + o + a) * io<T>::ld(dQ + o + a) - io<T>::ld(K + o + a) * io<T>::ld(dK + o + a);
+    }
+    acc += __shfl_xor(acc, 1);
+    acc += __shfl_xor(acc, 2);
+    acc += __shfl_xor(acc, 4);
+    acc += __shfl_xor(acc, 8);
+    if (row < rows && c == 0) db[row] = acc * inv_p;
+}
+
+// dlog_g[t] = sum_{i >= t} db[i] per head: one workgroup per head, each thread a run of tokens
+__global__ __launch_bounds__(1024) void k_gate_revsum(const float* __restrict__ db, float* __restrict__ dlog_g, int T) {
+    __shared__ float part[1024];
+    const int bh = blockIdx.x, tid = threadIdx.x;
+    const size_t base = (size_t)bh * T;
+    const int per = (T + 1023) / 1024;
+    const int lo = min(tid * per, T), hi = min(lo + per, T);
+    float s = 0.f;
+    for (int i = lo; i < hi; ++i) s += db[base + i];
+    part[tid] = s;
+    __syncthreads();
+    for (int off = 1; off < 1024; off <<= 1) {    // inclusive suffix scan of the per-thread sums
+        float add = tid + off < 1024 ? part[tid + off] : 0.f;
+        __syncthreads();
+        part[tid] += add;
+        __syncthreads();
+    }
+    float run = tid + 1 < 1024 ? part[tid + 1] : 0.f;   // everything after this thread's run
+    for (int i = hi - 1; i >= lo; --i) {
+        run += db[base + i];
+        dlog_g[base + i] = run;
+    }
+}
+
+}  // namespace
+
+size_t gate_workspace_bytes(const pa_problem& pr, bool backward) {
+    if (!pr.gated) return 0;
+    const size_t BH = (size_t)pr.B * pr.H;
+    const size_t tok = align_up(BH * pr.T * sizeof(float), 256);
+    return (backward ? 4 : 3) * tok + align_up(BH * (pr.T / pr.chunk) * sizeof(float), 256);
+}
+
+GateBuf gate_buffers(const pa_problem& pr, bool backward, char* base) {
+    GateBuf g;
+    if (!pr.gated) return g;
+    const size_t BH = (size_t)pr.B * pr.H;
+    const size_t tok = align_up(BH * pr.T * sizeof(float), 256);
+    g.bl = (float*)base;
+    g.qfac = (float*)(base + tok);
+    g.kfac = (float*)(base + 2 * tok);
+    g.lam = (float*)(base + 3 * tok);
+    if (backward) g.db = (float*)(base + 3 * tok + align_up(BH * (pr.T / pr.chunk) * sizeof(float), 256));
+    return g;
+}
+
+pa_status gate_prepare(const Ctx& c, const float* log_g) {
+    const pa_problem& pr = c.prob;
+    LaunchScope ls("gate_prep", c.stream);
+    hipLaunchKernelGGL(k_gate_prep, dim3(pr.T / pr.chunk, pr.B * pr.H), dim3(GT), 0, c.stream, log_g, c.gate.bl, c.gate.qfac,
+                       c.gate.kfac, c.gate.lam, pr.T, pr.chunk);
+    return launch_ok() ? PA_OK : PA_ERR_HIP;
+}
+
+pa_status gate_gradient(const Ctx& c, const void* Q, const void* K, const void* dQ, const void* dK, float* dlog_g) {
+    const pa_problem& pr = c.prob;
+    const long long rows = (long long)pr.B * pr.H * pr.T;
+    {
+        LaunchScope ls("gate_db", c.stream);
+        if (pr.dtype == PA_DTYPE_F32)
+            hipLaunchKernelGGL((k_gate_db<float>), dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, c.stream, (const float*)Q,
+                               (const float*)dQ, (const float*)K, (const float*)dK, c.gate.db, rows, pr.d, 1.f / pr.p);
+        else
+            hipLaunchKernelGGL((k_gate_db<bf16_t>), dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, c.stream, (const bf16_t*)Q,
+                               (const bf16_t*)dQ, (const bf16_t*)K, (const bf16_t*)dK, c.gate.db, rows, pr.d, 1.f / pr.p);
+    }
+    if (!launch_ok()) return PA_ERR_HIP;
+    {
+        LaunchScope ls("gate_revsum", c.stream);
+        hipLaunchKernelGGL(k_gate_revsum, dim3(pr.B * pr.H), dim3(1024), 0, c.stream, c.gate.db, dlog_g, pr.T);
+    }
+    return launch_ok() ? PA_OK : PA_ERR_HIP;
+}
+
+}  // namespace pa

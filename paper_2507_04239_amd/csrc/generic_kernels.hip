@@ -148,19 +148,23 @@ __global__ void k_prep_g(const T* __restrict__ dO, const T* __restrict__ O, cons
     out[v] = -delta * inv;
 }
 
-// ---- fused update-state + cumulative sum over chunks (App. E.2 + E.3, no gating) ---------
+// ---- fused update-state + cumulative sum over chunks (App. E.2 + E.3) ---------------------
 //
 // St[bh][n] = sum over the chunks before n (reverse: after n) of  m_r psi(xscale * X_j)_r Yp_j^T.
 // One thread owns (row r, columns x = xg, xg+4, ...) and walks the chunks in order, writing
-// the running sum before it adds the chunk.
+// the running sum before it adds the chunk.  Gated (fac, lam non-null): token j enters with the
+// weight fac_j and the running sum is multiplied by lam_n before chunk n is added, i.e. the
+// gated update-state S <- S * gamma + phi(K)^T V and the discounted cumulative sum.
 template <typename T, int P, int KX>
 __global__ __launch_bounds__(NT) void k_scan(const T* __restrict__ X, const float* __restrict__ Yp,
                                              const uchar4* __restrict__ idx, const float* __restrict__ mult,
                                              float* __restrict__ St, int Tlen, int d, int VP, int chunk, long long D,
-                                             float xscale, int reverse) {
+                                             float xscale, int reverse, const float* __restrict__ fac,
+                                             const float* __restrict__ lam) {
     extern __shared__ float smem[];
     float* xs = smem;            // [RT][d]
     float* ys = smem + RT * d;   // [RT][VP]
+    float* fs = ys + RT * VP;    // [RT]      per-token weights (gated)
     const int tid = threadIdx.x;
     const int xg = tid & 3;
     const long long row = (long long)blockIdx.x * (NT / 4) + (tid >> 2);
@@ -189,15 +193,21 @@ __global__ __launch_bounds__(NT) void k_scan(const T* __restrict__ X, const floa
             }
         }
         if (ci == nchunk - 1) break;  // the sum including the last chunk visited is never used
+        if (lam != nullptr) {
+            const float l = lam[(size_t)bh * nchunk + n];
+#pragma unroll
+            for (int k = 0; k < KX; ++k) acc[k] *= l;
+        }
         for (int t0 = 0; t0 < chunk; t0 += RT) {
             const int nt = min(RT, chunk - t0);
             const size_t tok0 = (size_t)n * chunk + t0;
             __syncthreads();
             for (int e = tid; e < nt * d; e += NT) xs[e] = xscale * io<T>::ld(Xb + tok0 * d + e);
             for (int e = tid; e < nt * VP; e += NT) ys[e] = Yb[tok0 * VP + e];
+            for (int e = tid; e < nt; e += NT) fs[e] = fac != nullptr ? fac[(size_t)bh * Tlen + tok0 + e] : 1.f;
             __syncthreads();
             for (int j = 0; j < nt; ++j) {
-                float coef = m * monomial<P>(xs + j * d, ix);
+                float coef = m * fs[j] * monomial<P>(xs + j * d, ix);
                 const float* yr = ys + j * VP;
 #pragma unroll
                 for (int k = 0; k < KX; ++k) {
@@ -215,7 +225,8 @@ __global__ __launch_bounds__(NT) void k_fwd_chunk(const T* __restrict__ Q, const
                                                   const float* __restrict__ Vp, const uchar4* __restrict__ idx,
                                                   const float* __restrict__ St, T* __restrict__ O,
                                                   float* __restrict__ Z, int Tlen, int d, int v, int chunk,
-                                                  long long D, float scale, int normalize) {
+                                                  long long D, float scale, int normalize,
+                                                  const float* __restrict__ bl, const float* __restrict__ qfac) {
     extern __shared__ float smem[];
     const int VP = v + 1;
     const int dq = d + 1;
@@ -223,6 +234,7 @@ __global__ __launch_bounds__(NT) void k_fwd_chunk(const T* __restrict__ Q, const
     float* ks = qs + TOK * dq;            // [RT][d]
     float* ts = ks + RT * d;              // [RT][VP]     state tile or V' tile
     uchar4* ixs = (uchar4*)(ts + RT * VP);  // [RT]
+    float* bls = (float*)(ixs + RT);      // [RT]         log-decay of the keys since the chunk's start (gated)
     const int tid = threadIdx.x;
     const int tok = tid >> 2, xg = tid & 3;
     const int n = blockIdx.x, bh = blockIdx.y;
@@ -262,7 +274,13 @@ __global__ __launch_bounds__(NT) void k_fwd_chunk(const T* __restrict__ Q, const
                     }
                 }
             }
+            if (qfac != nullptr) {   // the state is seen from the chunk's start: decay up to row i
+                const float f = live ? qfac[base_tok + il] : 0.f;
+#pragma unroll
+                for (int k = 0; k < KX; ++k) acc[k] *= f;
+            }
         }
+        const float bli = (bl != nullptr && live) ? bl[base_tok + il] : 0.f;
         // attention form inside the chunk, keys j <= i
         const int jmax = i0 + ntok;  // keys beyond the last row of this pass are masked for everyone
         for (int j0 = 0; j0 < jmax; j0 += RT) {
@@ -270,12 +288,15 @@ __global__ __launch_bounds__(NT) void k_fwd_chunk(const T* __restrict__ Q, const
             __syncthreads();
             for (int e = tid; e < nj * d; e += NT) ks[e] = io<T>::ld(K + (base_tok + j0) * d + e);
             for (int e = tid; e < nj * VP; e += NT) ts[e] = Vp[(base_tok + j0) * VP + e];
+            if (bl != nullptr)
+                for (int e = tid; e < nj; e += NT) bls[e] = bl[base_tok + j0 + e];
             __syncthreads();
             for (int jj = 0; jj < nj; ++jj) {
                 float part = 0.f;
                 for (int a = xg; a < d; a += 4) part += qrow[a] * ks[jj * d + a];
                 float s = quad_sum(part);
                 float w = (j0 + jj <= il) ? ipow<P>(s) : 0.f;
+                if (bl != nullptr && j0 + jj <= il) w *= __expf(bli - bls[jj]);
                 const float* vr = ts + jj * VP;
 #pragma unroll
                 for (int k = 0; k < KX; ++k) {
@@ -310,7 +331,8 @@ __global__ __launch_bounds__(NT) void k_bwd_dq(const T* __restrict__ Q, const T*
                                                const float* __restrict__ Vp, const float* __restrict__ Gp,
                                                const uchar4* __restrict__ idx, const float* __restrict__ St,
                                                T* __restrict__ dQ, int Tlen, int d, int v, int chunk, long long D,
-                                               float scale) {
+                                               float scale, const float* __restrict__ bl,
+                                               const float* __restrict__ qfac) {
     extern __shared__ float smem[];
     const int VP = v + 1;
     const int dq = d + 1;
@@ -319,6 +341,7 @@ __global__ __launch_bounds__(NT) void k_bwd_dq(const T* __restrict__ Q, const T*
     float* ks = dqs + TOK * dq;       // [RT][d]
     float* ts = ks + RT * d;          // [RT][VP]
     uchar4* ixs = (uchar4*)(ts + RT * VP);
+    float* bls = (float*)(ixs + RT);  // [RT]        log-decay of the keys (gated)
     const int tid = threadIdx.x;
     const int tok = tid >> 2, xg = tid & 3;
     const int n = blockIdx.x, bh = blockIdx.y;
@@ -344,6 +367,8 @@ __global__ __launch_bounds__(NT) void k_bwd_dq(const T* __restrict__ Q, const T*
         }
         const float* qrow = qs + (live ? tok : 0) * dq;
         float* dqrow = dqs + tok * dq;
+        const float qf = (qfac != nullptr && live) ? qfac[base_tok + il] : 1.f;
+        const float bli = (bl != nullptr && live) ? bl[base_tok + il] : 0.f;
 
         if (n > 0) {
             for (long long r0 = 0; r0 < D; r0 += RT) {
@@ -360,7 +385,7 @@ __global__ __launch_bounds__(NT) void k_bwd_dq(const T* __restrict__ Q, const T*
                         int x = xg + 4 * k;
                         if (x < VP) part += sr[x] * gp[k];
                     }
-                    const float g = quad_sum(part);  // d loss / d psi(q)_r
+                    const float g = qf * quad_sum(part);  // d loss / d psi(q)_r
                     if (xg < P) {
                         uchar4 ix = ixs[rr];
                         atomicAdd(dqrow + index_at(ix, xg), g * monomial_without<P>(qrow, ix, xg));
@@ -374,6 +399,8 @@ __global__ __launch_bounds__(NT) void k_bwd_dq(const T* __restrict__ Q, const T*
             __syncthreads();
             for (int e = tid; e < nj * d; e += NT) ks[e] = io<T>::ld(K + (base_tok + j0) * d + e);
             for (int e = tid; e < nj * VP; e += NT) ts[e] = Vp[(base_tok + j0) * VP + e];
+            if (bl != nullptr)
+                for (int e = tid; e < nj; e += NT) bls[e] = bl[base_tok + j0 + e];
             __syncthreads();
             for (int jj = 0; jj < nj; ++jj) {
                 float ps = 0.f, pe = 0.f;
@@ -385,7 +412,8 @@ __global__ __launch_bounds__(NT) void k_bwd_dq(const T* __restrict__ Q, const T*
                     if (x < VP) pe += gp[k] * vr[x];
                 }
                 const float s = quad_sum(ps), e = quad_sum(pe);
-                const float t = (j0 + jj <= il) ? (float)P * ipow_m1<P>(s) * e : 0.f;
+                float t = (j0 + jj <= il) ? (float)P * ipow_m1<P>(s) * e : 0.f;
+                if (bl != nullptr && j0 + jj <= il) t *= __expf(bli - bls[jj]);
                 for (int a = xg; a < d; a += 4) dqrow[a] += t * ks[jj * d + a];
             }
         }
@@ -406,7 +434,8 @@ __global__ __launch_bounds__(NT) void k_bwd_dkdv(const T* __restrict__ Q, const 
                                                  const float* __restrict__ Vp, const float* __restrict__ Gp,
                                                  const uchar4* __restrict__ idx, const float* __restrict__ Rt,
                                                  T* __restrict__ dK, T* __restrict__ dV, int Tlen, int d, int v,
-                                                 int chunk, long long D, float scale) {
+                                                 int chunk, long long D, float scale, const float* __restrict__ bl,
+                                                 const float* __restrict__ kfac) {
     extern __shared__ float smem[];
     const int VP = v + 1;
     const int dq = d + 1;
@@ -415,6 +444,7 @@ __global__ __launch_bounds__(NT) void k_bwd_dkdv(const T* __restrict__ Q, const 
     float* qb = dks + TOK * dq;       // [RT][d]     scale * q of the rows i
     float* ts = qb + RT * d;          // [RT][VP]    R' tile or ghat' tile
     uchar4* ixs = (uchar4*)(ts + RT * VP);
+    float* bls = (float*)(ixs + RT);  // [RT]        log-decay of the rows i (gated)
     const int tid = threadIdx.x;
     const int tok = tid >> 2, xg = tid & 3;
     const int n = blockIdx.x, bh = blockIdx.y;
@@ -441,6 +471,8 @@ __global__ __launch_bounds__(NT) void k_bwd_dkdv(const T* __restrict__ Q, const 
         }
         const float* krow = kks + (live ? tok : 0) * dq;
         float* dkrow = dks + tok * dq;
+        const float kf = (kfac != nullptr && live) ? kfac[base_tok + jl] : 1.f;
+        const float blj = (bl != nullptr && live) ? bl[base_tok + jl] : 0.f;
 
         if (n < nchunk - 1) {
             for (long long r0 = 0; r0 < D; r0 += RT) {
@@ -452,7 +484,7 @@ __global__ __launch_bounds__(NT) void k_bwd_dkdv(const T* __restrict__ Q, const 
                 for (int rr = 0; rr < nr; ++rr) {
                     const float* rrow = ts + rr * VP;
                     const uchar4 ix = ixs[rr];
-                    const float coef = monomial<P>(krow, ix);
+                    const float coef = kf * monomial<P>(krow, ix);
                     float part = 0.f;
 #pragma unroll
                     for (int k = 0; k < KX; ++k) {
@@ -463,7 +495,7 @@ __global__ __launch_bounds__(NT) void k_bwd_dkdv(const T* __restrict__ Q, const 
                             part += rv * vp[k];
                         }
                     }
-                    const float g = quad_sum(part);  // d loss / d psi(k)_r
+                    const float g = kf * quad_sum(part);  // d loss / d psi(k)_r
                     if (xg < P) atomicAdd(dkrow + index_at(ix, xg), g * monomial_without<P>(krow, ix, xg));
                 }
             }
@@ -474,6 +506,8 @@ __global__ __launch_bounds__(NT) void k_bwd_dkdv(const T* __restrict__ Q, const 
             __syncthreads();
             for (int e = tid; e < ni * d; e += NT) qb[e] = scale * io<T>::ld(Q + (base_tok + i0) * d + e);
             for (int e = tid; e < ni * VP; e += NT) ts[e] = Gp[(base_tok + i0) * VP + e];
+            if (bl != nullptr)
+                for (int e = tid; e < ni; e += NT) bls[e] = bl[base_tok + i0 + e];
             __syncthreads();
             for (int ii = 0; ii < ni; ++ii) {
                 float ps = 0.f, pe = 0.f;
@@ -486,7 +520,8 @@ __global__ __launch_bounds__(NT) void k_bwd_dkdv(const T* __restrict__ Q, const 
                 }
                 const float s = quad_sum(ps), e = quad_sum(pe);
                 const bool on = (i0 + ii >= jl);
-                const float sm1 = ipow_m1<P>(s);
+                const float gate = (bl != nullptr && on) ? __expf(bls[ii] - blj) : 1.f;
+                const float sm1 = gate * ipow_m1<P>(s);
                 const float t = on ? (float)P * sm1 * e : 0.f;
                 const float w = on ? sm1 * s : 0.f;
                 for (int a = xg; a < d; a += 4) dkrow[a] += t * qb[ii * d + a];
@@ -546,12 +581,12 @@ Layout make_layout(const pa_problem& pr, bool backward) {
     return L;
 }
 
-size_t smem_scan(const pa_problem& pr) { return (size_t)(RT * pr.d + RT * (pr.v + 1)) * sizeof(float); }
+size_t smem_scan(const pa_problem& pr) { return (size_t)(RT * pr.d + RT * (pr.v + 1) + RT) * sizeof(float); }
 size_t smem_fwd(const pa_problem& pr) {
-    return (size_t)(TOK * (pr.d + 1) + RT * pr.d + RT * (pr.v + 1)) * sizeof(float) + RT * sizeof(uchar4);
+    return (size_t)(TOK * (pr.d + 1) + RT * pr.d + RT * (pr.v + 1) + RT) * sizeof(float) + RT * sizeof(uchar4);
 }
 size_t smem_bwd(const pa_problem& pr) {
-    return (size_t)(2 * TOK * (pr.d + 1) + RT * pr.d + RT * (pr.v + 1)) * sizeof(float) + RT * sizeof(uchar4);
+    return (size_t)(2 * TOK * (pr.d + 1) + RT * pr.d + RT * (pr.v + 1) + RT) * sizeof(float) + RT * sizeof(uchar4);
 }
 
 // LDS beyond the default per-kernel limit has to be requested once per kernel
@@ -591,7 +626,8 @@ pa_status run_fwd(const Ctx& c, const Layout& L, const T* Q, const T* K, const T
     {
         LaunchScope ls("generic_state_scan", c.stream);
         hipLaunchKernelGGL((k_scan<T, P, KX>), dim3((unsigned)((L.D + NT / 4 - 1) / (NT / 4)), (unsigned)BH), dim3(NT),
-                           smem_scan(pr), c.stream, K, Vp, idx, mult, St, pr.T, pr.d, L.VP, pr.chunk, L.D, 1.0f, 0);
+                           smem_scan(pr), c.stream, K, Vp, idx, mult, St, pr.T, pr.d, L.VP, pr.chunk, L.D, 1.0f, 0,
+                           (const float*)c.gate.kfac, (const float*)c.gate.lam);
     }
     PA_CHECK_LAUNCH();
     if (only_state) return PA_OK;
@@ -599,7 +635,8 @@ pa_status run_fwd(const Ctx& c, const Layout& L, const T* Q, const T* K, const T
     {
         LaunchScope ls("generic_fwd_chunk", c.stream);
         hipLaunchKernelGGL((k_fwd_chunk<T, P, KX>), dim3(L.nchunk, (unsigned)BH), dim3(NT), smem_fwd(pr), c.stream, Q, K,
-                           Vp, idx, St, O, Z, pr.T, pr.d, pr.v, pr.chunk, L.D, pr.scale, pr.normalize);
+                           Vp, idx, St, O, Z, pr.T, pr.d, pr.v, pr.chunk, L.D, pr.scale, pr.normalize,
+                           (const float*)c.gate.bl, (const float*)c.gate.qfac);
     }
     PA_CHECK_LAUNCH();
     return PA_OK;
@@ -629,20 +666,23 @@ pa_status run_bwd(const Ctx& c, const Layout& L, const T* Q, const T* K, const T
     {
         LaunchScope ls("generic_state_scan_reverse", c.stream);
         hipLaunchKernelGGL((k_scan<T, P, KX>), dim3((unsigned)((L.D + NT / 4 - 1) / (NT / 4)), (unsigned)BH), dim3(NT),
-                           smem_scan(pr), c.stream, Q, Gp, idx, mult, Rt, pr.T, pr.d, L.VP, pr.chunk, L.D, pr.scale, 1);
+                           smem_scan(pr), c.stream, Q, Gp, idx, mult, Rt, pr.T, pr.d, L.VP, pr.chunk, L.D, pr.scale, 1,
+                           (const float*)c.gate.qfac, (const float*)c.gate.lam);
     }
     PA_CHECK_LAUNCH();
     if (!allow_smem(k_bwd_dq<T, P, KX>, smem_bwd(pr)) || !allow_smem(k_bwd_dkdv<T, P, KX>, smem_bwd(pr))) return PA_ERR_HIP;
     {
         LaunchScope ls("generic_bwd_dq", c.stream);
         hipLaunchKernelGGL((k_bwd_dq<T, P, KX>), dim3(L.nchunk, (unsigned)BH), dim3(NT), smem_bwd(pr), c.stream, Q, K, Vp,
-                           Gp, idx, St, dQ, pr.T, pr.d, pr.v, pr.chunk, L.D, pr.scale);
+                           Gp, idx, St, dQ, pr.T, pr.d, pr.v, pr.chunk, L.D, pr.scale, (const float*)c.gate.bl,
+                           (const float*)c.gate.qfac);
     }
     PA_CHECK_LAUNCH();
     {
         LaunchScope ls("generic_bwd_dkdv", c.stream);
         hipLaunchKernelGGL((k_bwd_dkdv<T, P, KX>), dim3(L.nchunk, (unsigned)BH), dim3(NT), smem_bwd(pr), c.stream, Q, K,
-                           Vp, Gp, idx, Rt, dK, dV, pr.T, pr.d, pr.v, pr.chunk, L.D, pr.scale);
+                           Vp, Gp, idx, Rt, dK, dV, pr.T, pr.d, pr.v, pr.chunk, L.D, pr.scale, (const float*)c.gate.bl,
+                           (const float*)c.gate.kfac);
     }
     PA_CHECK_LAUNCH();
     return PA_OK;

@@ -53,6 +53,7 @@ Layout make_layout(const pa_problem& pr, bool backward) {
 pa_status mfma_supported(const pa_problem& pr, bool backward) {
     (void)backward;
     if (pr.dtype != PA_DTYPE_BF16 || pr.p != 2) return PA_ERR_UNSUPPORTED;
+    if (pr.gated) return PA_ERR_UNSUPPORTED;   // gating: generic family only so far
     if (pr.d != DH || pr.v != DH) return PA_ERR_UNSUPPORTED;
     if (pr.chunk % QBLK != 0) return PA_ERR_UNSUPPORTED;
     if ((size_t)pr.B * pr.H > 65535u) return PA_ERR_UNSUPPORTED;

@@ -28,6 +28,7 @@ pa_status validate(const pa_problem* pr) {
     if (pr->dtype != PA_DTYPE_F32 && pr->dtype != PA_DTYPE_BF16) return PA_ERR_INVALID_ARG;
     if (pr->impl != PA_IMPL_AUTO && pr->impl != PA_IMPL_GENERIC && pr->impl != PA_IMPL_MFMA) return PA_ERR_INVALID_ARG;
     if (!(pr->scale == pr->scale) || pr->scale == 0.f) return PA_ERR_INVALID_ARG;
+    if (pr->gated != 0 && pr->gated != 1) return PA_ERR_INVALID_ARG;
     return PA_OK;
 }
 
@@ -45,6 +46,62 @@ int choose(const pa_problem& pr, bool backward, pa_status* why) {
     if (st == PA_OK) return PA_IMPL_GENERIC;
     *why = st;
     return -1;
+}
+
+// workspace of the kernel family, rounded so that the gating buffers can follow it
+size_t family_bytes(int impl, const pa_problem& pr, bool backward) {
+    return align_up(impl == PA_IMPL_MFMA ? mfma_workspace_bytes(pr, backward) : generic_workspace_bytes(pr, backward), 256);
+}
+
+pa_status run_fwd(const pa_problem* prob, const void* Q, const void* K, const void* V, const float* log_g, void* O, float* Z,
+                  void* workspace, size_t workspace_bytes, void* hip_stream, int gated) {
+    pa_status st = validate(prob);
+    if (st != PA_OK) return st;
+    if (prob->gated != gated) return PA_ERR_INVALID_ARG;
+    if (Q == nullptr || K == nullptr || V == nullptr || O == nullptr || (gated && log_g == nullptr)) return PA_ERR_INVALID_ARG;
+    pa_status why = PA_ERR_UNSUPPORTED;
+    int impl = choose(*prob, false, &why);
+    if (impl < 0) return why;
+    const size_t fam = family_bytes(impl, *prob, false);
+    const size_t need = fam + gate_workspace_bytes(*prob, false);
+    if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return PA_ERR_WORKSPACE;
+    if (((uintptr_t)workspace & 255u) != 0) return PA_ERR_WORKSPACE;
+    (void)hipGetLastError();  // errors left behind by earlier, unrelated runtime calls are not ours
+    Ctx c{*prob, (hipStream_t)hip_stream, (char*)workspace, workspace_bytes, gate_buffers(*prob, false, (char*)workspace + fam)};
+    if (gated) {
+        st = gate_prepare(c, log_g);
+        if (st != PA_OK) return st;
+    }
+    return impl == PA_IMPL_MFMA ? mfma_fwd(c, Q, K, V, O, Z) : generic_fwd(c, Q, K, V, O, Z);
+}
+
+pa_status run_bwd(const pa_problem* prob, const void* Q, const void* K, const void* V, const float* log_g, const void* O,
+                  const float* Z, const void* dO, void* dQ, void* dK, void* dV, float* dlog_g, void* workspace,
+                  size_t workspace_bytes, void* hip_stream, int gated) {
+    pa_status st = validate(prob);
+    if (st != PA_OK) return st;
+    if (prob->gated != gated) return PA_ERR_INVALID_ARG;
+    if (Q == nullptr || K == nullptr || V == nullptr || dO == nullptr || dQ == nullptr || dK == nullptr || dV == nullptr)
+        return PA_ERR_INVALID_ARG;
+    if (gated && (log_g == nullptr || dlog_g == nullptr)) return PA_ERR_INVALID_ARG;
+    if (prob->normalize != 0 && (O == nullptr || Z == nullptr)) return PA_ERR_INVALID_ARG;
+    pa_status why = PA_ERR_UNSUPPORTED;
+    int impl = choose(*prob, true, &why);
+    if (impl < 0) return why;
+    const size_t fam = family_bytes(impl, *prob, true);
+    const size_t need = fam + gate_workspace_bytes(*prob, true);
+    if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return PA_ERR_WORKSPACE;
+    if (((uintptr_t)workspace & 255u) != 0) return PA_ERR_WORKSPACE;
+    (void)hipGetLastError();
+    Ctx c{*prob, (hipStream_t)hip_stream, (char*)workspace, workspace_bytes, gate_buffers(*prob, true, (char*)workspace + fam)};
+    if (gated) {
+        // the factors are rebuilt here: the forward pass keeps its own copy only inside its workspace
+        st = gate_prepare(c, log_g);
+        if (st != PA_OK) return st;
+    }
+    st = impl == PA_IMPL_MFMA ? mfma_bwd(c, Q, K, V, O, Z, dO, dQ, dK, dV) : generic_bwd(c, Q, K, V, O, Z, dO, dQ, dK, dV);
+    if (st != PA_OK || !gated) return st;
+    return gate_gradient(c, Q, K, dQ, dK, dlog_g);
 }
 
 }  // namespace
@@ -103,8 +160,7 @@ size_t power_attn_workspace_bytes(const pa_problem* prob, int for_backward) {
     pa_status why;
     int impl = choose(*prob, for_backward != 0, &why);
     if (impl < 0) return 0;
-    return impl == PA_IMPL_MFMA ? mfma_workspace_bytes(*prob, for_backward != 0)
-                                : generic_workspace_bytes(*prob, for_backward != 0);
+    return family_bytes(impl, *prob, for_backward != 0) + gate_workspace_bytes(*prob, for_backward != 0);
 }
 
 long long power_attn_state_rows(const pa_problem* prob) {
@@ -117,38 +173,24 @@ long long power_attn_state_rows(const pa_problem* prob) {
 
 pa_status power_attn_fwd(const pa_problem* prob, const void* Q, const void* K, const void* V, void* O, float* Z,
                          void* workspace, size_t workspace_bytes, void* hip_stream) {
-    pa_status st = validate(prob);
-    if (st != PA_OK) return st;
-    if (Q == nullptr || K == nullptr || V == nullptr || O == nullptr) return PA_ERR_INVALID_ARG;
-    pa_status why = PA_ERR_UNSUPPORTED;
-    int impl = choose(*prob, false, &why);
-    if (impl < 0) return why;
-    size_t need = impl == PA_IMPL_MFMA ? mfma_workspace_bytes(*prob, false) : generic_workspace_bytes(*prob, false);
-    if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return PA_ERR_WORKSPACE;
-    if (((uintptr_t)workspace & 255u) != 0) return PA_ERR_WORKSPACE;
-    (void)hipGetLastError();  // errors left behind by earlier, unrelated runtime calls are not ours
-    Ctx c{*prob, (hipStream_t)hip_stream, (char*)workspace, workspace_bytes};
-    return impl == PA_IMPL_MFMA ? mfma_fwd(c, Q, K, V, O, Z) : generic_fwd(c, Q, K, V, O, Z);
+    return run_fwd(prob, Q, K, V, nullptr, O, Z, workspace, workspace_bytes, hip_stream, 0);
 }
 
 pa_status power_attn_bwd(const pa_problem* prob, const void* Q, const void* K, const void* V, const void* O,
                          const float* Z, const void* dO, void* dQ, void* dK, void* dV, void* workspace,
                          size_t workspace_bytes, void* hip_stream) {
-    pa_status st = validate(prob);
-    if (st != PA_OK) return st;
-    if (Q == nullptr || K == nullptr || V == nullptr || dO == nullptr || dQ == nullptr || dK == nullptr || dV == nullptr)
-        return PA_ERR_INVALID_ARG;
-    if (prob->normalize != 0 && (O == nullptr || Z == nullptr)) return PA_ERR_INVALID_ARG;
-    pa_status why = PA_ERR_UNSUPPORTED;
-    int impl = choose(*prob, true, &why);
-    if (impl < 0) return why;
-    size_t need = impl == PA_IMPL_MFMA ? mfma_workspace_bytes(*prob, true) : generic_workspace_bytes(*prob, true);
-    if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return PA_ERR_WORKSPACE;
-    if (((uintptr_t)workspace & 255u) != 0) return PA_ERR_WORKSPACE;
-    (void)hipGetLastError();
-    Ctx c{*prob, (hipStream_t)hip_stream, (char*)workspace, workspace_bytes};
-    return impl == PA_IMPL_MFMA ? mfma_bwd(c, Q, K, V, O, Z, dO, dQ, dK, dV)
-                                : generic_bwd(c, Q, K, V, O, Z, dO, dQ, dK, dV);
+    return run_bwd(prob, Q, K, V, nullptr, O, Z, dO, dQ, dK, dV, nullptr, workspace, workspace_bytes, hip_stream, 0);
+}
+
+pa_status power_attn_fwd_gated(const pa_problem* prob, const void* Q, const void* K, const void* V, const float* log_g,
+                               void* O, float* Z, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return run_fwd(prob, Q, K, V, log_g, O, Z, workspace, workspace_bytes, hip_stream, 1);
+}
+
+pa_status power_attn_bwd_gated(const pa_problem* prob, const void* Q, const void* K, const void* V, const float* log_g,
+                               const void* O, const float* Z, const void* dO, void* dQ, void* dK, void* dV, float* dlog_g,
+                               void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return run_bwd(prob, Q, K, V, log_g, O, Z, dO, dQ, dK, dV, dlog_g, workspace, workspace_bytes, hip_stream, 1);
 }
 
 const char* power_attn_last_hip_error(void) { return g_last_error; }

@@ -74,3 +74,11 @@ def make_workload(name: str, with_grad: bool | None = None):
     w = WORKLOADS[name]
     wg = w["backward"] if with_grad is None else with_grad
     return make_qkvg(w["B"], w["H"], w["T"], w["d"], 1000 + w["position"], w["dtype"], with_grad=wg)
+
+
+def make_log_gates(B, H, T, seed, mean_decay=0.02):
+    """Seeded log-gates [B, H, T], float32, <= 0: log g_t = -mean_decay * e_t with e_t exponential
+    of mean 1 (most steps keep nearly everything, a few forget a lot), as a learned per-head,
+    per-timestep gate would give.  Both the oracle and the library read these float32 values."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    return (-mean_decay * rng.exponential(1.0, size=(B, H, T))).astype(np.float32)

@@ -30,24 +30,28 @@ def to_np(t):
 
 
 def run_fwd_bwd(Q, K, V, G, p, chunk, dtype, normalize=True, scale=1.0, impl="auto", backward=True,
-                keep_state=False):
-    """-> dict of numpy arrays O, Z (and dQ, dK, dV) computed by the HIP library.  keep_state: the
-    backward pass reuses the chunk states the forward pass left in a shared workspace."""
+                keep_state=False, log_g=None):
+    """-> dict of numpy arrays O, Z (and dQ, dK, dV; dlog_g when log_g is given) computed by the HIP
+    library.  keep_state: the backward pass reuses the chunk states the forward pass left in a
+    shared workspace."""
     import torch
     from paper_2507_04239_amd import binding, power_attn_bwd, power_attn_fwd
     tq, tk, tv = (to_dev(a, dtype) for a in (Q, K, V))
+    tl = None if log_g is None else torch.from_numpy(np.ascontiguousarray(log_g, dtype=np.float32)).to("cuda:0")
     ws = None
     if keep_state:
         B, H, T, d = Q.shape
-        prob = binding.make_problem(B, H, T, d, V.shape[3], p, chunk, normalize, scale, dtype, impl, True)
+        prob = binding.make_problem(B, H, T, d, V.shape[3], p, chunk, normalize, scale, dtype, impl, True, log_g is not None)
         ws = torch.empty(max(binding.power_attn_workspace_bytes(prob, True), 256), dtype=torch.uint8, device="cuda:0")
-    O, Z = power_attn_fwd(tq, tk, tv, p, chunk, normalize, scale, impl, workspace=ws, keep_state=keep_state)
+    O, Z = power_attn_fwd(tq, tk, tv, p, chunk, normalize, scale, impl, workspace=ws, keep_state=keep_state, log_g=tl)
     out = {"O": O, "Z": Z}
     if backward:
         tg = to_dev(G, dtype)
-        dQ, dK, dV = power_attn_bwd(tq, tk, tv, O, Z, tg, p, chunk, normalize, scale, impl, workspace=ws,
-                                    keep_state=keep_state)
-        out.update(dQ=dQ, dK=dK, dV=dV)
+        res = power_attn_bwd(tq, tk, tv, O, Z, tg, p, chunk, normalize, scale, impl, workspace=ws,
+                             keep_state=keep_state, log_g=tl)
+        out.update(dQ=res[0], dK=res[1], dV=res[2])
+        if log_g is not None:
+            out.update(dlog_g=res[3])
     torch.cuda.synchronize()
     return {k: to_np(t) for k, t in out.items()}
 
