@@ -62,9 +62,11 @@ static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; 
 //   qfac  [BH][T]       exp(bl_i): decay of query i since the start of its chunk
 //   kfac  [BH][T]       exp(bl_end - bl_j): decay of key j until the end of its chunk
 //   lam   [BH][T/chunk] exp(bl_end): decay across the whole chunk
-//   db    [BH][T]       scratch of the backward pass: dL/db_i
+//   db    [BH][T]       scratch of the backward pass: dL/db_i, or q_i . dq_i when a kernel family
+//                       forms the two dot products itself from its float32 accumulators
+//   db2   [BH][T]       then: k_i . dk_i
 struct GateBuf {
-    float *bl = nullptr, *qfac = nullptr, *kfac = nullptr, *lam = nullptr, *db = nullptr;
+    float *bl = nullptr, *qfac = nullptr, *kfac = nullptr, *lam = nullptr, *db = nullptr, *db2 = nullptr;
 };
 
 struct Ctx {
@@ -79,7 +81,9 @@ struct Ctx {
 size_t gate_workspace_bytes(const pa_problem& pr, bool backward);
 GateBuf gate_buffers(const pa_problem& pr, bool backward, char* base);
 pa_status gate_prepare(const Ctx& c, const float* log_g);
-pa_status gate_gradient(const Ctx& c, const void* Q, const void* K, const void* dQ, const void* dK, float* dlog_g);
+// have_dots: the family's kernels have already written q.dq into gate.db and k.dk into gate.db2
+pa_status gate_gradient(const Ctx& c, const void* Q, const void* K, const void* dQ, const void* dK, float* dlog_g,
+                        bool have_dots);
 
 // generic (vector-ALU, float32) family
 size_t generic_workspace_bytes(const pa_problem& pr, bool backward);

@@ -63,14 +63,17 @@ __global__ __launch_bounds__(256) void k_gate_db(const T* __restrict__ Q, const 
 }
 
 // dlog_g[t] = sum_{i >= t} db[i] per head: one workgroup per head, each thread a run of tokens
-__global__ __launch_bounds__(1024) void k_gate_revsum(const float* __restrict__ db, float* __restrict__ dlog_g, int T) {
+// (db2 null: db holds dL/db_i.  Else dL/db_i = (db[i] - db2[i]) * inv_p.)
+__global__ __launch_bounds__(1024) void k_gate_revsum(const float* __restrict__ db, const float* __restrict__ db2,
+                                                      float inv_p, float* __restrict__ dlog_g, int T) {
     __shared__ float part[1024];
     const int bh = blockIdx.x, tid = threadIdx.x;
     const size_t base = (size_t)bh * T;
     const int per = (T + 1023) / 1024;
     const int lo = min(tid * per, T), hi = min(lo + per, T);
+    auto term = [&](int i) { return db2 != nullptr ? (db[base + i] - db2[base + i]) * inv_p : db[base + i]; };
     float s = 0.f;
-    for (int i = lo; i < hi; ++i) s += db[base + i];
+    for (int i = lo; i < hi; ++i) s += term(i);
     part[tid] = s;
     __syncthreads();
     for (int off = 1; off < 1024; off <<= 1) {    // inclusive suffix scan of the per-thread sums
@@ -81,7 +84,7 @@ __global__ __launch_bounds__(1024) void k_gate_revsum(const float* __restrict__ 
     }
     float run = tid + 1 < 1024 ? part[tid + 1] : 0.f;   // everything after this thread's run
     for (int i = hi - 1; i >= lo; --i) {
-        run += db[base + i];
+        run += term(i);
         dlog_g[base + i] = run;
     }
 }
@@ -92,7 +95,7 @@ size_t gate_workspace_bytes(const pa_problem& pr, bool backward) {
     if (!pr.gated) return 0;
     const size_t BH = (size_t)pr.B * pr.H;
     const size_t tok = align_up(BH * pr.T * sizeof(float), 256);
-    return (backward ? 4 : 3) * tok + align_up(BH * (pr.T / pr.chunk) * sizeof(float), 256);
+    return (backward ? 5 : 3) * tok + align_up(BH * (pr.T / pr.chunk) * sizeof(float), 256);
 }
 
 GateBuf gate_buffers(const pa_problem& pr, bool backward, char* base) {
@@ -104,7 +107,10 @@ GateBuf gate_buffers(const pa_problem& pr, bool backward, char* base) {
     g.qfac = (float*)(base + tok);
     g.kfac = (float*)(base + 2 * tok);
     g.lam = (float*)(base + 3 * tok);
-    if (backward) g.db = (float*)(base + 3 * tok + align_up(BH * (pr.T / pr.chunk) * sizeof(float), 256));
+    if (backward) {
+        g.db = (float*)(base + 3 * tok + align_up(BH * (pr.T / pr.chunk) * sizeof(float), 256));
+        g.db2 = g.db + tok / sizeof(float);
+    }
     return g;
 }
 
@@ -116,10 +122,11 @@ pa_status gate_prepare(const Ctx& c, const float* log_g) {
     return launch_ok() ? PA_OK : PA_ERR_HIP;
 }
 
-pa_status gate_gradient(const Ctx& c, const void* Q, const void* K, const void* dQ, const void* dK, float* dlog_g) {
+pa_status gate_gradient(const Ctx& c, const void* Q, const void* K, const void* dQ, const void* dK, float* dlog_g,
+                        bool have_dots) {
     const pa_problem& pr = c.prob;
     const long long rows = (long long)pr.B * pr.H * pr.T;
-    {
+    if (!have_dots) {
         LaunchScope ls("gate_db", c.stream);
         if (pr.dtype == PA_DTYPE_F32)
             hipLaunchKernelGGL((k_gate_db<float>), dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, c.stream, (const float*)Q,
@@ -128,10 +135,11 @@ pa_status gate_gradient(const Ctx& c, const void* Q, const void* K, const void* 
             hipLaunchKernelGGL((k_gate_db<bf16_t>), dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, c.stream, (const bf16_t*)Q,
                                (const bf16_t*)dQ, (const bf16_t*)K, (const bf16_t*)dK, c.gate.db, rows, pr.d, 1.f / pr.p);
     }
-    if (!launch_ok()) return PA_ERR_HIP;
+    if (!have_dots && !launch_ok()) return PA_ERR_HIP;
     {
         LaunchScope ls("gate_revsum", c.stream);
-        hipLaunchKernelGGL(k_gate_revsum, dim3(pr.B * pr.H), dim3(1024), 0, c.stream, c.gate.db, dlog_g, pr.T);
+        hipLaunchKernelGGL(k_gate_revsum, dim3(pr.B * pr.H), dim3(1024), 0, c.stream, c.gate.db,
+                           have_dots ? (const float*)c.gate.db2 : (const float*)nullptr, 1.f / pr.p, dlog_g, pr.T);
     }
     return launch_ok() ? PA_OK : PA_ERR_HIP;
 }

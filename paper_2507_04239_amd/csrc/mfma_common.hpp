@@ -71,26 +71,25 @@ __device__ __forceinline__ void vm_wait() {
 
 // ---- launchers (each defined next to its kernels) ------------------------------------------
 // feature-major copy in blocks of 64 tokens: [BH][T][DH] -> [BH][T/64][DH][64]
-bool launch_transpose(hipStream_t s, const bf16_t* in, bf16_t* out, int BH, int T);
+// fac (may be null): per-token factors; the copy is then of x_t * sqrt(fac_t)
+bool launch_transpose(hipStream_t s, const bf16_t* in, bf16_t* out, int BH, int T, const float* fac = nullptr);
 // state scan; rev = 0: S_n from (Kt, Vt); rev = 1: R_m from (Qt, Ght) with the weights gz.
 // gam receives Gamma (rev = 0) or Omega (rev = 1).
 bool launch_scan(const char* name, hipStream_t s, bool rev, const bf16_t* Xt, const bf16_t* Yt, const float* wgt, bf16_t* stC,
-                 bf16_t* gam, int BH, int T, int cs, float out_scale);
+                 bf16_t* gam, int BH, int T, int cs, float out_scale, const float* lam = nullptr);
+// `bl`, `qfac` / `kfac`: per-token gating arrays (see GateBuf), all null when not gated; gated dQ / dK kernels
+// also write q_i . dq_i (qdq) and k_j . dk_j (kdk) from their float32 accumulators
 bool launch_fwd_chunk(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* Vt, const bf16_t* stC,
-                      const bf16_t* gam, bf16_t* O, float* Z, int BH, int T, int cs, float scale, int normalize);
+                      const bf16_t* gam, bf16_t* O, float* Z, int BH, int T, int cs, float scale, int normalize,
+                      const float* bl, const float* qfac);
 bool launch_bwd_prep(hipStream_t s, const bf16_t* dO, const bf16_t* O, const float* Z, bf16_t* Gh, float* gz,
                      long long rows, int normalize);
 bool launch_bwd_dq(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* V, const bf16_t* Gh,
                    const float* gz, const bf16_t* Kt, const bf16_t* stC, const bf16_t* gam, bf16_t* dQ, int BH, int T,
-                   int cs, float scale);
-bool launch_bwd_dk(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* V, const bf16_t* Gh,
-                   const float* gz, const bf16_t* Qt, const bf16_t* rtC, const bf16_t* omg, bf16_t* dK, int BH, int T,
-                   int cs, float scale);
+                   int cs, float scale, const float* bl, const float* qfac, float* qdq);
 bool launch_bwd_dkdv(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* V, const bf16_t* Gh, const float* gz,
                      const bf16_t* Qt, const bf16_t* Ght, const bf16_t* rtC, const bf16_t* omg, bf16_t* dK, bf16_t* dV, int BH,
-                     int T, int cs, float scale);
-bool launch_bwd_dv(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* Ght, const bf16_t* rtC,
-                   bf16_t* dV, int BH, int T, int cs, float scale);
+                     int T, int cs, float scale, const float* bl, const float* kfac, float* kdk);
 
 }  // namespace mfma
 }  // namespace pa

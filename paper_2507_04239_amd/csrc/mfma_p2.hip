@@ -12,6 +12,7 @@ struct Layout {
     bool keep;
     size_t off_kt, off_vt, off_gam, off_sc;                      // forward
     size_t off_qt, off_gh, off_ght, off_gz, off_omg, off_rc;     // backward only
+    size_t off_kts, off_qts;                                     // gated: copies of K, Q scaled for the scans
     size_t total;
 };
 
@@ -36,6 +37,8 @@ Layout make_layout(const pa_problem& pr, bool backward) {
     L.off_vt = take(tok);
     L.off_gam = take(gm);
     L.off_sc = take(st);
+    L.off_kts = pr.gated ? take(tok) : L.off_kt;
+    L.off_qts = 0;
     if (backward || L.keep) {
         L.off_qt = take(tok);
         L.off_gh = take(tok);
@@ -43,6 +46,7 @@ Layout make_layout(const pa_problem& pr, bool backward) {
         L.off_gz = take(BH * pr.T * sizeof(float));
         L.off_omg = take(gm);
         L.off_rc = take(st);
+        L.off_qts = pr.gated ? take(tok) : L.off_qt;
     }
     L.total = off;
     return L;
@@ -53,7 +57,6 @@ Layout make_layout(const pa_problem& pr, bool backward) {
 pa_status mfma_supported(const pa_problem& pr, bool backward) {
     (void)backward;
     if (pr.dtype != PA_DTYPE_BF16 || pr.p != 2) return PA_ERR_UNSUPPORTED;
-    if (pr.gated) return PA_ERR_UNSUPPORTED;   // gating: generic family only so far
     if (pr.d != DH || pr.v != DH) return PA_ERR_UNSUPPORTED;
     if (pr.chunk % QBLK != 0) return PA_ERR_UNSUPPORTED;
     if ((size_t)pr.B * pr.H > 65535u) return PA_ERR_UNSUPPORTED;
@@ -67,19 +70,26 @@ size_t mfma_workspace_bytes(const pa_problem& pr, bool backward) { return make_l
 #define PA_TRY(CALL) \
     if (!(CALL)) return PA_ERR_HIP;
 
+// Gated problems (c.gate non-null): the scans read copies of K (Q in the backward pass) scaled by
+// the square root of the per-token decay, and multiply the running sum by the per-chunk decay;
+// the per-chunk kernels apply the remaining factors (see the chunk kernels).
 pa_status mfma_fwd(const Ctx& c, const void* Q, const void* K, const void* V, void* O, float* Z) {
     const pa_problem& pr = c.prob;
     const Layout L = make_layout(pr, false);
     const int BH = pr.B * pr.H;
+    const GateBuf& gt = c.gate;
     bf16_t* Kt = (bf16_t*)(c.ws + L.off_kt);
+    bf16_t* Kts = (bf16_t*)(c.ws + L.off_kts);
     bf16_t* Vt = (bf16_t*)(c.ws + L.off_vt);
     bf16_t* Sc = (bf16_t*)(c.ws + L.off_sc);
     bf16_t* Gam = (bf16_t*)(c.ws + L.off_gam);
-    PA_TRY(launch_transpose(c.stream, (const bf16_t*)K, Kt, BH, pr.T))
+    if (!pr.gated || L.keep)   // the plain copy of K serves the scan (un-gated) and the backward pass's dQ
+        PA_TRY(launch_transpose(c.stream, (const bf16_t*)K, Kt, BH, pr.T))
+    if (pr.gated) PA_TRY(launch_transpose(c.stream, (const bf16_t*)K, Kts, BH, pr.T, gt.kfac))
     PA_TRY(launch_transpose(c.stream, (const bf16_t*)V, Vt, BH, pr.T))
-    PA_TRY(launch_scan("mfma_state_scan", c.stream, false, Kt, Vt, nullptr, Sc, Gam, BH, pr.T, L.cs, 1.0f))
+    PA_TRY(launch_scan("mfma_state_scan", c.stream, false, Kts, Vt, nullptr, Sc, Gam, BH, pr.T, L.cs, 1.0f, gt.lam))
     PA_TRY(launch_fwd_chunk(c.stream, (const bf16_t*)Q, (const bf16_t*)K, Vt, Sc, Gam, (bf16_t*)O, Z, BH, pr.T, L.cs,
-                            pr.scale, pr.normalize))
+                            pr.scale, pr.normalize, gt.bl, gt.qfac))
     return PA_OK;
 }
 
@@ -113,9 +123,12 @@ pa_status mfma_bwd(const Ctx& c, const void* Q, const void* K, const void* V, co
     const pa_problem& pr = c.prob;
     const Layout L = make_layout(pr, true);
     const int BH = pr.B * pr.H;
+    const GateBuf& gt = c.gate;
     bf16_t* Kt = (bf16_t*)(c.ws + L.off_kt);
+    bf16_t* Kts = (bf16_t*)(c.ws + L.off_kts);
     bf16_t* Vt = (bf16_t*)(c.ws + L.off_vt);
     bf16_t* Qt = (bf16_t*)(c.ws + L.off_qt);
+    bf16_t* Qts = (bf16_t*)(c.ws + L.off_qts);
     bf16_t* Gh = (bf16_t*)(c.ws + L.off_gh);
     bf16_t* Ght = (bf16_t*)(c.ws + L.off_ght);
     float* gz = (float*)(c.ws + L.off_gz);
@@ -131,6 +144,7 @@ pa_status mfma_bwd(const Ctx& c, const void* Q, const void* K, const void* V, co
 
     PA_TRY(launch_bwd_prep(s_main, (const bf16_t*)dO, (const bf16_t*)O, Z, Gh, gz, (long long)BH * pr.T, pr.normalize))
     PA_TRY(launch_transpose(s_main, q, Qt, BH, pr.T))
+    if (pr.gated) PA_TRY(launch_transpose(s_main, q, Qts, BH, pr.T, gt.qfac))
     PA_TRY(launch_transpose(s_main, Gh, Ght, BH, pr.T))
     // The fork sits here, not right after the preparation kernel that dQ depends on: the scan's
     // workgroups need most of a CU's LDS and must be placed before dQ's fill the CUs.
@@ -139,16 +153,18 @@ pa_status mfma_bwd(const Ctx& c, const void* Q, const void* K, const void* V, co
             return PA_ERR_HIP;
     }
     // strand R (caller's stream, so that its workgroups are placed first): state-gradient scan
-    PA_TRY(launch_scan("mfma_state_grad_scan", s_main, true, Qt, Ght, gz, Rc, Omg, BH, pr.T, L.cs, s2))
+    PA_TRY(launch_scan("mfma_state_grad_scan", s_main, true, Qts, Ght, gz, Rc, Omg, BH, pr.T, L.cs, s2, gt.lam))
     // strand S (side stream): dQ from the forward state
     if (!L.keep) {
         // nothing but O and Z was saved: rebuild the chunk states
         PA_TRY(launch_transpose(s_side, k, Kt, BH, pr.T))
+        if (pr.gated) PA_TRY(launch_transpose(s_side, k, Kts, BH, pr.T, gt.kfac))
         PA_TRY(launch_transpose(s_side, v, Vt, BH, pr.T))
-        PA_TRY(launch_scan("mfma_state_scan_bwd", s_side, false, Kt, Vt, nullptr, Sc, Gam, BH, pr.T, L.cs, 1.0f))
+        PA_TRY(launch_scan("mfma_state_scan_bwd", s_side, false, Kts, Vt, nullptr, Sc, Gam, BH, pr.T, L.cs, 1.0f, gt.lam))
     }
-    PA_TRY(launch_bwd_dq(s_side, q, k, v, Gh, gz, Kt, Sc, Gam, (bf16_t*)dQ, BH, pr.T, L.cs, pr.scale))
-    PA_TRY(launch_bwd_dkdv(s_main, q, k, v, Gh, gz, Qt, Ght, Rc, Omg, (bf16_t*)dK, (bf16_t*)dV, BH, pr.T, L.cs, pr.scale))
+    PA_TRY(launch_bwd_dq(s_side, q, k, v, Gh, gz, Kt, Sc, Gam, (bf16_t*)dQ, BH, pr.T, L.cs, pr.scale, gt.bl, gt.qfac, gt.db))
+    PA_TRY(launch_bwd_dkdv(s_main, q, k, v, Gh, gz, Qt, Ght, Rc, Omg, (bf16_t*)dK, (bf16_t*)dV, BH, pr.T, L.cs, pr.scale,
+                           gt.bl, gt.kfac, gt.db2))
     if (side.ok) {
         if (hipEventRecord(side.join, s_side) != hipSuccess || hipStreamWaitEvent(s_main, side.join, 0) != hipSuccess)
             return PA_ERR_HIP;

@@ -187,9 +187,10 @@ constexpr int dphi_block_begin(int fbi, int fbj) {
 // of the d phi contraction from a swizzled ring, for a workgroup whose other waves do that
 // contraction on the same ring.  `wv`: which 64 tokens; `wr`: this wave's index among the NW
 // waves that share the ring.
-template <int RING_TILES, int NW, bool DORDER>
+// GATED: the contribution of token column ib is multiplied by colf[ib] (folded into x[8 tj ..]).
+template <int RING_TILES, int NW, bool DORDER, bool GATED = false>
 __device__ __forceinline__ void readout(f32x4 (&acc)[4][4], const bf16_t* __restrict__ Sn, ChunkSmem<RING_TILES>& sm,
-                                        float xscale, int wv, int wr, int lane) {
+                                        float xscale, int wv, int wr, int lane, const float* colf = nullptr) {
     const int r16 = lane & 15, g = lane >> 4;
     const XbRow* Xb = sm.xb;
     // fragment (s, vb) of a tile: unit (a = 4 s + g, v = 16 vb + r16); swizzled: v ^ 4 (a & 1)
@@ -223,6 +224,10 @@ __device__ __forceinline__ void readout(f32x4 (&acc)[4][4], const bf16_t* __rest
                 xbv[ib][2] = bf_lo(raw.y); xbv[ib][3] = bf_hi(raw.y);
                 xbv[ib][4] = bf_lo(raw.z); xbv[ib][5] = bf_hi(raw.z);
                 xbv[ib][6] = bf_lo(raw.w); xbv[ib][7] = bf_hi(raw.w);
+                if (GATED) {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) xbv[ib][i] *= colf[ib];
+                }
             }
         }
         lds_read_wait(sf[0][0], sf[0][1], sf[0][2], sf[0][3], sf[1][0], sf[1][1], sf[1][2], sf[1][3]);
@@ -263,9 +268,10 @@ __device__ __forceinline__ void readout(f32x4 (&acc)[4][4], const bf16_t* __rest
 // column block tj and lands once per visit; term 1 is summed across the lane pair, exchanged
 // across the half-waves and added by the lane that owns feature 8 ti + a in the accumulator
 // layout (feature 16 fb + 4 g' + r').
-template <int FBI, int FBJ, int RING_TILES, int NW>
+template <int FBI, int FBJ, int RING_TILES, int NW, bool GATED>
 __device__ __forceinline__ void dphi_block(f32x4 (&acc)[4][4], const bf16_t* __restrict__ Sn, ChunkSmem<RING_TILES>& sm,
-                                           const Frag (&yf)[4][2], float xscale, int wv, int wr, int lane PA_PROBE_PARAM) {
+                                           const Frag (&yf)[4][2], float xscale, int wv, int wr, int lane,
+                                           const float* colf PA_PROBE_PARAM) {
     constexpr int K0 = dphi_block_begin(FBI, FBJ), K1 = K0 + (FBI == FBJ ? 3 : 4);
     const int r16 = lane & 15, g = lane >> 4;
     const XbRow* Xb = sm.xb;
@@ -328,8 +334,9 @@ __device__ __forceinline__ void dphi_block(f32x4 (&acc)[4][4], const bf16_t* __r
                 const auto sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(own_a), __float_as_uint(own_b), false, false);
                 float lo, hi;
                 halves(__uint_as_float(sw[0]) + __uint_as_float(sw[1]), lo, hi);
-                acc[FBI][ib][2 * rb] += own_mask * lo;
-                acc[FBI][ib][2 * rb + 1] += own_mask * hi;
+                const float om = GATED ? own_mask * colf[ib] : own_mask;
+                acc[FBI][ib][2 * rb] += om * lo;
+                acc[FBI][ib][2 * rb + 1] += om * hi;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     u2[ib][r] += ca[r] * xa_a;
@@ -340,22 +347,26 @@ __device__ __forceinline__ void dphi_block(f32x4 (&acc)[4][4], const bf16_t* __r
         if (ti == min(tj, 2 * FBI + 1)) {   // last tile of the column block here: land term 2
             const float mk = ((g >> 1) == (tj & 1)) ? xscale : 0.f;
 #pragma unroll
-            for (int ib = 0; ib < 4; ++ib)
+            for (int ib = 0; ib < 4; ++ib) {
+                const float mkc = GATED ? mk * colf[ib] : mk;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) acc[FBJ][ib][r] += mk * xor32_sum(u2[ib][r]);
+                for (int r = 0; r < 4; ++r) acc[FBJ][ib][r] += mkc * xor32_sum(u2[ib][r]);
+            }
         }
     }
 }
 
 // Must be called by all NW waves that share the ring (it contains barriers), or run side by side
 // with waves that execute readout<.., NW, true> on the same ring.
-template <int RING_TILES, int NW>
+// GATED: the contribution of token column ib is multiplied by colf[ib] (folded into the masks).
+template <int RING_TILES, int NW, bool GATED = false>
 __device__ __forceinline__ void dphi(f32x4 (&acc)[4][4], const bf16_t* __restrict__ Sn, ChunkSmem<RING_TILES>& sm,
-                                     const Frag (&yf)[4][2], float xscale, int wv, int wr, int lane) {
+                                     const Frag (&yf)[4][2], float xscale, int wv, int wr, int lane,
+                                     const float* colf = nullptr) {
 #pragma unroll
     for (int k = 0; k < RING_TILES - 1; ++k) ring_issue<true, NW>(sm, k, Sn, DPHI_ORDER.v[k] >> 16, wr, lane);
     PA_PROBE_DECL
-#define PA_BLOCK(I, J) dphi_block<I, J, RING_TILES, NW>(acc, Sn, sm, yf, xscale, wv, wr, lane PA_PROBE_ARG);
+#define PA_BLOCK(I, J) dphi_block<I, J, RING_TILES, NW, GATED>(acc, Sn, sm, yf, xscale, wv, wr, lane, colf PA_PROBE_ARG);
     PA_BLOCK(0, 0) PA_BLOCK(0, 1) PA_BLOCK(1, 1) PA_BLOCK(0, 2) PA_BLOCK(1, 2) PA_BLOCK(2, 2)
     PA_BLOCK(0, 3) PA_BLOCK(1, 3) PA_BLOCK(2, 3) PA_BLOCK(3, 3)
 #undef PA_BLOCK
@@ -363,13 +374,50 @@ __device__ __forceinline__ void dphi(f32x4 (&acc)[4][4], const bf16_t* __restric
     vm_wait<0>();
 }
 
+// ---- gating ------------------------------------------------------------------------------------
+// Gated kernels (template flag GATED; Sec. 2 "Gating", App. E.2 / E.3) take two per-token arrays:
+// bl, the sum of the log-gates from the start of the token's chunk, and fac, the decay that goes
+// with the state term: exp(bl_i) for a query (the state is seen from the chunk's start), or
+// exp(bl_end - bl_j) for a key (its contribution to R is seen from the chunk's end).  The state
+// term's routines fold fac into values they already multiply by; a pair inside the chunk carries
+// exp(bl_i - bl_j).  Masked pairs are zeroed by selection, so an overflowing factor of a masked
+// pair is harmless.
+
+// x_t . (the accumulator column of token t) for the wave's tokens, from the float32 accumulators
+// acc[fb][ib] (16 features x 16 tokens; lane (r16, g) holds features 16 fb + 4 g + r of token r16)
+// and the bf16 rows x in LDS; written by the lanes g == 0.  These dot products give the gradient
+// of the log-gates: a_ij is homogeneous of degree p in q_i and in k_j.
+__device__ __forceinline__ void store_row_dots(float* __restrict__ out, size_t row0, const f32x4 (&acc)[4][4],
+                                               const XbRow* Xb, int xrow0, float mul, int r16, int g) {
+#pragma unroll
+    for (int ib = 0; ib < 4; ++ib) {
+        float s = 0.f;
+#pragma unroll
+        for (int fb = 0; fb < 4; ++fb) {
+            const uint2 raw = *(const uint2*)&Xb[xrow0 + 16 * ib + r16][16 * fb + 4 * g];
+            s += acc[fb][ib][0] * bf_lo(raw.x) + acc[fb][ib][1] * bf_hi(raw.x) + acc[fb][ib][2] * bf_lo(raw.y) +
+                 acc[fb][ib][3] * bf_hi(raw.y);
+        }
+        s = xor32_sum(xor16_sum(s));
+        if (g == 0) out[row0 + 16 * ib + r16] = mul * s;
+    }
+}
+
+// per-lane values of a per-token array for the wave's four 16-token column blocks
+__device__ __forceinline__ void load_cols(float (&out)[4], const float* __restrict__ arr, size_t row0, int r16) {
+#pragma unroll
+    for (int ib = 0; ib < 4; ++ib) out[ib] = arr[row0 + 16 * ib + r16];
+}
+
 // ---- forward chunk kernel -------------------------------------------------------------------------
 // acc[vb][ib] = O^T: 16 value columns x 16 queries.
+template <bool GATED>
 __global__ __launch_bounds__(128, 2) void k_mfma_fwd_chunk(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
                                                            const bf16_t* __restrict__ Vt, const bf16_t* __restrict__ StC,
                                                            const bf16_t* __restrict__ Gam, bf16_t* __restrict__ O,
                                                            float* __restrict__ Z, int T, int cs, float scale,
-                                                           int normalize) {
+                                                           int normalize, const float* __restrict__ bl,
+                                                           const float* __restrict__ qfac) {
     __shared__ __attribute__((aligned(16))) ChunkSmem<RING_RO> sm;
     XbRow* Xb = sm.xb;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -391,6 +439,9 @@ __global__ __launch_bounds__(128, 2) void k_mfma_fwd_chunk(const bf16_t* __restr
     float zsum[4] = {0.f, 0.f, 0.f, 0.f};     // per query block: partial sum of scores (this lane's k-slots)
     __syncthreads();
 
+    float blq[4] = {0.f, 0.f, 0.f, 0.f};
+    if (GATED) load_cols(blq, bl, head_tok + i0 + 64 * wv, r16);
+
     // attention form over the keys of the stretch, up to the diagonal
     for (int kb0 = n * cs; kb0 <= i0; kb0 += QBLK) {
         const bool diag = kb0 == i0;
@@ -402,6 +453,11 @@ __global__ __launch_bounds__(128, 2) void k_mfma_fwd_chunk(const bf16_t* __restr
             for (int jb = 0; jb < 2; ++jb) {
                 const size_t krow = head_tok + key0 + 16 * jb + r16;
                 const bf16x8 kf0 = glb_frag(K, krow, 0, g), kf1 = glb_frag(K, krow, 1, g);
+                float blk[4] = {0.f, 0.f, 0.f, 0.f};
+                if (GATED) {
+                    const float4 b4 = *(const float4*)(bl + head_tok + key0 + 16 * jb + 4 * g);
+                    blk[0] = b4.x; blk[1] = b4.y; blk[2] = b4.z; blk[3] = b4.w;
+                }
 #pragma unroll
                 for (int ib = 0; ib < 4; ++ib) {
                     const int qrow = 64 * wv + 16 * ib + r16;
@@ -410,6 +466,7 @@ __global__ __launch_bounds__(128, 2) void k_mfma_fwd_chunk(const bf16_t* __restr
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         float pv = s2 * c[r] * c[r];
+                        if (GATED) pv *= __expf(blq[ib] - blk[r]);
                         if (diag && key0 + 16 * jb + 4 * g + r > i0 + qrow) pv = 0.f;
                         zsum[ib] += pv;
                         pf[ib].v[4 * jb + r] = (__bf16)pv;
@@ -426,6 +483,8 @@ __global__ __launch_bounds__(128, 2) void k_mfma_fwd_chunk(const bf16_t* __restr
     }
 
     if (n > 0) {
+        float qf[4] = {1.f, 1.f, 1.f, 1.f};
+        if (GATED) load_cols(qf, qfac, head_tok + i0 + 64 * wv, r16);
         // phi(q~) . gamma = q~^T Gamma q~
         const bf16_t* Gn = Gam + (size_t)(bh * nstate + n) * DH * DH;
 #pragma unroll 1
@@ -437,10 +496,11 @@ __global__ __launch_bounds__(128, 2) void k_mfma_fwd_chunk(const bf16_t* __restr
                 f32x4 c = mfma16(gm0, lds_frag(Xb, qrow, 0, g), ZERO4);
                 c = mfma16(gm1, lds_frag(Xb, qrow, 1, g), c);
                 const uint2 raw = *(const uint2*)&Xb[qrow][16 * ab + 4 * g];
-                zsum[ib] += s2 * (c[0] * bf_lo(raw.x) + c[1] * bf_hi(raw.x) + c[2] * bf_lo(raw.y) + c[3] * bf_hi(raw.y));
+                const float zs = s2 * (c[0] * bf_lo(raw.x) + c[1] * bf_hi(raw.x) + c[2] * bf_lo(raw.y) + c[3] * bf_hi(raw.y));
+                zsum[ib] += GATED ? qf[ib] * zs : zs;
             }
         }
-        readout<RING_RO, 2, false>(acc, StC + (size_t)(bh * nstate + n) * STATE_ELEMS, sm, s2, wv, wv, lane);
+        readout<RING_RO, 2, false, GATED>(acc, StC + (size_t)(bh * nstate + n) * STATE_ELEMS, sm, s2, wv, wv, lane, qf);
     }
 
 #pragma unroll
@@ -502,11 +562,14 @@ __global__ __launch_bounds__(256) void k_mfma_bwd_prep(const bf16_t* __restrict_
 //   dq_i = scale * [ sum_{j<=i, same stretch} t_ij k_j + 2 gz_i Gamma q~_i + J_phi(q~_i)^T (S_n ghat_i) ]
 //   q~ = scale q,  s_ij = q~_i . k_j,  t_ij = 2 s_ij (ghat_i . v_j + gz_i)
 // acc[fb][ib] = (the bracket)^T: 16 features x 16 queries.
+template <bool GATED>
 __global__ __launch_bounds__(128, 2) void k_mfma_bwd_dq(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
                                                         const bf16_t* __restrict__ V, const bf16_t* __restrict__ Gh,
                                                         const float* __restrict__ gz, const bf16_t* __restrict__ Kt,
                                                         const bf16_t* __restrict__ StC, const bf16_t* __restrict__ Gam,
-                                                        bf16_t* __restrict__ dQ, int T, int cs, float scale) {
+                                                        bf16_t* __restrict__ dQ, int T, int cs, float scale,
+                                                        const float* __restrict__ bl, const float* __restrict__ qfac,
+                                                        float* __restrict__ qdq) {
     __shared__ __attribute__((aligned(16))) ChunkSmem<RING_DP> sm;
     XbRow* Xb = sm.xb;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -535,6 +598,9 @@ __global__ __launch_bounds__(128, 2) void k_mfma_bwd_dq(const bf16_t* __restrict
         for (int ib = 0; ib < 4; ++ib) acc[fb][ib] = ZERO4;
     __syncthreads();
 
+    float blq[4] = {0.f, 0.f, 0.f, 0.f};
+    if (GATED) load_cols(blq, bl, head_tok + i0 + 64 * wv, r16);
+
     for (int kb0 = n * cs; kb0 <= i0; kb0 += QBLK) {
         const bool diag = kb0 == i0;
         const int nsteps = diag ? 2 * (wv + 1) : 4;
@@ -546,6 +612,11 @@ __global__ __launch_bounds__(128, 2) void k_mfma_bwd_dq(const bf16_t* __restrict
                 const size_t krow = head_tok + key0 + 16 * jb + r16;
                 const bf16x8 kf0 = glb_frag(K, krow, 0, g), kf1 = glb_frag(K, krow, 1, g);
                 const bf16x8 vf0 = glb_frag(V, krow, 0, g), vf1 = glb_frag(V, krow, 1, g);
+                float blk[4] = {0.f, 0.f, 0.f, 0.f};
+                if (GATED) {
+                    const float4 b4 = *(const float4*)(bl + head_tok + key0 + 16 * jb + 4 * g);
+                    blk[0] = b4.x; blk[1] = b4.y; blk[2] = b4.z; blk[3] = b4.w;
+                }
 #pragma unroll
                 for (int ib = 0; ib < 4; ++ib) {
                     const int qrow = 64 * wv + 16 * ib + r16;
@@ -556,6 +627,7 @@ __global__ __launch_bounds__(128, 2) void k_mfma_bwd_dq(const bf16_t* __restrict
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         float tv = 2.f * scale * c[r] * (e[r] + gzq[ib]);
+                        if (GATED) tv *= __expf(blq[ib] - blk[r]);
                         if (diag && key0 + 16 * jb + 4 * g + r > i0 + qrow) tv = 0.f;
                         tf[ib].v[4 * jb + r] = (__bf16)tv;
                     }
@@ -569,8 +641,9 @@ __global__ __launch_bounds__(128, 2) void k_mfma_bwd_dq(const bf16_t* __restrict
             }
         }
     }
-
     if (n > 0) {
+        float qf[4] = {1.f, 1.f, 1.f, 1.f};
+        if (GATED) load_cols(qf, qfac, head_tok + i0 + 64 * wv, r16);
         // normaliser: d/dq~ of gz q~^T Gamma q~ = 2 gz Gamma q~
         const bf16_t* Gn = Gam + (size_t)(bh * nstate + n) * DH * DH;
 #pragma unroll
@@ -581,13 +654,14 @@ __global__ __launch_bounds__(128, 2) void k_mfma_bwd_dq(const bf16_t* __restrict
                 const int qrow = 64 * wv + 16 * ib + r16;
                 f32x4 c = mfma16(gm0, lds_frag(Xb, qrow, 0, g), ZERO4);
                 c = mfma16(gm1, lds_frag(Xb, qrow, 1, g), c);
-                const float f = 2.f * gzq[ib] * scale;
+                const float f = 2.f * gzq[ib] * scale * (GATED ? qf[ib] : 1.f);
 #pragma unroll
                 for (int r = 0; r < 4; ++r) acc[ab][ib][r] += f * c[r];
             }
         }
-        dphi<RING_DP, 2>(acc, StC + (size_t)(bh * nstate + n) * STATE_ELEMS, sm, gf, scale, wv, wv, lane);
+        dphi<RING_DP, 2, GATED>(acc, StC + (size_t)(bh * nstate + n) * STATE_ELEMS, sm, gf, scale, wv, wv, lane, qf);
     }
+    if (GATED) store_row_dots(qdq, head_tok + i0 + 64 * wv, acc, Xb, 64 * wv, scale, r16, g);
 #pragma unroll
     for (int ib = 0; ib < 4; ++ib) {
         const size_t row = head_tok + i0 + 64 * wv + 16 * ib + r16;
@@ -605,12 +679,13 @@ __global__ __launch_bounds__(128, 2) void k_mfma_bwd_dq(const bf16_t* __restrict
 //   dk_j = scale * sum_{i>=j, same stretch} t_ij q_i + 2 Omega_m k_j + J_phi(k_j)^T (R_m v_j)
 // (R and Omega already carry scale^2).  acc[fb][jb] = dK^T: 16 features x 16 keys.
 // Body for the 64 keys of token half `wv`; the block's K rows are already staged in sm.xb.
-template <int RING_TILES, int NW>
+template <int RING_TILES, int NW, bool GATED>
 __device__ __forceinline__ void dk_body(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
                                         const bf16_t* __restrict__ Gh, const float* __restrict__ gz,
                                         const bf16_t* __restrict__ Qt, const bf16_t* __restrict__ RtC,
                                         const bf16_t* __restrict__ Omg, bf16_t* __restrict__ dK, int T, int cs, float scale,
-                                        ChunkSmem<RING_TILES>& sm, int wv, int wr, int lane) {
+                                        const float* __restrict__ bl, const float* __restrict__ kfac,
+                                        float* __restrict__ kdk, ChunkSmem<RING_TILES>& sm, int wv, int wr, int lane) {
     const XbRow* Xb = sm.xb;
     const int r16 = lane & 15, g = lane >> 4;
     const int bh = blockIdx.y;
@@ -633,7 +708,11 @@ __device__ __forceinline__ void dk_body(const bf16_t* __restrict__ Q, const bf16
 #pragma unroll
         for (int jb = 0; jb < 4; ++jb) acc[fb][jb] = ZERO4;
 
-    const int q_hi = (m + 1) * cs;   // queries of the same stretch, from the diagonal block on
+    float blk[4] = {0.f, 0.f, 0.f, 0.f};
+    if (GATED) load_cols(blk, bl, head_tok + j0 + 64 * wv, r16);
+
+    const float ts = 2.f * scale * scale;   // d s / d k = scale q; t carries 2 scale
+    const int q_hi = (m + 1) * cs;          // queries of the same stretch, from the diagonal block on
     for (int qb0 = j0; qb0 < q_hi; qb0 += QBLK) {
         const bool diag = qb0 == j0;
         for (int s = diag ? 2 * wv : 0; s < 4; ++s) {   // queries before this wave's first key are masked
@@ -646,6 +725,11 @@ __device__ __forceinline__ void dk_body(const bf16_t* __restrict__ Q, const bf16
                 const bf16x8 ga0 = glb_frag(Gh, qrow, 0, g), ga1 = glb_frag(Gh, qrow, 1, g);
                 const float4 gz4 = *(const float4*)(gz + head_tok + q0 + 16 * ibq + 4 * g);
                 const float gzr[4] = {gz4.x, gz4.y, gz4.z, gz4.w};
+                float blq[4] = {0.f, 0.f, 0.f, 0.f};
+                if (GATED) {
+                    const float4 b4 = *(const float4*)(bl + head_tok + q0 + 16 * ibq + 4 * g);
+                    blq[0] = b4.x; blq[1] = b4.y; blq[2] = b4.z; blq[3] = b4.w;
+                }
 #pragma unroll
                 for (int jb = 0; jb < 4; ++jb) {
                     const int krow = 64 * wv + 16 * jb + r16;
@@ -655,7 +739,8 @@ __device__ __forceinline__ void dk_body(const bf16_t* __restrict__ Q, const bf16
                     e = mfma16(ga1, vf[jb][1].v, e);
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        float tv = 2.f * scale * c[r] * (e[r] + gzr[r]);
+                        float tv = ts * c[r] * (e[r] + gzr[r]);
+                        if (GATED) tv *= __expf(blq[r] - blk[jb]);
                         if (diag && q0 + 16 * ibq + 4 * g + r < j0 + krow) tv = 0.f;
                         tf[jb].v[4 * ibq + r] = (__bf16)tv;
                     }
@@ -669,15 +754,9 @@ __device__ __forceinline__ void dk_body(const bf16_t* __restrict__ Q, const bf16
             }
         }
     }
-    // d s / d k = scale q
-#pragma unroll
-    for (int fb = 0; fb < 4; ++fb)
-#pragma unroll
-        for (int jb = 0; jb < 4; ++jb)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) acc[fb][jb][r] *= scale;
-
     if (m < nstate - 1) {
+        float kf[4] = {1.f, 1.f, 1.f, 1.f};
+        if (GATED) load_cols(kf, kfac, head_tok + j0 + 64 * wv, r16);
         const bf16_t* Om = Omg + (size_t)(bh * nstate + m) * DH * DH;
 #pragma unroll
         for (int ab = 0; ab < 4; ++ab) {
@@ -687,12 +766,14 @@ __device__ __forceinline__ void dk_body(const bf16_t* __restrict__ Q, const bf16
                 const int krow = 64 * wv + 16 * jb + r16;
                 f32x4 c = mfma16(gm0, lds_frag(Xb, krow, 0, g), ZERO4);
                 c = mfma16(gm1, lds_frag(Xb, krow, 1, g), c);
+                const float f = GATED ? 2.f * kf[jb] : 2.f;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) acc[ab][jb][r] += 2.f * c[r];
+                for (int r = 0; r < 4; ++r) acc[ab][jb][r] += f * c[r];
             }
         }
-        dphi<RING_TILES, NW>(acc, RtC + (size_t)(bh * nstate + m) * STATE_ELEMS, sm, vf, 1.f, wv, wr, lane);
+        dphi<RING_TILES, NW, GATED>(acc, RtC + (size_t)(bh * nstate + m) * STATE_ELEMS, sm, vf, 1.f, wv, wr, lane, kf);
     }
+    if (GATED) store_row_dots(kdk, head_tok + j0 + 64 * wv, acc, Xb, 64 * wv, 1.f, r16, g);
 #pragma unroll
     for (int jb = 0; jb < 4; ++jb) {
         const size_t row = head_tok + j0 + 64 * wv + 16 * jb + r16;
@@ -706,27 +787,15 @@ __device__ __forceinline__ void dk_body(const bf16_t* __restrict__ Q, const bf16
     }
 }
 
-__global__ __launch_bounds__(128, 2) void k_mfma_bwd_dk(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
-                                                        const bf16_t* __restrict__ V, const bf16_t* __restrict__ Gh,
-                                                        const float* __restrict__ gz, const bf16_t* __restrict__ Qt,
-                                                        const bf16_t* __restrict__ RtC, const bf16_t* __restrict__ Omg,
-                                                        bf16_t* __restrict__ dK, int T, int cs, float scale) {
-    __shared__ __attribute__((aligned(16))) ChunkSmem<RING_DP> sm;
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    stage_rows(sm.xb, K, (size_t)blockIdx.y * T + blockIdx.x * QBLK, tid);
-    __syncthreads();
-    dk_body<RING_DP, 2>(Q, K, V, Gh, gz, Qt, RtC, Omg, dK, T, cs, scale, sm, wv, wv, lane);
-}
-
 // ---- backward, values: dV ---------------------------------------------------------------------------
 //   dv_j = sum_{i>=j, same stretch} s_ij^2 ghat_i + R_m^T phi(k_j)
 // acc[vb][jb] = dV^T: 16 value columns x 16 keys.
 // Body for the 64 keys of token half `wv`; the block's K rows are already staged in sm.xb.
-template <int RING_TILES, int NW, bool DORDER>
+template <int RING_TILES, int NW, bool DORDER, bool GATED>
 __device__ __forceinline__ void dv_body(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
                                         const bf16_t* __restrict__ Ght, const bf16_t* __restrict__ RtC,
-                                        bf16_t* __restrict__ dV, int T, int cs, float scale, ChunkSmem<RING_TILES>& sm, int wv,
-                                        int wr, int lane) {
+                                        bf16_t* __restrict__ dV, int T, int cs, float scale, const float* __restrict__ bl,
+                                        const float* __restrict__ kfac, ChunkSmem<RING_TILES>& sm, int wv, int wr, int lane) {
     const XbRow* Xb = sm.xb;
     const int r16 = lane & 15, g = lane >> 4;
     const int bh = blockIdx.y;
@@ -743,6 +812,9 @@ __device__ __forceinline__ void dv_body(const bf16_t* __restrict__ Q, const bf16
 #pragma unroll
         for (int jb = 0; jb < 4; ++jb) acc[vb][jb] = ZERO4;
 
+    float blk[4] = {0.f, 0.f, 0.f, 0.f};
+    if (GATED) load_cols(blk, bl, head_tok + j0 + 64 * wv, r16);
+
     const int q_hi = (m + 1) * cs;
     for (int qb0 = j0; qb0 < q_hi; qb0 += QBLK) {
         const bool diag = qb0 == j0;
@@ -753,6 +825,11 @@ __device__ __forceinline__ void dv_body(const bf16_t* __restrict__ Q, const bf16
             for (int ibq = 0; ibq < 2; ++ibq) {
                 const size_t qrow = head_tok + q0 + 16 * ibq + r16;
                 const bf16x8 qa0 = glb_frag(Q, qrow, 0, g), qa1 = glb_frag(Q, qrow, 1, g);
+                float blq[4] = {0.f, 0.f, 0.f, 0.f};
+                if (GATED) {
+                    const float4 b4 = *(const float4*)(bl + head_tok + q0 + 16 * ibq + 4 * g);
+                    blq[0] = b4.x; blq[1] = b4.y; blq[2] = b4.z; blq[3] = b4.w;
+                }
 #pragma unroll
                 for (int jb = 0; jb < 4; ++jb) {
                     const int krow = 64 * wv + 16 * jb + r16;
@@ -761,6 +838,7 @@ __device__ __forceinline__ void dv_body(const bf16_t* __restrict__ Q, const bf16
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         float av = s2 * c[r] * c[r];
+                        if (GATED) av *= __expf(blq[r] - blk[jb]);
                         if (diag && q0 + 16 * ibq + 4 * g + r < j0 + krow) av = 0.f;
                         af[jb].v[4 * ibq + r] = (__bf16)av;
                     }
@@ -774,8 +852,11 @@ __device__ __forceinline__ void dv_body(const bf16_t* __restrict__ Q, const bf16
             }
         }
     }
-    if (m < nstate - 1)
-        readout<RING_TILES, NW, DORDER>(acc, RtC + (size_t)(bh * nstate + m) * STATE_ELEMS, sm, 1.f, wv, wr, lane);
+    if (m < nstate - 1) {
+        float kf[4] = {1.f, 1.f, 1.f, 1.f};
+        if (GATED) load_cols(kf, kfac, head_tok + j0 + 64 * wv, r16);
+        readout<RING_TILES, NW, DORDER, GATED>(acc, RtC + (size_t)(bh * nstate + m) * STATE_ELEMS, sm, 1.f, wv, wr, lane, kf);
+    }
 #pragma unroll
     for (int jb = 0; jb < 4; ++jb) {
         const size_t row = head_tok + j0 + 64 * wv + 16 * jb + r16;
@@ -789,16 +870,6 @@ __device__ __forceinline__ void dv_body(const bf16_t* __restrict__ Q, const bf16
     }
 }
 
-__global__ __launch_bounds__(128, 2) void k_mfma_bwd_dv(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
-                                                        const bf16_t* __restrict__ Ght, const bf16_t* __restrict__ RtC,
-                                                        bf16_t* __restrict__ dV, int T, int cs, float scale) {
-    __shared__ __attribute__((aligned(16))) ChunkSmem<RING_RO> sm;
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    stage_rows(sm.xb, K, (size_t)blockIdx.y * T + blockIdx.x * QBLK, tid);
-    __syncthreads();
-    dv_body<RING_RO, 2, false>(Q, K, Ght, RtC, dV, T, cs, scale, sm, wv, wv, lane);
-}
-
 // ---- backward, keys and values in one pass over R ------------------------------------------------
 // dK and dV both stream the state gradient R_m of their chunk.  Here one workgroup of four waves
 // streams it once: waves 0, 1 run the dK body and waves 2, 3 the dV body for the same 128 keys,
@@ -806,29 +877,39 @@ __global__ __launch_bounds__(128, 2) void k_mfma_bwd_dv(const bf16_t* __restrict
 // in the d phi order; the read-out does not care about either).  The two bodies execute the same
 // number of barriers.
 constexpr int RING_KV = 4;
+template <bool GATED>
 __global__ __launch_bounds__(256, 2) void k_mfma_bwd_dkdv(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
                                                           const bf16_t* __restrict__ V, const bf16_t* __restrict__ Gh,
                                                           const float* __restrict__ gz, const bf16_t* __restrict__ Qt,
                                                           const bf16_t* __restrict__ Ght, const bf16_t* __restrict__ RtC,
                                                           const bf16_t* __restrict__ Omg, bf16_t* __restrict__ dK,
-                                                          bf16_t* __restrict__ dV, int T, int cs, float scale) {
+                                                          bf16_t* __restrict__ dV, int T, int cs, float scale,
+                                                          const float* __restrict__ bl, const float* __restrict__ kfac,
+                                                          float* __restrict__ kdk) {
     __shared__ __attribute__((aligned(16))) ChunkSmem<RING_KV> sm;
     const int tid = threadIdx.x, lane = tid & 63, w4 = tid >> 6;
     stage_rows(sm.xb, K, (size_t)blockIdx.y * T + blockIdx.x * QBLK, tid, 256);
     __syncthreads();
     if (w4 < 2)
-        dk_body<RING_KV, 4>(Q, K, V, Gh, gz, Qt, RtC, Omg, dK, T, cs, scale, sm, w4, w4, lane);
+        dk_body<RING_KV, 4, GATED>(Q, K, V, Gh, gz, Qt, RtC, Omg, dK, T, cs, scale, bl, kfac, kdk, sm, w4, w4, lane);
     else
-        dv_body<RING_KV, 4, true>(Q, K, Ght, RtC, dV, T, cs, scale, sm, w4 - 2, w4, lane);
+        dv_body<RING_KV, 4, true, GATED>(Q, K, Ght, RtC, dV, T, cs, scale, bl, kfac, sm, w4 - 2, w4, lane);
 }
 
 }  // namespace
 
+// `gate`: bl and the state-term decay (qfac for the query-side kernels, kfac for the key-side one),
+// both null when the problem is not gated
 bool launch_fwd_chunk(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* Vt, const bf16_t* stC,
-                      const bf16_t* gam, bf16_t* O, float* Z, int BH, int T, int cs, float scale, int normalize) {
+                      const bf16_t* gam, bf16_t* O, float* Z, int BH, int T, int cs, float scale, int normalize,
+                      const float* bl, const float* qfac) {
     LaunchScope ls("mfma_fwd_chunk", s);
-    hipLaunchKernelGGL(k_mfma_fwd_chunk, dim3(T / QBLK, BH), dim3(128), 0, s, Q, K, Vt, stC, gam, O, Z, T, cs, scale,
-                       normalize);
+    if (bl != nullptr)
+        hipLaunchKernelGGL(k_mfma_fwd_chunk<true>, dim3(T / QBLK, BH), dim3(128), 0, s, Q, K, Vt, stC, gam, O, Z, T, cs, scale,
+                           normalize, bl, qfac);
+    else
+        hipLaunchKernelGGL(k_mfma_fwd_chunk<false>, dim3(T / QBLK, BH), dim3(128), 0, s, Q, K, Vt, stC, gam, O, Z, T, cs, scale,
+                           normalize, bl, qfac);
     return launch_ok();
 }
 
@@ -842,35 +923,27 @@ bool launch_bwd_prep(hipStream_t s, const bf16_t* dO, const bf16_t* O, const flo
 
 bool launch_bwd_dq(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* V, const bf16_t* Gh,
                    const float* gz, const bf16_t* Kt, const bf16_t* stC, const bf16_t* gam, bf16_t* dQ, int BH, int T,
-                   int cs, float scale) {
+                   int cs, float scale, const float* bl, const float* qfac, float* qdq) {
     LaunchScope ls("mfma_bwd_dq", s);
-    hipLaunchKernelGGL(k_mfma_bwd_dq, dim3(T / QBLK, BH), dim3(128), 0, s, Q, K, V, Gh, gz, Kt, stC, gam, dQ, T, cs,
-                       scale);
+    if (bl != nullptr)
+        hipLaunchKernelGGL(k_mfma_bwd_dq<true>, dim3(T / QBLK, BH), dim3(128), 0, s, Q, K, V, Gh, gz, Kt, stC, gam, dQ, T, cs,
+                           scale, bl, qfac, qdq);
+    else
+        hipLaunchKernelGGL(k_mfma_bwd_dq<false>, dim3(T / QBLK, BH), dim3(128), 0, s, Q, K, V, Gh, gz, Kt, stC, gam, dQ, T, cs,
+                           scale, bl, qfac, qdq);
     return launch_ok();
 }
 
 bool launch_bwd_dkdv(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* V, const bf16_t* Gh, const float* gz,
                      const bf16_t* Qt, const bf16_t* Ght, const bf16_t* rtC, const bf16_t* omg, bf16_t* dK, bf16_t* dV, int BH,
-                     int T, int cs, float scale) {
+                     int T, int cs, float scale, const float* bl, const float* kfac, float* kdk) {
     LaunchScope ls("mfma_bwd_dkdv", s);
-    hipLaunchKernelGGL(k_mfma_bwd_dkdv, dim3(T / QBLK, BH), dim3(256), 0, s, Q, K, V, Gh, gz, Qt, Ght, rtC, omg, dK, dV, T, cs,
-                       scale);
-    return launch_ok();
-}
-
-bool launch_bwd_dk(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* V, const bf16_t* Gh,
-                   const float* gz, const bf16_t* Qt, const bf16_t* rtC, const bf16_t* omg, bf16_t* dK, int BH, int T,
-                   int cs, float scale) {
-    LaunchScope ls("mfma_bwd_dk", s);
-    hipLaunchKernelGGL(k_mfma_bwd_dk, dim3(T / QBLK, BH), dim3(128), 0, s, Q, K, V, Gh, gz, Qt, rtC, omg, dK, T, cs,
-                       scale);
-    return launch_ok();
-}
-
-bool launch_bwd_dv(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* Ght, const bf16_t* rtC,
-                   bf16_t* dV, int BH, int T, int cs, float scale) {
-    LaunchScope ls("mfma_bwd_dv", s);
-    hipLaunchKernelGGL(k_mfma_bwd_dv, dim3(T / QBLK, BH), dim3(128), 0, s, Q, K, Ght, rtC, dV, T, cs, scale);
+    if (bl != nullptr)
+        hipLaunchKernelGGL(k_mfma_bwd_dkdv<true>, dim3(T / QBLK, BH), dim3(256), 0, s, Q, K, V, Gh, gz, Qt, Ght, rtC, omg, dK,
+                           dV, T, cs, scale, bl, kfac, kdk);
+    else
+        hipLaunchKernelGGL(k_mfma_bwd_dkdv<false>, dim3(T / QBLK, BH), dim3(256), 0, s, Q, K, V, Gh, gz, Qt, Ght, rtC, omg, dK,
+                           dV, T, cs, scale, bl, kfac, kdk);
     return launch_ok();
 }
 

@@ -19,11 +19,20 @@ namespace {
 // accesses stay dense (rows of a plain [DH][T] transpose would sit a power of two apart and
 // pile onto the same memory channel).
 
-__global__ __launch_bounds__(256) void k_transpose(const bf16_t* __restrict__ in, bf16_t* __restrict__ out, int T) {
+// `fac` (gating, may be null): token t is multiplied by sqrt(fac[t]) on the way.  For p = 2 a
+// weight w on phi(x) is the same as sqrt(w) on x, so the scans of a gated problem read copies
+// scaled this way and need no per-token weights of their own.
+__global__ __launch_bounds__(256) void k_transpose(const bf16_t* __restrict__ in, bf16_t* __restrict__ out, int T,
+                                                   const float* __restrict__ fac) {
     __shared__ bf16_t tile[TBLK][DH + 2];
     const int bh = blockIdx.y, blk = blockIdx.x, tid = threadIdx.x;
     const bf16_t* src = in + ((size_t)bh * T + (size_t)blk * TBLK) * DH;
-    for (int e = tid; e < TBLK * DH; e += 256) tile[e / DH][e % DH] = src[e];
+    if (fac == nullptr) {
+        for (int e = tid; e < TBLK * DH; e += 256) tile[e / DH][e % DH] = src[e];
+    } else {
+        const float* f = fac + (size_t)bh * T + (size_t)blk * TBLK;
+        for (int e = tid; e < TBLK * DH; e += 256) tile[e / DH][e % DH] = f32_to_bf16(bf16_to_f32(src[e]) * sqrtf(f[e / DH]));
+    }
     __syncthreads();
     bf16_t* dst = out + ((size_t)bh * (T / TBLK) + blk) * DH * TBLK;
     for (int e = tid; e < TBLK * DH; e += 256) dst[e] = tile[e % TBLK][e / TBLK];
@@ -190,7 +199,7 @@ template <bool GAMMA, bool REV, bool EVERY>
 __device__ __forceinline__ void scan_body(const bf16_t* __restrict__ Xt, const bf16_t* __restrict__ Yt,
                                           const float* __restrict__ wgt, bf16_t* __restrict__ StC,
                                           bf16_t* __restrict__ Gam, int T, int cs,
-                                          float out_scale, ScanSmem& sm, int pair, int bh) {
+                                          float out_scale, const float* __restrict__ lam, ScanSmem& sm, int pair, int bh) {
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int r16 = lane & 15, g = lane >> 4;
     const int nstate = T / cs;
@@ -312,6 +321,13 @@ __device__ __forceinline__ void scan_body(const bf16_t* __restrict__ Xt, const b
         StateOut so_;                                                                         \
         if (EVERY) pack_state(so_, REV ? edge_ / cs - 1 : edge_ / cs);                        \
         else if (edge_ % cs == 0) write_state(REV ? edge_ / cs - 1 : edge_ / cs);             \
+        if (lam != nullptr && (EVERY || edge_ % cs == 0)) {                                   \
+            /* gated: the sum decays across the chunk that is about to be added */           \
+            const float l_ = lam[(size_t)bh * nstate + (REV ? edge_ / cs - 1 : edge_ / cs)];  \
+            _Pragma("unroll") for (int rbk_ = 0; rbk_ < 2; ++rbk_)                            \
+                _Pragma("unroll") for (int cb_ = 0; cb_ < 4; ++cb_)                           \
+                    _Pragma("unroll") for (int r_ = 0; r_ < 4; ++r_) acc[rbk_][cb_][r_] *= l_; \
+        }                                                                                     \
         PA_PROBE(1)                                                                           \
         PA_FILL_X(BUF, 0, x0_##J) PA_FILL_X(BUF, 1, x1_##J)                                   \
         PA_FILL_X(BUF, 2, x2_##J) PA_FILL_X(BUF, 3, x3_##J)                                   \
@@ -351,7 +367,7 @@ template <bool REV, bool EVERY>
 __global__ __launch_bounds__(256) void k_mfma_scan(const bf16_t* __restrict__ Xt, const bf16_t* __restrict__ Yt,
                                                    const float* __restrict__ wgt, bf16_t* __restrict__ StC,
                                                    bf16_t* __restrict__ Gam, int T, int cs, float out_scale,
-                                                   int nheads) {
+                                                   int nheads, const float* __restrict__ lam) {
     extern __shared__ __attribute__((aligned(16))) unsigned char scan_smem_raw[];
     ScanSmem& sm = *reinterpret_cast<ScanSmem*>(scan_smem_raw);
     // A scan workgroup is a long chain of dependent steps and the critical path of its pass; waves
@@ -371,9 +387,9 @@ __global__ __launch_bounds__(256) void k_mfma_scan(const bf16_t* __restrict__ Xt
     for (int i = 0; i < (int)(blockIdx.x % 32); ++i) __builtin_amdgcn_s_sleep(PA_STAGGER);
 #endif
     if (pair == NPAIR)
-        scan_body<true, REV, EVERY>(Xt, Yt, wgt, StC, Gam, T, cs, out_scale, sm, pair, bh);
+        scan_body<true, REV, EVERY>(Xt, Yt, wgt, StC, Gam, T, cs, out_scale, lam, sm, pair, bh);
     else
-        scan_body<false, REV, EVERY>(Xt, Yt, wgt, StC, Gam, T, cs, out_scale, sm, pair, bh);
+        scan_body<false, REV, EVERY>(Xt, Yt, wgt, StC, Gam, T, cs, out_scale, lam, sm, pair, bh);
 }
 
 }  // namespace
@@ -386,32 +402,32 @@ static bool allow_smem(F* fn, size_t bytes) {
     return e == hipSuccess;
 }
 
-bool launch_transpose(hipStream_t s, const bf16_t* in, bf16_t* out, int BH, int T) {
+bool launch_transpose(hipStream_t s, const bf16_t* in, bf16_t* out, int BH, int T, const float* fac) {
     LaunchScope ls("mfma_transpose", s);
-    hipLaunchKernelGGL(k_transpose, dim3(T / TBLK, BH), dim3(256), 0, s, in, out, T);
+    hipLaunchKernelGGL(k_transpose, dim3(T / TBLK, BH), dim3(256), 0, s, in, out, T, fac);
     return launch_ok();
 }
 
 template <bool REV, bool EVERY>
 static bool launch_scan_t(const char* name, hipStream_t s, const bf16_t* Xt, const bf16_t* Yt, const float* wgt,
-                          bf16_t* stC, bf16_t* gam, int BH, int T, int cs, float out_scale) {
+                          bf16_t* stC, bf16_t* gam, int BH, int T, int cs, float out_scale, const float* lam) {
     if (!allow_smem(k_mfma_scan<REV, EVERY>, scan_smem_bytes<REV>())) return false;
     LaunchScope ls(name, s);
     const int total = (NPAIR + 1) * BH;
     hipLaunchKernelGGL((k_mfma_scan<REV, EVERY>), dim3(8 * ((total + 7) / 8)), dim3(256), scan_smem_bytes<REV>(), s, Xt, Yt, wgt,
-                       stC, gam, T, cs, out_scale, BH);
+                       stC, gam, T, cs, out_scale, BH, lam);
     return launch_ok();
 }
 
 bool launch_scan(const char* name, hipStream_t s, bool rev, const bf16_t* Xt, const bf16_t* Yt, const float* wgt, bf16_t* stC,
-                 bf16_t* gam, int BH, int T, int cs, float out_scale) {
+                 bf16_t* gam, int BH, int T, int cs, float out_scale, const float* lam) {
     const bool every = cs == SCAN_TOK;
     if (!rev) {
-        if (every) return launch_scan_t<false, true>(name, s, Xt, Yt, wgt, stC, gam, BH, T, cs, out_scale);
-        return launch_scan_t<false, false>(name, s, Xt, Yt, wgt, stC, gam, BH, T, cs, out_scale);
+        if (every) return launch_scan_t<false, true>(name, s, Xt, Yt, wgt, stC, gam, BH, T, cs, out_scale, lam);
+        return launch_scan_t<false, false>(name, s, Xt, Yt, wgt, stC, gam, BH, T, cs, out_scale, lam);
     }
-    if (every) return launch_scan_t<true, true>(name, s, Xt, Yt, wgt, stC, gam, BH, T, cs, out_scale);
-    return launch_scan_t<true, false>(name, s, Xt, Yt, wgt, stC, gam, BH, T, cs, out_scale);
+    if (every) return launch_scan_t<true, true>(name, s, Xt, Yt, wgt, stC, gam, BH, T, cs, out_scale, lam);
+    return launch_scan_t<true, false>(name, s, Xt, Yt, wgt, stC, gam, BH, T, cs, out_scale, lam);
 }
 
 }  // namespace mfma

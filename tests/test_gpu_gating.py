@@ -19,6 +19,12 @@ CASES = [
     ("f32", "generic", 2, 1, 1, 130, 10, 26, False, 1.3, 0.3),      # strong decay, ragged sizes
     ("bf16", "generic", 2, 1, 2, 384, 32, 128, True, 1.0, 0.02),
     ("bf16", "generic", 4, 1, 1, 256, 16, 64, True, 1.0, 0.02),
+    ("bf16", "mfma", 2, 1, 2, 512, 64, 128, True, 1.0, 0.02),
+    ("bf16", "mfma", 2, 1, 1, 1024, 64, 256, True, 1.0, 0.01),     # two query blocks per chunk
+    ("bf16", "mfma", 2, 1, 1, 128, 64, 128, True, 1.0, 0.05),      # a single chunk
+    ("bf16", "mfma", 2, 1, 2, 768, 64, 128, True, 0.6, 0.1),       # scale != 1, stronger decay
+    ("bf16", "mfma", 2, 1, 1, 512, 64, 128, False, 1.0, 0.02),     # un-normalised
+    ("bf16", "mfma", 2, 1, 1, 1536, 64, 512, True, 1.0, 0.005),
 ]
 
 
@@ -30,6 +36,10 @@ def test_gated_forward_backward(case):
     Q, K, V, G = inputs.make_qkvg(B, H, T, d, seed=seed, dtype=dtype)
     lg = inputs.make_log_gates(B, H, T, seed + 500, decay)
     got = run_fwd_bwd(Q, K, V, G, p, chunk, dtype, normalize, scale, impl=impl, log_g=lg)
+    if impl == "mfma":   # also with the states kept from the forward pass
+        kept = run_fwd_bwd(Q, K, V, G, p, chunk, dtype, normalize, scale, impl=impl, log_g=lg, keep_state=True)
+        for key in got:
+            np.testing.assert_array_equal(kept[key], got[key], err_msg=f"keep_state changes {key}")
     O, Z = orc.fwd_bhtd(Q, K, V, p, None, normalize, scale, log_g=lg.astype(np.float64))
     dQ, dK, dV, dL = orc.bwd_bhtd(Q, K, V, G, p, None, normalize, scale, log_g=lg.astype(np.float64))
     assert_close(got, dict(O=O, Z=Z, dQ=dQ, dK=dK, dV=dV, dlog_g=dL), dtype, f"gated {case}")
