@@ -42,18 +42,22 @@ __global__ __launch_bounds__(GT) void k_gate_prep(const float* __restrict__ log_
     if (tid == 0) lam[(size_t)bh * (T / chunk) + n] = __expf(total);
 }
 
-// dL/db_i = (q_i . dq_i - k_i . dk_i) / p; 16 lanes per row
+// dL/db_i = (q_i . dq_i - k_i . dk_i) / p; 16 lanes per row.  use_q = 0 drops the first term:
+// with the sum normalisation it is the row sum of e_ij a_ij = ghat_i . N_i + gz_i Z_i, which is
+// zero identically, and what the rounded dq would put in its place is noise.
 template <typename T>
 __global__ __launch_bounds__(256) void k_gate_db(const T* __restrict__ Q, const T* __restrict__ dQ, const T* __restrict__ K,
                                                  const T* __restrict__ dK, float* __restrict__ db, long long rows, int d,
-                                                 float inv_p) {
+                                                 float inv_p, int use_q) {
     const long long row = (long long)blockIdx.x * 16 + (threadIdx.x >> 4);
     const int c = threadIdx.x & 15;
     float acc = 0.f;
     if (row < rows) {
         const size_t o = (size_t)row * d;
-        for (int a = c; a < d; a += 16)
-            acc += io<T>::ld(Q + o + a) * io<T>::ld(dQ + o + a) - io<T>::ld(K + o + a) * io<T>::ld(dK + o + a);
+        for (int a = c; a < d; a += 16) {
+            acc -= io<T>::ld(K + o + a) * io<T>::ld(dK + o + a);
+            if (use_q) acc += io<T>::ld(Q + o + a) * io<T>::ld(dQ + o + a);
+        }
     }
     acc += __shfl_xor(acc, 1);
     acc += __shfl_xor(acc, 2);
@@ -63,15 +67,17 @@ __global__ __launch_bounds__(256) void k_gate_db(const T* __restrict__ Q, const 
 }
 
 // dlog_g[t] = sum_{i >= t} db[i] per head: one workgroup per head, each thread a run of tokens
-// (db2 null: db holds dL/db_i.  Else dL/db_i = (db[i] - db2[i]) * inv_p.)
+// (db2 null: db holds dL/db_i.  Else dL/db_i = (use_q * db[i] - db2[i]) * inv_p.)
 __global__ __launch_bounds__(1024) void k_gate_revsum(const float* __restrict__ db, const float* __restrict__ db2,
-                                                      float inv_p, float* __restrict__ dlog_g, int T) {
+                                                      float inv_p, int use_q, float* __restrict__ dlog_g, int T) {
     __shared__ float part[1024];
     const int bh = blockIdx.x, tid = threadIdx.x;
     const size_t base = (size_t)bh * T;
     const int per = (T + 1023) / 1024;
     const int lo = min(tid * per, T), hi = min(lo + per, T);
-    auto term = [&](int i) { return db2 != nullptr ? (db[base + i] - db2[base + i]) * inv_p : db[base + i]; };
+    auto term = [&](int i) {
+        return db2 != nullptr ? ((use_q ? db[base + i] : 0.f) - db2[base + i]) * inv_p : db[base + i];
+    };
     float s = 0.f;
     for (int i = lo; i < hi; ++i) s += term(i);
     part[tid] = s;
@@ -130,16 +136,18 @@ pa_status gate_gradient(const Ctx& c, const void* Q, const void* K, const void* 
         LaunchScope ls("gate_db", c.stream);
         if (pr.dtype == PA_DTYPE_F32)
             hipLaunchKernelGGL((k_gate_db<float>), dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, c.stream, (const float*)Q,
-                               (const float*)dQ, (const float*)K, (const float*)dK, c.gate.db, rows, pr.d, 1.f / pr.p);
+                               (const float*)dQ, (const float*)K, (const float*)dK, c.gate.db, rows, pr.d, 1.f / pr.p, pr.normalize ? 0 : 1);
         else
             hipLaunchKernelGGL((k_gate_db<bf16_t>), dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, c.stream, (const bf16_t*)Q,
-                               (const bf16_t*)dQ, (const bf16_t*)K, (const bf16_t*)dK, c.gate.db, rows, pr.d, 1.f / pr.p);
+                               (const bf16_t*)dQ, (const bf16_t*)K, (const bf16_t*)dK, c.gate.db, rows, pr.d, 1.f / pr.p,
+                               pr.normalize ? 0 : 1);
     }
     if (!have_dots && !launch_ok()) return PA_ERR_HIP;
     {
         LaunchScope ls("gate_revsum", c.stream);
         hipLaunchKernelGGL(k_gate_revsum, dim3(pr.B * pr.H), dim3(1024), 0, c.stream, c.gate.db,
-                           have_dots ? (const float*)c.gate.db2 : (const float*)nullptr, 1.f / pr.p, dlog_g, pr.T);
+                           have_dots ? (const float*)c.gate.db2 : (const float*)nullptr, 1.f / pr.p, pr.normalize ? 0 : 1, dlog_g,
+                           pr.T);
     }
     return launch_ok() ? PA_OK : PA_ERR_HIP;
 }

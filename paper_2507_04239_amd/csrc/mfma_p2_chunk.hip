@@ -468,8 +468,12 @@ __global__ __launch_bounds__(128, 2) void k_mfma_fwd_chunk(const bf16_t* __restr
                         float pv = s2 * c[r] * c[r];
                         if (GATED) pv *= __expf(blq[ib] - blk[r]);
                         if (diag && key0 + 16 * jb + 4 * g + r > i0 + qrow) pv = 0.f;
-                        zsum[ib] += pv;
-                        pf[ib].v[4 * jb + r] = (__bf16)pv;
+                        // the denominator sums the ROUNDED weights, the ones the numerator uses: the
+                        // output is then an exact convex combination (a row that sees one key returns
+                        // that value bit for bit, which the backward pass's cancellations rely on)
+                        const __bf16 pb = (__bf16)pv;
+                        zsum[ib] += (float)pb;
+                        pf[ib].v[4 * jb + r] = pb;
                     }
                 }
             }

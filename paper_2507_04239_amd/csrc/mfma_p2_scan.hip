@@ -195,7 +195,7 @@ __device__ __forceinline__ void scan_stage(f32x4 (&acc)[2][4], const ScanSmem& s
 // and the compiler knows how many vector-memory operations separate a stage's loads from their
 // use; behind a branch it has to assume none, and waits for all but the newest loads, i.e. also
 // for the previous stage's stores.
-template <bool GAMMA, bool REV, bool EVERY>
+template <bool GAMMA, bool REV, bool EVERY, bool GATED>
 __device__ __forceinline__ void scan_body(const bf16_t* __restrict__ Xt, const bf16_t* __restrict__ Yt,
                                           const float* __restrict__ wgt, bf16_t* __restrict__ StC,
                                           bf16_t* __restrict__ Gam, int T, int cs,
@@ -321,7 +321,7 @@ __device__ __forceinline__ void scan_body(const bf16_t* __restrict__ Xt, const b
         StateOut so_;                                                                         \
         if (EVERY) pack_state(so_, REV ? edge_ / cs - 1 : edge_ / cs);                        \
         else if (edge_ % cs == 0) write_state(REV ? edge_ / cs - 1 : edge_ / cs);             \
-        if (lam != nullptr && (EVERY || edge_ % cs == 0)) {                                   \
+        if (GATED && (EVERY || edge_ % cs == 0)) {                                            \
             /* gated: the sum decays across the chunk that is about to be added */           \
             const float l_ = lam[(size_t)bh * nstate + (REV ? edge_ / cs - 1 : edge_ / cs)];  \
             _Pragma("unroll") for (int rbk_ = 0; rbk_ < 2; ++rbk_)                            \
@@ -363,7 +363,7 @@ __device__ __forceinline__ void scan_body(const bf16_t* __restrict__ Xt, const b
     write_state(REV ? 0 : nstate - 1);
 }
 
-template <bool REV, bool EVERY>
+template <bool REV, bool EVERY, bool GATED>
 __global__ __launch_bounds__(256) void k_mfma_scan(const bf16_t* __restrict__ Xt, const bf16_t* __restrict__ Yt,
                                                    const float* __restrict__ wgt, bf16_t* __restrict__ StC,
                                                    bf16_t* __restrict__ Gam, int T, int cs, float out_scale,
@@ -387,9 +387,9 @@ __global__ __launch_bounds__(256) void k_mfma_scan(const bf16_t* __restrict__ Xt
     for (int i = 0; i < (int)(blockIdx.x % 32); ++i) __builtin_amdgcn_s_sleep(PA_STAGGER);
 #endif
     if (pair == NPAIR)
-        scan_body<true, REV, EVERY>(Xt, Yt, wgt, StC, Gam, T, cs, out_scale, lam, sm, pair, bh);
+        scan_body<true, REV, EVERY, GATED>(Xt, Yt, wgt, StC, Gam, T, cs, out_scale, lam, sm, pair, bh);
     else
-        scan_body<false, REV, EVERY>(Xt, Yt, wgt, StC, Gam, T, cs, out_scale, lam, sm, pair, bh);
+        scan_body<false, REV, EVERY, GATED>(Xt, Yt, wgt, StC, Gam, T, cs, out_scale, lam, sm, pair, bh);
 }
 
 }  // namespace
@@ -408,13 +408,13 @@ bool launch_transpose(hipStream_t s, const bf16_t* in, bf16_t* out, int BH, int 
     return launch_ok();
 }
 
-template <bool REV, bool EVERY>
+template <bool REV, bool EVERY, bool GATED>
 static bool launch_scan_t(const char* name, hipStream_t s, const bf16_t* Xt, const bf16_t* Yt, const float* wgt,
                           bf16_t* stC, bf16_t* gam, int BH, int T, int cs, float out_scale, const float* lam) {
-    if (!allow_smem(k_mfma_scan<REV, EVERY>, scan_smem_bytes<REV>())) return false;
+    if (!allow_smem(k_mfma_scan<REV, EVERY, GATED>, scan_smem_bytes<REV>())) return false;
     LaunchScope ls(name, s);
     const int total = (NPAIR + 1) * BH;
-    hipLaunchKernelGGL((k_mfma_scan<REV, EVERY>), dim3(8 * ((total + 7) / 8)), dim3(256), scan_smem_bytes<REV>(), s, Xt, Yt, wgt,
+    hipLaunchKernelGGL((k_mfma_scan<REV, EVERY, GATED>), dim3(8 * ((total + 7) / 8)), dim3(256), scan_smem_bytes<REV>(), s, Xt, Yt, wgt,
                        stC, gam, T, cs, out_scale, BH, lam);
     return launch_ok();
 }
@@ -422,12 +422,22 @@ static bool launch_scan_t(const char* name, hipStream_t s, const bf16_t* Xt, con
 bool launch_scan(const char* name, hipStream_t s, bool rev, const bf16_t* Xt, const bf16_t* Yt, const float* wgt, bf16_t* stC,
                  bf16_t* gam, int BH, int T, int cs, float out_scale, const float* lam) {
     const bool every = cs == SCAN_TOK;
-    if (!rev) {
-        if (every) return launch_scan_t<false, true>(name, s, Xt, Yt, wgt, stC, gam, BH, T, cs, out_scale, lam);
-        return launch_scan_t<false, false>(name, s, Xt, Yt, wgt, stC, gam, BH, T, cs, out_scale, lam);
+#define PA_GO(R, E, G) return launch_scan_t<R, E, G>(name, s, Xt, Yt, wgt, stC, gam, BH, T, cs, out_scale, lam);
+    if (lam == nullptr) {
+        if (!rev) {
+            if (every) PA_GO(false, true, false)
+            PA_GO(false, false, false)
+        }
+        if (every) PA_GO(true, true, false)
+        PA_GO(true, false, false)
     }
-    if (every) return launch_scan_t<true, true>(name, s, Xt, Yt, wgt, stC, gam, BH, T, cs, out_scale, lam);
-    return launch_scan_t<true, false>(name, s, Xt, Yt, wgt, stC, gam, BH, T, cs, out_scale, lam);
+    if (!rev) {
+        if (every) PA_GO(false, true, true)
+        PA_GO(false, false, true)
+    }
+    if (every) PA_GO(true, true, true)
+    PA_GO(true, false, true)
+#undef PA_GO
 }
 
 }  // namespace mfma
