@@ -138,6 +138,8 @@ def main():
     ap.add_argument("--serial-kernels", action="store_true",
                     help="run every step with the library's per-kernel events on, i.e. kernels back to back with no "
                          "overlap between streams (for a rocprofv3 kernel trace whose averages are each kernel's own)")
+    ap.add_argument("--gated", action="store_true",
+                    help="time the gated layer (per-timestep log-gates, mean decay 0.02 per step) instead of the headline one")
     ap.add_argument("--recompute-states", action="store_true",
                     help="backward pass rebuilds the chunk states instead of reusing the forward pass's workspace")
     args = ap.parse_args()
@@ -157,7 +159,11 @@ def main():
     del Q, K, V, G
     p, chunk = w["p"], w["chunk"]
     keep = not args.recompute_states
-    prob = binding.make_problem(w["B"], w["H"], w["T"], w["d"], w["d"], p, chunk, True, 1.0, w["dtype"], args.impl, keep)
+    tl = None
+    if args.gated:
+        tl = torch.from_numpy(inputs.make_log_gates(w["B"], w["H"], w["T"], 1500 + w["position"])).to(dev)
+    prob = binding.make_problem(w["B"], w["H"], w["T"], w["d"], w["d"], p, chunk, True, 1.0, w["dtype"], args.impl, keep,
+                                args.gated)
     ws_bytes = max(binding.power_attn_workspace_bytes(prob, True), binding.power_attn_workspace_bytes(prob, False))
     ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
     O = torch.empty_like(tv)
@@ -165,8 +171,8 @@ def main():
     grads = (torch.empty_like(tq), torch.empty_like(tk), torch.empty_like(tv))
 
     def step():
-        power_attn_fwd(tq, tk, tv, p, chunk, impl=args.impl, workspace=ws, out=O, out_z=Z, keep_state=keep)
-        power_attn_bwd(tq, tk, tv, O, Z, tg, p, chunk, impl=args.impl, workspace=ws, out=grads, keep_state=keep)
+        power_attn_fwd(tq, tk, tv, p, chunk, impl=args.impl, workspace=ws, out=O, out_z=Z, keep_state=keep, log_g=tl)
+        power_attn_bwd(tq, tk, tv, O, Z, tg, p, chunk, impl=args.impl, workspace=ws, out=grads, keep_state=keep, log_g=tl)
 
     if args.serial_kernels:
         binding.profile_begin()
@@ -230,7 +236,7 @@ def main():
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": w["dtype"], "data": "synthetic",
         "config": {"workload": name, "B": w["B"], "H": w["H"], "T": w["T"], "d": w["d"], "p": p, "chunk": chunk,
-                   "normalize": True, "pass": "fwd+bwd", "impl": args.impl, "keep_state": keep, "serial_kernels": args.serial_kernels,
+                   "normalize": True, "pass": "fwd+bwd", "impl": args.impl, "keep_state": keep, "serial_kernels": args.serial_kernels, "gated": args.gated,
                    "state_rows": binding.power_attn_state_rows(prob)},
         "step_algorithmic_tflop": total_alg / 1e12,
         "step_frac_of_bf16_mfma_peak": total_alg / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS,

@@ -67,6 +67,7 @@ static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; 
 //   db2   [BH][T]       then: k_i . dk_i
 struct GateBuf {
     float *bl = nullptr, *qfac = nullptr, *kfac = nullptr, *lam = nullptr, *db = nullptr, *db2 = nullptr;
+    float* seg = nullptr;   // [BH][T/1024] scratch of the reverse running sum
 };
 
 struct Ctx {
