@@ -67,7 +67,7 @@ static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; 
 //   db2   [BH][T]       then: k_i . dk_i
 struct GateBuf {
     float *bl = nullptr, *qfac = nullptr, *kfac = nullptr, *lam = nullptr, *db = nullptr, *db2 = nullptr;
-    float* seg = nullptr;   // [BH][T/1024] scratch of the reverse running sum
+    float* xb = nullptr;    // [BH][T/chunk] backward: <R_m, S_{m+1}>, the pairs that straddle the end of chunk m (0 for the last)
 };
 
 struct Ctx {
@@ -82,7 +82,8 @@ struct Ctx {
 size_t gate_workspace_bytes(const pa_problem& pr, bool backward);
 GateBuf gate_buffers(const pa_problem& pr, bool backward, char* base);
 pa_status gate_prepare(const Ctx& c, const float* log_g);
-// have_dots: the family's kernels have already written q.dq into gate.db and k.dk into gate.db2
+// The family has already written gate.xb.  have_dots: its kernels have also written q.dq into gate.db and
+// k.dk into gate.db2 (else they are formed here from the outputs)
 pa_status gate_gradient(const Ctx& c, const void* Q, const void* K, const void* dQ, const void* dK, float* dlog_g,
                         bool have_dots);
 

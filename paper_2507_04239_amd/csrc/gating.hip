@@ -66,54 +66,41 @@ __global__ __launch_bounds__(256) void k_gate_db(const T* __restrict__ Q, const 
     if (row < rows && c == 0) db[row] = acc * inv_p;
 }
 
-// dlog_g[t] = sum_{i >= t} dL/db_i per head, in two passes over segments of SEG tokens: the sum of
-// every segment, then, per segment, the sums of the segments after it plus a suffix scan inside.
+// dlog_g[t] = sum_{i >= t} dL/db_i.  A running sum over the whole sequence would pile up the
+// rounding noise of tens of thousands of terms on a result that is local (only pairs within a few
+// decay lengths of t matter).  Instead: the part of the sum beyond the end of t's chunk m equals
+//     X_m = sum_{j <= end_m < i} e_ij a_ij = < R_m , S_{m+1} >,
+// the inner product of the two states that meet at that chunk boundary, which each kernel family
+// computes from its states (xb); only the part inside the chunk is summed here.
 // (db2 null: db holds dL/db_i.  Else dL/db_i = (use_q * db[i] - db2[i]) * inv_p.)
-constexpr int SEG = 1024;
-
 __device__ __forceinline__ float gate_term(const float* __restrict__ db, const float* __restrict__ db2, float inv_p,
                                            int use_q, size_t i) {
     return db2 != nullptr ? ((use_q ? db[i] : 0.f) - db2[i]) * inv_p : db[i];
 }
 
-__device__ __forceinline__ float block_sum(float x, float* red) {   // sum over the 1024 threads, in every thread
-    for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off);
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = x;
+__global__ __launch_bounds__(GT) void k_gate_finish(const float* __restrict__ db, const float* __restrict__ db2, float inv_p,
+                                                    int use_q, const float* __restrict__ xb, float* __restrict__ dlog_g,
+                                                    int T, int chunk) {
+    __shared__ float part[GT];
+    const int n = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x;
+    const size_t base = (size_t)bh * T + (size_t)n * chunk;
+    const int per = (chunk + GT - 1) / GT;
+    const int lo = min(tid * per, chunk), hi = min(lo + per, chunk);
+    float s = 0.f;
+    for (int i = lo; i < hi; ++i) s += gate_term(db, db2, inv_p, use_q, base + i);
+    part[tid] = s;
     __syncthreads();
-    float t = 0.f;
-    for (int w = 0; w < SEG / 64; ++w) t += red[w];
-    __syncthreads();
-    return t;
-}
-
-__global__ __launch_bounds__(SEG) void k_gate_segsum(const float* __restrict__ db, const float* __restrict__ db2, float inv_p,
-                                                     int use_q, float* __restrict__ segsum, int T) {
-    __shared__ float red[SEG / 64];
-    const int seg = blockIdx.x, bh = blockIdx.y, i = seg * SEG + threadIdx.x;
-    const float x = i < T ? gate_term(db, db2, inv_p, use_q, (size_t)bh * T + i) : 0.f;
-    const float t = block_sum(x, red);
-    if (threadIdx.x == 0) segsum[(size_t)bh * gridDim.x + seg] = t;
-}
-
-__global__ __launch_bounds__(SEG) void k_gate_revsum(const float* __restrict__ db, const float* __restrict__ db2, float inv_p,
-                                                     int use_q, const float* __restrict__ segsum,
-                                                     float* __restrict__ dlog_g, int T) {
-    __shared__ float red[SEG / 64];
-    __shared__ float part[SEG];
-    const int seg = blockIdx.x, nseg = gridDim.x, bh = blockIdx.y, tid = threadIdx.x, i = seg * SEG + tid;
-    // everything after this segment
-    float later = 0.f;
-    for (int s2 = seg + 1 + tid; s2 < nseg; s2 += SEG) later += segsum[(size_t)bh * nseg + s2];
-    later = block_sum(later, red);
-    part[tid] = i < T ? gate_term(db, db2, inv_p, use_q, (size_t)bh * T + i) : 0.f;
-    __syncthreads();
-    for (int off = 1; off < SEG; off <<= 1) {     // inclusive suffix scan inside the segment
-        const float add = tid + off < SEG ? part[tid + off] : 0.f;
+    for (int off = 1; off < GT; off <<= 1) {      // inclusive suffix scan of the per-thread sums
+        const float add = tid + off < GT ? part[tid + off] : 0.f;
         __syncthreads();
         part[tid] += add;
         __syncthreads();
     }
-    if (i < T) dlog_g[(size_t)bh * T + i] = part[tid] + later;
+    float run = xb[(size_t)bh * (T / chunk) + n] + (tid + 1 < GT ? part[tid + 1] : 0.f);
+    for (int i = hi - 1; i >= lo; --i) {
+        run += gate_term(db, db2, inv_p, use_q, base + i);
+        dlog_g[base + i] = run;
+    }
 }
 
 }  // namespace
@@ -122,8 +109,7 @@ size_t gate_workspace_bytes(const pa_problem& pr, bool backward) {
     if (!pr.gated) return 0;
     const size_t BH = (size_t)pr.B * pr.H;
     const size_t tok = align_up(BH * pr.T * sizeof(float), 256);
-    return (backward ? 5 : 3) * tok + align_up(BH * (pr.T / pr.chunk) * sizeof(float), 256) +
-           (backward ? align_up(BH * ((pr.T + SEG - 1) / SEG) * sizeof(float), 256) : 0);
+    return (backward ? 5 : 3) * tok + (backward ? 2 : 1) * align_up(BH * (pr.T / pr.chunk) * sizeof(float), 256);
 }
 
 GateBuf gate_buffers(const pa_problem& pr, bool backward, char* base) {
@@ -138,7 +124,7 @@ GateBuf gate_buffers(const pa_problem& pr, bool backward, char* base) {
     if (backward) {
         g.db = (float*)(base + 3 * tok + align_up(BH * (pr.T / pr.chunk) * sizeof(float), 256));
         g.db2 = g.db + tok / sizeof(float);
-        g.seg = g.db2 + tok / sizeof(float);
+        g.xb = g.db2 + tok / sizeof(float);
     }
     return g;
 }
@@ -167,17 +153,10 @@ pa_status gate_gradient(const Ctx& c, const void* Q, const void* K, const void* 
     }
     if (!have_dots && !launch_ok()) return PA_ERR_HIP;
     const float* d2 = have_dots ? (const float*)c.gate.db2 : (const float*)nullptr;
-    const int use_q = pr.normalize ? 0 : 1;
-    const dim3 grid((pr.T + SEG - 1) / SEG, pr.B * pr.H);
     {
-        LaunchScope ls("gate_segsum", c.stream);
-        hipLaunchKernelGGL(k_gate_segsum, grid, dim3(SEG), 0, c.stream, c.gate.db, d2, 1.f / pr.p, use_q, c.gate.seg, pr.T);
-    }
-    if (!launch_ok()) return PA_ERR_HIP;
-    {
-        LaunchScope ls("gate_revsum", c.stream);
-        hipLaunchKernelGGL(k_gate_revsum, grid, dim3(SEG), 0, c.stream, c.gate.db, d2, 1.f / pr.p, use_q,
-                           (const float*)c.gate.seg, dlog_g, pr.T);
+        LaunchScope ls("gate_finish", c.stream);
+        hipLaunchKernelGGL(k_gate_finish, dim3(pr.T / pr.chunk, pr.B * pr.H), dim3(GT), 0, c.stream, c.gate.db, d2, 1.f / pr.p,
+                           pr.normalize ? 0 : 1, (const float*)c.gate.xb, dlog_g, pr.T, pr.chunk);
     }
     return launch_ok() ? PA_OK : PA_ERR_HIP;
 }

@@ -547,6 +547,26 @@ __global__ __launch_bounds__(NT) void k_bwd_dkdv(const T* __restrict__ Q, const 
     }
 }
 
+// ---- gating: the pairs that straddle a chunk boundary -------------------------------------------
+// xb[bh][n] = < R_n , S_{n+1} > = sum_r St[n+1][r] . Rt[n][r] / m_r  (both hold the multiplicity
+// m_r; the inner product of the expanded vectors carries it once); 0 for the last chunk.
+__global__ __launch_bounds__(256) void k_gate_boundary(const float* __restrict__ St, const float* __restrict__ Rt,
+                                                       const float* __restrict__ mult, float* __restrict__ xb, long long D,
+                                                       int VP, int nchunk) {
+    __shared__ float red[4];
+    const int n = blockIdx.x, bh = blockIdx.y;
+    float acc = 0.f;
+    if (n < nchunk - 1) {
+        const float* S = St + ((size_t)bh * nchunk + n + 1) * D * VP;
+        const float* R = Rt + ((size_t)bh * nchunk + n) * D * VP;
+        for (long long e = threadIdx.x; e < D * VP; e += 256) acc += S[e] * R[e] / mult[e / VP];
+    }
+    for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) xb[(size_t)bh * nchunk + n] = red[0] + red[1] + red[2] + red[3];
+}
+
 // ---- host side -------------------------------------------------------------------------------
 
 struct Layout {
@@ -670,6 +690,12 @@ pa_status run_bwd(const Ctx& c, const Layout& L, const T* Q, const T* K, const T
                            (const float*)c.gate.qfac, (const float*)c.gate.lam);
     }
     PA_CHECK_LAUNCH();
+    if (pr.gated) {
+        LaunchScope ls("generic_gate_boundary", c.stream);
+        hipLaunchKernelGGL(k_gate_boundary, dim3(L.nchunk, (unsigned)BH), dim3(256), 0, c.stream, (const float*)St,
+                           (const float*)Rt, (const float*)mult, c.gate.xb, L.D, L.VP, L.nchunk);
+        PA_CHECK_LAUNCH();
+    }
     if (!allow_smem(k_bwd_dq<T, P, KX>, smem_bwd(pr)) || !allow_smem(k_bwd_dkdv<T, P, KX>, smem_bwd(pr))) return PA_ERR_HIP;
     {
         LaunchScope ls("generic_bwd_dq", c.stream);

@@ -91,5 +91,9 @@ bool launch_bwd_dkdv(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16
                      const bf16_t* Qt, const bf16_t* Ght, const bf16_t* rtC, const bf16_t* omg, bf16_t* dK, bf16_t* dV, int BH,
                      int T, int cs, float scale, const float* bl, const float* kfac, float* kdk);
 
+// gating: xb[bh][n] = the sum over the pairs that straddle the end of chunk n, from the stored states
+bool launch_gate_boundary(hipStream_t s, const bf16_t* stC, const bf16_t* rtC, const bf16_t* gam, const bf16_t* omg, float* xb,
+                          int BH, int nstate);
+
 }  // namespace mfma
 }  // namespace pa

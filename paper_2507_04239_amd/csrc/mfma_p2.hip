@@ -99,7 +99,7 @@ pa_status mfma_fwd(const Ctx& c, const void* Q, const void* K, const void* V, vo
 // once, default priority) so that dQ's workgroups fill the CUs under the scan.
 struct SideStream {
     hipStream_t stream = nullptr;
-    hipEvent_t fork = nullptr, join = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr, scanned = nullptr;
     bool ok = false;
     int device = -1;
 };
@@ -113,7 +113,8 @@ static SideStream side_stream() {
         s.device = dev;
         s.ok = hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking) == hipSuccess &&
                hipEventCreateWithFlags(&s.fork, hipEventDisableTiming) == hipSuccess &&
-               hipEventCreateWithFlags(&s.join, hipEventDisableTiming) == hipSuccess;
+               hipEventCreateWithFlags(&s.join, hipEventDisableTiming) == hipSuccess &&
+               hipEventCreateWithFlags(&s.scanned, hipEventDisableTiming) == hipSuccess;
     }
     return s.device == dev ? s : SideStream{};
 }
@@ -154,6 +155,7 @@ pa_status mfma_bwd(const Ctx& c, const void* Q, const void* K, const void* V, co
     }
     // strand R (caller's stream, so that its workgroups are placed first): state-gradient scan
     PA_TRY(launch_scan("mfma_state_grad_scan", s_main, true, Qts, Ght, gz, Rc, Omg, BH, pr.T, L.cs, s2, gt.lam))
+    if (pr.gated && side.ok && hipEventRecord(side.scanned, s_main) != hipSuccess) return PA_ERR_HIP;
     // strand S (side stream): dQ from the forward state
     if (!L.keep) {
         // nothing but O and Z was saved: rebuild the chunk states
@@ -165,6 +167,12 @@ pa_status mfma_bwd(const Ctx& c, const void* Q, const void* K, const void* V, co
     PA_TRY(launch_bwd_dq(s_side, q, k, v, Gh, gz, Kt, Sc, Gam, (bf16_t*)dQ, BH, pr.T, L.cs, pr.scale, gt.bl, gt.qfac, gt.db))
     PA_TRY(launch_bwd_dkdv(s_main, q, k, v, Gh, gz, Qt, Ght, Rc, Omg, (bf16_t*)dK, (bf16_t*)dV, BH, pr.T, L.cs, pr.scale,
                            gt.bl, gt.kfac, gt.db2))
+    if (pr.gated) {
+        // the pairs that straddle the chunk boundaries, from both sets of states: behind dQ on the side
+        // strand (S is complete there), once the scan on the caller's stream has produced R
+        if (side.ok && hipStreamWaitEvent(s_side, side.scanned, 0) != hipSuccess) return PA_ERR_HIP;
+        PA_TRY(launch_gate_boundary(s_side, Sc, Rc, Gam, Omg, gt.xb, BH, L.nstate))
+    }
     if (side.ok) {
         if (hipEventRecord(side.join, s_side) != hipSuccess || hipStreamWaitEvent(s_main, side.join, 0) != hipSuccess)
             return PA_ERR_HIP;

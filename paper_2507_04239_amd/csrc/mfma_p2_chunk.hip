@@ -900,7 +900,53 @@ __global__ __launch_bounds__(256, 2) void k_mfma_bwd_dkdv(const bf16_t* __restri
         dv_body<RING_KV, 4, true, GATED>(Q, K, Ght, RtC, dV, T, cs, scale, bl, kfac, sm, w4 - 2, w4, lane);
 }
 
+// ---- gating: the pairs that straddle a chunk boundary -------------------------------------------
+// xb[bh][n] = < R_n , S_{n+1} > + < Omega_n , Gamma_{n+1} >: the sum of e_ij a_ij over the pairs
+// j <= end of chunk n < i (0 for the last chunk), which the gradient of the log-gates needs per
+// boundary.  Both stored states carry the tile multiplicity; the inner product of the expanded
+// vectors carries it once, hence the 1/2 on the off-diagonal tiles.
+__device__ __forceinline__ float dot8(uint4 a, uint4 b) {
+    return bf_lo(a.x) * bf_lo(b.x) + bf_hi(a.x) * bf_hi(b.x) + bf_lo(a.y) * bf_lo(b.y) + bf_hi(a.y) * bf_hi(b.y) +
+           bf_lo(a.z) * bf_lo(b.z) + bf_hi(a.z) * bf_hi(b.z) + bf_lo(a.w) * bf_lo(b.w) + bf_hi(a.w) * bf_hi(b.w);
+}
+__global__ __launch_bounds__(256) void k_mfma_gate_boundary(const bf16_t* __restrict__ StC, const bf16_t* __restrict__ RtC,
+                                                            const bf16_t* __restrict__ Gam, const bf16_t* __restrict__ Omg,
+                                                            float* __restrict__ xb, int nstate) {
+    __shared__ float red[4];
+    const int n = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x;
+    float acc = 0.f;
+    if (n < nstate - 1) {
+        const uint4* S = (const uint4*)(StC + (size_t)(bh * nstate + n + 1) * STATE_ELEMS);
+        const uint4* R = (const uint4*)(RtC + (size_t)(bh * nstate + n) * STATE_ELEMS);
+        int ti = 0, tj = 0;
+        for (int tile = 0; tile < NTILES; ++tile) {
+            float part = 0.f;
+            for (int u = tid; u < TILE_U4; u += 256) part += dot8(S[tile * TILE_U4 + u], R[tile * TILE_U4 + u]);
+            acc += ti == tj ? part : 0.5f * part;
+            if (++ti > tj) {
+                ++tj;
+                ti = 0;
+            }
+        }
+        const uint4* G = (const uint4*)(Gam + (size_t)(bh * nstate + n + 1) * DH * DH);
+        const uint4* W = (const uint4*)(Omg + (size_t)(bh * nstate + n) * DH * DH);
+        for (int u = tid; u < DH * DH / 8; u += 256) acc += dot8(G[u], W[u]);
+    }
+    acc = xor32_sum(xor16_sum(acc));
+    for (int off = 8; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
+    if ((tid & 63) == 0) red[tid >> 6] = acc;
+    __syncthreads();
+    if (tid == 0) xb[(size_t)bh * nstate + n] = red[0] + red[1] + red[2] + red[3];
+}
+
 }  // namespace
+
+bool launch_gate_boundary(hipStream_t s, const bf16_t* stC, const bf16_t* rtC, const bf16_t* gam, const bf16_t* omg, float* xb,
+                          int BH, int nstate) {
+    LaunchScope ls("mfma_gate_boundary", s);
+    hipLaunchKernelGGL(k_mfma_gate_boundary, dim3(nstate, BH), dim3(256), 0, s, stC, rtC, gam, omg, xb, nstate);
+    return launch_ok();
+}
 
 // `gate`: bl and the state-term decay (qfac for the query-side kernels, kfac for the key-side one),
 // both null when the problem is not gated

@@ -131,3 +131,27 @@ def test_d128_config5_shape_reduced_batch():
     assert rel_l2(got["O"][0, 0][:n0], O_ref) <= TOL["bf16"]
     assert rel_l2(got["Z"][0, 0][:n0], Z_ref) <= TOL["bf16"]
     _check_sampled("cfg5", got, Q, K, V, G, dict(w, B=1, H=1), [(0, 0)], n_rows=12, n_cols=0)
+
+
+def test_headline_shape_gated():
+    """The headline head shape (T = 65536, d = 64, chunk 128, bf16) with per-timestep gates, two
+    heads: every output of one head against the chunked float64 oracle, sampled forward rows of
+    the other by the definition."""
+    name = "cfg3_bf16_p2_T65536_d64_c128"
+    w = inputs.WORKLOADS[name]
+    Q, K, V, G = inputs.make_qkvg(1, 2, w["T"], w["d"], seed=1103, dtype="bf16")
+    lg = inputs.make_log_gates(1, 2, w["T"], 1603, 0.02)
+    print("case", name, "gated", flush=True)
+    got = run_fwd_bwd(Q, K, V, G, 2, w["chunk"], "bf16", keep_state=True, log_g=lg)
+    for k, a in got.items():
+        assert np.isfinite(a).all(), k
+    h = 1
+    lg64 = lg[0, h].astype(np.float64)
+    O_ref, Z_ref = orc.fwd_chunked_gated(Q[0, h], K[0, h], V[0, h], lg64, 2, w["chunk"])
+    dQ_ref, dK_ref, dV_ref, dL_ref = orc.bwd_chunked_gated(Q[0, h], K[0, h], V[0, h], lg64, G[0, h], 2, w["chunk"])
+    assert_close({k: a[0, h] for k, a in got.items()},
+                 dict(O=O_ref, Z=Z_ref, dQ=dQ_ref, dK=dK_ref, dV=dV_ref, dlog_g=dL_ref), "bf16", f"{name} gated head 1")
+    rows = _sample_rows(w["T"], 8, seed=5)
+    ref = [orc.fwd_row_gated(Q[0, 0], K[0, 0], V[0, 0], lg[0, 0].astype(np.float64), i, 2) for i in rows]
+    assert rel_l2(got["O"][0, 0][rows], np.stack([r[0] for r in ref])) <= TOL["bf16"]
+    assert rel_l2(got["Z"][0, 0][rows], np.array([r[1] for r in ref])) <= TOL["bf16"]
