@@ -57,7 +57,9 @@ typedef struct {
     int   d;            /* query / key head size */
     int   v;            /* value head size */
     int   p;            /* degree of the power (Sec. 4 Eq. (7)); even when normalize != 0 */
-    int   chunk;        /* chunk size c of the chunked form; must divide T */
+    int   chunk;        /* chunk size c of the chunked form; must divide T.  chunk == T is the attention
+                           form (one chunk).  0: the library chooses between the two forms and the
+                           chunk size (see power_attn_resolved_chunk) */
     int   normalize;    /* 1: divide by the sum of the scores; 0: leave un-normalised */
     float scale;        /* multiplies q.k before the power ("softmax scaling", App. E.1 step 2) */
     int   dtype;        /* pa_dtype of Q, K, V, O, dO, dQ, dK, dV; accumulation is always float32 */
@@ -118,6 +120,9 @@ pa_status power_attn_bwd_gated(const pa_problem* prob,
                                const void* O, const float* Z, const void* dO,
                                void* dQ, void* dK, void* dV, float* dlog_g,
                                void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* The chunk size the calls use for `prob` (prob->chunk itself unless it is 0; 0 on an invalid problem). */
+int power_attn_resolved_chunk(const pa_problem* prob);
 
 /* Expanded state rows the chosen kernel family keeps per head for `prob`: C(d+p-1, p) for
  * the generic family (Lemma 4.2), C(d/d_tile+p-1, p) * d_tile^p for the tiled one

@@ -25,6 +25,7 @@ EXPORTED_SYMBOLS = (
     "power_attn_fwd_gated",
     "power_attn_bwd_gated",
     "power_attn_state_rows",
+    "power_attn_resolved_chunk",
     "power_attn_status_string",
     "power_attn_last_hip_error",
     "power_attn_profile_begin",
@@ -70,6 +71,8 @@ def load_library():
     lib.power_attn_workspace_bytes.argtypes = [P, ctypes.c_int]
     lib.power_attn_supported.restype = ctypes.c_int
     lib.power_attn_supported.argtypes = [P, ctypes.c_int]
+    lib.power_attn_resolved_chunk.restype = ctypes.c_int
+    lib.power_attn_resolved_chunk.argtypes = [P]
     lib.power_attn_state_rows.restype = ctypes.c_longlong
     lib.power_attn_state_rows.argtypes = [P]
     lib.power_attn_fwd.restype = ctypes.c_int
@@ -136,6 +139,10 @@ def _stream():
 
 def power_attn_workspace_bytes(prob: PaProblem, for_backward: bool) -> int:
     return int(load_library().power_attn_workspace_bytes(ctypes.byref(prob), int(for_backward)))
+
+
+def power_attn_resolved_chunk(prob: PaProblem) -> int:
+    return int(load_library().power_attn_resolved_chunk(ctypes.byref(prob)))
 
 
 def power_attn_state_rows(prob: PaProblem) -> int:

@@ -21,15 +21,39 @@ std::vector<Record> g_records;
 
 pa_status validate(const pa_problem* pr) {
     if (pr == nullptr) return PA_ERR_INVALID_ARG;
-    if (pr->B <= 0 || pr->H <= 0 || pr->T <= 0 || pr->d <= 0 || pr->v <= 0 || pr->p <= 0 || pr->chunk <= 0)
+    if (pr->B <= 0 || pr->H <= 0 || pr->T <= 0 || pr->d <= 0 || pr->v <= 0 || pr->p <= 0 || pr->chunk < 0)
         return PA_ERR_INVALID_ARG;
-    if (pr->T % pr->chunk != 0) return PA_ERR_INVALID_ARG;
+    if (pr->chunk > 0 && pr->T % pr->chunk != 0) return PA_ERR_INVALID_ARG;
     if (pr->normalize != 0 && (pr->p % 2) != 0) return PA_ERR_INVALID_ARG;  // scores must be positive to normalise
     if (pr->dtype != PA_DTYPE_F32 && pr->dtype != PA_DTYPE_BF16) return PA_ERR_INVALID_ARG;
     if (pr->impl != PA_IMPL_AUTO && pr->impl != PA_IMPL_GENERIC && pr->impl != PA_IMPL_MFMA) return PA_ERR_INVALID_ARG;
     if (!(pr->scale == pr->scale) || pr->scale == 0.f) return PA_ERR_INVALID_ARG;
     if (pr->gated != 0 && pr->gated != 1) return PA_ERR_INVALID_ARG;
     return PA_OK;
+}
+
+// chunk == 0: the library picks between the attention form (one chunk: cost ~ T per token) and the
+// chunked form (cost ~ the state size per token), Sec. 2 "Chunked form".  Where the bf16 MFMA
+// family applies the choice is measured: on MI355X the attention form wins only up to T = 1024, and
+// 256 is the best chunk beyond (128 when 256 does not divide T).  Elsewhere the two costs are
+// compared by their multiply-add counts, T (4 d + 2) / 2 per token against 4 D (v + 1).
+int auto_chunk(const pa_problem& pr) {
+    pa_problem probe = pr;
+    probe.chunk = pr.T % 256 == 0 ? 256 : 128;
+    if (pr.T % 128 == 0 && (pr.impl == PA_IMPL_AUTO || pr.impl == PA_IMPL_MFMA) && mfma_supported(probe, true) == PA_OK)
+        return pr.T <= 1024 ? pr.T : probe.chunk;
+    double D = 1.0;   // C(d + p - 1, p)
+    for (int i = 1; i <= pr.p; ++i) D = D * (pr.d + pr.p - i) / i;
+    if (0.5 * pr.T * (4.0 * pr.d + 2.0) <= 4.0 * D * (pr.v + 1)) return pr.T;
+    for (int c = 128; c >= 1; c >>= 1)
+        if (pr.T % c == 0) return c;
+    return 1;
+}
+
+pa_problem resolved(const pa_problem* prob) {
+    pa_problem pr = *prob;
+    if (pr.chunk == 0) pr.chunk = auto_chunk(pr);
+    return pr;
 }
 
 // PA_IMPL_GENERIC / PA_IMPL_MFMA, or a negative status
@@ -59,6 +83,8 @@ pa_status run_fwd(const pa_problem* prob, const void* Q, const void* K, const vo
     if (st != PA_OK) return st;
     if (prob->gated != gated) return PA_ERR_INVALID_ARG;
     if (Q == nullptr || K == nullptr || V == nullptr || O == nullptr || (gated && log_g == nullptr)) return PA_ERR_INVALID_ARG;
+    const pa_problem pr_ = resolved(prob);
+    prob = &pr_;
     pa_status why = PA_ERR_UNSUPPORTED;
     int impl = choose(*prob, false, &why);
     if (impl < 0) return why;
@@ -85,6 +111,8 @@ pa_status run_bwd(const pa_problem* prob, const void* Q, const void* K, const vo
         return PA_ERR_INVALID_ARG;
     if (gated && (log_g == nullptr || dlog_g == nullptr)) return PA_ERR_INVALID_ARG;
     if (prob->normalize != 0 && (O == nullptr || Z == nullptr)) return PA_ERR_INVALID_ARG;
+    const pa_problem pr_ = resolved(prob);
+    prob = &pr_;
     pa_status why = PA_ERR_UNSUPPORTED;
     int impl = choose(*prob, true, &why);
     if (impl < 0) return why;
@@ -151,24 +179,32 @@ const char* power_attn_status_string(pa_status s) {
 pa_status power_attn_supported(const pa_problem* prob, int for_backward) {
     pa_status st = validate(prob);
     if (st != PA_OK) return st;
+    const pa_problem pr_ = resolved(prob);
     pa_status why = PA_ERR_UNSUPPORTED;
-    return choose(*prob, for_backward != 0, &why) < 0 ? why : PA_OK;
+    return choose(pr_, for_backward != 0, &why) < 0 ? why : PA_OK;
 }
 
 size_t power_attn_workspace_bytes(const pa_problem* prob, int for_backward) {
     if (validate(prob) != PA_OK) return 0;
+    const pa_problem pr_ = resolved(prob);
     pa_status why;
-    int impl = choose(*prob, for_backward != 0, &why);
+    int impl = choose(pr_, for_backward != 0, &why);
     if (impl < 0) return 0;
-    return family_bytes(impl, *prob, for_backward != 0) + gate_workspace_bytes(*prob, for_backward != 0);
+    return family_bytes(impl, pr_, for_backward != 0) + gate_workspace_bytes(pr_, for_backward != 0);
 }
 
 long long power_attn_state_rows(const pa_problem* prob) {
     if (validate(prob) != PA_OK) return 0;
+    const pa_problem pr_ = resolved(prob);
     pa_status why;
-    int impl = choose(*prob, false, &why);
+    int impl = choose(pr_, false, &why);
     if (impl < 0) return 0;
-    return impl == PA_IMPL_MFMA ? mfma_state_rows(*prob) : generic_state_rows(*prob);
+    return impl == PA_IMPL_MFMA ? mfma_state_rows(pr_) : generic_state_rows(pr_);
+}
+
+int power_attn_resolved_chunk(const pa_problem* prob) {
+    if (validate(prob) != PA_OK) return 0;
+    return resolved(prob).chunk;
 }
 
 pa_status power_attn_fwd(const pa_problem* prob, const void* Q, const void* K, const void* V, void* O, float* Z,

@@ -74,3 +74,18 @@ def test_invalid_arguments_are_rejected():
         power_attn_fwd(q, q, q, 7, 16, normalize=False)  # no kernel for p = 7
     with pytest.raises(PowerAttnError):
         power_attn_fwd(q.cpu(), q.cpu(), q.cpu(), 2, 16)
+
+
+def test_automatic_chunk_matches_the_explicit_one():
+    import torch
+    from gpu_util import to_dev, to_np
+    from paper_2507_04239_amd import binding, power_attn_bwd, power_attn_fwd
+    for (B, H, T, d, dtype) in ((1, 2, 1024, 64, "bf16"), (1, 1, 2048, 64, "bf16"), (1, 1, 512, 16, "f32")):
+        Q, K, V, G = inputs.make_qkvg(B, H, T, d, seed=900 + T, dtype=dtype)
+        prob = binding.make_problem(B, H, T, d, d, 2, 0, True, 1.0, dtype)
+        c = binding.power_attn_resolved_chunk(prob)
+        assert c > 0 and T % c == 0
+        a = run_fwd_bwd(Q, K, V, G, 2, 0, dtype)
+        b = run_fwd_bwd(Q, K, V, G, 2, c, dtype)
+        for key in a:
+            np.testing.assert_array_equal(a[key], b[key], err_msg=f"T={T} chunk 0 vs {c}: {key}")

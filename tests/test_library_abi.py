@@ -59,3 +59,27 @@ def test_state_rows_match_the_embedding_dimension(lib):
     for d, p in [(16, 2), (32, 4), (12, 3)]:
         pr = binding.make_problem(1, 1, 64, d, d, p, 32, normalize=(p % 2 == 0), impl="generic")
         assert binding.power_attn_state_rows(pr) == math.comb(d + p - 1, p)
+
+
+def test_automatic_chunk_choice():
+    """chunk = 0 lets the library choose (host logic only): the attention form (one chunk) for short
+    sequences, the chunked form beyond; an explicit chunk is returned unchanged."""
+    from paper_2507_04239_amd import binding
+    mk = binding.make_problem
+    rc = binding.power_attn_resolved_chunk
+    assert rc(mk(1, 12, 65536, 64, 64, 2, 128)) == 128
+    assert rc(mk(1, 12, 65536, 64, 64, 2, 0)) == 256          # bf16, p = 2, d = 64: measured best chunk
+    assert rc(mk(1, 12, 65536 + 128, 64, 64, 2, 0)) == 128    # 256 does not divide T
+    assert rc(mk(4, 12, 1024, 64, 64, 2, 0)) == 1024          # short: attention form
+    assert rc(mk(4, 12, 512, 64, 64, 2, 0)) == 512
+    # p = 4, d = 32: the state is 52360 x 33 per head, the attention form stays cheaper far beyond 16k tokens
+    assert rc(mk(2, 8, 16384, 32, 32, 4, 0, dtype="bf16")) == 16384
+    # float32, small head: state 136 x 17; chunked from a few hundred tokens on
+    assert rc(mk(1, 1, 64, 16, 16, 2, 0, dtype="f32")) == 64
+    c = rc(mk(1, 1, 4096, 16, 16, 2, 0, dtype="f32"))
+    assert 0 < c <= 128 and 4096 % c == 0
+    assert rc(mk(1, 1, 96, 16, 16, 2, 0, dtype="f32", impl="generic")) == 96
+    assert rc(mk(1, 1, 4000, 16, 16, 2, 0, dtype="f32")) == 32   # largest power of two <= 128 dividing T
+    assert binding.power_attn_workspace_bytes(mk(1, 12, 65536, 64, 64, 2, 0), False) == \
+        binding.power_attn_workspace_bytes(mk(1, 12, 65536, 64, 64, 2, 256), False)
+    assert rc(mk(1, 1, 100, 16, 16, 2, 7)) == 0                  # invalid: 7 does not divide 100
