@@ -242,17 +242,24 @@ __device__ __forceinline__ void scan_body(const bf16_t* __restrict__ Xt, const b
     // Both stores below hand every lane 16 contiguous bytes: a lane's 4 accumulator rows are half
     // of an 8-row run whose other half sits 16 lanes away, so two lanes swap halves of two
     // column blocks (or row blocks) and each stores one complete run.
-    auto pack = [&](const f32x4& c) {
+    // gated: right after a state has been packed the running sum decays by `decay`, the factor of
+    // the chunk that is about to be added.  One pass over the accumulators does both: a second
+    // pass costs registers, and the reverse scan has to stay within 288 so that a wave of the dQ
+    // kernel (224) fits beside it on the SIMD.
+    auto pack = [&](f32x4& c, float decay) {
         union {
             bf16x4 v;
             uint2 u;
         } o;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) o.v[r] = (__bf16)(c[r] * mult);
+        for (int r = 0; r < 4; ++r) {
+            o.v[r] = (__bf16)(c[r] * mult);
+            if (GATED) c[r] *= decay;
+        }
         return o.u;
     };
     // the state as it stands, packed for storing as state n
-    auto pack_state = [&](StateOut& so, int n) {
+    auto pack_state = [&](StateOut& so, int n, float decay) {
         if (!GAMMA) {
             // layout [a][v][b]: accumulator rows are b = 4 (g & 1) + r of a = .. + (g >> 1)
             so.dst = StC + ((size_t)(bh * nstate + n) * NTILES + tile) * TILE_ELEMS +
@@ -260,20 +267,24 @@ __device__ __forceinline__ void scan_body(const bf16_t* __restrict__ Xt, const b
 #pragma unroll
             for (int rbk = 0; rbk < 2; ++rbk)
 #pragma unroll
-                for (int cp = 0; cp < 2; ++cp)   // g even: column block 2 cp; g odd: 2 cp + 1
-                    so.run[2 * rbk + cp] = pair_rows(pack(acc[rbk][2 * cp]), pack(acc[rbk][2 * cp + 1]));
+                for (int cp = 0; cp < 2; ++cp) {  // g even: column block 2 cp; g odd: 2 cp + 1
+                    const uint2 lo = pack(acc[rbk][2 * cp], decay), hi = pack(acc[rbk][2 * cp + 1], decay);
+                    so.run[2 * rbk + cp] = pair_rows(lo, hi);
+                }
         } else {
             // Gamma / Omega are symmetric: element (row, col) is stored at [col][row], where the
             // accumulator rows 32 w + 16 rbk + 4 g + r are contiguous
             so.dst = Gam + (size_t)(bh * nstate + n) * DH * DH + r16 * DH + 32 * (w & 1) + 16 * (g & 1) + 8 * (g >> 1);
 #pragma unroll
-            for (int cb = 0; cb < 4; ++cb)       // g even: row block 0; g odd: row block 1
-                so.run[cb] = pair_rows(pack(acc[0][cb]), pack(acc[1][cb]));
+            for (int cb = 0; cb < 4; ++cb) {     // g even: row block 0; g odd: row block 1
+                const uint2 lo = pack(acc[0][cb], decay), hi = pack(acc[1][cb], decay);
+                so.run[cb] = pair_rows(lo, hi);
+            }
         }
     };
-    auto write_state = [&](int n) {
+    auto write_state = [&](int n, float decay) {
         StateOut so;
-        pack_state(so, n);
+        pack_state(so, n, decay);
         if (has_rows) {
 #pragma unroll
             for (int k = 0; k < 4; ++k) store_run<GAMMA>(so, k);
@@ -319,14 +330,11 @@ __device__ __forceinline__ void scan_body(const bf16_t* __restrict__ Xt, const b
         const int edge_ = REV ? T - (ST) * SCAN_TOK : (ST) * SCAN_TOK;                        \
         PA_PROBE(0)                                                                           \
         StateOut so_;                                                                         \
-        if (EVERY) pack_state(so_, REV ? edge_ / cs - 1 : edge_ / cs);                        \
-        else if (edge_ % cs == 0) write_state(REV ? edge_ / cs - 1 : edge_ / cs);             \
-        if (GATED && (EVERY || edge_ % cs == 0)) {                                            \
-            /* gated: the sum decays across the chunk that is about to be added */           \
-            const float l_ = lam[(size_t)bh * nstate + (REV ? edge_ / cs - 1 : edge_ / cs)];  \
-            _Pragma("unroll") for (int rbk_ = 0; rbk_ < 2; ++rbk_)                            \
-                _Pragma("unroll") for (int cb_ = 0; cb_ < 4; ++cb_)                           \
-                    _Pragma("unroll") for (int r_ = 0; r_ < 4; ++r_) acc[rbk_][cb_][r_] *= l_; \
+        if (EVERY || edge_ % cs == 0) {                                                       \
+            const int n_ = REV ? edge_ / cs - 1 : edge_ / cs;                                 \
+            const float l_ = GATED ? lam[(size_t)bh * nstate + n_] : 1.f;                     \
+            if (EVERY) pack_state(so_, n_, l_);                                               \
+            else write_state(n_, l_);                                                         \
         }                                                                                     \
         PA_PROBE(1)                                                                           \
         PA_FILL_X(BUF, 0, x0_##J) PA_FILL_X(BUF, 1, x1_##J)                                   \
@@ -360,7 +368,7 @@ __device__ __forceinline__ void scan_body(const bf16_t* __restrict__ Xt, const b
 #undef PA_FILL_X
 #undef PA_LOAD_STAGE
     }
-    write_state(REV ? 0 : nstate - 1);
+    write_state(REV ? 0 : nstate - 1, 1.f);
 }
 
 template <bool REV, bool EVERY, bool GATED>
