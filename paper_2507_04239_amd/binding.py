@@ -64,6 +64,10 @@ def load_library():
     path = library_path()
     if not os.path.exists(path):
         raise PowerAttnError(f"{path} is missing: build it with `python -c 'import __graft_entry__ as g; g.build()'`")
+    # torch first: it brings a HIP runtime of its own, and the library has to end up on the runtime
+    # that owns the tensors' device context.  Loaded the other way round, every launch of the library
+    # fails with "no ROCm-capable device is detected".
+    import torch  # noqa: F401
     lib = ctypes.CDLL(path)
     P = ctypes.POINTER(PaProblem)
     vp = ctypes.c_void_p
@@ -139,6 +143,10 @@ def _stream():
 
 def power_attn_workspace_bytes(prob: PaProblem, for_backward: bool) -> int:
     return int(load_library().power_attn_workspace_bytes(ctypes.byref(prob), int(for_backward)))
+
+
+def power_attn_supported(prob: PaProblem, for_backward: bool) -> bool:
+    return int(load_library().power_attn_supported(ctypes.byref(prob), int(for_backward))) == 0
 
 
 def power_attn_resolved_chunk(prob: PaProblem) -> int:

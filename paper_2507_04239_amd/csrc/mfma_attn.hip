@@ -1,0 +1,578 @@
+// bf16 MFMA kernels for the attention form of power attention (arXiv 2507.04239, Sec. 2 Eq. 5 with
+// the kernel of Sec. 4 Eq. 7): the whole sequence is one chunk, no state is built,
+//     O_i = sum_{j <= i} a_ij v_j / Z_i,   a_ij = (scale q_i . k_j)^p,   Z_i = sum_{j <= i} a_ij,
+// for any degree p and head sizes d = v in {32, 64, 128}.  The paper switches to this form where
+// it is the cheaper one (Sec. 5, throughput comparison); here it is also what runs the degrees and
+// head sizes the chunked MFMA family (p = 2, d = 64) does not cover.
+//
+// Backward pass (the paper gives none; derived from the definition): with ghat_i = dO_i / Z_i and
+// gz_i = -ghat_i . O_i (normalised; ghat = dO, gz = 0 otherwise),
+//     e_ij = ghat_i . v_j + gz_i                       dL / d a_ij
+//     t_ij = e_ij p scale (scale q_i . k_j)^(p-1)      dL / d (q_i . k_j)
+//     dQ_i = sum_{j <= i} t_ij k_j,   dK_j = sum_{i >= j} t_ij q_i,   dV_j = sum_{i >= j} a_ij ghat_i.
+//
+// All three kernels have one shape: a workgroup of 4 waves owns a block of rows (queries for the
+// forward pass and dQ, keys for dK / dV), each wave OWN of them with its operands and accumulators
+// in registers, and walks over the other side's rows in tiles of 64 that are staged row-major in
+// LDS (double-buffered, one barrier per tile).  Operands that are needed transposed (V^T, K^T, Q^T,
+// ghat^T as the MFMA's A operand) come from the same row-major tile through the transposing LDS
+// read, so no transposed copy exists anywhere.  MFMA operand layouts as in mfma_common.hpp; the
+// 8 k-slots of the second contraction are rows 4g..4g+3 of two 16-row blocks, which is how the
+// first contraction's accumulators already hold them.
+#include "mfma_common.hpp"
+
+namespace pa {
+namespace mfma {
+namespace {
+
+constexpr int AT = 64;   // rows per streamed tile
+
+template <int HD>
+struct AttnTile {
+    bf16_t r[AT][HD + 8];   // pitch (HD + 8) / 2 dwords = 4 (mod 8): the 16 rows of a fragment read hit distinct banks
+};
+
+template <int P>
+__device__ __forceinline__ float ipow(float x) {
+    float r = 1.f;
+#pragma unroll
+    for (int i = 0; i < P; ++i) r *= x;
+    return r;
+}
+template <>
+__device__ __forceinline__ float ipow<4>(float x) {
+    const float x2 = x * x;
+    return x2 * x2;
+}
+
+// Staging of a 64-row tile of a row-major [.][HD] array: HD / 32 pieces of 16 bytes per thread,
+// piece id = tid + 256 q is row id / (HD / 8), features 8 (id % (HD / 8)) .. + 7.  The pieces wait
+// in registers while the tile before them is being used (plain arrays and unrolled loops in the
+// kernels: wrapped in a struct they end up in scratch memory).
+template <int HD>
+__device__ __forceinline__ uint4 piece_load(const bf16_t* __restrict__ src, int id) {
+    return *(const uint4*)(src + (size_t)(id / (HD / 8)) * HD + 8 * (id % (HD / 8)));
+}
+template <int HD>
+__device__ __forceinline__ void piece_store(AttnTile<HD>& dst, int id, uint4 u) {
+    *(uint4*)&dst.r[id / (HD / 8)][8 * (id % (HD / 8))] = u;
+}
+#define PA_TILE_LOAD(REGS, SRC)                     \
+    _Pragma("unroll") for (int q_ = 0; q_ < HD / 32; ++q_) REGS[q_] = piece_load<HD>(SRC, tid + 256 * q_);
+#define PA_TILE_STORE(DST, REGS)                    \
+    _Pragma("unroll") for (int q_ = 0; q_ < HD / 32; ++q_) piece_store<HD>(DST, tid + 256 * q_, REGS[q_]);
+
+// rows 16 blk + r16, features 32 ks + 8 g .. + 7: A operand (rows x features) or B operand
+// (features x rows) of a contraction over the features
+template <int HD>
+__device__ __forceinline__ bf16x8 row_frag(const AttnTile<HD>& t, int blk, int ks, int r16, int g) {
+    Frag f;
+    f.u = *(const uint4*)&t.r[16 * blk + r16][32 * ks + 8 * g];
+    return f.v;
+}
+template <int HD>
+__device__ __forceinline__ bf16x8 row_frag_global(const bf16_t* __restrict__ X, size_t row, int ks, int g) {
+    Frag f;
+    f.u = *(const uint4*)(X + row * HD + 32 * ks + 8 * g);
+    return f.v;
+}
+
+// A operand of a contraction over the tile's rows: column 16 cb + r16, k-slots = rows
+// 32 s + 4g .. + 3 and 32 s + 16 + 4g .. + 3.  The transposing read hands lane n of a 16-lane
+// group column n of the 4 x 16 block whose row j the lanes 4j .. 4j+3 point at (4 columns each).
+template <int HD>
+__device__ __forceinline__ bf16x8 col_frag(const AttnTile<HD>& t, int s, int cb, int r16, int g) {
+    typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
+    const bf16_t* p = &t.r[32 * s + 4 * g + (r16 >> 2)][16 * cb + 4 * (r16 & 3)];
+    union {
+        bf16x8 v;
+        bf16x4 h[2];
+    } f;
+    f.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)p);
+    f.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p + 16 * (HD + 8)));
+    return f.v;
+}
+
+// Workgroups are numbered so that the ones with the longest walk start first.
+__device__ __forceinline__ int heavy_first(int nblocks, bool longest_is_last) {
+    return longest_is_last ? nblocks - 1 - (int)blockIdx.x : (int)blockIdx.x;
+}
+
+// ---- forward ----------------------------------------------------------------------------------------
+// acc[vb][ib] = O^T: value columns 16 vb + 4g + r, query 16 ib + r16 of the wave's OWN queries.
+template <int P, int HD, int OWN>
+__global__ __launch_bounds__(256) void k_attn_fwd(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
+                                                  const bf16_t* __restrict__ V, bf16_t* __restrict__ O,
+                                                  float* __restrict__ Z, int T, float scale, int normalize) {
+    constexpr int NI = OWN / 16, NK = HD / 32, NV = HD / 16, WG = 4 * OWN;
+    extern __shared__ __attribute__((aligned(16))) unsigned char attn_smem[];
+    AttnTile<HD>* kt = reinterpret_cast<AttnTile<HD>*>(attn_smem);      // [2]
+    AttnTile<HD>* vt = kt + 2;                                          // [2]
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r16 = lane & 15, g = lane >> 4;
+    const int nblk = (T + WG - 1) / WG;
+    const int i0 = heavy_first(nblk, true) * WG;
+    const int q0 = i0 + OWN * w;                    // the wave's first query
+    const bool active = q0 < T;                     // T is a multiple of 64 >= OWN-row granularity of the last block
+    const size_t head = (size_t)blockIdx.y * T;
+    const bf16_t* Kh = K + head * HD;
+    const bf16_t* Vh = V + head * HD;
+
+    bf16x8 qf[NI][NK];
+    f32x4 acc[NV][NI];
+    float zsum[NI];
+#pragma unroll
+    for (int ib = 0; ib < NI; ++ib) {
+        zsum[ib] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < NK; ++ks)
+            qf[ib][ks] = row_frag_global<HD>(Q, head + min(q0 + 16 * ib + r16, T - 1), ks, g);
+#pragma unroll
+        for (int vb = 0; vb < NV; ++vb) acc[vb][ib] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    }
+
+    const int ntile = min(i0 + WG, T) / AT;         // key tiles 0 .. ntile - 1 reach the block's last query
+    uint4 kr[HD / 32], vr[HD / 32];
+    PA_TILE_LOAD(kr, Kh)
+    PA_TILE_LOAD(vr, Vh)
+    PA_TILE_STORE(kt[0], kr)
+    PA_TILE_STORE(vt[0], vr)
+    __syncthreads();
+    for (int t = 0; t < ntile; ++t) {
+        const int buf = t & 1, key0 = t * AT;
+        if (t + 1 < ntile) {
+            PA_TILE_LOAD(kr, Kh + (size_t)(key0 + AT) * HD)
+            PA_TILE_LOAD(vr, Vh + (size_t)(key0 + AT) * HD)
+        }
+        if (active && key0 <= q0 + OWN - 1) {
+            const bool diag = key0 + AT - 1 > q0;   // some pair of this tile lies above the diagonal
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                Frag pf[NI];
+#pragma unroll
+                for (int jb = 0; jb < 2; ++jb) {
+                    const int kb = 2 * s + jb;
+                    bf16x8 kf[NK];
+#pragma unroll
+                    for (int ks = 0; ks < NK; ++ks) kf[ks] = row_frag<HD>(kt[buf], kb, ks, r16, g);
+#pragma unroll
+                    for (int ib = 0; ib < NI; ++ib) {
+                        f32x4 c = {0.f, 0.f, 0.f, 0.f};    // S^T: key 16 kb + 4g + r, query 16 ib + r16
+#pragma unroll
+                        for (int ks = 0; ks < NK; ++ks) c = mfma16(kf[ks], qf[ib][ks], c);
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            float a = ipow<P>(scale * c[r]);
+                            if (diag && key0 + 16 * kb + 4 * g + r > q0 + 16 * ib + r16) a = 0.f;
+                            // the denominator sums the rounded weights, the ones the numerator uses:
+                            // the output is then an exact convex combination of the values
+                            const __bf16 ab = (__bf16)a;
+                            zsum[ib] += (float)ab;
+                            pf[ib].v[4 * jb + r] = ab;
+                        }
+                    }
+                }
+#pragma unroll
+                for (int vb = 0; vb < NV; ++vb) {
+                    const bf16x8 vf = col_frag<HD>(vt[buf], s, vb, r16, g);
+#pragma unroll
+                    for (int ib = 0; ib < NI; ++ib) acc[vb][ib] = mfma16(vf, pf[ib].v, acc[vb][ib]);
+                }
+            }
+        }
+        if (t + 1 < ntile) {
+            PA_TILE_STORE(kt[buf ^ 1], kr)
+            PA_TILE_STORE(vt[buf ^ 1], vr)
+        }
+        __syncthreads();
+    }
+
+    if (!active) return;
+#pragma unroll
+    for (int ib = 0; ib < NI; ++ib) {
+        float z = zsum[ib];
+        z += __shfl_xor(z, 16);
+        z += __shfl_xor(z, 32);
+        const float inv = normalize ? (z != 0.f ? 1.f / z : 0.f) : 1.f;
+        const size_t row = head + q0 + 16 * ib + r16;
+#pragma unroll
+        for (int vb = 0; vb < NV; ++vb) {
+            bf16x4 o;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) o[r] = (__bf16)(acc[vb][ib][r] * inv);
+            *(bf16x4*)(O + row * HD + 16 * vb + 4 * g) = o;
+        }
+        if (Z != nullptr && g == 0) Z[row] = z;
+    }
+}
+
+// ---- backward: preparation -------------------------------------------------------------------------
+// ghat = dO / Z (bf16) and gz = -(ghat . O) (float32); un-normalised: ghat = dO, gz = 0.  Rows with
+// Z == 0 give zeros.  HD / 4 lanes per row.  gz is formed from the rounded ghat, so that
+// ghat . v_j + gz = ghat . (v_j - O_i) keeps its exact cancellations.
+template <int HD>
+__global__ __launch_bounds__(256) void k_attn_prep(const bf16_t* __restrict__ dO, const bf16_t* __restrict__ O,
+                                                   const float* __restrict__ Z, bf16_t* __restrict__ Gh,
+                                                   float* __restrict__ gz, long long rows, int normalize) {
+    constexpr int LPR = HD / 4;
+    const long long row = (long long)blockIdx.x * (256 / LPR) + threadIdx.x / LPR;
+    const int c4 = threadIdx.x % LPR;
+    if (row >= rows) return;
+    const uint2 graw = *(const uint2*)(dO + row * HD + 4 * c4);
+    const float gv[4] = {bf_lo(graw.x), bf_hi(graw.x), bf_lo(graw.y), bf_hi(graw.y)};
+    float inv = 1.f;
+    if (normalize) {
+        const float z = Z[row];
+        inv = z != 0.f ? 1.f / z : 0.f;
+    }
+    bf16x4 o;
+    float gr[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        o[i] = (__bf16)(gv[i] * inv);
+        gr[i] = (float)o[i];
+    }
+    *(bf16x4*)(Gh + row * HD + 4 * c4) = o;
+    float delta = 0.f;
+    if (normalize) {
+        const uint2 oraw = *(const uint2*)(O + row * HD + 4 * c4);
+        delta = gr[0] * bf_lo(oraw.x) + gr[1] * bf_hi(oraw.x) + gr[2] * bf_lo(oraw.y) + gr[3] * bf_hi(oraw.y);
+#pragma unroll
+        for (int off = 1; off < LPR; off <<= 1) delta += __shfl_xor(delta, off);
+    }
+    if (c4 == 0) gz[row] = -delta;
+}
+
+// ---- backward: dQ -----------------------------------------------------------------------------------
+// acc[fb][ib] = dQ^T: feature 16 fb + 4g + r, query 16 ib + r16.
+template <int P, int HD, int OWN>
+__global__ __launch_bounds__(256) void k_attn_dq(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
+                                                 const bf16_t* __restrict__ V, const bf16_t* __restrict__ Gh,
+                                                 const float* __restrict__ gz, bf16_t* __restrict__ dQ, int T,
+                                                 float scale) {
+    constexpr int NI = OWN / 16, NK = HD / 32, NF = HD / 16, WG = 4 * OWN;
+    extern __shared__ __attribute__((aligned(16))) unsigned char attn_smem[];
+    AttnTile<HD>* kt = reinterpret_cast<AttnTile<HD>*>(attn_smem);      // [2]
+    AttnTile<HD>* vt = kt + 2;                                          // [2]
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r16 = lane & 15, g = lane >> 4;
+    const int nblk = (T + WG - 1) / WG;
+    const int i0 = heavy_first(nblk, true) * WG;
+    const int q0 = i0 + OWN * w;
+    const bool active = q0 < T;
+    const size_t head = (size_t)blockIdx.y * T;
+    const bf16_t* Kh = K + head * HD;
+    const bf16_t* Vh = V + head * HD;
+    const float pscale = (float)P * scale;
+
+    bf16x8 qf[NI][NK], gf[NI][NK];
+    f32x4 acc[NF][NI];
+    float gzq[NI];
+#pragma unroll
+    for (int ib = 0; ib < NI; ++ib) {
+        const size_t row = head + min(q0 + 16 * ib + r16, T - 1);
+        gzq[ib] = gz[row];
+#pragma unroll
+        for (int ks = 0; ks < NK; ++ks) {
+            qf[ib][ks] = row_frag_global<HD>(Q, row, ks, g);
+            gf[ib][ks] = row_frag_global<HD>(Gh, row, ks, g);
+        }
+#pragma unroll
+        for (int fb = 0; fb < NF; ++fb) acc[fb][ib] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    }
+
+    const int ntile = min(i0 + WG, T) / AT;
+    uint4 kr[HD / 32], vr[HD / 32];
+    PA_TILE_LOAD(kr, Kh)
+    PA_TILE_LOAD(vr, Vh)
+    PA_TILE_STORE(kt[0], kr)
+    PA_TILE_STORE(vt[0], vr)
+    __syncthreads();
+    for (int t = 0; t < ntile; ++t) {
+        const int buf = t & 1, key0 = t * AT;
+        if (t + 1 < ntile) {
+            PA_TILE_LOAD(kr, Kh + (size_t)(key0 + AT) * HD)
+            PA_TILE_LOAD(vr, Vh + (size_t)(key0 + AT) * HD)
+        }
+        if (active && key0 <= q0 + OWN - 1) {
+            const bool diag = key0 + AT - 1 > q0;
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                Frag tf[NI];
+#pragma unroll
+                for (int jb = 0; jb < 2; ++jb) {
+                    const int kb = 2 * s + jb;
+                    bf16x8 kf[NK], vf[NK];
+#pragma unroll
+                    for (int ks = 0; ks < NK; ++ks) {
+                        kf[ks] = row_frag<HD>(kt[buf], kb, ks, r16, g);
+                        vf[ks] = row_frag<HD>(vt[buf], kb, ks, r16, g);
+                    }
+#pragma unroll
+                    for (int ib = 0; ib < NI; ++ib) {
+                        f32x4 c = {0.f, 0.f, 0.f, 0.f}, e = {gzq[ib], gzq[ib], gzq[ib], gzq[ib]};
+#pragma unroll
+                        for (int ks = 0; ks < NK; ++ks) {
+                            c = mfma16(kf[ks], qf[ib][ks], c);    // S^T
+                            e = mfma16(vf[ks], gf[ib][ks], e);    // E^T = V ghat^T + gz
+                        }
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            float tv = e[r] * pscale * ipow<P - 1>(scale * c[r]);
+                            if (diag && key0 + 16 * kb + 4 * g + r > q0 + 16 * ib + r16) tv = 0.f;
+                            tf[ib].v[4 * jb + r] = (__bf16)tv;
+                        }
+                    }
+                }
+#pragma unroll
+                for (int fb = 0; fb < NF; ++fb) {
+                    const bf16x8 kc = col_frag<HD>(kt[buf], s, fb, r16, g);   // K^T
+#pragma unroll
+                    for (int ib = 0; ib < NI; ++ib) acc[fb][ib] = mfma16(kc, tf[ib].v, acc[fb][ib]);
+                }
+            }
+        }
+        if (t + 1 < ntile) {
+            PA_TILE_STORE(kt[buf ^ 1], kr)
+            PA_TILE_STORE(vt[buf ^ 1], vr)
+        }
+        __syncthreads();
+    }
+
+    if (!active) return;
+#pragma unroll
+    for (int ib = 0; ib < NI; ++ib) {
+        const size_t row = head + q0 + 16 * ib + r16;
+#pragma unroll
+        for (int fb = 0; fb < NF; ++fb) {
+            bf16x4 o;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) o[r] = (__bf16)acc[fb][ib][r];
+            *(bf16x4*)(dQ + row * HD + 16 * fb + 4 * g) = o;
+        }
+    }
+}
+
+// ---- backward: dK, dV ---------------------------------------------------------------------------------
+// dk[fb][kb] = dK^T: feature 16 fb + 4g + r, key 16 kb + r16 of the wave's OWN keys; dv likewise.
+// S and E are formed queries x keys here, so that their accumulators are the B operand (k-slots =
+// queries) of the two contractions over the queries.
+template <int P, int HD, int OWN>
+__global__ __launch_bounds__(256) void k_attn_dkdv(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
+                                                   const bf16_t* __restrict__ V, const bf16_t* __restrict__ Gh,
+                                                   const float* __restrict__ gz, bf16_t* __restrict__ dK,
+                                                   bf16_t* __restrict__ dV, int T, float scale) {
+    constexpr int NJ = OWN / 16, NK = HD / 32, NF = HD / 16, WG = 4 * OWN;
+    extern __shared__ __attribute__((aligned(16))) unsigned char attn_smem[];
+    AttnTile<HD>* qt = reinterpret_cast<AttnTile<HD>*>(attn_smem);      // [2]
+    AttnTile<HD>* gt = qt + 2;                                          // [2]
+    float(*gzt)[AT] = reinterpret_cast<float(*)[AT]>(gt + 2);           // [2][AT]
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r16 = lane & 15, g = lane >> 4;
+    const int j0 = heavy_first((T + WG - 1) / WG, false) * WG;
+    const int k0 = j0 + OWN * w;                    // the wave's first key
+    const bool active = k0 < T;
+    const size_t head = (size_t)blockIdx.y * T;
+    const bf16_t* Qh = Q + head * HD;
+    const bf16_t* Gh_h = Gh + head * HD;
+    const float* gzh = gz + head;
+    const float pscale = (float)P * scale;
+
+    bf16x8 kf[NJ][NK], vf[NJ][NK];
+    f32x4 dk[NF][NJ], dv[NF][NJ];
+#pragma unroll
+    for (int kb = 0; kb < NJ; ++kb) {
+        const size_t row = head + min(k0 + 16 * kb + r16, T - 1);
+#pragma unroll
+        for (int ks = 0; ks < NK; ++ks) {
+            kf[kb][ks] = row_frag_global<HD>(K, row, ks, g);
+            vf[kb][ks] = row_frag_global<HD>(V, row, ks, g);
+        }
+#pragma unroll
+        for (int fb = 0; fb < NF; ++fb) {
+            dk[fb][kb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+            dv[fb][kb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        }
+    }
+
+    const int t_first = j0 / AT, ntile = T / AT;    // query tiles t_first .. ntile - 1 reach the block's first key
+    uint4 qr[HD / 32], gr[HD / 32];
+    float gzr = 0.f;
+    PA_TILE_LOAD(qr, Qh + (size_t)t_first * AT * HD)
+    PA_TILE_LOAD(gr, Gh_h + (size_t)t_first * AT * HD)
+    if (tid < AT) gzr = gzh[t_first * AT + tid];
+    PA_TILE_STORE(qt[0], qr)
+    PA_TILE_STORE(gt[0], gr)
+    if (tid < AT) gzt[0][tid] = gzr;
+    __syncthreads();
+    for (int t = t_first; t < ntile; ++t) {
+        const int buf = (t - t_first) & 1, q0 = t * AT;
+        if (t + 1 < ntile) {
+            PA_TILE_LOAD(qr, Qh + (size_t)(q0 + AT) * HD)
+            PA_TILE_LOAD(gr, Gh_h + (size_t)(q0 + AT) * HD)
+            if (tid < AT) gzr = gzh[q0 + AT + tid];
+        }
+        if (active && q0 + AT - 1 >= k0) {
+            const bool diag = q0 < k0 + OWN - 1;    // some pair of this tile lies above the diagonal
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                Frag tf[NJ], pf[NJ];
+#pragma unroll
+                for (int jb = 0; jb < 2; ++jb) {
+                    const int qb = 2 * s + jb;
+                    bf16x8 qa[NK], ga[NK];
+#pragma unroll
+                    for (int ks = 0; ks < NK; ++ks) {
+                        qa[ks] = row_frag<HD>(qt[buf], qb, ks, r16, g);
+                        ga[ks] = row_frag<HD>(gt[buf], qb, ks, r16, g);
+                    }
+                    const float4 gz4 = *(const float4*)&gzt[buf][16 * qb + 4 * g];
+                    const f32x4 e0 = {gz4.x, gz4.y, gz4.z, gz4.w};
+#pragma unroll
+                    for (int kb = 0; kb < NJ; ++kb) {
+                        f32x4 c = {0.f, 0.f, 0.f, 0.f}, e = e0;   // query 16 qb + 4g + r, key 16 kb + r16
+#pragma unroll
+                        for (int ks = 0; ks < NK; ++ks) {
+                            c = mfma16(qa[ks], kf[kb][ks], c);    // S
+                            e = mfma16(ga[ks], vf[kb][ks], e);    // E = ghat V^T + gz
+                        }
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            const float sc = scale * c[r];
+                            const float pw = ipow<P - 1>(sc);
+                            float a = pw * sc, tv = e[r] * pscale * pw;
+                            if (diag && q0 + 16 * qb + 4 * g + r < k0 + 16 * kb + r16) {
+                                a = 0.f;
+                                tv = 0.f;
+                            }
+                            pf[kb].v[4 * jb + r] = (__bf16)a;
+                            tf[kb].v[4 * jb + r] = (__bf16)tv;
+                        }
+                    }
+                }
+#pragma unroll
+                for (int fb = 0; fb < NF; ++fb) {
+                    const bf16x8 qc = col_frag<HD>(qt[buf], s, fb, r16, g);   // Q^T
+                    const bf16x8 gc = col_frag<HD>(gt[buf], s, fb, r16, g);   // ghat^T
+#pragma unroll
+                    for (int kb = 0; kb < NJ; ++kb) {
+                        dk[fb][kb] = mfma16(qc, tf[kb].v, dk[fb][kb]);
+                        dv[fb][kb] = mfma16(gc, pf[kb].v, dv[fb][kb]);
+                    }
+                }
+            }
+        }
+        if (t + 1 < ntile) {
+            PA_TILE_STORE(qt[buf ^ 1], qr)
+            PA_TILE_STORE(gt[buf ^ 1], gr)
+            if (tid < AT) gzt[buf ^ 1][tid] = gzr;
+        }
+        __syncthreads();
+    }
+
+    if (!active) return;
+#pragma unroll
+    for (int kb = 0; kb < NJ; ++kb) {
+        const size_t row = head + k0 + 16 * kb + r16;
+#pragma unroll
+        for (int fb = 0; fb < NF; ++fb) {
+            bf16x4 a, b;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                a[r] = (__bf16)dk[fb][kb][r];
+                b[r] = (__bf16)dv[fb][kb][r];
+            }
+            *(bf16x4*)(dK + row * HD + 16 * fb + 4 * g) = a;
+            *(bf16x4*)(dV + row * HD + 16 * fb + 4 * g) = b;
+        }
+    }
+}
+
+template <int HD>
+constexpr size_t attn_smem_bytes() {
+    return 4 * sizeof(AttnTile<HD>) + 2 * AT * sizeof(float);
+}
+// LDS beyond the default per-kernel limit has to be requested once per kernel
+template <typename F>
+bool allow_smem(F* fn, size_t bytes) {
+    if (bytes <= 64 * 1024) return true;
+    hipError_t e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e != hipSuccess) note_hip_error(e, "hipFuncSetAttribute(max dynamic LDS)");
+    return e == hipSuccess;
+}
+
+// rows of the block one wave owns: as many as the accumulators leave room for
+template <int HD>
+struct Own {
+    static constexpr int FWD = 64;
+    static constexpr int DQ = HD == 128 ? 32 : 64;
+    static constexpr int DKDV = HD == 128 ? 32 : 64;
+};
+
+template <int P, int HD>
+bool fwd_t(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* V, bf16_t* O, float* Z, int BH, int T, float scale,
+           int normalize) {
+    constexpr int WG = 4 * Own<HD>::FWD;
+    if (!allow_smem(k_attn_fwd<P, HD, Own<HD>::FWD>, attn_smem_bytes<HD>())) return false;
+    LaunchScope ls("attn_fwd", s);
+    hipLaunchKernelGGL((k_attn_fwd<P, HD, Own<HD>::FWD>), dim3((T + WG - 1) / WG, BH), dim3(256), attn_smem_bytes<HD>(), s, Q, K,
+                       V, O, Z, T, scale, normalize);
+    return launch_ok();
+}
+
+template <int P, int HD>
+bool bwd_t(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* V, const bf16_t* O, const float* Z, const bf16_t* dO,
+           bf16_t* Gh, float* gz, bf16_t* dQ, bf16_t* dK, bf16_t* dV, int BH, int T, float scale, int normalize) {
+    const long long rows = (long long)BH * T;
+    {
+        constexpr int RPB = 256 / (HD / 4);
+        LaunchScope ls("attn_bwd_prep", s);
+        hipLaunchKernelGGL((k_attn_prep<HD>), dim3((unsigned)((rows + RPB - 1) / RPB)), dim3(256), 0, s, dO, O, Z, Gh, gz, rows,
+                           normalize);
+        if (!launch_ok()) return false;
+    }
+    {
+        constexpr int WG = 4 * Own<HD>::DKDV;
+        if (!allow_smem(k_attn_dkdv<P, HD, Own<HD>::DKDV>, attn_smem_bytes<HD>())) return false;
+        LaunchScope ls("attn_bwd_dkdv", s);
+        hipLaunchKernelGGL((k_attn_dkdv<P, HD, Own<HD>::DKDV>), dim3((T + WG - 1) / WG, BH), dim3(256), attn_smem_bytes<HD>(), s, Q,
+                           K, V, Gh, gz, dK, dV, T, scale);
+        if (!launch_ok()) return false;
+    }
+    {
+        constexpr int WG = 4 * Own<HD>::DQ;
+        if (!allow_smem(k_attn_dq<P, HD, Own<HD>::DQ>, attn_smem_bytes<HD>())) return false;
+        LaunchScope ls("attn_bwd_dq", s);
+        hipLaunchKernelGGL((k_attn_dq<P, HD, Own<HD>::DQ>), dim3((T + WG - 1) / WG, BH), dim3(256), attn_smem_bytes<HD>(), s, Q, K,
+                           V, Gh, gz, dQ, T, scale);
+        if (!launch_ok()) return false;
+    }
+    return true;
+}
+
+}  // namespace
+
+bool attn_shape_ok(int p, int d) { return (p == 2 || p == 3 || p == 4) && (d == 32 || d == 64 || d == 128); }
+
+bool launch_attn_fwd(hipStream_t s, int p, int d, const bf16_t* Q, const bf16_t* K, const bf16_t* V, bf16_t* O, float* Z, int BH,
+                     int T, float scale, int normalize) {
+#define PA_CASE(PP, DD) \
+    if (p == PP && d == DD) return fwd_t<PP, DD>(s, Q, K, V, O, Z, BH, T, scale, normalize);
+    PA_CASE(2, 32) PA_CASE(2, 64) PA_CASE(2, 128)
+    PA_CASE(3, 32) PA_CASE(3, 64) PA_CASE(3, 128)
+    PA_CASE(4, 32) PA_CASE(4, 64) PA_CASE(4, 128)
+#undef PA_CASE
+    return false;
+}
+
+bool launch_attn_bwd(hipStream_t s, int p, int d, const bf16_t* Q, const bf16_t* K, const bf16_t* V, const bf16_t* O,
+                     const float* Z, const bf16_t* dO, bf16_t* Gh, float* gz, bf16_t* dQ, bf16_t* dK, bf16_t* dV, int BH, int T,
+                     float scale, int normalize) {
+#define PA_CASE(PP, DD) \
+    if (p == PP && d == DD) return bwd_t<PP, DD>(s, Q, K, V, O, Z, dO, Gh, gz, dQ, dK, dV, BH, T, scale, normalize);
+    PA_CASE(2, 32) PA_CASE(2, 64) PA_CASE(2, 128)
+    PA_CASE(3, 32) PA_CASE(3, 64) PA_CASE(3, 128)
+    PA_CASE(4, 32) PA_CASE(4, 64) PA_CASE(4, 128)
+#undef PA_CASE
+    return false;
+}
+
+}  // namespace mfma
+}  // namespace pa

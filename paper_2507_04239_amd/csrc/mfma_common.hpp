@@ -95,5 +95,14 @@ bool launch_bwd_dkdv(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16
 bool launch_gate_boundary(hipStream_t s, const bf16_t* stC, const bf16_t* rtC, const bf16_t* gam, const bf16_t* omg, float* xb,
                           int BH, int nstate);
 
+// attention form (chunk == T): p in {2, 3, 4}, d = v in {32, 64, 128}, T a multiple of 64.
+// Gh [BH][T][d] bf16 and gz [BH][T] float32 are scratch of the backward pass.
+bool attn_shape_ok(int p, int d);
+bool launch_attn_fwd(hipStream_t s, int p, int d, const bf16_t* Q, const bf16_t* K, const bf16_t* V, bf16_t* O, float* Z, int BH,
+                     int T, float scale, int normalize);
+bool launch_attn_bwd(hipStream_t s, int p, int d, const bf16_t* Q, const bf16_t* K, const bf16_t* V, const bf16_t* O,
+                     const float* Z, const bf16_t* dO, bf16_t* Gh, float* gz, bf16_t* dQ, bf16_t* dK, bf16_t* dV, int BH, int T,
+                     float scale, int normalize);
+
 }  // namespace mfma
 }  // namespace pa

@@ -1,5 +1,6 @@
-// Host side of the bf16 MFMA kernel family (p = 2): support check, workspace layout and the
-// launch sequences of the forward and backward passes.
+// Host side of the bf16 MFMA kernel families: support check, workspace layout and the launch
+// sequences of the forward and backward passes.  Two sets of kernels: the chunked form for p = 2,
+// d = v = 64, and the attention form (chunk == T, no state) for p in {2, 3, 4}, d = v in {32, 64, 128}.
 #include "mfma_common.hpp"
 
 namespace pa {
@@ -52,20 +53,44 @@ Layout make_layout(const pa_problem& pr, bool backward) {
     return L;
 }
 
+bool chunked_ok(const pa_problem& pr) {
+    return pr.dtype == PA_DTYPE_BF16 && pr.p == 2 && pr.d == DH && pr.v == DH && pr.chunk % QBLK == 0 &&
+           (size_t)pr.B * pr.H <= 65535u;
+}
+bool attn_ok(const pa_problem& pr) {
+    return pr.dtype == PA_DTYPE_BF16 && pr.d == pr.v && attn_shape_ok(pr.p, pr.d) && pr.chunk == pr.T && pr.T % 64 == 0 &&
+           !pr.gated && (size_t)pr.B * pr.H <= 65535u;
+}
+// The attention-form kernels run what the chunked kernels do not cover; where both apply (p = 2,
+// d = 64, one chunk) the chunked kernels' in-chunk part does the same work.
+bool use_attn(const pa_problem& pr) { return attn_ok(pr) && !chunked_ok(pr); }
+
+// attention form, backward: ghat (bf16) and gz (float32) per token
+struct AttnLayout {
+    size_t off_gh, off_gz, total;
+};
+AttnLayout make_attn_layout(const pa_problem& pr, bool backward) {
+    AttnLayout L{};
+    if (!backward) return L;
+    const size_t rows = (size_t)pr.B * pr.H * pr.T;
+    L.off_gh = 0;
+    L.off_gz = align_up(rows * pr.d * 2, 256);
+    L.total = L.off_gz + align_up(rows * sizeof(float), 256);
+    return L;
+}
+
 }  // namespace
 
 pa_status mfma_supported(const pa_problem& pr, bool backward) {
     (void)backward;
-    if (pr.dtype != PA_DTYPE_BF16 || pr.p != 2) return PA_ERR_UNSUPPORTED;
-    if (pr.d != DH || pr.v != DH) return PA_ERR_UNSUPPORTED;
-    if (pr.chunk % QBLK != 0) return PA_ERR_UNSUPPORTED;
-    if ((size_t)pr.B * pr.H > 65535u) return PA_ERR_UNSUPPORTED;
-    return PA_OK;
+    return chunked_ok(pr) || attn_ok(pr) ? PA_OK : PA_ERR_UNSUPPORTED;
 }
 
-long long mfma_state_rows(const pa_problem&) { return (long long)NTILES * 64; }
+long long mfma_state_rows(const pa_problem& pr) { return use_attn(pr) ? 0 : (long long)NTILES * 64; }
 
-size_t mfma_workspace_bytes(const pa_problem& pr, bool backward) { return make_layout(pr, backward).total; }
+size_t mfma_workspace_bytes(const pa_problem& pr, bool backward) {
+    return use_attn(pr) ? make_attn_layout(pr, backward).total : make_layout(pr, backward).total;
+}
 
 #define PA_TRY(CALL) \
     if (!(CALL)) return PA_ERR_HIP;
@@ -75,8 +100,13 @@ size_t mfma_workspace_bytes(const pa_problem& pr, bool backward) { return make_l
 // the per-chunk kernels apply the remaining factors (see the chunk kernels).
 pa_status mfma_fwd(const Ctx& c, const void* Q, const void* K, const void* V, void* O, float* Z) {
     const pa_problem& pr = c.prob;
-    const Layout L = make_layout(pr, false);
     const int BH = pr.B * pr.H;
+    if (use_attn(pr)) {
+        PA_TRY(launch_attn_fwd(c.stream, pr.p, pr.d, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (bf16_t*)O, Z, BH, pr.T,
+                               pr.scale, pr.normalize))
+        return PA_OK;
+    }
+    const Layout L = make_layout(pr, false);
     const GateBuf& gt = c.gate;
     bf16_t* Kt = (bf16_t*)(c.ws + L.off_kt);
     bf16_t* Kts = (bf16_t*)(c.ws + L.off_kts);
@@ -122,8 +152,15 @@ static SideStream side_stream() {
 pa_status mfma_bwd(const Ctx& c, const void* Q, const void* K, const void* V, const void* O, const float* Z,
                    const void* dO, void* dQ, void* dK, void* dV) {
     const pa_problem& pr = c.prob;
-    const Layout L = make_layout(pr, true);
     const int BH = pr.B * pr.H;
+    if (use_attn(pr)) {
+        const AttnLayout A = make_attn_layout(pr, true);
+        PA_TRY(launch_attn_bwd(c.stream, pr.p, pr.d, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)O, Z,
+                               (const bf16_t*)dO, (bf16_t*)(c.ws + A.off_gh), (float*)(c.ws + A.off_gz), (bf16_t*)dQ, (bf16_t*)dK,
+                               (bf16_t*)dV, BH, pr.T, pr.scale, pr.normalize))
+        return PA_OK;
+    }
+    const Layout L = make_layout(pr, true);
     const GateBuf& gt = c.gate;
     bf16_t* Kt = (bf16_t*)(c.ws + L.off_kt);
     bf16_t* Kts = (bf16_t*)(c.ws + L.off_kts);

@@ -40,8 +40,12 @@ pa_status validate(const pa_problem* pr) {
 int auto_chunk(const pa_problem& pr) {
     pa_problem probe = pr;
     probe.chunk = pr.T % 256 == 0 ? 256 : 128;
-    if (pr.T % 128 == 0 && (pr.impl == PA_IMPL_AUTO || pr.impl == PA_IMPL_MFMA) && mfma_supported(probe, true) == PA_OK)
-        return pr.T <= 1024 ? pr.T : probe.chunk;
+    const bool may_mfma = pr.impl == PA_IMPL_AUTO || pr.impl == PA_IMPL_MFMA;
+    if (pr.T % 128 == 0 && may_mfma && mfma_supported(probe, true) == PA_OK) return pr.T <= 1024 ? pr.T : probe.chunk;
+    // other degrees and head sizes: the matrix-core kernels exist for the attention form only, and
+    // that beats the chunked form on the vector ALUs at any length the chunked form is sensible for
+    probe.chunk = pr.T;
+    if (may_mfma && mfma_supported(probe, true) == PA_OK) return pr.T;
     double D = 1.0;   // C(d + p - 1, p)
     for (int i = 1; i <= pr.p; ++i) D = D * (pr.d + pr.p - i) / i;
     if (0.5 * pr.T * (4.0 * pr.d + 2.0) <= 4.0 * D * (pr.v + 1)) return pr.T;

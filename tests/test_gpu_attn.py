@@ -1,0 +1,67 @@
+"""GPU parity of the bf16 MFMA attention-form kernels (one chunk = the whole sequence; degrees 2, 3, 4,
+head sizes 32, 64, 128) against the float64 oracle, element by element, through the C ABI."""
+import numpy as np
+import pytest
+
+from oracle import power_attn_oracle as orc
+from paper_2507_04239_amd import binding, inputs
+
+from gpu_util import assert_close, run_fwd_bwd
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    # p, d, B, H, T, normalize, scale
+    (4, 32, 1, 2, 512, True, 1.0),       # config 4's degree and head size
+    (4, 32, 1, 1, 64, True, 1.0),        # a single tile: the diagonal only
+    (4, 32, 2, 1, 320, True, 1.3),       # a block that is not full (320 = 256 + 64), scale != 1
+    (2, 128, 1, 2, 512, True, 1.0),      # config 5's head size
+    (2, 128, 1, 1, 192, True, 0.7),      # not a multiple of the block of either kernel
+    (2, 128, 1, 1, 704, False, 1.0),     # un-normalised
+    (2, 32, 1, 1, 384, True, 1.0),
+    (4, 64, 1, 1, 448, True, 1.0),
+    (4, 128, 1, 1, 256, True, 1.0),
+    (3, 64, 1, 2, 384, False, 1.0),      # odd degree: signed weights, un-normalised only
+    (3, 32, 1, 1, 128, False, 0.8),
+    (3, 128, 1, 1, 320, False, 1.0),
+]
+
+
+@pytest.mark.parametrize("case", CASES, ids=lambda c: "-".join(str(x) for x in c))
+def test_attention_form_forward_backward(case):
+    p, d, B, H, T, normalize, scale = case
+    print("case", case, flush=True)
+    prob = binding.make_problem(B, H, T, d, d, p, T, normalize, scale, "bf16", "mfma")
+    assert binding.power_attn_supported(prob, True)
+    assert binding.power_attn_state_rows(prob) == 0          # no state is built
+    Q, K, V, G = inputs.make_qkvg(B, H, T, d, seed=7000 + CASES.index(case), dtype="bf16")
+    got = run_fwd_bwd(Q, K, V, G, p, T, "bf16", normalize, scale, impl="mfma")
+    O, Z = orc.fwd_bhtd(Q, K, V, p, None, normalize, scale)
+    dQ, dK, dV = orc.bwd_bhtd(Q, K, V, G, p, None, normalize, scale)
+    assert_close(got, dict(O=O, Z=Z, dQ=dQ, dK=dK, dV=dV), "bf16", f"attention form {case}")
+
+
+def test_auto_chunk_picks_the_attention_form_for_other_shapes():
+    """chunk = 0 with a degree / head size the chunked matrix-core kernels do not have: the library
+    runs the attention form on the matrix cores rather than the chunked form on the vector ALUs."""
+    for p, d in ((4, 32), (2, 128)):
+        prob = binding.make_problem(1, 1, 2048, d, d, p, 0, True, 1.0, "bf16", "auto")
+        assert binding.power_attn_resolved_chunk(prob) == 2048
+    Q, K, V, G = inputs.make_qkvg(1, 1, 256, 32, seed=7100, dtype="bf16")
+    got = run_fwd_bwd(Q, K, V, G, 4, 0, "bf16")
+    O, Z = orc.fwd_bhtd(Q, K, V, 4, None, True, 1.0)
+    dQ, dK, dV = orc.bwd_bhtd(Q, K, V, G, 4, None, True, 1.0)
+    assert_close(got, dict(O=O, Z=Z, dQ=dQ, dK=dK, dV=dV), "bf16", "auto chunk, p = 4, d = 32")
+
+
+def test_attention_form_zero_rows():
+    """All-zero queries have Z = 0: O = 0 and no gradient through the row."""
+    Q, K, V, G = inputs.make_qkvg(1, 1, 256, 32, seed=7200, dtype="bf16")
+    Q[0, 0, 3] = 0
+    Q[0, 0, 130] = 0
+    K[0, 0, 70] = 0
+    got = run_fwd_bwd(Q, K, V, G, 4, 256, "bf16", impl="mfma")
+    O, Z = orc.fwd_bhtd(Q, K, V, 4, None, True, 1.0)
+    dQ, dK, dV = orc.bwd_bhtd(Q, K, V, G, 4, None, True, 1.0)
+    assert_close(got, dict(O=O, Z=Z, dQ=dQ, dK=dK, dV=dV), "bf16", "attention form zero rows")
+    assert (got["O"][0, 0, 3] == 0).all() and (got["dQ"][0, 0, 3] == 0).all()
