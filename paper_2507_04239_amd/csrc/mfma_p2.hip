@@ -61,9 +61,9 @@ bool attn_ok(const pa_problem& pr) {
     return pr.dtype == PA_DTYPE_BF16 && pr.d == pr.v && attn_shape_ok(pr.p, pr.d) && pr.chunk == pr.T && pr.T % 64 == 0 &&
            !pr.gated && (size_t)pr.B * pr.H <= 65535u;
 }
-// The attention-form kernels run what the chunked kernels do not cover; where both apply (p = 2,
-// d = 64, one chunk) the chunked kernels' in-chunk part does the same work.
-bool use_attn(const pa_problem& pr) { return attn_ok(pr) && !chunked_ok(pr); }
+// One chunk: the attention-form kernels.  (The chunked kernels can run p = 2, d = 64 as one chunk
+// too; that path remains for gated problems, which the attention-form kernels do not take.)
+bool use_attn(const pa_problem& pr) { return attn_ok(pr); }
 
 // attention form, backward: ghat (bf16) and gz (float32) per token
 struct AttnLayout {

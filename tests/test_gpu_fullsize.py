@@ -155,3 +155,57 @@ def test_headline_shape_gated():
     ref = [orc.fwd_row_gated(Q[0, 0], K[0, 0], V[0, 0], lg[0, 0].astype(np.float64), i, 2) for i in rows]
     assert rel_l2(got["O"][0, 0][rows], np.stack([r[0] for r in ref])) <= TOL["bf16"]
     assert rel_l2(got["Z"][0, 0][rows], np.array([r[1] for r in ref])) <= TOL["bf16"]
+
+
+def test_config4_attention_form_full_shape():
+    """Config 4's full shape (bf16 fwd+bwd, p=4, B2 H8 T16384 d32) with chunk = 0: the library runs the
+    attention form on the matrix cores.  Sampled rows of every head by the definition; on one head O, Z
+    of every row by the definition and sampled columns of dK, dV."""
+    name = "cfg4_bf16_p4_T16384_d32_c128"
+    w = dict(inputs.WORKLOADS[name])
+    Q, K, V, G = (a.astype(np.float64) for a in inputs.make_workload(name))
+    print("case", name, "chunk = 0", flush=True)
+    got = run_fwd_bwd(Q, K, V, G, w["p"], 0, "bf16")
+    for k, a in got.items():
+        assert np.isfinite(a).all(), k
+    b, h = 1, 3
+    O_ref, Z_ref = orc.fwd_quadratic(Q[b, h], K[b, h], V[b, h], w["p"])
+    assert_close({k: got[k][b, h] for k in ("O", "Z")}, dict(O=O_ref, Z=Z_ref), "bf16", f"{name} head (1,3) by the definition")
+    heads = [(bb, hh) for bb in range(w["B"]) for hh in range(w["H"])]
+    _check_sampled(name, got, Q, K, V, G, w, heads, n_rows=5, n_cols=12, ref_head=((b, h), (O_ref, Z_ref)))
+
+
+def test_config5_shape_attention_form_reduced_batch():
+    """Config 5's head shape (bf16 fwd+bwd, p=2, d=128, T=32768) with chunk = 0, two of its 128 heads:
+    sampled rows of O, Z, dQ by the definition; columns of dK, dV among the last 512 keys (their
+    sums need O, Z of every later row, which the definition gives row by row)."""
+    w = dict(inputs.WORKLOADS["cfg5_bf16_p2_T32768_d128_c256"], B=1, H=2)
+    T = w["T"]
+    Q, K, V, G = (a.astype(np.float64) for a in inputs.make_qkvg(1, 2, T, w["d"], seed=1105, dtype="bf16"))
+    print("case cfg5 two heads, chunk = 0", flush=True)
+    got = run_fwd_bwd(Q, K, V, G, 2, 0, "bf16")
+    for k, a in got.items():
+        assert np.isfinite(a).all(), k
+    _check_sampled("cfg5", got, Q, K, V, G, w, [(0, 0), (0, 1)], n_rows=8, n_cols=0)
+    h, tail = 1, 512
+    O_t = np.zeros((T, w["d"]))
+    Z_t = np.ones(T)
+    for i in range(T - tail, T):
+        O_t[i], Z_t[i] = orc.fwd_row(Q[0, h], K[0, h], V[0, h], i, 2)
+    cols = sorted(set(int(x) for x in np.random.default_rng(55).integers(T - tail, T, size=10)) | {T - tail, T - 1})
+    pairs = [orc.bwd_dkdv_col(Q[0, h], K[0, h], V[0, h], G[0, h], O_t, Z_t, j, 2) for j in cols]
+    dk_err = rel_l2(got["dK"][0, h][cols], np.stack([a for a, _ in pairs]))
+    dv_err = rel_l2(got["dV"][0, h][cols], np.stack([c for _, c in pairs]))
+    print(f"cfg5 tail columns: dK={dk_err:.2e} dV={dv_err:.2e}", flush=True)
+    assert dk_err <= TOL["bf16"] and dv_err <= TOL["bf16"]
+
+
+def test_d128_attention_form_every_output_at_4096():
+    """d = 128, T = 4096 (64 key tiles, 16 to 32 workgroups per kernel and head): every output against
+    the definition."""
+    Q, K, V, G = inputs.make_qkvg(1, 1, 4096, 128, seed=1106, dtype="bf16")
+    print("case d128 T4096", flush=True)
+    got = run_fwd_bwd(Q, K, V, G, 2, 4096, "bf16", impl="mfma")
+    O, Z = orc.fwd_bhtd(Q, K, V, 2, None, True, 1.0)
+    dQ, dK, dV = orc.bwd_bhtd(Q, K, V, G, 2, None, True, 1.0)
+    assert_close(got, dict(O=O, Z=Z, dQ=dQ, dK=dK, dV=dV), "bf16", "d128 T4096 attention form")
