@@ -85,6 +85,10 @@ KERNEL_ROLE = {
     "mfma_bwd_dkdv": ("bwd_dkdv", PEAK_BF16_MFMA_TFLOPS),
     "mfma_bwd_dk": ("bwd_dk", PEAK_BF16_MFMA_TFLOPS),
     "mfma_bwd_dv": ("bwd_dv", PEAK_BF16_MFMA_TFLOPS),
+    # attention form (one chunk, no state): the same formulas with n = 1
+    "attn_fwd": ("fwd_chunk", PEAK_BF16_MFMA_TFLOPS),
+    "attn_bwd_dq": ("bwd_dq", PEAK_BF16_MFMA_TFLOPS),
+    "attn_bwd_dkdv": ("bwd_dkdv", PEAK_BF16_MFMA_TFLOPS),
 }
 
 
@@ -129,6 +133,8 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default=None, help="name from paper_2507_04239_amd.inputs.WORKLOADS")
+    ap.add_argument("--chunk", type=int, default=None,
+                    help="chunk size instead of the workload's own; 0 lets the library choose (attention form or chunked)")
     ap.add_argument("--impl", default="auto", choices=["auto", "generic", "mfma"])
     ap.add_argument("--cpu-sample-heads", type=int, default=2, help="heads the CPU oracle is timed on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -151,7 +157,10 @@ def main():
     from paper_2507_04239_amd import binding, inputs, power_attn_bwd, power_attn_fwd
 
     name = args.workload or inputs.HEADLINE
-    w = inputs.WORKLOADS[name]
+    w = dict(inputs.WORKLOADS[name])
+    oracle_chunk = w["chunk"]
+    if args.chunk is not None:
+        w["chunk"] = args.chunk
     dev = torch.device("cuda:0")
     tdt = torch.bfloat16 if w["dtype"] == "bf16" else torch.float32
     Q, K, V, G = inputs.make_workload(name, with_grad=True)
@@ -164,6 +173,7 @@ def main():
         tl = torch.from_numpy(inputs.make_log_gates(w["B"], w["H"], w["T"], 1500 + w["position"])).to(dev)
     prob = binding.make_problem(w["B"], w["H"], w["T"], w["d"], w["d"], p, chunk, True, 1.0, w["dtype"], args.impl, keep,
                                 args.gated)
+    w["chunk"] = binding.power_attn_resolved_chunk(prob)      # what the library runs (differs when 0 was asked for)
     ws_bytes = max(binding.power_attn_workspace_bytes(prob, True), binding.power_attn_workspace_bytes(prob, False))
     ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
     O = torch.empty_like(tv)
@@ -235,8 +245,8 @@ def main():
         "value": tokens / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": w["dtype"], "data": "synthetic",
-        "config": {"workload": name, "B": w["B"], "H": w["H"], "T": w["T"], "d": w["d"], "p": p, "chunk": chunk,
-                   "normalize": True, "pass": "fwd+bwd", "impl": args.impl, "keep_state": keep, "serial_kernels": args.serial_kernels, "gated": args.gated,
+        "config": {"workload": name, "B": w["B"], "H": w["H"], "T": w["T"], "d": w["d"], "p": p, "chunk": w["chunk"],
+                   "chunk_requested": chunk, "normalize": True, "pass": "fwd+bwd", "impl": args.impl, "keep_state": keep, "serial_kernels": args.serial_kernels, "gated": args.gated,
                    "state_rows": binding.power_attn_state_rows(prob)},
         "step_algorithmic_tflop": total_alg / 1e12,
         "step_frac_of_bf16_mfma_peak": total_alg / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS,
@@ -244,7 +254,7 @@ def main():
         "kernels": per_kernel,
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, args.cpu_sample_heads)
+        out["cpu_baseline"] = cpu_baseline(dict(w, chunk=oracle_chunk), args.cpu_sample_heads)
     print(json.dumps(out), flush=True)
 
 

@@ -49,7 +49,9 @@ typedef enum { PA_DTYPE_F32 = 0, PA_DTYPE_BF16 = 1 } pa_dtype;
 typedef enum {
     PA_IMPL_AUTO    = 0,
     PA_IMPL_GENERIC = 1,  /* float32 arithmetic on the vector ALUs; any 1 <= p <= 4, d, v <= 128; both dtypes */
-    PA_IMPL_MFMA    = 2   /* bf16 MFMA with float32 accumulation; bf16 only; p = 2; see power_attn_supported() */
+    PA_IMPL_MFMA    = 2   /* bf16 MFMA with float32 accumulation; bf16 only.  Chunked form: p = 2, d = v = 64,
+                             chunk a multiple of 128.  Attention form (chunk == T, T a multiple of 64, not
+                             gated): p in {2, 3, 4}, d = v in {32, 64, 128}.  See power_attn_supported() */
 } pa_impl;
 
 typedef struct {
@@ -126,7 +128,7 @@ int power_attn_resolved_chunk(const pa_problem* prob);
 
 /* Expanded state rows the chosen kernel family keeps per head for `prob`: C(d+p-1, p) for
  * the generic family (Lemma 4.2), C(d/d_tile+p-1, p) * d_tile^p for the tiled one
- * (Sec. 4.1.1).  0 on an invalid problem. */
+ * (Sec. 4.1.1).  0 when no state is built (the attention-form kernels) and on an invalid problem. */
 long long power_attn_state_rows(const pa_problem* prob);
 
 const char* power_attn_status_string(pa_status s);
