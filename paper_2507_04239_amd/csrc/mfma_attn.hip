@@ -19,6 +19,8 @@
 // read, so no transposed copy exists anywhere.  MFMA operand layouts as in mfma_common.hpp; the
 // 8 k-slots of the second contraction are rows 4g..4g+3 of two 16-row blocks, which is how the
 // first contraction's accumulators already hold them.
+#include <type_traits>
+
 #include "mfma_common.hpp"
 
 namespace pa {
@@ -100,10 +102,13 @@ __device__ __forceinline__ int heavy_first(int nblocks, bool longest_is_last) {
 
 // ---- forward ----------------------------------------------------------------------------------------
 // acc[vb][ib] = O^T: value columns 16 vb + 4g + r, query 16 ib + r16 of the wave's OWN queries.
-template <int P, int HD, int OWN>
-__global__ __launch_bounds__(256) void k_attn_fwd(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
-                                                  const bf16_t* __restrict__ V, bf16_t* __restrict__ O,
-                                                  float* __restrict__ Z, int T, float scale, int normalize) {
+// WPE: waves per SIMD the register budget is set for.  With 2 (at most 256 registers) the MFMAs
+// write plain vector registers; with 1 the compiler moves every score through the accumulation
+// registers and back, which costs more vector-ALU instructions than the arithmetic itself.
+template <int P, int HD, int OWN, int WPE>
+__global__ __launch_bounds__(256, WPE) void k_attn_fwd(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
+                                                       const bf16_t* __restrict__ V, bf16_t* __restrict__ O,
+                                                       float* __restrict__ Z, int T, float scale, int normalize) {
     constexpr int NI = OWN / 16, NK = HD / 32, NV = HD / 16, WG = 4 * OWN;
     extern __shared__ __attribute__((aligned(16))) unsigned char attn_smem[];
     AttnTile<HD>* kt = reinterpret_cast<AttnTile<HD>*>(attn_smem);      // [2]
@@ -112,23 +117,65 @@ __global__ __launch_bounds__(256) void k_attn_fwd(const bf16_t* __restrict__ Q, 
     const int nblk = (T + WG - 1) / WG;
     const int i0 = heavy_first(nblk, true) * WG;
     const int q0 = i0 + OWN * w;                    // the wave's first query
-    const bool active = q0 < T;                     // T is a multiple of 64 >= OWN-row granularity of the last block
+    const bool active = q0 < T;                     // T is a multiple of 64, and so is q0 or q0 + 32
     const size_t head = (size_t)blockIdx.y * T;
     const bf16_t* Kh = K + head * HD;
     const bf16_t* Vh = V + head * HD;
 
     bf16x8 qf[NI][NK];
     f32x4 acc[NV][NI];
-    float zsum[NI];
+    // Z rides on the matrix cores too: a row of ones as the A operand sums the rounded weights of
+    // a step's 32 keys for every query (all four accumulator rows of a lane hold the same sum)
+    f32x4 zacc[NI];
+    Frag ones;
+    ones.u = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);
 #pragma unroll
     for (int ib = 0; ib < NI; ++ib) {
-        zsum[ib] = 0.f;
+        zacc[ib] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < NK; ++ks)
             qf[ib][ks] = row_frag_global<HD>(Q, head + min(q0 + 16 * ib + r16, T - 1), ks, g);
 #pragma unroll
         for (int vb = 0; vb < NV; ++vb) acc[vb][ib] = (f32x4){0.f, 0.f, 0.f, 0.f};
     }
+
+    // one 64-key tile; DIAG: some pair of the tile lies above the diagonal and has to be masked
+    auto tile = [&](auto diag_c, int buf, int key0) {
+        constexpr bool DIAG = decltype(diag_c)::value;
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            Frag pf[NI];
+#pragma unroll
+            for (int jb = 0; jb < 2; ++jb) {
+                const int kb = 2 * s + jb;
+                bf16x8 kf[NK];
+#pragma unroll
+                for (int ks = 0; ks < NK; ++ks) kf[ks] = row_frag<HD>(kt[buf], kb, ks, r16, g);
+#pragma unroll
+                for (int ib = 0; ib < NI; ++ib) {
+                    f32x4 c = {0.f, 0.f, 0.f, 0.f};    // S^T: key 16 kb + 4g + r, query 16 ib + r16
+#pragma unroll
+                    for (int ks = 0; ks < NK; ++ks) c = mfma16(kf[ks], qf[ib][ks], c);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        float a = ipow<P>(scale * c[r]);
+                        if (DIAG && key0 + 16 * kb + 4 * g + r > q0 + 16 * ib + r16) a = 0.f;
+                        pf[ib].v[4 * jb + r] = (__bf16)a;
+                    }
+                }
+            }
+            // the denominator sums the rounded weights, the ones the numerator uses: the output is
+            // then an exact convex combination of the values
+#pragma unroll
+            for (int ib = 0; ib < NI; ++ib) zacc[ib] = mfma16(ones.v, pf[ib].v, zacc[ib]);
+#pragma unroll
+            for (int vb = 0; vb < NV; ++vb) {
+                const bf16x8 vf = col_frag<HD>(vt[buf], s, vb, r16, g);
+#pragma unroll
+                for (int ib = 0; ib < NI; ++ib) acc[vb][ib] = mfma16(vf, pf[ib].v, acc[vb][ib]);
+            }
+        }
+    };
 
     const int ntile = min(i0 + WG, T) / AT;         // key tiles 0 .. ntile - 1 reach the block's last query
     uint4 kr[HD / 32], vr[HD / 32];
@@ -144,40 +191,8 @@ __global__ __launch_bounds__(256) void k_attn_fwd(const bf16_t* __restrict__ Q, 
             PA_TILE_LOAD(vr, Vh + (size_t)(key0 + AT) * HD)
         }
         if (active && key0 <= q0 + OWN - 1) {
-            const bool diag = key0 + AT - 1 > q0;   // some pair of this tile lies above the diagonal
-#pragma unroll
-            for (int s = 0; s < 2; ++s) {
-                Frag pf[NI];
-#pragma unroll
-                for (int jb = 0; jb < 2; ++jb) {
-                    const int kb = 2 * s + jb;
-                    bf16x8 kf[NK];
-#pragma unroll
-                    for (int ks = 0; ks < NK; ++ks) kf[ks] = row_frag<HD>(kt[buf], kb, ks, r16, g);
-#pragma unroll
-                    for (int ib = 0; ib < NI; ++ib) {
-                        f32x4 c = {0.f, 0.f, 0.f, 0.f};    // S^T: key 16 kb + 4g + r, query 16 ib + r16
-#pragma unroll
-                        for (int ks = 0; ks < NK; ++ks) c = mfma16(kf[ks], qf[ib][ks], c);
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            float a = ipow<P>(scale * c[r]);
-                            if (diag && key0 + 16 * kb + 4 * g + r > q0 + 16 * ib + r16) a = 0.f;
-                            // the denominator sums the rounded weights, the ones the numerator uses:
-                            // the output is then an exact convex combination of the values
-                            const __bf16 ab = (__bf16)a;
-                            zsum[ib] += (float)ab;
-                            pf[ib].v[4 * jb + r] = ab;
-                        }
-                    }
-                }
-#pragma unroll
-                for (int vb = 0; vb < NV; ++vb) {
-                    const bf16x8 vf = col_frag<HD>(vt[buf], s, vb, r16, g);
-#pragma unroll
-                    for (int ib = 0; ib < NI; ++ib) acc[vb][ib] = mfma16(vf, pf[ib].v, acc[vb][ib]);
-                }
-            }
+            if (key0 + AT - 1 > q0) tile(std::true_type{}, buf, key0);
+            else tile(std::false_type{}, buf, key0);
         }
         if (t + 1 < ntile) {
             PA_TILE_STORE(kt[buf ^ 1], kr)
@@ -189,9 +204,7 @@ __global__ __launch_bounds__(256) void k_attn_fwd(const bf16_t* __restrict__ Q, 
     if (!active) return;
 #pragma unroll
     for (int ib = 0; ib < NI; ++ib) {
-        float z = zsum[ib];
-        z += __shfl_xor(z, 16);
-        z += __shfl_xor(z, 32);
+        const float z = zacc[ib][0];
         const float inv = normalize ? (z != 0.f ? 1.f / z : 0.f) : 1.f;
         const size_t row = head + q0 + 16 * ib + r16;
 #pragma unroll
@@ -244,8 +257,8 @@ __global__ __launch_bounds__(256) void k_attn_prep(const bf16_t* __restrict__ dO
 
 // ---- backward: dQ -----------------------------------------------------------------------------------
 // acc[fb][ib] = dQ^T: feature 16 fb + 4g + r, query 16 ib + r16.
-template <int P, int HD, int OWN>
-__global__ __launch_bounds__(256) void k_attn_dq(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
+template <int P, int HD, int OWN, int WPE>
+__global__ __launch_bounds__(256, WPE) void k_attn_dq(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
                                                  const bf16_t* __restrict__ V, const bf16_t* __restrict__ Gh,
                                                  const float* __restrict__ gz, bf16_t* __restrict__ dQ, int T,
                                                  float scale) {
@@ -279,6 +292,45 @@ __global__ __launch_bounds__(256) void k_attn_dq(const bf16_t* __restrict__ Q, c
         for (int fb = 0; fb < NF; ++fb) acc[fb][ib] = (f32x4){0.f, 0.f, 0.f, 0.f};
     }
 
+    auto tile = [&](auto diag_c, int buf, int key0) {
+        constexpr bool DIAG = decltype(diag_c)::value;
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            Frag tf[NI];
+#pragma unroll
+            for (int jb = 0; jb < 2; ++jb) {
+                const int kb = 2 * s + jb;
+                bf16x8 kf[NK], vf[NK];
+#pragma unroll
+                for (int ks = 0; ks < NK; ++ks) {
+                    kf[ks] = row_frag<HD>(kt[buf], kb, ks, r16, g);
+                    vf[ks] = row_frag<HD>(vt[buf], kb, ks, r16, g);
+                }
+#pragma unroll
+                for (int ib = 0; ib < NI; ++ib) {
+                    f32x4 c = {0.f, 0.f, 0.f, 0.f}, e = {gzq[ib], gzq[ib], gzq[ib], gzq[ib]};
+#pragma unroll
+                    for (int ks = 0; ks < NK; ++ks) {
+                        c = mfma16(kf[ks], qf[ib][ks], c);    // S^T
+                        e = mfma16(vf[ks], gf[ib][ks], e);    // E^T = V ghat^T + gz
+                    }
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        float tv = e[r] * pscale * ipow<P - 1>(scale * c[r]);
+                        if (DIAG && key0 + 16 * kb + 4 * g + r > q0 + 16 * ib + r16) tv = 0.f;
+                        tf[ib].v[4 * jb + r] = (__bf16)tv;
+                    }
+                }
+            }
+#pragma unroll
+            for (int fb = 0; fb < NF; ++fb) {
+                const bf16x8 kc = col_frag<HD>(kt[buf], s, fb, r16, g);   // K^T
+#pragma unroll
+                for (int ib = 0; ib < NI; ++ib) acc[fb][ib] = mfma16(kc, tf[ib].v, acc[fb][ib]);
+            }
+        }
+    };
+
     const int ntile = min(i0 + WG, T) / AT;
     uint4 kr[HD / 32], vr[HD / 32];
     PA_TILE_LOAD(kr, Kh)
@@ -293,42 +345,8 @@ __global__ __launch_bounds__(256) void k_attn_dq(const bf16_t* __restrict__ Q, c
             PA_TILE_LOAD(vr, Vh + (size_t)(key0 + AT) * HD)
         }
         if (active && key0 <= q0 + OWN - 1) {
-            const bool diag = key0 + AT - 1 > q0;
-#pragma unroll
-            for (int s = 0; s < 2; ++s) {
-                Frag tf[NI];
-#pragma unroll
-                for (int jb = 0; jb < 2; ++jb) {
-                    const int kb = 2 * s + jb;
-                    bf16x8 kf[NK], vf[NK];
-#pragma unroll
-                    for (int ks = 0; ks < NK; ++ks) {
-                        kf[ks] = row_frag<HD>(kt[buf], kb, ks, r16, g);
-                        vf[ks] = row_frag<HD>(vt[buf], kb, ks, r16, g);
-                    }
-#pragma unroll
-                    for (int ib = 0; ib < NI; ++ib) {
-                        f32x4 c = {0.f, 0.f, 0.f, 0.f}, e = {gzq[ib], gzq[ib], gzq[ib], gzq[ib]};
-#pragma unroll
-                        for (int ks = 0; ks < NK; ++ks) {
-                            c = mfma16(kf[ks], qf[ib][ks], c);    // S^T
-                            e = mfma16(vf[ks], gf[ib][ks], e);    // E^T = V ghat^T + gz
-                        }
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            float tv = e[r] * pscale * ipow<P - 1>(scale * c[r]);
-                            if (diag && key0 + 16 * kb + 4 * g + r > q0 + 16 * ib + r16) tv = 0.f;
-                            tf[ib].v[4 * jb + r] = (__bf16)tv;
-                        }
-                    }
-                }
-#pragma unroll
-                for (int fb = 0; fb < NF; ++fb) {
-                    const bf16x8 kc = col_frag<HD>(kt[buf], s, fb, r16, g);   // K^T
-#pragma unroll
-                    for (int ib = 0; ib < NI; ++ib) acc[fb][ib] = mfma16(kc, tf[ib].v, acc[fb][ib]);
-                }
-            }
+            if (key0 + AT - 1 > q0) tile(std::true_type{}, buf, key0);
+            else tile(std::false_type{}, buf, key0);
         }
         if (t + 1 < ntile) {
             PA_TILE_STORE(kt[buf ^ 1], kr)
@@ -355,8 +373,8 @@ __global__ __launch_bounds__(256) void k_attn_dq(const bf16_t* __restrict__ Q, c
 // dk[fb][kb] = dK^T: feature 16 fb + 4g + r, key 16 kb + r16 of the wave's OWN keys; dv likewise.
 // S and E are formed queries x keys here, so that their accumulators are the B operand (k-slots =
 // queries) of the two contractions over the queries.
-template <int P, int HD, int OWN>
-__global__ __launch_bounds__(256) void k_attn_dkdv(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
+template <int P, int HD, int OWN, int WPE>
+__global__ __launch_bounds__(256, WPE) void k_attn_dkdv(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
                                                    const bf16_t* __restrict__ V, const bf16_t* __restrict__ Gh,
                                                    const float* __restrict__ gz, bf16_t* __restrict__ dK,
                                                    bf16_t* __restrict__ dV, int T, float scale) {
@@ -392,6 +410,57 @@ __global__ __launch_bounds__(256) void k_attn_dkdv(const bf16_t* __restrict__ Q,
         }
     }
 
+    auto tile = [&](auto diag_c, int buf, int q0) {
+        constexpr bool DIAG = decltype(diag_c)::value;
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            Frag tf[NJ], pf[NJ];
+#pragma unroll
+            for (int jb = 0; jb < 2; ++jb) {
+                const int qb = 2 * s + jb;
+                bf16x8 qa[NK], ga[NK];
+#pragma unroll
+                for (int ks = 0; ks < NK; ++ks) {
+                    qa[ks] = row_frag<HD>(qt[buf], qb, ks, r16, g);
+                    ga[ks] = row_frag<HD>(gt[buf], qb, ks, r16, g);
+                }
+                const float4 gz4 = *(const float4*)&gzt[buf][16 * qb + 4 * g];
+                const f32x4 e0 = {gz4.x, gz4.y, gz4.z, gz4.w};
+#pragma unroll
+                for (int kb = 0; kb < NJ; ++kb) {
+                    f32x4 c = {0.f, 0.f, 0.f, 0.f}, e = e0;   // query 16 qb + 4g + r, key 16 kb + r16
+#pragma unroll
+                    for (int ks = 0; ks < NK; ++ks) {
+                        c = mfma16(qa[ks], kf[kb][ks], c);    // S
+                        e = mfma16(ga[ks], vf[kb][ks], e);    // E = ghat V^T + gz
+                    }
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const float sc = scale * c[r];
+                        const float pw = ipow<P - 1>(sc);
+                        float a = pw * sc, tv = e[r] * pscale * pw;
+                        if (DIAG && q0 + 16 * qb + 4 * g + r < k0 + 16 * kb + r16) {
+                            a = 0.f;
+                            tv = 0.f;
+                        }
+                        pf[kb].v[4 * jb + r] = (__bf16)a;
+                        tf[kb].v[4 * jb + r] = (__bf16)tv;
+                    }
+                }
+            }
+#pragma unroll
+            for (int fb = 0; fb < NF; ++fb) {
+                const bf16x8 qc = col_frag<HD>(qt[buf], s, fb, r16, g);   // Q^T
+                const bf16x8 gc = col_frag<HD>(gt[buf], s, fb, r16, g);   // ghat^T
+#pragma unroll
+                for (int kb = 0; kb < NJ; ++kb) {
+                    dk[fb][kb] = mfma16(qc, tf[kb].v, dk[fb][kb]);
+                    dv[fb][kb] = mfma16(gc, pf[kb].v, dv[fb][kb]);
+                }
+            }
+        }
+    };
+
     const int t_first = j0 / AT, ntile = T / AT;    // query tiles t_first .. ntile - 1 reach the block's first key
     uint4 qr[HD / 32], gr[HD / 32];
     float gzr = 0.f;
@@ -410,54 +479,8 @@ __global__ __launch_bounds__(256) void k_attn_dkdv(const bf16_t* __restrict__ Q,
             if (tid < AT) gzr = gzh[q0 + AT + tid];
         }
         if (active && q0 + AT - 1 >= k0) {
-            const bool diag = q0 < k0 + OWN - 1;    // some pair of this tile lies above the diagonal
-#pragma unroll
-            for (int s = 0; s < 2; ++s) {
-                Frag tf[NJ], pf[NJ];
-#pragma unroll
-                for (int jb = 0; jb < 2; ++jb) {
-                    const int qb = 2 * s + jb;
-                    bf16x8 qa[NK], ga[NK];
-#pragma unroll
-                    for (int ks = 0; ks < NK; ++ks) {
-                        qa[ks] = row_frag<HD>(qt[buf], qb, ks, r16, g);
-                        ga[ks] = row_frag<HD>(gt[buf], qb, ks, r16, g);
-                    }
-                    const float4 gz4 = *(const float4*)&gzt[buf][16 * qb + 4 * g];
-                    const f32x4 e0 = {gz4.x, gz4.y, gz4.z, gz4.w};
-#pragma unroll
-                    for (int kb = 0; kb < NJ; ++kb) {
-                        f32x4 c = {0.f, 0.f, 0.f, 0.f}, e = e0;   // query 16 qb + 4g + r, key 16 kb + r16
-#pragma unroll
-                        for (int ks = 0; ks < NK; ++ks) {
-                            c = mfma16(qa[ks], kf[kb][ks], c);    // S
-                            e = mfma16(ga[ks], vf[kb][ks], e);    // E = ghat V^T + gz
-                        }
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            const float sc = scale * c[r];
-                            const float pw = ipow<P - 1>(sc);
-                            float a = pw * sc, tv = e[r] * pscale * pw;
-                            if (diag && q0 + 16 * qb + 4 * g + r < k0 + 16 * kb + r16) {
-                                a = 0.f;
-                                tv = 0.f;
-                            }
-                            pf[kb].v[4 * jb + r] = (__bf16)a;
-                            tf[kb].v[4 * jb + r] = (__bf16)tv;
-                        }
-                    }
-                }
-#pragma unroll
-                for (int fb = 0; fb < NF; ++fb) {
-                    const bf16x8 qc = col_frag<HD>(qt[buf], s, fb, r16, g);   // Q^T
-                    const bf16x8 gc = col_frag<HD>(gt[buf], s, fb, r16, g);   // ghat^T
-#pragma unroll
-                    for (int kb = 0; kb < NJ; ++kb) {
-                        dk[fb][kb] = mfma16(qc, tf[kb].v, dk[fb][kb]);
-                        dv[fb][kb] = mfma16(gc, pf[kb].v, dv[fb][kb]);
-                    }
-                }
-            }
+            if (q0 < k0 + OWN - 1) tile(std::true_type{}, buf, q0);   // some pair of this tile lies above the diagonal
+            else tile(std::false_type{}, buf, q0);
         }
         if (t + 1 < ntile) {
             PA_TILE_STORE(qt[buf ^ 1], qr)
@@ -498,21 +521,25 @@ bool allow_smem(F* fn, size_t bytes) {
     return e == hipSuccess;
 }
 
-// rows of the block one wave owns: as many as the accumulators leave room for
+// Rows of the block one wave owns and the waves per SIMD the kernel is compiled for.  Two waves
+// per SIMD (at most 256 registers) let one wave's vector-ALU work run under the other's MFMAs
+// and are worth more than the larger block: measured, dK / dV at d = 64 take 1.05 ms with 32 keys
+// per wave and two waves against 1.58 ms with 64 keys and one.  Only dK / dV at d = 128 (192
+// registers of operands and accumulators per wave) cannot fit two.
 template <int HD>
-struct Own {
-    static constexpr int FWD = 64;
-    static constexpr int DQ = HD == 128 ? 32 : 64;
-    static constexpr int DKDV = HD == 128 ? 32 : 64;
+struct Shape {
+    static constexpr int FWD_OWN = HD == 128 ? 32 : 64, FWD_WPE = 2;
+    static constexpr int DQ_OWN = HD == 128 ? 32 : 64, DQ_WPE = 2;
+    static constexpr int DKDV_OWN = HD == 32 ? 64 : 32, DKDV_WPE = HD == 128 ? 1 : 2;
 };
 
 template <int P, int HD>
 bool fwd_t(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* V, bf16_t* O, float* Z, int BH, int T, float scale,
            int normalize) {
-    constexpr int WG = 4 * Own<HD>::FWD;
-    if (!allow_smem(k_attn_fwd<P, HD, Own<HD>::FWD>, attn_smem_bytes<HD>())) return false;
+    constexpr int WG = 4 * Shape<HD>::FWD_OWN;
+    if (!allow_smem(k_attn_fwd<P, HD, Shape<HD>::FWD_OWN, Shape<HD>::FWD_WPE>, attn_smem_bytes<HD>())) return false;
     LaunchScope ls("attn_fwd", s);
-    hipLaunchKernelGGL((k_attn_fwd<P, HD, Own<HD>::FWD>), dim3((T + WG - 1) / WG, BH), dim3(256), attn_smem_bytes<HD>(), s, Q, K,
+    hipLaunchKernelGGL((k_attn_fwd<P, HD, Shape<HD>::FWD_OWN, Shape<HD>::FWD_WPE>), dim3((T + WG - 1) / WG, BH), dim3(256), attn_smem_bytes<HD>(), s, Q, K,
                        V, O, Z, T, scale, normalize);
     return launch_ok();
 }
@@ -529,18 +556,18 @@ bool bwd_t(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* V, con
         if (!launch_ok()) return false;
     }
     {
-        constexpr int WG = 4 * Own<HD>::DKDV;
-        if (!allow_smem(k_attn_dkdv<P, HD, Own<HD>::DKDV>, attn_smem_bytes<HD>())) return false;
+        constexpr int WG = 4 * Shape<HD>::DKDV_OWN;
+        if (!allow_smem(k_attn_dkdv<P, HD, Shape<HD>::DKDV_OWN, Shape<HD>::DKDV_WPE>, attn_smem_bytes<HD>())) return false;
         LaunchScope ls("attn_bwd_dkdv", s);
-        hipLaunchKernelGGL((k_attn_dkdv<P, HD, Own<HD>::DKDV>), dim3((T + WG - 1) / WG, BH), dim3(256), attn_smem_bytes<HD>(), s, Q,
+        hipLaunchKernelGGL((k_attn_dkdv<P, HD, Shape<HD>::DKDV_OWN, Shape<HD>::DKDV_WPE>), dim3((T + WG - 1) / WG, BH), dim3(256), attn_smem_bytes<HD>(), s, Q,
                            K, V, Gh, gz, dK, dV, T, scale);
         if (!launch_ok()) return false;
     }
     {
-        constexpr int WG = 4 * Own<HD>::DQ;
-        if (!allow_smem(k_attn_dq<P, HD, Own<HD>::DQ>, attn_smem_bytes<HD>())) return false;
+        constexpr int WG = 4 * Shape<HD>::DQ_OWN;
+        if (!allow_smem(k_attn_dq<P, HD, Shape<HD>::DQ_OWN, Shape<HD>::DQ_WPE>, attn_smem_bytes<HD>())) return false;
         LaunchScope ls("attn_bwd_dq", s);
-        hipLaunchKernelGGL((k_attn_dq<P, HD, Own<HD>::DQ>), dim3((T + WG - 1) / WG, BH), dim3(256), attn_smem_bytes<HD>(), s, Q, K,
+        hipLaunchKernelGGL((k_attn_dq<P, HD, Shape<HD>::DQ_OWN, Shape<HD>::DQ_WPE>), dim3((T + WG - 1) / WG, BH), dim3(256), attn_smem_bytes<HD>(), s, Q, K,
                            V, Gh, gz, dQ, T, scale);
         if (!launch_ok()) return false;
     }
