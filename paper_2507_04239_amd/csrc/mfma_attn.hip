@@ -1,7 +1,7 @@
 // bf16 MFMA kernels for the attention form of power attention (arXiv 2507.04239, Sec. 2 Eq. 5 with
 // the kernel of Sec. 4 Eq. 7): the whole sequence is one chunk, no state is built,
 //     O_i = sum_{j <= i} a_ij v_j / Z_i,   a_ij = (scale q_i . k_j)^p,   Z_i = sum_{j <= i} a_ij,
-// for any degree p and head sizes d = v in {32, 64, 128}.  The paper switches to this form where
+// for degrees p in {2, 3, 4}, head sizes d = v in {32, 64, 128} and any sequence length.  The paper switches to this form where
 // it is the cheaper one (Sec. 5, throughput comparison); here it is also what runs the degrees and
 // head sizes the chunked MFMA family (p = 2, d = 64) does not cover.
 //
@@ -51,16 +51,21 @@ __device__ __forceinline__ float ipow<4>(float x) {
 // piece id = tid + 256 q is row id / (HD / 8), features 8 (id % (HD / 8)) .. + 7.  The pieces wait
 // in registers while the tile before them is being used (plain arrays and unrolled loops in the
 // kernels: wrapped in a struct they end up in scratch memory).
-template <int HD>
-__device__ __forceinline__ uint4 piece_load(const bf16_t* __restrict__ src, int id) {
-    return *(const uint4*)(src + (size_t)(id / (HD / 8)) * HD + 8 * (id % (HD / 8)));
+// T need not be a multiple of the tile: rows past the end are read as row T - 1 (keys and queries
+// there are masked out by causality, or never stored) or, with ZERO, as zeros (ghat, whose rows
+// past the end must not contribute to dK, dV).
+template <int HD, bool ZERO>
+__device__ __forceinline__ uint4 piece_load(const bf16_t* __restrict__ head_base, int row0, int id, int T) {
+    const int row = row0 + id / (HD / 8);
+    const uint4 u = *(const uint4*)(head_base + (size_t)min(row, T - 1) * HD + 8 * (id % (HD / 8)));
+    return ZERO && row >= T ? make_uint4(0, 0, 0, 0) : u;
 }
 template <int HD>
 __device__ __forceinline__ void piece_store(AttnTile<HD>& dst, int id, uint4 u) {
     *(uint4*)&dst.r[id / (HD / 8)][8 * (id % (HD / 8))] = u;
 }
-#define PA_TILE_LOAD(REGS, SRC)                     \
-    _Pragma("unroll") for (int q_ = 0; q_ < HD / 32; ++q_) REGS[q_] = piece_load<HD>(SRC, tid + 256 * q_);
+#define PA_TILE_LOAD(REGS, BASE, ROW0, ZERO)        \
+    _Pragma("unroll") for (int q_ = 0; q_ < HD / 32; ++q_) REGS[q_] = piece_load<HD, ZERO>(BASE, ROW0, tid + 256 * q_, T);
 #define PA_TILE_STORE(DST, REGS)                    \
     _Pragma("unroll") for (int q_ = 0; q_ < HD / 32; ++q_) piece_store<HD>(DST, tid + 256 * q_, REGS[q_]);
 
@@ -117,7 +122,7 @@ __global__ __launch_bounds__(256, WPE) void k_attn_fwd(const bf16_t* __restrict_
     const int nblk = (T + WG - 1) / WG;
     const int i0 = heavy_first(nblk, true) * WG;
     const int q0 = i0 + OWN * w;                    // the wave's first query
-    const bool active = q0 < T;                     // T is a multiple of 64, and so is q0 or q0 + 32
+    const bool active = q0 < T;
     const size_t head = (size_t)blockIdx.y * T;
     const bf16_t* Kh = K + head * HD;
     const bf16_t* Vh = V + head * HD;
@@ -177,18 +182,18 @@ __global__ __launch_bounds__(256, WPE) void k_attn_fwd(const bf16_t* __restrict_
         }
     };
 
-    const int ntile = min(i0 + WG, T) / AT;         // key tiles 0 .. ntile - 1 reach the block's last query
+    const int ntile = (min(i0 + WG, T) + AT - 1) / AT;   // key tiles 0 .. ntile - 1 reach the block's last query
     uint4 kr[HD / 32], vr[HD / 32];
-    PA_TILE_LOAD(kr, Kh)
-    PA_TILE_LOAD(vr, Vh)
+    PA_TILE_LOAD(kr, Kh, 0, false)
+    PA_TILE_LOAD(vr, Vh, 0, false)
     PA_TILE_STORE(kt[0], kr)
     PA_TILE_STORE(vt[0], vr)
     __syncthreads();
     for (int t = 0; t < ntile; ++t) {
         const int buf = t & 1, key0 = t * AT;
         if (t + 1 < ntile) {
-            PA_TILE_LOAD(kr, Kh + (size_t)(key0 + AT) * HD)
-            PA_TILE_LOAD(vr, Vh + (size_t)(key0 + AT) * HD)
+            PA_TILE_LOAD(kr, Kh, key0 + AT, false)
+            PA_TILE_LOAD(vr, Vh, key0 + AT, false)
         }
         if (active && key0 <= q0 + OWN - 1) {
             if (key0 + AT - 1 > q0) tile(std::true_type{}, buf, key0);
@@ -206,6 +211,7 @@ __global__ __launch_bounds__(256, WPE) void k_attn_fwd(const bf16_t* __restrict_
     for (int ib = 0; ib < NI; ++ib) {
         const float z = zacc[ib][0];
         const float inv = normalize ? (z != 0.f ? 1.f / z : 0.f) : 1.f;
+        if (q0 + 16 * ib + r16 >= T) continue;      // past the end of a sequence that is not a multiple of the block
         const size_t row = head + q0 + 16 * ib + r16;
 #pragma unroll
         for (int vb = 0; vb < NV; ++vb) {
@@ -331,18 +337,18 @@ __global__ __launch_bounds__(256, WPE) void k_attn_dq(const bf16_t* __restrict__
         }
     };
 
-    const int ntile = min(i0 + WG, T) / AT;
+    const int ntile = (min(i0 + WG, T) + AT - 1) / AT;
     uint4 kr[HD / 32], vr[HD / 32];
-    PA_TILE_LOAD(kr, Kh)
-    PA_TILE_LOAD(vr, Vh)
+    PA_TILE_LOAD(kr, Kh, 0, false)
+    PA_TILE_LOAD(vr, Vh, 0, false)
     PA_TILE_STORE(kt[0], kr)
     PA_TILE_STORE(vt[0], vr)
     __syncthreads();
     for (int t = 0; t < ntile; ++t) {
         const int buf = t & 1, key0 = t * AT;
         if (t + 1 < ntile) {
-            PA_TILE_LOAD(kr, Kh + (size_t)(key0 + AT) * HD)
-            PA_TILE_LOAD(vr, Vh + (size_t)(key0 + AT) * HD)
+            PA_TILE_LOAD(kr, Kh, key0 + AT, false)
+            PA_TILE_LOAD(vr, Vh, key0 + AT, false)
         }
         if (active && key0 <= q0 + OWN - 1) {
             if (key0 + AT - 1 > q0) tile(std::true_type{}, buf, key0);
@@ -358,6 +364,7 @@ __global__ __launch_bounds__(256, WPE) void k_attn_dq(const bf16_t* __restrict__
     if (!active) return;
 #pragma unroll
     for (int ib = 0; ib < NI; ++ib) {
+        if (q0 + 16 * ib + r16 >= T) continue;
         const size_t row = head + q0 + 16 * ib + r16;
 #pragma unroll
         for (int fb = 0; fb < NF; ++fb) {
@@ -461,12 +468,12 @@ __global__ __launch_bounds__(256, WPE) void k_attn_dkdv(const bf16_t* __restrict
         }
     };
 
-    const int t_first = j0 / AT, ntile = T / AT;    // query tiles t_first .. ntile - 1 reach the block's first key
+    const int t_first = j0 / AT, ntile = (T + AT - 1) / AT;    // query tiles t_first .. ntile - 1 reach the block's first key
     uint4 qr[HD / 32], gr[HD / 32];
     float gzr = 0.f;
-    PA_TILE_LOAD(qr, Qh + (size_t)t_first * AT * HD)
-    PA_TILE_LOAD(gr, Gh_h + (size_t)t_first * AT * HD)
-    if (tid < AT) gzr = gzh[t_first * AT + tid];
+    PA_TILE_LOAD(qr, Qh, t_first * AT, false)
+    PA_TILE_LOAD(gr, Gh_h, t_first * AT, true)
+    if (tid < AT) gzr = t_first * AT + tid < T ? gzh[t_first * AT + tid] : 0.f;
     PA_TILE_STORE(qt[0], qr)
     PA_TILE_STORE(gt[0], gr)
     if (tid < AT) gzt[0][tid] = gzr;
@@ -474,9 +481,9 @@ __global__ __launch_bounds__(256, WPE) void k_attn_dkdv(const bf16_t* __restrict
     for (int t = t_first; t < ntile; ++t) {
         const int buf = (t - t_first) & 1, q0 = t * AT;
         if (t + 1 < ntile) {
-            PA_TILE_LOAD(qr, Qh + (size_t)(q0 + AT) * HD)
-            PA_TILE_LOAD(gr, Gh_h + (size_t)(q0 + AT) * HD)
-            if (tid < AT) gzr = gzh[q0 + AT + tid];
+            PA_TILE_LOAD(qr, Qh, q0 + AT, false)
+            PA_TILE_LOAD(gr, Gh_h, q0 + AT, true)
+            if (tid < AT) gzr = q0 + AT + tid < T ? gzh[q0 + AT + tid] : 0.f;
         }
         if (active && q0 + AT - 1 >= k0) {
             if (q0 < k0 + OWN - 1) tile(std::true_type{}, buf, q0);   // some pair of this tile lies above the diagonal
@@ -493,6 +500,7 @@ __global__ __launch_bounds__(256, WPE) void k_attn_dkdv(const bf16_t* __restrict
     if (!active) return;
 #pragma unroll
     for (int kb = 0; kb < NJ; ++kb) {
+        if (k0 + 16 * kb + r16 >= T) continue;
         const size_t row = head + k0 + 16 * kb + r16;
 #pragma unroll
         for (int fb = 0; fb < NF; ++fb) {

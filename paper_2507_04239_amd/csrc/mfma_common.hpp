@@ -95,7 +95,7 @@ bool launch_bwd_dkdv(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16
 bool launch_gate_boundary(hipStream_t s, const bf16_t* stC, const bf16_t* rtC, const bf16_t* gam, const bf16_t* omg, float* xb,
                           int BH, int nstate);
 
-// attention form (chunk == T): p in {2, 3, 4}, d = v in {32, 64, 128}, T a multiple of 64.
+// attention form (chunk == T): p in {2, 3, 4}, d = v in {32, 64, 128}, any T.
 // Gh [BH][T][d] bf16 and gz [BH][T] float32 are scratch of the backward pass.
 bool attn_shape_ok(int p, int d);
 bool launch_attn_fwd(hipStream_t s, int p, int d, const bf16_t* Q, const bf16_t* K, const bf16_t* V, bf16_t* O, float* Z, int BH,

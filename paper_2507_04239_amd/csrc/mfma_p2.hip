@@ -58,8 +58,8 @@ bool chunked_ok(const pa_problem& pr) {
            (size_t)pr.B * pr.H <= 65535u;
 }
 bool attn_ok(const pa_problem& pr) {
-    return pr.dtype == PA_DTYPE_BF16 && pr.d == pr.v && attn_shape_ok(pr.p, pr.d) && pr.chunk == pr.T && pr.T % 64 == 0 &&
-           !pr.gated && (size_t)pr.B * pr.H <= 65535u;
+    return pr.dtype == PA_DTYPE_BF16 && pr.d == pr.v && attn_shape_ok(pr.p, pr.d) && pr.chunk == pr.T && !pr.gated &&
+           (size_t)pr.B * pr.H <= 65535u;
 }
 // One chunk: the attention-form kernels.  (The chunked kernels can run p = 2, d = 64 as one chunk
 // too; that path remains for gated problems, which the attention-form kernels do not take.)

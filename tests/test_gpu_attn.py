@@ -24,6 +24,13 @@ CASES = [
     (3, 64, 1, 2, 384, False, 1.0),      # odd degree: signed weights, un-normalised only
     (3, 32, 1, 1, 128, False, 0.8),
     (3, 128, 1, 1, 320, False, 1.0),
+    # sequence lengths that are not a multiple of the 64-row tile, nor of a wave's rows
+    (2, 64, 1, 2, 333, True, 1.0),
+    (4, 32, 1, 1, 65, True, 1.0),
+    (2, 128, 1, 1, 271, True, 1.0),
+    (2, 64, 1, 1, 17, True, 1.0),
+    (3, 32, 2, 1, 100, False, 1.0),
+    (2, 128, 1, 1, 1, True, 1.0),        # a single token
 ]
 
 
