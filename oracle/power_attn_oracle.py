@@ -18,6 +18,8 @@ What it follows (arXiv 2507.04239):
   * the backward pass is not in the paper; it is derived here from the definition
     of the forward pass and pinned by finite differences in the tests.
   * gating (Sec. 2 "Gating", App. E.2 / E.3): per-timestep log-gates, see the section below.
+  * the single-token decode step: one iteration of the recurrent form with the state kept
+    between calls.
 
 Conventions: arrays of one head are 2-D, ``Q, K: [T, d]``, ``V, G: [T, v]``.  ``scale``
 multiplies the score before the power, ``s_ij = scale * (q_i . k_j)``.  A row whose
@@ -442,6 +444,31 @@ def fwd_recurrent_gated(Q, K, V, log_g, p: int, normalize: bool = True, scale: f
         Z[i] = y[v]
         O[i] = (y[:v] / y[v] if y[v] != 0.0 else 0.0) if normalize else y[:v]
     return O, Z
+
+
+# --------------------------------------------------------------------------------------
+# Single-token decode step (Sec. 2 Eq. (6), one iteration; the inference use of App. D)
+# --------------------------------------------------------------------------------------
+
+def decode_state_init(d: int, v: int, p: int) -> np.ndarray:
+    """The empty state: D x (v + 1) zeros, D = C(d + p - 1, p); column v is the normaliser."""
+    return np.zeros((dim_spow(d, p), v + 1), dtype=F64)
+
+
+def decode_step(S, q, k, v, p: int, normalize: bool = True, scale: float = 1.0, log_g=None):
+    """One token: S' = g S + phi(k) [v, 1]^T, then y = S'^T phi(scale q) (the token attends to
+    itself).  Returns (S', o [v], z); g = exp(log_g), 1 when log_g is None."""
+    S = np.asarray(S, dtype=F64)
+    vv = np.asarray(v, dtype=F64)
+    g = 1.0 if log_g is None else math.exp(float(log_g))
+    S_new = g * S + np.outer(spow(np.asarray(k, dtype=F64), p), np.append(vv, 1.0))
+    y = spow(scale * np.asarray(q, dtype=F64), p) @ S_new
+    z = y[-1]
+    if normalize:
+        o = y[:-1] / z if z != 0.0 else np.zeros_like(vv)
+    else:
+        o = y[:-1]
+    return S_new, o, z
 
 
 def _chunk_gate_factors(b: np.ndarray, lo: int, hi: int):
