@@ -127,6 +127,57 @@ def cpu_baseline(w, heads):
                       f"scaled by {heads}/{w['H']}", "seconds": dt}
 
 
+def decode_bench(args, name, w):
+    """One decode step = one new token for each of --decode-batch sequences, all heads; the state
+    (D x (v+1) float32 per head) is read and written once per step."""
+    import torch
+    from paper_2507_04239_amd import binding
+    B, H, d, p = args.decode_batch, w["H"], w["d"], w["p"]
+    dev = torch.device("cuda:0")
+    tdt = torch.bfloat16 if w["dtype"] == "bf16" else torch.float32
+    prob = binding.make_problem(B, H, 1, d, d, p, 1, True, 1.0, w["dtype"], "auto", False, args.gated)
+    state = binding.power_attn_decode_init(prob)
+    g = torch.Generator(device=dev)
+    g.manual_seed(2000 + w["position"])
+    q = (torch.randn((B, H, d), device=dev, generator=g) * d ** -0.5).to(tdt)
+    k = (torch.randn((B, H, d), device=dev, generator=g) * d ** -0.5).to(tdt)
+    v = torch.randn((B, H, d), device=dev, generator=g).to(tdt)
+    lg = -0.02 * torch.rand((B, H), device=dev, generator=g) if args.gated else None
+    o = torch.empty_like(v)
+    z = torch.empty((B, H), dtype=torch.float32, device=dev)
+
+    def step():
+        binding.power_attn_decode_step(prob, q, k, v, state, lg, out=o, out_z=z)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    binding.profile_begin()
+    for _ in range(args.steps):
+        step()
+    kernels = binding.profile_end()
+    D = math.comb(d + p - 1, p)
+    alg_bytes = 2 * B * H * D * (d + 1) * 4                 # the state, read and written once
+    kms = kernels["decode_step"][1] / kernels["decode_step"][0]
+    achieved = alg_bytes / (kms * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": "power-attention decode tokens/sec (one token per sequence and step, state resident)",
+        "value": B / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32 state, " + w["dtype"] + " tokens",
+        "data": "synthetic",
+        "config": {"workload": name + " head shape, decode", "B": B, "H": H, "d": d, "p": p, "state_rows": D, "gated": args.gated},
+        "roofline": {"bound": "hbm", "kernel": "decode_step", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": achieved / PEAK_HBM_GBS, "traffic": None, "avg_kernel_ms": kms,
+                     "algorithmic_bytes_per_launch": alg_bytes},
+        "kernels": {n: {"launches_per_step": l / args.steps, "avg_ms": t / l} for n, (l, t) in kernels.items()},
+    }), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -148,6 +199,9 @@ def main():
                     help="time the gated layer (per-timestep log-gates, mean decay 0.02 per step) instead of the headline one")
     ap.add_argument("--recompute-states", action="store_true",
                     help="backward pass rebuilds the chunk states instead of reusing the forward pass's workspace")
+    ap.add_argument("--decode-batch", type=int, default=0,
+                    help="instead of the training step: time the single-token decode step of the workload's head shape "
+                         "on this many sequences (state resident in HBM)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures one GPU only (the path shards over batch and heads with no "
@@ -158,6 +212,8 @@ def main():
 
     name = args.workload or inputs.HEADLINE
     w = dict(inputs.WORKLOADS[name])
+    if args.decode_batch > 0:
+        return decode_bench(args, name, w)
     oracle_chunk = w["chunk"]
     if args.chunk is not None:
         w["chunk"] = args.chunk

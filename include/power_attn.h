@@ -123,6 +123,28 @@ pa_status power_attn_bwd_gated(const pa_problem* prob,
                                void* dQ, void* dK, void* dV, float* dlog_g,
                                void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* ---- single-token decode step ----------------------------------------------------------------
+ * The recurrent form (Sec. 2 Eq. (6)), one iteration per call, with the state kept in device
+ * memory between calls (the fixed-cost inference of App. D):
+ *     S <- g S + phi(k) [v, 1]^T,    y = S^T phi(scale q),    o = y[:v] / y[v]  (normalize)  or  y[:v]
+ * i.e. after n steps on k_1..k_n, v_1..v_n the output equals row n of power_attn_fwd on the same
+ * sequence (with the same gates).  Of `prob` the fields B, H, d, v, p, normalize, scale, dtype and
+ * gated are used (1 <= p <= 4, d, v <= 128); T, chunk, impl and keep_state are ignored.
+ *
+ * state: DEVICE, caller-owned, power_attn_decode_state_bytes(prob) bytes, float32 inside; it
+ * belongs to one (prob, sequence batch) and must be initialised by power_attn_decode_init before
+ * the first step (which also builds the index table the steps read).  q, k: DEVICE [B, H, d];
+ * v, o: DEVICE [B, H, v], in prob->dtype; z (may be NULL): DEVICE float32 [B, H], the
+ * denominator; log_g: DEVICE float32 [B, H], log of this step's gate (<= 0), required when
+ * prob->gated, else must be NULL.  Calls are queued on hip_stream and return at once; steps on one
+ * state must be ordered by the caller (same stream).  Errors as for the other calls; nothing is
+ * launched when validation fails. */
+size_t power_attn_decode_state_bytes(const pa_problem* prob);     /* 0 if the problem is invalid or unsupported */
+pa_status power_attn_decode_init(const pa_problem* prob, void* state, size_t state_bytes, void* hip_stream);
+pa_status power_attn_decode_step(const pa_problem* prob, const void* q, const void* k, const void* v,
+                                 const float* log_g, void* state, size_t state_bytes,
+                                 void* o, float* z, void* hip_stream);
+
 /* The chunk size the calls use for `prob` (prob->chunk itself unless it is 0; 0 on an invalid problem). */
 int power_attn_resolved_chunk(const pa_problem* prob);
 

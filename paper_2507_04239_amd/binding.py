@@ -20,6 +20,9 @@ _IMPL = {"auto": PA_IMPL_AUTO, "generic": PA_IMPL_GENERIC, "mfma": PA_IMPL_MFMA}
 EXPORTED_SYMBOLS = (
     "power_attn_workspace_bytes",
     "power_attn_supported",
+    "power_attn_decode_state_bytes",
+    "power_attn_decode_init",
+    "power_attn_decode_step",
     "power_attn_fwd",
     "power_attn_bwd",
     "power_attn_fwd_gated",
@@ -79,6 +82,12 @@ def load_library():
     lib.power_attn_resolved_chunk.argtypes = [P]
     lib.power_attn_state_rows.restype = ctypes.c_longlong
     lib.power_attn_state_rows.argtypes = [P]
+    lib.power_attn_decode_state_bytes.restype = ctypes.c_size_t
+    lib.power_attn_decode_state_bytes.argtypes = [P]
+    lib.power_attn_decode_init.restype = ctypes.c_int
+    lib.power_attn_decode_init.argtypes = [P, vp, ctypes.c_size_t, vp]
+    lib.power_attn_decode_step.restype = ctypes.c_int
+    lib.power_attn_decode_step.argtypes = [P, vp, vp, vp, vp, vp, ctypes.c_size_t, vp, vp, vp]
     lib.power_attn_fwd.restype = ctypes.c_int
     lib.power_attn_fwd.argtypes = [P, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.power_attn_bwd.restype = ctypes.c_int
@@ -253,3 +262,36 @@ def profile_end(max_entries: int = 64):
     n = ctypes.c_int(0)
     _check(lib, lib.power_attn_profile_end(arr, max_entries, ctypes.byref(n)), "power_attn_profile_end")
     return {arr[i].name.decode(): (int(arr[i].launches), float(arr[i].ms_total)) for i in range(n.value)}
+
+
+def power_attn_decode_state_bytes(prob: PaProblem) -> int:
+    return int(load_library().power_attn_decode_state_bytes(ctypes.byref(prob)))
+
+
+def power_attn_decode_init(prob: PaProblem, state=None):
+    """-> the initialised (empty) state of a decode session: a uint8 tensor on the current device
+    (allocated here unless one of sufficient size is passed in)."""
+    import torch
+    lib = load_library()
+    need = int(lib.power_attn_decode_state_bytes(ctypes.byref(prob)))
+    if need == 0:
+        raise PowerAttnError("power_attn_decode_init: invalid or unsupported problem")
+    if state is None:
+        state = torch.empty(need, dtype=torch.uint8, device=torch.device("cuda", torch.cuda.current_device()))
+    _check(lib, lib.power_attn_decode_init(ctypes.byref(prob), _dev_ptr(state, name="state"), state.numel(), _stream()),
+           "power_attn_decode_init")
+    return state
+
+
+def power_attn_decode_step(prob: PaProblem, q, k, v, state, log_g=None, out=None, out_z=None):
+    """One token for every (batch, head): q, k [B, H, d], v [B, H, v] -> (o [B, H, v], z [B, H]); the
+    state is updated in place."""
+    import torch
+    lib = load_library()
+    o = out if out is not None else torch.empty_like(v)
+    z = out_z if out_z is not None else torch.empty(v.shape[:2], dtype=torch.float32, device=v.device)
+    lg = None if log_g is None else _dev_ptr(log_g, name="log_g")
+    _check(lib, lib.power_attn_decode_step(ctypes.byref(prob), _dev_ptr(q, name="q"), _dev_ptr(k, q, "k"), _dev_ptr(v, q, "v"), lg,
+                                           _dev_ptr(state, name="state"), state.numel(), _dev_ptr(o, q, "o"),
+                                           _dev_ptr(z, name="z"), _stream()), "power_attn_decode_step")
+    return o, z

@@ -90,6 +90,15 @@ pa_status gate_gradient(const Ctx& c, const void* Q, const void* K, const void* 
 // generic (vector-ALU, float32) family
 size_t generic_workspace_bytes(const pa_problem& pr, bool backward);
 long long generic_state_rows(const pa_problem& pr);
+// Row r of the lexicographic list of non-decreasing multi-indices of Lemma 4.2 -> idx[r] (uchar4, its
+// p indices padded with 0) and mult[r] (its multiplicity p! / prod(run lengths)!); device arrays of D rows
+bool build_monomial_table(hipStream_t s, int d, int p, long long D, void* idx, float* mult);
+
+// single-token decode step (state resident between calls)
+size_t decode_state_bytes(const pa_problem& pr);
+pa_status decode_init(const pa_problem& pr, void* state, hipStream_t s);
+pa_status decode_step(const pa_problem& pr, const void* q, const void* k, const void* v, const float* log_g, void* state, void* o,
+                      float* z, hipStream_t s);
 pa_status generic_supported(const pa_problem& pr);
 pa_status generic_fwd(const Ctx& c, const void* Q, const void* K, const void* V, void* O, float* Z);
 pa_status generic_bwd(const Ctx& c, const void* Q, const void* K, const void* V, const void* O, const float* Z,

@@ -1,0 +1,285 @@
+// Single-token decode step of power attention: the recurrent form of arXiv 2507.04239, Sec. 2
+// Eq. (6), one iteration per call with the state resident in device memory between calls
+// (the constant-cost inference the paper argues for in App. D):
+//     S <- g S + phi(k) [v, 1]^T,      y = S^T phi(scale q),      o = y[:v] / y[v].
+//
+// Embedding as in the generic kernel family: the monomials psi(x)_r = prod_z x[i_z] over the
+// non-decreasing multi-indices of Lemma 4.2, with the integer multiplicity m_r on the state only
+// (S_r = sum m_r psi(k)_r [v, 1]), read out with the bare psi(q): the product is (q.k)^p.
+//
+// The state is float32 and caller-owned; one buffer per problem holds
+//     S     [B*H][D][v]     the value part
+//     gamma [B*H][D]        the normaliser column
+//     idx   [D] uchar4, mult [D] float   the multi-index table (built by decode_init)
+//     part  [B*H][nblk][v+1]             partial read-outs of the step in flight
+// A step reads and writes S and gamma once: it is bound by HBM bandwidth, 8 bytes per state
+// element and token.
+#include "common.hpp"
+
+namespace pa {
+namespace {
+
+constexpr int DRB = 128;   // state rows per workgroup
+constexpr int DMAX = 128;  // largest head size
+
+template <int P>
+__device__ __forceinline__ float monomial(const float* __restrict__ x, uchar4 ix) {
+    float c = x[ix.x];
+    if (P > 1) c *= x[ix.y];
+    if (P > 2) c *= x[ix.z];
+    if (P > 3) c *= x[ix.w];
+    return c;
+}
+
+struct DecodeLayout {
+    long long D;
+    int nblk;
+    size_t off_s, off_gam, off_idx, off_mult, off_part, total;
+};
+
+DecodeLayout make_decode_layout(const pa_problem& pr) {
+    DecodeLayout L;
+    L.D = generic_state_rows(pr);
+    L.nblk = (int)((L.D + DRB - 1) / DRB);
+    const size_t BH = (size_t)pr.B * pr.H;
+    size_t off = 0;
+    L.off_s = off;    off = align_up(off + BH * (size_t)L.D * pr.v * sizeof(float), 256);
+    L.off_gam = off;  off = align_up(off + BH * (size_t)L.D * sizeof(float), 256);
+    L.off_idx = off;  off = align_up(off + (size_t)L.D * sizeof(uchar4), 256);
+    L.off_mult = off; off = align_up(off + (size_t)L.D * sizeof(float), 256);
+    L.off_part = off; off = align_up(off + BH * (size_t)L.nblk * (pr.v + 1) * sizeof(float), 256);
+    L.total = off;
+    return L;
+}
+
+__global__ __launch_bounds__(256) void k_decode_zero(float4* __restrict__ p, size_t n4) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (size_t)gridDim.x * 256)
+        p[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+}
+
+// grid (nblk, B*H): rows [DRB blk, DRB (blk + 1)) of one head's state.  A wave takes one row at
+// a time (its lanes the value columns: 256-byte runs), then the block's rows of the normaliser
+// column go one per thread.
+template <typename T, int P>
+__global__ __launch_bounds__(256) void k_decode_step(const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ vin,
+                                                     const float* __restrict__ log_g, float* __restrict__ S,
+                                                     float* __restrict__ gam, const uchar4* __restrict__ idx,
+                                                     const float* __restrict__ mult, float* __restrict__ part, long long D,
+                                                     int d, int v, float scale) {
+    __shared__ float qs[DMAX], ks[DMAX], vs[DMAX];
+    __shared__ float red[4][DMAX + 1];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int blk = blockIdx.x, bh = blockIdx.y, nblk = gridDim.x;
+    if (tid < d) {
+        qs[tid] = scale * io<T>::ld(q + (size_t)bh * d + tid);
+        ks[tid] = io<T>::ld(k + (size_t)bh * d + tid);
+    }
+    if (tid < v) vs[tid] = io<T>::ld(vin + (size_t)bh * v + tid);
+    const float g = log_g != nullptr ? __expf(log_g[bh]) : 1.f;
+    __syncthreads();
+
+    const long long r_begin = (long long)blk * DRB;
+    const long long r_end = r_begin + DRB < D ? r_begin + DRB : D;
+    float y0 = 0.f, y1 = 0.f;
+    const float v0 = lane < v ? vs[lane] : 0.f, v1 = lane + 64 < v ? vs[lane + 64] : 0.f;
+    for (long long r = r_begin + w; r < r_end; r += 4) {
+        const uchar4 ix = idx[r];
+        const float ck = mult[r] * monomial<P>(ks, ix), cq = monomial<P>(qs, ix);
+        float* row = S + ((size_t)bh * D + r) * v;
+        if (lane < v) {
+            const float s = g * row[lane] + ck * v0;
+            row[lane] = s;
+            y0 += cq * s;
+        }
+        if (lane + 64 < v) {
+            const float s = g * row[lane + 64] + ck * v1;
+            row[lane + 64] = s;
+            y1 += cq * s;
+        }
+    }
+    float zp = 0.f;
+    for (long long r = r_begin + tid; r < r_end; r += 256) {
+        const uchar4 ix = idx[r];
+        const float ck = mult[r] * monomial<P>(ks, ix), cq = monomial<P>(qs, ix);
+        const float s = g * gam[(size_t)bh * D + r] + ck;
+        gam[(size_t)bh * D + r] = s;
+        zp += cq * s;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) zp += __shfl_xor(zp, off);
+    red[w][lane] = y0;
+    red[w][lane + 64] = y1;
+    if (lane == 0) red[w][DMAX] = zp;
+    __syncthreads();
+    if (tid <= v) {
+        const int c = tid < v ? tid : DMAX;
+        part[((size_t)bh * nblk + blk) * (v + 1) + tid] = red[0][c] + red[1][c] + red[2][c] + red[3][c];
+    }
+}
+
+// The same for v in {4, 8, ..., 128} (a power of two): v / 4 lanes share a row, each with four
+// columns (16-byte accesses), so a wave has 256 / v rows in flight per pass and two passes
+// unrolled - the row-at-a-time kernel above leaves the memory system mostly idle.
+template <typename T, int P, int V>
+__global__ __launch_bounds__(256) void k_decode_step_vec(const T* __restrict__ q, const T* __restrict__ k,
+                                                         const T* __restrict__ vin, const float* __restrict__ log_g,
+                                                         float* __restrict__ S, float* __restrict__ gam,
+                                                         const uchar4* __restrict__ idx, const float* __restrict__ mult,
+                                                         float* __restrict__ part, long long D, int d, float scale) {
+    constexpr int LPR = V / 4, RPW = 64 / LPR, RPB = 4 * RPW;   // lanes per row, rows per wave and per block pass
+    __shared__ float qs[DMAX], ks[DMAX];
+    __shared__ __attribute__((aligned(16))) float vs[DMAX];
+    __shared__ __attribute__((aligned(16))) float red[4][DMAX + 4];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int blk = blockIdx.x, bh = blockIdx.y, nblk = gridDim.x;
+    if (tid < d) {
+        qs[tid] = scale * io<T>::ld(q + (size_t)bh * d + tid);
+        ks[tid] = io<T>::ld(k + (size_t)bh * d + tid);
+    }
+    if (tid < V) vs[tid] = io<T>::ld(vin + (size_t)bh * V + tid);
+    const float g = log_g != nullptr ? __expf(log_g[bh]) : 1.f;
+    __syncthreads();
+
+    const long long r_begin = (long long)blk * DRB;
+    const long long r_end = r_begin + DRB < D ? r_begin + DRB : D;
+    const int c4 = lane % LPR, rl = w * RPW + lane / LPR;        // column quad, row inside a block pass
+    const float4 vv = *(const float4*)&vs[4 * c4];
+    float4 y = make_float4(0.f, 0.f, 0.f, 0.f);
+    static_assert(DRB % (2 * RPB) == 0 || RPB > DRB / 2, "two passes per trip");
+    for (long long r0 = r_begin; r0 < r_end; r0 += 2 * RPB) {
+        const long long ra = r0 + rl, rb = r0 + RPB + rl;
+        const bool oka = ra < r_end, okb = rb < r_end;
+        float4* pa = (float4*)(S + ((size_t)bh * D + (oka ? ra : r_begin)) * V) + c4;
+        float4* pb = (float4*)(S + ((size_t)bh * D + (okb ? rb : r_begin)) * V) + c4;
+        const float4 sa = *pa, sb = *pb;
+        const uchar4 ia = idx[oka ? ra : r_begin], ib = idx[okb ? rb : r_begin];
+        const float cka = mult[oka ? ra : r_begin] * monomial<P>(ks, ia), cqa = oka ? monomial<P>(qs, ia) : 0.f;
+        const float ckb = mult[okb ? rb : r_begin] * monomial<P>(ks, ib), cqb = okb ? monomial<P>(qs, ib) : 0.f;
+        const float4 na = make_float4(g * sa.x + cka * vv.x, g * sa.y + cka * vv.y, g * sa.z + cka * vv.z, g * sa.w + cka * vv.w);
+        const float4 nb = make_float4(g * sb.x + ckb * vv.x, g * sb.y + ckb * vv.y, g * sb.z + ckb * vv.z, g * sb.w + ckb * vv.w);
+        if (oka) *pa = na;
+        if (okb) *pb = nb;
+        y.x += cqa * na.x + cqb * nb.x;
+        y.y += cqa * na.y + cqb * nb.y;
+        y.z += cqa * na.z + cqb * nb.z;
+        y.w += cqa * na.w + cqb * nb.w;
+    }
+    float zp = 0.f;
+    for (long long r = r_begin + tid; r < r_end; r += 256) {
+        const uchar4 ix = idx[r];
+        const float ck = mult[r] * monomial<P>(ks, ix), cq = monomial<P>(qs, ix);
+        const float s = g * gam[(size_t)bh * D + r] + ck;
+        gam[(size_t)bh * D + r] = s;
+        zp += cq * s;
+    }
+    // rows of a wave: lanes LPR apart hold the same columns
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1) {
+        y.x += __shfl_xor(y.x, off);
+        y.y += __shfl_xor(y.y, off);
+        y.z += __shfl_xor(y.z, off);
+        y.w += __shfl_xor(y.w, off);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) zp += __shfl_xor(zp, off);
+    if (lane < LPR) *(float4*)&red[w][4 * lane] = y;
+    if (lane == 0) red[w][DMAX] = zp;
+    __syncthreads();
+    if (tid <= V) {
+        const int c = tid < V ? tid : DMAX;
+        part[((size_t)bh * nblk + blk) * (V + 1) + tid] = red[0][c] + red[1][c] + red[2][c] + red[3][c];
+    }
+}
+
+// grid B*H: sums the blocks' partial read-outs, divides, stores
+template <typename T>
+__global__ __launch_bounds__(256) void k_decode_finish(const float* __restrict__ part, int nblk, T* __restrict__ o,
+                                                       float* __restrict__ z, int v, int normalize) {
+    __shared__ float zs;
+    const int bh = blockIdx.x, tid = threadIdx.x;
+    float acc = 0.f;
+    if (tid <= v)
+        for (int b = 0; b < nblk; ++b) acc += part[((size_t)bh * nblk + b) * (v + 1) + tid];
+    if (tid == v) zs = acc;
+    __syncthreads();
+    const float zz = zs;
+    if (tid < v) {
+        const float inv = normalize ? (zz != 0.f ? 1.f / zz : 0.f) : 1.f;
+        io<T>::st(o + (size_t)bh * v + tid, acc * inv);
+    }
+    if (tid == v && z != nullptr) z[bh] = zz;
+}
+
+pa_status decode_supported(const pa_problem& pr) {
+    if (pr.p < 1 || pr.p > 4 || pr.d > DMAX || pr.v > DMAX) return PA_ERR_UNSUPPORTED;
+    if ((size_t)pr.B * pr.H > 65535u) return PA_ERR_UNSUPPORTED;
+    return PA_OK;
+}
+
+template <typename T, int P>
+bool launch_step(const pa_problem& pr, const DecodeLayout& L, const void* q, const void* k, const void* v, const float* log_g,
+                 char* st, void* o, float* z, hipStream_t s) {
+    const int BH = pr.B * pr.H;
+    {
+        LaunchScope ls("decode_step", s);
+#define PA_VEC(VV)                                                                                                          \
+    if (pr.v == VV)                                                                                                         \
+        hipLaunchKernelGGL((k_decode_step_vec<T, P, VV>), dim3(L.nblk, BH), dim3(256), 0, s, (const T*)q, (const T*)k,      \
+                           (const T*)v, log_g, (float*)(st + L.off_s), (float*)(st + L.off_gam),                            \
+                           (const uchar4*)(st + L.off_idx), (const float*)(st + L.off_mult), (float*)(st + L.off_part), L.D, \
+                           pr.d, pr.scale);                                                                                 \
+    else
+        PA_VEC(16) PA_VEC(32) PA_VEC(64) PA_VEC(128)
+#undef PA_VEC
+        hipLaunchKernelGGL((k_decode_step<T, P>), dim3(L.nblk, BH), dim3(256), 0, s, (const T*)q, (const T*)k, (const T*)v, log_g,
+                           (float*)(st + L.off_s), (float*)(st + L.off_gam), (const uchar4*)(st + L.off_idx),
+                           (const float*)(st + L.off_mult), (float*)(st + L.off_part), L.D, pr.d, pr.v, pr.scale);
+        if (!launch_ok()) return false;
+    }
+    LaunchScope ls("decode_finish", s);
+    hipLaunchKernelGGL((k_decode_finish<T>), dim3(BH), dim3(256), 0, s, (const float*)(st + L.off_part), L.nblk, (T*)o, z, pr.v,
+                       pr.normalize);
+    return launch_ok();
+}
+
+template <typename T>
+bool launch_step_p(const pa_problem& pr, const DecodeLayout& L, const void* q, const void* k, const void* v, const float* log_g,
+                   char* st, void* o, float* z, hipStream_t s) {
+    switch (pr.p) {
+        case 1: return launch_step<T, 1>(pr, L, q, k, v, log_g, st, o, z, s);
+        case 2: return launch_step<T, 2>(pr, L, q, k, v, log_g, st, o, z, s);
+        case 3: return launch_step<T, 3>(pr, L, q, k, v, log_g, st, o, z, s);
+        default: return launch_step<T, 4>(pr, L, q, k, v, log_g, st, o, z, s);
+    }
+}
+
+}  // namespace
+
+size_t decode_state_bytes(const pa_problem& pr) { return decode_supported(pr) == PA_OK ? make_decode_layout(pr).total : 0; }
+
+pa_status decode_init(const pa_problem& pr, void* state, hipStream_t s) {
+    pa_status st = decode_supported(pr);
+    if (st != PA_OK) return st;
+    const DecodeLayout L = make_decode_layout(pr);
+    {
+        // a kernel, not a memset: the call may be recorded into a graph
+        LaunchScope ls("decode_zero", s);
+        const size_t n4 = L.off_idx / sizeof(float4);     // S and gamma, both padded to 256 bytes
+        hipLaunchKernelGGL(k_decode_zero, dim3(1024), dim3(256), 0, s, (float4*)state, n4);
+        if (!launch_ok()) return PA_ERR_HIP;
+    }
+    char* base = (char*)state;
+    return build_monomial_table(s, pr.d, pr.p, L.D, base + L.off_idx, (float*)(base + L.off_mult)) ? PA_OK : PA_ERR_HIP;
+}
+
+pa_status decode_step(const pa_problem& pr, const void* q, const void* k, const void* v, const float* log_g, void* state, void* o,
+                      float* z, hipStream_t s) {
+    pa_status st = decode_supported(pr);
+    if (st != PA_OK) return st;
+    const DecodeLayout L = make_decode_layout(pr);
+    const bool ok = pr.dtype == PA_DTYPE_F32 ? launch_step_p<float>(pr, L, q, k, v, log_g, (char*)state, o, z, s)
+                                             : launch_step_p<bf16_t>(pr, L, q, k, v, log_g, (char*)state, o, z, s);
+    return ok ? PA_OK : PA_ERR_HIP;
+}
+
+}  // namespace pa

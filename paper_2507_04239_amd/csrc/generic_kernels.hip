@@ -752,6 +752,12 @@ pa_status dispatch(bool bwd, const Ctx& c, const void* Q, const void* K, const v
 
 }  // namespace
 
+bool build_monomial_table(hipStream_t s, int d, int p, long long D, void* idx, float* mult) {
+    LaunchScope ls("build_table", s);
+    hipLaunchKernelGGL(k_build_table, dim3((unsigned)((D + 255) / 256)), dim3(256), 0, s, d, p, D, (uchar4*)idx, mult);
+    return launch_ok();
+}
+
 pa_status generic_supported(const pa_problem& pr) {
     if (pr.p < 1 || pr.p > PMAX) return PA_ERR_UNSUPPORTED;
     if (pr.d > 128 || pr.v > 128) return PA_ERR_UNSUPPORTED;

@@ -208,6 +208,42 @@ long long power_attn_state_rows(const pa_problem* prob) {
     return impl == PA_IMPL_MFMA ? mfma_state_rows(pr_) : generic_state_rows(pr_);
 }
 
+// the fields a decode step reads, checked like the same fields of the other calls
+static pa_status validate_decode(const pa_problem* pr) {
+    if (pr == nullptr) return PA_ERR_INVALID_ARG;
+    if (pr->B <= 0 || pr->H <= 0 || pr->d <= 0 || pr->v <= 0 || pr->p <= 0) return PA_ERR_INVALID_ARG;
+    if (pr->normalize != 0 && (pr->p % 2) != 0) return PA_ERR_INVALID_ARG;
+    if (pr->dtype != PA_DTYPE_F32 && pr->dtype != PA_DTYPE_BF16) return PA_ERR_INVALID_ARG;
+    if (!(pr->scale == pr->scale) || pr->scale == 0.f) return PA_ERR_INVALID_ARG;
+    if (pr->gated != 0 && pr->gated != 1) return PA_ERR_INVALID_ARG;
+    return PA_OK;
+}
+
+size_t power_attn_decode_state_bytes(const pa_problem* prob) {
+    return validate_decode(prob) == PA_OK ? decode_state_bytes(*prob) : 0;
+}
+
+pa_status power_attn_decode_init(const pa_problem* prob, void* state, size_t state_bytes, void* hip_stream) {
+    pa_status st = validate_decode(prob);
+    if (st != PA_OK) return st;
+    const size_t need = decode_state_bytes(*prob);
+    if (need == 0) return PA_ERR_UNSUPPORTED;
+    if (state == nullptr || state_bytes < need) return PA_ERR_WORKSPACE;
+    return decode_init(*prob, state, (hipStream_t)hip_stream);
+}
+
+pa_status power_attn_decode_step(const pa_problem* prob, const void* q, const void* k, const void* v, const float* log_g,
+                                 void* state, size_t state_bytes, void* o, float* z, void* hip_stream) {
+    pa_status st = validate_decode(prob);
+    if (st != PA_OK) return st;
+    if (q == nullptr || k == nullptr || v == nullptr || o == nullptr) return PA_ERR_INVALID_ARG;
+    if ((prob->gated != 0) != (log_g != nullptr)) return PA_ERR_INVALID_ARG;
+    const size_t need = decode_state_bytes(*prob);
+    if (need == 0) return PA_ERR_UNSUPPORTED;
+    if (state == nullptr || state_bytes < need) return PA_ERR_WORKSPACE;
+    return decode_step(*prob, q, k, v, log_g, state, o, z, (hipStream_t)hip_stream);
+}
+
 int power_attn_resolved_chunk(const pa_problem* prob) {
     if (validate(prob) != PA_OK) return 0;
     return resolved(prob).chunk;

@@ -1,0 +1,114 @@
+"""GPU parity of the single-token decode step against the float64 oracle, through the C ABI: a
+sequence is fed token by token and every step's output is compared; the state left behind is
+compared with the oracle's (the device keeps the integer multiplicity of each monomial on the state,
+the oracle its square root on both sides: S_dev[r] = sqrt(m_r) S_oracle[r])."""
+import numpy as np
+import pytest
+
+from oracle import power_attn_oracle as orc
+from paper_2507_04239_amd import binding, inputs
+
+from gpu_util import TOL, rel_l2, to_dev, to_np
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    # dtype, p, B, H, T, d, normalize, scale, gated
+    ("f32", 2, 1, 2, 40, 16, True, 1.0, False),
+    ("f32", 2, 2, 1, 24, 64, True, 0.8, True),
+    ("bf16", 2, 1, 3, 48, 64, True, 1.0, False),       # the headline head shape
+    ("bf16", 2, 1, 2, 32, 64, True, 1.0, True),
+    ("f32", 4, 1, 1, 20, 16, True, 1.0, True),
+    ("bf16", 4, 1, 2, 16, 32, True, 1.0, False),       # config 4's head shape: 52360 state rows
+    ("f32", 3, 1, 2, 24, 24, False, 1.0, False),       # odd degree, un-normalised
+    ("bf16", 2, 1, 1, 12, 128, True, 1.0, False),      # config 5's head shape: two column passes per row
+    ("f32", 1, 1, 1, 16, 8, False, 1.0, True),         # degree 1: gated linear attention
+]
+
+
+@pytest.mark.parametrize("case", CASES, ids=lambda c: "-".join(str(x) for x in c))
+def test_decode_steps_match_the_oracle(case):
+    import torch
+    dtype, p, B, H, T, d, normalize, scale, gated = case
+    print("case", case, flush=True)
+    Q, K, V, _ = inputs.make_qkvg(B, H, T, d, seed=8000 + CASES.index(case), dtype=dtype, with_grad=False)
+    lg = inputs.make_log_gates(B, H, T, 8100 + CASES.index(case), 0.1) if gated else None
+    prob = binding.make_problem(B, H, 1, d, d, p, 1, normalize, scale, dtype, "auto", False, gated)
+    state = binding.power_attn_decode_init(prob)
+    tq, tk, tv = (to_dev(a, dtype) for a in (Q, K, V))
+    tl = None if lg is None else torch.from_numpy(np.ascontiguousarray(lg)).to("cuda:0")
+    outs, zs = [], []
+    for t in range(T):
+        o, z = binding.power_attn_decode_step(prob, tq[:, :, t].contiguous(), tk[:, :, t].contiguous(),
+                                              tv[:, :, t].contiguous(), state,
+                                              None if tl is None else tl[:, :, t].contiguous())
+        outs.append(o)
+        zs.append(z)
+    torch.cuda.synchronize()
+    got_o = np.stack([to_np(o) for o in outs], axis=2)       # [B, H, T, v]
+    got_z = np.stack([to_np(z) for z in zs], axis=2)         # [B, H, T]
+    ref_o, ref_z = np.zeros_like(got_o, dtype=np.float64), np.zeros_like(got_z, dtype=np.float64)
+    D = orc.dim_spow(d, p)
+    S_ref = np.zeros((B, H, D, d + 1))
+    for b in range(B):
+        for h in range(H):
+            S = orc.decode_state_init(d, d, p)
+            for t in range(T):
+                S, ref_o[b, h, t], ref_z[b, h, t] = orc.decode_step(S, Q[b, h, t], K[b, h, t], V[b, h, t], p, normalize, scale,
+                                                                    None if lg is None else lg[b, h, t])
+            S_ref[b, h] = S
+    # Numerator and denominator are sums over the expanded dimension whose terms cancel down to
+    # (q.k)^p; in float32 each is accurate relative to the size of those terms, not to its own value.
+    # So: the denominator and the numerator o z are compared as they are, and the quotient on the rows
+    # whose denominator is not far below the typical one (a first token with a tiny score is not).
+    ez = rel_l2(got_z, ref_z)
+    en = rel_l2(got_o * got_z[..., None], ref_o * ref_z[..., None]) if normalize else rel_l2(got_o, ref_o)
+    well = np.abs(ref_z) >= 0.05 * np.median(np.abs(ref_z)) if normalize else np.ones_like(ref_z, dtype=bool)
+    assert well.mean() > 0.6
+    eo = rel_l2(got_o[well], ref_o[well])
+    # the state itself: float32 words at the start of the buffer, S [BH][D][v] then gamma [BH][D]
+    words = state.view(torch.float32)
+    S_dev = to_np(words[: B * H * D * d]).reshape(B, H, D, d)
+    off_gam = ((B * H * D * d * 4 + 255) // 256 * 256) // 4
+    gam_dev = to_np(words[off_gam: off_gam + B * H * D]).reshape(B, H, D)
+    sq = np.sqrt(np.array([orc.multiplicity(r) for r in orc.ndmi(d, p)], dtype=np.float64))
+    es = rel_l2(S_dev, S_ref[..., :d] * sq[None, None, :, None])
+    eg = rel_l2(gam_dev, S_ref[..., d] * sq[None, None, :])
+    print(f"decode {case}: o={eo:.2e} ({well.sum()} of {well.size} rows) numerator={en:.2e} z={ez:.2e} state={es:.2e} gamma={eg:.2e}",
+          flush=True)
+    assert eo <= TOL[dtype] and ez <= TOL[dtype] and en <= TOL[dtype]
+    assert es <= TOL[dtype] and eg <= TOL[dtype]
+
+
+def test_decode_agrees_with_the_whole_sequence_call():
+    """Token by token, the decode step returns the rows the forward call returns for the sequence."""
+    import torch
+    from paper_2507_04239_amd import power_attn_fwd
+    B, H, T, d = 1, 2, 256, 64
+    Q, K, V, _ = inputs.make_qkvg(B, H, T, d, seed=8200, dtype="bf16", with_grad=False)
+    tq, tk, tv = (to_dev(a, "bf16") for a in (Q, K, V))
+    O, Z = power_attn_fwd(tq, tk, tv, 2, 128)
+    prob = binding.make_problem(B, H, 1, d, d, 2, 1, True, 1.0, "bf16")
+    state = binding.power_attn_decode_init(prob)
+    for t in range(T):
+        o, z = binding.power_attn_decode_step(prob, tq[:, :, t].contiguous(), tk[:, :, t].contiguous(), tv[:, :, t].contiguous(), state)
+        if t in (0, 1, 127, 128, 200, 255):
+            torch.cuda.synchronize()
+            assert rel_l2(to_np(o), to_np(O[:, :, t])) <= TOL["bf16"], t
+            assert rel_l2(to_np(z), to_np(Z[:, :, t])) <= TOL["bf16"], t
+
+
+def test_decode_refusals():
+    import torch
+    prob = binding.make_problem(1, 1, 1, 16, 16, 2, 1, True, 1.0, "f32")
+    need = binding.power_attn_decode_state_bytes(prob)
+    assert need > 0
+    small = torch.empty(need - 256, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(binding.PowerAttnError):
+        binding.power_attn_decode_init(prob, small)
+    odd = binding.make_problem(1, 1, 1, 16, 16, 3, 1, True, 1.0, "f32")          # odd degree cannot be normalised
+    assert binding.power_attn_decode_state_bytes(odd) == 0
+    state = binding.power_attn_decode_init(prob)
+    x = torch.zeros(1, 1, 16, device="cuda:0")
+    with pytest.raises(binding.PowerAttnError):                                   # gates given to an un-gated problem
+        binding.power_attn_decode_step(prob, x, x, x, state, torch.zeros(1, 1, device="cuda:0"))
