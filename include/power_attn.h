@@ -129,7 +129,8 @@ pa_status power_attn_bwd_gated(const pa_problem* prob,
  *     S <- g S + phi(k) [v, 1]^T,    y = S^T phi(scale q),    o = y[:v] / y[v]  (normalize)  or  y[:v]
  * i.e. after n steps on k_1..k_n, v_1..v_n the output equals row n of power_attn_fwd on the same
  * sequence (with the same gates).  Of `prob` the fields B, H, d, v, p, normalize, scale, dtype and
- * gated are used (1 <= p <= 4, d, v <= 128); T, chunk, impl and keep_state are ignored.
+ * gated are used (1 <= p <= 4, d, v <= 128); chunk, impl and keep_state are ignored, and T only by
+ * power_attn_decode_absorb.
  *
  * state: DEVICE, caller-owned, power_attn_decode_state_bytes(prob) bytes, float32 inside; it
  * belongs to one (prob, sequence batch) and must be initialised by power_attn_decode_init before
@@ -141,6 +142,11 @@ pa_status power_attn_bwd_gated(const pa_problem* prob,
  * launched when validation fails. */
 size_t power_attn_decode_state_bytes(const pa_problem* prob);     /* 0 if the problem is invalid or unsupported */
 pa_status power_attn_decode_init(const pa_problem* prob, void* state, size_t state_bytes, void* hip_stream);
+/* The hand-over from a prompt: updates `state` as prob->T decode steps on K [B, H, T, d], V [B, H, T, v]
+ * (log_g [B, H, T] when prob->gated, else NULL) would, without producing their outputs - those are
+ * what power_attn_fwd returns for the prompt.  May be called on a state that already holds tokens. */
+pa_status power_attn_decode_absorb(const pa_problem* prob, const void* K, const void* V, const float* log_g,
+                                   void* state, size_t state_bytes, void* hip_stream);
 pa_status power_attn_decode_step(const pa_problem* prob, const void* q, const void* k, const void* v,
                                  const float* log_g, void* state, size_t state_bytes,
                                  void* o, float* z, void* hip_stream);

@@ -22,6 +22,7 @@ EXPORTED_SYMBOLS = (
     "power_attn_supported",
     "power_attn_decode_state_bytes",
     "power_attn_decode_init",
+    "power_attn_decode_absorb",
     "power_attn_decode_step",
     "power_attn_fwd",
     "power_attn_bwd",
@@ -86,6 +87,8 @@ def load_library():
     lib.power_attn_decode_state_bytes.argtypes = [P]
     lib.power_attn_decode_init.restype = ctypes.c_int
     lib.power_attn_decode_init.argtypes = [P, vp, ctypes.c_size_t, vp]
+    lib.power_attn_decode_absorb.restype = ctypes.c_int
+    lib.power_attn_decode_absorb.argtypes = [P, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.power_attn_decode_step.restype = ctypes.c_int
     lib.power_attn_decode_step.argtypes = [P, vp, vp, vp, vp, vp, ctypes.c_size_t, vp, vp, vp]
     lib.power_attn_fwd.restype = ctypes.c_int
@@ -280,6 +283,17 @@ def power_attn_decode_init(prob: PaProblem, state=None):
         state = torch.empty(need, dtype=torch.uint8, device=torch.device("cuda", torch.cuda.current_device()))
     _check(lib, lib.power_attn_decode_init(ctypes.byref(prob), _dev_ptr(state, name="state"), state.numel(), _stream()),
            "power_attn_decode_init")
+    return state
+
+
+def power_attn_decode_absorb(prob: PaProblem, K, V, state, log_g=None):
+    """Feeds the prompt K [B, H, T, d], V [B, H, T, v] (prob.T = T) into the state, as T decode steps
+    would, without outputs."""
+    lib = load_library()
+    lg = None if log_g is None else _dev_ptr(log_g, name="log_g")
+    _check(lib, lib.power_attn_decode_absorb(ctypes.byref(prob), _dev_ptr(K, name="K"), _dev_ptr(V, K, "V"), lg,
+                                             _dev_ptr(state, name="state"), state.numel(), _stream()),
+           "power_attn_decode_absorb")
     return state
 
 

@@ -97,6 +97,7 @@ bool build_monomial_table(hipStream_t s, int d, int p, long long D, void* idx, f
 // single-token decode step (state resident between calls)
 size_t decode_state_bytes(const pa_problem& pr);
 pa_status decode_init(const pa_problem& pr, void* state, hipStream_t s);
+pa_status decode_absorb(const pa_problem& pr, const void* K, const void* V, const float* log_g, void* state, hipStream_t s);
 pa_status decode_step(const pa_problem& pr, const void* q, const void* k, const void* v, const float* log_g, void* state, void* o,
                       float* z, hipStream_t s);
 pa_status generic_supported(const pa_problem& pr);

@@ -191,6 +191,84 @@ __global__ __launch_bounds__(256) void k_decode_step_vec(const T* __restrict__ q
     }
 }
 
+// ---- absorbing a whole prompt ------------------------------------------------------------------------
+// S <- (prod of the prompt's gates) S + sum_t (prod of the gates after t) m_r psi(k_t)_r [v_t, 1], i.e. the
+// state after stepping through K, V [B*H][Tlen][.] token by token, without producing outputs (those come
+// from power_attn_fwd).  One thread owns a state row and every fourth column, holds them in registers
+// and walks the tokens, which are staged through LDS 32 at a time; the decay is applied token by
+// token (acc <- g_t acc + ...), which needs no running sums of the log-gates.
+constexpr int ART = 32;   // tokens per LDS batch
+// NQ: column quads per thread (thread xg of a row's four owns the quads xg, xg + 4, ...: 16-byte LDS
+// reads); the normaliser column rides with thread 0 of the four.
+template <typename T, int P, int NQ, bool GATED>
+__global__ __launch_bounds__(256) void k_decode_absorb(const T* __restrict__ K, const T* __restrict__ V,
+                                                       const float* __restrict__ log_g, float* __restrict__ S,
+                                                       float* __restrict__ gam, const uchar4* __restrict__ idx,
+                                                       const float* __restrict__ mult, long long D, int Tlen, int d, int v) {
+    __shared__ float ks[ART][DMAX];
+    __shared__ __attribute__((aligned(16))) float vs[ART][DMAX];
+    __shared__ float gs[ART];
+    const int tid = threadIdx.x, xg = tid & 3, bh = blockIdx.y;
+    const long long row = (long long)blockIdx.x * 64 + (tid >> 2);
+    const bool live = row < D;
+    uchar4 ix = make_uchar4(0, 0, 0, 0);
+    float m = 0.f;
+    if (live) {
+        ix = idx[row];
+        m = mult[row];
+    }
+    float* srow = S + ((size_t)bh * D + (live ? row : 0)) * v;
+    float* grow = gam + (size_t)bh * D + (live ? row : 0);
+    const int nquad = (v + 3) / 4;
+    float4 acc[NQ];
+    float accz = live && xg == 0 ? *grow : 0.f;
+#pragma unroll
+    for (int kk = 0; kk < NQ; ++kk) {
+        const int x = 4 * (xg + 4 * kk);
+        acc[kk] = make_float4(live && x < v ? srow[x] : 0.f, live && x + 1 < v ? srow[x + 1] : 0.f,
+                              live && x + 2 < v ? srow[x + 2] : 0.f, live && x + 3 < v ? srow[x + 3] : 0.f);
+    }
+    const T* Kb = K + (size_t)bh * Tlen * d;
+    const T* Vb = V + (size_t)bh * Tlen * v;
+    for (int t0 = 0; t0 < Tlen; t0 += ART) {
+        const int nt = min(ART, Tlen - t0);
+        __syncthreads();
+        for (int e = tid; e < nt * d; e += 256) ks[e / d][e % d] = io<T>::ld(Kb + (size_t)t0 * d + e);
+        for (int e = tid; e < nt * 4 * nquad; e += 256) {        // columns past v read as zero
+            const int j = e / (4 * nquad), x = e % (4 * nquad);
+            vs[j][x] = x < v ? io<T>::ld(Vb + (size_t)(t0 + j) * v + x) : 0.f;
+        }
+        if (GATED && tid < nt) gs[tid] = __expf(log_g[(size_t)bh * Tlen + t0 + tid]);
+        __syncthreads();
+#pragma unroll 4
+        for (int j = 0; j < nt; ++j) {
+            const float coef = m * monomial<P>(ks[j], ix);
+            const float g = GATED ? gs[j] : 1.f;
+            accz = GATED ? g * accz + coef : accz + coef;
+#pragma unroll
+            for (int kk = 0; kk < NQ; ++kk) {
+                if (xg + 4 * kk < nquad) {
+                    const float4 y = *(const float4*)&vs[j][4 * (xg + 4 * kk)];
+                    if (GATED) {
+                        acc[kk].x *= g; acc[kk].y *= g; acc[kk].z *= g; acc[kk].w *= g;
+                    }
+                    acc[kk].x += coef * y.x; acc[kk].y += coef * y.y; acc[kk].z += coef * y.z; acc[kk].w += coef * y.w;
+                }
+            }
+        }
+    }
+    if (!live) return;
+#pragma unroll
+    for (int kk = 0; kk < NQ; ++kk) {
+        const int x = 4 * (xg + 4 * kk);
+        if (x < v) srow[x] = acc[kk].x;
+        if (x + 1 < v) srow[x + 1] = acc[kk].y;
+        if (x + 2 < v) srow[x + 2] = acc[kk].z;
+        if (x + 3 < v) srow[x + 3] = acc[kk].w;
+    }
+    if (xg == 0) *grow = accz;
+}
+
 // grid B*H: sums the blocks' partial read-outs, divides, stores
 template <typename T>
 __global__ __launch_bounds__(256) void k_decode_finish(const float* __restrict__ part, int nblk, T* __restrict__ o,
@@ -253,7 +331,52 @@ bool launch_step_p(const pa_problem& pr, const DecodeLayout& L, const void* q, c
     }
 }
 
+template <typename T, int P>
+bool launch_absorb_kx(const pa_problem& pr, const DecodeLayout& L, const void* K, const void* V, const float* log_g, char* st,
+                      hipStream_t s) {
+    const int nq = ((pr.v + 3) / 4 + 3) / 4;      // column quads per thread
+    const dim3 grid((unsigned)((L.D + 63) / 64), pr.B * pr.H);
+    LaunchScope ls("decode_absorb", s);
+#define PA_GO(NQ, G)                                                                                                    \
+    hipLaunchKernelGGL((k_decode_absorb<T, P, NQ, G>), grid, dim3(256), 0, s, (const T*)K, (const T*)V, log_g,           \
+                       (float*)(st + L.off_s), (float*)(st + L.off_gam), (const uchar4*)(st + L.off_idx),                \
+                       (const float*)(st + L.off_mult), L.D, pr.T, pr.d, pr.v)
+    if (log_g != nullptr) {
+        if (nq <= 1) PA_GO(1, true);
+        else if (nq <= 2) PA_GO(2, true);
+        else if (nq <= 4) PA_GO(4, true);
+        else PA_GO(8, true);
+    } else {
+        if (nq <= 1) PA_GO(1, false);
+        else if (nq <= 2) PA_GO(2, false);
+        else if (nq <= 4) PA_GO(4, false);
+        else PA_GO(8, false);
+    }
+#undef PA_GO
+    return launch_ok();
+}
+
+template <typename T>
+bool launch_absorb_p(const pa_problem& pr, const DecodeLayout& L, const void* K, const void* V, const float* log_g, char* st,
+                     hipStream_t s) {
+    switch (pr.p) {
+        case 1: return launch_absorb_kx<T, 1>(pr, L, K, V, log_g, st, s);
+        case 2: return launch_absorb_kx<T, 2>(pr, L, K, V, log_g, st, s);
+        case 3: return launch_absorb_kx<T, 3>(pr, L, K, V, log_g, st, s);
+        default: return launch_absorb_kx<T, 4>(pr, L, K, V, log_g, st, s);
+    }
+}
+
 }  // namespace
+
+pa_status decode_absorb(const pa_problem& pr, const void* K, const void* V, const float* log_g, void* state, hipStream_t s) {
+    pa_status st = decode_supported(pr);
+    if (st != PA_OK) return st;
+    const DecodeLayout L = make_decode_layout(pr);
+    const bool ok = pr.dtype == PA_DTYPE_F32 ? launch_absorb_p<float>(pr, L, K, V, log_g, (char*)state, s)
+                                             : launch_absorb_p<bf16_t>(pr, L, K, V, log_g, (char*)state, s);
+    return ok ? PA_OK : PA_ERR_HIP;
+}
 
 size_t decode_state_bytes(const pa_problem& pr) { return decode_supported(pr) == PA_OK ? make_decode_layout(pr).total : 0; }
 

@@ -232,6 +232,18 @@ pa_status power_attn_decode_init(const pa_problem* prob, void* state, size_t sta
     return decode_init(*prob, state, (hipStream_t)hip_stream);
 }
 
+pa_status power_attn_decode_absorb(const pa_problem* prob, const void* K, const void* V, const float* log_g, void* state,
+                                   size_t state_bytes, void* hip_stream) {
+    pa_status st = validate_decode(prob);
+    if (st != PA_OK) return st;
+    if (prob->T <= 0 || K == nullptr || V == nullptr) return PA_ERR_INVALID_ARG;
+    if ((prob->gated != 0) != (log_g != nullptr)) return PA_ERR_INVALID_ARG;
+    const size_t need = decode_state_bytes(*prob);
+    if (need == 0) return PA_ERR_UNSUPPORTED;
+    if (state == nullptr || state_bytes < need) return PA_ERR_WORKSPACE;
+    return decode_absorb(*prob, K, V, log_g, state, (hipStream_t)hip_stream);
+}
+
 pa_status power_attn_decode_step(const pa_problem* prob, const void* q, const void* k, const void* v, const float* log_g,
                                  void* state, size_t state_bytes, void* o, float* z, void* hip_stream) {
     pa_status st = validate_decode(prob);

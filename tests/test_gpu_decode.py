@@ -112,3 +112,86 @@ def test_decode_refusals():
     x = torch.zeros(1, 1, 16, device="cuda:0")
     with pytest.raises(binding.PowerAttnError):                                   # gates given to an un-gated problem
         binding.power_attn_decode_step(prob, x, x, x, state, torch.zeros(1, 1, device="cuda:0"))
+
+
+ABSORB_CASES = [
+    # dtype, p, B, H, T, d, normalize, gated
+    ("bf16", 2, 1, 2, 200, 64, True, False),
+    ("bf16", 2, 1, 2, 77, 64, True, True),
+    ("f32", 4, 1, 1, 50, 16, True, True),
+    ("bf16", 2, 1, 1, 40, 128, True, False),
+    ("f32", 3, 2, 1, 33, 24, False, False),
+]
+
+
+@pytest.mark.parametrize("case", ABSORB_CASES, ids=lambda c: "-".join(str(x) for x in c))
+def test_absorbing_a_prompt_equals_stepping_through_it(case):
+    """The hand-over from a prompt: the state after power_attn_decode_absorb is the oracle's state after
+    stepping through the same tokens, also when the prompt arrives in two pieces, and the next decode
+    step returns the oracle's output."""
+    import torch
+    dtype, p, B, H, T, d, normalize, gated = case
+    print("case", case, flush=True)
+    Q, K, V, _ = inputs.make_qkvg(B, H, T + 1, d, seed=8300 + ABSORB_CASES.index(case), dtype=dtype, with_grad=False)
+    lg = inputs.make_log_gates(B, H, T + 1, 8400 + ABSORB_CASES.index(case), 0.05) if gated else None
+    tq, tk, tv = (to_dev(a, dtype) for a in (Q, K, V))
+    tl = None if lg is None else torch.from_numpy(np.ascontiguousarray(lg)).to("cuda:0")
+
+    def absorb(lo, hi, state):
+        prob = binding.make_problem(B, H, hi - lo, d, d, p, 1, normalize, 1.0, dtype, "auto", False, gated)
+        return binding.power_attn_decode_absorb(prob, tk[:, :, lo:hi].contiguous(), tv[:, :, lo:hi].contiguous(), state,
+                                                None if tl is None else tl[:, :, lo:hi].contiguous())
+
+    prob1 = binding.make_problem(B, H, 1, d, d, p, 1, normalize, 1.0, dtype, "auto", False, gated)
+    whole = absorb(0, T, binding.power_attn_decode_init(prob1))
+    pieces = absorb(T // 3, T, absorb(0, T // 3, binding.power_attn_decode_init(prob1)))
+    D = orc.dim_spow(d, p)
+    n_s = B * H * D * d
+    off_gam = ((n_s * 4 + 255) // 256 * 256) // 4
+    sq = np.sqrt(np.array([orc.multiplicity(r) for r in orc.ndmi(d, p)], dtype=np.float64))
+    S_ref = np.zeros((B, H, D, d + 1))
+    o_ref, z_ref = np.zeros((B, H, d)), np.zeros((B, H))
+    for b in range(B):
+        for h in range(H):
+            S = orc.decode_state_init(d, d, p)
+            for t in range(T):
+                S, _, _ = orc.decode_step(S, Q[b, h, t], K[b, h, t], V[b, h, t], p, normalize, 1.0, None if lg is None else lg[b, h, t])
+            S_ref[b, h] = S
+            _, o_ref[b, h], z_ref[b, h] = orc.decode_step(S, Q[b, h, T], K[b, h, T], V[b, h, T], p, normalize, 1.0,
+                                                          None if lg is None else lg[b, h, T])
+    for name, state in (("whole", whole), ("two pieces", pieces)):
+        words = state.view(torch.float32)
+        S_dev = to_np(words[:n_s]).reshape(B, H, D, d)
+        gam_dev = to_np(words[off_gam: off_gam + B * H * D]).reshape(B, H, D)
+        es = rel_l2(S_dev, S_ref[..., :d] * sq[None, None, :, None])
+        eg = rel_l2(gam_dev, S_ref[..., d] * sq[None, None, :])
+        print(f"absorb {case} {name}: state={es:.2e} gamma={eg:.2e}", flush=True)
+        assert es <= 1e-5 and eg <= 1e-5          # float32 sums of exactly representable inputs
+    o, z = binding.power_attn_decode_step(prob1, tq[:, :, T].contiguous(), tk[:, :, T].contiguous(), tv[:, :, T].contiguous(), whole,
+                                          None if tl is None else tl[:, :, T].contiguous())
+    torch.cuda.synchronize()
+    ez = rel_l2(to_np(z), z_ref)
+    en = rel_l2(to_np(o) * to_np(z)[..., None], o_ref * z_ref[..., None]) if normalize else rel_l2(to_np(o), o_ref)
+    print(f"absorb {case}: next step numerator={en:.2e} z={ez:.2e}", flush=True)
+    assert ez <= TOL[dtype] and en <= TOL[dtype]
+
+
+def test_prefill_then_decode_continues_the_sequence():
+    """power_attn_fwd on a prompt, the prompt handed to a decode state, then decode steps: every
+    decoded row equals the row power_attn_fwd returns for the longer sequence."""
+    import torch
+    from paper_2507_04239_amd import power_attn_fwd
+    B, H, T, extra, d = 1, 2, 512, 128, 64
+    Q, K, V, _ = inputs.make_qkvg(B, H, T + extra, d, seed=8500, dtype="bf16", with_grad=False)
+    tq, tk, tv = (to_dev(a, "bf16") for a in (Q, K, V))
+    O_all, Z_all = power_attn_fwd(tq, tk, tv, 2, 128)
+    prob_prompt = binding.make_problem(B, H, T, d, d, 2, 1, True, 1.0, "bf16")
+    prob1 = binding.make_problem(B, H, 1, d, d, 2, 1, True, 1.0, "bf16")
+    state = binding.power_attn_decode_init(prob1)
+    binding.power_attn_decode_absorb(prob_prompt, tk[:, :, :T].contiguous(), tv[:, :, :T].contiguous(), state)
+    for t in range(T, T + extra):
+        o, z = binding.power_attn_decode_step(prob1, tq[:, :, t].contiguous(), tk[:, :, t].contiguous(), tv[:, :, t].contiguous(), state)
+        if t in (T, T + 1, T + 63, T + extra - 1):
+            torch.cuda.synchronize()
+            assert rel_l2(to_np(o), to_np(O_all[:, :, t])) <= TOL["bf16"], t
+            assert rel_l2(to_np(z), to_np(Z_all[:, :, t])) <= TOL["bf16"], t
