@@ -20,9 +20,14 @@
  * (HIP global memory on the current device); `const pa_problem*` and the profiling
  * arguments are HOST pointers.  Tensors are dense row-major [B, H, T, d] (Q, K, dQ, dK),
  * [B, H, T, v] (V, O, dO, dV) in `dtype`, and [B, H, T] float32 (Z).  The caller owns
- * every buffer; the library allocates no device memory, keeps no per-call state and only
+ * every buffer; the library allocates no device memory, keeps no per-call state and
  * enqueues work on `hip_stream` (a hipStream_t passed as void*, NULL = the default
- * stream); it does not synchronise.  Outputs are overwritten, never accumulated into.
+ * stream); it does not synchronise the host.  One exception to "only on hip_stream": the
+ * bf16 MFMA backward pass runs independent kernels side by side on one more stream that the
+ * library creates once per process (non-blocking, default priority), forked from and joined
+ * back into hip_stream with events, so that for the caller the call is ordered on hip_stream
+ * like any other.  Calls may not be issued concurrently from several host threads.  Outputs
+ * are overwritten, never accumulated into.
  * No function throws; all errors are return codes and nothing is launched when
  * validation fails.
  */
