@@ -105,11 +105,18 @@ __global__ __launch_bounds__(GT) void k_gate_finish(const float* __restrict__ db
 
 }  // namespace
 
+// entries per head of the per-chunk arrays: the boundary sums of the backward pass may be kept per
+// 128 tokens when the chunk is longer (the attention form)
+static size_t chunk_slots(const pa_problem& pr) {
+    const size_t a = (size_t)(pr.T / pr.chunk), b = (size_t)((pr.T + 127) / 128);
+    return a > b ? a : b;
+}
+
 size_t gate_workspace_bytes(const pa_problem& pr, bool backward) {
     if (!pr.gated) return 0;
     const size_t BH = (size_t)pr.B * pr.H;
     const size_t tok = align_up(BH * pr.T * sizeof(float), 256);
-    return (backward ? 5 : 3) * tok + (backward ? 2 : 1) * align_up(BH * (pr.T / pr.chunk) * sizeof(float), 256);
+    return (backward ? 5 : 3) * tok + (backward ? 2 : 1) * align_up(BH * chunk_slots(pr) * sizeof(float), 256);
 }
 
 GateBuf gate_buffers(const pa_problem& pr, bool backward, char* base) {
@@ -122,7 +129,7 @@ GateBuf gate_buffers(const pa_problem& pr, bool backward, char* base) {
     g.kfac = (float*)(base + 2 * tok);
     g.lam = (float*)(base + 3 * tok);
     if (backward) {
-        g.db = (float*)(base + 3 * tok + align_up(BH * (pr.T / pr.chunk) * sizeof(float), 256));
+        g.db = (float*)(base + 3 * tok + align_up(BH * chunk_slots(pr) * sizeof(float), 256));
         g.db2 = g.db + tok / sizeof(float);
         g.xb = g.db2 + tok / sizeof(float);
     }
@@ -138,25 +145,30 @@ pa_status gate_prepare(const Ctx& c, const float* log_g) {
 }
 
 pa_status gate_gradient(const Ctx& c, const void* Q, const void* K, const void* dQ, const void* dK, float* dlog_g,
-                        bool have_dots) {
+                        bool have_dots, int fin_chunk, bool exact_rows) {
     const pa_problem& pr = c.prob;
+    // Under the sum normalisation q_i . dq_i is zero in exact arithmetic.  A family whose dot products carry
+    // the rounding noise of the stored gradients is better off without the term; one that sums the row
+    // in float32 from unrounded weights (exact_rows) keeps it: what is left in it is the rounding of O_i,
+    // which the k_j . dk_j terms of the later keys contain with the opposite sign.
+    const int use_q = (!pr.normalize || exact_rows) ? 1 : 0;
     const long long rows = (long long)pr.B * pr.H * pr.T;
     if (!have_dots) {
         LaunchScope ls("gate_db", c.stream);
         if (pr.dtype == PA_DTYPE_F32)
             hipLaunchKernelGGL((k_gate_db<float>), dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, c.stream, (const float*)Q,
-                               (const float*)dQ, (const float*)K, (const float*)dK, c.gate.db, rows, pr.d, 1.f / pr.p, pr.normalize ? 0 : 1);
+                               (const float*)dQ, (const float*)K, (const float*)dK, c.gate.db, rows, pr.d, 1.f / pr.p, use_q);
         else
             hipLaunchKernelGGL((k_gate_db<bf16_t>), dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, c.stream, (const bf16_t*)Q,
                                (const bf16_t*)dQ, (const bf16_t*)K, (const bf16_t*)dK, c.gate.db, rows, pr.d, 1.f / pr.p,
-                               pr.normalize ? 0 : 1);
+                               use_q);
     }
     if (!have_dots && !launch_ok()) return PA_ERR_HIP;
     const float* d2 = have_dots ? (const float*)c.gate.db2 : (const float*)nullptr;
     {
         LaunchScope ls("gate_finish", c.stream);
-        hipLaunchKernelGGL(k_gate_finish, dim3(pr.T / pr.chunk, pr.B * pr.H), dim3(GT), 0, c.stream, c.gate.db, d2, 1.f / pr.p,
-                           pr.normalize ? 0 : 1, (const float*)c.gate.xb, dlog_g, pr.T, pr.chunk);
+        hipLaunchKernelGGL(k_gate_finish, dim3(pr.T / fin_chunk, pr.B * pr.H), dim3(GT), 0, c.stream, c.gate.db, d2, 1.f / pr.p,
+                           use_q, (const float*)c.gate.xb, dlog_g, pr.T, fin_chunk);
     }
     return launch_ok() ? PA_OK : PA_ERR_HIP;
 }

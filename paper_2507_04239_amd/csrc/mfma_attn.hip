@@ -100,6 +100,30 @@ __device__ __forceinline__ bf16x8 col_frag(const AttnTile<HD>& t, int s, int cb,
     return f.v;
 }
 
+// Gating (Sec. 2 "Gating"): the pair (i, j) carries exp(b_i - b_j), b the running sum of the log-gates.
+// For a tile whose every pair is below the diagonal the factor is split at a reference m inside the
+// gap between the two sides, exp(b_i - m) exp(m - b_j), both <= 1: one of them is staged with the tile
+// (GateTile::f, per streamed row), the other is formed once per tile for the rows a lane owns.  Tiles
+// on the diagonal use the difference itself (GateTile::b), where a split could overflow.
+struct GateTile {
+    float b[AT], f[AT];
+};
+// streamed rows row0 .. row0 + 63 of one head; m_row: the row whose b is the reference;
+// sign = +1: f = exp(m - b) (streamed keys), -1: f = exp(b - m) (streamed queries)
+__device__ __forceinline__ void gate_tile_load(float& b, float& f, const float* __restrict__ bl_head, int row0, int m_row,
+                                               float sign, int tid, int T) {
+    if (tid < AT) {
+        b = bl_head[min(row0 + tid, T - 1)];
+        f = __expf(sign * (bl_head[min(m_row, T - 1)] - b));
+    }
+}
+__device__ __forceinline__ void gate_tile_store(GateTile& t, float b, float f, int tid) {
+    if (tid < AT) {
+        t.b[tid] = b;
+        t.f[tid] = f;
+    }
+}
+
 // Workgroups are numbered so that the ones with the longest walk start first.
 __device__ __forceinline__ int heavy_first(int nblocks, bool longest_is_last) {
     return longest_is_last ? nblocks - 1 - (int)blockIdx.x : (int)blockIdx.x;
@@ -110,14 +134,16 @@ __device__ __forceinline__ int heavy_first(int nblocks, bool longest_is_last) {
 // WPE: waves per SIMD the register budget is set for.  With 2 (at most 256 registers) the MFMAs
 // write plain vector registers; with 1 the compiler moves every score through the accumulation
 // registers and back, which costs more vector-ALU instructions than the arithmetic itself.
-template <int P, int HD, int OWN, int WPE>
+template <int P, int HD, int OWN, int WPE, bool GATED>
 __global__ __launch_bounds__(256, WPE) void k_attn_fwd(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
                                                        const bf16_t* __restrict__ V, bf16_t* __restrict__ O,
-                                                       float* __restrict__ Z, int T, float scale, int normalize) {
+                                                       float* __restrict__ Z, int T, float scale, int normalize,
+                                                       const float* __restrict__ bl) {
     constexpr int NI = OWN / 16, NK = HD / 32, NV = HD / 16, WG = 4 * OWN;
     extern __shared__ __attribute__((aligned(16))) unsigned char attn_smem[];
     AttnTile<HD>* kt = reinterpret_cast<AttnTile<HD>*>(attn_smem);      // [2]
     AttnTile<HD>* vt = kt + 2;                                          // [2]
+    GateTile* gtile = reinterpret_cast<GateTile*>(vt + 2);              // [2]
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r16 = lane & 15, g = lane >> 4;
     const int nblk = (T + WG - 1) / WG;
     const int i0 = heavy_first(nblk, true) * WG;
@@ -143,10 +169,20 @@ __global__ __launch_bounds__(256, WPE) void k_attn_fwd(const bf16_t* __restrict_
 #pragma unroll
         for (int vb = 0; vb < NV; ++vb) acc[vb][ib] = (f32x4){0.f, 0.f, 0.f, 0.f};
     }
+    const float* bl_head = GATED ? bl + head : nullptr;
+    float bq[NI];
+#pragma unroll
+    for (int ib = 0; ib < NI; ++ib) bq[ib] = GATED ? bl_head[min(q0 + 16 * ib + r16, T - 1)] : 0.f;
 
     // one 64-key tile; DIAG: some pair of the tile lies above the diagonal and has to be masked
     auto tile = [&](auto diag_c, int buf, int key0) {
         constexpr bool DIAG = decltype(diag_c)::value;
+        float fq[NI];
+        if (GATED && !DIAG) {
+            const float m = gtile[buf].b[AT - 1];          // the tile's last key
+#pragma unroll
+            for (int ib = 0; ib < NI; ++ib) fq[ib] = __expf(bq[ib] - m);
+        }
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
             Frag pf[NI];
@@ -156,6 +192,9 @@ __global__ __launch_bounds__(256, WPE) void k_attn_fwd(const bf16_t* __restrict_
                 bf16x8 kf[NK];
 #pragma unroll
                 for (int ks = 0; ks < NK; ++ks) kf[ks] = row_frag<HD>(kt[buf], kb, ks, r16, g);
+                float4 gk = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (GATED) gk = *(const float4*)(DIAG ? &gtile[buf].b[16 * kb + 4 * g] : &gtile[buf].f[16 * kb + 4 * g]);
+                const float gkr[4] = {gk.x, gk.y, gk.z, gk.w};
 #pragma unroll
                 for (int ib = 0; ib < NI; ++ib) {
                     f32x4 c = {0.f, 0.f, 0.f, 0.f};    // S^T: key 16 kb + 4g + r, query 16 ib + r16
@@ -164,6 +203,7 @@ __global__ __launch_bounds__(256, WPE) void k_attn_fwd(const bf16_t* __restrict_
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         float a = ipow<P>(scale * c[r]);
+                        if (GATED) a *= DIAG ? __expf(bq[ib] - gkr[r]) : fq[ib] * gkr[r];
                         if (DIAG && key0 + 16 * kb + 4 * g + r > q0 + 16 * ib + r16) a = 0.f;
                         pf[ib].v[4 * jb + r] = (__bf16)a;
                     }
@@ -184,16 +224,20 @@ __global__ __launch_bounds__(256, WPE) void k_attn_fwd(const bf16_t* __restrict_
 
     const int ntile = (min(i0 + WG, T) + AT - 1) / AT;   // key tiles 0 .. ntile - 1 reach the block's last query
     uint4 kr[HD / 32], vr[HD / 32];
+    float gb = 0.f, gf = 0.f;
     PA_TILE_LOAD(kr, Kh, 0, false)
     PA_TILE_LOAD(vr, Vh, 0, false)
+    if (GATED) gate_tile_load(gb, gf, bl_head, 0, AT - 1, 1.f, tid, T);
     PA_TILE_STORE(kt[0], kr)
     PA_TILE_STORE(vt[0], vr)
+    if (GATED) gate_tile_store(gtile[0], gb, gf, tid);
     __syncthreads();
     for (int t = 0; t < ntile; ++t) {
         const int buf = t & 1, key0 = t * AT;
         if (t + 1 < ntile) {
             PA_TILE_LOAD(kr, Kh, key0 + AT, false)
             PA_TILE_LOAD(vr, Vh, key0 + AT, false)
+            if (GATED) gate_tile_load(gb, gf, bl_head, key0 + AT, key0 + 2 * AT - 1, 1.f, tid, T);
         }
         if (active && key0 <= q0 + OWN - 1) {
             if (key0 + AT - 1 > q0) tile(std::true_type{}, buf, key0);
@@ -202,6 +246,7 @@ __global__ __launch_bounds__(256, WPE) void k_attn_fwd(const bf16_t* __restrict_
         if (t + 1 < ntile) {
             PA_TILE_STORE(kt[buf ^ 1], kr)
             PA_TILE_STORE(vt[buf ^ 1], vr)
+            if (GATED) gate_tile_store(gtile[buf ^ 1], gb, gf, tid);
         }
         __syncthreads();
     }
@@ -263,15 +308,16 @@ __global__ __launch_bounds__(256) void k_attn_prep(const bf16_t* __restrict__ dO
 
 // ---- backward: dQ -----------------------------------------------------------------------------------
 // acc[fb][ib] = dQ^T: feature 16 fb + 4g + r, query 16 ib + r16.
-template <int P, int HD, int OWN, int WPE>
+template <int P, int HD, int OWN, int WPE, bool GATED>
 __global__ __launch_bounds__(256, WPE) void k_attn_dq(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
                                                  const bf16_t* __restrict__ V, const bf16_t* __restrict__ Gh,
                                                  const float* __restrict__ gz, bf16_t* __restrict__ dQ, int T,
-                                                 float scale) {
+                                                 float scale, const float* __restrict__ bl, float* __restrict__ qdq) {
     constexpr int NI = OWN / 16, NK = HD / 32, NF = HD / 16, WG = 4 * OWN;
     extern __shared__ __attribute__((aligned(16))) unsigned char attn_smem[];
     AttnTile<HD>* kt = reinterpret_cast<AttnTile<HD>*>(attn_smem);      // [2]
     AttnTile<HD>* vt = kt + 2;                                          // [2]
+    GateTile* gtile = reinterpret_cast<GateTile*>(vt + 2);              // [2]
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r16 = lane & 15, g = lane >> 4;
     const int nblk = (T + WG - 1) / WG;
     const int i0 = heavy_first(nblk, true) * WG;
@@ -298,8 +344,25 @@ __global__ __launch_bounds__(256, WPE) void k_attn_dq(const bf16_t* __restrict__
         for (int fb = 0; fb < NF; ++fb) acc[fb][ib] = (f32x4){0.f, 0.f, 0.f, 0.f};
     }
 
+    const float* bl_head = GATED ? bl + head : nullptr;
+    // gated: rsum = sum_j t_ij (q_i . k_j) = q_i . dq_i, the row's share of the gate gradient, summed
+    // here from the unrounded t (the dot product of the stored dq with q carries bf16 noise that a
+    // sum over a block of tokens amplifies)
+    float bq[NI], rsum[NI];
+#pragma unroll
+    for (int ib = 0; ib < NI; ++ib) {
+        bq[ib] = GATED ? bl_head[min(q0 + 16 * ib + r16, T - 1)] : 0.f;
+        rsum[ib] = 0.f;
+    }
+
     auto tile = [&](auto diag_c, int buf, int key0) {
         constexpr bool DIAG = decltype(diag_c)::value;
+        float fq[NI];
+        if (GATED && !DIAG) {
+            const float m = gtile[buf].b[AT - 1];          // the tile's last key
+#pragma unroll
+            for (int ib = 0; ib < NI; ++ib) fq[ib] = __expf(bq[ib] - m);
+        }
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
             Frag tf[NI];
@@ -312,6 +375,9 @@ __global__ __launch_bounds__(256, WPE) void k_attn_dq(const bf16_t* __restrict__
                     kf[ks] = row_frag<HD>(kt[buf], kb, ks, r16, g);
                     vf[ks] = row_frag<HD>(vt[buf], kb, ks, r16, g);
                 }
+                float4 gk = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (GATED) gk = *(const float4*)(DIAG ? &gtile[buf].b[16 * kb + 4 * g] : &gtile[buf].f[16 * kb + 4 * g]);
+                const float gkr[4] = {gk.x, gk.y, gk.z, gk.w};
 #pragma unroll
                 for (int ib = 0; ib < NI; ++ib) {
                     f32x4 c = {0.f, 0.f, 0.f, 0.f}, e = {gzq[ib], gzq[ib], gzq[ib], gzq[ib]};
@@ -323,7 +389,9 @@ __global__ __launch_bounds__(256, WPE) void k_attn_dq(const bf16_t* __restrict__
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         float tv = e[r] * pscale * ipow<P - 1>(scale * c[r]);
+                        if (GATED) tv *= DIAG ? __expf(bq[ib] - gkr[r]) : fq[ib] * gkr[r];
                         if (DIAG && key0 + 16 * kb + 4 * g + r > q0 + 16 * ib + r16) tv = 0.f;
+                        if (GATED) rsum[ib] += tv * c[r];
                         tf[ib].v[4 * jb + r] = (__bf16)tv;
                     }
                 }
@@ -339,16 +407,20 @@ __global__ __launch_bounds__(256, WPE) void k_attn_dq(const bf16_t* __restrict__
 
     const int ntile = (min(i0 + WG, T) + AT - 1) / AT;
     uint4 kr[HD / 32], vr[HD / 32];
+    float gb = 0.f, gf2 = 0.f;
     PA_TILE_LOAD(kr, Kh, 0, false)
     PA_TILE_LOAD(vr, Vh, 0, false)
+    if (GATED) gate_tile_load(gb, gf2, bl_head, 0, AT - 1, 1.f, tid, T);
     PA_TILE_STORE(kt[0], kr)
     PA_TILE_STORE(vt[0], vr)
+    if (GATED) gate_tile_store(gtile[0], gb, gf2, tid);
     __syncthreads();
     for (int t = 0; t < ntile; ++t) {
         const int buf = t & 1, key0 = t * AT;
         if (t + 1 < ntile) {
             PA_TILE_LOAD(kr, Kh, key0 + AT, false)
             PA_TILE_LOAD(vr, Vh, key0 + AT, false)
+            if (GATED) gate_tile_load(gb, gf2, bl_head, key0 + AT, key0 + 2 * AT - 1, 1.f, tid, T);
         }
         if (active && key0 <= q0 + OWN - 1) {
             if (key0 + AT - 1 > q0) tile(std::true_type{}, buf, key0);
@@ -357,6 +429,7 @@ __global__ __launch_bounds__(256, WPE) void k_attn_dq(const bf16_t* __restrict__
         if (t + 1 < ntile) {
             PA_TILE_STORE(kt[buf ^ 1], kr)
             PA_TILE_STORE(vt[buf ^ 1], vr)
+            if (GATED) gate_tile_store(gtile[buf ^ 1], gb, gf2, tid);
         }
         __syncthreads();
     }
@@ -364,14 +437,20 @@ __global__ __launch_bounds__(256, WPE) void k_attn_dq(const bf16_t* __restrict__
     if (!active) return;
 #pragma unroll
     for (int ib = 0; ib < NI; ++ib) {
-        if (q0 + 16 * ib + r16 >= T) continue;
-        const size_t row = head + q0 + 16 * ib + r16;
+        const bool in = q0 + 16 * ib + r16 < T;
+        const size_t row = head + min(q0 + 16 * ib + r16, T - 1);
 #pragma unroll
         for (int fb = 0; fb < NF; ++fb) {
             bf16x4 o;
 #pragma unroll
             for (int r = 0; r < 4; ++r) o[r] = (__bf16)acc[fb][ib][r];
-            *(bf16x4*)(dQ + row * HD + 16 * fb + 4 * g) = o;
+            if (in) *(bf16x4*)(dQ + row * HD + 16 * fb + 4 * g) = o;
+        }
+        if (GATED) {
+            float dot = rsum[ib];
+            dot += __shfl_xor(dot, 16);
+            dot += __shfl_xor(dot, 32);
+            if (in && g == 0) qdq[row] = dot;
         }
     }
 }
@@ -380,16 +459,19 @@ __global__ __launch_bounds__(256, WPE) void k_attn_dq(const bf16_t* __restrict__
 // dk[fb][kb] = dK^T: feature 16 fb + 4g + r, key 16 kb + r16 of the wave's OWN keys; dv likewise.
 // S and E are formed queries x keys here, so that their accumulators are the B operand (k-slots =
 // queries) of the two contractions over the queries.
-template <int P, int HD, int OWN, int WPE>
+template <int P, int HD, int OWN, int WPE, bool GATED>
 __global__ __launch_bounds__(256, WPE) void k_attn_dkdv(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
                                                    const bf16_t* __restrict__ V, const bf16_t* __restrict__ Gh,
                                                    const float* __restrict__ gz, bf16_t* __restrict__ dK,
-                                                   bf16_t* __restrict__ dV, int T, float scale) {
+                                                   bf16_t* __restrict__ dV, int T, float scale,
+                                                   const float* __restrict__ bl, float* __restrict__ kdk,
+                                                   float* __restrict__ wsum) {
     constexpr int NJ = OWN / 16, NK = HD / 32, NF = HD / 16, WG = 4 * OWN;
     extern __shared__ __attribute__((aligned(16))) unsigned char attn_smem[];
     AttnTile<HD>* qt = reinterpret_cast<AttnTile<HD>*>(attn_smem);      // [2]
     AttnTile<HD>* gt = qt + 2;                                          // [2]
     float(*gzt)[AT] = reinterpret_cast<float(*)[AT]>(gt + 2);           // [2][AT]
+    GateTile* gtile = reinterpret_cast<GateTile*>(gzt + 2);             // [2]
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r16 = lane & 15, g = lane >> 4;
     const int j0 = heavy_first((T + WG - 1) / WG, false) * WG;
     const int k0 = j0 + OWN * w;                    // the wave's first key
@@ -417,8 +499,25 @@ __global__ __launch_bounds__(256, WPE) void k_attn_dkdv(const bf16_t* __restrict
         }
     }
 
+    const float* bl_head = GATED ? bl + head : nullptr;
+    // gated: csum = sum_i e_ij a_ij = k_j . dk_j / p, the key's share of the gate gradient, from the
+    // unrounded weights
+    float bk[NJ], csum[NJ];
+#pragma unroll
+    for (int kb = 0; kb < NJ; ++kb) {
+        bk[kb] = GATED ? bl_head[min(k0 + 16 * kb + r16, T - 1)] : 0.f;
+        csum[kb] = 0.f;
+    }
+
+    float wprev = 0.f;   // the wave's total of csum at the end of the last complete block of queries
     auto tile = [&](auto diag_c, int buf, int q0) {
         constexpr bool DIAG = decltype(diag_c)::value;
+        float fk[NJ];
+        if (GATED && !DIAG) {
+            const float m = gtile[buf].b[0];               // the tile's first query
+#pragma unroll
+            for (int kb = 0; kb < NJ; ++kb) fk[kb] = __expf(m - bk[kb]);
+        }
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
             Frag tf[NJ], pf[NJ];
@@ -433,6 +532,9 @@ __global__ __launch_bounds__(256, WPE) void k_attn_dkdv(const bf16_t* __restrict
                 }
                 const float4 gz4 = *(const float4*)&gzt[buf][16 * qb + 4 * g];
                 const f32x4 e0 = {gz4.x, gz4.y, gz4.z, gz4.w};
+                float4 gq = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (GATED) gq = *(const float4*)(DIAG ? &gtile[buf].b[16 * qb + 4 * g] : &gtile[buf].f[16 * qb + 4 * g]);
+                const float gqr[4] = {gq.x, gq.y, gq.z, gq.w};
 #pragma unroll
                 for (int kb = 0; kb < NJ; ++kb) {
                     f32x4 c = {0.f, 0.f, 0.f, 0.f}, e = e0;   // query 16 qb + 4g + r, key 16 kb + r16
@@ -446,10 +548,16 @@ __global__ __launch_bounds__(256, WPE) void k_attn_dkdv(const bf16_t* __restrict
                         const float sc = scale * c[r];
                         const float pw = ipow<P - 1>(sc);
                         float a = pw * sc, tv = e[r] * pscale * pw;
+                        if (GATED) {
+                            const float gg = DIAG ? __expf(gqr[r] - bk[kb]) : gqr[r] * fk[kb];
+                            a *= gg;
+                            tv *= gg;
+                        }
                         if (DIAG && q0 + 16 * qb + 4 * g + r < k0 + 16 * kb + r16) {
                             a = 0.f;
                             tv = 0.f;
                         }
+                        if (GATED) csum[kb] += e[r] * a;
                         pf[kb].v[4 * jb + r] = (__bf16)a;
                         tf[kb].v[4 * jb + r] = (__bf16)tv;
                     }
@@ -470,13 +578,15 @@ __global__ __launch_bounds__(256, WPE) void k_attn_dkdv(const bf16_t* __restrict
 
     const int t_first = j0 / AT, ntile = (T + AT - 1) / AT;    // query tiles t_first .. ntile - 1 reach the block's first key
     uint4 qr[HD / 32], gr[HD / 32];
-    float gzr = 0.f;
+    float gzr = 0.f, gb = 0.f, gf2 = 0.f;
     PA_TILE_LOAD(qr, Qh, t_first * AT, false)
     PA_TILE_LOAD(gr, Gh_h, t_first * AT, true)
     if (tid < AT) gzr = t_first * AT + tid < T ? gzh[t_first * AT + tid] : 0.f;
+    if (GATED) gate_tile_load(gb, gf2, bl_head, t_first * AT, t_first * AT, -1.f, tid, T);
     PA_TILE_STORE(qt[0], qr)
     PA_TILE_STORE(gt[0], gr)
     if (tid < AT) gzt[0][tid] = gzr;
+    if (GATED) gate_tile_store(gtile[0], gb, gf2, tid);
     __syncthreads();
     for (int t = t_first; t < ntile; ++t) {
         const int buf = (t - t_first) & 1, q0 = t * AT;
@@ -484,15 +594,30 @@ __global__ __launch_bounds__(256, WPE) void k_attn_dkdv(const bf16_t* __restrict
             PA_TILE_LOAD(qr, Qh, q0 + AT, false)
             PA_TILE_LOAD(gr, Gh_h, q0 + AT, true)
             if (tid < AT) gzr = q0 + AT + tid < T ? gzh[q0 + AT + tid] : 0.f;
+            if (GATED) gate_tile_load(gb, gf2, bl_head, q0 + AT, q0 + AT, -1.f, tid, T);
         }
         if (active && q0 + AT - 1 >= k0) {
             if (q0 < k0 + OWN - 1) tile(std::true_type{}, buf, q0);   // some pair of this tile lies above the diagonal
             else tile(std::false_type{}, buf, q0);
         }
+        if (GATED && active && (q0 + AT) % WG == 0) {
+            // a block of queries is complete: the wave's sum goes to wsum[head][key block][query block][wave]
+            // (the key block's own query block is not a boundary sum: its pairs are summed per token)
+            // = what the block added to the wave's running column sums
+            const int jblk = j0 / WG, iblk = q0 / WG, nblk = T / WG;
+            float v = 0.f;
+#pragma unroll
+            for (int kb = 0; kb < NJ; ++kb) v += csum[kb];
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+            if (iblk > jblk && lane == 0) wsum[(((size_t)blockIdx.y * nblk + jblk) * nblk + iblk) * 4 + w] = v - wprev;
+            wprev = v;
+        }
         if (t + 1 < ntile) {
             PA_TILE_STORE(qt[buf ^ 1], qr)
             PA_TILE_STORE(gt[buf ^ 1], gr)
             if (tid < AT) gzt[buf ^ 1][tid] = gzr;
+            if (GATED) gate_tile_store(gtile[buf ^ 1], gb, gf2, tid);
         }
         __syncthreads();
     }
@@ -500,8 +625,8 @@ __global__ __launch_bounds__(256, WPE) void k_attn_dkdv(const bf16_t* __restrict
     if (!active) return;
 #pragma unroll
     for (int kb = 0; kb < NJ; ++kb) {
-        if (k0 + 16 * kb + r16 >= T) continue;
-        const size_t row = head + k0 + 16 * kb + r16;
+        const bool in = k0 + 16 * kb + r16 < T;
+        const size_t row = head + min(k0 + 16 * kb + r16, T - 1);
 #pragma unroll
         for (int fb = 0; fb < NF; ++fb) {
             bf16x4 a, b;
@@ -510,15 +635,23 @@ __global__ __launch_bounds__(256, WPE) void k_attn_dkdv(const bf16_t* __restrict
                 a[r] = (__bf16)dk[fb][kb][r];
                 b[r] = (__bf16)dv[fb][kb][r];
             }
-            *(bf16x4*)(dK + row * HD + 16 * fb + 4 * g) = a;
-            *(bf16x4*)(dV + row * HD + 16 * fb + 4 * g) = b;
+            if (in) {
+                *(bf16x4*)(dK + row * HD + 16 * fb + 4 * g) = a;
+                *(bf16x4*)(dV + row * HD + 16 * fb + 4 * g) = b;
+            }
+        }
+        if (GATED) {
+            float dot = csum[kb];
+            dot += __shfl_xor(dot, 16);
+            dot += __shfl_xor(dot, 32);
+            if (in && g == 0) kdk[row] = (float)P * dot;
         }
     }
 }
 
 template <int HD>
 constexpr size_t attn_smem_bytes() {
-    return 4 * sizeof(AttnTile<HD>) + 2 * AT * sizeof(float);
+    return 4 * sizeof(AttnTile<HD>) + 2 * AT * sizeof(float) + 2 * sizeof(GateTile);
 }
 // LDS beyond the default per-kernel limit has to be requested once per kernel
 template <typename F>
@@ -527,6 +660,29 @@ bool allow_smem(F* fn, size_t bytes) {
     hipError_t e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
     if (e != hipSuccess) note_hip_error(e, "hipFuncSetAttribute(max dynamic LDS)");
     return e == hipSuccess;
+}
+
+// Gate gradient, the part that crosses block boundaries: xb[head][m] = sum of e_ij a_ij over the pairs
+// with key block <= m < query block, from wsum[head][key block][query block][wave].
+// First along the query blocks: wsum[J][m][0] <- sum over I > m (one thread per key block J) ...
+__global__ __launch_bounds__(64) void k_attn_gate_rows(float* __restrict__ wsum, int nblk) {
+    const int jb = blockIdx.x * 64 + threadIdx.x, bh = blockIdx.y;
+    if (jb >= nblk) return;
+    float* rowp = wsum + ((size_t)bh * nblk + jb) * nblk * 4;
+    float run = 0.f;
+    for (int i = nblk - 1; i >= jb; --i) {
+        const float here = i > jb ? rowp[4 * i] + rowp[4 * i + 1] + rowp[4 * i + 2] + rowp[4 * i + 3] : 0.f;
+        rowp[4 * i] = run;
+        run += here;
+    }
+}
+// ... then down the key blocks: xb[m] = sum over J <= m (one thread per boundary m)
+__global__ __launch_bounds__(64) void k_attn_gate_cols(const float* __restrict__ wsum, float* __restrict__ xb, int nblk) {
+    const int m = blockIdx.x * 64 + threadIdx.x, bh = blockIdx.y;
+    if (m >= nblk) return;
+    float acc = 0.f;
+    for (int jb = 0; jb <= m; ++jb) acc += wsum[(((size_t)bh * nblk + jb) * nblk + m) * 4];
+    xb[(size_t)bh * nblk + m] = acc;
 }
 
 // Rows of the block one wave owns and the waves per SIMD the kernel is compiled for.  Two waves
@@ -541,20 +697,23 @@ struct Shape {
     static constexpr int DKDV_OWN = HD == 32 ? 64 : 32, DKDV_WPE = HD == 128 ? 1 : 2;
 };
 
-template <int P, int HD>
+template <int P, int HD, bool GATED>
 bool fwd_t(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* V, bf16_t* O, float* Z, int BH, int T, float scale,
-           int normalize) {
+           int normalize, const float* bl) {
     constexpr int WG = 4 * Shape<HD>::FWD_OWN;
-    if (!allow_smem(k_attn_fwd<P, HD, Shape<HD>::FWD_OWN, Shape<HD>::FWD_WPE>, attn_smem_bytes<HD>())) return false;
+    auto kern = k_attn_fwd<P, HD, Shape<HD>::FWD_OWN, Shape<HD>::FWD_WPE, GATED>;
+    if (!allow_smem(kern, attn_smem_bytes<HD>())) return false;
     LaunchScope ls("attn_fwd", s);
-    hipLaunchKernelGGL((k_attn_fwd<P, HD, Shape<HD>::FWD_OWN, Shape<HD>::FWD_WPE>), dim3((T + WG - 1) / WG, BH), dim3(256), attn_smem_bytes<HD>(), s, Q, K,
-                       V, O, Z, T, scale, normalize);
+    hipLaunchKernelGGL(kern, dim3((T + WG - 1) / WG, BH), dim3(256), attn_smem_bytes<HD>(), s, Q, K, V, O, Z, T, scale, normalize,
+                       bl);
     return launch_ok();
 }
 
-template <int P, int HD>
+template <int P, int HD, bool GATED>
 bool bwd_t(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* V, const bf16_t* O, const float* Z, const bf16_t* dO,
-           bf16_t* Gh, float* gz, bf16_t* dQ, bf16_t* dK, bf16_t* dV, int BH, int T, float scale, int normalize) {
+           bf16_t* Gh, float* gz, bf16_t* dQ, bf16_t* dK, bf16_t* dV, int BH, int T, float scale, int normalize,
+           const AttnGate& gate) {
+    const float* bl = gate.bl;
     const long long rows = (long long)BH * T;
     {
         constexpr int RPB = 256 / (HD / 4);
@@ -565,18 +724,27 @@ bool bwd_t(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* V, con
     }
     {
         constexpr int WG = 4 * Shape<HD>::DKDV_OWN;
-        if (!allow_smem(k_attn_dkdv<P, HD, Shape<HD>::DKDV_OWN, Shape<HD>::DKDV_WPE>, attn_smem_bytes<HD>())) return false;
+        auto kern = k_attn_dkdv<P, HD, Shape<HD>::DKDV_OWN, Shape<HD>::DKDV_WPE, GATED>;
+        if (!allow_smem(kern, attn_smem_bytes<HD>())) return false;
         LaunchScope ls("attn_bwd_dkdv", s);
-        hipLaunchKernelGGL((k_attn_dkdv<P, HD, Shape<HD>::DKDV_OWN, Shape<HD>::DKDV_WPE>), dim3((T + WG - 1) / WG, BH), dim3(256), attn_smem_bytes<HD>(), s, Q,
-                           K, V, Gh, gz, dK, dV, T, scale);
+        hipLaunchKernelGGL(kern, dim3((T + WG - 1) / WG, BH), dim3(256), attn_smem_bytes<HD>(), s, Q, K, V, Gh, gz, dK, dV, T,
+                           scale, bl, gate.kdk, gate.wsum);
         if (!launch_ok()) return false;
+        if (GATED) {
+            const int nblk = T / WG;
+            LaunchScope ls2("attn_gate_boundary", s);
+            hipLaunchKernelGGL(k_attn_gate_rows, dim3((nblk + 63) / 64, BH), dim3(64), 0, s, gate.wsum, nblk);
+            hipLaunchKernelGGL(k_attn_gate_cols, dim3((nblk + 63) / 64, BH), dim3(64), 0, s, gate.wsum, gate.xb, nblk);
+            if (!launch_ok()) return false;
+        }
     }
     {
         constexpr int WG = 4 * Shape<HD>::DQ_OWN;
-        if (!allow_smem(k_attn_dq<P, HD, Shape<HD>::DQ_OWN, Shape<HD>::DQ_WPE>, attn_smem_bytes<HD>())) return false;
+        auto kern = k_attn_dq<P, HD, Shape<HD>::DQ_OWN, Shape<HD>::DQ_WPE, GATED>;
+        if (!allow_smem(kern, attn_smem_bytes<HD>())) return false;
         LaunchScope ls("attn_bwd_dq", s);
-        hipLaunchKernelGGL((k_attn_dq<P, HD, Shape<HD>::DQ_OWN, Shape<HD>::DQ_WPE>), dim3((T + WG - 1) / WG, BH), dim3(256), attn_smem_bytes<HD>(), s, Q, K,
-                           V, Gh, gz, dQ, T, scale);
+        hipLaunchKernelGGL(kern, dim3((T + WG - 1) / WG, BH), dim3(256), attn_smem_bytes<HD>(), s, Q, K, V, Gh, gz, dQ, T, scale,
+                           bl, gate.qdq);
         if (!launch_ok()) return false;
     }
     return true;
@@ -584,12 +752,16 @@ bool bwd_t(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* V, con
 
 }  // namespace
 
+int attn_gate_block(int d) { return 4 * (d == 128 ? Shape<128>::DKDV_OWN : d == 64 ? Shape<64>::DKDV_OWN : Shape<32>::DKDV_OWN); }
+
 bool attn_shape_ok(int p, int d) { return (p == 2 || p == 3 || p == 4) && (d == 32 || d == 64 || d == 128); }
 
 bool launch_attn_fwd(hipStream_t s, int p, int d, const bf16_t* Q, const bf16_t* K, const bf16_t* V, bf16_t* O, float* Z, int BH,
-                     int T, float scale, int normalize) {
-#define PA_CASE(PP, DD) \
-    if (p == PP && d == DD) return fwd_t<PP, DD>(s, Q, K, V, O, Z, BH, T, scale, normalize);
+                     int T, float scale, int normalize, const float* bl) {
+#define PA_CASE(PP, DD)                                                                                      \
+    if (p == PP && d == DD)                                                                                  \
+        return bl != nullptr ? fwd_t<PP, DD, true>(s, Q, K, V, O, Z, BH, T, scale, normalize, bl)            \
+                             : fwd_t<PP, DD, false>(s, Q, K, V, O, Z, BH, T, scale, normalize, bl);
     PA_CASE(2, 32) PA_CASE(2, 64) PA_CASE(2, 128)
     PA_CASE(3, 32) PA_CASE(3, 64) PA_CASE(3, 128)
     PA_CASE(4, 32) PA_CASE(4, 64) PA_CASE(4, 128)
@@ -599,9 +771,11 @@ bool launch_attn_fwd(hipStream_t s, int p, int d, const bf16_t* Q, const bf16_t*
 
 bool launch_attn_bwd(hipStream_t s, int p, int d, const bf16_t* Q, const bf16_t* K, const bf16_t* V, const bf16_t* O,
                      const float* Z, const bf16_t* dO, bf16_t* Gh, float* gz, bf16_t* dQ, bf16_t* dK, bf16_t* dV, int BH, int T,
-                     float scale, int normalize) {
-#define PA_CASE(PP, DD) \
-    if (p == PP && d == DD) return bwd_t<PP, DD>(s, Q, K, V, O, Z, dO, Gh, gz, dQ, dK, dV, BH, T, scale, normalize);
+                     float scale, int normalize, const AttnGate& gate) {
+#define PA_CASE(PP, DD)                                                                                                          \
+    if (p == PP && d == DD)                                                                                                      \
+        return gate.bl != nullptr ? bwd_t<PP, DD, true>(s, Q, K, V, O, Z, dO, Gh, gz, dQ, dK, dV, BH, T, scale, normalize, gate) \
+                                  : bwd_t<PP, DD, false>(s, Q, K, V, O, Z, dO, Gh, gz, dQ, dK, dV, BH, T, scale, normalize, gate);
     PA_CASE(2, 32) PA_CASE(2, 64) PA_CASE(2, 128)
     PA_CASE(3, 32) PA_CASE(3, 64) PA_CASE(3, 128)
     PA_CASE(4, 32) PA_CASE(4, 64) PA_CASE(4, 128)

@@ -98,11 +98,21 @@ bool launch_gate_boundary(hipStream_t s, const bf16_t* stC, const bf16_t* rtC, c
 // attention form (chunk == T): p in {2, 3, 4}, d = v in {32, 64, 128}, any T.
 // Gh [BH][T][d] bf16 and gz [BH][T] float32 are scratch of the backward pass.
 bool attn_shape_ok(int p, int d);
+// bl (null when not gated): [BH][T] running sums of the log-gates from the start of the sequence
 bool launch_attn_fwd(hipStream_t s, int p, int d, const bf16_t* Q, const bf16_t* K, const bf16_t* V, bf16_t* O, float* Z, int BH,
-                     int T, float scale, int normalize);
+                     int T, float scale, int normalize, const float* bl = nullptr);
+// Gated backward pass (bl non-null; T a multiple of attn_gate_block(d)): also leaves what the gradient of
+// the log-gates needs: qdq [BH][T] = q_i . dq_i, kdk [BH][T] = k_j . dk_j (from float32 accumulators) and
+// xb [BH][T / block] = the sum of e_ij a_ij over the pairs j <= end of block m < i.
+// wsum: scratch, BH * (T / block)^2 * 4 floats.
+struct AttnGate {
+    const float* bl = nullptr;
+    float *qdq = nullptr, *kdk = nullptr, *xb = nullptr, *wsum = nullptr;
+};
+int attn_gate_block(int d);
 bool launch_attn_bwd(hipStream_t s, int p, int d, const bf16_t* Q, const bf16_t* K, const bf16_t* V, const bf16_t* O,
                      const float* Z, const bf16_t* dO, bf16_t* Gh, float* gz, bf16_t* dQ, bf16_t* dK, bf16_t* dV, int BH, int T,
-                     float scale, int normalize);
+                     float scale, int normalize, const AttnGate& gate = AttnGate());
 
 }  // namespace mfma
 }  // namespace pa

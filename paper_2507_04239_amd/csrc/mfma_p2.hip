@@ -57,17 +57,18 @@ bool chunked_ok(const pa_problem& pr) {
     return pr.dtype == PA_DTYPE_BF16 && pr.p == 2 && pr.d == DH && pr.v == DH && pr.chunk % QBLK == 0 &&
            (size_t)pr.B * pr.H <= 65535u;
 }
+// gated: the boundary sums of the gate gradient are kept per block of keys of the dK / dV kernel
 bool attn_ok(const pa_problem& pr) {
-    return pr.dtype == PA_DTYPE_BF16 && pr.d == pr.v && attn_shape_ok(pr.p, pr.d) && pr.chunk == pr.T && !pr.gated &&
-           (size_t)pr.B * pr.H <= 65535u;
+    return pr.dtype == PA_DTYPE_BF16 && pr.d == pr.v && attn_shape_ok(pr.p, pr.d) && pr.chunk == pr.T &&
+           (!pr.gated || pr.T % attn_gate_block(pr.d) == 0) && (size_t)pr.B * pr.H <= 65535u;
 }
 // One chunk: the attention-form kernels.  (The chunked kernels can run p = 2, d = 64 as one chunk
-// too; that path remains for gated problems, which the attention-form kernels do not take.)
+// too; that path remains for gated sequences that are a multiple of 128 but not of the block.)
 bool use_attn(const pa_problem& pr) { return attn_ok(pr); }
 
 // attention form, backward: ghat (bf16) and gz (float32) per token
 struct AttnLayout {
-    size_t off_gh, off_gz, total;
+    size_t off_gh, off_gz, off_wsum, total;
 };
 AttnLayout make_attn_layout(const pa_problem& pr, bool backward) {
     AttnLayout L{};
@@ -75,11 +76,19 @@ AttnLayout make_attn_layout(const pa_problem& pr, bool backward) {
     const size_t rows = (size_t)pr.B * pr.H * pr.T;
     L.off_gh = 0;
     L.off_gz = align_up(rows * pr.d * 2, 256);
-    L.total = L.off_gz + align_up(rows * sizeof(float), 256);
+    L.off_wsum = L.off_gz + align_up(rows * sizeof(float), 256);
+    L.total = L.off_wsum;
+    if (pr.gated) {
+        const size_t nblk = (size_t)(pr.T / attn_gate_block(pr.d));
+        L.total += align_up((size_t)pr.B * pr.H * nblk * nblk * 4 * sizeof(float), 256);
+    }
     return L;
 }
 
 }  // namespace
+
+bool mfma_gate_exact_rows(const pa_problem& pr) { return use_attn(pr); }
+int mfma_gate_fin_chunk(const pa_problem& pr) { return use_attn(pr) ? attn_gate_block(pr.d) : pr.chunk; }
 
 pa_status mfma_supported(const pa_problem& pr, bool backward) {
     (void)backward;
@@ -103,7 +112,7 @@ pa_status mfma_fwd(const Ctx& c, const void* Q, const void* K, const void* V, vo
     const int BH = pr.B * pr.H;
     if (use_attn(pr)) {
         PA_TRY(launch_attn_fwd(c.stream, pr.p, pr.d, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (bf16_t*)O, Z, BH, pr.T,
-                               pr.scale, pr.normalize))
+                               pr.scale, pr.normalize, c.gate.bl))
         return PA_OK;
     }
     const Layout L = make_layout(pr, false);
@@ -155,9 +164,17 @@ pa_status mfma_bwd(const Ctx& c, const void* Q, const void* K, const void* V, co
     const int BH = pr.B * pr.H;
     if (use_attn(pr)) {
         const AttnLayout A = make_attn_layout(pr, true);
+        AttnGate ag;
+        if (pr.gated) {
+            ag.bl = c.gate.bl;       // with chunk == T: running sums from the start of the sequence
+            ag.qdq = c.gate.db;
+            ag.kdk = c.gate.db2;
+            ag.xb = c.gate.xb;
+            ag.wsum = (float*)(c.ws + A.off_wsum);
+        }
         PA_TRY(launch_attn_bwd(c.stream, pr.p, pr.d, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)O, Z,
                                (const bf16_t*)dO, (bf16_t*)(c.ws + A.off_gh), (float*)(c.ws + A.off_gz), (bf16_t*)dQ, (bf16_t*)dK,
-                               (bf16_t*)dV, BH, pr.T, pr.scale, pr.normalize))
+                               (bf16_t*)dV, BH, pr.T, pr.scale, pr.normalize, ag))
         return PA_OK;
     }
     const Layout L = make_layout(pr, true);

@@ -72,3 +72,48 @@ def test_attention_form_zero_rows():
     dQ, dK, dV = orc.bwd_bhtd(Q, K, V, G, 4, None, True, 1.0)
     assert_close(got, dict(O=O, Z=Z, dQ=dQ, dK=dK, dV=dV), "bf16", "attention form zero rows")
     assert (got["O"][0, 0, 3] == 0).all() and (got["dQ"][0, 0, 3] == 0).all()
+
+
+GATED_CASES = [
+    # p, d, B, H, T, normalize, scale, mean decay per step
+    (4, 32, 1, 2, 768, True, 1.0, 0.02),       # three blocks of 256 keys
+    (2, 128, 1, 2, 512, True, 1.0, 0.02),      # four blocks of 128
+    (2, 64, 1, 1, 640, True, 0.7, 0.05),
+    (4, 64, 1, 1, 256, True, 1.0, 0.01),
+    (3, 64, 1, 2, 384, False, 1.0, 0.03),      # un-normalised: the q . dq term of the gate gradient counts
+    (2, 32, 2, 1, 256, False, 1.0, 0.5),       # strong decay: the factors underflow far from the diagonal
+    (2, 32, 2, 1, 256, True, 1.0, 0.5),        # normalised: the rounding of O_i enters every e_ij = ghat_i . (v_j - O_i);
+    (2, 32, 2, 1, 256, True, 1.0, 0.15),       # it cancels between the row term and the column terms of the gate gradient
+    (2, 128, 1, 1, 128, True, 1.0, 0.02),      # a single block: no boundary sums
+]
+
+
+@pytest.mark.parametrize("case", GATED_CASES, ids=lambda c: "-".join(str(x) for x in c))
+def test_gated_attention_form(case):
+    """Per-timestep gates in the attention-form kernels: outputs, dQ, dK, dV and the gradient of the
+    log-gates against the float64 oracle."""
+    p, d, B, H, T, normalize, scale, decay = case
+    print("case", case, flush=True)
+    Q, K, V, G = inputs.make_qkvg(B, H, T, d, seed=7300 + GATED_CASES.index(case), dtype="bf16")
+    lg = inputs.make_log_gates(B, H, T, 7400 + GATED_CASES.index(case), decay)
+    prob = binding.make_problem(B, H, T, d, d, p, T, normalize, scale, "bf16", "mfma", False, True)
+    assert binding.power_attn_supported(prob, True)
+    got = run_fwd_bwd(Q, K, V, G, p, T, "bf16", normalize, scale, impl="mfma", log_g=lg)
+    O, Z = orc.fwd_bhtd(Q, K, V, p, None, normalize, scale, log_g=lg)
+    dQ, dK, dV, dL = orc.bwd_bhtd(Q, K, V, G, p, None, normalize, scale, log_g=lg)
+    assert_close(got, dict(O=O, Z=Z, dQ=dQ, dK=dK, dV=dV, dlog_g=dL), "bf16", f"gated attention form {case}")
+
+
+def test_gated_attention_form_long():
+    """Gate gradient over many blocks (T = 8192, d = 128: 64 blocks): the part that crosses block
+    boundaries comes from the block sums, not from a running sum over the sequence."""
+    p, d, T = 2, 128, 8192
+    Q, K, V, G = inputs.make_qkvg(1, 1, T, d, seed=7500, dtype="bf16")
+    lg = inputs.make_log_gates(1, 1, T, 7501, 0.02)
+    print("case gated attention form long", flush=True)
+    got = run_fwd_bwd(Q, K, V, G, p, T, "bf16", impl="mfma", log_g=lg)
+    lg64 = lg[0, 0].astype(np.float64)
+    O, Z = orc.fwd_chunked_gated(Q[0, 0], K[0, 0], V[0, 0], lg64, p, 512)
+    dQ, dK, dV, dL = orc.bwd_chunked_gated(Q[0, 0], K[0, 0], V[0, 0], lg64, G[0, 0], p, 512)
+    assert_close({k: a[0, 0] for k, a in got.items()}, dict(O=O, Z=Z, dQ=dQ, dK=dK, dV=dV, dlog_g=dL), "bf16",
+                 "gated attention form T = 8192")
