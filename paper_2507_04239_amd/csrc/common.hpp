@@ -86,7 +86,7 @@ pa_status gate_prepare(const Ctx& c, const float* log_g);
 // k.dk into gate.db2 (else they are formed here from the outputs)
 // fin_chunk: the token granularity of gate.xb (the problem's chunk, or finer when the family says so)
 pa_status gate_gradient(const Ctx& c, const void* Q, const void* K, const void* dQ, const void* dK, float* dlog_g,
-                        bool have_dots, int fin_chunk, bool exact_rows);
+                        bool have_dots, int fin_chunk);
 
 // generic (vector-ALU, float32) family
 size_t generic_workspace_bytes(const pa_problem& pr, bool backward);
@@ -115,7 +115,5 @@ pa_status mfma_bwd(const Ctx& c, const void* Q, const void* K, const void* V, co
                    const void* dO, void* dQ, void* dK, void* dV);
 // tokens per entry of GateBuf::xb as mfma_bwd leaves it (gated problems)
 int mfma_gate_fin_chunk(const pa_problem& pr);
-// true if mfma_bwd forms q_i . dq_i in float32 from unrounded weights (see gate_gradient)
-bool mfma_gate_exact_rows(const pa_problem& pr);
 
 }  // namespace pa

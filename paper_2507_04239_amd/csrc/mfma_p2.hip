@@ -87,7 +87,6 @@ AttnLayout make_attn_layout(const pa_problem& pr, bool backward) {
 
 }  // namespace
 
-bool mfma_gate_exact_rows(const pa_problem& pr) { return use_attn(pr); }
 int mfma_gate_fin_chunk(const pa_problem& pr) { return use_attn(pr) ? attn_gate_block(pr.d) : pr.chunk; }
 
 pa_status mfma_supported(const pa_problem& pr, bool backward) {

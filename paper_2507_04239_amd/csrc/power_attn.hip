@@ -136,8 +136,7 @@ pa_status run_bwd(const pa_problem* prob, const void* Q, const void* K, const vo
     st = impl == PA_IMPL_MFMA ? mfma_bwd(c, Q, K, V, O, Z, dO, dQ, dK, dV) : generic_bwd(c, Q, K, V, O, Z, dO, dQ, dK, dV);
     if (st != PA_OK || !gated) return st;
     return gate_gradient(c, Q, K, dQ, dK, dlog_g, impl == PA_IMPL_MFMA,
-                         impl == PA_IMPL_MFMA ? mfma_gate_fin_chunk(*prob) : prob->chunk,
-                         impl == PA_IMPL_MFMA && mfma_gate_exact_rows(*prob));
+                         impl == PA_IMPL_MFMA ? mfma_gate_fin_chunk(*prob) : prob->chunk);
 }
 
 }  // namespace
