@@ -35,8 +35,8 @@ pa_status validate(const pa_problem* pr) {
 // chunk == 0: the library picks between the attention form (one chunk: cost ~ T per token) and the
 // chunked form (cost ~ the state size per token), Sec. 2 "Chunked form".  Where the bf16 MFMA
 // kernels apply the choice is measured on MI355X.  p = 2, d = 64, which has both forms on the
-// matrix cores: the attention form wins up to T = 2048 (1024 with gating, which runs the chunk
-// kernels as one chunk), and 256 is the best chunk beyond (128 when 256 does not divide T).  Other
+// matrix cores: the attention form wins up to T = 4096 (2048 with gating), and 256 is the best chunk
+// beyond (128 when 256 does not divide T).  Other
 // degrees and head sizes have matrix-core kernels for the attention form only, and that beats the
 // chunked form on the vector ALUs at any length the latter is sensible for.  Elsewhere the two costs
 // are compared by their multiply-add counts, T (4 d + 2) / 2 per token against 4 D (v + 1).
@@ -45,7 +45,7 @@ int auto_chunk(const pa_problem& pr) {
     pa_problem probe = pr;
     probe.chunk = pr.T % 256 == 0 ? 256 : 128;
     if (pr.T % 128 == 0 && may_mfma && mfma_supported(probe, true) == PA_OK)
-        return pr.T <= (pr.gated ? 1024 : 2048) ? pr.T : probe.chunk;
+        return pr.T <= (pr.gated ? 2048 : 4096) ? pr.T : probe.chunk;
     probe.chunk = pr.T;
     if (may_mfma && mfma_supported(probe, true) == PA_OK) return pr.T;
     double D = 1.0;   // C(d + p - 1, p)

@@ -70,10 +70,10 @@ def test_automatic_chunk_choice():
     assert rc(mk(1, 12, 65536, 64, 64, 2, 128)) == 128
     assert rc(mk(1, 12, 65536, 64, 64, 2, 0)) == 256          # bf16, p = 2, d = 64: measured best chunk
     assert rc(mk(1, 12, 65536 + 128, 64, 64, 2, 0)) == 128    # 256 does not divide T
-    assert rc(mk(4, 12, 2048, 64, 64, 2, 0)) == 2048          # short: attention form
-    assert rc(mk(4, 12, 4096, 64, 64, 2, 0)) == 256
-    assert rc(mk(4, 12, 2048, 64, 64, 2, 0, gated=True)) == 256
-    assert rc(mk(4, 12, 1024, 64, 64, 2, 0, gated=True)) == 1024
+    assert rc(mk(4, 12, 4096, 64, 64, 2, 0)) == 4096          # short: attention form
+    assert rc(mk(4, 12, 8192, 64, 64, 2, 0)) == 256
+    assert rc(mk(4, 12, 4096, 64, 64, 2, 0, gated=True)) == 256
+    assert rc(mk(4, 12, 2048, 64, 64, 2, 0, gated=True)) == 2048
     assert rc(mk(4, 12, 512, 64, 64, 2, 0)) == 512
     # d = 128: matrix-core kernels exist for the attention form only
     assert rc(mk(8, 16, 32768, 128, 128, 2, 0)) == 32768
