@@ -88,3 +88,43 @@ def test_automatic_chunk_choice():
     assert binding.power_attn_workspace_bytes(mk(1, 12, 65536, 64, 64, 2, 0), False) == \
         binding.power_attn_workspace_bytes(mk(1, 12, 65536, 64, 64, 2, 256), False)
     assert rc(mk(1, 1, 100, 16, 16, 2, 7)) == 0                  # invalid: 7 does not divide 100
+
+
+def test_support_matrix_host_logic():
+    """Which problems the matrix-core kernels take (host logic only, nothing is launched)."""
+    from paper_2507_04239_amd import binding
+    mk, ok, rows = binding.make_problem, binding.power_attn_supported, binding.power_attn_state_rows
+    # chunked form: p = 2, d = 64, chunk a multiple of 128
+    assert ok(mk(1, 2, 1024, 64, 64, 2, 128, impl="mfma"), True)
+    assert rows(mk(1, 2, 1024, 64, 64, 2, 128, impl="mfma")) == 36 * 64            # tiled embedding, d_tile = 8
+    assert not ok(mk(1, 2, 1024, 64, 64, 2, 64, impl="mfma"), True)
+    assert not ok(mk(1, 2, 1024, 128, 128, 2, 256, impl="mfma"), True)             # no chunked kernels at d = 128
+    assert ok(mk(1, 2, 1024, 128, 128, 2, 256, impl="auto"), True)                 # ... the generic family runs it
+    assert rows(mk(1, 2, 1024, 128, 128, 2, 256)) == 8256                          # C(129, 2), Lemma 4.2
+    # attention form: one chunk, degrees 2-4, head sizes 32 / 64 / 128, any length
+    for p, d in ((2, 32), (3, 64), (4, 128), (4, 32)):
+        assert ok(mk(1, 1, 1000, d, d, p, 1000, normalize=(p % 2 == 0), impl="mfma"), True), (p, d)
+        assert rows(mk(1, 1, 1000, d, d, p, 1000, normalize=(p % 2 == 0), impl="mfma")) == 0
+    assert not ok(mk(1, 1, 1024, 48, 48, 2, 1024, impl="mfma"), True)
+    assert not ok(mk(1, 1, 1024, 64, 32, 2, 1024, impl="mfma"), True)              # d != v
+    # with gates the sequence has to be a multiple of the dK / dV kernel's key block
+    assert ok(mk(1, 1, 1024, 128, 128, 2, 1024, impl="mfma", gated=True), True)
+    assert not ok(mk(1, 1, 1000, 128, 128, 2, 1000, impl="mfma", gated=True), True)
+    assert ok(mk(1, 1, 1000, 128, 128, 2, 1000, impl="auto", gated=True), True)    # generic
+    assert not ok(mk(1, 1, 128, 32, 32, 4, 128, impl="mfma", gated=True), True)    # d = 32: blocks of 256 keys
+    assert ok(mk(1, 1, 256, 32, 32, 4, 256, impl="mfma", gated=True), True)
+    # f32 never runs on the MFMA kernels
+    assert not ok(mk(1, 1, 256, 64, 64, 2, 128, dtype="f32", impl="mfma"), True)
+
+
+def test_decode_state_size_host_logic():
+    from paper_2507_04239_amd import binding
+    import math
+    for (B, H, d, p) in ((1, 12, 64, 2), (2, 3, 32, 4), (1, 1, 128, 2)):
+        prob = binding.make_problem(B, H, 1, d, d, p, 1)
+        D = math.comb(d + p - 1, p)
+        need = binding.power_attn_decode_state_bytes(prob)
+        assert need >= B * H * D * (d + 1) * 4          # the float32 state itself
+        assert need <= B * H * D * (d + 1) * 4 + D * 8 + B * H * ((D + 127) // 128) * (d + 1) * 4 + 5 * 256
+    assert binding.power_attn_decode_state_bytes(binding.make_problem(1, 1, 1, 200, 200, 2, 1)) == 0   # head size above 128
+    assert binding.power_attn_decode_state_bytes(binding.make_problem(1, 1, 1, 16, 16, 5, 1, normalize=False)) == 0
