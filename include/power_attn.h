@@ -42,7 +42,7 @@ extern "C" {
 
 typedef enum {
     PA_OK = 0,
-    PA_ERR_INVALID_ARG = 1,   /* null pointer, non-positive size, T % chunk != 0, odd p with normalize, ... */
+    PA_ERR_INVALID_ARG = 1,   /* null pointer, non-positive size, odd p with normalize, ... */
     PA_ERR_UNSUPPORTED = 2,   /* a valid problem this build has no kernel for (see pa_problem) */
     PA_ERR_WORKSPACE   = 3,   /* workspace is NULL or smaller than power_attn_workspace_bytes() */
     PA_ERR_HIP         = 4    /* a HIP runtime call or kernel launch failed */
@@ -64,9 +64,12 @@ typedef struct {
     int   d;            /* query / key head size */
     int   v;            /* value head size */
     int   p;            /* degree of the power (Sec. 4 Eq. (7)); even when normalize != 0 */
-    int   chunk;        /* chunk size c of the chunked form; must divide T.  chunk == T is the attention
-                           form (one chunk).  0: the library chooses between the two forms and the
-                           chunk size (see power_attn_resolved_chunk) */
+    int   chunk;        /* chunk size c of the chunked form.  chunk == T is the attention form (one chunk).
+                           0: the library chooses between the two forms and the chunk size (see
+                           power_attn_resolved_chunk).  A chunk that does not divide T (a ragged last
+                           chunk) is taken by the chunked bf16 MFMA kernels only, which then run the
+                           sequence padded with zero rows inside the workspace; elsewhere it is
+                           PA_ERR_UNSUPPORTED */
     int   normalize;    /* 1: divide by the sum of the scores; 0: leave un-normalised */
     float scale;        /* multiplies q.k before the power ("softmax scaling", App. E.1 step 2) */
     int   dtype;        /* pa_dtype of Q, K, V, O, dO, dQ, dK, dV; accumulation is always float32 */

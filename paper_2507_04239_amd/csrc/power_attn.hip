@@ -23,7 +23,6 @@ pa_status validate(const pa_problem* pr) {
     if (pr == nullptr) return PA_ERR_INVALID_ARG;
     if (pr->B <= 0 || pr->H <= 0 || pr->T <= 0 || pr->d <= 0 || pr->v <= 0 || pr->p <= 0 || pr->chunk < 0)
         return PA_ERR_INVALID_ARG;
-    if (pr->chunk > 0 && pr->T % pr->chunk != 0) return PA_ERR_INVALID_ARG;
     if (pr->normalize != 0 && (pr->p % 2) != 0) return PA_ERR_INVALID_ARG;  // scores must be positive to normalise
     if (pr->dtype != PA_DTYPE_F32 && pr->dtype != PA_DTYPE_BF16) return PA_ERR_INVALID_ARG;
     if (pr->impl != PA_IMPL_AUTO && pr->impl != PA_IMPL_GENERIC && pr->impl != PA_IMPL_MFMA) return PA_ERR_INVALID_ARG;
@@ -43,11 +42,13 @@ pa_status validate(const pa_problem* pr) {
 int auto_chunk(const pa_problem& pr) {
     const bool may_mfma = pr.impl == PA_IMPL_AUTO || pr.impl == PA_IMPL_MFMA;
     pa_problem probe = pr;
-    probe.chunk = pr.T % 256 == 0 ? 256 : 128;
-    if (pr.T % 128 == 0 && may_mfma && mfma_supported(probe, true) == PA_OK)
-        return pr.T <= (pr.gated ? 2048 : 4096) ? pr.T : probe.chunk;
     probe.chunk = pr.T;
-    if (may_mfma && mfma_supported(probe, true) == PA_OK) return pr.T;
+    const bool attn = may_mfma && mfma_supported(probe, true) == PA_OK;
+    // the chunked kernels, on the sequence rounded up to whole chunks when it is ragged (see Padding)
+    probe.chunk = pr.T % 256 == 0 || pr.T % 128 != 0 ? 256 : 128;
+    probe.T = (pr.T + probe.chunk - 1) / probe.chunk * probe.chunk;
+    if (may_mfma && mfma_supported(probe, true) == PA_OK && !(attn && pr.T <= (pr.gated ? 2048 : 4096))) return probe.chunk;
+    if (attn) return pr.T;
     double D = 1.0;   // C(d + p - 1, p)
     for (int i = 1; i <= pr.p; ++i) D = D * (pr.d + pr.p - i) / i;
     if (0.5 * pr.T * (4.0 * pr.d + 2.0) <= 4.0 * D * (pr.v + 1)) return pr.T;
@@ -78,6 +79,62 @@ int choose(const pa_problem& pr, bool backward, pa_status* why) {
     return -1;
 }
 
+// ---- sequences that are not a multiple of the chunk -----------------------------------------------
+// The chunked MFMA kernels work on whole chunks.  A ragged sequence is run as the next longer one:
+// Q, K, V (dO, O, Z, log-gates) are copied into the workspace with zero rows appended - zero keys and
+// values add nothing to any state or sum, zero upstream gradients and gates of one (log 0) neither -
+// and the first T rows of the results are copied back.  Costs one pass over every operand.
+struct Padding {
+    bool on = false;
+    pa_problem prob;        // the problem the kernels see (T rounded up)
+    size_t tok = 0, vec = 0;   // bytes of one padded [B,H,T,d] operand and of one padded [B,H,T] float array
+};
+
+Padding padding_for(const pa_problem& pr) {
+    Padding pd;
+    pd.prob = pr;
+    if (pr.chunk <= 0 || pr.T % pr.chunk == 0) return pd;
+    pd.on = true;
+    pd.prob.T = (pr.T + pr.chunk - 1) / pr.chunk * pr.chunk;
+    const size_t rows = (size_t)pr.B * pr.H * pd.prob.T;
+    pd.tok = align_up(rows * pr.d * (pr.dtype == PA_DTYPE_BF16 ? 2 : 4), 256);
+    pd.vec = align_up(rows * sizeof(float), 256);
+    return pd;
+}
+size_t padding_bytes(const Padding& pd, bool backward) {
+    if (!pd.on) return 0;
+    const size_t ntok = backward ? 8 : 4, nvec = (backward ? 1 : 1) + (pd.prob.gated ? (backward ? 2 : 1) : 0);
+    return ntok * pd.tok + nvec * pd.vec;
+}
+
+// rows of `elems` elements: out [BH][T_out][elems] <- in [BH][T_in][elems], zero where t >= T_in
+template <typename E>
+__global__ __launch_bounds__(256) void k_copy_rows(const E* __restrict__ in, E* __restrict__ out, long long total, int T_in,
+                                                   int T_out, int elems) {
+    const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    const int e = (int)(i % elems);
+    const long long r = i / elems;
+    const int t = (int)(r % T_out);
+    const long long bh = r / T_out;
+    E zero{};
+    out[i] = t < T_in ? in[(bh * T_in + t) * elems + e] : zero;
+}
+// bytes_per_row: 4 for the per-token float arrays, d * element size for the operands (a multiple of 16 there)
+bool copy_rows(hipStream_t s, const void* in, void* out, size_t BH, int T_in, int T_out, int bytes_per_row) {
+    LaunchScope ls("pad_rows", s);
+    if (bytes_per_row % 16 == 0) {
+        const long long total = (long long)BH * T_out * (bytes_per_row / 16);
+        hipLaunchKernelGGL((k_copy_rows<uint4>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, (const uint4*)in,
+                           (uint4*)out, total, T_in, T_out, bytes_per_row / 16);
+    } else {
+        const long long total = (long long)BH * T_out * (bytes_per_row / 4);
+        hipLaunchKernelGGL((k_copy_rows<float>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, (const float*)in,
+                           (float*)out, total, T_in, T_out, bytes_per_row / 4);
+    }
+    return launch_ok();
+}
+
 // workspace of the kernel family, rounded so that the gating buffers can follow it
 size_t family_bytes(int impl, const pa_problem& pr, bool backward) {
     return align_up(impl == PA_IMPL_MFMA ? mfma_workspace_bytes(pr, backward) : generic_workspace_bytes(pr, backward), 256);
@@ -89,22 +146,52 @@ pa_status run_fwd(const pa_problem* prob, const void* Q, const void* K, const vo
     if (st != PA_OK) return st;
     if (prob->gated != gated) return PA_ERR_INVALID_ARG;
     if (Q == nullptr || K == nullptr || V == nullptr || O == nullptr || (gated && log_g == nullptr)) return PA_ERR_INVALID_ARG;
-    const pa_problem pr_ = resolved(prob);
-    prob = &pr_;
+    const pa_problem asked = resolved(prob);
+    const Padding pd = padding_for(asked);
+    prob = &pd.prob;
     pa_status why = PA_ERR_UNSUPPORTED;
     int impl = choose(*prob, false, &why);
     if (impl < 0) return why;
+    if (pd.on && impl != PA_IMPL_MFMA) return PA_ERR_UNSUPPORTED;     // only the MFMA kernels run padded
     const size_t fam = family_bytes(impl, *prob, false);
-    const size_t need = fam + gate_workspace_bytes(*prob, false);
+    const size_t inner = fam + gate_workspace_bytes(*prob, false);
+    const size_t need = inner + padding_bytes(pd, false);
     if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return PA_ERR_WORKSPACE;
     if (((uintptr_t)workspace & 255u) != 0) return PA_ERR_WORKSPACE;
     (void)hipGetLastError();  // errors left behind by earlier, unrelated runtime calls are not ours
-    Ctx c{*prob, (hipStream_t)hip_stream, (char*)workspace, workspace_bytes, gate_buffers(*prob, false, (char*)workspace + fam)};
+    hipStream_t s = (hipStream_t)hip_stream;
+    void* Zout = Z;
+    void* Oout = O;
+    if (pd.on) {
+        char* base = (char*)workspace + inner;
+        const size_t BH = (size_t)asked.B * asked.H;
+        const int row = asked.d * 2;
+        void *Qp = base, *Kp = base + pd.tok, *Vp = base + 2 * pd.tok;
+        if (!copy_rows(s, Q, Qp, BH, asked.T, prob->T, row) || !copy_rows(s, K, Kp, BH, asked.T, prob->T, row) ||
+            !copy_rows(s, V, Vp, BH, asked.T, prob->T, row))
+            return PA_ERR_HIP;
+        Q = Qp;
+        K = Kp;
+        V = Vp;
+        O = base + 3 * pd.tok;
+        Z = (float*)(base + 4 * pd.tok);
+        if (gated) {
+            float* lp = (float*)(base + 4 * pd.tok + pd.vec);
+            if (!copy_rows(s, log_g, lp, BH, asked.T, prob->T, 4)) return PA_ERR_HIP;
+            log_g = lp;
+        }
+    }
+    Ctx c{*prob, s, (char*)workspace, workspace_bytes, gate_buffers(*prob, false, (char*)workspace + fam)};
     if (gated) {
         st = gate_prepare(c, log_g);
         if (st != PA_OK) return st;
     }
-    return impl == PA_IMPL_MFMA ? mfma_fwd(c, Q, K, V, O, Z) : generic_fwd(c, Q, K, V, O, Z);
+    st = impl == PA_IMPL_MFMA ? mfma_fwd(c, Q, K, V, O, Z) : generic_fwd(c, Q, K, V, O, Z);
+    if (st != PA_OK || !pd.on) return st;
+    const size_t BH = (size_t)asked.B * asked.H;
+    if (!copy_rows(s, O, Oout, BH, prob->T, asked.T, asked.v * 2)) return PA_ERR_HIP;
+    if (Zout != nullptr && !copy_rows(s, Z, Zout, BH, prob->T, asked.T, 4)) return PA_ERR_HIP;
+    return PA_OK;
 }
 
 pa_status run_bwd(const pa_problem* prob, const void* Q, const void* K, const void* V, const float* log_g, const void* O,
@@ -117,26 +204,67 @@ pa_status run_bwd(const pa_problem* prob, const void* Q, const void* K, const vo
         return PA_ERR_INVALID_ARG;
     if (gated && (log_g == nullptr || dlog_g == nullptr)) return PA_ERR_INVALID_ARG;
     if (prob->normalize != 0 && (O == nullptr || Z == nullptr)) return PA_ERR_INVALID_ARG;
-    const pa_problem pr_ = resolved(prob);
-    prob = &pr_;
+    const pa_problem asked = resolved(prob);
+    const Padding pd = padding_for(asked);
+    prob = &pd.prob;
     pa_status why = PA_ERR_UNSUPPORTED;
     int impl = choose(*prob, true, &why);
     if (impl < 0) return why;
+    if (pd.on && impl != PA_IMPL_MFMA) return PA_ERR_UNSUPPORTED;
     const size_t fam = family_bytes(impl, *prob, true);
-    const size_t need = fam + gate_workspace_bytes(*prob, true);
+    const size_t inner = fam + gate_workspace_bytes(*prob, true);
+    const size_t need = inner + padding_bytes(pd, true);
     if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return PA_ERR_WORKSPACE;
     if (((uintptr_t)workspace & 255u) != 0) return PA_ERR_WORKSPACE;
     (void)hipGetLastError();
-    Ctx c{*prob, (hipStream_t)hip_stream, (char*)workspace, workspace_bytes, gate_buffers(*prob, true, (char*)workspace + fam)};
+    hipStream_t s = (hipStream_t)hip_stream;
+    const size_t BH = (size_t)asked.B * asked.H;
+    void *dQout = dQ, *dKout = dK, *dVout = dV;
+    float* dlout = dlog_g;
+    if (pd.on) {
+        char* base = (char*)workspace + inner;
+        const int row = asked.d * 2;
+        void* buf[8];
+        for (int i = 0; i < 8; ++i) buf[i] = base + i * pd.tok;
+        float* Zp = (float*)(base + 8 * pd.tok);
+        if (!copy_rows(s, Q, buf[0], BH, asked.T, prob->T, row) || !copy_rows(s, K, buf[1], BH, asked.T, prob->T, row) ||
+            !copy_rows(s, V, buf[2], BH, asked.T, prob->T, row) || !copy_rows(s, dO, buf[3], BH, asked.T, prob->T, row))
+            return PA_ERR_HIP;
+        if (O != nullptr && !copy_rows(s, O, buf[4], BH, asked.T, prob->T, row)) return PA_ERR_HIP;
+        if (Z != nullptr && !copy_rows(s, Z, Zp, BH, asked.T, prob->T, 4)) return PA_ERR_HIP;
+        Q = buf[0];
+        K = buf[1];
+        V = buf[2];
+        dO = buf[3];
+        if (O != nullptr) O = buf[4];
+        if (Z != nullptr) Z = Zp;
+        dQ = buf[5];
+        dK = buf[6];
+        dV = buf[7];
+        if (gated) {
+            float* lp = (float*)(base + 8 * pd.tok + pd.vec);
+            if (!copy_rows(s, log_g, lp, BH, asked.T, prob->T, 4)) return PA_ERR_HIP;
+            log_g = lp;
+            dlog_g = lp + pd.vec / sizeof(float);
+        }
+    }
+    Ctx c{*prob, s, (char*)workspace, workspace_bytes, gate_buffers(*prob, true, (char*)workspace + fam)};
     if (gated) {
         // the factors are rebuilt here: the forward pass keeps its own copy only inside its workspace
         st = gate_prepare(c, log_g);
         if (st != PA_OK) return st;
     }
     st = impl == PA_IMPL_MFMA ? mfma_bwd(c, Q, K, V, O, Z, dO, dQ, dK, dV) : generic_bwd(c, Q, K, V, O, Z, dO, dQ, dK, dV);
-    if (st != PA_OK || !gated) return st;
-    return gate_gradient(c, Q, K, dQ, dK, dlog_g, impl == PA_IMPL_MFMA,
-                         impl == PA_IMPL_MFMA ? mfma_gate_fin_chunk(*prob) : prob->chunk);
+    if (st == PA_OK && gated)
+        st = gate_gradient(c, Q, K, dQ, dK, dlog_g, impl == PA_IMPL_MFMA,
+                           impl == PA_IMPL_MFMA ? mfma_gate_fin_chunk(*prob) : prob->chunk);
+    if (st != PA_OK || !pd.on) return st;
+    const int row = asked.d * 2;
+    if (!copy_rows(s, dQ, dQout, BH, prob->T, asked.T, row) || !copy_rows(s, dK, dKout, BH, prob->T, asked.T, row) ||
+        !copy_rows(s, dV, dVout, BH, prob->T, asked.T, row))
+        return PA_ERR_HIP;
+    if (gated && !copy_rows(s, dlog_g, dlout, BH, prob->T, asked.T, 4)) return PA_ERR_HIP;
+    return PA_OK;
 }
 
 }  // namespace
@@ -186,27 +314,30 @@ const char* power_attn_status_string(pa_status s) {
 pa_status power_attn_supported(const pa_problem* prob, int for_backward) {
     pa_status st = validate(prob);
     if (st != PA_OK) return st;
-    const pa_problem pr_ = resolved(prob);
+    const Padding pd = padding_for(resolved(prob));
     pa_status why = PA_ERR_UNSUPPORTED;
-    return choose(pr_, for_backward != 0, &why) < 0 ? why : PA_OK;
+    const int impl = choose(pd.prob, for_backward != 0, &why);
+    if (impl < 0) return why;
+    return pd.on && impl != PA_IMPL_MFMA ? PA_ERR_UNSUPPORTED : PA_OK;
 }
 
 size_t power_attn_workspace_bytes(const pa_problem* prob, int for_backward) {
     if (validate(prob) != PA_OK) return 0;
-    const pa_problem pr_ = resolved(prob);
+    const Padding pd = padding_for(resolved(prob));
     pa_status why;
-    int impl = choose(pr_, for_backward != 0, &why);
-    if (impl < 0) return 0;
-    return family_bytes(impl, pr_, for_backward != 0) + gate_workspace_bytes(pr_, for_backward != 0);
+    int impl = choose(pd.prob, for_backward != 0, &why);
+    if (impl < 0 || (pd.on && impl != PA_IMPL_MFMA)) return 0;
+    return family_bytes(impl, pd.prob, for_backward != 0) + gate_workspace_bytes(pd.prob, for_backward != 0) +
+           padding_bytes(pd, for_backward != 0);
 }
 
 long long power_attn_state_rows(const pa_problem* prob) {
     if (validate(prob) != PA_OK) return 0;
-    const pa_problem pr_ = resolved(prob);
+    const Padding pd = padding_for(resolved(prob));
     pa_status why;
-    int impl = choose(pr_, false, &why);
-    if (impl < 0) return 0;
-    return impl == PA_IMPL_MFMA ? mfma_state_rows(pr_) : generic_state_rows(pr_);
+    int impl = choose(pd.prob, false, &why);
+    if (impl < 0 || (pd.on && impl != PA_IMPL_MFMA)) return 0;
+    return impl == PA_IMPL_MFMA ? mfma_state_rows(pd.prob) : generic_state_rows(pd.prob);
 }
 
 // the fields a decode step reads, checked like the same fields of the other calls

@@ -114,3 +114,51 @@ def test_mfma_zero_rows():
     dQ, dK, dV = orc.bwd_bhtd(Q, K, V, G, 2, None, True, 1.0)
     assert_close(got, dict(O=O, Z=Z, dQ=dQ, dK=dK, dV=dV), "bf16", "mfma zero rows")
     assert (got["O"][0, 0, 5] == 0).all() and (got["dQ"][0, 0, 5] == 0).all()
+
+
+RAGGED_CASES = [
+    # B, H, T, chunk, normalize, gated
+    (1, 2, 300, 128, True, False),       # 2 whole chunks + 44 tokens
+    (2, 1, 517, 256, True, False),
+    (1, 1, 129, 128, False, False),      # one token beyond a chunk
+    (1, 2, 400, 128, True, True),
+    (1, 1, 100, 128, True, False),       # shorter than one chunk
+]
+
+
+@pytest.mark.parametrize("keep_state", [False, True], ids=["recompute", "keep_state"])
+@pytest.mark.parametrize("case", RAGGED_CASES, ids=lambda c: "-".join(str(x) for x in c))
+def test_mfma_ragged_last_chunk(case, keep_state):
+    """A sequence that is not a multiple of the chunk: the chunked kernels run it padded with zero
+    rows; every output of the T real tokens against the oracle."""
+    B, H, T, chunk, normalize, gated = case
+    print("case", case, "keep_state", keep_state, flush=True)
+    Q, K, V, G = inputs.make_qkvg(B, H, T, 64, seed=5100 + RAGGED_CASES.index(case), dtype="bf16")
+    lg = inputs.make_log_gates(B, H, T, 5150 + RAGGED_CASES.index(case), 0.03) if gated else None
+    got = run_fwd_bwd(Q, K, V, G, 2, chunk, "bf16", normalize, 1.0, impl="mfma", keep_state=keep_state, log_g=lg)
+    O, Z = orc.fwd_bhtd(Q, K, V, 2, None, normalize, 1.0, log_g=lg)
+    ref = orc.bwd_bhtd(Q, K, V, G, 2, None, normalize, 1.0, log_g=lg)
+    want = dict(O=O, Z=Z, dQ=ref[0], dK=ref[1], dV=ref[2])
+    if gated:
+        want["dlog_g"] = ref[3]
+    for k, a in got.items():
+        assert a.shape[2] == T, k
+    assert_close(got, want, "bf16", f"mfma ragged {case}")
+
+
+def test_automatic_chunk_on_a_long_ragged_sequence():
+    """chunk = 0 at a length that no chunk divides and that is too long for the attention form: the chunked
+    kernels on the padded sequence; sampled rows by the definition."""
+    from paper_2507_04239_amd import binding
+    T = 8192 + 37
+    prob = binding.make_problem(1, 1, T, 64, 64, 2, 0)
+    assert binding.power_attn_resolved_chunk(prob) == 256
+    Q, K, V, G = inputs.make_qkvg(1, 1, T, 64, seed=5200, dtype="bf16")
+    got = run_fwd_bwd(Q, K, V, G, 2, 0, "bf16")
+    q, k, v = (a[0, 0].astype(np.float64) for a in (Q, K, V))
+    rows = [0, 255, 256, 4096, 8191, 8192, T - 2, T - 1]
+    o_ref = np.stack([orc.fwd_row(q, k, v, i, 2)[0] for i in rows])
+    dq_ref = np.stack([orc.bwd_dq_row(q, k, v, G[0, 0].astype(np.float64), i, 2) for i in rows])
+    from gpu_util import TOL, rel_l2
+    assert rel_l2(got["O"][0, 0][rows], o_ref) <= TOL["bf16"]
+    assert rel_l2(got["dQ"][0, 0][rows], dq_ref) <= TOL["bf16"]

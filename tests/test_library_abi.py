@@ -37,9 +37,14 @@ def test_validation_and_sizes(lib):
     assert lib.power_attn_supported(ctypes.byref(ok), 1) == 0
     assert binding.power_attn_state_rows(ok) == 136
     assert binding.power_attn_workspace_bytes(ok, True) > binding.power_attn_workspace_bytes(ok, False) > 0
-    bad_chunk = binding.make_problem(1, 1, 256, 16, 16, 2, 48)
-    assert lib.power_attn_supported(ctypes.byref(bad_chunk), 0) == 1
-    assert binding.power_attn_workspace_bytes(bad_chunk, False) == 0
+    # a ragged last chunk is a valid request, but only the chunked matrix-core kernels take it
+    ragged = binding.make_problem(1, 1, 256, 16, 16, 2, 48)
+    assert lib.power_attn_supported(ctypes.byref(ragged), 0) == 2
+    assert binding.power_attn_workspace_bytes(ragged, False) == 0
+    ragged_mfma = binding.make_problem(1, 2, 300, 64, 64, 2, 128)
+    assert lib.power_attn_supported(ctypes.byref(ragged_mfma), 1) == 0
+    whole = binding.make_problem(1, 2, 384, 64, 64, 2, 128)
+    assert binding.power_attn_workspace_bytes(ragged_mfma, True) > binding.power_attn_workspace_bytes(whole, True) > 0
     odd_p = binding.make_problem(1, 1, 256, 16, 16, 3, 32, normalize=True)
     assert lib.power_attn_supported(ctypes.byref(odd_p), 0) == 1
     odd_p_unnorm = binding.make_problem(1, 1, 256, 16, 16, 3, 32, normalize=False)
@@ -70,6 +75,8 @@ def test_automatic_chunk_choice():
     assert rc(mk(1, 12, 65536, 64, 64, 2, 128)) == 128
     assert rc(mk(1, 12, 65536, 64, 64, 2, 0)) == 256          # bf16, p = 2, d = 64: measured best chunk
     assert rc(mk(1, 12, 65536 + 128, 64, 64, 2, 0)) == 128    # 256 does not divide T
+    assert rc(mk(1, 12, 65536 + 5, 64, 64, 2, 0)) == 256      # ragged: chunked all the same, the sequence is padded
+    assert rc(mk(1, 12, 3000, 64, 64, 2, 0)) == 3000          # short and ragged: attention form, any length
     assert rc(mk(4, 12, 4096, 64, 64, 2, 0)) == 4096          # short: attention form
     assert rc(mk(4, 12, 8192, 64, 64, 2, 0)) == 256
     assert rc(mk(4, 12, 4096, 64, 64, 2, 0, gated=True)) == 256
@@ -87,7 +94,9 @@ def test_automatic_chunk_choice():
     assert rc(mk(1, 1, 4000, 16, 16, 2, 0, dtype="f32")) == 32   # largest power of two <= 128 dividing T
     assert binding.power_attn_workspace_bytes(mk(1, 12, 65536, 64, 64, 2, 0), False) == \
         binding.power_attn_workspace_bytes(mk(1, 12, 65536, 64, 64, 2, 256), False)
-    assert rc(mk(1, 1, 100, 16, 16, 2, 7)) == 0                  # invalid: 7 does not divide 100
+    assert rc(mk(1, 1, 100, 16, 16, 2, 7)) == 7                  # an explicit chunk is returned as it is ...
+    assert not binding.power_attn_supported(mk(1, 1, 100, 16, 16, 2, 7), False)   # ... supported or not
+    assert rc(mk(1, 1, 100, 16, 16, 2, -1)) == 0                 # invalid
 
 
 def test_support_matrix_host_logic():
