@@ -152,9 +152,15 @@ size_t power_attn_decode_state_bytes(const pa_problem* prob);     /* 0 if the pr
 pa_status power_attn_decode_init(const pa_problem* prob, void* state, size_t state_bytes, void* hip_stream);
 /* The hand-over from a prompt: updates `state` as prob->T decode steps on K [B, H, T, d], V [B, H, T, v]
  * (log_g [B, H, T] when prob->gated, else NULL) would, without producing their outputs - those are
- * what power_attn_fwd returns for the prompt.  May be called on a state that already holds tokens. */
+ * what power_attn_fwd returns for the prompt.  May be called on a state that already holds tokens.
+ * workspace (DEVICE, 256-byte aligned, may be NULL): with power_attn_decode_absorb_workspace_bytes(prob)
+ * bytes of it (0 = no such path for this problem: bf16, p = 2, d = v = 64, T a multiple of 128 have one)
+ * the prompt goes through the matrix-core state scan, some 20x faster, its sums rounded to bf16 once
+ * as the chunk states of power_attn_fwd are; without, through a float32 kernel on the vector ALUs. */
+size_t power_attn_decode_absorb_workspace_bytes(const pa_problem* prob);
 pa_status power_attn_decode_absorb(const pa_problem* prob, const void* K, const void* V, const float* log_g,
-                                   void* state, size_t state_bytes, void* hip_stream);
+                                   void* state, size_t state_bytes, void* workspace, size_t workspace_bytes,
+                                   void* hip_stream);
 pa_status power_attn_decode_step(const pa_problem* prob, const void* q, const void* k, const void* v,
                                  const float* log_g, void* state, size_t state_bytes,
                                  void* o, float* z, void* hip_stream);

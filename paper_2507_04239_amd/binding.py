@@ -23,6 +23,7 @@ EXPORTED_SYMBOLS = (
     "power_attn_decode_state_bytes",
     "power_attn_decode_init",
     "power_attn_decode_absorb",
+    "power_attn_decode_absorb_workspace_bytes",
     "power_attn_decode_step",
     "power_attn_fwd",
     "power_attn_bwd",
@@ -88,7 +89,9 @@ def load_library():
     lib.power_attn_decode_init.restype = ctypes.c_int
     lib.power_attn_decode_init.argtypes = [P, vp, ctypes.c_size_t, vp]
     lib.power_attn_decode_absorb.restype = ctypes.c_int
-    lib.power_attn_decode_absorb.argtypes = [P, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.power_attn_decode_absorb.argtypes = [P, vp, vp, vp, vp, ctypes.c_size_t, vp, ctypes.c_size_t, vp]
+    lib.power_attn_decode_absorb_workspace_bytes.restype = ctypes.c_size_t
+    lib.power_attn_decode_absorb_workspace_bytes.argtypes = [P]
     lib.power_attn_decode_step.restype = ctypes.c_int
     lib.power_attn_decode_step.argtypes = [P, vp, vp, vp, vp, vp, ctypes.c_size_t, vp, vp, vp]
     lib.power_attn_fwd.restype = ctypes.c_int
@@ -286,13 +289,22 @@ def power_attn_decode_init(prob: PaProblem, state=None):
     return state
 
 
-def power_attn_decode_absorb(prob: PaProblem, K, V, state, log_g=None):
+def power_attn_decode_absorb_workspace_bytes(prob: PaProblem) -> int:
+    return int(load_library().power_attn_decode_absorb_workspace_bytes(ctypes.byref(prob)))
+
+
+def power_attn_decode_absorb(prob: PaProblem, K, V, state, log_g=None, fast: bool = True):
     """Feeds the prompt K [B, H, T, d], V [B, H, T, v] (prob.T = T) into the state, as T decode steps
-    would, without outputs."""
+    would, without outputs.  fast: give the library the workspace its matrix-core path asks for, where
+    it has one (sums rounded to bf16 once); else the float32 kernel runs."""
+    import torch
     lib = load_library()
     lg = None if log_g is None else _dev_ptr(log_g, name="log_g")
+    need = int(lib.power_attn_decode_absorb_workspace_bytes(ctypes.byref(prob))) if fast else 0
+    ws = torch.empty(need, dtype=torch.uint8, device=K.device) if need > 0 else None
     _check(lib, lib.power_attn_decode_absorb(ctypes.byref(prob), _dev_ptr(K, name="K"), _dev_ptr(V, K, "V"), lg,
-                                             _dev_ptr(state, name="state"), state.numel(), _stream()),
+                                             _dev_ptr(state, name="state"), state.numel(),
+                                             None if ws is None else _dev_ptr(ws, name="workspace"), need, _stream()),
            "power_attn_decode_absorb")
     return state
 

@@ -98,7 +98,9 @@ bool build_monomial_table(hipStream_t s, int d, int p, long long D, void* idx, f
 // single-token decode step (state resident between calls)
 size_t decode_state_bytes(const pa_problem& pr);
 pa_status decode_init(const pa_problem& pr, void* state, hipStream_t s);
-pa_status decode_absorb(const pa_problem& pr, const void* K, const void* V, const float* log_g, void* state, hipStream_t s);
+size_t decode_absorb_workspace_bytes(const pa_problem& pr);
+pa_status decode_absorb(const pa_problem& pr, const void* K, const void* V, const float* log_g, void* state, void* ws,
+                        size_t ws_bytes, hipStream_t s);
 pa_status decode_step(const pa_problem& pr, const void* q, const void* k, const void* v, const float* log_g, void* state, void* o,
                       float* z, hipStream_t s);
 pa_status generic_supported(const pa_problem& pr);
@@ -113,6 +115,12 @@ pa_status mfma_supported(const pa_problem& pr, bool backward);
 pa_status mfma_fwd(const Ctx& c, const void* Q, const void* K, const void* V, void* O, float* Z);
 pa_status mfma_bwd(const Ctx& c, const void* Q, const void* K, const void* V, const void* O, const float* Z,
                    const void* dO, void* dQ, void* dK, void* dV);
+// A prompt K, V [B,H,T,d] (pr.T tokens) added into a decode state (S [BH][D][v], gamd [BH][D], float32, D rows in the
+// monomial basis of the decode step) by way of the state scan; bf16, p = 2, d = v = 64, T a multiple of 128
+bool mfma_absorb_supported(const pa_problem& pr);
+size_t mfma_absorb_workspace_bytes(const pa_problem& pr);
+pa_status mfma_absorb(const pa_problem& pr, const void* K, const void* V, const float* log_g, char* ws, hipStream_t s, float* S,
+                      float* gamd, int D);
 // tokens per entry of GateBuf::xb as mfma_bwd leaves it (gated problems)
 int mfma_gate_fin_chunk(const pa_problem& pr);
 

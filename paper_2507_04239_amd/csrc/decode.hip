@@ -369,10 +369,20 @@ bool launch_absorb_p(const pa_problem& pr, const DecodeLayout& L, const void* K,
 
 }  // namespace
 
-pa_status decode_absorb(const pa_problem& pr, const void* K, const void* V, const float* log_g, void* state, hipStream_t s) {
+size_t decode_absorb_workspace_bytes(const pa_problem& pr) {
+    return decode_supported(pr) == PA_OK ? mfma_absorb_workspace_bytes(pr) : 0;
+}
+
+// With a workspace, and where the matrix-core scan applies, the prompt goes through that (the sums are then
+// rounded to bf16 once, like the chunk states of the forward pass); else through the float32 kernel above.
+pa_status decode_absorb(const pa_problem& pr, const void* K, const void* V, const float* log_g, void* state, void* ws,
+                        size_t ws_bytes, hipStream_t s) {
     pa_status st = decode_supported(pr);
     if (st != PA_OK) return st;
     const DecodeLayout L = make_decode_layout(pr);
+    if (ws != nullptr && mfma_absorb_supported(pr) && ws_bytes >= mfma_absorb_workspace_bytes(pr))
+        return mfma_absorb(pr, K, V, log_g, (char*)ws, s, (float*)((char*)state + L.off_s), (float*)((char*)state + L.off_gam),
+                           (int)L.D);
     const bool ok = pr.dtype == PA_DTYPE_F32 ? launch_absorb_p<float>(pr, L, K, V, log_g, (char*)state, s)
                                              : launch_absorb_p<bf16_t>(pr, L, K, V, log_g, (char*)state, s);
     return ok ? PA_OK : PA_ERR_HIP;

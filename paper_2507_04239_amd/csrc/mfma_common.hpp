@@ -72,7 +72,8 @@ __device__ __forceinline__ void vm_wait() {
 // ---- launchers (each defined next to its kernels) ------------------------------------------
 // feature-major copy in blocks of 64 tokens: [BH][T][DH] -> [BH][T/64][DH][64]
 // fac (may be null): per-token factors; the copy is then of x_t * sqrt(fac_t)
-bool launch_transpose(hipStream_t s, const bf16_t* in, bf16_t* out, int BH, int T, const float* fac = nullptr);
+// out_T (0: T): tokens per head the output buffer is laid out for
+bool launch_transpose(hipStream_t s, const bf16_t* in, bf16_t* out, int BH, int T, const float* fac = nullptr, int out_T = 0);
 // state scan; rev = 0: S_n from (Kt, Vt); rev = 1: R_m from (Qt, Ght) with the weights gz.
 // gam receives Gamma (rev = 0) or Omega (rev = 1).
 bool launch_scan(const char* name, hipStream_t s, bool rev, const bf16_t* Xt, const bf16_t* Yt, const float* wgt, bf16_t* stC,

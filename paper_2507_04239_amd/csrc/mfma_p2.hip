@@ -233,4 +233,101 @@ pa_status mfma_bwd(const Ctx& c, const void* Q, const void* K, const void* V, co
     return PA_OK;
 }
 
+// ---- a prompt into a decode state, through the state scan ----------------------------------------------
+// The sum the decode state needs is what the forward scan accumulates.  The prompt is scanned as the first
+// of two chunks of its own length (the second is never read): the state "before chunk 1" is the sum over
+// the whole prompt, written once, in bf16 tiles.  A small kernel then adds it, in the decode step's basis
+// (monomials x_i x_j, i <= j, multiplicity on the state), to the float32 decode state: off-diagonal tiles
+// map one to one, a diagonal tile holds (a, b) and (b, a) of one monomial.  Gates: keys scaled by the square
+// root of their decay to the end of the prompt (one chunk, so no per-chunk decay), the old state by the
+// decay across the whole prompt.
+namespace {
+
+struct AbsorbLayout {
+    size_t off_kt, off_vt, off_sc, off_gam, off_gate, total;
+};
+AbsorbLayout make_absorb_layout(const pa_problem& pr) {
+    AbsorbLayout L{};
+    const size_t BH = (size_t)pr.B * pr.H;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        size_t o = off;
+        off = align_up(off + bytes, 256);
+        return o;
+    };
+    L.off_kt = take(BH * 2 * pr.T * DH * 2);
+    L.off_vt = take(BH * 2 * pr.T * DH * 2);
+    L.off_sc = take(BH * 2 * (size_t)STATE_ELEMS * 2);
+    L.off_gam = take(BH * 2 * (size_t)DH * DH * 2);
+    L.off_gate = off;
+    pa_problem gp = pr;
+    gp.chunk = pr.T;
+    L.total = off + gate_workspace_bytes(gp, false);
+    return L;
+}
+
+__global__ __launch_bounds__(256) void k_absorb_convert(const bf16_t* __restrict__ StC, const bf16_t* __restrict__ Gam,
+                                                        const float* __restrict__ lam, float* __restrict__ S,
+                                                        float* __restrict__ gamd, int D) {
+    const int bh = blockIdx.y;
+    const int idx = blockIdx.x * 256 + threadIdx.x;          // (row r, column c), c == DH: the normaliser column
+    if (idx >= D * (DH + 1)) return;
+    const int r = idx / (DH + 1), c = idx % (DH + 1);
+    int i = 0, rem = r;
+    while (rem >= DH - i) {
+        rem -= DH - i;
+        ++i;
+    }
+    const int j = i + rem;
+    const float decay = lam != nullptr ? lam[bh] : 1.f;
+    if (c == DH) {
+        const float g = bf16_to_f32(Gam[((size_t)bh * 2 + 1) * DH * DH + (size_t)j * DH + i]);
+        float* dst = gamd + (size_t)bh * D + r;
+        *dst = decay * *dst + (i == j ? g : 2.f * g);
+        return;
+    }
+    const int ti = i >> 3, a = i & 7, tj = j >> 3, b = j & 7;
+    const bf16_t* tile = StC + (((size_t)bh * 2 + 1) * NTILES + (tj * (tj + 1) / 2 + ti)) * TILE_ELEMS;
+    float x = bf16_to_f32(tile[(a * DH + c) * 8 + b]);
+    if (ti == tj && a != b) x += bf16_to_f32(tile[(b * DH + c) * 8 + a]);
+    float* dst = S + ((size_t)bh * D + r) * DH + c;
+    *dst = decay * *dst + x;
+}
+
+}  // namespace
+
+bool mfma_absorb_supported(const pa_problem& pr) {
+    return pr.dtype == PA_DTYPE_BF16 && pr.p == 2 && pr.d == DH && pr.v == DH && pr.T % QBLK == 0 &&
+           (size_t)pr.B * pr.H <= 65535u;
+}
+size_t mfma_absorb_workspace_bytes(const pa_problem& pr) { return mfma_absorb_supported(pr) ? make_absorb_layout(pr).total : 0; }
+
+pa_status mfma_absorb(const pa_problem& pr, const void* K, const void* V, const float* log_g, char* ws, hipStream_t s, float* S,
+                      float* gamd, int D) {
+    const AbsorbLayout L = make_absorb_layout(pr);
+    const int BH = pr.B * pr.H;
+    bf16_t* Kt = (bf16_t*)(ws + L.off_kt);
+    bf16_t* Vt = (bf16_t*)(ws + L.off_vt);
+    bf16_t* Sc = (bf16_t*)(ws + L.off_sc);
+    bf16_t* Gam = (bf16_t*)(ws + L.off_gam);
+    const float *kfac = nullptr, *lam = nullptr;
+    if (log_g != nullptr) {
+        pa_problem gp = pr;
+        gp.chunk = pr.T;
+        gp.gated = 1;
+        Ctx c{gp, s, ws, L.total, gate_buffers(gp, false, ws + L.off_gate)};
+        pa_status st = gate_prepare(c, log_g);
+        if (st != PA_OK) return st;
+        kfac = c.gate.kfac;
+        lam = c.gate.lam;
+    }
+    PA_TRY(launch_transpose(s, (const bf16_t*)K, Kt, BH, pr.T, kfac, 2 * pr.T))
+    PA_TRY(launch_transpose(s, (const bf16_t*)V, Vt, BH, pr.T, nullptr, 2 * pr.T))
+    PA_TRY(launch_scan("decode_absorb_scan", s, false, Kt, Vt, nullptr, Sc, Gam, BH, 2 * pr.T, pr.T, 1.0f, nullptr))
+    LaunchScope ls("decode_absorb_convert", s);
+    hipLaunchKernelGGL(k_absorb_convert, dim3((D * (DH + 1) + 255) / 256, BH), dim3(256), 0, s, (const bf16_t*)Sc,
+                       (const bf16_t*)Gam, lam, S, gamd, D);
+    return launch_ok() ? PA_OK : PA_ERR_HIP;
+}
+
 }  // namespace pa

@@ -23,7 +23,7 @@ namespace {
 // weight w on phi(x) is the same as sqrt(w) on x, so the scans of a gated problem read copies
 // scaled this way and need no per-token weights of their own.
 __global__ __launch_bounds__(256) void k_transpose(const bf16_t* __restrict__ in, bf16_t* __restrict__ out, int T,
-                                                   const float* __restrict__ fac) {
+                                                   const float* __restrict__ fac, int out_blocks) {
     __shared__ bf16_t tile[TBLK][DH + 2];
     const int bh = blockIdx.y, blk = blockIdx.x, tid = threadIdx.x;
     const bf16_t* src = in + ((size_t)bh * T + (size_t)blk * TBLK) * DH;
@@ -34,7 +34,7 @@ __global__ __launch_bounds__(256) void k_transpose(const bf16_t* __restrict__ in
         for (int e = tid; e < TBLK * DH; e += 256) tile[e / DH][e % DH] = f32_to_bf16(bf16_to_f32(src[e]) * sqrtf(f[e / DH]));
     }
     __syncthreads();
-    bf16_t* dst = out + ((size_t)bh * (T / TBLK) + blk) * DH * TBLK;
+    bf16_t* dst = out + ((size_t)bh * out_blocks + blk) * DH * TBLK;
     for (int e = tid; e < TBLK * DH; e += 256) dst[e] = tile[e % TBLK][e / TBLK];
 }
 
@@ -410,9 +410,9 @@ static bool allow_smem(F* fn, size_t bytes) {
     return e == hipSuccess;
 }
 
-bool launch_transpose(hipStream_t s, const bf16_t* in, bf16_t* out, int BH, int T, const float* fac) {
+bool launch_transpose(hipStream_t s, const bf16_t* in, bf16_t* out, int BH, int T, const float* fac, int out_T) {
     LaunchScope ls("mfma_transpose", s);
-    hipLaunchKernelGGL(k_transpose, dim3(T / TBLK, BH), dim3(256), 0, s, in, out, T, fac);
+    hipLaunchKernelGGL(k_transpose, dim3(T / TBLK, BH), dim3(256), 0, s, in, out, T, fac, (out_T > 0 ? out_T : T) / TBLK);
     return launch_ok();
 }
 

@@ -364,8 +364,12 @@ pa_status power_attn_decode_init(const pa_problem* prob, void* state, size_t sta
     return decode_init(*prob, state, (hipStream_t)hip_stream);
 }
 
+size_t power_attn_decode_absorb_workspace_bytes(const pa_problem* prob) {
+    return validate_decode(prob) == PA_OK && prob->T > 0 ? decode_absorb_workspace_bytes(*prob) : 0;
+}
+
 pa_status power_attn_decode_absorb(const pa_problem* prob, const void* K, const void* V, const float* log_g, void* state,
-                                   size_t state_bytes, void* hip_stream) {
+                                   size_t state_bytes, void* workspace, size_t workspace_bytes, void* hip_stream) {
     pa_status st = validate_decode(prob);
     if (st != PA_OK) return st;
     if (prob->T <= 0 || K == nullptr || V == nullptr) return PA_ERR_INVALID_ARG;
@@ -373,7 +377,8 @@ pa_status power_attn_decode_absorb(const pa_problem* prob, const void* K, const 
     const size_t need = decode_state_bytes(*prob);
     if (need == 0) return PA_ERR_UNSUPPORTED;
     if (state == nullptr || state_bytes < need) return PA_ERR_WORKSPACE;
-    return decode_absorb(*prob, K, V, log_g, state, (hipStream_t)hip_stream);
+    if (workspace != nullptr && ((uintptr_t)workspace & 255u) != 0) return PA_ERR_WORKSPACE;
+    return decode_absorb(*prob, K, V, log_g, state, workspace, workspace_bytes, (hipStream_t)hip_stream);
 }
 
 pa_status power_attn_decode_step(const pa_problem* prob, const void* q, const void* k, const void* v, const float* log_g,

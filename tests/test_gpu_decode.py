@@ -176,7 +176,53 @@ def test_absorbing_a_prompt_equals_stepping_through_it(case):
     assert ez <= TOL[dtype] and en <= TOL[dtype]
 
 
-def test_prefill_then_decode_continues_the_sequence():
+@pytest.mark.parametrize("gated", [False, True], ids=["plain", "gated"])
+def test_prompt_through_the_matrix_core_scan(gated):
+    """bf16, p = 2, d = 64, a prompt of a multiple of 128 tokens: with a workspace the hand-over runs the
+    state scan on the matrix cores.  Its sums are rounded to bf16 once (2^-9 per entry); state and next
+    decode step against the oracle, and against the float32 hand-over."""
+    import torch
+    B, H, T, d, p = 1, 3, 640, 64, 2
+    Q, K, V, _ = inputs.make_qkvg(B, H, T + 1, d, seed=8600 + int(gated), dtype="bf16", with_grad=False)
+    lg = inputs.make_log_gates(B, H, T + 1, 8610, 0.03) if gated else None
+    tq, tk, tv = (to_dev(a, "bf16") for a in (Q, K, V))
+    tl = None if lg is None else torch.from_numpy(np.ascontiguousarray(lg)).to("cuda:0")
+    prob = binding.make_problem(B, H, T, d, d, p, 1, True, 1.0, "bf16", "auto", False, gated)
+    prob1 = binding.make_problem(B, H, 1, d, d, p, 1, True, 1.0, "bf16", "auto", False, gated)
+    assert binding.power_attn_decode_absorb_workspace_bytes(prob) > 0
+    assert binding.power_attn_decode_absorb_workspace_bytes(binding.make_problem(B, H, T + 1, d, d, p, 1)) == 0
+    kk, vv = tk[:, :, :T].contiguous(), tv[:, :, :T].contiguous()
+    ll = None if tl is None else tl[:, :, :T].contiguous()
+    fast = binding.power_attn_decode_absorb(prob, kk, vv, binding.power_attn_decode_init(prob1), ll, fast=True)
+    slow = binding.power_attn_decode_absorb(prob, kk, vv, binding.power_attn_decode_init(prob1), ll, fast=False)
+    # a second prompt on top of the first: the old state decays across it
+    fast = binding.power_attn_decode_absorb(prob, kk, vv, fast, ll, fast=True)
+    slow = binding.power_attn_decode_absorb(prob, kk, vv, slow, ll, fast=False)
+    D = orc.dim_spow(d, p)
+    n_s = B * H * D * d
+    off_gam = ((n_s * 4 + 255) // 256 * 256) // 4
+    wf, wsl = fast.view(torch.float32), slow.view(torch.float32)
+    e_s = rel_l2(to_np(wf[:n_s]), to_np(wsl[:n_s]))
+    e_g = rel_l2(to_np(wf[off_gam: off_gam + B * H * D]), to_np(wsl[off_gam: off_gam + B * H * D]))
+    print(f"scan hand-over vs float32 hand-over: state={e_s:.2e} gamma={e_g:.2e}", flush=True)
+    assert e_s <= 5e-3 and e_g <= 5e-3
+    o, z = binding.power_attn_decode_step(prob1, tq[:, :, T].contiguous(), tk[:, :, T].contiguous(), tv[:, :, T].contiguous(), fast,
+                                          None if tl is None else tl[:, :, T].contiguous())
+    torch.cuda.synchronize()
+    o_ref, z_ref = np.zeros((B, H, d)), np.zeros((B, H))
+    for h in range(H):
+        S = orc.decode_state_init(d, d, p)
+        for rep in range(2):
+            for t in range(T):
+                S, _, _ = orc.decode_step(S, Q[0, h, t], K[0, h, t], V[0, h, t], p, True, 1.0, None if lg is None else lg[0, h, t])
+        _, o_ref[0, h], z_ref[0, h] = orc.decode_step(S, Q[0, h, T], K[0, h, T], V[0, h, T], p, True, 1.0,
+                                                      None if lg is None else lg[0, h, T])
+    assert rel_l2(to_np(z), z_ref) <= TOL["bf16"]
+    assert rel_l2(to_np(o) * to_np(z)[..., None], o_ref * z_ref[..., None]) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("fast", [False, True], ids=["float32", "scan"])
+def test_prefill_then_decode_continues_the_sequence(fast):
     """power_attn_fwd on a prompt, the prompt handed to a decode state, then decode steps: every
     decoded row equals the row power_attn_fwd returns for the longer sequence."""
     import torch
@@ -188,7 +234,7 @@ def test_prefill_then_decode_continues_the_sequence():
     prob_prompt = binding.make_problem(B, H, T, d, d, 2, 1, True, 1.0, "bf16")
     prob1 = binding.make_problem(B, H, 1, d, d, 2, 1, True, 1.0, "bf16")
     state = binding.power_attn_decode_init(prob1)
-    binding.power_attn_decode_absorb(prob_prompt, tk[:, :, :T].contiguous(), tv[:, :, :T].contiguous(), state)
+    binding.power_attn_decode_absorb(prob_prompt, tk[:, :, :T].contiguous(), tv[:, :, :T].contiguous(), state, fast=fast)
     for t in range(T, T + extra):
         o, z = binding.power_attn_decode_step(prob1, tq[:, :, t].contiguous(), tk[:, :, t].contiguous(), tv[:, :, t].contiguous(), state)
         if t in (T, T + 1, T + 63, T + extra - 1):
