@@ -199,6 +199,7 @@ def main():
                     help="time the gated layer (per-timestep log-gates, mean decay 0.02 per step) instead of the headline one")
     ap.add_argument("--recompute-states", action="store_true",
                     help="backward pass rebuilds the chunk states instead of reusing the forward pass's workspace")
+    ap.add_argument("--forward-only", action="store_true", help="time the forward pass alone")
     ap.add_argument("--decode-batch", type=int, default=0,
                     help="instead of the training step: time the single-token decode step of the workload's head shape "
                          "on this many sequences (state resident in HBM)")
@@ -236,9 +237,12 @@ def main():
     Z = torch.empty(tq.shape[:3], dtype=torch.float32, device=dev)
     grads = (torch.empty_like(tq), torch.empty_like(tk), torch.empty_like(tv))
 
+    with_bwd = bool(w.get("backward", True)) and not args.forward_only    # configs 1 and 2 are forward-only
+
     def step():
         power_attn_fwd(tq, tk, tv, p, chunk, impl=args.impl, workspace=ws, out=O, out_z=Z, keep_state=keep, log_g=tl)
-        power_attn_bwd(tq, tk, tv, O, Z, tg, p, chunk, impl=args.impl, workspace=ws, out=grads, keep_state=keep, log_g=tl)
+        if with_bwd:
+            power_attn_bwd(tq, tk, tv, O, Z, tg, p, chunk, impl=args.impl, workspace=ws, out=grads, keep_state=keep, log_g=tl)
 
     if args.serial_kernels:
         binding.profile_begin()
@@ -295,14 +299,14 @@ def main():
                     "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak, "traffic": measured_traffic(name, dom),
                     "avg_kernel_ms": dom_ms, "algorithmic_flops_per_launch": fl[role],
                     "algorithmic_bytes_per_launch": by[role]}
-    total_alg = fl["fwd_total"] + fl["bwd_total"]
+    total_alg = fl["fwd_total"] + (fl["bwd_total"] if with_bwd else 0)
     out = {
         "metric": "power-attention fwd+bwd tokens/sec at p=2,d=64,T=64k; % bf16 MFMA peak",
         "value": tokens / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": w["dtype"], "data": "synthetic",
         "config": {"workload": name, "B": w["B"], "H": w["H"], "T": w["T"], "d": w["d"], "p": p, "chunk": w["chunk"],
-                   "chunk_requested": chunk, "normalize": True, "pass": "fwd+bwd", "impl": args.impl, "keep_state": keep, "serial_kernels": args.serial_kernels, "gated": args.gated,
+                   "chunk_requested": chunk, "normalize": True, "pass": "fwd+bwd" if with_bwd else "fwd", "impl": args.impl, "keep_state": keep, "serial_kernels": args.serial_kernels, "gated": args.gated,
                    "state_rows": binding.power_attn_state_rows(prob)},
         "step_algorithmic_tflop": total_alg / 1e12,
         "step_frac_of_bf16_mfma_peak": total_alg / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS,
