@@ -62,9 +62,8 @@ static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; 
 //   qfac  [BH][T]       exp(bl_i): decay of query i since the start of its chunk
 //   kfac  [BH][T]       exp(bl_end - bl_j): decay of key j until the end of its chunk
 //   lam   [BH][T/chunk] exp(bl_end): decay across the whole chunk
-//   db    [BH][T]       scratch of the backward pass: dL/db_i, or q_i . dq_i when a kernel family
-//                       forms the two dot products itself from its float32 accumulators
-//   db2   [BH][T]       then: k_i . dk_i
+//   db    [BH][T]       backward pass: q_i . dq_i, written by the family's dQ kernel from its float32 accumulators
+//   db2   [BH][T]       backward pass: k_i . dk_i, likewise
 struct GateBuf {
     float *bl = nullptr, *qfac = nullptr, *kfac = nullptr, *lam = nullptr, *db = nullptr, *db2 = nullptr;
     float* xb = nullptr;    // [BH][T/chunk] backward: <R_m, S_{m+1}>, the pairs that straddle the end of chunk m (0 for the last)
@@ -82,11 +81,9 @@ struct Ctx {
 size_t gate_workspace_bytes(const pa_problem& pr, bool backward);
 GateBuf gate_buffers(const pa_problem& pr, bool backward, char* base);
 pa_status gate_prepare(const Ctx& c, const float* log_g);
-// The family has already written gate.xb.  have_dots: its kernels have also written q.dq into gate.db and
-// k.dk into gate.db2 (else they are formed here from the outputs)
+// The family has already written gate.xb, q.dq into gate.db and k.dk into gate.db2.
 // fin_chunk: the token granularity of gate.xb (the problem's chunk, or finer when the family says so)
-pa_status gate_gradient(const Ctx& c, const void* Q, const void* K, const void* dQ, const void* dK, float* dlog_g,
-                        bool have_dots, int fin_chunk);
+pa_status gate_gradient(const Ctx& c, float* dlog_g, int fin_chunk);
 
 // generic (vector-ALU, float32) family
 size_t generic_workspace_bytes(const pa_problem& pr, bool backward);

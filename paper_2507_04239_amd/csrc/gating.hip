@@ -42,38 +42,16 @@ __global__ __launch_bounds__(GT) void k_gate_prep(const float* __restrict__ log_
     if (tid == 0) lam[(size_t)bh * (T / chunk) + n] = __expf(total);
 }
 
-// dL/db_i = (q_i . dq_i - k_i . dk_i) / p; 16 lanes per row.
-template <typename T>
-__global__ __launch_bounds__(256) void k_gate_db(const T* __restrict__ Q, const T* __restrict__ dQ, const T* __restrict__ K,
-                                                 const T* __restrict__ dK, float* __restrict__ db, long long rows, int d,
-                                                 float inv_p) {
-    const long long row = (long long)blockIdx.x * 16 + (threadIdx.x >> 4);
-    const int c = threadIdx.x & 15;
-    float acc = 0.f;
-    if (row < rows) {
-        const size_t o = (size_t)row * d;
-        for (int a = c; a < d; a += 16) {
-            acc -= io<T>::ld(K + o + a) * io<T>::ld(dK + o + a);
-            acc += io<T>::ld(Q + o + a) * io<T>::ld(dQ + o + a);
-        }
-    }
-    acc += __shfl_xor(acc, 1);
-    acc += __shfl_xor(acc, 2);
-    acc += __shfl_xor(acc, 4);
-    acc += __shfl_xor(acc, 8);
-    if (row < rows && c == 0) db[row] = acc * inv_p;
-}
-
 // dlog_g[t] = sum_{i >= t} dL/db_i.  A running sum over the whole sequence would pile up the
 // rounding noise of tens of thousands of terms on a result that is local (only pairs within a few
 // decay lengths of t matter).  Instead: the part of the sum beyond the end of t's chunk m equals
 //     X_m = sum_{j <= end_m < i} e_ij a_ij = < R_m , S_{m+1} >,
 // the inner product of the two states that meet at that chunk boundary, which each kernel family
 // computes from its states (xb); only the part inside the chunk is summed here.
-// (db2 null: db holds dL/db_i.  Else dL/db_i = (db[i] - db2[i]) * inv_p.)
+// db holds q_i . dq_i and db2 k_i . dk_i: dL/db_i = (db[i] - db2[i]) / p.
 __device__ __forceinline__ float gate_term(const float* __restrict__ db, const float* __restrict__ db2, float inv_p,
                                            size_t i) {
-    return db2 != nullptr ? (db[i] - db2[i]) * inv_p : db[i];
+    return (db[i] - db2[i]) * inv_p;
 }
 
 __global__ __launch_bounds__(GT) void k_gate_finish(const float* __restrict__ db, const float* __restrict__ db2, float inv_p,
@@ -142,30 +120,17 @@ pa_status gate_prepare(const Ctx& c, const float* log_g) {
     return launch_ok() ? PA_OK : PA_ERR_HIP;
 }
 
-pa_status gate_gradient(const Ctx& c, const void* Q, const void* K, const void* dQ, const void* dK, float* dlog_g,
-                        bool have_dots, int fin_chunk) {
+pa_status gate_gradient(const Ctx& c, float* dlog_g, int fin_chunk) {
     const pa_problem& pr = c.prob;
     // Under the sum normalisation q_i . dq_i is zero in exact arithmetic, yet the term stays: what the
     // device finds there is dO_i . (O_i - rounded O_i), and the k_j . dk_j of the keys after t contain
-    // exactly that with the opposite sign, row by row.  (Measured, bf16, decay 0.5 per step: relative L2
-    // error of dlog_g 1.8e-2 without the term, 9e-3 with it; no worse at weak decay.)
-    const long long rows = (long long)pr.B * pr.H * pr.T;
-    if (!have_dots) {
-        LaunchScope ls("gate_db", c.stream);
-        if (pr.dtype == PA_DTYPE_F32)
-            hipLaunchKernelGGL((k_gate_db<float>), dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, c.stream, (const float*)Q,
-                               (const float*)dQ, (const float*)K, (const float*)dK, c.gate.db, rows, pr.d, 1.f / pr.p);
-        else
-            hipLaunchKernelGGL((k_gate_db<bf16_t>), dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, c.stream, (const bf16_t*)Q,
-                               (const bf16_t*)dQ, (const bf16_t*)K, (const bf16_t*)dK, c.gate.db, rows, pr.d, 1.f / pr.p);
-    }
-    if (!have_dots && !launch_ok()) return PA_ERR_HIP;
-    const float* d2 = have_dots ? (const float*)c.gate.db2 : (const float*)nullptr;
-    {
-        LaunchScope ls("gate_finish", c.stream);
-        hipLaunchKernelGGL(k_gate_finish, dim3(pr.T / fin_chunk, pr.B * pr.H), dim3(GT), 0, c.stream, c.gate.db, d2, 1.f / pr.p,
-                           (const float*)c.gate.xb, dlog_g, pr.T, fin_chunk);
-    }
+    // exactly that with the opposite sign, row by row.  Both dot products come from the kernels' float32
+    // accumulators: formed from the rounded bf16 outputs they would carry 2^-9 of terms that cancel.
+    // (Measured, bf16, decay 0.5 per step: relative L2 error of dlog_g 1.8e-2 without the row term, 9e-3
+    // with it from rounded outputs, 3e-3 from the accumulators; no worse at weak decay.)
+    LaunchScope ls("gate_finish", c.stream);
+    hipLaunchKernelGGL(k_gate_finish, dim3(pr.T / fin_chunk, pr.B * pr.H), dim3(GT), 0, c.stream, (const float*)c.gate.db,
+                       (const float*)c.gate.db2, 1.f / pr.p, (const float*)c.gate.xb, dlog_g, pr.T, fin_chunk);
     return launch_ok() ? PA_OK : PA_ERR_HIP;
 }
 

@@ -332,7 +332,7 @@ __global__ __launch_bounds__(NT) void k_bwd_dq(const T* __restrict__ Q, const T*
                                                const uchar4* __restrict__ idx, const float* __restrict__ St,
                                                T* __restrict__ dQ, int Tlen, int d, int v, int chunk, long long D,
                                                float scale, const float* __restrict__ bl,
-                                               const float* __restrict__ qfac) {
+                                               const float* __restrict__ qfac, float* __restrict__ qdq) {
     extern __shared__ float smem[];
     const int VP = v + 1;
     const int dq = d + 1;
@@ -422,6 +422,13 @@ __global__ __launch_bounds__(NT) void k_bwd_dq(const T* __restrict__ Q, const T*
             int t = e / d, a = e - t * d;
             io<T>::st(dQ + (base_tok + i0 + t) * d + a, scale * dqs[t * dq + a]);
         }
+        if (qdq != nullptr) {
+            // q_i . dq_i for the gate gradient, from the unrounded accumulators (qs carries the scale dq lacks)
+            float part = 0.f;
+            for (int a = xg; a < d; a += 4) part += qrow[a] * dqrow[a];
+            part = quad_sum(part);
+            if (live && xg == 0) qdq[base_tok + il] = part;
+        }
     }
 }
 
@@ -435,7 +442,7 @@ __global__ __launch_bounds__(NT) void k_bwd_dkdv(const T* __restrict__ Q, const 
                                                  const uchar4* __restrict__ idx, const float* __restrict__ Rt,
                                                  T* __restrict__ dK, T* __restrict__ dV, int Tlen, int d, int v,
                                                  int chunk, long long D, float scale, const float* __restrict__ bl,
-                                                 const float* __restrict__ kfac) {
+                                                 const float* __restrict__ kfac, float* __restrict__ kdk) {
     extern __shared__ float smem[];
     const int VP = v + 1;
     const int dq = d + 1;
@@ -536,6 +543,12 @@ __global__ __launch_bounds__(NT) void k_bwd_dkdv(const T* __restrict__ Q, const 
         for (int e = tid; e < ntok * d; e += NT) {
             int t = e / d, a = e - t * d;
             io<T>::st(dK + (base_tok + j0 + t) * d + a, dks[t * dq + a]);
+        }
+        if (kdk != nullptr) {
+            float part = 0.f;
+            for (int a = xg; a < d; a += 4) part += krow[a] * dkrow[a];
+            part = quad_sum(part);
+            if (live && xg == 0) kdk[base_tok + jl] = part;
         }
         if (live) {
 #pragma unroll
@@ -701,14 +714,14 @@ pa_status run_bwd(const Ctx& c, const Layout& L, const T* Q, const T* K, const T
         LaunchScope ls("generic_bwd_dq", c.stream);
         hipLaunchKernelGGL((k_bwd_dq<T, P, KX>), dim3(L.nchunk, (unsigned)BH), dim3(NT), smem_bwd(pr), c.stream, Q, K, Vp,
                            Gp, idx, St, dQ, pr.T, pr.d, pr.v, pr.chunk, L.D, pr.scale, (const float*)c.gate.bl,
-                           (const float*)c.gate.qfac);
+                           (const float*)c.gate.qfac, c.gate.db);
     }
     PA_CHECK_LAUNCH();
     {
         LaunchScope ls("generic_bwd_dkdv", c.stream);
         hipLaunchKernelGGL((k_bwd_dkdv<T, P, KX>), dim3(L.nchunk, (unsigned)BH), dim3(NT), smem_bwd(pr), c.stream, Q, K,
                            Vp, Gp, idx, Rt, dK, dV, pr.T, pr.d, pr.v, pr.chunk, L.D, pr.scale, (const float*)c.gate.bl,
-                           (const float*)c.gate.kfac);
+                           (const float*)c.gate.kfac, c.gate.db2);
     }
     PA_CHECK_LAUNCH();
     return PA_OK;

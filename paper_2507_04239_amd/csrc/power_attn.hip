@@ -258,8 +258,7 @@ pa_status run_bwd(const pa_problem* prob, const void* Q, const void* K, const vo
     }
     st = impl == PA_IMPL_MFMA ? mfma_bwd(c, Q, K, V, O, Z, dO, dQ, dK, dV) : generic_bwd(c, Q, K, V, O, Z, dO, dQ, dK, dV);
     if (st == PA_OK && gated)
-        st = gate_gradient(c, Q, K, dQ, dK, dlog_g, impl == PA_IMPL_MFMA,
-                           impl == PA_IMPL_MFMA ? mfma_gate_fin_chunk(*prob) : prob->chunk);
+        st = gate_gradient(c, dlog_g, impl == PA_IMPL_MFMA ? mfma_gate_fin_chunk(*prob) : prob->chunk);
     if (st != PA_OK || !pd.on) return st;
     const int row = asked.d * 2;
     if (!copy_rows(s, dQ, dQout, BH, prob->T, asked.T, row) || !copy_rows(s, dK, dKout, BH, prob->T, asked.T, row) ||

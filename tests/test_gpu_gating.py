@@ -19,6 +19,8 @@ CASES = [
     ("f32", "generic", 2, 1, 1, 130, 10, 26, False, 1.3, 0.3),      # strong decay, ragged sizes
     ("bf16", "generic", 2, 1, 2, 384, 32, 128, True, 1.0, 0.02),
     ("bf16", "generic", 4, 1, 1, 256, 16, 64, True, 1.0, 0.02),
+    ("bf16", "generic", 2, 1, 1, 256, 32, 64, True, 1.0, 0.5),      # strong decay: the gate gradient is a small
+    ("bf16", "generic", 4, 1, 1, 256, 16, 64, False, 1.0, 0.5),     # difference of sums that nearly cancel
     ("bf16", "mfma", 2, 1, 2, 512, 64, 128, True, 1.0, 0.02),
     ("bf16", "mfma", 2, 1, 1, 1024, 64, 256, True, 1.0, 0.01),     # two query blocks per chunk
     ("bf16", "mfma", 2, 1, 1, 128, 64, 128, True, 1.0, 0.05),      # a single chunk
