@@ -42,8 +42,17 @@ __global__ __launch_bounds__(256) void k_transpose(const bf16_t* __restrict__ in
 // Fused update-state + cumulative sum over chunks (App. E.2 + E.3, no gating), used for
 //   the forward state     S_n = sum_{j <  n cs}     phi(k_j) v_j^T        (X = K, Y = V)
 //   the state gradient    R_m = sum_{i >= (m+1) cs} phi(q_i) ghat_i^T     (X = Q, Y = dO/Z, REV)
-// One workgroup of 256 threads per (tile pair, head).  Workgroup `pair` owns the two 64 x DH state tiles
-// 2 pair, 2 pair + 1; wave w owns 32 rows (a in 4(w&1) .. +3) of tile 2 pair + (w >> 1).
+// One workgroup of 256 threads per (tile pair, head).  Workgroup `pair` owns two 64 x DH state tiles of
+// one tile row, (ti, tj0) and (ti, tj1) (a tile row with an odd number of tiles ends in a "pair" of
+// one tile taken twice: both halves then compute and store the same values); wave w owns the rows
+// a = 2 w, 2 w + 1 of both.  A 16-row MFMA block is one a and the 8 + 8 values b of the two tiles, so
+// the factor x[8 ti + a] of its 16 rows is the same for all of them: a lane reads ONE float of it per
+// k-step (token 8 g + (r16 & 7) of row a = 2 w + (r16 >> 3)) and the multiply fetches the token it
+// needs from that lane of its 16-lane row by DPP (row_newbcast), instead of reading the 8 tokens per
+// lane and row block from LDS (64 of 160 bytes per lane and k-step).  A tile pair stages only the
+// 24 feature rows of X it multiplies.  (Measured on the headline shape: 11 % off the scan at 256 or
+// more tokens per state; at 128 the scan is bound by its 1.86 GB of state writes - with the MFMAs
+// taken out it is no faster, with the stores taken out it is.)
 // Workgroup NPAIR owns the normaliser in its d x d form: Gamma = sum k k^T, or
 // Omega = sum gz_i q_i q_i^T for the gradient (same code: the A operand is x itself, times the
 // weight, and the B operand comes from X instead of Y; only waves 0 and 1 have rows).
@@ -53,12 +62,12 @@ __global__ __launch_bounds__(256) void k_transpose(const bf16_t* __restrict__ in
 // (bf16) are staged in LDS, feature-major, and shared by the four waves; the global loads of
 // SCAN_PF further stages are in flight in registers.
 //
-constexpr int NPAIR = NTILES / 2;
+constexpr int NPAIR = 20;                      // 4 + 4 + 3 + 3 + 2 + 2 + 1 + 1 pairs in the tile rows ti = 0 .. 7
 constexpr int SCAN_TOK = 128;                  // tokens per stage
 constexpr int SCAN_PF = 3;                     // stages in flight in registers
 constexpr int XS_PITCH = SCAN_TOK + 4;         // floats; pitch = 4 mod 64 banks
 constexpr int YS_PITCH = SCAN_TOK + 8;         // bf16;   pitch = 4 mod 64 banks (in dwords)
-static_assert(NTILES % 2 == 0, "tiles are handled in pairs");
+static_assert(NTILES == 36 && DH == 64, "the pair table below is written for 8 x 8 tiles of 64 rows");
 
 // The reverse scan (state gradient) runs side by side with the dQ kernel, whose workgroups need
 // LDS of their own on the same CU: there Y is single-buffered (ys[1] is not allocated), at the
@@ -78,20 +87,31 @@ constexpr size_t scan_smem_bytes() {
 // alone on its CU (one wave per SIMD): the LDS operands of k-step s+1 are read and its A
 // operands expanded while the MFMAs of k-step s run.
 struct ScanOps {          // LDS operands of one k-step for one lane
-    float4 xal[2], xah[2];   // x[fa(rbk)][8 tokens]
+    float4 xal[2], xah[2];   // normaliser only: x[fa(rbk)][8 tokens]
+    float xa1;               // tiles: x[8 ti + 2 w + (r16 >> 3)][token 8 g + (r16 & 7)], shared along the 16-lane row
     float4 xbl, xbh;         // x[fb][8 tokens]  (or the weights / ones for the normaliser)
     uint4 b[4];              // Y^T fragments, 4 column blocks
 };
+
+// the value of lane L of this lane's 16-lane row
+template <int L>
+__device__ __forceinline__ float row_lane(float x) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x150 + L, 0xf, 0xf, false));
+}
 
 template <bool GAMMA, bool REV>
 __device__ __forceinline__ void scan_load_ops(ScanOps& o, const ScanSmem& sm, int buf, int s, int fa0, int fa_step,
                                               int fb, int r16, int g) {
     const int t0 = 32 * s + 8 * g;
+    if (GAMMA) {
 #pragma unroll
-    for (int rbk = 0; rbk < 2; ++rbk) {
-        const float* xa = &sm.xs[buf][fa0 + fa_step * rbk][t0];
-        o.xal[rbk] = *(const float4*)xa;
-        o.xah[rbk] = *(const float4*)(xa + 4);
+        for (int rbk = 0; rbk < 2; ++rbk) {
+            const float* xa = &sm.xs[buf][fa0 + fa_step * rbk][t0];
+            o.xal[rbk] = *(const float4*)xa;
+            o.xah[rbk] = *(const float4*)(xa + 4);
+        }
+    } else {
+        o.xa1 = sm.xs[buf][fa0][t0 + (r16 & 7)];
     }
     if (!GAMMA) {
         o.xbl = *(const float4*)&sm.xs[buf][fb][t0];
@@ -107,7 +127,20 @@ __device__ __forceinline__ void scan_load_ops(ScanOps& o, const ScanSmem& sm, in
     for (int cb = 0; cb < 4; ++cb) o.b[cb] = *(const uint4*)&sm.ys[REV ? 0 : buf][16 * cb + r16][t0];
 }
 
+template <bool GAMMA>
 __device__ __forceinline__ void scan_expand(Frag (&af)[2], const ScanOps& o) {
+    if (!GAMMA) {
+        // row block rbk: a = 2 w + rbk, whose 8 tokens sit in lanes 8 rbk .. 8 rbk + 7 of the row
+        af[0].v[0] = (__bf16)(row_lane<0>(o.xa1) * o.xbl.x); af[0].v[1] = (__bf16)(row_lane<1>(o.xa1) * o.xbl.y);
+        af[0].v[2] = (__bf16)(row_lane<2>(o.xa1) * o.xbl.z); af[0].v[3] = (__bf16)(row_lane<3>(o.xa1) * o.xbl.w);
+        af[0].v[4] = (__bf16)(row_lane<4>(o.xa1) * o.xbh.x); af[0].v[5] = (__bf16)(row_lane<5>(o.xa1) * o.xbh.y);
+        af[0].v[6] = (__bf16)(row_lane<6>(o.xa1) * o.xbh.z); af[0].v[7] = (__bf16)(row_lane<7>(o.xa1) * o.xbh.w);
+        af[1].v[0] = (__bf16)(row_lane<8>(o.xa1) * o.xbl.x); af[1].v[1] = (__bf16)(row_lane<9>(o.xa1) * o.xbl.y);
+        af[1].v[2] = (__bf16)(row_lane<10>(o.xa1) * o.xbl.z); af[1].v[3] = (__bf16)(row_lane<11>(o.xa1) * o.xbl.w);
+        af[1].v[4] = (__bf16)(row_lane<12>(o.xa1) * o.xbh.x); af[1].v[5] = (__bf16)(row_lane<13>(o.xa1) * o.xbh.y);
+        af[1].v[6] = (__bf16)(row_lane<14>(o.xa1) * o.xbh.z); af[1].v[7] = (__bf16)(row_lane<15>(o.xa1) * o.xbh.w);
+        return;
+    }
 #pragma unroll
     for (int rbk = 0; rbk < 2; ++rbk) {
         af[rbk].v[0] = (__bf16)(o.xal[rbk].x * o.xbl.x); af[rbk].v[1] = (__bf16)(o.xal[rbk].y * o.xbl.y);
@@ -153,8 +186,8 @@ struct StateOut {
 };
 template <bool GAMMA>
 __device__ __forceinline__ void store_run(const StateOut& so, int k) {
-    // state tile [a][v][b]: run k = (row block k >> 1, column-block pair k & 1); Gamma: column block k
-    const int off = GAMMA ? 16 * DH * k : (k >> 1) * (2 * DH * 8) + (k & 1) * (32 * 8);
+    // state tile [a][v][b]: run k = (row block k >> 1 = a, column-block pair k & 1); Gamma: column block k
+    const int off = GAMMA ? 16 * DH * k : (k >> 1) * (DH * 8) + (k & 1) * (32 * 8);
     *(uint4*)(so.dst + off) = so.run[k];
 }
 
@@ -168,22 +201,22 @@ __device__ __forceinline__ void scan_stage(f32x4 (&acc)[2][4], const ScanSmem& s
     Frag af0[2], af1[2];
     scan_load_ops<GAMMA, REV>(o0, sm, buf, 0, fa0, fa_step, fb, r16, g);
     scan_load_ops<GAMMA, REV>(o1, sm, buf, 1, fa0, fa_step, fb, r16, g);
-    scan_expand(af0, o0);
+    scan_expand<GAMMA>(af0, o0);
     __builtin_amdgcn_sched_barrier(0);
     scan_mma(acc, af0, o0);          // k-step 0
-    scan_expand(af1, o1);
+    scan_expand<GAMMA>(af1, o1);
     scan_interleave_hint();
     if (PACED) store_run<GAMMA>(so, 0);
     __builtin_amdgcn_sched_barrier(0);
     scan_load_ops<GAMMA, REV>(o0, sm, buf, 2, fa0, fa_step, fb, r16, g);
     scan_mma(acc, af1, o1);          // k-step 1
-    scan_expand(af0, o0);
+    scan_expand<GAMMA>(af0, o0);
     scan_interleave_hint();
     if (PACED) store_run<GAMMA>(so, 1);
     __builtin_amdgcn_sched_barrier(0);
     scan_load_ops<GAMMA, REV>(o1, sm, buf, 3, fa0, fa_step, fb, r16, g);
     scan_mma(acc, af0, o0);          // k-step 2
-    scan_expand(af1, o1);
+    scan_expand<GAMMA>(af1, o1);
     scan_interleave_hint();
     if (PACED) store_run<GAMMA>(so, 2);
     __builtin_amdgcn_sched_barrier(0);
@@ -203,20 +236,27 @@ __device__ __forceinline__ void scan_body(const bf16_t* __restrict__ Xt, const b
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int r16 = lane & 15, g = lane >> 4;
     const int nstate = T / cs;
-    const int tile = GAMMA ? 0 : 2 * pair + (w >> 1);
-    int ti = 0, tj = 0;
-    for (int l = 0; l < tile; ++l) {
-        if (++ti > tj) {
-            ++tj;
-            ti = 0;
+    // pair -> tile row ti and the two tiles (ti, tj0), (ti, tj1) of it: row ti has 8 - ti tiles
+    int ti = 0, tj0 = 0;
+    if (!GAMMA) {
+        int left = pair;
+        while (left >= (9 - ti) / 2) {
+            left -= (9 - ti) / 2;
+            ++ti;
         }
+        tj0 = ti + 2 * left;
     }
-    const float mult = GAMMA ? out_scale : ((ti == tj) ? 1.f : 2.f) * out_scale;
-    // feature rows this lane expands: row block rbk in {0,1} covers tile rows 32 (w&1) + 16 rbk + r16
-    //   tiles: a = 4 (w&1) + 2 rbk + (r16 >> 3), b = r16 & 7;   Gamma: feature 32 w + 16 rbk + r16
-    const int fa0 = GAMMA ? (32 * (w & 1) + r16) : 8 * ti + 4 * (w & 1) + (r16 >> 3);
-    const int fa_step = GAMMA ? 16 : 2;
-    const int fb = 8 * tj + (r16 & 7);
+    const int tj1 = min(tj0 + 1, DH / 8 - 1);
+    // As an A operand, lane r16 is row (tile r16 >> 3, b = r16 & 7) of the row block; as an accumulator,
+    // lane (r16, g) holds rows 4 g + r: tile g >> 1, b = 4 (g & 1) + r.
+    const int tj_c = (g >> 1) ? tj1 : tj0;
+    const int tile = GAMMA ? 0 : tj_c * (tj_c + 1) / 2 + ti;   // storage order of the tiles: by columns tj
+    const float mult = GAMMA ? out_scale : ((ti == tj_c) ? 1.f : 2.f) * out_scale;
+    // tiles: the shared factor's feature (lanes 0-7 of a row: a = 2 w, lanes 8-15: a = 2 w + 1), and this
+    // lane's own;   Gamma: feature 32 w + 16 rbk + r16
+    const int fa0 = GAMMA ? (32 * (w & 1) + r16) : 8 * ti + 2 * w + (r16 >> 3);
+    const int fa_step = GAMMA ? 16 : 0;
+    const int fb = 8 * ((r16 >> 3) ? tj1 : tj0) + (r16 & 7);
     const bool has_rows = !GAMMA || w < 2;
 
     // global -> LDS staging: thread t moves pieces t, t + 256, t + 512, t + 768 of the stage; a
@@ -231,6 +271,24 @@ __device__ __forceinline__ void scan_body(const bf16_t* __restrict__ Xt, const b
         p_feat[q] = id >> 4;
         p_tok[q] = 8 * (id & 15);                                        // token inside the stage
         p_off[q] = (p_tok[q] >> 6) * (DH * TBLK) + p_feat[q] * TBLK + (p_tok[q] & 63);
+    }
+    // X: a tile pair multiplies only the 3 x 8 features of ti, tj0 and tj1, 384 pieces: threads 0 .. 127
+    // move two, the others one (and repeat the last piece: same bytes to the same place).  The
+    // normaliser needs all 64 rows, pieces as for Y.
+    int x_feat[4], x_tok[4], x_off[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        if (GAMMA) {
+            x_feat[q] = p_feat[q];
+            x_tok[q] = p_tok[q];
+            x_off[q] = p_off[q];
+        } else {
+            const int id = min(tid + 256 * (q & 1), 24 * 16 - 1);
+            const int grp = id >> 7;
+            x_feat[q] = 8 * (grp == 0 ? ti : (grp == 1 ? tj0 : tj1)) + ((id >> 4) & 7);
+            x_tok[q] = 8 * (id & 15);
+            x_off[q] = (x_tok[q] >> 6) * (DH * TBLK) + x_feat[q] * TBLK + (x_tok[q] & 63);
+        }
     }
 
     f32x4 acc[2][4];
@@ -261,9 +319,9 @@ __device__ __forceinline__ void scan_body(const bf16_t* __restrict__ Xt, const b
     // the state as it stands, packed for storing as state n
     auto pack_state = [&](StateOut& so, int n, float decay) {
         if (!GAMMA) {
-            // layout [a][v][b]: accumulator rows are b = 4 (g & 1) + r of a = .. + (g >> 1)
-            so.dst = StC + ((size_t)(bh * nstate + n) * NTILES + tile) * TILE_ELEMS +
-                     ((4 * (w & 1) + (g >> 1)) * DH + 16 * (g & 1) + r16) * 8;
+            // layout [a][v][b]: accumulator rows are b = 4 (g & 1) + r of tile (ti, tj0 / tj1 by g >> 1),
+            // row block rbk is a = 2 w + rbk
+            so.dst = StC + ((size_t)(bh * nstate + n) * NTILES + tile) * TILE_ELEMS + (2 * w * DH + 16 * (g & 1) + r16) * 8;
 #pragma unroll
             for (int rbk = 0; rbk < 2; ++rbk)
 #pragma unroll
@@ -309,10 +367,12 @@ __device__ __forceinline__ void scan_body(const bf16_t* __restrict__ Xt, const b
         const int sc_ = min((ST), nstage - 1);                                            \
         const int sidx_ = REV ? nstage_all - 1 - sc_ : sc_;                               \
         const size_t so_ = (size_t)sidx_ * (2 * DH * TBLK);                               \
-        x0_##J = *(const uint4*)(Xh + so_ + p_off[0]);                                    \
-        x1_##J = *(const uint4*)(Xh + so_ + p_off[1]);                                    \
-        x2_##J = *(const uint4*)(Xh + so_ + p_off[2]);                                    \
-        x3_##J = *(const uint4*)(Xh + so_ + p_off[3]);                                    \
+        x0_##J = *(const uint4*)(Xh + so_ + x_off[0]);                                    \
+        x1_##J = *(const uint4*)(Xh + so_ + x_off[1]);                                    \
+        if (GAMMA) {                                                                      \
+            x2_##J = *(const uint4*)(Xh + so_ + x_off[2]);                                \
+            x3_##J = *(const uint4*)(Xh + so_ + x_off[3]);                                \
+        }                                                                                 \
         y0_##J = *(const uint4*)(Yh + so_ + p_off[0]);                                    \
         y1_##J = *(const uint4*)(Yh + so_ + p_off[1]);                                    \
         y2_##J = *(const uint4*)(Yh + so_ + p_off[2]);                                    \
@@ -321,7 +381,7 @@ __device__ __forceinline__ void scan_body(const bf16_t* __restrict__ Xt, const b
     }
 #define PA_FILL_X(BUF, Q, XR)                                                             \
     {                                                                                     \
-        float* d_ = &sm.xs[BUF][p_feat[Q]][p_tok[Q]];                                     \
+        float* d_ = &sm.xs[BUF][x_feat[Q]][x_tok[Q]];                                     \
         *(float4*)d_ = make_float4(bf_lo(XR.x), bf_hi(XR.x), bf_lo(XR.y), bf_hi(XR.y));   \
         *(float4*)(d_ + 4) = make_float4(bf_lo(XR.z), bf_hi(XR.z), bf_lo(XR.w), bf_hi(XR.w)); \
     }
@@ -338,7 +398,9 @@ __device__ __forceinline__ void scan_body(const bf16_t* __restrict__ Xt, const b
         }                                                                                     \
         PA_PROBE(1)                                                                           \
         PA_FILL_X(BUF, 0, x0_##J) PA_FILL_X(BUF, 1, x1_##J)                                   \
-        PA_FILL_X(BUF, 2, x2_##J) PA_FILL_X(BUF, 3, x3_##J)                                   \
+        if (GAMMA) {                                                                          \
+            PA_FILL_X(BUF, 2, x2_##J) PA_FILL_X(BUF, 3, x3_##J)                               \
+        }                                                                                     \
         if (GAMMA && REV && tid < SCAN_TOK) sm.ws[BUF][tid] = wv_##J;                         \
         if (REV) lds_barrier(); /* every wave is done with the Y of the stage before */       \
         *(uint4*)&sm.ys[REV ? 0 : BUF][p_feat[0]][p_tok[0]] = y0_##J;                         \
