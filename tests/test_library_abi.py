@@ -88,10 +88,9 @@ def test_automatic_chunk_choice():
     assert rc(mk(2, 8, 16384, 32, 32, 4, 0, dtype="bf16")) == 16384
     # float32, small head: state 136 x 17; chunked from a few hundred tokens on
     assert rc(mk(1, 1, 64, 16, 16, 2, 0, dtype="f32")) == 64
-    c = rc(mk(1, 1, 4096, 16, 16, 2, 0, dtype="f32"))
-    assert 0 < c <= 128 and 4096 % c == 0
+    assert rc(mk(1, 1, 4096, 16, 16, 2, 0, dtype="f32")) == 64   # generic kernels: measured best chunk
     assert rc(mk(1, 1, 96, 16, 16, 2, 0, dtype="f32", impl="generic")) == 96
-    assert rc(mk(1, 1, 4000, 16, 16, 2, 0, dtype="f32")) == 32   # largest power of two <= 128 dividing T
+    assert rc(mk(1, 1, 4000, 16, 16, 2, 0, dtype="f32")) == 32   # largest power of two <= 64 dividing T
     assert binding.power_attn_workspace_bytes(mk(1, 12, 65536, 64, 64, 2, 0), False) == \
         binding.power_attn_workspace_bytes(mk(1, 12, 65536, 64, 64, 2, 256), False)
     assert rc(mk(1, 1, 100, 16, 16, 2, 7)) == 7                  # an explicit chunk is returned as it is ...
