@@ -27,6 +27,7 @@ CASES = [
     ("bf16", "mfma", 2, 1, 2, 768, 64, 128, True, 0.6, 0.1),       # scale != 1, stronger decay
     ("bf16", "mfma", 2, 1, 1, 512, 64, 128, False, 1.0, 0.02),     # un-normalised
     ("bf16", "mfma", 2, 1, 1, 1536, 64, 512, True, 1.0, 0.005),
+    ("bf16", "mfma", 2, 1, 1, 4096, 64, 256, True, 1.0, 0.01),     # block ids of a chunk dealt out 8 apart
 ]
 
 

@@ -39,6 +39,8 @@ BWD_CASES = [
     (1, 2, 768, 128, True, 0.6),
     (1, 2, 512, 128, False, 1.0),
     (1, 1, 1536, 512, True, 1.0),
+    (1, 1, 4096, 256, True, 1.0),      # 32 blocks of 128 tokens: the blocks of a chunk are dealt out 8 ids apart
+    (1, 1, 4096, 512, True, 1.0),      # the same with four blocks per chunk
 ]
 
 
