@@ -453,9 +453,6 @@ __global__ __launch_bounds__(256) void k_mfma_scan(const bf16_t* __restrict__ Xt
     if (q >= cnt) return;
     const int item = xcd * base_cnt + min(xcd, extra) + q;
     const int bh = item / (NPAIR + 1), pair = item % (NPAIR + 1);
-#ifdef PA_STAGGER
-    for (int i = 0; i < (int)(blockIdx.x % 32); ++i) __builtin_amdgcn_s_sleep(PA_STAGGER);
-#endif
     if (pair == NPAIR)
         scan_body<true, REV, EVERY, GATED>(Xt, Yt, wgt, StC, Gam, T, cs, out_scale, lam, sm, pair, bh);
     else
