@@ -41,6 +41,7 @@ BWD_CASES = [
     (1, 1, 1536, 512, True, 1.0),
     (1, 1, 4096, 256, True, 1.0),      # 32 blocks of 128 tokens: the blocks of a chunk are dealt out 8 ids apart
     (1, 1, 4096, 512, True, 1.0),      # the same with four blocks per chunk
+    (1, 1, 3072, 384, True, 1.0),      # three blocks per chunk, 24 blocks: one full group of the dealing
 ]
 
 
