@@ -79,6 +79,29 @@ def test_headline_config3_fwd_bwd():
                    ref_head=((b, h), (O_ref, Z_ref)))
 
 
+def test_headline_shape_with_the_library_chosen_chunk():
+    """The headline shape with chunk = 0: the library resolves it to 256, where the two 128-token blocks of a
+    chunk are dealt to the same XCD.  One head in full against the chunked float64 oracle, sampled rows of
+    four heads against the definition."""
+    from paper_2507_04239_amd import binding
+    name = "cfg3_bf16_p2_T65536_d64_c128"
+    w = dict(inputs.WORKLOADS[name])
+    assert binding.power_attn_resolved_chunk(binding.make_problem(w["B"], w["H"], w["T"], w["d"], w["d"], w["p"], 0)) == 256
+    Q, K, V, G = inputs.make_workload(name)
+    print("case", name, "chunk 0", flush=True)
+    got = run_fwd_bwd(Q, K, V, G, w["p"], 0, "bf16", keep_state=True)
+    for k, a in got.items():
+        assert np.isfinite(a).all(), k
+    b, h = 0, 7
+    O_ref, Z_ref = orc.fwd_chunked(Q[b, h], K[b, h], V[b, h], w["p"], 256)
+    dQ_ref, dK_ref, dV_ref = orc.bwd_chunked(Q[b, h], K[b, h], V[b, h], G[b, h], w["p"], 256)
+    assert_close({k: a[b, h] for k, a in got.items()}, dict(O=O_ref, Z=Z_ref, dQ=dQ_ref, dK=dK_ref, dV=dV_ref),
+                 "bf16", f"{name} chunk 0 head (0,7) vs chunked oracle")
+    w["chunk"] = 256
+    _check_sampled(name, got, Q, K, V, G, w, [(0, hh) for hh in (0, 3, 7, 11)], n_rows=6, n_cols=12,
+                   ref_head=((b, h), (O_ref, Z_ref)))
+
+
 def test_config2_forward():
     """bf16 forward, p=2, B4 H12 T8192 d64 chunk 128."""
     name = "cfg2_bf16_p2_T8192_d64_c128"
