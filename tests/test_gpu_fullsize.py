@@ -11,7 +11,7 @@ import pytest
 from oracle import power_attn_oracle as orc
 from paper_2507_04239_amd import inputs
 
-from gpu_util import TOL, assert_close, rel_l2, run_fwd_bwd
+from gpu_util import ROW_TOL, TOL, assert_close, max_row_err, rel_l2, run_fwd_bwd
 
 pytestmark = pytest.mark.gpu
 
@@ -43,20 +43,23 @@ def _check_sampled(name, got, Q, K, V, G, w, heads, n_rows, n_cols, ref_head=Non
                 pairs = [orc.bwd_dkdv_col(q, k, v, G[b, h], O_full, Z_full, j, p) for j in cols]
                 errs["dK"].append((got["dK"][b, h][cols], np.stack([a for a, _ in pairs])))
                 errs["dV"].append((got["dV"][b, h][cols], np.stack([c for _, c in pairs])))
-    report = {}
+    report, rows_off = {}, {}
     for key, lst in errs.items():
         if lst:
             g = np.concatenate([a.reshape(len(a), -1) for a, _ in lst])
             r = np.concatenate([c.reshape(len(c), -1) for _, c in lst])
             report[key] = rel_l2(g, r)
-    print(f"{name} sampled: " + " ".join(f"{k}={v:.2e}" for k, v in report.items()), flush=True)
+            rows_off[key] = max_row_err(g, r)     # worst sampled row against the rms norm of the sampled rows
+    print(f"{name} sampled: " + " ".join(f"{k}={v:.2e} (row {rows_off[k]:.2e})" for k, v in report.items()), flush=True)
     for key, lst in errs.items():
-        if lst and not report[key] <= TOL[dtype]:
+        if lst and not (report[key] <= TOL[dtype] and rows_off[key] <= ROW_TOL[dtype]):
             for g, r in lst:
                 per_row = np.linalg.norm((g - r).reshape(len(g), -1), axis=1)
                 print(f"  {key}: |err| per sampled row {np.round(per_row, 4)} |ref| {np.round(np.linalg.norm(r.reshape(len(r), -1), axis=1), 4)}", flush=True)
     bad = {k: v for k, v in report.items() if not v <= TOL[dtype]}
     assert not bad, f"{name}: sampled relative L2 error above {TOL[dtype]}: {bad}"
+    bad = {k: v for k, v in rows_off.items() if not v <= ROW_TOL[dtype]}
+    assert not bad, f"{name}: a sampled row is off by more than {ROW_TOL[dtype]} of the rms row norm: {bad}"
 
 
 def test_headline_config3_fwd_bwd():
@@ -128,32 +131,38 @@ def test_chunk_size_invariance_on_device():
 
 
 def test_p4_config4_shape_reduced_batch():
-    """bf16 fwd+bwd, p=4, d=32, chunk 128, T=16384 (config 4's head shape; one of its 16 heads:
-    the degree-4 state of one head is already 128 x 52360 x 33 floats)."""
+    """Config 4 as stated (bf16 fwd+bwd, p=4, d=32, chunk 128, T=16384), one of its 16 heads - the chunked
+    form of this degree runs on the vector-ALU family, whose state of one head is already 128 x 52360 x 33
+    floats.  Covered: O and Z of every row by the definition, 12 sampled rows of dQ, 12 sampled columns of
+    dK and dV.  Not covered here: the other 15 heads (B2 H8), which test_config4_attention_form_full_shape
+    runs in the attention form."""
     w = dict(inputs.WORKLOADS["cfg4_bf16_p4_T16384_d32_c128"])
-    Q, K, V, G = inputs.make_qkvg(1, 1, w["T"], w["d"], seed=1004, dtype="bf16")
+    Q, K, V, G = (a.astype(np.float64) for a in inputs.make_qkvg(1, 1, w["T"], w["d"], seed=1004, dtype="bf16"))
     print("case cfg4 one head", flush=True)
     got = run_fwd_bwd(Q, K, V, G, 4, w["chunk"], "bf16")
-    w1 = dict(w, B=1, H=1)
-    O_ref, Z_ref = orc.fwd_chunked(Q[0, 0][:2048], K[0, 0][:2048], V[0, 0][:2048], 4, w["chunk"])
-    assert rel_l2(got["O"][0, 0][:2048], O_ref) <= TOL["bf16"]
-    assert rel_l2(got["Z"][0, 0][:2048], Z_ref) <= TOL["bf16"]
-    _check_sampled("cfg4", got, Q, K, V, G, w1, [(0, 0)], n_rows=12, n_cols=0)
+    for k, a in got.items():
+        assert np.isfinite(a).all(), k
+    O_ref, Z_ref = orc.fwd_quadratic(Q[0, 0], K[0, 0], V[0, 0], 4)
+    assert_close({k: got[k][0, 0] for k in ("O", "Z")}, dict(O=O_ref, Z=Z_ref), "bf16", "cfg4 chunk 128, one head, by the definition")
+    _check_sampled("cfg4", got, Q, K, V, G, dict(w, B=1, H=1), [(0, 0)], n_rows=12, n_cols=12, ref_head=((0, 0), (O_ref, Z_ref)))
 
 
 def test_d128_config5_shape_reduced_batch():
-    """bf16 fwd+bwd, p=2, d=128, chunk 256, T=32768 (config 5's head shape; one of its 128 heads)."""
+    """Config 5 as stated (bf16 fwd+bwd, p=2, d=128, chunk 256, T=32768), two of its 128 heads.  Covered:
+    one head, every output (O, Z, dQ, dK, dV) against the chunked float64 oracle; the other head, sampled
+    rows of O, Z, dQ by the definition.  Not covered here: the remaining 126 heads of B8 H16."""
     w = dict(inputs.WORKLOADS["cfg5_bf16_p2_T32768_d128_c256"])
-    Q, K, V, G = inputs.make_qkvg(1, 1, w["T"], w["d"], seed=1005, dtype="bf16")
-    print("case cfg5 one head", flush=True)
+    Q, K, V, G = inputs.make_qkvg(1, 2, w["T"], w["d"], seed=1005, dtype="bf16")
+    print("case cfg5 two heads", flush=True)
     got = run_fwd_bwd(Q, K, V, G, 2, w["chunk"], "bf16")
     for k, a in got.items():
         assert np.isfinite(a).all(), k
-    n0 = 1024   # the first four chunks, every output, against the chunked oracle (dK, dV need the whole future: not here)
-    O_ref, Z_ref = orc.fwd_chunked(Q[0, 0][:n0], K[0, 0][:n0], V[0, 0][:n0], 2, w["chunk"])
-    assert rel_l2(got["O"][0, 0][:n0], O_ref) <= TOL["bf16"]
-    assert rel_l2(got["Z"][0, 0][:n0], Z_ref) <= TOL["bf16"]
-    _check_sampled("cfg5", got, Q, K, V, G, dict(w, B=1, H=1), [(0, 0)], n_rows=12, n_cols=0)
+    h = 1
+    O_ref, Z_ref = orc.fwd_chunked(Q[0, h], K[0, h], V[0, h], 2, w["chunk"])
+    dQ_ref, dK_ref, dV_ref = orc.bwd_chunked(Q[0, h], K[0, h], V[0, h], G[0, h], 2, w["chunk"])
+    assert_close({k: a[0, h] for k, a in got.items()}, dict(O=O_ref, Z=Z_ref, dQ=dQ_ref, dK=dK_ref, dV=dV_ref),
+                 "bf16", "cfg5 chunk 256, head 1 vs chunked oracle")
+    _check_sampled("cfg5", got, Q, K, V, G, dict(w, B=1, H=2), [(0, 0)], n_rows=12, n_cols=0)
 
 
 def test_headline_shape_gated():
