@@ -4,10 +4,12 @@ import numpy as np
 
 TOL = {"f32": 1e-4, "bf16": 2e-2}   # relative L2 error per tensor (the bar the benchmark names)
 # Per-row bound: no single row (one token's vector, or one scalar of Z / dlog_g) may be off by more than
-# this fraction of the root-mean-square row norm of the reference.  The tensor-level bar alone lets one
-# entirely wrong row of a 4096-row tensor through (sqrt(1/4096) = 1.6e-2); a wrong row scores about 1.4
-# here, one that is 30 % off about 0.3.  Rounding alone reaches 3-5 times the tensor-level error in the
-# worst row (observed: bf16 1.2e-2, f32 2e-6), so the limit sits at 2.5 x the tensor-level bar.
+# this fraction of its own norm or of the root-mean-square row norm of the reference, whichever is
+# larger (gradient rows are heavy-tailed: a few are many times the typical size, and their rounding
+# error grows with them).  The tensor-level bar alone lets one entirely wrong row of a 4096-row tensor
+# through (sqrt(1/4096) = 1.6e-2); a wrong row scores about 1 here, one that is 30 % off about 0.3.
+# Rounding alone reaches up to ten times the tensor-level error in the worst row (observed on the GPU:
+# bf16 up to 4.2e-2 at 3-5e-3 per tensor, f32 2e-6), so the limit sits at 2.5 x the tensor-level bar.
 ROW_TOL = {"f32": 2.5e-4, "bf16": 5e-2}
 
 
@@ -26,17 +28,18 @@ def max_over_rms(got, want):
 
 
 def max_row_err(got, want):
-    """max_i |got_i - want_i|_2 / rms_i |want_i|_2 over the rows (last axis = one row; 1-D: every
-    element is a row)."""
+    """max_i |got_i - want_i|_2 / max(|want_i|_2, rms_i |want_i|_2) over the rows (last axis = one row;
+    1-D: every element is a row)."""
     want = np.asarray(want, dtype=np.float64)
     got = np.asarray(got, dtype=np.float64)
     if want.ndim <= 1:
         want, got = want.reshape(-1, 1), got.reshape(-1, 1)
     else:
         want, got = want.reshape(-1, want.shape[-1]), got.reshape(-1, got.shape[-1])
-    rms = np.sqrt(np.mean(np.sum(want ** 2, axis=1)))
+    norm = np.sqrt(np.sum(want ** 2, axis=1))
+    rms = np.sqrt(np.mean(norm ** 2))
     err = np.sqrt(np.sum((got - want) ** 2, axis=1))
-    return float(err.max() / rms) if rms > 0 else float(err.max())
+    return float((err / np.maximum(norm, rms)).max()) if rms > 0 else float(err.max())
 
 
 def to_dev(a, dtype):
