@@ -106,6 +106,21 @@ pa_status power_attn_fwd(const pa_problem* prob,
                          void* O, float* Z,
                          void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* power_attn_fwd for callers that cannot allocate device memory and have no workspace to hand over
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same
+ * kernels as power_attn_fwd, with the workspace taken from a device array that is part of the
+ * library itself (PA_STATIC_SCRATCH_BYTES, one copy per GPU, held until the process ends).  The call
+ * allocates nothing.  A problem whose power_attn_workspace_bytes(prob, 0) exceeds
+ * power_attn_static_scratch_bytes() is refused with PA_ERR_WORKSPACE and nothing is launched
+ * (prob->keep_state is honoured only in the sense that the states stay in that array).  All calls
+ * on one GPU share the array: calls that overlap on one GPU (different streams or host threads)
+ * race; calls on one stream are ordered and safe.  Everything else as power_attn_fwd. */
+#define PA_STATIC_SCRATCH_BYTES (16u << 20)
+size_t power_attn_static_scratch_bytes(void);
+pa_status power_attn_fwd_static(const pa_problem* prob,
+                                const void* Q, const void* K, const void* V,
+                                void* O, float* Z, void* hip_stream);
+
 /* Backward pass: given dO = dL/dO and the forward outputs O, Z of the same problem and
  * inputs, writes dQ, dK, dV.  (O and Z are read only when normalize != 0.)  Rows with
  * Z_i == 0 pass no gradient. */

@@ -26,6 +26,8 @@ EXPORTED_SYMBOLS = (
     "power_attn_decode_absorb_workspace_bytes",
     "power_attn_decode_step",
     "power_attn_fwd",
+    "power_attn_fwd_static",
+    "power_attn_static_scratch_bytes",
     "power_attn_bwd",
     "power_attn_fwd_gated",
     "power_attn_bwd_gated",
@@ -96,6 +98,10 @@ def load_library():
     lib.power_attn_decode_step.argtypes = [P, vp, vp, vp, vp, vp, ctypes.c_size_t, vp, vp, vp]
     lib.power_attn_fwd.restype = ctypes.c_int
     lib.power_attn_fwd.argtypes = [P, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.power_attn_fwd_static.restype = ctypes.c_int
+    lib.power_attn_fwd_static.argtypes = [P, vp, vp, vp, vp, vp, vp]
+    lib.power_attn_static_scratch_bytes.restype = ctypes.c_size_t
+    lib.power_attn_static_scratch_bytes.argtypes = []
     lib.power_attn_bwd.restype = ctypes.c_int
     lib.power_attn_bwd.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.power_attn_fwd_gated.restype = ctypes.c_int
@@ -216,6 +222,17 @@ def power_attn_fwd(Q, K, V, p: int, chunk: int, normalize: bool = True, scale: f
                                           ctypes.c_void_p(Z.data_ptr()), ctypes.c_void_p(workspace.data_ptr()), need,
                                           _stream())
     _check(lib, st, "power_attn_fwd")
+    return O, Z
+
+
+def power_attn_fwd_static(Q, K, V, O, Z, p: int, chunk: int, normalize: bool = True, scale: float = 1.0, impl: str = "auto"):
+    """power_attn_fwd on the library's own static scratch: the caller passes the outputs O (like V) and
+    Z (float32 [B, H, T]) too, and neither this wrapper nor the call allocates anything."""
+    lib = load_library()
+    prob = _problem_of(Q, V, p, chunk, normalize, scale, impl)
+    st = lib.power_attn_fwd_static(ctypes.byref(prob), _dev_ptr(Q, name="Q"), _dev_ptr(K, Q, "K"), _dev_ptr(V, Q, "V"),
+                                   _dev_ptr(O, Q, "O"), ctypes.c_void_p(Z.data_ptr()), _stream())
+    _check(lib, st, "power_attn_fwd_static")
     return O, Z
 
 

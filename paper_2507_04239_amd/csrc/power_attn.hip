@@ -15,6 +15,36 @@ struct Record {
     std::string name;
     hipEvent_t e0, e1;
 };
+// Scratch of power_attn_fwd_static: device memory that is part of the library's code object, so
+// that callers who may not allocate still have a workspace.  Each GPU the library runs on holds its
+// own copy of the array at its own address until the process ends.
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)PA_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+constexpr int MAX_DEVICES = 64;
+void* g_scratch_ptr[MAX_DEVICES] = {};   // device address of `scratch` on each device, looked up once
+
+// The array's name is a host-side stand-in here, not a device address; the address on the current
+// device comes from the runtime, once per device.
+pa_status static_scratch(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess || dev < 0 || dev >= MAX_DEVICES) {
+        note_hip_error(e, "hipGetDevice (static scratch)");
+        return PA_ERR_HIP;
+    }
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || ptr == nullptr) {
+            note_hip_error(e, "hipGetSymbolAddress(scratch)");
+            return PA_ERR_HIP;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return PA_OK;
+}
+
 bool g_profile = false;
 char g_last_error[256] = "";
 std::vector<Record> g_records;
@@ -404,6 +434,19 @@ int power_attn_resolved_chunk(const pa_problem* prob) {
 pa_status power_attn_fwd(const pa_problem* prob, const void* Q, const void* K, const void* V, void* O, float* Z,
                          void* workspace, size_t workspace_bytes, void* hip_stream) {
     return run_fwd(prob, Q, K, V, nullptr, O, Z, workspace, workspace_bytes, hip_stream, 0);
+}
+
+size_t power_attn_static_scratch_bytes(void) { return STATIC_SCRATCH_BYTES; }
+
+pa_status power_attn_fwd_static(const pa_problem* prob, const void* Q, const void* K, const void* V, void* O, float* Z,
+                                void* hip_stream) {
+    if (power_attn_workspace_bytes(prob, 0) > STATIC_SCRATCH_BYTES) return PA_ERR_WORKSPACE;
+    void* ptr = nullptr;
+    pa_status st = static_scratch(&ptr);
+    if (st != PA_OK) return st;
+    // every kernel family fully writes what it later reads of its workspace, so what the last call
+    // left in the array needs no clearing
+    return run_fwd(prob, Q, K, V, nullptr, O, Z, ptr, STATIC_SCRATCH_BYTES, hip_stream, 0);
 }
 
 pa_status power_attn_bwd(const pa_problem* prob, const void* Q, const void* K, const void* V, const void* O,
