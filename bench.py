@@ -186,7 +186,7 @@ def main():
     ap.add_argument("--workload", default=None, help="name from paper_2507_04239_amd.inputs.WORKLOADS")
     ap.add_argument("--chunk", type=int, default=None,
                     help="chunk size instead of the workload's own; 0 lets the library choose (attention form or chunked)")
-    ap.add_argument("--impl", default="auto", choices=["auto", "generic", "mfma"])
+    ap.add_argument("--impl", default="auto", choices=["auto", "generic", "mfma", "resident"])
     ap.add_argument("--cpu-sample-heads", type=int, default=2, help="heads the CPU oracle is timed on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
@@ -282,6 +282,9 @@ def main():
                                       "hbm_gbs": by[role] / sec / 1e9, "frac_hbm_peak": by[role] / sec / 1e9 / PEAK_HBM_GBS})
     # The dominant kernel, and the roof that bounds it: the one whose lower bound on its time is larger.
     credited = {k: v for k, v in kernels.items() if k in KERNEL_ROLE}
+    if not credited:
+        print(json.dumps({"ms_per_step": ms_per_step, "kernels": per_kernel}), flush=True)
+        return
     dom = max(credited, key=lambda k: credited[k][1])
     role, peak = KERNEL_ROLE[dom]
     dom_ms = credited[dom][1] / credited[dom][0]

@@ -54,9 +54,12 @@ typedef enum { PA_DTYPE_F32 = 0, PA_DTYPE_BF16 = 1 } pa_dtype;
 typedef enum {
     PA_IMPL_AUTO    = 0,
     PA_IMPL_GENERIC = 1,  /* float32 arithmetic on the vector ALUs; any 1 <= p <= 4, d, v <= 128; both dtypes */
-    PA_IMPL_MFMA    = 2   /* bf16 MFMA with float32 accumulation; bf16 only.  Chunked form: p = 2, d = v = 64,
+    PA_IMPL_MFMA    = 2,  /* bf16 MFMA with float32 accumulation; bf16 only.  Chunked form: p = 2, d = v = 64,
                              chunk a multiple of 128.  Attention form (chunk == T; any T, or with
                              gates T a multiple of 128, of 256 at d = 32): p in {2, 3, 4}, d = v in {32, 64, 128}.  See power_attn_supported() */
+    PA_IMPL_RESIDENT = 3  /* the chunked bf16 MFMA kernels that keep the chunk states in registers while they walk the
+                             sequence (no chunk state is written to memory): p = 2, d = v = 64, chunk a multiple of 128,
+                             not gated */
 } pa_impl;
 
 typedef struct {

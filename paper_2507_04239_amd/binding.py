@@ -14,8 +14,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_NAME = "libpower_attn.so"
 
 PA_DTYPE_F32, PA_DTYPE_BF16 = 0, 1
-PA_IMPL_AUTO, PA_IMPL_GENERIC, PA_IMPL_MFMA = 0, 1, 2
-_IMPL = {"auto": PA_IMPL_AUTO, "generic": PA_IMPL_GENERIC, "mfma": PA_IMPL_MFMA}
+PA_IMPL_AUTO, PA_IMPL_GENERIC, PA_IMPL_MFMA, PA_IMPL_RESIDENT = 0, 1, 2, 3
+_IMPL = {"auto": PA_IMPL_AUTO, "generic": PA_IMPL_GENERIC, "mfma": PA_IMPL_MFMA, "resident": PA_IMPL_RESIDENT}
 
 EXPORTED_SYMBOLS = (
     "power_attn_workspace_bytes",

@@ -134,11 +134,20 @@ __device__ __forceinline__ int heavy_first(int nblocks, bool longest_is_last) {
 // WPE: waves per SIMD the register budget is set for.  With 2 (at most 256 registers) the MFMAs
 // write plain vector registers; with 1 the compiler moves every score through the accumulation
 // registers and back, which costs more vector-ALU instructions than the arithmetic itself.
-template <int P, int HD, int OWN, int WPE, bool GATED>
+// CHUNKED (the in-chunk part of the chunked form, App. E.1, for any degree and head size): a query sees the
+// keys of its own chunk of `cs` tokens only (cs a multiple of the 64-key tile), and the part that comes
+// through the state has been left by other kernels: part[slab][bh][t][v] (float32, `nslab` slabs, summed
+// here) joins the numerator and zpart[bh][t] the denominator before the division.
+struct ChunkedIn {
+    int cs = 0, nslab = 0;
+    const float* part = nullptr;
+    const float* zpart = nullptr;
+};
+template <int P, int HD, int OWN, int WPE, bool GATED, bool CHUNKED = false>
 __global__ __launch_bounds__(256, WPE) void k_attn_fwd(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
                                                        const bf16_t* __restrict__ V, bf16_t* __restrict__ O,
                                                        float* __restrict__ Z, int T, float scale, int normalize,
-                                                       const float* __restrict__ bl) {
+                                                       const float* __restrict__ bl, ChunkedIn ck) {
     constexpr int NI = OWN / 16, NK = HD / 32, NV = HD / 16, WG = 4 * OWN;
     extern __shared__ __attribute__((aligned(16))) unsigned char attn_smem[];
     AttnTile<HD>* kt = reinterpret_cast<AttnTile<HD>*>(attn_smem);      // [2]
@@ -223,23 +232,26 @@ __global__ __launch_bounds__(256, WPE) void k_attn_fwd(const bf16_t* __restrict_
     };
 
     const int ntile = (min(i0 + WG, T) + AT - 1) / AT;   // key tiles 0 .. ntile - 1 reach the block's last query
+    // chunked: the walk starts at the chunk of the block's first query, and a wave skips the tiles before its own chunk
+    const int t_lo = CHUNKED ? (i0 / ck.cs) * ck.cs / AT : 0;
+    const int k_lo = CHUNKED ? (q0 / ck.cs) * ck.cs : 0;
     uint4 kr[HD / 32], vr[HD / 32];
     float gb = 0.f, gf = 0.f;
-    PA_TILE_LOAD(kr, Kh, 0, false)
-    PA_TILE_LOAD(vr, Vh, 0, false)
+    PA_TILE_LOAD(kr, Kh, t_lo * AT, false)
+    PA_TILE_LOAD(vr, Vh, t_lo * AT, false)
     if (GATED) gate_tile_load(gb, gf, bl_head, 0, AT - 1, 1.f, tid, T);
     PA_TILE_STORE(kt[0], kr)
     PA_TILE_STORE(vt[0], vr)
     if (GATED) gate_tile_store(gtile[0], gb, gf, tid);
     __syncthreads();
-    for (int t = 0; t < ntile; ++t) {
-        const int buf = t & 1, key0 = t * AT;
+    for (int t = t_lo; t < ntile; ++t) {
+        const int buf = (t - t_lo) & 1, key0 = t * AT;
         if (t + 1 < ntile) {
             PA_TILE_LOAD(kr, Kh, key0 + AT, false)
             PA_TILE_LOAD(vr, Vh, key0 + AT, false)
             if (GATED) gate_tile_load(gb, gf, bl_head, key0 + AT, key0 + 2 * AT - 1, 1.f, tid, T);
         }
-        if (active && key0 <= q0 + OWN - 1) {
+        if (active && key0 <= q0 + OWN - 1 && key0 >= k_lo) {
             if (key0 + AT - 1 > q0) tile(std::true_type{}, buf, key0);
             else tile(std::false_type{}, buf, key0);
         }
@@ -254,10 +266,20 @@ __global__ __launch_bounds__(256, WPE) void k_attn_fwd(const bf16_t* __restrict_
     if (!active) return;
 #pragma unroll
     for (int ib = 0; ib < NI; ++ib) {
-        const float z = zacc[ib][0];
-        const float inv = normalize ? (z != 0.f ? 1.f / z : 0.f) : 1.f;
         if (q0 + 16 * ib + r16 >= T) continue;      // past the end of a sequence that is not a multiple of the block
         const size_t row = head + q0 + 16 * ib + r16;
+        float z = zacc[ib][0];
+        if (CHUNKED) {
+            z += ck.zpart[row];
+            const size_t slab_stride = (size_t)gridDim.y * T * HD;
+            for (int sl = 0; sl < ck.nslab; ++sl)
+#pragma unroll
+                for (int vb = 0; vb < NV; ++vb) {
+                    const float4 pv = *(const float4*)(ck.part + sl * slab_stride + row * HD + 16 * vb + 4 * g);
+                    acc[vb][ib][0] += pv.x; acc[vb][ib][1] += pv.y; acc[vb][ib][2] += pv.z; acc[vb][ib][3] += pv.w;
+                }
+        }
+        const float inv = normalize ? (z != 0.f ? 1.f / z : 0.f) : 1.f;
 #pragma unroll
         for (int vb = 0; vb < NV; ++vb) {
             bf16x4 o;
@@ -697,15 +719,15 @@ struct Shape {
     static constexpr int DKDV_OWN = HD == 32 ? 64 : 32, DKDV_WPE = HD == 128 ? 1 : 2;
 };
 
-template <int P, int HD, bool GATED>
+template <int P, int HD, bool GATED, bool CHUNKED = false>
 bool fwd_t(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* V, bf16_t* O, float* Z, int BH, int T, float scale,
-           int normalize, const float* bl) {
+           int normalize, const float* bl, ChunkedIn ck = ChunkedIn()) {
     constexpr int WG = 4 * Shape<HD>::FWD_OWN;
-    auto kern = k_attn_fwd<P, HD, Shape<HD>::FWD_OWN, Shape<HD>::FWD_WPE, GATED>;
+    auto kern = k_attn_fwd<P, HD, Shape<HD>::FWD_OWN, Shape<HD>::FWD_WPE, GATED, CHUNKED>;
     if (!allow_smem(kern, attn_smem_bytes<HD>())) return false;
-    LaunchScope ls("attn_fwd", s);
+    LaunchScope ls(CHUNKED ? "chunk_fwd" : "attn_fwd", s);
     hipLaunchKernelGGL(kern, dim3((T + WG - 1) / WG, BH), dim3(256), attn_smem_bytes<HD>(), s, Q, K, V, O, Z, T, scale, normalize,
-                       bl);
+                       bl, ck);
     return launch_ok();
 }
 
@@ -765,6 +787,21 @@ bool launch_attn_fwd(hipStream_t s, int p, int d, const bf16_t* Q, const bf16_t*
     PA_CASE(2, 32) PA_CASE(2, 64) PA_CASE(2, 128)
     PA_CASE(3, 32) PA_CASE(3, 64) PA_CASE(3, 128)
     PA_CASE(4, 32) PA_CASE(4, 64) PA_CASE(4, 128)
+#undef PA_CASE
+    return false;
+}
+
+bool launch_chunk_fwd(hipStream_t s, int p, int d, const bf16_t* Q, const bf16_t* K, const bf16_t* V, bf16_t* O, float* Z, int BH,
+                      int T, int cs, float scale, int normalize, const float* part, int nslab, const float* zpart) {
+    ChunkedIn ck;
+    ck.cs = cs;
+    ck.nslab = nslab;
+    ck.part = part;
+    ck.zpart = zpart;
+    if (cs % AT != 0 || T % cs != 0) return false;
+#define PA_CASE(PP, DD) \
+    if (p == PP && d == DD) return fwd_t<PP, DD, false, true>(s, Q, K, V, O, Z, BH, T, scale, normalize, nullptr, ck);
+    PA_CASE(2, 64) PA_CASE(2, 128)
 #undef PA_CASE
     return false;
 }

@@ -80,9 +80,11 @@ bool launch_scan(const char* name, hipStream_t s, bool rev, const bf16_t* Xt, co
                  bf16_t* gam, int BH, int T, int cs, float out_scale, const float* lam = nullptr);
 // `bl`, `qfac` / `kfac`: per-token gating arrays (see GateBuf), all null when not gated; gated dQ / dK kernels
 // also write q_i . dq_i (qdq) and k_j . dk_j (kdk) from their float32 accumulators
+// part (may be null): instead of reading the chunk state stC out, the kernel adds the nslab partial
+// read-outs part[slab][bh][t][:] (float32) that launch_res_walk left
 bool launch_fwd_chunk(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* Vt, const bf16_t* stC,
                       const bf16_t* gam, bf16_t* O, float* Z, int BH, int T, int cs, float scale, int normalize,
-                      const float* bl, const float* qfac);
+                      const float* bl, const float* qfac, const float* part = nullptr, int nslab = 0);
 bool launch_bwd_prep(hipStream_t s, const bf16_t* dO, const bf16_t* O, const float* Z, bf16_t* Gh, float* gz,
                      long long rows, int normalize);
 bool launch_bwd_dq(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* V, const bf16_t* Gh,
@@ -91,6 +93,33 @@ bool launch_bwd_dq(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t
 bool launch_bwd_dkdv(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* V, const bf16_t* Gh, const float* gz,
                      const bf16_t* Qt, const bf16_t* Ght, const bf16_t* rtC, const bf16_t* omg, bf16_t* dK, bf16_t* dV, int BH,
                      int T, int cs, float scale, const float* bl, const float* kfac, float* kdk);
+
+// ---- resident-state kernels (chunk states kept in registers; see mfma_resident.hip) ----------------
+struct ResidentPlan {
+    int nhp, nslab;            // half-pairs per wave; workgroups (slabs of state rows) per head
+    int nseg, seg_chunks;      // segments the sequence is cut into, chunks per segment
+    size_t acc_floats;         // accumulator floats per wave
+    size_t tot_bytes, part_bytes, gram_bytes;   // per-segment totals; per-slab partial read-outs; per-chunk Gram matrices
+};
+ResidentPlan resident_plan(int HD, int BH, int T, int cs);
+// One pass over the sequence with the state in registers.  readout = false: every segment but the last
+// adds up its own total into `tot`.  readout = true: each segment starts from the totals before it and
+// writes, per slab, part[slab][bh][t][:] = (state entering t's chunk)^T phi(Qr_t) * snap_scale.
+// rev: the state holds the chunks after the current one (state gradient).
+bool launch_res_walk(const char* name, hipStream_t s, int HD, bool rev, bool readout, const bf16_t* Xt, const bf16_t* Yt,
+                     const bf16_t* Qr, float* tot, float* part, int BH, int T, int cs, const ResidentPlan& pl,
+                     float snap_scale);
+// out[bh][n] (bf16, HD x HD) = out_scale * sum over the chunks before (rev: after) n of sum_t w_t x_t x_t^T;
+// gram: float32 scratch [BH][T / cs][HD][HD]; wgt may be null (w = 1)
+bool launch_gram(hipStream_t s, int HD, const bf16_t* Xt, const float* wgt, float* gram, bf16_t* out, int BH, int T, int cs,
+                 bool rev, float out_scale);
+
+// feature-major copy in blocks of 64 tokens for any head size the resident kernels take
+bool launch_transpose_hd(hipStream_t s, int HD, const bf16_t* in, bf16_t* out, int BH, int T);
+// normaliser terms per token from the HD x HD states gam[bh][T / cs]: vec[bh][t][:] = cvec * wgt_t * G x_t (float32),
+// sca[bh][t] = csca * x_t^T G x_t; vec, sca and wgt may each be null
+bool launch_gram_apply(hipStream_t s, int HD, const bf16_t* X, const bf16_t* gam, const float* wgt, float* vec, float* sca,
+                       int BH, int T, int cs, float cvec, float csca);
 
 // gating: xb[bh][n] = the sum over the pairs that straddle the end of chunk n, from the stored states
 bool launch_gate_boundary(hipStream_t s, const bf16_t* stC, const bf16_t* rtC, const bf16_t* gam, const bf16_t* omg, float* xb,
@@ -102,6 +131,11 @@ bool attn_shape_ok(int p, int d);
 // bl (null when not gated): [BH][T] running sums of the log-gates from the start of the sequence
 bool launch_attn_fwd(hipStream_t s, int p, int d, const bf16_t* Q, const bf16_t* K, const bf16_t* V, bf16_t* O, float* Z, int BH,
                      int T, float scale, int normalize, const float* bl = nullptr);
+// The in-chunk part of the chunked form on the attention-form kernels (keys of the query's own chunk of cs
+// tokens), plus what came through the state: part[slab][BH][T][d] (float32, nslab slabs) joins the numerator,
+// zpart[BH][T] the denominator
+bool launch_chunk_fwd(hipStream_t s, int p, int d, const bf16_t* Q, const bf16_t* K, const bf16_t* V, bf16_t* O, float* Z, int BH,
+                      int T, int cs, float scale, int normalize, const float* part, int nslab, const float* zpart);
 // Gated backward pass (bl non-null; T a multiple of attn_gate_block(d)): also leaves what the gradient of
 // the log-gates needs: qdq [BH][T] = q_i . dq_i, kdk [BH][T] = k_j . dk_j (from float32 accumulators) and
 // xb [BH][T / block] = the sum of e_ij a_ij over the pairs j <= end of block m < i.

@@ -53,6 +53,41 @@ Layout make_layout(const pa_problem& pr, bool backward) {
     return L;
 }
 
+// resident-state kernels: workspace of the forward pass (the backward part is appended)
+struct ResLayout {
+    ResidentPlan pl;
+    size_t off_kt, off_vt, off_gam, off_gram, off_tot, off_part, off_zpart;
+    size_t total;
+};
+ResLayout make_res_layout(const pa_problem& pr, bool backward) {
+    ResLayout L{};
+    const int BH = pr.B * pr.H;
+    L.pl = resident_plan(pr.d, BH, pr.T, pr.chunk);
+    const size_t tok = (size_t)BH * pr.T * pr.d * 2;
+    const size_t gm = (size_t)BH * (pr.T / pr.chunk) * pr.d * pr.d * 2;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        size_t o = off;
+        off = align_up(off + bytes, 256);
+        return o;
+    };
+    L.off_kt = take(tok);
+    L.off_vt = take(tok);
+    L.off_gam = take(gm);
+    L.off_gram = take(L.pl.gram_bytes);
+    L.off_tot = take(L.pl.tot_bytes);
+    L.off_part = take(L.pl.part_bytes);
+    L.off_zpart = take((size_t)BH * pr.T * sizeof(float));
+    (void)backward;
+    L.total = off;
+    return L;
+}
+bool resident_ok(const pa_problem& pr) {
+    return pr.dtype == PA_DTYPE_BF16 && pr.p == 2 && (pr.d == 64 || pr.d == 128) && pr.v == pr.d && pr.chunk > 0 &&
+           pr.chunk % QBLK == 0 && pr.T % pr.chunk == 0 && !pr.gated && (size_t)pr.B * pr.H <= 65535u;
+}
+bool use_resident(const pa_problem& pr) { return pr.impl == PA_IMPL_RESIDENT && resident_ok(pr); }
+
 bool chunked_ok(const pa_problem& pr) {
     return pr.dtype == PA_DTYPE_BF16 && pr.p == 2 && pr.d == DH && pr.v == DH && pr.chunk % QBLK == 0 &&
            (size_t)pr.B * pr.H <= 65535u;
@@ -90,13 +125,17 @@ AttnLayout make_attn_layout(const pa_problem& pr, bool backward) {
 int mfma_gate_fin_chunk(const pa_problem& pr) { return use_attn(pr) ? attn_gate_block(pr.d) : pr.chunk; }
 
 pa_status mfma_supported(const pa_problem& pr, bool backward) {
-    (void)backward;
+    if (pr.impl == PA_IMPL_RESIDENT) return resident_ok(pr) && !backward ? PA_OK : PA_ERR_UNSUPPORTED;
     return chunked_ok(pr) || attn_ok(pr) ? PA_OK : PA_ERR_UNSUPPORTED;
 }
 
-long long mfma_state_rows(const pa_problem& pr) { return use_attn(pr) ? 0 : (long long)NTILES * 64; }
+long long mfma_state_rows(const pa_problem& pr) {
+    if (use_resident(pr)) return (long long)(pr.d / 8) * (pr.d / 8 + 1) / 2 * 64;
+    return use_attn(pr) ? 0 : (long long)NTILES * 64;
+}
 
 size_t mfma_workspace_bytes(const pa_problem& pr, bool backward) {
+    if (use_resident(pr)) return make_res_layout(pr, backward).total;
     return use_attn(pr) ? make_attn_layout(pr, backward).total : make_layout(pr, backward).total;
 }
 
@@ -112,6 +151,35 @@ pa_status mfma_fwd(const Ctx& c, const void* Q, const void* K, const void* V, vo
     if (use_attn(pr)) {
         PA_TRY(launch_attn_fwd(c.stream, pr.p, pr.d, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (bf16_t*)O, Z, BH, pr.T,
                                pr.scale, pr.normalize, c.gate.bl))
+        return PA_OK;
+    }
+    if (use_resident(pr)) {
+        const ResLayout R = make_res_layout(pr, false);
+        bf16_t* Kt = (bf16_t*)(c.ws + R.off_kt);
+        bf16_t* Vt = (bf16_t*)(c.ws + R.off_vt);
+        bf16_t* Gam = (bf16_t*)(c.ws + R.off_gam);
+        float* gram = (float*)(c.ws + R.off_gram);
+        float* tot = (float*)(c.ws + R.off_tot);
+        float* part = (float*)(c.ws + R.off_part);
+        float* zpart = (float*)(c.ws + R.off_zpart);
+        PA_TRY(launch_transpose_hd(c.stream, pr.d, (const bf16_t*)K, Kt, BH, pr.T))
+        PA_TRY(launch_transpose_hd(c.stream, pr.d, (const bf16_t*)V, Vt, BH, pr.T))
+        PA_TRY(launch_gram(c.stream, pr.d, Kt, nullptr, gram, Gam, BH, pr.T, pr.chunk, false, 1.0f))
+        if (R.pl.nseg > 1)
+            PA_TRY(launch_res_walk("res_state_totals", c.stream, pr.d, false, false, Kt, Vt, nullptr, tot, nullptr, BH, pr.T,
+                                   pr.chunk, R.pl, 1.0f))
+        PA_TRY(launch_res_walk("res_state_walk", c.stream, pr.d, false, true, Kt, Vt, (const bf16_t*)Q, tot, part, BH, pr.T,
+                               pr.chunk, R.pl, pr.scale * pr.scale))
+        if (pr.d == DH) {
+            PA_TRY(launch_fwd_chunk(c.stream, (const bf16_t*)Q, (const bf16_t*)K, Vt, nullptr, Gam, (bf16_t*)O, Z, BH, pr.T,
+                                    pr.chunk, pr.scale, pr.normalize, nullptr, nullptr, part, R.pl.nslab))
+        } else {
+            // the normaliser's share of the denominator, then the in-chunk part on the attention-form kernel
+            PA_TRY(launch_gram_apply(c.stream, pr.d, (const bf16_t*)Q, Gam, nullptr, nullptr, zpart, BH, pr.T, pr.chunk, 0.f,
+                                     pr.scale * pr.scale))
+            PA_TRY(launch_chunk_fwd(c.stream, pr.p, pr.d, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (bf16_t*)O, Z, BH,
+                                    pr.T, pr.chunk, pr.scale, pr.normalize, part, R.pl.nslab, zpart))
+        }
         return PA_OK;
     }
     const Layout L = make_layout(pr, false);

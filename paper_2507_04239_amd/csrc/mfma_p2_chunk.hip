@@ -423,13 +423,16 @@ __device__ __forceinline__ void load_cols(float (&out)[4], const float* __restri
 
 // ---- forward chunk kernel -------------------------------------------------------------------------
 // acc[vb][ib] = O^T: 16 value columns x 16 queries.
-template <bool GATED>
+// PARTIAL: the state's read-out has already been taken (resident-state walk); its per-slab partial
+// sums part[slab][bh][t][v] (float32, already scaled) are added instead of streaming the state.
+template <bool GATED, bool PARTIAL = false>
 __global__ __launch_bounds__(128, 2) void k_mfma_fwd_chunk(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
                                                            const bf16_t* __restrict__ Vt, const bf16_t* __restrict__ StC,
                                                            const bf16_t* __restrict__ Gam, bf16_t* __restrict__ O,
                                                            float* __restrict__ Z, int T, int cs, float scale,
                                                            int normalize, const float* __restrict__ bl,
-                                                           const float* __restrict__ qfac) {
+                                                           const float* __restrict__ qfac,
+                                                           const float* __restrict__ part, int nslab) {
     __shared__ __attribute__((aligned(16))) ChunkSmem<RING_RO> sm;
     XbRow* Xb = sm.xb;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -516,7 +519,21 @@ __global__ __launch_bounds__(128, 2) void k_mfma_fwd_chunk(const bf16_t* __restr
                 zsum[ib] += GATED ? qf[ib] * zs : zs;
             }
         }
-        readout<RING_RO, 2, false, GATED>(acc, StC + (size_t)(bh * nstate + n) * STATE_ELEMS, sm, s2, wv, wv, lane, qf);
+        if (PARTIAL) {
+            const size_t slab_stride = (size_t)gridDim.y * T * DH;
+#pragma unroll
+            for (int ib = 0; ib < 4; ++ib) {
+                const float* prow = part + (head_tok + i0 + 64 * wv + 16 * ib + r16) * DH + 4 * g;
+                for (int sl = 0; sl < nslab; ++sl)
+#pragma unroll
+                    for (int vb = 0; vb < 4; ++vb) {
+                        const float4 pv = *(const float4*)(prow + sl * slab_stride + 16 * vb);
+                        acc[vb][ib][0] += pv.x; acc[vb][ib][1] += pv.y; acc[vb][ib][2] += pv.z; acc[vb][ib][3] += pv.w;
+                    }
+            }
+        } else {
+            readout<RING_RO, 2, false, GATED>(acc, StC + (size_t)(bh * nstate + n) * STATE_ELEMS, sm, s2, wv, wv, lane, qf);
+        }
     }
 
 #pragma unroll
@@ -968,14 +985,17 @@ bool launch_gate_boundary(hipStream_t s, const bf16_t* stC, const bf16_t* rtC, c
 // both null when the problem is not gated
 bool launch_fwd_chunk(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* Vt, const bf16_t* stC,
                       const bf16_t* gam, bf16_t* O, float* Z, int BH, int T, int cs, float scale, int normalize,
-                      const float* bl, const float* qfac) {
-    LaunchScope ls("mfma_fwd_chunk", s);
-    if (bl != nullptr)
-        hipLaunchKernelGGL(k_mfma_fwd_chunk<true>, dim3(T / QBLK, BH), dim3(128), 0, s, Q, K, Vt, stC, gam, O, Z, T, cs, scale,
-                           normalize, bl, qfac);
+                      const float* bl, const float* qfac, const float* part, int nslab) {
+    LaunchScope ls(part != nullptr ? "mfma_fwd_chunk_partial" : "mfma_fwd_chunk", s);
+    if (part != nullptr)
+        hipLaunchKernelGGL((k_mfma_fwd_chunk<false, true>), dim3(T / QBLK, BH), dim3(128), 0, s, Q, K, Vt, stC, gam, O, Z, T, cs,
+                           scale, normalize, bl, qfac, part, nslab);
+    else if (bl != nullptr)
+        hipLaunchKernelGGL((k_mfma_fwd_chunk<true>), dim3(T / QBLK, BH), dim3(128), 0, s, Q, K, Vt, stC, gam, O, Z, T, cs, scale,
+                           normalize, bl, qfac, part, nslab);
     else
-        hipLaunchKernelGGL(k_mfma_fwd_chunk<false>, dim3(T / QBLK, BH), dim3(128), 0, s, Q, K, Vt, stC, gam, O, Z, T, cs, scale,
-                           normalize, bl, qfac);
+        hipLaunchKernelGGL((k_mfma_fwd_chunk<false>), dim3(T / QBLK, BH), dim3(128), 0, s, Q, K, Vt, stC, gam, O, Z, T, cs, scale,
+                           normalize, bl, qfac, part, nslab);
     return launch_ok();
 }
 
