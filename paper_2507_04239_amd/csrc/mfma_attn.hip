@@ -139,9 +139,10 @@ __device__ __forceinline__ int heavy_first(int nblocks, bool longest_is_last) {
 // through the state has been left by other kernels: part[slab][bh][t][v] (float32, `nslab` slabs, summed
 // here) joins the numerator and zpart[bh][t] the denominator before the division.
 struct ChunkedIn {
-    int cs = 0, nslab = 0;
-    const float* part = nullptr;
-    const float* zpart = nullptr;
+    int cs = 0, nslab = 0, nslab2 = 0;
+    const float* part = nullptr;     // forward: numerator; dQ kernel: dQ; dK / dV kernel: dK
+    const float* part2 = nullptr;    // dK / dV kernel: dV (nslab2 slabs)
+    const float* zpart = nullptr;    // forward: denominator
 };
 template <int P, int HD, int OWN, int WPE, bool GATED, bool CHUNKED = false>
 __global__ __launch_bounds__(256, WPE) void k_attn_fwd(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
@@ -330,11 +331,12 @@ __global__ __launch_bounds__(256) void k_attn_prep(const bf16_t* __restrict__ dO
 
 // ---- backward: dQ -----------------------------------------------------------------------------------
 // acc[fb][ib] = dQ^T: feature 16 fb + 4g + r, query 16 ib + r16.
-template <int P, int HD, int OWN, int WPE, bool GATED>
+template <int P, int HD, int OWN, int WPE, bool GATED, bool CHUNKED = false>
 __global__ __launch_bounds__(256, WPE) void k_attn_dq(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
                                                  const bf16_t* __restrict__ V, const bf16_t* __restrict__ Gh,
                                                  const float* __restrict__ gz, bf16_t* __restrict__ dQ, int T,
-                                                 float scale, const float* __restrict__ bl, float* __restrict__ qdq) {
+                                                 float scale, const float* __restrict__ bl, float* __restrict__ qdq,
+                                                 ChunkedIn ck) {
     constexpr int NI = OWN / 16, NK = HD / 32, NF = HD / 16, WG = 4 * OWN;
     extern __shared__ __attribute__((aligned(16))) unsigned char attn_smem[];
     AttnTile<HD>* kt = reinterpret_cast<AttnTile<HD>*>(attn_smem);      // [2]
@@ -428,23 +430,25 @@ __global__ __launch_bounds__(256, WPE) void k_attn_dq(const bf16_t* __restrict__
     };
 
     const int ntile = (min(i0 + WG, T) + AT - 1) / AT;
+    const int t_lo = CHUNKED ? (i0 / ck.cs) * ck.cs / AT : 0;     // chunked: keys of the query's own chunk only
+    const int k_lo = CHUNKED ? (q0 / ck.cs) * ck.cs : 0;
     uint4 kr[HD / 32], vr[HD / 32];
     float gb = 0.f, gf2 = 0.f;
-    PA_TILE_LOAD(kr, Kh, 0, false)
-    PA_TILE_LOAD(vr, Vh, 0, false)
+    PA_TILE_LOAD(kr, Kh, t_lo * AT, false)
+    PA_TILE_LOAD(vr, Vh, t_lo * AT, false)
     if (GATED) gate_tile_load(gb, gf2, bl_head, 0, AT - 1, 1.f, tid, T);
     PA_TILE_STORE(kt[0], kr)
     PA_TILE_STORE(vt[0], vr)
     if (GATED) gate_tile_store(gtile[0], gb, gf2, tid);
     __syncthreads();
-    for (int t = 0; t < ntile; ++t) {
-        const int buf = t & 1, key0 = t * AT;
+    for (int t = t_lo; t < ntile; ++t) {
+        const int buf = (t - t_lo) & 1, key0 = t * AT;
         if (t + 1 < ntile) {
             PA_TILE_LOAD(kr, Kh, key0 + AT, false)
             PA_TILE_LOAD(vr, Vh, key0 + AT, false)
             if (GATED) gate_tile_load(gb, gf2, bl_head, key0 + AT, key0 + 2 * AT - 1, 1.f, tid, T);
         }
-        if (active && key0 <= q0 + OWN - 1) {
+        if (active && key0 <= q0 + OWN - 1 && key0 >= k_lo) {
             if (key0 + AT - 1 > q0) tile(std::true_type{}, buf, key0);
             else tile(std::false_type{}, buf, key0);
         }
@@ -461,6 +465,15 @@ __global__ __launch_bounds__(256, WPE) void k_attn_dq(const bf16_t* __restrict__
     for (int ib = 0; ib < NI; ++ib) {
         const bool in = q0 + 16 * ib + r16 < T;
         const size_t row = head + min(q0 + 16 * ib + r16, T - 1);
+        if (CHUNKED) {   // what came through the state (and the normaliser), per slab
+            const size_t slab_stride = (size_t)gridDim.y * T * HD;
+            for (int sl = 0; sl < ck.nslab; ++sl)
+#pragma unroll
+                for (int fb = 0; fb < NF; ++fb) {
+                    const float4 pv = *(const float4*)(ck.part + sl * slab_stride + row * HD + 16 * fb + 4 * g);
+                    acc[fb][ib][0] += pv.x; acc[fb][ib][1] += pv.y; acc[fb][ib][2] += pv.z; acc[fb][ib][3] += pv.w;
+                }
+        }
 #pragma unroll
         for (int fb = 0; fb < NF; ++fb) {
             bf16x4 o;
@@ -481,13 +494,13 @@ __global__ __launch_bounds__(256, WPE) void k_attn_dq(const bf16_t* __restrict__
 // dk[fb][kb] = dK^T: feature 16 fb + 4g + r, key 16 kb + r16 of the wave's OWN keys; dv likewise.
 // S and E are formed queries x keys here, so that their accumulators are the B operand (k-slots =
 // queries) of the two contractions over the queries.
-template <int P, int HD, int OWN, int WPE, bool GATED>
+template <int P, int HD, int OWN, int WPE, bool GATED, bool CHUNKED = false>
 __global__ __launch_bounds__(256, WPE) void k_attn_dkdv(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K,
                                                    const bf16_t* __restrict__ V, const bf16_t* __restrict__ Gh,
                                                    const float* __restrict__ gz, bf16_t* __restrict__ dK,
                                                    bf16_t* __restrict__ dV, int T, float scale,
                                                    const float* __restrict__ bl, float* __restrict__ kdk,
-                                                   float* __restrict__ wsum) {
+                                                   float* __restrict__ wsum, ChunkedIn ck) {
     constexpr int NJ = OWN / 16, NK = HD / 32, NF = HD / 16, WG = 4 * OWN;
     extern __shared__ __attribute__((aligned(16))) unsigned char attn_smem[];
     AttnTile<HD>* qt = reinterpret_cast<AttnTile<HD>*>(attn_smem);      // [2]
@@ -598,7 +611,11 @@ __global__ __launch_bounds__(256, WPE) void k_attn_dkdv(const bf16_t* __restrict
         }
     };
 
-    const int t_first = j0 / AT, ntile = (T + AT - 1) / AT;    // query tiles t_first .. ntile - 1 reach the block's first key
+    // query tiles t_first .. ntile - 1 reach the block's first key; chunked: up to the end of the chunk of the block's
+    // last key, and a wave stops at the end of its own keys' chunk
+    const int t_first = j0 / AT;
+    const int ntile = CHUNKED ? min(((j0 + WG - 1) / ck.cs + 1) * ck.cs, T) / AT : (T + AT - 1) / AT;
+    const int q_hi = CHUNKED ? (k0 / ck.cs + 1) * ck.cs : T + AT;
     uint4 qr[HD / 32], gr[HD / 32];
     float gzr = 0.f, gb = 0.f, gf2 = 0.f;
     PA_TILE_LOAD(qr, Qh, t_first * AT, false)
@@ -618,7 +635,7 @@ __global__ __launch_bounds__(256, WPE) void k_attn_dkdv(const bf16_t* __restrict
             if (tid < AT) gzr = q0 + AT + tid < T ? gzh[q0 + AT + tid] : 0.f;
             if (GATED) gate_tile_load(gb, gf2, bl_head, q0 + AT, q0 + AT, -1.f, tid, T);
         }
-        if (active && q0 + AT - 1 >= k0) {
+        if (active && q0 + AT - 1 >= k0 && q0 < q_hi) {
             if (q0 < k0 + OWN - 1) tile(std::true_type{}, buf, q0);   // some pair of this tile lies above the diagonal
             else tile(std::false_type{}, buf, q0);
         }
@@ -649,6 +666,21 @@ __global__ __launch_bounds__(256, WPE) void k_attn_dkdv(const bf16_t* __restrict
     for (int kb = 0; kb < NJ; ++kb) {
         const bool in = k0 + 16 * kb + r16 < T;
         const size_t row = head + min(k0 + 16 * kb + r16, T - 1);
+        if (CHUNKED) {
+            const size_t slab_stride = (size_t)gridDim.y * T * HD;
+            for (int sl = 0; sl < ck.nslab; ++sl)
+#pragma unroll
+                for (int fb = 0; fb < NF; ++fb) {
+                    const float4 pv = *(const float4*)(ck.part + sl * slab_stride + row * HD + 16 * fb + 4 * g);
+                    dk[fb][kb][0] += pv.x; dk[fb][kb][1] += pv.y; dk[fb][kb][2] += pv.z; dk[fb][kb][3] += pv.w;
+                }
+            for (int sl = 0; sl < ck.nslab2; ++sl)
+#pragma unroll
+                for (int fb = 0; fb < NF; ++fb) {
+                    const float4 pv = *(const float4*)(ck.part2 + sl * slab_stride + row * HD + 16 * fb + 4 * g);
+                    dv[fb][kb][0] += pv.x; dv[fb][kb][1] += pv.y; dv[fb][kb][2] += pv.z; dv[fb][kb][3] += pv.w;
+                }
+        }
 #pragma unroll
         for (int fb = 0; fb < NF; ++fb) {
             bf16x4 a, b;
@@ -731,13 +763,13 @@ bool fwd_t(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* V, bf1
     return launch_ok();
 }
 
-template <int P, int HD, bool GATED>
+template <int P, int HD, bool GATED, bool CHUNKED = false>
 bool bwd_t(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* V, const bf16_t* O, const float* Z, const bf16_t* dO,
            bf16_t* Gh, float* gz, bf16_t* dQ, bf16_t* dK, bf16_t* dV, int BH, int T, float scale, int normalize,
-           const AttnGate& gate) {
+           const AttnGate& gate, ChunkedIn ckq = ChunkedIn(), ChunkedIn ckk = ChunkedIn()) {
     const float* bl = gate.bl;
     const long long rows = (long long)BH * T;
-    {
+    if (!CHUNKED) {
         constexpr int RPB = 256 / (HD / 4);
         LaunchScope ls("attn_bwd_prep", s);
         hipLaunchKernelGGL((k_attn_prep<HD>), dim3((unsigned)((rows + RPB - 1) / RPB)), dim3(256), 0, s, dO, O, Z, Gh, gz, rows,
@@ -746,11 +778,11 @@ bool bwd_t(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* V, con
     }
     {
         constexpr int WG = 4 * Shape<HD>::DKDV_OWN;
-        auto kern = k_attn_dkdv<P, HD, Shape<HD>::DKDV_OWN, Shape<HD>::DKDV_WPE, GATED>;
+        auto kern = k_attn_dkdv<P, HD, Shape<HD>::DKDV_OWN, Shape<HD>::DKDV_WPE, GATED, CHUNKED>;
         if (!allow_smem(kern, attn_smem_bytes<HD>())) return false;
-        LaunchScope ls("attn_bwd_dkdv", s);
+        LaunchScope ls(CHUNKED ? "chunk_bwd_dkdv" : "attn_bwd_dkdv", s);
         hipLaunchKernelGGL(kern, dim3((T + WG - 1) / WG, BH), dim3(256), attn_smem_bytes<HD>(), s, Q, K, V, Gh, gz, dK, dV, T,
-                           scale, bl, gate.kdk, gate.wsum);
+                           scale, bl, gate.kdk, gate.wsum, ckk);
         if (!launch_ok()) return false;
         if (GATED) {
             const int nblk = T / WG;
@@ -762,11 +794,11 @@ bool bwd_t(hipStream_t s, const bf16_t* Q, const bf16_t* K, const bf16_t* V, con
     }
     {
         constexpr int WG = 4 * Shape<HD>::DQ_OWN;
-        auto kern = k_attn_dq<P, HD, Shape<HD>::DQ_OWN, Shape<HD>::DQ_WPE, GATED>;
+        auto kern = k_attn_dq<P, HD, Shape<HD>::DQ_OWN, Shape<HD>::DQ_WPE, GATED, CHUNKED>;
         if (!allow_smem(kern, attn_smem_bytes<HD>())) return false;
-        LaunchScope ls("attn_bwd_dq", s);
+        LaunchScope ls(CHUNKED ? "chunk_bwd_dq" : "attn_bwd_dq", s);
         hipLaunchKernelGGL(kern, dim3((T + WG - 1) / WG, BH), dim3(256), attn_smem_bytes<HD>(), s, Q, K, V, Gh, gz, dQ, T, scale,
-                           bl, gate.qdq);
+                           bl, gate.qdq, ckq);
         if (!launch_ok()) return false;
     }
     return true;
@@ -801,6 +833,38 @@ bool launch_chunk_fwd(hipStream_t s, int p, int d, const bf16_t* Q, const bf16_t
     if (cs % AT != 0 || T % cs != 0) return false;
 #define PA_CASE(PP, DD) \
     if (p == PP && d == DD) return fwd_t<PP, DD, false, true>(s, Q, K, V, O, Z, BH, T, scale, normalize, nullptr, ck);
+    PA_CASE(2, 64) PA_CASE(2, 128)
+#undef PA_CASE
+    return false;
+}
+
+bool launch_attn_prep(hipStream_t s, int d, const bf16_t* dO, const bf16_t* O, const float* Z, bf16_t* Gh, float* gz, long long rows,
+                      int normalize) {
+    LaunchScope ls("attn_bwd_prep", s);
+    if (d == 64)
+        hipLaunchKernelGGL((k_attn_prep<64>), dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, s, dO, O, Z, Gh, gz, rows, normalize);
+    else if (d == 128)
+        hipLaunchKernelGGL((k_attn_prep<128>), dim3((unsigned)((rows + 7) / 8)), dim3(256), 0, s, dO, O, Z, Gh, gz, rows, normalize);
+    else
+        return false;
+    return launch_ok();
+}
+
+bool launch_chunk_bwd(hipStream_t s, int p, int d, const bf16_t* Q, const bf16_t* K, const bf16_t* V, const bf16_t* Gh,
+                      const float* gz, bf16_t* dQ, bf16_t* dK, bf16_t* dV, int BH, int T, int cs, float scale, const float* part_dq,
+                      int nslab_dq, const float* part_dk, int nslab_dk, const float* part_dv, int nslab_dv) {
+    ChunkedIn ckq, ckk;
+    ckq.cs = ckk.cs = cs;
+    ckq.part = part_dq;
+    ckq.nslab = nslab_dq;
+    ckk.part = part_dk;
+    ckk.nslab = nslab_dk;
+    ckk.part2 = part_dv;
+    ckk.nslab2 = nslab_dv;
+    if (cs % AT != 0 || T % cs != 0) return false;
+#define PA_CASE(PP, DD)     \
+    if (p == PP && d == DD) \
+        return bwd_t<PP, DD, false, true>(s, Q, K, V, nullptr, nullptr, nullptr, const_cast<bf16_t*>(Gh), const_cast<float*>(gz), dQ, dK, dV, BH, T, scale, 1, AttnGate(), ckq, ckk);
     PA_CASE(2, 64) PA_CASE(2, 128)
 #undef PA_CASE
     return false;

@@ -63,6 +63,27 @@ __device__ __forceinline__ uint32_t lds_addr(const void* p) {
 }
 
 
+// Cross-lane sums without the LDS pipe: v_permlane16_swap / v_permlane32_swap exchange 16-lane rows (resp.
+// 32-lane halves) between two registers.
+__device__ __forceinline__ float xor16_sum(float x) {   // x + (value in lane ^ 16), in every lane
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ void halves(float x, float& lo, float& hi) {   // lane (l & 31) of each half, in every lane
+    const auto q = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    lo = __uint_as_float(q[0]);
+    hi = __uint_as_float(q[1]);
+}
+__device__ __forceinline__ float xor32_sum(float x) {
+    float lo, hi;
+    halves(x, lo, hi);
+    return lo + hi;
+}
+// float add into LDS without a return value
+__device__ __forceinline__ void lds_add(float* p, float x) {
+    (void)__hip_atomic_fetch_add(p, x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
 // wait until at most `n` of this wave's vector-memory operations are outstanding (they retire in order)
 template <int N>
 __device__ __forceinline__ void vm_wait() {
@@ -106,8 +127,10 @@ ResidentPlan resident_plan(int HD, int BH, int T, int cs);
 // adds up its own total into `tot`.  readout = true: each segment starts from the totals before it and
 // writes, per slab, part[slab][bh][t][:] = (state entering t's chunk)^T phi(Qr_t) * snap_scale.
 // rev: the state holds the chunks after the current one (state gradient).
-bool launch_res_walk(const char* name, hipStream_t s, int HD, bool rev, bool readout, const bf16_t* Xt, const bf16_t* Yt,
-                     const bf16_t* Qr, float* tot, float* part, int BH, int T, int cs, const ResidentPlan& pl,
+// mode 2 (d phi): part[slab][bh][t][:] = J_phi(Qr_t)^T (state . Gr_t) * snap_scale, Gr the token-major rows the state's
+// value columns are contracted with
+bool launch_res_walk(const char* name, hipStream_t s, int HD, bool rev, int mode, const bf16_t* Xt, const bf16_t* Yt,
+                     const bf16_t* Qr, const bf16_t* Gr, float* tot, float* part, int BH, int T, int cs, const ResidentPlan& pl,
                      float snap_scale);
 // out[bh][n] (bf16, HD x HD) = out_scale * sum over the chunks before (rev: after) n of sum_t w_t x_t x_t^T;
 // gram: float32 scratch [BH][T / cs][HD][HD]; wgt may be null (w = 1)
@@ -136,6 +159,14 @@ bool launch_attn_fwd(hipStream_t s, int p, int d, const bf16_t* Q, const bf16_t*
 // zpart[BH][T] the denominator
 bool launch_chunk_fwd(hipStream_t s, int p, int d, const bf16_t* Q, const bf16_t* K, const bf16_t* V, bf16_t* O, float* Z, int BH,
                       int T, int cs, float scale, int normalize, const float* part, int nslab, const float* zpart);
+// ghat = dO / Z (bf16) and gz = -(ghat . O) (float32) per token, d in {64, 128}
+bool launch_attn_prep(hipStream_t s, int d, const bf16_t* dO, const bf16_t* O, const float* Z, bf16_t* Gh, float* gz, long long rows,
+                      int normalize);
+// backward of the same: the in-chunk gradients plus the per-slab parts that came through the states (float32
+// [slab][BH][T][d]; the slab counts include the normaliser's slab where there is one)
+bool launch_chunk_bwd(hipStream_t s, int p, int d, const bf16_t* Q, const bf16_t* K, const bf16_t* V, const bf16_t* Gh,
+                      const float* gz, bf16_t* dQ, bf16_t* dK, bf16_t* dV, int BH, int T, int cs, float scale, const float* part_dq,
+                      int nslab_dq, const float* part_dk, int nslab_dk, const float* part_dv, int nslab_dv);
 // Gated backward pass (bl non-null; T a multiple of attn_gate_block(d)): also leaves what the gradient of
 // the log-gates needs: qdq [BH][T] = q_i . dq_i, kdk [BH][T] = k_j . dk_j (from float32 accumulators) and
 // xb [BH][T / block] = the sum of e_ij a_ij over the pairs j <= end of block m < i.

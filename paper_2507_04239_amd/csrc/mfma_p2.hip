@@ -57,6 +57,7 @@ Layout make_layout(const pa_problem& pr, bool backward) {
 struct ResLayout {
     ResidentPlan pl;
     size_t off_kt, off_vt, off_gam, off_gram, off_tot, off_part, off_zpart;
+    size_t off_qt, off_ght, off_gh, off_gz, off_omg, off_totr, off_pdq, off_pdk;   // backward only
     size_t total;
 };
 ResLayout make_res_layout(const pa_problem& pr, bool backward) {
@@ -78,7 +79,17 @@ ResLayout make_res_layout(const pa_problem& pr, bool backward) {
     L.off_tot = take(L.pl.tot_bytes);
     L.off_part = take(L.pl.part_bytes);
     L.off_zpart = take((size_t)BH * pr.T * sizeof(float));
-    (void)backward;
+    if (backward || pr.keep_state) {
+        const size_t slab = (size_t)BH * pr.T * pr.d * sizeof(float);
+        L.off_qt = take(tok);
+        L.off_ght = take(tok);
+        L.off_gh = take(tok);
+        L.off_gz = take((size_t)BH * pr.T * sizeof(float));
+        L.off_omg = take(gm);
+        L.off_totr = take(L.pl.tot_bytes);
+        L.off_pdq = take((L.pl.nslab + 1) * slab);     // the last slab is the normaliser's share
+        L.off_pdk = take((L.pl.nslab + 1) * slab);
+    }
     L.total = off;
     return L;
 }
@@ -125,7 +136,7 @@ AttnLayout make_attn_layout(const pa_problem& pr, bool backward) {
 int mfma_gate_fin_chunk(const pa_problem& pr) { return use_attn(pr) ? attn_gate_block(pr.d) : pr.chunk; }
 
 pa_status mfma_supported(const pa_problem& pr, bool backward) {
-    if (pr.impl == PA_IMPL_RESIDENT) return resident_ok(pr) && !backward ? PA_OK : PA_ERR_UNSUPPORTED;
+    if (pr.impl == PA_IMPL_RESIDENT) return resident_ok(pr) ? PA_OK : PA_ERR_UNSUPPORTED;
     return chunked_ok(pr) || attn_ok(pr) ? PA_OK : PA_ERR_UNSUPPORTED;
 }
 
@@ -154,7 +165,7 @@ pa_status mfma_fwd(const Ctx& c, const void* Q, const void* K, const void* V, vo
         return PA_OK;
     }
     if (use_resident(pr)) {
-        const ResLayout R = make_res_layout(pr, false);
+        const ResLayout R = make_res_layout(pr, pr.keep_state != 0);
         bf16_t* Kt = (bf16_t*)(c.ws + R.off_kt);
         bf16_t* Vt = (bf16_t*)(c.ws + R.off_vt);
         bf16_t* Gam = (bf16_t*)(c.ws + R.off_gam);
@@ -166,9 +177,9 @@ pa_status mfma_fwd(const Ctx& c, const void* Q, const void* K, const void* V, vo
         PA_TRY(launch_transpose_hd(c.stream, pr.d, (const bf16_t*)V, Vt, BH, pr.T))
         PA_TRY(launch_gram(c.stream, pr.d, Kt, nullptr, gram, Gam, BH, pr.T, pr.chunk, false, 1.0f))
         if (R.pl.nseg > 1)
-            PA_TRY(launch_res_walk("res_state_totals", c.stream, pr.d, false, false, Kt, Vt, nullptr, tot, nullptr, BH, pr.T,
+            PA_TRY(launch_res_walk("res_state_totals", c.stream, pr.d, false, 0, Kt, Vt, nullptr, nullptr, tot, nullptr, BH, pr.T,
                                    pr.chunk, R.pl, 1.0f))
-        PA_TRY(launch_res_walk("res_state_walk", c.stream, pr.d, false, true, Kt, Vt, (const bf16_t*)Q, tot, part, BH, pr.T,
+        PA_TRY(launch_res_walk("res_state_walk", c.stream, pr.d, false, 1, Kt, Vt, (const bf16_t*)Q, nullptr, tot, part, BH, pr.T,
                                pr.chunk, R.pl, pr.scale * pr.scale))
         if (pr.d == DH) {
             PA_TRY(launch_fwd_chunk(c.stream, (const bf16_t*)Q, (const bf16_t*)K, Vt, nullptr, Gam, (bf16_t*)O, Z, BH, pr.T,
@@ -242,6 +253,54 @@ pa_status mfma_bwd(const Ctx& c, const void* Q, const void* K, const void* V, co
         PA_TRY(launch_attn_bwd(c.stream, pr.p, pr.d, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)O, Z,
                                (const bf16_t*)dO, (bf16_t*)(c.ws + A.off_gh), (float*)(c.ws + A.off_gz), (bf16_t*)dQ, (bf16_t*)dK,
                                (bf16_t*)dV, BH, pr.T, pr.scale, pr.normalize, ag))
+        return PA_OK;
+    }
+    if (use_resident(pr)) {
+        // Every part that goes through a state is left per slab in float32 by a walk that keeps that state in
+        // registers: J_phi(q)^T (S ghat) for dQ from a forward walk, R^T phi(k) for dV and J_phi(k)^T (R v) for dK
+        // from two backward walks over R (the two contractions want the accumulators in different orientations);
+        // the normaliser's shares come from the d x d states; one kernel then adds the in-chunk gradients.
+        const ResLayout R = make_res_layout(pr, true);
+        const float s2 = pr.scale * pr.scale;
+        const size_t slab = (size_t)BH * pr.T * pr.d;   // floats
+        bf16_t* Kt = (bf16_t*)(c.ws + R.off_kt);
+        bf16_t* Vt = (bf16_t*)(c.ws + R.off_vt);
+        bf16_t* Qt = (bf16_t*)(c.ws + R.off_qt);
+        bf16_t* Ght = (bf16_t*)(c.ws + R.off_ght);
+        bf16_t* Gh = (bf16_t*)(c.ws + R.off_gh);
+        float* gz = (float*)(c.ws + R.off_gz);
+        bf16_t* Gam = (bf16_t*)(c.ws + R.off_gam);
+        bf16_t* Omg = (bf16_t*)(c.ws + R.off_omg);
+        float* gram = (float*)(c.ws + R.off_gram);
+        float* totS = (float*)(c.ws + R.off_tot);
+        float* totR = (float*)(c.ws + R.off_totr);
+        float* pdv = (float*)(c.ws + R.off_part);
+        float* pdq = (float*)(c.ws + R.off_pdq);
+        float* pdk = (float*)(c.ws + R.off_pdk);
+        const bf16_t *q = (const bf16_t*)Q, *k = (const bf16_t*)K, *v = (const bf16_t*)V;
+        hipStream_t st = c.stream;
+        PA_TRY(launch_attn_prep(st, pr.d, (const bf16_t*)dO, (const bf16_t*)O, Z, Gh, gz, (long long)BH * pr.T, pr.normalize))
+        PA_TRY(launch_transpose_hd(st, pr.d, q, Qt, BH, pr.T))
+        PA_TRY(launch_transpose_hd(st, pr.d, Gh, Ght, BH, pr.T))
+        if (!pr.keep_state) {
+            PA_TRY(launch_transpose_hd(st, pr.d, k, Kt, BH, pr.T))
+            PA_TRY(launch_transpose_hd(st, pr.d, v, Vt, BH, pr.T))
+            PA_TRY(launch_gram(st, pr.d, Kt, nullptr, gram, Gam, BH, pr.T, pr.chunk, false, 1.0f))
+            if (R.pl.nseg > 1)
+                PA_TRY(launch_res_walk("res_state_totals", st, pr.d, false, 0, Kt, Vt, nullptr, nullptr, totS, nullptr, BH, pr.T,
+                                       pr.chunk, R.pl, 1.0f))
+        }
+        PA_TRY(launch_gram(st, pr.d, Qt, gz, gram, Omg, BH, pr.T, pr.chunk, true, s2))
+        PA_TRY(launch_gram_apply(st, pr.d, q, Gam, gz, pdq + R.pl.nslab * slab, nullptr, BH, pr.T, pr.chunk, 2.f * s2, 0.f))
+        PA_TRY(launch_gram_apply(st, pr.d, k, Omg, nullptr, pdk + R.pl.nslab * slab, nullptr, BH, pr.T, pr.chunk, 2.f, 0.f))
+        PA_TRY(launch_res_walk("res_dq_walk", st, pr.d, false, 2, Kt, Vt, q, Gh, totS, pdq, BH, pr.T, pr.chunk, R.pl, s2))
+        if (R.pl.nseg > 1)
+            PA_TRY(launch_res_walk("res_grad_totals", st, pr.d, true, 0, Qt, Ght, nullptr, nullptr, totR, nullptr, BH, pr.T,
+                                   pr.chunk, R.pl, 1.0f))
+        PA_TRY(launch_res_walk("res_dv_walk", st, pr.d, true, 1, Qt, Ght, k, nullptr, totR, pdv, BH, pr.T, pr.chunk, R.pl, s2))
+        PA_TRY(launch_res_walk("res_dk_walk", st, pr.d, true, 2, Qt, Ght, k, v, totR, pdk, BH, pr.T, pr.chunk, R.pl, s2))
+        PA_TRY(launch_chunk_bwd(st, pr.p, pr.d, q, k, v, Gh, gz, (bf16_t*)dQ, (bf16_t*)dK, (bf16_t*)dV, BH, pr.T, pr.chunk, pr.scale,
+                                pdq, R.pl.nslab + 1, pdk, R.pl.nslab + 1, pdv, R.pl.nslab))
         return PA_OK;
     }
     const Layout L = make_layout(pr, true);

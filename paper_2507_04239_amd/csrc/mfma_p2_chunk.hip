@@ -93,23 +93,6 @@ struct ChunkSmem {
     uint4 ring[RING_TILES][TILE_U4];
 };
 
-// Cross-lane sums without the LDS pipe: v_permlane16_swap / v_permlane32_swap exchange 16-lane
-// rows (resp. 32-lane halves) between two registers.
-__device__ __forceinline__ float xor16_sum(float x) {   // x + (value in lane ^ 16), in every lane
-    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
-__device__ __forceinline__ void halves(float x, float& lo, float& hi) {   // lane (l & 31) of each half, in every lane
-    const auto q = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    lo = __uint_as_float(q[0]);
-    hi = __uint_as_float(q[1]);
-}
-__device__ __forceinline__ float xor32_sum(float x) {
-    float lo, hi;
-    halves(x, lo, hi);
-    return lo + hi;
-}
-
 __device__ __forceinline__ uint4 lds_read16(uint32_t addr) {
     uint4 v;
     asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(addr) : "memory");

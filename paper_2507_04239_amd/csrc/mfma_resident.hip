@@ -96,16 +96,19 @@ __device__ __forceinline__ float row_lane_mul(float x, float y) {
 
 // LDS of the walk.  A read-out phase uses qs and ob, an update phase xs and ys; the two never overlap
 // in time, so their inputs share storage.
-template <int HD, int GRP, int OBT, bool READOUT>
+template <int HD, int GRP, int OBT, int MODE>
 struct WalkSmem {
     union {
-        float qs[READOUT ? GRP : 1][HD + 4];     // read-out side (queries), token-major
+        struct {
+            float qs[MODE != 0 ? GRP : 1][HD + 4];       // read-out side rows (queries), token-major
+            bf16_t gs[MODE == 2 ? GRP : 1][HD + 8];      // d phi: the rows the state is contracted with (ghat), token-major
+        } rd;
         struct {
             float xs[HD][GRP + 4];               // update side (keys), feature-major
             bf16_t ys[HD][GRP + 8];              // values, feature-major
         } kv;
     } in;
-    float ob[READOUT ? 2 : 1][4][READOUT ? OBT : 1][HD + 4];   // each wave's partial read-out of OBT tokens, double-buffered
+    float ob[MODE != 0 ? 2 : 1][4][MODE != 0 ? OBT : 1][HD + 4];   // each wave's partial result for OBT tokens, double-buffered
 };
 
 // one dword of an expanded operand: two products, rounded to bf16
@@ -132,18 +135,28 @@ __device__ __forceinline__ uint32_t pk_bf16(float lo, float hi) {
 // input is in flight in registers while a phase computes.
 // READOUT = false: a segment's own total is written to tot[segment] (segments 0 .. nseg - 2 are launched).
 // READOUT = true: the segment starts from the sum of tot[0 .. segment - 1]; every read-out goes to `part`.
-template <int HD, int NHP, int GRP, int OBT, bool REV, bool READOUT>
+//
+// MODE 2 (d phi, the backward pass's gradient through the embedding): the accumulators are kept transposed,
+// C[v][b-slot], so that, rounded to bf16, they are the A operand of the contraction over the value columns,
+//     A[b-slot][token] = sum_v S[(a, b-slot), v] y_token[v]          (y = Gr: ghat for dQ, v for dK),
+// whose result block holds, in lane (token r16, g), the b-slots 4 g .. 4 g + 3 of one a.  The Jacobian of phi
+// follows on the vector ALUs, in registers: x[8 J + b] A[b] summed over b goes to feature 8 I + a, and
+// x[8 I + a] A[b] summed over a to feature 8 J + b; per 16 tokens the sums land in the wave's LDS buffer.
+// `part` then receives J_phi(x_t)^T (S y_t) * snap_scale per slab, token and feature.
+template <int HD, int NHP, int GRP, int OBT, bool REV, int MODE>
 __global__ __launch_bounds__(256, 1) void k_res_walk(const bf16_t* __restrict__ Xt, const bf16_t* __restrict__ Yt,
-                                                     const bf16_t* __restrict__ Qr, float* __restrict__ tot,
+                                                     const bf16_t* __restrict__ Qr, const bf16_t* __restrict__ Gr,
+                                                     float* __restrict__ tot,
                                                      float* __restrict__ part, int T, int cs, int nheads, int nseg,
                                                      int seg_chunks, float snap_scale) {
     typedef ResShape<HD, NHP> SH;
     constexpr int NVB = SH::NVB, NSLAB = SH::NSLAB;
+    constexpr bool READOUT = MODE != 0, DPHI = MODE == 2;
     static_assert(HD * GRP / 8 / 256 == 4, "four 16-byte pieces per thread and staged array");
     static_assert(GRP % OBT == 0 && OBT % 16 == 0 && OBT * HD / 4 / 256 == 2, "read-out buffer shape");
     static_assert(GRP % 64 == 0, "a group is whole 64-token blocks of the feature-major copies");
     extern __shared__ __attribute__((aligned(16))) unsigned char res_smem_raw[];
-    WalkSmem<HD, GRP, OBT, READOUT>& sm = *reinterpret_cast<WalkSmem<HD, GRP, OBT, READOUT>*>(res_smem_raw);
+    WalkSmem<HD, GRP, OBT, MODE>& sm = *reinterpret_cast<WalkSmem<HD, GRP, OBT, MODE>*>(res_smem_raw);
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, r16 = lane & 15, g = lane >> 4;
 
     // Workgroups are dealt to the 8 XCDs round-robin by their linear id; the slabs of one head and segment
@@ -177,7 +190,8 @@ __global__ __launch_bounds__(256, 1) void k_res_walk(const bf16_t* __restrict__ 
         fb[h] = 8 * (r16 < 8 ? jb0 : jb1) + (r16 & 7);
         qa_col[h] = 8 * ia + 4 * ah;
         qb_col[h] = 8 * (g < 2 ? jb0 : jb1) + 4 * (g & 1);
-        ml[h] = (pi < SH::NPAIR ? (g < 2 ? m0 : m1) : 0.f) * snap_scale;
+        // multiplicity of the tile this lane's accumulator rows belong to (b-slots 4 g .. : g; transposed: r16)
+        ml[h] = (pi < SH::NPAIR ? ((DPHI ? r16 < 8 : g < 2) ? m0 : m1) : 0.f) * snap_scale;
     }
 
     f32x4 acc[NHP][4][NVB];
@@ -199,13 +213,18 @@ __global__ __launch_bounds__(256, 1) void k_res_walk(const bf16_t* __restrict__ 
 #pragma unroll
                     for (int vb = 0; vb < NVB; ++vb)
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) acc[h][a][vb][r] += src[(((h * 4 + a) * NVB + vb) * 16 + 4 * g + r) * 16 + r16];
+                        for (int r = 0; r < 4; ++r)
+                            acc[h][a][vb][r] += DPHI ? src[(((h * 4 + a) * NVB + vb) * 16 + r16) * 16 + 4 * g + r]
+                                                     : src[(((h * 4 + a) * NVB + vb) * 16 + 4 * g + r) * 16 + r16];
         }
+        // the waves' result buffers start from zero (the d phi sums are added into them)
+        for (int e = tid; e < (int)(sizeof(sm.ob) / sizeof(float)); e += 256) (&sm.ob[0][0][0][0])[e] = 0.f;
     }
 
     const bf16_t* Xh = Xt + (size_t)bh * HD * T;
     const bf16_t* Yh = Yt + (size_t)bh * HD * T;
     const bf16_t* Qh = READOUT ? Qr + (size_t)bh * T * HD : nullptr;
+    const bf16_t* Gh = DPHI ? Gr + (size_t)bh * T * HD : nullptr;
     // Phase ph of the segment: chunk c_lo + ph / ppc (walk order); of its ppc phases the first gpc read out
     // (READOUT), the others update; token group (walk order) gw, tokens [tok0, tok0 + GRP).
 #define PA_PH_IS_R(PH) (READOUT && ((PH) % ppc) < gpc)
@@ -232,6 +251,13 @@ __global__ __launch_bounds__(256, 1) void k_res_walk(const bf16_t* __restrict__ 
             p1 = *(const uint4*)(src_ + 2048);                                             \
             p2 = *(const uint4*)(src_ + 4096);                                             \
             p3 = *(const uint4*)(src_ + 6144);                                             \
+            if (DPHI) {                                                                    \
+                const bf16_t* gsrc_ = Gh + (size_t)tok0_ * HD + (size_t)tid * 8;           \
+                p4 = *(const uint4*)(gsrc_);                                               \
+                p5 = *(const uint4*)(gsrc_ + 2048);                                        \
+                p6 = *(const uint4*)(gsrc_ + 4096);                                        \
+                p7 = *(const uint4*)(gsrc_ + 6144);                                        \
+            }                                                                              \
         } else {                                                                           \
             const size_t blk_ = (size_t)(tok0_ / TBLK) * (HD * TBLK);                      \
             p0 = *(const uint4*)(Xh + blk_ + PA_KV_SRC(0));                                \
@@ -252,10 +278,16 @@ __global__ __launch_bounds__(256, 1) void k_res_walk(const bf16_t* __restrict__ 
 #define PA_STORE_PHASE(PH)                                                                 \
     {                                                                                      \
         if (PA_PH_IS_R(PH)) {                                                              \
-            PA_UNPACK8(&sm.in.qs[(tid + 0) / (HD / 8)][(tid % (HD / 8)) * 8], p0)          \
-            PA_UNPACK8(&sm.in.qs[(tid + 256) / (HD / 8)][(tid % (HD / 8)) * 8], p1)        \
-            PA_UNPACK8(&sm.in.qs[(tid + 512) / (HD / 8)][(tid % (HD / 8)) * 8], p2)        \
-            PA_UNPACK8(&sm.in.qs[(tid + 768) / (HD / 8)][(tid % (HD / 8)) * 8], p3)        \
+            PA_UNPACK8(&sm.in.rd.qs[(tid + 0) / (HD / 8)][(tid % (HD / 8)) * 8], p0)          \
+            PA_UNPACK8(&sm.in.rd.qs[(tid + 256) / (HD / 8)][(tid % (HD / 8)) * 8], p1)        \
+            PA_UNPACK8(&sm.in.rd.qs[(tid + 512) / (HD / 8)][(tid % (HD / 8)) * 8], p2)        \
+            PA_UNPACK8(&sm.in.rd.qs[(tid + 768) / (HD / 8)][(tid % (HD / 8)) * 8], p3)        \
+            if (DPHI) {                                                                    \
+                *(uint4*)&sm.in.rd.gs[(tid + 0) / (HD / 8)][(tid % (HD / 8)) * 8] = p4;    \
+                *(uint4*)&sm.in.rd.gs[(tid + 256) / (HD / 8)][(tid % (HD / 8)) * 8] = p5;  \
+                *(uint4*)&sm.in.rd.gs[(tid + 512) / (HD / 8)][(tid % (HD / 8)) * 8] = p6;  \
+                *(uint4*)&sm.in.rd.gs[(tid + 768) / (HD / 8)][(tid % (HD / 8)) * 8] = p7;  \
+            }                                                                              \
         } else {                                                                           \
             PA_UNPACK8(&sm.in.kv.xs[PA_KV_FEAT(0)][PA_KV_TOK(0)], p0)                      \
             PA_UNPACK8(&sm.in.kv.xs[PA_KV_FEAT(1)][PA_KV_TOK(1)], p1)                      \
@@ -277,18 +309,20 @@ __global__ __launch_bounds__(256, 1) void k_res_walk(const bf16_t* __restrict__ 
         if (READOUT) {
             // the state entering this chunk, as the read-out's A operands (dead again once the chunk's
             // read-out phases are over)
-            Frag snap[NHP][2][NVB];
+            // read-out: [a pair][column block], k-slots = b-slots 4 g .. of blocks a, a + 1;
+            // d phi: [a][column block pair], k-slots = value columns 4 g .. of column blocks vb, vb + 1
+            Frag snap[NHP][DPHI ? 4 : 2][DPHI ? NVB / 2 : NVB];
             {
 #pragma unroll
                 for (int h = 0; h < NHP; ++h)
 #pragma unroll
-                    for (int a2 = 0; a2 < 2; ++a2)
+                    for (int i = 0; i < (DPHI ? 4 : 2); ++i)
 #pragma unroll
-                        for (int vb = 0; vb < NVB; ++vb)
+                        for (int j = 0; j < (DPHI ? NVB / 2 : NVB); ++j)
 #pragma unroll
                             for (int r = 0; r < 4; ++r) {
-                                snap[h][a2][vb].v[r] = (__bf16)(acc[h][2 * a2][vb][r] * ml[h]);
-                                snap[h][a2][vb].v[4 + r] = (__bf16)(acc[h][2 * a2 + 1][vb][r] * ml[h]);
+                                snap[h][i][j].v[r] = (__bf16)((DPHI ? acc[h][i][2 * j][r] : acc[h][2 * i][j][r]) * ml[h]);
+                                snap[h][i][j].v[4 + r] = (__bf16)((DPHI ? acc[h][i][2 * j + 1][r] : acc[h][2 * i + 1][j][r]) * ml[h]);
                             }
             }
             // read-out: O^T[v][token] += S^T phi(q)^T, 16 tokens at a time; every OBT tokens the four waves'
@@ -303,13 +337,46 @@ __global__ __launch_bounds__(256, 1) void k_res_walk(const bf16_t* __restrict__ 
 #pragma unroll 1
                 for (int tb = 0; tb < OBT / 16; ++tb) {
                     const int tok = OBT * hb + 16 * tb + r16;
+                    if (DPHI) {
+                        Frag gf[NVB / 2];   // y^T: value columns 32 j + 4 g .. + 3 and 32 j + 16 + 4 g .. + 3 of this lane's token
+#pragma unroll
+                        for (int j = 0; j < NVB / 2; ++j) {
+                            gf[j].h[0] = *(const uint2*)&sm.in.rd.gs[tok][32 * j + 4 * g];
+                            gf[j].h[1] = *(const uint2*)&sm.in.rd.gs[tok][32 * j + 16 + 4 * g];
+                        }
+                        float* drow = &sm.ob[buf][w][16 * tb + r16][0];
+#pragma unroll
+                        for (int h = 0; h < NHP; ++h) {
+                            const float4 qa = *(const float4*)&sm.in.rd.qs[tok][qa_col[h]];
+                            const float4 qb = *(const float4*)&sm.in.rd.qs[tok][qb_col[h]];
+                            const float qav[4] = {qa.x, qa.y, qa.z, qa.w};
+                            float ua[4], ub[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                            for (int a = 0; a < 4; ++a) {
+                                f32x4 c2 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                                for (int j = 0; j < NVB / 2; ++j) c2 = mfma16(snap[h][a][j].v, gf[j].v, c2);
+                                ua[a] = c2[0] * qb.x + c2[1] * qb.y + c2[2] * qb.z + c2[3] * qb.w;
+#pragma unroll
+                                for (int r = 0; r < 4; ++r) ub[r] += c2[r] * qav[a];
+                            }
+                            // the sums over b are spread over the four lanes g of a token; lane g keeps feature a = g
+#pragma unroll
+                            for (int a = 0; a < 4; ++a) ua[a] = xor32_sum(xor16_sum(ua[a]));
+                            const float mine = g == 0 ? ua[0] : (g == 1 ? ua[1] : (g == 2 ? ua[2] : ua[3]));
+                            lds_add(drow + qa_col[h] + g, mine);
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) lds_add(drow + qb_col[h] + r, ub[r]);
+                        }
+                        continue;
+                    }
                     f32x4 o[NVB];
 #pragma unroll
                     for (int vb = 0; vb < NVB; ++vb) o[vb] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                     for (int h = 0; h < NHP; ++h) {
-                        const float4 qa = *(const float4*)&sm.in.qs[tok][qa_col[h]];
-                        const float4 qb = *(const float4*)&sm.in.qs[tok][qb_col[h]];
+                        const float4 qa = *(const float4*)&sm.in.rd.qs[tok][qa_col[h]];
+                        const float4 qb = *(const float4*)&sm.in.rd.qs[tok][qb_col[h]];
                         const float qav[4] = {qa.x, qa.y, qa.z, qa.w};
 #pragma unroll
                         for (int a2 = 0; a2 < 2; ++a2) {
@@ -336,6 +403,13 @@ __global__ __launch_bounds__(256, 1) void k_res_walk(const bf16_t* __restrict__ 
                     *(float4*)(dst + (size_t)(OBT * hb + tok) * HD + c4) =
                         make_float4((a0.x + a1.x) + (a2.x + a3.x), (a0.y + a1.y) + (a2.y + a3.y), (a0.z + a1.z) + (a2.z + a3.z),
                                     (a0.w + a1.w) + (a2.w + a3.w));
+                    if (DPHI) {
+                        const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+                        *(float4*)&sm.ob[buf][0][tok][c4] = zero;
+                        *(float4*)&sm.ob[buf][1][tok][c4] = zero;
+                        *(float4*)&sm.ob[buf][2][tok][c4] = zero;
+                        *(float4*)&sm.ob[buf][3][tok][c4] = zero;
+                    }
                 }
             }
             // every wave is past its last read of qs (the barrier above): the next phase's input may land
@@ -386,7 +460,7 @@ __global__ __launch_bounds__(256, 1) void k_res_walk(const bf16_t* __restrict__ 
 #pragma unroll
                         for (int vb = 0; vb < NVB; ++vb) {
                             __builtin_amdgcn_sched_barrier(0);
-                            acc[h][a][vb] = mfma16(fr[cur].v, yf[vb].v, acc[h][a][vb]);
+                            acc[h][a][vb] = DPHI ? mfma16(yf[vb].v, fr[cur].v, acc[h][a][vb]) : mfma16(fr[cur].v, yf[vb].v, acc[h][a][vb]);
                             if (!last && vb < 4) {
                                 // (hn, an, vb) are compile-time after unrolling; the switch keeps the macro's lane indices constant
                                 uint32_t dw = 0;
@@ -560,16 +634,16 @@ bool allow_smem(F* fn, size_t bytes) {
     return e == hipSuccess;
 }
 
-template <int HD, int NHP, int GRP, int OBT, bool REV, bool READOUT>
-bool launch_walk_t(const char* name, hipStream_t s, const bf16_t* Xt, const bf16_t* Yt, const bf16_t* Qr, float* tot,
-                   float* part, int BH, int T, int cs, int nseg, int seg_chunks, float snap_scale) {
-    const size_t smem = sizeof(WalkSmem<HD, GRP, OBT, READOUT>);
-    auto* fn = k_res_walk<HD, NHP, GRP, OBT, REV, READOUT>;
+template <int HD, int NHP, int GRP, int OBT, bool REV, int MODE>
+bool launch_walk_t(const char* name, hipStream_t s, const bf16_t* Xt, const bf16_t* Yt, const bf16_t* Qr, const bf16_t* Gr,
+                   float* tot, float* part, int BH, int T, int cs, int nseg, int seg_chunks, float snap_scale) {
+    const size_t smem = sizeof(WalkSmem<HD, GRP, OBT, MODE>);
+    auto* fn = k_res_walk<HD, NHP, GRP, OBT, REV, MODE>;
     if (!allow_smem(fn, smem)) return false;
-    const int total = (READOUT ? nseg : nseg - 1) * BH * ResShape<HD, NHP>::NSLAB;
+    const int total = (MODE != 0 ? nseg : nseg - 1) * BH * ResShape<HD, NHP>::NSLAB;
     if (total <= 0) return true;
     LaunchScope ls(name, s);
-    hipLaunchKernelGGL(fn, dim3(8 * ((total + 7) / 8)), dim3(256), smem, s, Xt, Yt, Qr, tot, part, T, cs, BH, nseg,
+    hipLaunchKernelGGL(fn, dim3(8 * ((total + 7) / 8)), dim3(256), smem, s, Xt, Yt, Qr, Gr, tot, part, T, cs, BH, nseg,
                        seg_chunks, snap_scale);
     return launch_ok();
 }
@@ -594,27 +668,24 @@ ResidentPlan resident_plan(int HD, int BH, int T, int cs) {
     return p;
 }
 
-bool launch_res_walk(const char* name, hipStream_t s, int HD, bool rev, bool readout, const bf16_t* Xt, const bf16_t* Yt,
-                     const bf16_t* Qr, float* tot, float* part, int BH, int T, int cs, const ResidentPlan& pl,
+bool launch_res_walk(const char* name, hipStream_t s, int HD, bool rev, int mode, const bf16_t* Xt, const bf16_t* Yt,
+                     const bf16_t* Qr, const bf16_t* Gr, float* tot, float* part, int BH, int T, int cs, const ResidentPlan& pl,
                      float snap_scale) {
-#define PA_GO(HDV, NHPV, GRPV, OBTV, R, RO) \
-    return launch_walk_t<HDV, NHPV, GRPV, OBTV, R, RO>(name, s, Xt, Yt, Qr, tot, part, BH, T, cs, pl.nseg, pl.seg_chunks, snap_scale);
-    if (HD == 64) {
-        if (!rev) {
-            if (readout) PA_GO(64, 3, 128, 32, false, true)
-            PA_GO(64, 3, 128, 32, false, false)
-        }
-        if (readout) PA_GO(64, 3, 128, 32, true, true)
-        PA_GO(64, 3, 128, 32, true, false)
+#define PA_GO(HDV, NHPV, GRPV, OBTV, R, M) \
+    return launch_walk_t<HDV, NHPV, GRPV, OBTV, R, M>(name, s, Xt, Yt, Qr, Gr, tot, part, BH, T, cs, pl.nseg, pl.seg_chunks, snap_scale);
+#define PA_MODES(HDV, NHPV, GRPV, OBTV)              \
+    if (!rev) {                                      \
+        if (mode == 0) PA_GO(HDV, NHPV, GRPV, OBTV, false, 0) \
+        if (mode == 1) PA_GO(HDV, NHPV, GRPV, OBTV, false, 1) \
+        if (mode == 2) PA_GO(HDV, NHPV, GRPV, OBTV, false, 2) \
+    } else {                                         \
+        if (mode == 0) PA_GO(HDV, NHPV, GRPV, OBTV, true, 0)  \
+        if (mode == 1) PA_GO(HDV, NHPV, GRPV, OBTV, true, 1)  \
+        if (mode == 2) PA_GO(HDV, NHPV, GRPV, OBTV, true, 2)  \
     }
-    if (HD == 128) {
-        if (!rev) {
-            if (readout) PA_GO(128, 2, 64, 16, false, true)
-            PA_GO(128, 2, 64, 16, false, false)
-        }
-        if (readout) PA_GO(128, 2, 64, 16, true, true)
-        PA_GO(128, 2, 64, 16, true, false)
-    }
+    if (HD == 64) { PA_MODES(64, 3, 128, 32) }
+    if (HD == 128) { PA_MODES(128, 2, 64, 16) }
+#undef PA_MODES
 #undef PA_GO
     return false;
 }

@@ -47,3 +47,24 @@ def test_resident_forward_d128(B, H, T, chunk, scale):
     got = run_fwd_bwd(Q, K, V, None, 2, chunk, "bf16", scale=scale, impl="resident", backward=False)
     O, Z = orc.fwd_bhtd(Q, K, V, 2, chunk, True, scale)
     assert_close(got, dict(O=O, Z=Z), "bf16", f"resident fwd d128 {(B, H, T, chunk, scale)}")
+
+
+# forward + backward: (B, H, T, d, chunk, scale, keep_state)
+BWD_CASES = [
+    (1, 2, 512, 64, 128, 1.0, False),
+    (1, 1, 128 * 23, 64, 128, 1.0, True),
+    (2, 2, 1024, 64, 256, 0.7, True),
+    (1, 1, 512, 128, 256, 1.0, False),
+    (1, 2, 1024, 128, 128, 1.0, True),
+    (1, 1, 256 * 7, 128, 256, 0.8, True),
+]
+
+
+@pytest.mark.parametrize("B,H,T,d,chunk,scale,keep", BWD_CASES)
+def test_resident_forward_backward(B, H, T, d, chunk, scale, keep):
+    Q, K, V, G = inputs.make_qkvg(B, H, T, d, seed=4200 + T + H + d, dtype="bf16")
+    print("case bwd", (B, H, T, d, chunk, scale, keep), flush=True)
+    got = run_fwd_bwd(Q, K, V, G, 2, chunk, "bf16", scale=scale, impl="resident", keep_state=keep)
+    O, Z = orc.fwd_bhtd(Q, K, V, 2, chunk, True, scale)
+    dQ, dK, dV = orc.bwd_bhtd(Q, K, V, G, 2, chunk, True, scale)
+    assert_close(got, dict(O=O, Z=Z, dQ=dQ, dK=dK, dV=dV), "bf16", f"resident fwd+bwd {(B, H, T, d, chunk, scale, keep)}")
