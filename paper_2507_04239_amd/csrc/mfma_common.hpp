@@ -79,11 +79,6 @@ __device__ __forceinline__ float xor32_sum(float x) {
     halves(x, lo, hi);
     return lo + hi;
 }
-// float add into LDS without a return value
-__device__ __forceinline__ void lds_add(float* p, float x) {
-    (void)__hip_atomic_fetch_add(p, x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-}
-
 // wait until at most `n` of this wave's vector-memory operations are outstanding (they retire in order)
 template <int N>
 __device__ __forceinline__ void vm_wait() {

@@ -345,28 +345,54 @@ __global__ __launch_bounds__(256, 1) void k_res_walk(const bf16_t* __restrict__ 
                             gf[j].h[1] = *(const uint2*)&sm.in.rd.gs[tok][32 * j + 16 + 4 * g];
                         }
                         float* drow = &sm.ob[buf][w][16 * tb + r16][0];
+                        // The four blocks a of a half-pair are four independent MFMA chains; the next half-pair's
+                        // chains are issued before this one's Jacobian, which then runs in their shadow.
+                        f32x4 c2[2][4];
+#pragma unroll
+                        for (int a = 0; a < 4; ++a) c2[0][a] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                        for (int j = 0; j < NVB / 2; ++j)
+#pragma unroll
+                            for (int a = 0; a < 4; ++a) c2[0][a] = mfma16(snap[0][a][j].v, gf[j].v, c2[0][a]);
 #pragma unroll
                         for (int h = 0; h < NHP; ++h) {
+                            const int cur = h & 1;
+                            if (h + 1 < NHP) {
+#pragma unroll
+                                for (int a = 0; a < 4; ++a) c2[cur ^ 1][a] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                                for (int j = 0; j < NVB / 2; ++j)
+#pragma unroll
+                                    for (int a = 0; a < 4; ++a)
+                                        c2[cur ^ 1][a] = mfma16(snap[h + 1 < NHP ? h + 1 : 0][a][j].v, gf[j].v, c2[cur ^ 1][a]);
+                            }
                             const float4 qa = *(const float4*)&sm.in.rd.qs[tok][qa_col[h]];
                             const float4 qb = *(const float4*)&sm.in.rd.qs[tok][qb_col[h]];
                             const float qav[4] = {qa.x, qa.y, qa.z, qa.w};
                             float ua[4], ub[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                             for (int a = 0; a < 4; ++a) {
-                                f32x4 c2 = {0.f, 0.f, 0.f, 0.f};
+                                const f32x4 c = c2[cur][a];
+                                ua[a] = c[0] * qb.x + c[1] * qb.y + c[2] * qb.z + c[3] * qb.w;
 #pragma unroll
-                                for (int j = 0; j < NVB / 2; ++j) c2 = mfma16(snap[h][a][j].v, gf[j].v, c2);
-                                ua[a] = c2[0] * qb.x + c2[1] * qb.y + c2[2] * qb.z + c2[3] * qb.w;
-#pragma unroll
-                                for (int r = 0; r < 4; ++r) ub[r] += c2[r] * qav[a];
+                                for (int r = 0; r < 4; ++r) ub[r] += c[r] * qav[a];
                             }
-                            // the sums over b are spread over the four lanes g of a token; lane g keeps feature a = g
-#pragma unroll
-                            for (int a = 0; a < 4; ++a) ua[a] = xor32_sum(xor16_sum(ua[a]));
-                            const float mine = g == 0 ? ua[0] : (g == 1 ? ua[1] : (g == 2 ? ua[2] : ua[3]));
-                            lds_add(drow + qa_col[h] + g, mine);
-#pragma unroll
-                            for (int r = 0; r < 4; ++r) lds_add(drow + qb_col[h] + r, ub[r]);
+                            // The sums over b are spread over the four lanes g of a token.  Two swaps of 16-lane rows
+                            // and one of the 32-lane halves, each followed by an add, leave the total for a = g in lane g.
+                            const auto s01 = __builtin_amdgcn_permlane16_swap(__float_as_uint(ua[0]), __float_as_uint(ua[1]), false, false);
+                            const auto s23 = __builtin_amdgcn_permlane16_swap(__float_as_uint(ua[2]), __float_as_uint(ua[3]), false, false);
+                            const float t01 = __uint_as_float(s01[0]) + __uint_as_float(s01[1]);
+                            const float t23 = __uint_as_float(s23[0]) + __uint_as_float(s23[1]);
+                            const auto sf = __builtin_amdgcn_permlane32_swap(__float_as_uint(t01), __float_as_uint(t23), false, false);
+                            // plain read-add-write: the buffer row belongs to this wave, an instruction's lanes hit
+                            // distinct addresses, and a wave's LDS operations stay in order (LDS float atomics
+                            // run at a small fraction of this rate)
+                            float* pa = drow + qa_col[h] + g;
+                            *pa += __uint_as_float(sf[0]) + __uint_as_float(sf[1]);
+                            float4* pb = (float4*)(drow + qb_col[h]);
+                            float4 cur4 = *pb;
+                            cur4.x += ub[0]; cur4.y += ub[1]; cur4.z += ub[2]; cur4.w += ub[3];
+                            *pb = cur4;
                         }
                         continue;
                     }
