@@ -97,8 +97,6 @@ bool resident_ok(const pa_problem& pr) {
     return pr.dtype == PA_DTYPE_BF16 && pr.p == 2 && (pr.d == 64 || pr.d == 128) && pr.v == pr.d && pr.chunk > 0 &&
            pr.chunk % QBLK == 0 && pr.T % pr.chunk == 0 && !pr.gated && (size_t)pr.B * pr.H <= 65535u;
 }
-bool use_resident(const pa_problem& pr) { return pr.impl == PA_IMPL_RESIDENT && resident_ok(pr); }
-
 bool chunked_ok(const pa_problem& pr) {
     return pr.dtype == PA_DTYPE_BF16 && pr.p == 2 && pr.d == DH && pr.v == DH && pr.chunk % QBLK == 0 &&
            (size_t)pr.B * pr.H <= 65535u;
@@ -110,7 +108,12 @@ bool attn_ok(const pa_problem& pr) {
 }
 // One chunk: the attention-form kernels.  (The chunked kernels can run p = 2, d = 64 as one chunk
 // too; that path remains for gated sequences that are a multiple of 128 but not of the block.)
-bool use_attn(const pa_problem& pr) { return attn_ok(pr); }
+bool use_attn(const pa_problem& pr) { return attn_ok(pr) && pr.impl != PA_IMPL_RESIDENT; }
+// The resident-state kernels run when asked for by name, and wherever they are the only matrix-core kernels
+// for the chunked form (d = 128)
+bool use_resident(const pa_problem& pr) {
+    return resident_ok(pr) && (pr.impl == PA_IMPL_RESIDENT || (!chunked_ok(pr) && !attn_ok(pr)));
+}
 
 // attention form, backward: ghat (bf16) and gz (float32) per token
 struct AttnLayout {
@@ -137,7 +140,7 @@ int mfma_gate_fin_chunk(const pa_problem& pr) { return use_attn(pr) ? attn_gate_
 
 pa_status mfma_supported(const pa_problem& pr, bool backward) {
     if (pr.impl == PA_IMPL_RESIDENT) return resident_ok(pr) ? PA_OK : PA_ERR_UNSUPPORTED;
-    return chunked_ok(pr) || attn_ok(pr) ? PA_OK : PA_ERR_UNSUPPORTED;
+    return chunked_ok(pr) || attn_ok(pr) || resident_ok(pr) ? PA_OK : PA_ERR_UNSUPPORTED;
 }
 
 long long mfma_state_rows(const pa_problem& pr) {

@@ -165,6 +165,27 @@ def test_d128_config5_shape_reduced_batch():
     _check_sampled("cfg5", got, Q, K, V, G, dict(w, B=1, H=2), [(0, 0)], n_rows=12, n_cols=0)
 
 
+def test_config5_as_stated_full_shape():
+    """Config 5 as stated, all of it: bf16 fwd+bwd, p=2, B8 H16 T32768 d128, chunk 256, as bench.py runs it (the
+    resident-state matrix-core kernels, states kept between the passes).  One head, every output, against the
+    chunked float64 oracle; eight more heads spread over the batch, sampled rows of O, Z, dQ by the definition;
+    sampled columns of dK, dV on the fully checked head."""
+    name = "cfg5_bf16_p2_T32768_d128_c256"
+    w = inputs.WORKLOADS[name]
+    Q, K, V, G = inputs.make_workload(name)
+    print("case", name, "as stated", flush=True)
+    got = run_fwd_bwd(Q, K, V, G, w["p"], w["chunk"], "bf16", keep_state=True)
+    for k, a in got.items():
+        assert np.isfinite(a).all(), k
+    b, h = 5, 11
+    O_ref, Z_ref = orc.fwd_chunked(Q[b, h], K[b, h], V[b, h], w["p"], w["chunk"])
+    dQ_ref, dK_ref, dV_ref = orc.bwd_chunked(Q[b, h], K[b, h], V[b, h], G[b, h], w["p"], w["chunk"])
+    assert_close({k: a[b, h] for k, a in got.items()}, dict(O=O_ref, Z=Z_ref, dQ=dQ_ref, dK=dK_ref, dV=dV_ref),
+                 "bf16", f"{name} head (5,11) vs chunked oracle")
+    heads = [(5, 11), (0, 0), (1, 15), (2, 3), (3, 8), (4, 12), (6, 5), (7, 15), (7, 0)]
+    _check_sampled(name, got, Q, K, V, G, w, heads, n_rows=4, n_cols=10, ref_head=((b, h), (O_ref, Z_ref)))
+
+
 def test_headline_shape_gated():
     """The headline head shape (T = 65536, d = 64, chunk 128, bf16) with per-timestep gates, two
     heads: every output of one head against the chunked float64 oracle, sampled forward rows of
