@@ -40,6 +40,14 @@ def algorithmic_flops(w):
         "bwd_dk": state + pairs * 2 * d,
         "bwd_dv": BH * (n - 1) * c * 2 * D * v + pairs * 2 * v,
     }
+    # resident-state kernels: a walk does the update and one contraction with the state in one launch
+    f["walk_fwd"] = 2 * state                                             # update-state + query-state
+    f["walk_dq"] = state                                                  # d phi(q); rebuilding S is executed, not credited
+    f["walk_dv"] = state + BH * (n - 1) * c * 2 * D * v                   # state gradient + its read-out
+    f["walk_dk"] = state                                                  # d phi(k); R is credited to the dV walk
+    f["chunk_fwd"] = pairs * (2 * d + 2 * (v + 1))
+    f["chunk_dq"] = pairs * (4 * d + 2 * v + 2)
+    f["chunk_dkdv"] = pairs * (2 * d + 2 * v)
     f["recompute"] = 0   # a backward pass that rebuilds the chunk states: executed, not credited
     f["fwd_total"] = f["update_state"] + f["fwd_chunk"]
     f["bwd_total"] = f["state_grad"] + f["bwd_dq"] + f["bwd_dkdv"]
@@ -67,6 +75,11 @@ def algorithmic_bytes(w):
         "bwd_dk": states + 5 * tok + BH * T * 4,
         "bwd_dv": states + 4 * tok,                  # Q, K, ghat in; dV out
         "recompute": 0,
+        # resident-state kernels: no state leaves the chip; what is credited is the token rows in and the
+        # result out (the per-slab float32 partial results they exchange are overhead)
+        "walk_fwd": 3 * tok + BH * T * v * 4, "walk_dq": 4 * tok + BH * T * d * 4,
+        "walk_dv": 3 * tok + BH * T * v * 4, "walk_dk": 4 * tok + BH * T * d * 4,
+        "chunk_fwd": 4 * tok + BH * T * 4, "chunk_dq": 5 * tok + BH * T * 4, "chunk_dkdv": 7 * tok + BH * T * 4,
     }
 
 
@@ -85,6 +98,16 @@ KERNEL_ROLE = {
     "mfma_bwd_dkdv": ("bwd_dkdv", PEAK_BF16_MFMA_TFLOPS),
     "mfma_bwd_dk": ("bwd_dk", PEAK_BF16_MFMA_TFLOPS),
     "mfma_bwd_dv": ("bwd_dv", PEAK_BF16_MFMA_TFLOPS),
+    "res_state_walk": ("walk_fwd", PEAK_BF16_MFMA_TFLOPS),
+    "res_state_totals": ("recompute", PEAK_BF16_MFMA_TFLOPS),
+    "res_grad_totals": ("recompute", PEAK_BF16_MFMA_TFLOPS),
+    "res_dq_walk": ("walk_dq", PEAK_BF16_MFMA_TFLOPS),
+    "res_dv_walk": ("walk_dv", PEAK_BF16_MFMA_TFLOPS),
+    "res_dk_walk": ("walk_dk", PEAK_BF16_MFMA_TFLOPS),
+    "mfma_fwd_chunk_partial": ("chunk_fwd", PEAK_BF16_MFMA_TFLOPS),
+    "chunk_fwd": ("chunk_fwd", PEAK_BF16_MFMA_TFLOPS),
+    "chunk_bwd_dq": ("chunk_dq", PEAK_BF16_MFMA_TFLOPS),
+    "chunk_bwd_dkdv": ("chunk_dkdv", PEAK_BF16_MFMA_TFLOPS),
     # attention form (one chunk, no state): the same formulas with n = 1
     "attn_fwd": ("fwd_chunk", PEAK_BF16_MFMA_TFLOPS),
     "attn_bwd_dq": ("bwd_dq", PEAK_BF16_MFMA_TFLOPS),
@@ -103,6 +126,15 @@ def measured_traffic(workload, kernel):
         if len(f) == 4 and f[0] == "TRAFFIC" and f[1] == workload and f[2] == kernel:
             return float(f[3])
     return None
+
+
+def traffic_source():
+    """The line of profiles/hbm_traffic.txt that says which commit its counters were taken at."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    for line in open(path):
+        if line.startswith("COMMIT"):
+            return line.strip()
+    return "profiles/hbm_traffic.txt (commit not recorded)"
 
 
 def cpu_baseline(w, heads):
@@ -200,6 +232,8 @@ def main():
     ap.add_argument("--recompute-states", action="store_true",
                     help="backward pass rebuilds the chunk states instead of reusing the forward pass's workspace")
     ap.add_argument("--forward-only", action="store_true", help="time the forward pass alone")
+    ap.add_argument("--all-configs", action="store_true",
+                    help="run the five benchmark configurations as stated, one JSON line each")
     ap.add_argument("--decode-batch", type=int, default=0,
                     help="instead of the training step: time the single-token decode step of the workload's head shape "
                          "on this many sequences (state resident in HBM)")
@@ -208,13 +242,38 @@ def main():
         sys.exit("bench.py: this build measures one GPU only (the path shards over batch and heads with no "
                  "communication); run with --gpus 1")
 
+    from paper_2507_04239_amd import inputs
+    if args.decode_batch > 0:
+        name = args.workload or inputs.HEADLINE
+        return decode_bench(args, name, dict(inputs.WORKLOADS[name]))
+    if args.all_configs:
+        # every benchmark configuration as stated, one JSON line each (the headline one carries the CPU baseline)
+        for name in sorted(inputs.WORKLOADS, key=lambda n: inputs.WORKLOADS[n]["position"]):
+            out = run_workload(args, name, cpu=(name == inputs.HEADLINE and not args.no_cpu_baseline))
+            print(json.dumps(out), flush=True)
+        return
+    name = args.workload or inputs.HEADLINE
+    print(json.dumps(run_workload(args, name, cpu=not args.no_cpu_baseline)), flush=True)
+
+
+def event_times(step, steps):
+    """Milliseconds of `steps` calls of step(), each bracketed by a pair of HIP events on the current stream
+    (the stream the library launches on; its side stream is forked from and joined back into it)."""
+    import torch
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for e0, e1 in ev:
+        e0.record()
+        step()
+        e1.record()
+    torch.cuda.synchronize()
+    return sorted(e0.elapsed_time(e1) for e0, e1 in ev)
+
+
+def run_workload(args, name, cpu):
     import torch
     from paper_2507_04239_amd import binding, inputs, power_attn_bwd, power_attn_fwd
 
-    name = args.workload or inputs.HEADLINE
     w = dict(inputs.WORKLOADS[name])
-    if args.decode_batch > 0:
-        return decode_bench(args, name, w)
     oracle_chunk = w["chunk"]
     if args.chunk is not None:
         w["chunk"] = args.chunk
@@ -239,10 +298,16 @@ def main():
 
     with_bwd = bool(w.get("backward", True)) and not args.forward_only    # configs 1 and 2 are forward-only
 
-    def step():
+    def fwd():
         power_attn_fwd(tq, tk, tv, p, chunk, impl=args.impl, workspace=ws, out=O, out_z=Z, keep_state=keep, log_g=tl)
+
+    def bwd():
+        power_attn_bwd(tq, tk, tv, O, Z, tg, p, chunk, impl=args.impl, workspace=ws, out=grads, keep_state=keep, log_g=tl)
+
+    def step():
+        fwd()
         if with_bwd:
-            power_attn_bwd(tq, tk, tv, O, Z, tg, p, chunk, impl=args.impl, workspace=ws, out=grads, keep_state=keep, log_g=tl)
+            bwd()
 
     if args.serial_kernels:
         binding.profile_begin()
@@ -257,6 +322,16 @@ def main():
     if args.serial_kernels:
         binding.profile_end()
     tokens = w["B"] * w["T"]
+
+    # the same steps again, each one between a pair of HIP events; then the two passes on their own
+    ev_step = event_times(step, args.steps)
+    ev_fwd = event_times(fwd, args.steps)
+    ev_bwd = event_times(bwd, args.steps) if with_bwd else None
+    med = lambda xs: xs[len(xs) // 2]
+    timing = {"clock": "hip events on the launch stream, per step", "step_ms_median": med(ev_step), "step_ms_min": ev_step[0],
+              "step_ms_max": ev_step[-1], "fwd_ms_median": med(ev_fwd), "fwd_ms_min": ev_fwd[0]}
+    if ev_bwd:
+        timing.update({"bwd_ms_median": med(ev_bwd), "bwd_ms_min": ev_bwd[0]})
 
     if args.copy_calibration_mib > 0:
         src = torch.empty(args.copy_calibration_mib << 20, dtype=torch.uint8, device=dev)
@@ -281,27 +356,26 @@ def main():
             per_kernel[kname].update({"tflops": fl[role] / sec / 1e12, "frac_compute_peak": fl[role] / sec / 1e12 / peak,
                                       "hbm_gbs": by[role] / sec / 1e9, "frac_hbm_peak": by[role] / sec / 1e9 / PEAK_HBM_GBS})
     # The dominant kernel, and the roof that bounds it: the one whose lower bound on its time is larger.
-    credited = {k: v for k, v in kernels.items() if k in KERNEL_ROLE}
-    if not credited:
-        print(json.dumps({"ms_per_step": ms_per_step, "kernels": per_kernel}), flush=True)
-        return
+    credited = {k: v for k, v in kernels.items() if k in KERNEL_ROLE and KERNEL_ROLE[k][0] != "recompute"}
     dom = max(credited, key=lambda k: credited[k][1])
     role, peak = KERNEL_ROLE[dom]
     dom_ms = credited[dom][1] / credited[dom][0]
     t_compute = fl[role] / (peak * 1e12)
     t_hbm = by[role] / (PEAK_HBM_GBS * 1e9)
+    traffic = measured_traffic(name, dom)
     if t_hbm >= t_compute:
         achieved = by[role] / (dom_ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                    "frac": achieved / PEAK_HBM_GBS, "traffic": measured_traffic(name, dom), "avg_kernel_ms": dom_ms,
+                    "frac": achieved / PEAK_HBM_GBS, "traffic": traffic, "avg_kernel_ms": dom_ms,
                     "algorithmic_bytes_per_launch": by[role], "algorithmic_flops_per_launch": fl[role],
                     "frac_of_compute_peak": fl[role] / (dom_ms * 1e-3) / 1e12 / peak}
     else:
         achieved = fl[role] / (dom_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma" if peak == PEAK_BF16_MFMA_TFLOPS else "alu", "kernel": dom, "achieved": achieved,
-                    "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak, "traffic": measured_traffic(name, dom),
+                    "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak, "traffic": traffic,
                     "avg_kernel_ms": dom_ms, "algorithmic_flops_per_launch": fl[role],
                     "algorithmic_bytes_per_launch": by[role]}
+    roofline["traffic_source"] = traffic_source() if traffic is not None else None
     total_alg = fl["fwd_total"] + (fl["bwd_total"] if with_bwd else 0)
     out = {
         "metric": "power-attention fwd+bwd tokens/sec at p=2,d=64,T=64k; % bf16 MFMA peak",
@@ -311,14 +385,17 @@ def main():
         "config": {"workload": name, "B": w["B"], "H": w["H"], "T": w["T"], "d": w["d"], "p": p, "chunk": w["chunk"],
                    "chunk_requested": chunk, "normalize": True, "pass": "fwd+bwd" if with_bwd else "fwd", "impl": args.impl, "keep_state": keep, "serial_kernels": args.serial_kernels, "gated": args.gated,
                    "state_rows": binding.power_attn_state_rows(prob)},
+        "timing": timing,
         "step_algorithmic_tflop": total_alg / 1e12,
         "step_frac_of_bf16_mfma_peak": total_alg / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS,
         "roofline": roofline,
         "kernels": per_kernel,
     }
-    if not args.no_cpu_baseline:
+    if cpu:
         out["cpu_baseline"] = cpu_baseline(dict(w, chunk=oracle_chunk), args.cpu_sample_heads)
-    print(json.dumps(out), flush=True)
+    del ws, tq, tk, tv, tg, O, Z, grads
+    torch.cuda.empty_cache()
+    return out
 
 
 if __name__ == "__main__":
