@@ -19,15 +19,22 @@
  * All pointers named Q, K, V, O, Z, dO, dQ, dK, dV and `workspace` are DEVICE pointers
  * (HIP global memory on the current device); `const pa_problem*` and the profiling
  * arguments are HOST pointers.  Tensors are dense row-major [B, H, T, d] (Q, K, dQ, dK),
- * [B, H, T, v] (V, O, dO, dV) in `dtype`, and [B, H, T] float32 (Z).  The caller owns
- * every buffer; the library allocates no device memory, keeps no per-call state and
- * enqueues work on `hip_stream` (a hipStream_t passed as void*, NULL = the default
- * stream); it does not synchronise the host.  One exception to "only on hip_stream": the
- * bf16 MFMA backward pass runs independent kernels side by side on one more stream that the
- * library creates once per process (non-blocking, default priority), forked from and joined
- * back into hip_stream with events, so that for the caller the call is ordered on hip_stream
- * like any other.  Calls may not be issued concurrently from several host threads.  Outputs
- * are overwritten, never accumulated into.
+ * [B, H, T, v] (V, O, dO, dV) in `dtype`, and [B, H, T] float32 (Z, log_g, dlog_g).  Every
+ * tensor pointer must be 16-byte aligned (they are accessed with 16-byte vector loads and
+ * stores) and every workspace 256-byte aligned; a misaligned pointer is PA_ERR_INVALID_ARG
+ * (PA_ERR_WORKSPACE for a workspace) and nothing is launched.  The caller owns every buffer;
+ * the library allocates no device memory, keeps no per-call state and enqueues work on
+ * `hip_stream` (a hipStream_t passed as void*, NULL = the default stream); it does not
+ * synchronise the host.  One exception to "only on hip_stream": the bf16 MFMA backward pass
+ * runs independent kernels side by side on one more stream (non-blocking, default priority),
+ * forked from and joined back into hip_stream with events, so that for the caller the call
+ * is ordered on hip_stream like any other.
+ * Host threads: what the library keeps between calls is kept per host thread - that side
+ * stream and its events (created on the thread's first such call, destroyed by
+ * power_attn_release_thread), the text of the last HIP error, and the profiling switch with
+ * its records - so calls may be issued concurrently from several host threads, each on a
+ * stream and buffers of its own.  The exception is power_attn_fwd_static, whose scratch is
+ * one array per GPU.  Outputs are overwritten, never accumulated into.
  * No function throws; all errors are return codes and nothing is launched when
  * validation fails.
  */
@@ -197,7 +204,13 @@ const char* power_attn_status_string(pa_status s);
  * owned by the library, valid until the next failing call. */
 const char* power_attn_last_hip_error(void);
 
-/* Optional per-kernel timing for benchmarks (host-side global switch, not thread-safe).
+/* Destroys the calling host thread's side stream and events (see the top of this file), if it has
+ * created any; the next backward call of the thread creates them again.  Call it before a thread that
+ * has run power_attn_bwd ends, or not at all (the process's exit releases them). */
+void power_attn_release_thread(void);
+
+/* Optional per-kernel timing for benchmarks (a switch per host thread: it records the calls of the
+ * thread that turned it on).
  * Between _begin and _end every kernel the library launches is bracketed by a pair of HIP
  * events on the launch stream; _end waits for them and returns, per kernel name, the number
  * of launches and the summed elapsed milliseconds.  `out` is a HOST array of `max_entries`

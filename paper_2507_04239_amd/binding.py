@@ -35,6 +35,7 @@ EXPORTED_SYMBOLS = (
     "power_attn_resolved_chunk",
     "power_attn_status_string",
     "power_attn_last_hip_error",
+    "power_attn_release_thread",
     "power_attn_profile_begin",
     "power_attn_profile_end",
 )
@@ -112,6 +113,8 @@ def load_library():
     lib.power_attn_status_string.argtypes = [ctypes.c_int]
     lib.power_attn_last_hip_error.restype = ctypes.c_char_p
     lib.power_attn_last_hip_error.argtypes = []
+    lib.power_attn_release_thread.restype = None
+    lib.power_attn_release_thread.argtypes = []
     lib.power_attn_profile_begin.restype = ctypes.c_int
     lib.power_attn_profile_begin.argtypes = []
     lib.power_attn_profile_end.restype = ctypes.c_int

@@ -118,6 +118,8 @@ bool mfma_absorb_supported(const pa_problem& pr);
 size_t mfma_absorb_workspace_bytes(const pa_problem& pr);
 pa_status mfma_absorb(const pa_problem& pr, const void* K, const void* V, const float* log_g, char* ws, hipStream_t s, float* S,
                       float* gamd, int D);
+// destroys the calling thread's side stream and events of the MFMA backward pass, if it has any
+void mfma_release_side_stream();
 // tokens per entry of GateBuf::xb as mfma_bwd leaves it (gated problems)
 int mfma_gate_fin_chunk(const pa_problem& pr);
 

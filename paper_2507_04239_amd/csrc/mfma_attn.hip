@@ -2,7 +2,7 @@
 // the kernel of Sec. 4 Eq. 7): the whole sequence is one chunk, no state is built,
 //     O_i = sum_{j <= i} a_ij v_j / Z_i,   a_ij = (scale q_i . k_j)^p,   Z_i = sum_{j <= i} a_ij,
 // for degrees p in {2, 3, 4}, head sizes d = v in {32, 64, 128} and any sequence length.  The paper switches to this form where
-// it is the cheaper one (Sec. 5, throughput comparison); here it is also what runs the degrees and
+// it is the cheaper one (Sec. 4.1.2, the throughput comparison); here it is also what runs the degrees and
 // head sizes the chunked MFMA family (p = 2, d = 64) does not cover.
 //
 // Backward pass (the paper gives none; derived from the definition): with ghat_i = dO_i / Z_i and

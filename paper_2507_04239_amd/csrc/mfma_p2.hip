@@ -223,10 +223,12 @@ struct SideStream {
     bool ok = false;
     int device = -1;
 };
-// One side stream per process, bound to the device of the first backward call; a call on any
-// other device simply runs both strands on the caller's stream.
+// One side stream per host thread (so that calls from several threads never share one), bound to the
+// device of the thread's first backward call; a call on any other device simply runs both strands on the
+// caller's stream.  power_attn_release_thread() destroys it.
+static thread_local SideStream t_side;
 static SideStream side_stream() {
-    static SideStream s;
+    SideStream& s = t_side;
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess) return SideStream{};
     if (s.device < 0) {
@@ -237,6 +239,15 @@ static SideStream side_stream() {
                hipEventCreateWithFlags(&s.scanned, hipEventDisableTiming) == hipSuccess;
     }
     return s.device == dev ? s : SideStream{};
+}
+
+void mfma_release_side_stream() {
+    SideStream& s = t_side;
+    if (s.stream != nullptr) (void)hipStreamDestroy(s.stream);
+    if (s.fork != nullptr) (void)hipEventDestroy(s.fork);
+    if (s.join != nullptr) (void)hipEventDestroy(s.join);
+    if (s.scanned != nullptr) (void)hipEventDestroy(s.scanned);
+    s = SideStream{};
 }
 
 pa_status mfma_bwd(const Ctx& c, const void* Q, const void* K, const void* V, const void* O, const float* Z,

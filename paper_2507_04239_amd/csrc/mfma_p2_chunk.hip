@@ -9,16 +9,6 @@
 // and one wave's vector-ALU work (building phi, the Jacobian of phi) overlaps the other's MFMAs.
 #include "mfma_common.hpp"
 
-// Hooks for a cycle-counter profile of the per-tile phases; a profiling harness that includes
-// this file defines them, the library build leaves them empty.
-#ifndef PA_PROBE
-#define PA_PROBE_DECL
-#define PA_PROBE_PARAM
-#define PA_PROBE_ARG
-#define PA_PROBE(I)
-#define PA_PROBE_DUMP
-#endif
-
 namespace pa {
 namespace mfma {
 namespace {
@@ -266,7 +256,7 @@ __device__ __forceinline__ void readout(f32x4 (&acc)[4][4], const bf16_t* __rest
 template <int FBI, int FBJ, int RING_TILES, int NW, bool GATED>
 __device__ __forceinline__ void dphi_block(f32x4 (&acc)[4][4], const bf16_t* __restrict__ Sn, ChunkSmem<RING_TILES>& sm,
                                            const Frag (&yf)[4][2], float xscale, int wv, int wr, int lane,
-                                           const float* colf PA_PROBE_PARAM) {
+                                           const float* colf) {
     constexpr int K0 = dphi_block_begin(FBI, FBJ), K1 = K0 + (FBI == FBJ ? 3 : 4);
     const int r16 = lane & 15, g = lane >> 4;
     const XbRow* Xb = sm.xb;
@@ -283,11 +273,8 @@ __device__ __forceinline__ void dphi_block(f32x4 (&acc)[4][4], const bf16_t* __r
     for (int k = K0; k < K1; ++k) {
         const int code = DPHI_ORDER.v[k];
         const int ti = code & 255, tj = (code >> 8) & 255;
-        PA_PROBE(0)
         vm_wait<(8 / NW) * (RING_TILES - 2)>();
-        PA_PROBE(1)
         __builtin_amdgcn_s_barrier();
-        PA_PROBE(2)
         ring_issue<true, NW>(sm, (k + RING_TILES - 1) % RING_TILES, Sn, DPHI_ORDER.v[min(k + RING_TILES - 1, NTILES)] >> 16, wr, lane);
         const uint32_t slot_lo = ring_lo + (uint32_t)(k % RING_TILES) * (TILE_U4 * 16u);
         const uint32_t slot_hi = ring_hi + (uint32_t)(k % RING_TILES) * (TILE_U4 * 16u);
@@ -313,7 +300,6 @@ __device__ __forceinline__ void dphi_block(f32x4 (&acc)[4][4], const bf16_t* __r
         // the lanes g with (g & 1) = a >> 2, and the two lanes g >> 1 = ti & 1 own those features.
         const float own_mask = ((g >> 1) == (ti & 1)) ? 1.f : 0.f;
         lds_read_wait(sf[0][0], sf[0][1], sf[1][0], sf[1][1], sf[2][0], sf[2][1], sf[3][0], sf[3][1]);
-        PA_PROBE(3)
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb) {
 #pragma unroll
@@ -360,12 +346,10 @@ __device__ __forceinline__ void dphi(f32x4 (&acc)[4][4], const bf16_t* __restric
                                      const float* colf = nullptr) {
 #pragma unroll
     for (int k = 0; k < RING_TILES - 1; ++k) ring_issue<true, NW>(sm, k, Sn, DPHI_ORDER.v[k] >> 16, wr, lane);
-    PA_PROBE_DECL
-#define PA_BLOCK(I, J) dphi_block<I, J, RING_TILES, NW, GATED>(acc, Sn, sm, yf, xscale, wv, wr, lane, colf PA_PROBE_ARG);
+#define PA_BLOCK(I, J) dphi_block<I, J, RING_TILES, NW, GATED>(acc, Sn, sm, yf, xscale, wv, wr, lane, colf);
     PA_BLOCK(0, 0) PA_BLOCK(0, 1) PA_BLOCK(1, 1) PA_BLOCK(0, 2) PA_BLOCK(1, 2) PA_BLOCK(2, 2)
     PA_BLOCK(0, 3) PA_BLOCK(1, 3) PA_BLOCK(2, 3) PA_BLOCK(3, 3)
 #undef PA_BLOCK
-    PA_PROBE_DUMP
     vm_wait<0>();
 }
 

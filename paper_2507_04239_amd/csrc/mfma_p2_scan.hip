@@ -2,14 +2,6 @@
 // update-state + cumulative sum over chunks.  See mfma_common.hpp for the embedding and layouts.
 #include "mfma_common.hpp"
 
-// Hooks for a cycle-counter profile of the scan's phases; a profiling harness that includes this
-// file defines them, the library build leaves them empty.
-#ifndef PA_PROBE
-#define PA_PROBE_DECL
-#define PA_PROBE(I)
-#define PA_PROBE_DUMP
-#endif
-
 namespace pa {
 namespace mfma {
 namespace {
@@ -388,7 +380,6 @@ __device__ __forceinline__ void scan_body(const bf16_t* __restrict__ Xt, const b
 #define PA_CONSUME(J, ST, BUF)                                                                \
     if ((ST) < nstage) { /* uniform; no global loads inside this branch */                    \
         const int edge_ = REV ? T - (ST) * SCAN_TOK : (ST) * SCAN_TOK;                        \
-        PA_PROBE(0)                                                                           \
         StateOut so_;                                                                         \
         if (EVERY || edge_ % cs == 0) {                                                       \
             const int n_ = REV ? edge_ / cs - 1 : edge_ / cs;                                 \
@@ -396,7 +387,6 @@ __device__ __forceinline__ void scan_body(const bf16_t* __restrict__ Xt, const b
             if (EVERY) pack_state(so_, n_, l_);                                               \
             else write_state(n_, l_);                                                         \
         }                                                                                     \
-        PA_PROBE(1)                                                                           \
         PA_FILL_X(BUF, 0, x0_##J) PA_FILL_X(BUF, 1, x1_##J)                                   \
         if (GAMMA) {                                                                          \
             PA_FILL_X(BUF, 2, x2_##J) PA_FILL_X(BUF, 3, x3_##J)                               \
@@ -407,16 +397,12 @@ __device__ __forceinline__ void scan_body(const bf16_t* __restrict__ Xt, const b
         *(uint4*)&sm.ys[REV ? 0 : BUF][p_feat[1]][p_tok[1]] = y1_##J;                         \
         *(uint4*)&sm.ys[REV ? 0 : BUF][p_feat[2]][p_tok[2]] = y2_##J;                         \
         *(uint4*)&sm.ys[REV ? 0 : BUF][p_feat[3]][p_tok[3]] = y3_##J;                         \
-        PA_PROBE(2)                                                                           \
         lds_barrier();                                                                        \
-        PA_PROBE(3)                                                                           \
         if (has_rows) scan_stage<GAMMA, REV, EVERY>(acc, sm, BUF, fa0, fa_step, fb, r16, g, so_); \
-        PA_PROBE(4)                                                                           \
     }
         // The LDS buffer alternates with the stage parity; 2 * SCAN_PF stages per trip keep both
         // the ring slot and the buffer compile-time constants.
         PA_LOAD_STAGE(0, 0) PA_LOAD_STAGE(1, 1) PA_LOAD_STAGE(2, 2)
-        PA_PROBE_DECL
         for (int st0 = 0; st0 < nstage; st0 += 2 * SCAN_PF) {
             PA_CONSUME(0, st0 + 0, 0) PA_LOAD_STAGE(0, st0 + 3)
             PA_CONSUME(1, st0 + 1, 1) PA_LOAD_STAGE(1, st0 + 4)
@@ -425,7 +411,6 @@ __device__ __forceinline__ void scan_body(const bf16_t* __restrict__ Xt, const b
             PA_CONSUME(1, st0 + 4, 0) PA_LOAD_STAGE(1, st0 + 7)
             PA_CONSUME(2, st0 + 5, 1) PA_LOAD_STAGE(2, st0 + 8)
         }
-        PA_PROBE_DUMP
 #undef PA_CONSUME
 #undef PA_FILL_X
 #undef PA_LOAD_STAGE

@@ -45,9 +45,14 @@ pa_status static_scratch(void** out) {
     return PA_OK;
 }
 
-bool g_profile = false;
-char g_last_error[256] = "";
-std::vector<Record> g_records;
+// Per host thread: the profiling switch and its records, and the text of the last HIP error.  Calls from
+// different host threads share nothing but the static scratch of power_attn_fwd_static.
+thread_local bool g_profile = false;
+thread_local char g_last_error[256] = "";
+thread_local std::vector<Record> g_records;
+
+// the tensor arguments are read and written with 16-byte vector accesses
+bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
 pa_status validate(const pa_problem* pr) {
     if (pr == nullptr) return PA_ERR_INVALID_ARG;
@@ -80,7 +85,10 @@ int auto_chunk(const pa_problem& pr) {
     // the chunked kernels, on the sequence rounded up to whole chunks when it is ragged (see Padding)
     probe.chunk = pr.T % 256 == 0 || pr.T % 128 != 0 ? 256 : 128;
     probe.T = (pr.T + probe.chunk - 1) / probe.chunk * probe.chunk;
-    if (may_mfma && mfma_supported(probe, true) == PA_OK && !(attn && pr.T <= (pr.gated ? 2048 : 4096))) return probe.chunk;
+    // (d = 128 has chunked matrix-core kernels too, the resident-state ones; measured at B8 H16 T32768 they take
+    // 231 ms a step against 166 ms for the attention form, so the choice there stays with the attention form)
+    if (may_mfma && pr.d == 64 && mfma_supported(probe, true) == PA_OK && !(attn && pr.T <= (pr.gated ? 2048 : 4096)))
+        return probe.chunk;
     if (attn) return pr.T;
     double D = 1.0;   // C(d + p - 1, p)
     for (int i = 1; i <= pr.p; ++i) D = D * (pr.d + pr.p - i) / i;
@@ -181,6 +189,8 @@ pa_status run_fwd(const pa_problem* prob, const void* Q, const void* K, const vo
     if (st != PA_OK) return st;
     if (prob->gated != gated) return PA_ERR_INVALID_ARG;
     if (Q == nullptr || K == nullptr || V == nullptr || O == nullptr || (gated && log_g == nullptr)) return PA_ERR_INVALID_ARG;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(Z) || !aligned16(log_g))
+        return PA_ERR_INVALID_ARG;
     const pa_problem asked = resolved(prob);
     const Padding pd = padding_for(asked);
     prob = &pd.prob;
@@ -239,6 +249,9 @@ pa_status run_bwd(const pa_problem* prob, const void* Q, const void* K, const vo
         return PA_ERR_INVALID_ARG;
     if (gated && (log_g == nullptr || dlog_g == nullptr)) return PA_ERR_INVALID_ARG;
     if (prob->normalize != 0 && (O == nullptr || Z == nullptr)) return PA_ERR_INVALID_ARG;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(Z) || !aligned16(dO) || !aligned16(dQ) ||
+        !aligned16(dK) || !aligned16(dV) || !aligned16(log_g) || !aligned16(dlog_g))
+        return PA_ERR_INVALID_ARG;
     const pa_problem asked = resolved(prob);
     const Padding pd = padding_for(asked);
     prob = &pd.prob;
@@ -411,6 +424,7 @@ pa_status power_attn_decode_absorb(const pa_problem* prob, const void* K, const 
     const size_t need = decode_state_bytes(*prob);
     if (need == 0) return PA_ERR_UNSUPPORTED;
     if (state == nullptr || state_bytes < need) return PA_ERR_WORKSPACE;
+    if (!aligned16(K) || !aligned16(V) || !aligned16(state)) return PA_ERR_INVALID_ARG;
     if (workspace != nullptr && ((uintptr_t)workspace & 255u) != 0) return PA_ERR_WORKSPACE;
     return decode_absorb(*prob, K, V, log_g, state, workspace, workspace_bytes, (hipStream_t)hip_stream);
 }
@@ -424,6 +438,7 @@ pa_status power_attn_decode_step(const pa_problem* prob, const void* q, const vo
     const size_t need = decode_state_bytes(*prob);
     if (need == 0) return PA_ERR_UNSUPPORTED;
     if (state == nullptr || state_bytes < need) return PA_ERR_WORKSPACE;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(state)) return PA_ERR_INVALID_ARG;
     return decode_step(*prob, q, k, v, log_g, state, o, z, (hipStream_t)hip_stream);
 }
 
@@ -468,6 +483,8 @@ pa_status power_attn_bwd_gated(const pa_problem* prob, const void* Q, const void
 }
 
 const char* power_attn_last_hip_error(void) { return g_last_error; }
+
+void power_attn_release_thread(void) { mfma_release_side_stream(); }
 
 pa_status power_attn_profile_begin(void) {
     for (auto& r : g_records) {

@@ -106,9 +106,16 @@ def test_support_matrix_host_logic():
     assert ok(mk(1, 2, 1024, 64, 64, 2, 128, impl="mfma"), True)
     assert rows(mk(1, 2, 1024, 64, 64, 2, 128, impl="mfma")) == 36 * 64            # tiled embedding, d_tile = 8
     assert not ok(mk(1, 2, 1024, 64, 64, 2, 64, impl="mfma"), True)
-    assert not ok(mk(1, 2, 1024, 128, 128, 2, 256, impl="mfma"), True)             # no chunked kernels at d = 128
+    # d = 128 chunked: the resident-state kernels (136 tiles of 64 rows), also when asked for by name at d = 64
+    assert ok(mk(1, 2, 1024, 128, 128, 2, 256, impl="mfma"), True)
+    assert rows(mk(1, 2, 1024, 128, 128, 2, 256, impl="mfma")) == 136 * 64
+    assert ok(mk(1, 2, 1024, 64, 64, 2, 128, impl="resident"), True)
+    assert not ok(mk(1, 2, 1024, 64, 64, 2, 64, impl="resident"), True)            # chunk a multiple of 128
+    assert not ok(mk(1, 2, 1024, 32, 32, 4, 128, impl="resident"), True)           # p = 2 only
+    assert not ok(mk(1, 2, 1024, 64, 64, 2, 128, impl="resident", gated=True), True)
     assert ok(mk(1, 2, 1024, 128, 128, 2, 256, impl="auto"), True)                 # ... the generic family runs it
-    assert rows(mk(1, 2, 1024, 128, 128, 2, 256)) == 8256                          # C(129, 2), Lemma 4.2
+    assert rows(mk(1, 2, 1024, 128, 128, 2, 256)) == 8704                          # auto: the tiled embedding (Sec. 4.1.1)
+    assert rows(mk(1, 2, 1024, 128, 128, 2, 256, impl="generic")) == 8256          # C(129, 2), Lemma 4.2
     # attention form: one chunk, degrees 2-4, head sizes 32 / 64 / 128, any length
     for p, d in ((2, 32), (3, 64), (4, 128), (4, 32)):
         assert ok(mk(1, 1, 1000, d, d, p, 1000, normalize=(p % 2 == 0), impl="mfma"), True), (p, d)
