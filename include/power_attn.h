@@ -64,9 +64,14 @@ typedef enum {
     PA_IMPL_MFMA    = 2,  /* bf16 MFMA with float32 accumulation; bf16 only.  Chunked form: p = 2, d = v = 64,
                              chunk a multiple of 128.  Attention form (chunk == T; any T, or with
                              gates T a multiple of 128, of 256 at d = 32): p in {2, 3, 4}, d = v in {32, 64, 128}.  See power_attn_supported() */
-    PA_IMPL_RESIDENT = 3  /* the chunked bf16 MFMA kernels that keep the chunk states in registers while they walk the
-                             sequence (no chunk state is written to memory): p = 2, d = v = 64, chunk a multiple of 128,
-                             not gated */
+    PA_IMPL_RESIDENT = 3, /* the chunked bf16 MFMA kernels that keep the chunk states in registers while they walk the
+                             sequence (no chunk state is written to memory): p = 2, d = v in {64, 128}, chunk a multiple
+                             of 128, not gated */
+    PA_IMPL_TILED = 4     /* the chunked bf16 MFMA kernels with the degree and the tile width of the embedding
+                             (Sec. 4.1.1) as parameters, chunk states in memory: d = v = 32 with (p, d_tile) in
+                             {(2,4), (2,8), (2,16), (3,4), (4,2), (4,4)}, d = v = 64 with {(2,4), (2,8), (2,16), (3,4)};
+                             chunk a multiple of 128 that divides T, at least two chunks, not gated.  What AUTO runs for
+                             the chunked form of p = 3 and p = 4 */
 } pa_impl;
 
 typedef struct {
@@ -98,6 +103,10 @@ typedef struct {
                            pair (i, j) is weighted by the gates of the steps j+1 .. i:
                                a_ij = s_ij^p exp(b_i - b_j),
                            N_i = sum_j a_ij v_j, Z_i = sum_j a_ij. */
+    int   d_tile;       /* tile width of the tiled symmetric-power embedding (Sec. 4.1.1).  0: the kernel family's
+                           own (8 for p = 2, 4 for p = 3 and p = 4).  A value > 0 asks for the PA_IMPL_TILED kernels
+                           with that width (PA_ERR_UNSUPPORTED if they do not take the problem); the result does
+                           not depend on it beyond rounding. */
 } pa_problem;
 
 /* Bytes of device scratch the calls below need for `prob` (0 on an invalid problem).

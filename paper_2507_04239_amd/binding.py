@@ -14,8 +14,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_NAME = "libpower_attn.so"
 
 PA_DTYPE_F32, PA_DTYPE_BF16 = 0, 1
-PA_IMPL_AUTO, PA_IMPL_GENERIC, PA_IMPL_MFMA, PA_IMPL_RESIDENT = 0, 1, 2, 3
-_IMPL = {"auto": PA_IMPL_AUTO, "generic": PA_IMPL_GENERIC, "mfma": PA_IMPL_MFMA, "resident": PA_IMPL_RESIDENT}
+PA_IMPL_AUTO, PA_IMPL_GENERIC, PA_IMPL_MFMA, PA_IMPL_RESIDENT, PA_IMPL_TILED = 0, 1, 2, 3, 4
+_IMPL = {"auto": PA_IMPL_AUTO, "generic": PA_IMPL_GENERIC, "mfma": PA_IMPL_MFMA, "resident": PA_IMPL_RESIDENT,
+         "tiled": PA_IMPL_TILED}
 
 EXPORTED_SYMBOLS = (
     "power_attn_workspace_bytes",
@@ -49,7 +50,7 @@ class PaProblem(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int), ("H", ctypes.c_int), ("T", ctypes.c_int), ("d", ctypes.c_int),
                 ("v", ctypes.c_int), ("p", ctypes.c_int), ("chunk", ctypes.c_int), ("normalize", ctypes.c_int),
                 ("scale", ctypes.c_float), ("dtype", ctypes.c_int), ("impl", ctypes.c_int),
-                ("keep_state", ctypes.c_int), ("gated", ctypes.c_int)]
+                ("keep_state", ctypes.c_int), ("gated", ctypes.c_int), ("d_tile", ctypes.c_int)]
 
 
 class PaKernelTime(ctypes.Structure):
@@ -130,13 +131,13 @@ def _check(lib, status: int, what: str):
 
 
 def make_problem(B, H, T, d, v, p, chunk, normalize=True, scale=1.0, dtype="bf16", impl="auto",
-                 keep_state=False, gated=False) -> PaProblem:
+                 keep_state=False, gated=False, d_tile=0) -> PaProblem:
     return PaProblem(B, H, T, d, v, p, chunk, int(bool(normalize)), float(scale),
                      PA_DTYPE_BF16 if dtype == "bf16" else PA_DTYPE_F32, _IMPL[impl], int(bool(keep_state)),
-                     int(bool(gated)))
+                     int(bool(gated)), int(d_tile))
 
 
-def _problem_of(Q, V, p, chunk, normalize, scale, impl, keep_state=False, gated=False) -> PaProblem:
+def _problem_of(Q, V, p, chunk, normalize, scale, impl, keep_state=False, gated=False, d_tile=0) -> PaProblem:
     import torch
     if Q.dim() != 4 or V.dim() != 4:
         raise PowerAttnError("tensors must be [B, H, T, d]")
@@ -147,7 +148,7 @@ def _problem_of(Q, V, p, chunk, normalize, scale, impl, keep_state=False, gated=
     else:
         raise PowerAttnError(f"unsupported dtype {Q.dtype}")
     B, H, T, d = Q.shape
-    return make_problem(B, H, T, d, V.shape[3], p, chunk, normalize, scale, dtype, impl, keep_state, gated)
+    return make_problem(B, H, T, d, V.shape[3], p, chunk, normalize, scale, dtype, impl, keep_state, gated, d_tile)
 
 
 def _dev_ptr(t, like=None, name="tensor"):
@@ -199,7 +200,7 @@ def _gate_ptr(log_g, Q, name):
 
 
 def power_attn_fwd(Q, K, V, p: int, chunk: int, normalize: bool = True, scale: float = 1.0, impl: str = "auto",
-                   workspace=None, out=None, out_z=None, keep_state: bool = False, log_g=None):
+                   workspace=None, out=None, out_z=None, keep_state: bool = False, log_g=None, d_tile: int = 0):
     """Forward pass on the current stream.  Returns (O, Z): O like V, Z float32 [B, H, T].
     keep_state=True needs a caller-provided workspace that is then handed, untouched, to
     power_attn_bwd(..., keep_state=True).  log_g (float32 [B, H, T], <= 0) switches gating on."""
@@ -207,7 +208,7 @@ def power_attn_fwd(Q, K, V, p: int, chunk: int, normalize: bool = True, scale: f
     lib = load_library()
     for t, name in ((Q, "Q"), (K, "K"), (V, "V")):
         _dev_ptr(t, None, name)
-    prob = _problem_of(Q, V, p, chunk, normalize, scale, impl, keep_state, log_g is not None)
+    prob = _problem_of(Q, V, p, chunk, normalize, scale, impl, keep_state, log_g is not None, d_tile)
     if keep_state and workspace is None:
         raise PowerAttnError("keep_state=True needs a workspace that outlives the call")
     _check(lib, lib.power_attn_supported(ctypes.byref(prob), 0), "power_attn_fwd")
@@ -240,14 +241,14 @@ def power_attn_fwd_static(Q, K, V, O, Z, p: int, chunk: int, normalize: bool = T
 
 
 def power_attn_bwd(Q, K, V, O, Z, dO, p: int, chunk: int, normalize: bool = True, scale: float = 1.0,
-                   impl: str = "auto", workspace=None, out=None, keep_state: bool = False, log_g=None):
+                   impl: str = "auto", workspace=None, out=None, keep_state: bool = False, log_g=None, d_tile: int = 0):
     """Backward pass on the current stream.  Returns (dQ, dK, dV), or (dQ, dK, dV, dlog_g) when
     log_g is given."""
     import torch
     lib = load_library()
     for t, name in ((Q, "Q"), (K, "K"), (V, "V"), (dO, "dO")):
         _dev_ptr(t, None, name)
-    prob = _problem_of(Q, V, p, chunk, normalize, scale, impl, keep_state, log_g is not None)
+    prob = _problem_of(Q, V, p, chunk, normalize, scale, impl, keep_state, log_g is not None, d_tile)
     if keep_state and workspace is None:
         raise PowerAttnError("keep_state=True needs the workspace the forward pass used")
     _check(lib, lib.power_attn_supported(ctypes.byref(prob), 1), "power_attn_bwd")

@@ -833,7 +833,9 @@ bool launch_chunk_fwd(hipStream_t s, int p, int d, const bf16_t* Q, const bf16_t
     if (cs % AT != 0 || T % cs != 0) return false;
 #define PA_CASE(PP, DD) \
     if (p == PP && d == DD) return fwd_t<PP, DD, false, true>(s, Q, K, V, O, Z, BH, T, scale, normalize, nullptr, ck);
-    PA_CASE(2, 64) PA_CASE(2, 128)
+    PA_CASE(2, 32) PA_CASE(2, 64) PA_CASE(2, 128)
+    PA_CASE(3, 32) PA_CASE(3, 64)
+    PA_CASE(4, 32)
 #undef PA_CASE
     return false;
 }
@@ -841,7 +843,9 @@ bool launch_chunk_fwd(hipStream_t s, int p, int d, const bf16_t* Q, const bf16_t
 bool launch_attn_prep(hipStream_t s, int d, const bf16_t* dO, const bf16_t* O, const float* Z, bf16_t* Gh, float* gz, long long rows,
                       int normalize) {
     LaunchScope ls("attn_bwd_prep", s);
-    if (d == 64)
+    if (d == 32)
+        hipLaunchKernelGGL((k_attn_prep<32>), dim3((unsigned)((rows + 31) / 32)), dim3(256), 0, s, dO, O, Z, Gh, gz, rows, normalize);
+    else if (d == 64)
         hipLaunchKernelGGL((k_attn_prep<64>), dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, s, dO, O, Z, Gh, gz, rows, normalize);
     else if (d == 128)
         hipLaunchKernelGGL((k_attn_prep<128>), dim3((unsigned)((rows + 7) / 8)), dim3(256), 0, s, dO, O, Z, Gh, gz, rows, normalize);
@@ -865,7 +869,9 @@ bool launch_chunk_bwd(hipStream_t s, int p, int d, const bf16_t* Q, const bf16_t
 #define PA_CASE(PP, DD)     \
     if (p == PP && d == DD) \
         return bwd_t<PP, DD, false, true>(s, Q, K, V, nullptr, nullptr, nullptr, const_cast<bf16_t*>(Gh), const_cast<float*>(gz), dQ, dK, dV, BH, T, scale, 1, AttnGate(), ckq, ckk);
-    PA_CASE(2, 64) PA_CASE(2, 128)
+    PA_CASE(2, 32) PA_CASE(2, 64) PA_CASE(2, 128)
+    PA_CASE(3, 32) PA_CASE(3, 64)
+    PA_CASE(4, 32)
 #undef PA_CASE
     return false;
 }

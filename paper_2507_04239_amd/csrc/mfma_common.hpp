@@ -139,6 +139,35 @@ bool launch_transpose_hd(hipStream_t s, int HD, const bf16_t* in, bf16_t* out, i
 bool launch_gram_apply(hipStream_t s, int HD, const bf16_t* X, const bf16_t* gam, const float* wgt, float* vec, float* sca,
                        int BH, int T, int cs, float cvec, float csca);
 
+// ---- chunked form for any degree and tile width (state kept in memory; see mfma_tiled.hip) -------------
+// One tile of the tiled symmetric-power embedding: its p block indices (non-decreasing) and its multiplicity
+struct TileDesc {
+    unsigned char t[4];
+    float mult;
+};
+struct TiledPlan {
+    int p, dt, hd, vp;            // degree, tile width, head size, value columns of a state row (hd + 16)
+    int ntile, rows_per_tile;     // tiles of the embedding, dt^p rows each
+    int nunit_real, nunit;        // 64-row units that hold state, and the count the layout is padded to (a multiple of 4)
+    int nentry;                   // entries of the tile table (padding entries have multiplicity 0)
+    size_t state_elems;           // bf16 elements of one (head, chunk) state
+};
+bool tiled_shape_ok(int p, int d, int dt);
+int tiled_default_dt(int p);
+TiledPlan tiled_plan(int p, int d, int dt);
+bool launch_tiled_table(hipStream_t s, const TiledPlan& pl, TileDesc* tab);
+// Yp[row] = [Y[row] (hd values), col[row] (1 when col is null), 15 zeros], bf16
+bool launch_tiled_pack(hipStream_t s, int hd, const bf16_t* Y, const float* col, bf16_t* Yp, long long rows);
+// st[bh][c] = multiplicity x sum over the chunks before c (rev: after c) of phi(xscale X_t) Yp_t^T
+bool launch_tiled_scan(const char* name, hipStream_t s, const TiledPlan& pl, bool rev, const bf16_t* X, const bf16_t* Yp,
+                       const TileDesc* tab, bf16_t* st, int BH, int T, int cs, float xscale);
+// part[bh][t][:] = (state of t's chunk)^T phi(xscale X_t), columns 0 .. hd - 1; zpart[bh][t] (may be null) = column hd
+bool launch_tiled_readout(const char* name, hipStream_t s, const TiledPlan& pl, const bf16_t* X, const TileDesc* tab, const bf16_t* st,
+                          float* part, float* zpart, int BH, int T, int cs, float xscale);
+// part[bh][t][:] = outscale J_phi(xscale X_t)^T (state of t's chunk . Yp_t)
+bool launch_tiled_dphi(const char* name, hipStream_t s, const TiledPlan& pl, const bf16_t* X, const bf16_t* Yp, const TileDesc* tab,
+                       const bf16_t* st, float* part, int BH, int T, int cs, float xscale, float outscale);
+
 // gating: xb[bh][n] = the sum over the pairs that straddle the end of chunk n, from the stored states
 bool launch_gate_boundary(hipStream_t s, const bf16_t* stC, const bf16_t* rtC, const bf16_t* gam, const bf16_t* omg, float* xb,
                           int BH, int nstate);
@@ -154,7 +183,7 @@ bool launch_attn_fwd(hipStream_t s, int p, int d, const bf16_t* Q, const bf16_t*
 // zpart[BH][T] the denominator
 bool launch_chunk_fwd(hipStream_t s, int p, int d, const bf16_t* Q, const bf16_t* K, const bf16_t* V, bf16_t* O, float* Z, int BH,
                       int T, int cs, float scale, int normalize, const float* part, int nslab, const float* zpart);
-// ghat = dO / Z (bf16) and gz = -(ghat . O) (float32) per token, d in {64, 128}
+// ghat = dO / Z (bf16) and gz = -(ghat . O) (float32) per token, d in {32, 64, 128}
 bool launch_attn_prep(hipStream_t s, int d, const bf16_t* dO, const bf16_t* O, const float* Z, bf16_t* Gh, float* gz, long long rows,
                       int normalize);
 // backward of the same: the in-chunk gradients plus the per-slab parts that came through the states (float32

@@ -108,11 +108,53 @@ bool attn_ok(const pa_problem& pr) {
 }
 // One chunk: the attention-form kernels.  (The chunked kernels can run p = 2, d = 64 as one chunk
 // too; that path remains for gated sequences that are a multiple of 128 but not of the block.)
-bool use_attn(const pa_problem& pr) { return attn_ok(pr) && pr.impl != PA_IMPL_RESIDENT; }
+bool use_attn(const pa_problem& pr) { return attn_ok(pr) && pr.impl != PA_IMPL_RESIDENT && pr.impl != PA_IMPL_TILED; }
 // The resident-state kernels run when asked for by name, and wherever they are the only matrix-core kernels
 // for the chunked form (d = 128)
 bool use_resident(const pa_problem& pr) {
-    return resident_ok(pr) && (pr.impl == PA_IMPL_RESIDENT || (!chunked_ok(pr) && !attn_ok(pr)));
+    return pr.impl != PA_IMPL_TILED && resident_ok(pr) && (pr.impl == PA_IMPL_RESIDENT || (!chunked_ok(pr) && !attn_ok(pr)));
+}
+
+// tiled kernels (any degree and tile width, chunk states in memory): workspace of the forward pass, the backward
+// part appended
+struct TiledLayout {
+    TiledPlan pl;
+    size_t off_tab, off_vp, off_sc, off_part, off_zpart;
+    size_t off_gh, off_gz, off_gp, off_rc, off_pdq, off_pdk;   // backward only
+    size_t total;
+};
+int tiled_dt(const pa_problem& pr) { return pr.d_tile > 0 ? pr.d_tile : tiled_default_dt(pr.p); }
+TiledLayout make_tiled_layout(const pa_problem& pr, bool backward) {
+    TiledLayout L{};
+    const size_t BH = (size_t)pr.B * pr.H;
+    L.pl = tiled_plan(pr.p, pr.d, tiled_dt(pr));
+    const size_t rows = BH * pr.T;
+    const size_t st = BH * (pr.T / pr.chunk) * L.pl.state_elems * 2;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        size_t o = off;
+        off = align_up(off + bytes, 256);
+        return o;
+    };
+    L.off_tab = take((size_t)L.pl.nentry * sizeof(TileDesc));
+    L.off_vp = take(rows * L.pl.vp * 2);
+    L.off_sc = take(st);
+    L.off_part = take(rows * pr.d * sizeof(float));
+    L.off_zpart = take(rows * sizeof(float));
+    if (backward || pr.keep_state) {
+        L.off_gh = take(rows * pr.d * 2);
+        L.off_gz = take(rows * sizeof(float));
+        L.off_gp = take(rows * L.pl.vp * 2);
+        L.off_rc = take(st);
+        L.off_pdq = take(rows * pr.d * sizeof(float));
+        L.off_pdk = take(rows * pr.d * sizeof(float));
+    }
+    L.total = off;
+    return L;
+}
+bool tiled_ok(const pa_problem& pr) {
+    return pr.dtype == PA_DTYPE_BF16 && pr.d == pr.v && pr.chunk > 0 && pr.chunk % QBLK == 0 && pr.T % pr.chunk == 0 &&
+           pr.chunk < pr.T && !pr.gated && tiled_shape_ok(pr.p, pr.d, tiled_dt(pr)) && (size_t)pr.B * pr.H <= 65535u;
 }
 
 // attention form, backward: ghat (bf16) and gz (float32) per token
@@ -134,21 +176,36 @@ AttnLayout make_attn_layout(const pa_problem& pr, bool backward) {
     return L;
 }
 
+// The tiled kernels run when asked for by name or for a tile width, and wherever no other matrix-core kernel takes the
+// chunked form of the problem (degrees 3 and 4, d = 32)
+bool use_tiled(const pa_problem& pr) {
+    if (!tiled_ok(pr)) return false;
+    if (pr.impl == PA_IMPL_TILED) return true;
+    if (pr.impl == PA_IMPL_RESIDENT) return false;
+    return pr.d_tile > 0 || (!chunked_ok(pr) && !attn_ok(pr) && !resident_ok(pr));
+}
+
 }  // namespace
 
 int mfma_gate_fin_chunk(const pa_problem& pr) { return use_attn(pr) ? attn_gate_block(pr.d) : pr.chunk; }
 
 pa_status mfma_supported(const pa_problem& pr, bool backward) {
     if (pr.impl == PA_IMPL_RESIDENT) return resident_ok(pr) ? PA_OK : PA_ERR_UNSUPPORTED;
-    return chunked_ok(pr) || attn_ok(pr) || resident_ok(pr) ? PA_OK : PA_ERR_UNSUPPORTED;
+    if (pr.impl == PA_IMPL_TILED || pr.d_tile > 0) return tiled_ok(pr) ? PA_OK : PA_ERR_UNSUPPORTED;
+    return chunked_ok(pr) || attn_ok(pr) || resident_ok(pr) || tiled_ok(pr) ? PA_OK : PA_ERR_UNSUPPORTED;
 }
 
 long long mfma_state_rows(const pa_problem& pr) {
+    if (use_tiled(pr)) {
+        const TiledPlan pl = tiled_plan(pr.p, pr.d, tiled_dt(pr));
+        return (long long)pl.ntile * pl.rows_per_tile;
+    }
     if (use_resident(pr)) return (long long)(pr.d / 8) * (pr.d / 8 + 1) / 2 * 64;
     return use_attn(pr) ? 0 : (long long)NTILES * 64;
 }
 
 size_t mfma_workspace_bytes(const pa_problem& pr, bool backward) {
+    if (use_tiled(pr)) return make_tiled_layout(pr, backward).total;
     if (use_resident(pr)) return make_res_layout(pr, backward).total;
     return use_attn(pr) ? make_attn_layout(pr, backward).total : make_layout(pr, backward).total;
 }
@@ -165,6 +222,24 @@ pa_status mfma_fwd(const Ctx& c, const void* Q, const void* K, const void* V, vo
     if (use_attn(pr)) {
         PA_TRY(launch_attn_fwd(c.stream, pr.p, pr.d, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (bf16_t*)O, Z, BH, pr.T,
                                pr.scale, pr.normalize, c.gate.bl))
+        return PA_OK;
+    }
+    if (use_tiled(pr)) {
+        // tile table, values extended by the normaliser's one, state scan, read-out; the in-chunk part and the
+        // division on the chunk-local attention kernel
+        const TiledLayout L = make_tiled_layout(pr, pr.keep_state != 0);
+        TileDesc* tab = (TileDesc*)(c.ws + L.off_tab);
+        bf16_t* Vp = (bf16_t*)(c.ws + L.off_vp);
+        bf16_t* Sc = (bf16_t*)(c.ws + L.off_sc);
+        float* part = (float*)(c.ws + L.off_part);
+        float* zpart = (float*)(c.ws + L.off_zpart);
+        PA_TRY(launch_tiled_table(c.stream, L.pl, tab))
+        PA_TRY(launch_tiled_pack(c.stream, pr.d, (const bf16_t*)V, nullptr, Vp, (long long)BH * pr.T))
+        PA_TRY(launch_tiled_scan("tiled_state_scan", c.stream, L.pl, false, (const bf16_t*)K, Vp, tab, Sc, BH, pr.T, pr.chunk, 1.0f))
+        PA_TRY(launch_tiled_readout("tiled_query_state", c.stream, L.pl, (const bf16_t*)Q, tab, Sc, part, zpart, BH, pr.T, pr.chunk,
+                                    pr.scale))
+        PA_TRY(launch_chunk_fwd(c.stream, pr.p, pr.d, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (bf16_t*)O, Z, BH, pr.T,
+                                pr.chunk, pr.scale, pr.normalize, part, 1, zpart))
         return PA_OK;
     }
     if (use_resident(pr)) {
@@ -267,6 +342,38 @@ pa_status mfma_bwd(const Ctx& c, const void* Q, const void* K, const void* V, co
         PA_TRY(launch_attn_bwd(c.stream, pr.p, pr.d, (const bf16_t*)Q, (const bf16_t*)K, (const bf16_t*)V, (const bf16_t*)O, Z,
                                (const bf16_t*)dO, (bf16_t*)(c.ws + A.off_gh), (float*)(c.ws + A.off_gz), (bf16_t*)dQ, (bf16_t*)dK,
                                (bf16_t*)dV, BH, pr.T, pr.scale, pr.normalize, ag))
+        return PA_OK;
+    }
+    if (use_tiled(pr)) {
+        // dQ's state part from S and [ghat, gz]; the state gradient R from phi(q) [ghat, gz]^T, read out with phi(k) for
+        // dV and contracted with [v, 1] for dK; one kernel then adds the in-chunk gradients
+        const TiledLayout L = make_tiled_layout(pr, true);
+        TileDesc* tab = (TileDesc*)(c.ws + L.off_tab);
+        bf16_t* Vp = (bf16_t*)(c.ws + L.off_vp);
+        bf16_t* Sc = (bf16_t*)(c.ws + L.off_sc);
+        bf16_t* Gh = (bf16_t*)(c.ws + L.off_gh);
+        float* gz = (float*)(c.ws + L.off_gz);
+        bf16_t* Gp = (bf16_t*)(c.ws + L.off_gp);
+        bf16_t* Rc = (bf16_t*)(c.ws + L.off_rc);
+        float* pdv = (float*)(c.ws + L.off_part);
+        float* pdq = (float*)(c.ws + L.off_pdq);
+        float* pdk = (float*)(c.ws + L.off_pdk);
+        const bf16_t *q = (const bf16_t*)Q, *k = (const bf16_t*)K, *v = (const bf16_t*)V;
+        const long long rows = (long long)BH * pr.T;
+        hipStream_t st = c.stream;
+        PA_TRY(launch_attn_prep(st, pr.d, (const bf16_t*)dO, (const bf16_t*)O, Z, Gh, gz, rows, pr.normalize))
+        PA_TRY(launch_tiled_pack(st, pr.d, Gh, gz, Gp, rows))
+        if (!pr.keep_state) {
+            PA_TRY(launch_tiled_table(st, L.pl, tab))
+            PA_TRY(launch_tiled_pack(st, pr.d, v, nullptr, Vp, rows))
+            PA_TRY(launch_tiled_scan("tiled_state_scan_bwd", st, L.pl, false, k, Vp, tab, Sc, BH, pr.T, pr.chunk, 1.0f))
+        }
+        PA_TRY(launch_tiled_dphi("tiled_dq", st, L.pl, q, Gp, tab, Sc, pdq, BH, pr.T, pr.chunk, pr.scale, pr.scale))
+        PA_TRY(launch_tiled_scan("tiled_state_grad_scan", st, L.pl, true, q, Gp, tab, Rc, BH, pr.T, pr.chunk, pr.scale))
+        PA_TRY(launch_tiled_readout("tiled_dv", st, L.pl, k, tab, Rc, pdv, nullptr, BH, pr.T, pr.chunk, 1.0f))
+        PA_TRY(launch_tiled_dphi("tiled_dk", st, L.pl, k, Vp, tab, Rc, pdk, BH, pr.T, pr.chunk, 1.0f, 1.0f))
+        PA_TRY(launch_chunk_bwd(st, pr.p, pr.d, q, k, v, Gh, gz, (bf16_t*)dQ, (bf16_t*)dK, (bf16_t*)dV, BH, pr.T, pr.chunk, pr.scale,
+                                pdq, 1, pdk, 1, pdv, 1))
         return PA_OK;
     }
     if (use_resident(pr)) {

@@ -1,0 +1,676 @@
+// Chunked form on the matrix cores for any degree and tile width: the tiled symmetric-power embedding of
+// arXiv 2507.04239 Sec. 4.1.1 (TSPOW) with the degree p and the tile width d_tile as template parameters,
+// update-state + cumulative sum (App. E.2, E.3), query-state (App. E.4) and the state parts of the backward
+// pass (derived from the forward definition; the paper gives none).
+//
+// Embedding.  The d features are cut into d / d_tile blocks; a tile is a non-decreasing multi-index
+// (t_1 <= ... <= t_p) of blocks and holds the d_tile^p products x[d_tile t_1 + a_1] ... x[d_tile t_p + a_p].
+// Its multiplicity p! / prod(run lengths)! is an integer and is put on the state (once) instead of its
+// square root on both sides.  A row is written as (alpha, beta): alpha runs over the first p / 2 positions
+// ("left", NL = d_tile^(p/2) values), beta over the others ("right", NR values), row = alpha NR + beta, so
+// that phi[row] = uL[alpha] uR[beta] and the Jacobian factors the same way (dL/duL[alpha] = sum_beta A uR,
+// dL/duR[beta] = sum_alpha A uL, then the chain rule through the one or two features of each side).
+//
+// Work is cut into units of 64 state rows: a 64-row slice of a tile (all beta for 64 / NR values of alpha)
+// when a tile has 64 rows or more, else 64 / rows whole tiles.  phi is formed by one thread per token from
+// that token's features (all digit loops are compile-time, no lane holds a lane-dependent digit), rounded to
+// bf16 once and laid down in LDS as a [token][row] tile, from which the MFMA operands are read - plainly for
+// a contraction over the rows, through the transposing LDS read for a contraction over the tokens.  The
+// gradient with respect to phi takes the same road back: MFMA results go to LDS as [token][row] float32 and
+// the thread that owns the token applies the Jacobian and adds into that token's d accumulators (LDS,
+// [feature][token], touched by their owner only: plain read-add-write).
+//
+// States: per (head, chunk) `nunit` units of 64 rows x VP = d + 16 value columns, bf16, row-major; column d
+// carries the normaliser (the values are extended by a one, App. E.4's l), the remaining 15 are zero.
+// MFMA: v_mfma_f32_16x16x32_bf16, and v_mfma_f32_16x16x16_bf16 for the 16 columns beyond d where the
+// contraction runs over the value columns.  Operand layouts as in mfma_common.hpp.
+#include "mfma_common.hpp"
+
+namespace pa {
+namespace mfma {
+namespace {
+
+constexpr int ipowc(int b, int e) { return e == 0 ? 1 : b * ipowc(b, e - 1); }
+
+template <int P, int DT>
+struct Emb {
+    static constexpr int PL = P / 2, PR = P - PL;
+    static constexpr int NL = ipowc(DT, PL), NR = ipowc(DT, PR), R = NL * NR;
+    static constexpr int TPU = R >= 64 ? 1 : 64 / R;    // tiles per unit
+    static constexpr int UPT = R >= 64 ? R / 64 : 1;    // units per tile
+    static constexpr int NA = R >= 64 ? 64 / NR : NL;   // left indices per unit (per tile when a unit holds whole tiles)
+    static_assert(R % 16 == 0 && (R >= 64 ? 64 % NR == 0 : 64 % R == 0), "tile shape");
+};
+
+// 64 rows x (W + 8) bf16; pitch (W + 8) / 2 dwords = 4 (mod 8) for W = 48, 64, 80, 144
+template <int W>
+struct Tile64 {
+    bf16_t r[64][W + 8];
+};
+
+typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
+
+// Operand of a contraction over the tile's 64 rows: k-slots = rows 32 s + 4g .. + 3 and 32 s + 16 + 4g .. + 3,
+// lane r16 = column c0 + r16 % 4 of the four columns its pointer lane r16 / 4 names.  (The transposing read
+// hands lane n of a 16-lane group column n of the 4 x 16 block whose row j the lanes 4j .. 4j+3 point at.)
+template <int W>
+__device__ __forceinline__ bf16x8 col_frag_at(const Tile64<W>& t, int s, int col4, int r16, int g) {
+    const bf16_t* p = &t.r[32 * s + 4 * g + (r16 >> 2)][col4];
+    union {
+        bf16x8 v;
+        bf16x4 h[2];
+    } f;
+    f.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)p);
+    f.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p + 16 * (W + 8)));
+    return f.v;
+}
+// columns 16 cb .. 16 cb + 15 in order
+template <int W>
+__device__ __forceinline__ bf16x8 col_frag(const Tile64<W>& t, int s, int cb, int r16, int g) {
+    return col_frag_at<W>(t, s, 16 * cb + 4 * (r16 & 3), r16, g);
+}
+
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+__device__ __forceinline__ f32x4 mfma16k16(uint2 a, uint2 b, f32x4 c) {
+    union {
+        uint2 u;
+        s16x4 v;
+    } fa, fb;
+    fa.u = a;
+    fb.u = b;
+    return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(fa.v, fb.v, c, 0, 0, 0);
+}
+
+// LDS traffic of one wave is ordered; this keeps the compiler from moving accesses across the hand-over
+// between the lanes of a wave
+__device__ __forceinline__ void wave_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// ---- the embedding, one thread per token ----------------------------------------------------------------
+// x: the token's features (float32, LDS).  td: the tile (uniform over the wave).
+template <int P, int DT>
+__device__ __forceinline__ void right_feats(const float* x, const TileDesc& td, float (&uR)[Emb<P, DT>::NR]) {
+    using E = Emb<P, DT>;
+    if constexpr (E::PR == 1) {
+#pragma unroll
+        for (int b = 0; b < DT; ++b) uR[b] = x[DT * td.t[E::PL] + b];
+    } else {
+        float xc[DT], xd[DT];
+#pragma unroll
+        for (int i = 0; i < DT; ++i) {
+            xc[i] = x[DT * td.t[E::PL] + i];
+            xd[i] = x[DT * td.t[E::PL + 1] + i];
+        }
+#pragma unroll
+        for (int c = 0; c < DT; ++c)
+#pragma unroll
+            for (int d = 0; d < DT; ++d) uR[c * DT + d] = xc[c] * xd[d];
+    }
+}
+// alpha may be a run-time value (uniform over the wave): features are fetched from LDS by address
+template <int P, int DT>
+__device__ __forceinline__ float left_feat(const float* x, const TileDesc& td, int alpha) {
+    using E = Emb<P, DT>;
+    if constexpr (E::PL == 1) return x[DT * td.t[0] + alpha];
+    else return x[DT * td.t[0] + alpha / DT] * x[DT * td.t[1] + alpha % DT];
+}
+
+template <int P, int DT>
+__device__ __forceinline__ void unit_phi(const float* x, const TileDesc* __restrict__ tab, int unit, float (&phi)[64]) {
+    using E = Emb<P, DT>;
+    if constexpr (E::R >= 64) {
+        const TileDesc td = tab[unit / E::UPT];
+        const int a0 = (unit % E::UPT) * E::NA;
+        float uR[E::NR];
+        right_feats<P, DT>(x, td, uR);
+#pragma unroll
+        for (int ai = 0; ai < E::NA; ++ai) {
+            const float ul = left_feat<P, DT>(x, td, a0 + ai);
+#pragma unroll
+            for (int b = 0; b < E::NR; ++b) phi[ai * E::NR + b] = ul * uR[b];
+        }
+    } else {
+#pragma unroll
+        for (int tt = 0; tt < E::TPU; ++tt) {
+            const TileDesc td = tab[unit * E::TPU + tt];
+            float uR[E::NR];
+            right_feats<P, DT>(x, td, uR);
+#pragma unroll
+            for (int a = 0; a < E::NL; ++a) {
+                const float ul = left_feat<P, DT>(x, td, a);
+#pragma unroll
+                for (int b = 0; b < E::NR; ++b) phi[tt * E::R + a * E::NR + b] = ul * uR[b];
+            }
+        }
+    }
+}
+
+// dx[f] += v for the token whose accumulators start at dx (stride 64 floats between features)
+__device__ __forceinline__ void dx_add(float* dx, int f, float v) { dx[64 * f] += v; }
+
+// chain rule through one side: du[i] = dL/du for the N = DT^PS values of the side whose first position is
+// `pos`; alpha0: index of du[0] within the side (non-zero only for a slice of the left side)
+template <int DT, int PS, int N>
+__device__ __forceinline__ void side_chain(const float* x, const TileDesc& td, int pos, int alpha0, const float (&du)[N], float* dx) {
+    if constexpr (PS == 1) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) dx_add(dx, DT * td.t[pos] + alpha0 + i, du[i]);
+    } else if constexpr (N == DT * DT) {
+        float xc[DT], xd[DT];
+#pragma unroll
+        for (int i = 0; i < DT; ++i) {
+            xc[i] = x[DT * td.t[pos] + i];
+            xd[i] = x[DT * td.t[pos + 1] + i];
+        }
+#pragma unroll
+        for (int c = 0; c < DT; ++c) {
+            float s = 0.f;
+#pragma unroll
+            for (int d = 0; d < DT; ++d) s += du[c * DT + d] * xd[d];
+            dx_add(dx, DT * td.t[pos] + c, s);
+        }
+#pragma unroll
+        for (int d = 0; d < DT; ++d) {
+            float s = 0.f;
+#pragma unroll
+            for (int c = 0; c < DT; ++c) s += du[c * DT + d] * xc[c];
+            dx_add(dx, DT * td.t[pos + 1] + d, s);
+        }
+    } else {
+        // a slice of a two-position side: N consecutive values starting at alpha0 (run-time, uniform)
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const int c = (alpha0 + i) / DT, d = (alpha0 + i) % DT;
+            dx_add(dx, DT * td.t[pos] + c, du[i] * x[DT * td.t[pos + 1] + d]);
+            dx_add(dx, DT * td.t[pos + 1] + d, du[i] * x[DT * td.t[pos] + c]);
+        }
+    }
+}
+
+// A[row] = dL/dphi[row] of the unit's 64 rows for this token; adds J_phi(x)^T A into the token's accumulators
+template <int P, int DT>
+__device__ __forceinline__ void unit_jacobian(const float* x, const TileDesc* __restrict__ tab, int unit, const float (&A)[64],
+                                              float* dx) {
+    using E = Emb<P, DT>;
+    if constexpr (E::R >= 64) {
+        const TileDesc td = tab[unit / E::UPT];
+        const int a0 = (unit % E::UPT) * E::NA;
+        float uR[E::NR], dR[E::NR], dL[E::NA];
+        right_feats<P, DT>(x, td, uR);
+#pragma unroll
+        for (int b = 0; b < E::NR; ++b) dR[b] = 0.f;
+#pragma unroll
+        for (int ai = 0; ai < E::NA; ++ai) {
+            const float ul = left_feat<P, DT>(x, td, a0 + ai);
+            float s = 0.f;
+#pragma unroll
+            for (int b = 0; b < E::NR; ++b) {
+                s += A[ai * E::NR + b] * uR[b];
+                dR[b] += A[ai * E::NR + b] * ul;
+            }
+            dL[ai] = s;
+        }
+        side_chain<DT, E::PL, E::NA>(x, td, 0, a0, dL, dx);
+        side_chain<DT, E::PR, E::NR>(x, td, E::PL, 0, dR, dx);
+    } else {
+#pragma unroll
+        for (int tt = 0; tt < E::TPU; ++tt) {
+            const TileDesc td = tab[unit * E::TPU + tt];
+            float uR[E::NR], dR[E::NR], dL[E::NL];
+            right_feats<P, DT>(x, td, uR);
+#pragma unroll
+            for (int b = 0; b < E::NR; ++b) dR[b] = 0.f;
+#pragma unroll
+            for (int a = 0; a < E::NL; ++a) {
+                const float ul = left_feat<P, DT>(x, td, a);
+                float s = 0.f;
+#pragma unroll
+                for (int b = 0; b < E::NR; ++b) {
+                    s += A[tt * E::R + a * E::NR + b] * uR[b];
+                    dR[b] += A[tt * E::R + a * E::NR + b] * ul;
+                }
+                dL[a] = s;
+            }
+            side_chain<DT, E::PL, E::NL>(x, td, 0, 0, dL, dx);
+            side_chain<DT, E::PR, E::NR>(x, td, E::PL, 0, dR, dx);
+        }
+    }
+}
+
+// 64 token rows of X (bf16, [.][HD]) -> xs[token][HD + 1] float32, times xscale
+template <int HD, int NT>
+__device__ __forceinline__ void stage_x(float (*xs)[HD + 1], const bf16_t* __restrict__ Xrows, int ntok, float xscale, int tid) {
+    for (int id = tid; id < ntok * (HD / 8); id += NT) {
+        const int row = id / (HD / 8), c8 = id % (HD / 8);
+        const uint4 u = *(const uint4*)(Xrows + (size_t)row * HD + 8 * c8);
+        float* dst = &xs[row][8 * c8];
+        dst[0] = xscale * bf_lo(u.x); dst[1] = xscale * bf_hi(u.x);
+        dst[2] = xscale * bf_lo(u.y); dst[3] = xscale * bf_hi(u.y);
+        dst[4] = xscale * bf_lo(u.z); dst[5] = xscale * bf_hi(u.z);
+        dst[6] = xscale * bf_lo(u.w); dst[7] = xscale * bf_hi(u.w);
+    }
+}
+
+// phi[64] -> one row of a [token][row] tile, rounded to bf16
+__device__ __forceinline__ void put_phi(Tile64<64>& t, int token, const float (&phi)[64]) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        Frag f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) f.v[j] = (__bf16)phi[8 * i + j];
+        *(uint4*)&t.r[token][8 * i] = f.u;
+    }
+}
+
+// ---- tile table ------------------------------------------------------------------------------------------
+__device__ __forceinline__ int binom(int n, int k) {
+    if (k < 0 || k > n) return 0;
+    int r = 1;
+    for (int i = 1; i <= k; ++i) r = r * (n - k + i) / i;
+    return r;
+}
+// entry i: the i-th non-decreasing multi-index of length p over nb blocks (lexicographic) and its
+// multiplicity; entries from ntile on are padding (multiplicity 0: their state rows stay zero)
+__global__ __launch_bounds__(256) void k_tile_table(TileDesc* __restrict__ tab, int p, int nb, int ntile, int nentry) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= nentry) return;
+    TileDesc td;
+    td.t[0] = td.t[1] = td.t[2] = td.t[3] = 0;
+    td.mult = 0.f;
+    if (i < ntile) {
+        int rem = i, lo = 0;
+        for (int pos = 0; pos < p; ++pos) {
+            const int left = p - pos - 1;   // positions after this one
+            for (int f = lo; f < nb; ++f) {
+                const int cnt = binom(nb - f + left - 1, left);   // non-decreasing tails over blocks f .. nb - 1
+                if (rem < cnt) {
+                    td.t[pos] = (unsigned char)f;
+                    lo = f;
+                    break;
+                }
+                rem -= cnt;
+            }
+        }
+        float m = 1.f;
+        int run = 1;
+        for (int pos = 0; pos < p; ++pos) {
+            m *= (float)(pos + 1);
+            if (pos > 0 && td.t[pos] == td.t[pos - 1]) ++run; else run = 1;
+            m /= (float)run;
+        }
+        td.mult = m;
+    }
+    tab[i] = td;
+}
+
+// Yp[row][0 .. HD-1] = Y[row], Yp[row][HD] = col[row] (1 when col is null), zeros up to HD + 15
+template <int HD>
+__global__ __launch_bounds__(256) void k_tiled_pack(const bf16_t* __restrict__ Y, const float* __restrict__ col,
+                                                    bf16_t* __restrict__ Yp, long long rows) {
+    constexpr int VP = HD + 16, PPR = VP / 8;
+    const long long id = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (id >= rows * PPR) return;
+    const long long row = id / PPR;
+    const int c8 = (int)(id % PPR);
+    uint4 u = make_uint4(0, 0, 0, 0);
+    if (c8 < HD / 8) u = *(const uint4*)(Y + row * HD + 8 * c8);
+    else if (c8 == HD / 8) u.x = f32_to_bf16(col != nullptr ? col[row] : 1.f);
+    *(uint4*)(Yp + row * VP + 8 * c8) = u;
+}
+
+// ---- update-state and cumulative sum ----------------------------------------------------------------------
+// One workgroup walks a group of four units (256 state rows) of one head over the whole sequence; wave w owns
+// unit 4 group + w as float32 accumulators, transposed (value column x state row, so that a lane ends up
+// with VP / 4 consecutive value columns of one state row).  Before the tokens of chunk c are added, the
+// running sum - the state entering chunk c - is stored (REV: the walk runs from the last chunk down and the
+// stored sum is the state gradient of the chunks after c).  X: the rows phi is formed from (K; REV: Q, times
+// xscale), Yp: the extended value rows ([V, 1]; REV: [ghat, gz]).
+template <int P, int DT, int HD, bool REV>
+__global__ __launch_bounds__(256) void k_tiled_scan(const bf16_t* __restrict__ X, const bf16_t* __restrict__ Yp,
+                                                    const TileDesc* __restrict__ tab, bf16_t* __restrict__ st, int T, int cs,
+                                                    int nunit, float xscale) {
+    using E = Emb<P, DT>;
+    constexpr int VP = HD + 16, NVB = VP / 16;
+    __shared__ float xs[64][HD + 1];
+    __shared__ __attribute__((aligned(16))) Tile64<VP> yt;
+    __shared__ __attribute__((aligned(16))) Tile64<64> phis[4];
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6), r16 = lane & 15, g = lane >> 4;
+    const int unit = blockIdx.x * 4 + w, bh = blockIdx.y, nchunk = T / cs;
+    const size_t head = (size_t)bh * T;
+
+    float mult[4];
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb) mult[nb] = tab[E::R >= 64 ? unit / E::UPT : unit * E::TPU + (16 * nb) / E::R].mult;
+    f32x4 acc[NVB][4];
+#pragma unroll
+    for (int vb = 0; vb < NVB; ++vb)
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb) acc[vb][nb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    for (int ci = 0; ci < nchunk; ++ci) {
+        const int c = REV ? nchunk - 1 - ci : ci;
+        bf16_t* dst = st + (((size_t)bh * nchunk + c) * nunit + unit) * 64 * VP;
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+            for (int vb = 0; vb < NVB; ++vb) {
+                bf16x4 o;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) o[r] = (__bf16)(acc[vb][nb][r] * mult[nb]);
+                *(bf16x4*)(dst + (size_t)(16 * nb + r16) * VP + g * (VP / 4) + 4 * vb) = o;
+            }
+        if (ci == nchunk - 1) break;   // nothing reads a sum that includes the last chunk walked
+        for (int step = 0; step < cs / 64; ++step) {
+            const size_t tok0 = head + (size_t)c * cs + 64 * step;
+            __syncthreads();
+            stage_x<HD, 256>(xs, X + tok0 * HD, 64, xscale, tid);
+            for (int id = tid; id < 64 * (VP / 8); id += 256) {
+                const int row = id / (VP / 8), c8 = id % (VP / 8);
+                *(uint4*)&yt.r[row][8 * c8] = *(const uint4*)(Yp + (tok0 + row) * VP + 8 * c8);
+            }
+            __syncthreads();
+            {
+                float phi[64];
+                unit_phi<P, DT>(&xs[lane][0], tab, unit, phi);
+                put_phi(phis[w], lane, phi);
+            }
+            wave_sync();
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                bf16x8 pf[4];
+#pragma unroll
+                for (int nb = 0; nb < 4; ++nb) pf[nb] = col_frag<64>(phis[w], s, nb, r16, g);
+#pragma unroll
+                for (int vb = 0; vb < NVB; ++vb) {
+                    // A row 4 g' + r of block vb is value column g' VP / 4 + 4 vb + r
+                    const bf16x8 yf = col_frag_at<VP>(yt, s, (r16 & 3) * (VP / 4) + 4 * vb, r16, g);
+#pragma unroll
+                    for (int nb = 0; nb < 4; ++nb) acc[vb][nb] = mfma16(yf, pf[nb], acc[vb][nb]);
+                }
+            }
+            wave_sync();
+        }
+    }
+}
+
+// ---- query-state: part[t][:] = S_chunk(t)^T phi(x_t) -------------------------------------------------------
+// A workgroup of two waves takes 128 tokens of one chunk (64 per wave, O^T accumulators in registers) and
+// streams that chunk's state, unit by unit, through a two-slot LDS ring.  zpart (may be null) receives the
+// normaliser column's share.  Also serves dV: the state gradient read out with phi(k).
+template <int P, int DT, int HD>
+__global__ __launch_bounds__(128) void k_tiled_readout(const bf16_t* __restrict__ X, const TileDesc* __restrict__ tab,
+                                                       const bf16_t* __restrict__ st, float* __restrict__ part,
+                                                       float* __restrict__ zpart, int T, int cs, int nunit, int nunit_real,
+                                                       float xscale) {
+    constexpr int VP = HD + 16, NVB = VP / 16, PIECES = 64 * (VP / 8), PPT = (PIECES + 127) / 128;
+    __shared__ float xs[128][HD + 1];
+    __shared__ __attribute__((aligned(16))) Tile64<VP> stt[2];
+    __shared__ __attribute__((aligned(16))) Tile64<64> phis[2];
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6), r16 = lane & 15, g = lane >> 4;
+    const int bh = blockIdx.y, tok0 = blockIdx.x * 128, nchunk = T / cs, chunk = tok0 / cs;
+    const size_t head = (size_t)bh * T;
+    const bf16_t* sbase = st + ((size_t)bh * nchunk + chunk) * nunit * 64 * VP;
+
+    stage_x<HD, 128>(xs, X + (head + tok0) * HD, 128, xscale, tid);
+    f32x4 acc[NVB][4];
+#pragma unroll
+    for (int vb = 0; vb < NVB; ++vb)
+#pragma unroll
+        for (int ib = 0; ib < 4; ++ib) acc[vb][ib] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    uint4 pre[PPT];
+#pragma unroll
+    for (int q = 0; q < PPT; ++q) {
+        const int id = tid + 128 * q;
+        if (id < PIECES) pre[q] = *(const uint4*)(sbase + (size_t)id * 8);
+    }
+    for (int u = 0; u < nunit_real; ++u) {
+        Tile64<VP>& cur = stt[u & 1];
+#pragma unroll
+        for (int q = 0; q < PPT; ++q) {
+            const int id = tid + 128 * q;
+            if (id < PIECES) *(uint4*)&cur.r[id / (VP / 8)][8 * (id % (VP / 8))] = pre[q];
+        }
+        __syncthreads();
+        if (u + 1 < nunit_real) {
+#pragma unroll
+            for (int q = 0; q < PPT; ++q) {
+                const int id = tid + 128 * q;
+                if (id < PIECES) pre[q] = *(const uint4*)(sbase + ((size_t)(u + 1) * PIECES + id) * 8);
+            }
+        }
+        {
+            float phi[64];
+            unit_phi<P, DT>(&xs[64 * w + lane][0], tab, u, phi);
+            put_phi(phis[w], lane, phi);
+        }
+        wave_sync();
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            Frag qf[4];
+#pragma unroll
+            for (int ib = 0; ib < 4; ++ib) {
+                qf[ib].h[0] = *(const uint2*)&phis[w].r[16 * ib + r16][32 * s + 4 * g];
+                qf[ib].h[1] = *(const uint2*)&phis[w].r[16 * ib + r16][32 * s + 16 + 4 * g];
+            }
+#pragma unroll
+            for (int vb = 0; vb < NVB; ++vb) {
+                const bf16x8 sf = col_frag<VP>(cur, s, vb, r16, g);
+#pragma unroll
+                for (int ib = 0; ib < 4; ++ib) acc[vb][ib] = mfma16(sf, qf[ib].v, acc[vb][ib]);
+            }
+        }
+        wave_sync();
+    }
+#pragma unroll
+    for (int ib = 0; ib < 4; ++ib) {
+        const size_t row = head + tok0 + 64 * w + 16 * ib + r16;
+#pragma unroll
+        for (int vb = 0; vb < HD / 16; ++vb)
+            *(float4*)(part + row * HD + 16 * vb + 4 * g) =
+                make_float4(acc[vb][ib][0], acc[vb][ib][1], acc[vb][ib][2], acc[vb][ib][3]);
+        if (zpart != nullptr && g == 0) zpart[row] = acc[HD / 16][ib][0];
+    }
+}
+
+// ---- d phi and the Jacobian: part[t][:] = outscale J_phi(x_t)^T (S_chunk(t) y'_t) --------------------------
+// Same shape as the read-out.  Per unit: A = S y'^T on the matrix cores (contraction over the VP value
+// columns; y' = [ghat, gz] for dQ, [v, 1] for dK, held as operand fragments in registers), laid down in
+// LDS as [token][row], then the Jacobian by the thread that owns the token.
+template <int P, int DT, int HD>
+__global__ __launch_bounds__(128) void k_tiled_dphi(const bf16_t* __restrict__ X, const bf16_t* __restrict__ Yp,
+                                                    const TileDesc* __restrict__ tab, const bf16_t* __restrict__ st,
+                                                    float* __restrict__ part, int T, int cs, int nunit, int nunit_real,
+                                                    float xscale, float outscale) {
+    constexpr int VP = HD + 16, NK = HD / 32, PIECES = 64 * (VP / 8), PPT = (PIECES + 127) / 128, AP = 64 + 4;
+    __shared__ float xs[128][HD + 1];
+    __shared__ __attribute__((aligned(16))) Tile64<VP> stt[2];
+    __shared__ __attribute__((aligned(16))) float dph[2][64][AP];
+    __shared__ float dxs[2][HD][64];
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6), r16 = lane & 15, g = lane >> 4;
+    const int bh = blockIdx.y, tok0 = blockIdx.x * 128, nchunk = T / cs, chunk = tok0 / cs;
+    const size_t head = (size_t)bh * T;
+    const bf16_t* sbase = st + ((size_t)bh * nchunk + chunk) * nunit * 64 * VP;
+
+    stage_x<HD, 128>(xs, X + (head + tok0) * HD, 128, xscale, tid);
+#pragma unroll
+    for (int f = 0; f < HD; ++f) dxs[w][f][lane] = 0.f;
+    Frag yf[4][NK];
+    uint2 ytail[4];
+#pragma unroll
+    for (int ib = 0; ib < 4; ++ib) {
+        const bf16_t* yrow = Yp + (head + tok0 + 64 * w + 16 * ib + r16) * VP;
+#pragma unroll
+        for (int ks = 0; ks < NK; ++ks) yf[ib][ks].u = *(const uint4*)(yrow + 32 * ks + 8 * g);
+        ytail[ib] = *(const uint2*)(yrow + HD + 4 * g);
+    }
+
+    uint4 pre[PPT];
+#pragma unroll
+    for (int q = 0; q < PPT; ++q) {
+        const int id = tid + 128 * q;
+        if (id < PIECES) pre[q] = *(const uint4*)(sbase + (size_t)id * 8);
+    }
+    for (int u = 0; u < nunit_real; ++u) {
+        Tile64<VP>& cur = stt[u & 1];
+#pragma unroll
+        for (int q = 0; q < PPT; ++q) {
+            const int id = tid + 128 * q;
+            if (id < PIECES) *(uint4*)&cur.r[id / (VP / 8)][8 * (id % (VP / 8))] = pre[q];
+        }
+        __syncthreads();
+        if (u + 1 < nunit_real) {
+#pragma unroll
+            for (int q = 0; q < PPT; ++q) {
+                const int id = tid + 128 * q;
+                if (id < PIECES) pre[q] = *(const uint4*)(sbase + ((size_t)(u + 1) * PIECES + id) * 8);
+            }
+        }
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb) {
+            Frag sf[NK];
+#pragma unroll
+            for (int ks = 0; ks < NK; ++ks) sf[ks].u = *(const uint4*)&cur.r[16 * nb + r16][32 * ks + 8 * g];
+            const uint2 stail = *(const uint2*)&cur.r[16 * nb + r16][HD + 4 * g];
+#pragma unroll
+            for (int ib = 0; ib < 4; ++ib) {
+                f32x4 c = {0.f, 0.f, 0.f, 0.f};   // rows 16 nb + 4g + r, token 16 ib + r16
+#pragma unroll
+                for (int ks = 0; ks < NK; ++ks) c = mfma16(sf[ks].v, yf[ib][ks].v, c);
+                c = mfma16k16(stail, ytail[ib], c);
+                *(float4*)&dph[w][16 * ib + r16][16 * nb + 4 * g] = make_float4(c[0], c[1], c[2], c[3]);
+            }
+        }
+        wave_sync();
+        {
+            float A[64];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const float4 a4 = *(const float4*)&dph[w][lane][4 * i];
+                A[4 * i] = a4.x; A[4 * i + 1] = a4.y; A[4 * i + 2] = a4.z; A[4 * i + 3] = a4.w;
+            }
+            unit_jacobian<P, DT>(&xs[64 * w + lane][0], tab, u, A, &dxs[w][0][lane]);
+        }
+        wave_sync();
+    }
+    float* out = part + (head + tok0 + 64 * w + lane) * HD;
+#pragma unroll
+    for (int f4 = 0; f4 < HD / 4; ++f4)
+        *(float4*)(out + 4 * f4) = make_float4(outscale * dxs[w][4 * f4][lane], outscale * dxs[w][4 * f4 + 1][lane],
+                                               outscale * dxs[w][4 * f4 + 2][lane], outscale * dxs[w][4 * f4 + 3][lane]);
+}
+
+template <int P, int DT, int HD>
+bool scan_t(const char* name, hipStream_t s, const TiledPlan& pl, bool rev, const bf16_t* X, const bf16_t* Yp, const TileDesc* tab,
+            bf16_t* st, int BH, int T, int cs, float xscale) {
+    LaunchScope ls(name, s);
+    const dim3 grid(pl.nunit / 4, BH);
+    if (rev) hipLaunchKernelGGL((k_tiled_scan<P, DT, HD, true>), grid, dim3(256), 0, s, X, Yp, tab, st, T, cs, pl.nunit, xscale);
+    else hipLaunchKernelGGL((k_tiled_scan<P, DT, HD, false>), grid, dim3(256), 0, s, X, Yp, tab, st, T, cs, pl.nunit, xscale);
+    return launch_ok();
+}
+template <int P, int DT, int HD>
+bool readout_t(const char* name, hipStream_t s, const TiledPlan& pl, const bf16_t* X, const TileDesc* tab, const bf16_t* st,
+               float* part, float* zpart, int BH, int T, int cs, float xscale) {
+    LaunchScope ls(name, s);
+    hipLaunchKernelGGL((k_tiled_readout<P, DT, HD>), dim3(T / 128, BH), dim3(128), 0, s, X, tab, st, part, zpart, T, cs, pl.nunit,
+                       pl.nunit_real, xscale);
+    return launch_ok();
+}
+template <int P, int DT, int HD>
+bool dphi_t(const char* name, hipStream_t s, const TiledPlan& pl, const bf16_t* X, const bf16_t* Yp, const TileDesc* tab,
+            const bf16_t* st, float* part, int BH, int T, int cs, float xscale, float outscale) {
+    LaunchScope ls(name, s);
+    hipLaunchKernelGGL((k_tiled_dphi<P, DT, HD>), dim3(T / 128, BH), dim3(128), 0, s, X, Yp, tab, st, part, T, cs, pl.nunit,
+                       pl.nunit_real, xscale, outscale);
+    return launch_ok();
+}
+
+}  // namespace
+
+// every (degree, tile width, head size) the kernels are built for
+#define PA_TILED_SHAPES(X) \
+    X(2, 4, 32) X(2, 8, 32) X(2, 16, 32) X(3, 4, 32) X(4, 2, 32) X(4, 4, 32) \
+    X(2, 4, 64) X(2, 8, 64) X(2, 16, 64) X(3, 4, 64)
+
+bool tiled_shape_ok(int p, int d, int dt) {
+#define PA_X(PP, DD, HH) \
+    if (p == PP && dt == DD && d == HH) return true;
+    PA_TILED_SHAPES(PA_X)
+#undef PA_X
+    return false;
+}
+
+int tiled_default_dt(int p) { return p == 2 ? 8 : 4; }
+
+TiledPlan tiled_plan(int p, int d, int dt) {
+    TiledPlan pl{};
+    pl.p = p;
+    pl.dt = dt;
+    pl.hd = d;
+    pl.vp = d + 16;
+    const int nb = d / dt;
+    long long nt = 1;   // C(nb + p - 1, p)
+    for (int i = 1; i <= p; ++i) nt = nt * (nb + p - i) / i;
+    pl.ntile = (int)nt;
+    int rows = 1;
+    for (int i = 0; i < p; ++i) rows *= dt;
+    pl.rows_per_tile = rows;
+    pl.nunit_real = rows >= 64 ? pl.ntile * (rows / 64) : (pl.ntile + 64 / rows - 1) / (64 / rows);
+    pl.nunit = (pl.nunit_real + 3) / 4 * 4;
+    pl.nentry = rows >= 64 ? (pl.nunit + rows / 64 - 1) / (rows / 64) : pl.nunit * (64 / rows);
+    pl.state_elems = (size_t)pl.nunit * 64 * pl.vp;
+    return pl;
+}
+
+bool launch_tiled_table(hipStream_t s, const TiledPlan& pl, TileDesc* tab) {
+    LaunchScope ls("tiled_table", s);
+    hipLaunchKernelGGL(k_tile_table, dim3((pl.nentry + 255) / 256), dim3(256), 0, s, tab, pl.p, pl.hd / pl.dt, pl.ntile, pl.nentry);
+    return launch_ok();
+}
+
+bool launch_tiled_pack(hipStream_t s, int hd, const bf16_t* Y, const float* col, bf16_t* Yp, long long rows) {
+    LaunchScope ls("tiled_pack", s);
+    const long long n = rows * ((hd + 16) / 8);
+    if (hd == 32) hipLaunchKernelGGL((k_tiled_pack<32>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, Y, col, Yp, rows);
+    else if (hd == 64) hipLaunchKernelGGL((k_tiled_pack<64>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, Y, col, Yp, rows);
+    else return false;
+    return launch_ok();
+}
+
+bool launch_tiled_scan(const char* name, hipStream_t s, const TiledPlan& pl, bool rev, const bf16_t* X, const bf16_t* Yp,
+                       const TileDesc* tab, bf16_t* st, int BH, int T, int cs, float xscale) {
+    if (cs % 128 != 0 || T % cs != 0) return false;
+#define PA_X(PP, DD, HH) \
+    if (pl.p == PP && pl.dt == DD && pl.hd == HH) return scan_t<PP, DD, HH>(name, s, pl, rev, X, Yp, tab, st, BH, T, cs, xscale);
+    PA_TILED_SHAPES(PA_X)
+#undef PA_X
+    return false;
+}
+
+bool launch_tiled_readout(const char* name, hipStream_t s, const TiledPlan& pl, const bf16_t* X, const TileDesc* tab, const bf16_t* st,
+                          float* part, float* zpart, int BH, int T, int cs, float xscale) {
+    if (cs % 128 != 0 || T % cs != 0) return false;
+#define PA_X(PP, DD, HH) \
+    if (pl.p == PP && pl.dt == DD && pl.hd == HH) return readout_t<PP, DD, HH>(name, s, pl, X, tab, st, part, zpart, BH, T, cs, xscale);
+    PA_TILED_SHAPES(PA_X)
+#undef PA_X
+    return false;
+}
+
+bool launch_tiled_dphi(const char* name, hipStream_t s, const TiledPlan& pl, const bf16_t* X, const bf16_t* Yp, const TileDesc* tab,
+                       const bf16_t* st, float* part, int BH, int T, int cs, float xscale, float outscale) {
+    if (cs % 128 != 0 || T % cs != 0) return false;
+#define PA_X(PP, DD, HH)                           \
+    if (pl.p == PP && pl.dt == DD && pl.hd == HH) \
+        return dphi_t<PP, DD, HH>(name, s, pl, X, Yp, tab, st, part, BH, T, cs, xscale, outscale);
+    PA_TILED_SHAPES(PA_X)
+#undef PA_X
+    return false;
+}
+
+}  // namespace mfma
+}  // namespace pa

@@ -60,8 +60,10 @@ pa_status validate(const pa_problem* pr) {
         return PA_ERR_INVALID_ARG;
     if (pr->normalize != 0 && (pr->p % 2) != 0) return PA_ERR_INVALID_ARG;  // scores must be positive to normalise
     if (pr->dtype != PA_DTYPE_F32 && pr->dtype != PA_DTYPE_BF16) return PA_ERR_INVALID_ARG;
-    if (pr->impl != PA_IMPL_AUTO && pr->impl != PA_IMPL_GENERIC && pr->impl != PA_IMPL_MFMA && pr->impl != PA_IMPL_RESIDENT)
+    if (pr->impl != PA_IMPL_AUTO && pr->impl != PA_IMPL_GENERIC && pr->impl != PA_IMPL_MFMA && pr->impl != PA_IMPL_RESIDENT &&
+        pr->impl != PA_IMPL_TILED)
         return PA_ERR_INVALID_ARG;
+    if (pr->d_tile < 0) return PA_ERR_INVALID_ARG;
     if (!(pr->scale == pr->scale) || pr->scale == 0.f) return PA_ERR_INVALID_ARG;
     if (pr->gated != 0 && pr->gated != 1) return PA_ERR_INVALID_ARG;
     return PA_OK;
@@ -78,7 +80,7 @@ pa_status validate(const pa_problem* pr) {
 // factor of two against the attention form: the generic kernels' in-chunk code does about half as many
 // multiply-adds per second as their state code (config 1, T = 256: 0.32 ms as one chunk, 0.14 ms chunked).
 int auto_chunk(const pa_problem& pr) {
-    const bool may_mfma = pr.impl == PA_IMPL_AUTO || pr.impl == PA_IMPL_MFMA || pr.impl == PA_IMPL_RESIDENT;
+    const bool may_mfma = pr.impl == PA_IMPL_AUTO || pr.impl == PA_IMPL_MFMA || pr.impl == PA_IMPL_RESIDENT || pr.impl == PA_IMPL_TILED;
     pa_problem probe = pr;
     probe.chunk = pr.T;
     const bool attn = may_mfma && mfma_supported(probe, true) == PA_OK;
@@ -108,10 +110,10 @@ pa_problem resolved(const pa_problem* prob) {
 
 // PA_IMPL_GENERIC / PA_IMPL_MFMA, or a negative status
 int choose(const pa_problem& pr, bool backward, pa_status* why) {
-    if (pr.impl == PA_IMPL_MFMA || pr.impl == PA_IMPL_RESIDENT || pr.impl == PA_IMPL_AUTO) {
+    if (pr.impl == PA_IMPL_MFMA || pr.impl == PA_IMPL_RESIDENT || pr.impl == PA_IMPL_TILED || pr.impl == PA_IMPL_AUTO) {
         pa_status st = mfma_supported(pr, backward);
         if (st == PA_OK) return PA_IMPL_MFMA;
-        if (pr.impl != PA_IMPL_AUTO) {
+        if (pr.impl != PA_IMPL_AUTO || pr.d_tile > 0) {   // a tile width is a request for the kernels that have one
             *why = st;
             return -1;
         }

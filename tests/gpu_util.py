@@ -53,7 +53,7 @@ def to_np(t):
 
 
 def run_fwd_bwd(Q, K, V, G, p, chunk, dtype, normalize=True, scale=1.0, impl="auto", backward=True,
-                keep_state=False, log_g=None):
+                keep_state=False, log_g=None, d_tile=0):
     """-> dict of numpy arrays O, Z (and dQ, dK, dV; dlog_g when log_g is given) computed by the HIP
     library.  keep_state: the backward pass reuses the chunk states the forward pass left in a
     shared workspace."""
@@ -64,14 +64,15 @@ def run_fwd_bwd(Q, K, V, G, p, chunk, dtype, normalize=True, scale=1.0, impl="au
     ws = None
     if keep_state:
         B, H, T, d = Q.shape
-        prob = binding.make_problem(B, H, T, d, V.shape[3], p, chunk, normalize, scale, dtype, impl, True, log_g is not None)
+        prob = binding.make_problem(B, H, T, d, V.shape[3], p, chunk, normalize, scale, dtype, impl, True, log_g is not None, d_tile)
         ws = torch.empty(max(binding.power_attn_workspace_bytes(prob, True), 256), dtype=torch.uint8, device="cuda:0")
-    O, Z = power_attn_fwd(tq, tk, tv, p, chunk, normalize, scale, impl, workspace=ws, keep_state=keep_state, log_g=tl)
+    O, Z = power_attn_fwd(tq, tk, tv, p, chunk, normalize, scale, impl, workspace=ws, keep_state=keep_state, log_g=tl,
+                          d_tile=d_tile)
     out = {"O": O, "Z": Z}
     if backward:
         tg = to_dev(G, dtype)
         res = power_attn_bwd(tq, tk, tv, O, Z, tg, p, chunk, normalize, scale, impl, workspace=ws,
-                             keep_state=keep_state, log_g=tl)
+                             keep_state=keep_state, log_g=tl, d_tile=d_tile)
         out.update(dQ=res[0], dK=res[1], dV=res[2])
         if log_g is not None:
             out.update(dlog_g=res[3])

@@ -1,0 +1,65 @@
+"""GPU parity of the tiled chunked kernels (impl = "tiled": degree and tile width of the embedding as
+parameters, chunk states in memory) against the float64 oracle, for every (p, d_tile, d) they are built for."""
+import numpy as np
+import pytest
+
+from oracle import power_attn_oracle as orc
+from paper_2507_04239_amd import inputs
+
+from gpu_util import assert_close, run_fwd_bwd
+
+pytestmark = pytest.mark.gpu
+
+# (p, d_tile, d): tiles of 16, 64 and 256 rows; one and two features per side of a row's product
+SHAPES = [
+    (2, 4, 32), (2, 8, 32), (2, 16, 32), (3, 4, 32), (4, 2, 32), (4, 4, 32),
+    (2, 4, 64), (2, 8, 64), (2, 16, 64), (3, 4, 64),
+]
+
+
+@pytest.mark.parametrize("p,dt,d", SHAPES)
+def test_tiled_forward_backward(p, dt, d):
+    B, H, T, chunk = 1, 2, 512, 128
+    norm = p % 2 == 0
+    Q, K, V, G = inputs.make_qkvg(B, H, T, d, seed=5000 + 100 * p + dt + d, dtype="bf16")
+    print("case", (p, dt, d), flush=True)
+    got = run_fwd_bwd(Q, K, V, G, p, chunk, "bf16", normalize=norm, impl="tiled", d_tile=dt)
+    O, Z = orc.fwd_bhtd(Q, K, V, p, chunk, norm, 1.0)
+    dQ, dK, dV = orc.bwd_bhtd(Q, K, V, G, p, chunk, norm, 1.0)
+    want = dict(O=O, Z=Z, dQ=dQ, dK=dK, dV=dV) if norm else dict(O=O, dQ=dQ, dK=dK, dV=dV)
+    assert_close(got, want, "bf16", f"tiled {(p, dt, d)}")
+
+
+# (p, d_tile, d, B, H, T, chunk, scale, keep_state): larger chunks, several heads, kept states, a scale
+CASES = [
+    (4, 4, 32, 2, 2, 1024, 256, 0.8, True),
+    (4, 2, 32, 1, 3, 768, 128, 1.0, True),
+    (3, 4, 32, 1, 2, 1024, 512, 0.7, False),
+    (2, 8, 64, 1, 2, 1024, 256, 1.0, True),
+    (3, 4, 64, 1, 1, 512, 128, 1.2, True),
+]
+
+
+@pytest.mark.parametrize("p,dt,d,B,H,T,chunk,scale,keep", CASES)
+def test_tiled_shapes(p, dt, d, B, H, T, chunk, scale, keep):
+    norm = p % 2 == 0
+    Q, K, V, G = inputs.make_qkvg(B, H, T, d, seed=5100 + T + 10 * p + dt, dtype="bf16")
+    print("case", (p, dt, d, B, H, T, chunk, scale, keep), flush=True)
+    got = run_fwd_bwd(Q, K, V, G, p, chunk, "bf16", normalize=norm, scale=scale, impl="tiled", keep_state=keep, d_tile=dt)
+    O, Z = orc.fwd_bhtd(Q, K, V, p, chunk, norm, scale)
+    dQ, dK, dV = orc.bwd_bhtd(Q, K, V, G, p, chunk, norm, scale)
+    want = dict(O=O, Z=Z, dQ=dQ, dK=dK, dV=dV) if norm else dict(O=O, dQ=dQ, dK=dK, dV=dV)
+    assert_close(got, want, "bf16", f"tiled {(p, dt, d, B, H, T, chunk, scale, keep)}")
+
+
+def test_automatic_choice_runs_the_tiled_kernels_for_degree_four():
+    """The chunked form of p = 4, d = 32 with no family named: the state rows reported are those of the tiled
+    embedding (330 tiles of 256 rows), i.e. the matrix-core kernels run, not the vector-ALU family."""
+    from paper_2507_04239_amd import binding
+    prob = binding.make_problem(1, 2, 512, 32, 32, 4, 128, True, 1.0, "bf16", "auto")
+    assert binding.power_attn_state_rows(prob) == 330 * 256
+    Q, K, V, G = inputs.make_qkvg(1, 2, 512, 32, seed=5200, dtype="bf16")
+    got = run_fwd_bwd(Q, K, V, G, 4, 128, "bf16")
+    O, Z = orc.fwd_bhtd(Q, K, V, 4, 128, True, 1.0)
+    dQ, dK, dV = orc.bwd_bhtd(Q, K, V, G, 4, 128, True, 1.0)
+    assert_close(got, dict(O=O, Z=Z, dQ=dQ, dK=dK, dV=dV), "bf16", "auto p=4 d=32")
