@@ -48,6 +48,10 @@ def algorithmic_flops(w):
     f["chunk_fwd"] = pairs * (2 * d + 2 * (v + 1))
     f["chunk_dq"] = pairs * (4 * d + 2 * v + 2)
     f["chunk_dkdv"] = pairs * (2 * d + 2 * v)
+    # tiled kernels: each state contraction is a launch of its own, the in-chunk parts run on the chunk_* kernels
+    f["query_state"] = state
+    f["dphi"] = state
+    f["dv_readout"] = BH * (n - 1) * c * 2 * D * v
     f["recompute"] = 0   # a backward pass that rebuilds the chunk states: executed, not credited
     f["fwd_total"] = f["update_state"] + f["fwd_chunk"]
     f["bwd_total"] = f["state_grad"] + f["bwd_dq"] + f["bwd_dkdv"]
@@ -80,6 +84,9 @@ def algorithmic_bytes(w):
         "walk_fwd": 3 * tok + BH * T * v * 4, "walk_dq": 4 * tok + BH * T * d * 4,
         "walk_dv": 3 * tok + BH * T * v * 4, "walk_dk": 4 * tok + BH * T * d * 4,
         "chunk_fwd": 4 * tok + BH * T * 4, "chunk_dq": 5 * tok + BH * T * 4, "chunk_dkdv": 7 * tok + BH * T * 4,
+        # tiled kernels: the states once, the token rows in, the float32 result out
+        "query_state": states + tok + BH * T * (v + 1) * 4, "dphi": states + 2 * tok + BH * T * d * 4,
+        "dv_readout": states + tok + BH * T * v * 4,
     }
 
 
@@ -104,6 +111,13 @@ KERNEL_ROLE = {
     "res_dq_walk": ("walk_dq", PEAK_BF16_MFMA_TFLOPS),
     "res_dv_walk": ("walk_dv", PEAK_BF16_MFMA_TFLOPS),
     "res_dk_walk": ("walk_dk", PEAK_BF16_MFMA_TFLOPS),
+    "tiled_state_scan": ("update_state", PEAK_BF16_MFMA_TFLOPS),
+    "tiled_state_scan_bwd": ("recompute", PEAK_BF16_MFMA_TFLOPS),
+    "tiled_query_state": ("query_state", PEAK_BF16_MFMA_TFLOPS),
+    "tiled_state_grad_scan": ("state_grad", PEAK_BF16_MFMA_TFLOPS),
+    "tiled_dq": ("dphi", PEAK_BF16_MFMA_TFLOPS),
+    "tiled_dk": ("dphi", PEAK_BF16_MFMA_TFLOPS),
+    "tiled_dv": ("dv_readout", PEAK_BF16_MFMA_TFLOPS),
     "mfma_fwd_chunk_partial": ("chunk_fwd", PEAK_BF16_MFMA_TFLOPS),
     "chunk_fwd": ("chunk_fwd", PEAK_BF16_MFMA_TFLOPS),
     "chunk_bwd_dq": ("chunk_dq", PEAK_BF16_MFMA_TFLOPS),
@@ -218,7 +232,8 @@ def main():
     ap.add_argument("--workload", default=None, help="name from paper_2507_04239_amd.inputs.WORKLOADS")
     ap.add_argument("--chunk", type=int, default=None,
                     help="chunk size instead of the workload's own; 0 lets the library choose (attention form or chunked)")
-    ap.add_argument("--impl", default="auto", choices=["auto", "generic", "mfma", "resident"])
+    ap.add_argument("--impl", default="auto", choices=["auto", "generic", "mfma", "resident", "tiled"])
+    ap.add_argument("--d-tile", type=int, default=0, help="tile width of the embedding for the tiled kernels (0: their default)")
     ap.add_argument("--cpu-sample-heads", type=int, default=2, help="heads the CPU oracle is timed on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
@@ -288,7 +303,7 @@ def run_workload(args, name, cpu):
     if args.gated:
         tl = torch.from_numpy(inputs.make_log_gates(w["B"], w["H"], w["T"], 1500 + w["position"])).to(dev)
     prob = binding.make_problem(w["B"], w["H"], w["T"], w["d"], w["d"], p, chunk, True, 1.0, w["dtype"], args.impl, keep,
-                                args.gated)
+                                args.gated, args.d_tile)
     w["chunk"] = binding.power_attn_resolved_chunk(prob)      # what the library runs (differs when 0 was asked for)
     ws_bytes = max(binding.power_attn_workspace_bytes(prob, True), binding.power_attn_workspace_bytes(prob, False))
     ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
@@ -299,10 +314,12 @@ def run_workload(args, name, cpu):
     with_bwd = bool(w.get("backward", True)) and not args.forward_only    # configs 1 and 2 are forward-only
 
     def fwd():
-        power_attn_fwd(tq, tk, tv, p, chunk, impl=args.impl, workspace=ws, out=O, out_z=Z, keep_state=keep, log_g=tl)
+        power_attn_fwd(tq, tk, tv, p, chunk, impl=args.impl, workspace=ws, out=O, out_z=Z, keep_state=keep, log_g=tl,
+                       d_tile=args.d_tile)
 
     def bwd():
-        power_attn_bwd(tq, tk, tv, O, Z, tg, p, chunk, impl=args.impl, workspace=ws, out=grads, keep_state=keep, log_g=tl)
+        power_attn_bwd(tq, tk, tv, O, Z, tg, p, chunk, impl=args.impl, workspace=ws, out=grads, keep_state=keep, log_g=tl,
+                       d_tile=args.d_tile)
 
     def step():
         fwd()
@@ -383,7 +400,7 @@ def run_workload(args, name, cpu):
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": w["dtype"], "data": "synthetic",
         "config": {"workload": name, "B": w["B"], "H": w["H"], "T": w["T"], "d": w["d"], "p": p, "chunk": w["chunk"],
-                   "chunk_requested": chunk, "normalize": True, "pass": "fwd+bwd" if with_bwd else "fwd", "impl": args.impl, "keep_state": keep, "serial_kernels": args.serial_kernels, "gated": args.gated,
+                   "chunk_requested": chunk, "normalize": True, "pass": "fwd+bwd" if with_bwd else "fwd", "impl": args.impl, "d_tile": args.d_tile, "keep_state": keep, "serial_kernels": args.serial_kernels, "gated": args.gated,
                    "state_rows": binding.power_attn_state_rows(prob)},
         "timing": timing,
         "step_algorithmic_tflop": total_alg / 1e12,

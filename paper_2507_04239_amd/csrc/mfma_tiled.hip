@@ -190,55 +190,57 @@ __device__ __forceinline__ void side_chain(const float* x, const TileDesc& td, i
     }
 }
 
-// A[row] = dL/dphi[row] of the unit's 64 rows for this token; adds J_phi(x)^T A into the token's accumulators
+// The Jacobian of a unit, one block of 16 rows at a time (block nb = rows 16 nb .. 16 nb + 15 of the unit), for one
+// token: A[i] = dL/dphi of the block's rows.  The right side's sums run over the whole unit (units of whole tiles:
+// over the block's tile) and are landed by finish().
 template <int P, int DT>
-__device__ __forceinline__ void unit_jacobian(const float* x, const TileDesc* __restrict__ tab, int unit, const float (&A)[64],
-                                              float* dx) {
+struct UnitJacobian {
     using E = Emb<P, DT>;
-    if constexpr (E::R >= 64) {
-        const TileDesc td = tab[unit / E::UPT];
-        const int a0 = (unit % E::UPT) * E::NA;
-        float uR[E::NR], dR[E::NR], dL[E::NA];
-        right_feats<P, DT>(x, td, uR);
-#pragma unroll
-        for (int b = 0; b < E::NR; ++b) dR[b] = 0.f;
-#pragma unroll
-        for (int ai = 0; ai < E::NA; ++ai) {
-            const float ul = left_feat<P, DT>(x, td, a0 + ai);
-            float s = 0.f;
-#pragma unroll
-            for (int b = 0; b < E::NR; ++b) {
-                s += A[ai * E::NR + b] * uR[b];
-                dR[b] += A[ai * E::NR + b] * ul;
-            }
-            dL[ai] = s;
-        }
-        side_chain<DT, E::PL, E::NA>(x, td, 0, a0, dL, dx);
-        side_chain<DT, E::PR, E::NR>(x, td, E::PL, 0, dR, dx);
-    } else {
-#pragma unroll
-        for (int tt = 0; tt < E::TPU; ++tt) {
-            const TileDesc td = tab[unit * E::TPU + tt];
-            float uR[E::NR], dR[E::NR], dL[E::NL];
+    static constexpr bool SLICE = E::R >= 64;                  // the unit is a slice of one tile
+    static constexpr int APB = SLICE ? 16 / E::NR : E::NL;      // left indices per block
+    static_assert(!SLICE || (E::NR <= 16 && 16 % E::NR == 0), "a block of 16 rows holds whole left indices");
+    static_assert(SLICE || E::R == 16, "a block of 16 rows is one tile");
+    float uR[E::NR], dR[E::NR];
+    TileDesc td;
+    int a0;
+
+    __device__ __forceinline__ void begin(const float* x, const TileDesc* __restrict__ tab, int unit) {
+        if constexpr (SLICE) {
+            td = tab[unit / E::UPT];
+            a0 = (unit % E::UPT) * E::NA;
             right_feats<P, DT>(x, td, uR);
 #pragma unroll
             for (int b = 0; b < E::NR; ++b) dR[b] = 0.f;
-#pragma unroll
-            for (int a = 0; a < E::NL; ++a) {
-                const float ul = left_feat<P, DT>(x, td, a);
-                float s = 0.f;
-#pragma unroll
-                for (int b = 0; b < E::NR; ++b) {
-                    s += A[tt * E::R + a * E::NR + b] * uR[b];
-                    dR[b] += A[tt * E::R + a * E::NR + b] * ul;
-                }
-                dL[a] = s;
-            }
-            side_chain<DT, E::PL, E::NL>(x, td, 0, 0, dL, dx);
-            side_chain<DT, E::PR, E::NR>(x, td, E::PL, 0, dR, dx);
         }
     }
-}
+    __device__ __forceinline__ void block(const float* x, const TileDesc* __restrict__ tab, int unit, int nb, const float (&A)[16],
+                                          float* dx) {
+        if constexpr (!SLICE) {
+            td = tab[unit * E::TPU + nb];
+            a0 = 0;
+            right_feats<P, DT>(x, td, uR);
+#pragma unroll
+            for (int b = 0; b < E::NR; ++b) dR[b] = 0.f;
+        }
+        float dL[APB];
+#pragma unroll
+        for (int aa = 0; aa < APB; ++aa) {
+            const float ul = left_feat<P, DT>(x, td, a0 + (SLICE ? nb * APB : 0) + aa);
+            float s = 0.f;
+#pragma unroll
+            for (int b = 0; b < E::NR; ++b) {
+                s += A[aa * E::NR + b] * uR[b];
+                dR[b] += A[aa * E::NR + b] * ul;
+            }
+            dL[aa] = s;
+        }
+        side_chain<DT, E::PL, APB>(x, td, 0, a0 + (SLICE ? nb * APB : 0), dL, dx);
+        if constexpr (!SLICE) side_chain<DT, E::PR, E::NR>(x, td, E::PL, 0, dR, dx);
+    }
+    __device__ __forceinline__ void finish(const float* x, float* dx) {
+        if constexpr (SLICE) side_chain<DT, E::PR, E::NR>(x, td, E::PL, 0, dR, dx);
+    }
+};
 
 // 64 token rows of X (bf16, [.][HD]) -> xs[token][HD + 1] float32, times xscale
 template <int HD, int NT>
@@ -350,56 +352,104 @@ __global__ __launch_bounds__(256) void k_tiled_scan(const bf16_t* __restrict__ X
 #pragma unroll
         for (int nb = 0; nb < 4; ++nb) acc[vb][nb] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    for (int ci = 0; ci < nchunk; ++ci) {
-        const int c = REV ? nchunk - 1 - ci : ci;
-        bf16_t* dst = st + (((size_t)bh * nchunk + c) * nunit + unit) * 64 * VP;
+    // the token rows of a step wait in registers while the step before them is being worked on
+    constexpr int XP = (64 * (HD / 8) + 255) / 256, YP = (64 * (VP / 8) + 255) / 256;
+    u32x4 xr[XP], yr[YP];   // (a true vector type: copies of HIP's uint4 struct become memcpy calls that keep the array in scratch)
+    const int spc = cs / 64, nstep = (nchunk - 1) * spc;    // the last chunk walked is never added
+#define PA_STEP_FETCH(SL)                                                                                        \
+    {                                                                                                            \
+        const int ci_ = (SL) / spc, c_ = REV ? nchunk - 1 - ci_ : ci_;                                           \
+        const size_t tok0_ = head + (size_t)c_ * cs + 64 * ((SL) % spc);                                         \
+        _Pragma("unroll") for (int q_ = 0; q_ < XP; ++q_) {                                                      \
+            const int id_ = min(tid + 256 * q_, 64 * (HD / 8) - 1);                                              \
+            xr[q_] = *(const u32x4*)(X + tok0_ * HD + (size_t)id_ * 8);                                          \
+        }                                                                                                        \
+        _Pragma("unroll") for (int q_ = 0; q_ < YP; ++q_) {                                                      \
+            const int id_ = min(tid + 256 * q_, 64 * (VP / 8) - 1);                                              \
+            yr[q_] = *(const u32x4*)(Yp + tok0_ * VP + (size_t)id_ * 8);                                         \
+        }                                                                                                        \
+    }
+    PA_STEP_FETCH(0)   // (a sequence of one chunk never gets here: the launchers ask for at least two)
+    for (int sl = 0; sl <= nstep; ++sl) {
+        if (sl % spc == 0) {
+            // the running sum is the state entering this chunk (REV: the state gradient of the chunks after it)
+            const int ci = sl / spc, c = REV ? nchunk - 1 - ci : ci;
+            bf16_t* dst = st + (((size_t)bh * nchunk + c) * nunit + unit) * 64 * VP;
 #pragma unroll
-        for (int nb = 0; nb < 4; ++nb)
-#pragma unroll
-            for (int vb = 0; vb < NVB; ++vb) {
-                bf16x4 o;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) o[r] = (__bf16)(acc[vb][nb][r] * mult[nb]);
-                *(bf16x4*)(dst + (size_t)(16 * nb + r16) * VP + g * (VP / 4) + 4 * vb) = o;
-            }
-        if (ci == nchunk - 1) break;   // nothing reads a sum that includes the last chunk walked
-        for (int step = 0; step < cs / 64; ++step) {
-            const size_t tok0 = head + (size_t)c * cs + 64 * step;
-            __syncthreads();
-            stage_x<HD, 256>(xs, X + tok0 * HD, 64, xscale, tid);
-            for (int id = tid; id < 64 * (VP / 8); id += 256) {
-                const int row = id / (VP / 8), c8 = id % (VP / 8);
-                *(uint4*)&yt.r[row][8 * c8] = *(const uint4*)(Yp + (tok0 + row) * VP + 8 * c8);
-            }
-            __syncthreads();
-            {
-                float phi[64];
-                unit_phi<P, DT>(&xs[lane][0], tab, unit, phi);
-                put_phi(phis[w], lane, phi);
-            }
-            wave_sync();
-#pragma unroll
-            for (int s = 0; s < 2; ++s) {
-                bf16x8 pf[4];
-#pragma unroll
-                for (int nb = 0; nb < 4; ++nb) pf[nb] = col_frag<64>(phis[w], s, nb, r16, g);
+            for (int nb = 0; nb < 4; ++nb)
 #pragma unroll
                 for (int vb = 0; vb < NVB; ++vb) {
-                    // A row 4 g' + r of block vb is value column g' VP / 4 + 4 vb + r
-                    const bf16x8 yf = col_frag_at<VP>(yt, s, (r16 & 3) * (VP / 4) + 4 * vb, r16, g);
+                    bf16x4 o;
 #pragma unroll
-                    for (int nb = 0; nb < 4; ++nb) acc[vb][nb] = mfma16(yf, pf[nb], acc[vb][nb]);
+                    for (int r = 0; r < 4; ++r) o[r] = (__bf16)(acc[vb][nb][r] * mult[nb]);
+                    *(bf16x4*)(dst + (size_t)(16 * nb + r16) * VP + g * (VP / 4) + 4 * vb) = o;
                 }
-            }
-            wave_sync();
         }
+        if (sl == nstep) break;
+        __syncthreads();
+        // (threads past the last piece repeat it: same data to the same place)
+#pragma unroll
+        for (int q = 0; q < XP; ++q) {
+            const int id = min(tid + 256 * q, 64 * (HD / 8) - 1);
+            float* dst = &xs[id / (HD / 8)][8 * (id % (HD / 8))];
+            const u32x4 u = xr[q];
+            dst[0] = xscale * bf_lo(u[0]); dst[1] = xscale * bf_hi(u[0]);
+            dst[2] = xscale * bf_lo(u[1]); dst[3] = xscale * bf_hi(u[1]);
+            dst[4] = xscale * bf_lo(u[2]); dst[5] = xscale * bf_hi(u[2]);
+            dst[6] = xscale * bf_lo(u[3]); dst[7] = xscale * bf_hi(u[3]);
+        }
+#pragma unroll
+        for (int q = 0; q < YP; ++q) {
+            const int id = min(tid + 256 * q, 64 * (VP / 8) - 1);
+            *(u32x4*)&yt.r[id / (VP / 8)][8 * (id % (VP / 8))] = yr[q];
+        }
+        __syncthreads();
+        PA_STEP_FETCH(min(sl + 1, nstep - 1))
+        {
+            float phi[64];
+            unit_phi<P, DT>(&xs[lane][0], tab, unit, phi);
+            put_phi(phis[w], lane, phi);
+        }
+        wave_sync();
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            bf16x8 pf[4];
+#pragma unroll
+            for (int nb = 0; nb < 4; ++nb) pf[nb] = col_frag<64>(phis[w], s, nb, r16, g);
+#pragma unroll
+            for (int vb = 0; vb < NVB; ++vb) {
+                // A row 4 g' + r of block vb is value column g' VP / 4 + 4 vb + r
+                const bf16x8 yf = col_frag_at<VP>(yt, s, (r16 & 3) * (VP / 4) + 4 * vb, r16, g);
+#pragma unroll
+                for (int nb = 0; nb < 4; ++nb) acc[vb][nb] = mfma16(yf, pf[nb], acc[vb][nb]);
+            }
+        }
+        wave_sync();
     }
+#undef PA_STEP_FETCH
 }
 
 // ---- query-state: part[t][:] = S_chunk(t)^T phi(x_t) -------------------------------------------------------
 // A workgroup of two waves takes 128 tokens of one chunk (64 per wave, O^T accumulators in registers) and
-// streams that chunk's state, unit by unit, through a two-slot LDS ring.  zpart (may be null) receives the
-// normaliser column's share.  Also serves dV: the state gradient read out with phi(k).
+// streams that chunk's state, unit by unit: NPF units are on their way from memory in registers while one is
+// being worked on from a two-slot LDS ring.  zpart (may be null) receives the normaliser column's share.
+// Also serves dV: the state gradient read out with phi(k).
+constexpr int NPF = 4;   // units in flight per workgroup
+
+// unit u (64 x VP bf16, contiguous) of the state at sbase -> registers; PPT pieces of 16 bytes per thread
+// (loads are unconditional, on clamped indices: an array that is assigned under a condition is kept in scratch
+// memory by the compiler, and the load then waits to be stored there)
+#define PA_UNIT_LOAD(REGS, U)                                                                                    \
+    _Pragma("unroll") for (int q_ = 0; q_ < PPT; ++q_) {                                                         \
+        const int id_ = min(tid + 128 * q_, PIECES - 1);                                                         \
+        REGS[q_] = *(const u32x4*)(sbase + ((size_t)min((U), nunit_real - 1) * PIECES + id_) * 8);               \
+    }
+#define PA_UNIT_STORE(DST, REGS)                                                                                 \
+    _Pragma("unroll") for (int q_ = 0; q_ < PPT; ++q_) {                                                         \
+        const int id_ = min(tid + 128 * q_, PIECES - 1);                                                         \
+        *(u32x4*)&DST.r[id_ / (VP / 8)][8 * (id_ % (VP / 8))] = REGS[q_];                                        \
+    }
+
 template <int P, int DT, int HD>
 __global__ __launch_bounds__(128) void k_tiled_readout(const bf16_t* __restrict__ X, const TileDesc* __restrict__ tab,
                                                        const bf16_t* __restrict__ st, float* __restrict__ part,
@@ -414,6 +464,9 @@ __global__ __launch_bounds__(128) void k_tiled_readout(const bf16_t* __restrict_
     const size_t head = (size_t)bh * T;
     const bf16_t* sbase = st + ((size_t)bh * nchunk + chunk) * nunit * 64 * VP;
 
+    u32x4 pre[NPF][PPT];
+#pragma unroll
+    for (int j = 0; j < NPF - 1; ++j) PA_UNIT_LOAD(pre[j], j)
     stage_x<HD, 128>(xs, X + (head + tok0) * HD, 128, xscale, tid);
     f32x4 acc[NVB][4];
 #pragma unroll
@@ -421,49 +474,38 @@ __global__ __launch_bounds__(128) void k_tiled_readout(const bf16_t* __restrict_
 #pragma unroll
         for (int ib = 0; ib < 4; ++ib) acc[vb][ib] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    uint4 pre[PPT];
+    for (int u0 = 0; u0 < nunit_real; u0 += NPF) {
 #pragma unroll
-    for (int q = 0; q < PPT; ++q) {
-        const int id = tid + 128 * q;
-        if (id < PIECES) pre[q] = *(const uint4*)(sbase + (size_t)id * 8);
-    }
-    for (int u = 0; u < nunit_real; ++u) {
-        Tile64<VP>& cur = stt[u & 1];
-#pragma unroll
-        for (int q = 0; q < PPT; ++q) {
-            const int id = tid + 128 * q;
-            if (id < PIECES) *(uint4*)&cur.r[id / (VP / 8)][8 * (id % (VP / 8))] = pre[q];
-        }
-        __syncthreads();
-        if (u + 1 < nunit_real) {
-#pragma unroll
-            for (int q = 0; q < PPT; ++q) {
-                const int id = tid + 128 * q;
-                if (id < PIECES) pre[q] = *(const uint4*)(sbase + ((size_t)(u + 1) * PIECES + id) * 8);
+        for (int j = 0; j < NPF; ++j) {
+            const int u = u0 + j;
+            PA_UNIT_LOAD(pre[(j + NPF - 1) % NPF], u + NPF - 1)
+            if (u >= nunit_real) continue;
+            Tile64<VP>& cur = stt[j & 1];
+            PA_UNIT_STORE(cur, pre[j])
+            __syncthreads();
+            {
+                float phi[64];
+                unit_phi<P, DT>(&xs[64 * w + lane][0], tab, u, phi);
+                put_phi(phis[w], lane, phi);
             }
-        }
-        {
-            float phi[64];
-            unit_phi<P, DT>(&xs[64 * w + lane][0], tab, u, phi);
-            put_phi(phis[w], lane, phi);
-        }
-        wave_sync();
+            wave_sync();
 #pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            Frag qf[4];
+            for (int s = 0; s < 2; ++s) {
+                Frag qf[4];
 #pragma unroll
-            for (int ib = 0; ib < 4; ++ib) {
-                qf[ib].h[0] = *(const uint2*)&phis[w].r[16 * ib + r16][32 * s + 4 * g];
-                qf[ib].h[1] = *(const uint2*)&phis[w].r[16 * ib + r16][32 * s + 16 + 4 * g];
+                for (int ib = 0; ib < 4; ++ib) {
+                    qf[ib].h[0] = *(const uint2*)&phis[w].r[16 * ib + r16][32 * s + 4 * g];
+                    qf[ib].h[1] = *(const uint2*)&phis[w].r[16 * ib + r16][32 * s + 16 + 4 * g];
+                }
+#pragma unroll
+                for (int vb = 0; vb < NVB; ++vb) {
+                    const bf16x8 sf = col_frag<VP>(cur, s, vb, r16, g);
+#pragma unroll
+                    for (int ib = 0; ib < 4; ++ib) acc[vb][ib] = mfma16(sf, qf[ib].v, acc[vb][ib]);
+                }
             }
-#pragma unroll
-            for (int vb = 0; vb < NVB; ++vb) {
-                const bf16x8 sf = col_frag<VP>(cur, s, vb, r16, g);
-#pragma unroll
-                for (int ib = 0; ib < 4; ++ib) acc[vb][ib] = mfma16(sf, qf[ib].v, acc[vb][ib]);
-            }
+            wave_sync();
         }
-        wave_sync();
     }
 #pragma unroll
     for (int ib = 0; ib < 4; ++ib) {
@@ -477,17 +519,17 @@ __global__ __launch_bounds__(128) void k_tiled_readout(const bf16_t* __restrict_
 }
 
 // ---- d phi and the Jacobian: part[t][:] = outscale J_phi(x_t)^T (S_chunk(t) y'_t) --------------------------
-// Same shape as the read-out.  Per unit: A = S y'^T on the matrix cores (contraction over the VP value
-// columns; y' = [ghat, gz] for dQ, [v, 1] for dK, held as operand fragments in registers), laid down in
-// LDS as [token][row], then the Jacobian by the thread that owns the token.
+// Same shape as the read-out.  Per block of 16 state rows: A = S y'^T on the matrix cores (contraction over
+// the VP value columns; y' = [ghat, gz] for dQ, [v, 1] for dK, held as operand fragments in registers), laid
+// down in LDS as [token][row], then the Jacobian by the thread that owns the token.
 template <int P, int DT, int HD>
 __global__ __launch_bounds__(128) void k_tiled_dphi(const bf16_t* __restrict__ X, const bf16_t* __restrict__ Yp,
                                                     const TileDesc* __restrict__ tab, const bf16_t* __restrict__ st,
                                                     float* __restrict__ part, int T, int cs, int nunit, int nunit_real,
                                                     float xscale, float outscale) {
-    constexpr int VP = HD + 16, NK = HD / 32, PIECES = 64 * (VP / 8), PPT = (PIECES + 127) / 128, AP = 64 + 4;
+    constexpr int VP = HD + 16, NK = HD / 32, PIECES = 64 * (VP / 8), PPT = (PIECES + 127) / 128, AP = 16 + 4;
     __shared__ float xs[128][HD + 1];
-    __shared__ __attribute__((aligned(16))) Tile64<VP> stt[2];
+    __shared__ __attribute__((aligned(16))) Tile64<VP> stt;   // one slot (LDS decides how many workgroups share a CU): two barriers per unit
     __shared__ __attribute__((aligned(16))) float dph[2][64][AP];
     __shared__ float dxs[2][HD][64];
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6), r16 = lane & 15, g = lane >> 4;
@@ -495,6 +537,9 @@ __global__ __launch_bounds__(128) void k_tiled_dphi(const bf16_t* __restrict__ X
     const size_t head = (size_t)bh * T;
     const bf16_t* sbase = st + ((size_t)bh * nchunk + chunk) * nunit * 64 * VP;
 
+    u32x4 pre[NPF][PPT];
+#pragma unroll
+    for (int j = 0; j < NPF - 1; ++j) PA_UNIT_LOAD(pre[j], j)
     stage_x<HD, 128>(xs, X + (head + tok0) * HD, 128, xscale, tid);
 #pragma unroll
     for (int f = 0; f < HD; ++f) dxs[w][f][lane] = 0.f;
@@ -507,61 +552,57 @@ __global__ __launch_bounds__(128) void k_tiled_dphi(const bf16_t* __restrict__ X
         for (int ks = 0; ks < NK; ++ks) yf[ib][ks].u = *(const uint4*)(yrow + 32 * ks + 8 * g);
         ytail[ib] = *(const uint2*)(yrow + HD + 4 * g);
     }
+    const float* xrow = &xs[64 * w + lane][0];
+    float* dxcol = &dxs[w][0][lane];
 
-    uint4 pre[PPT];
+    for (int u0 = 0; u0 < nunit_real; u0 += NPF) {
 #pragma unroll
-    for (int q = 0; q < PPT; ++q) {
-        const int id = tid + 128 * q;
-        if (id < PIECES) pre[q] = *(const uint4*)(sbase + (size_t)id * 8);
+        for (int j = 0; j < NPF; ++j) {
+            const int u = u0 + j;
+            PA_UNIT_LOAD(pre[(j + NPF - 1) % NPF], u + NPF - 1)
+            if (u >= nunit_real) continue;
+            Tile64<VP>& cur = stt;
+            __syncthreads();
+            PA_UNIT_STORE(cur, pre[j])
+            __syncthreads();
+            UnitJacobian<P, DT> jac;
+            jac.begin(xrow, tab, u);
+#pragma unroll
+            for (int nb = 0; nb < 4; ++nb) {
+                Frag sf[NK];
+#pragma unroll
+                for (int ks = 0; ks < NK; ++ks) sf[ks].u = *(const uint4*)&cur.r[16 * nb + r16][32 * ks + 8 * g];
+                const uint2 stail = *(const uint2*)&cur.r[16 * nb + r16][HD + 4 * g];
+#pragma unroll
+                for (int ib = 0; ib < 4; ++ib) {
+                    f32x4 c = {0.f, 0.f, 0.f, 0.f};   // rows 16 nb + 4g + r, token 16 ib + r16
+#pragma unroll
+                    for (int ks = 0; ks < NK; ++ks) c = mfma16(sf[ks].v, yf[ib][ks].v, c);
+                    c = mfma16k16(stail, ytail[ib], c);
+                    *(float4*)&dph[w][16 * ib + r16][4 * g] = make_float4(c[0], c[1], c[2], c[3]);
+                }
+                wave_sync();
+                float A[16];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float4 a4 = *(const float4*)&dph[w][lane][4 * i];
+                    A[4 * i] = a4.x; A[4 * i + 1] = a4.y; A[4 * i + 2] = a4.z; A[4 * i + 3] = a4.w;
+                }
+                wave_sync();
+                jac.block(xrow, tab, u, nb, A, dxcol);
+            }
+            jac.finish(xrow, dxcol);
+        }
     }
-    for (int u = 0; u < nunit_real; ++u) {
-        Tile64<VP>& cur = stt[u & 1];
-#pragma unroll
-        for (int q = 0; q < PPT; ++q) {
-            const int id = tid + 128 * q;
-            if (id < PIECES) *(uint4*)&cur.r[id / (VP / 8)][8 * (id % (VP / 8))] = pre[q];
-        }
-        __syncthreads();
-        if (u + 1 < nunit_real) {
-#pragma unroll
-            for (int q = 0; q < PPT; ++q) {
-                const int id = tid + 128 * q;
-                if (id < PIECES) pre[q] = *(const uint4*)(sbase + ((size_t)(u + 1) * PIECES + id) * 8);
-            }
-        }
-#pragma unroll
-        for (int nb = 0; nb < 4; ++nb) {
-            Frag sf[NK];
-#pragma unroll
-            for (int ks = 0; ks < NK; ++ks) sf[ks].u = *(const uint4*)&cur.r[16 * nb + r16][32 * ks + 8 * g];
-            const uint2 stail = *(const uint2*)&cur.r[16 * nb + r16][HD + 4 * g];
-#pragma unroll
-            for (int ib = 0; ib < 4; ++ib) {
-                f32x4 c = {0.f, 0.f, 0.f, 0.f};   // rows 16 nb + 4g + r, token 16 ib + r16
-#pragma unroll
-                for (int ks = 0; ks < NK; ++ks) c = mfma16(sf[ks].v, yf[ib][ks].v, c);
-                c = mfma16k16(stail, ytail[ib], c);
-                *(float4*)&dph[w][16 * ib + r16][16 * nb + 4 * g] = make_float4(c[0], c[1], c[2], c[3]);
-            }
-        }
-        wave_sync();
-        {
-            float A[64];
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const float4 a4 = *(const float4*)&dph[w][lane][4 * i];
-                A[4 * i] = a4.x; A[4 * i + 1] = a4.y; A[4 * i + 2] = a4.z; A[4 * i + 3] = a4.w;
-            }
-            unit_jacobian<P, DT>(&xs[64 * w + lane][0], tab, u, A, &dxs[w][0][lane]);
-        }
-        wave_sync();
-    }
+    wave_sync();
     float* out = part + (head + tok0 + 64 * w + lane) * HD;
 #pragma unroll
     for (int f4 = 0; f4 < HD / 4; ++f4)
         *(float4*)(out + 4 * f4) = make_float4(outscale * dxs[w][4 * f4][lane], outscale * dxs[w][4 * f4 + 1][lane],
                                                outscale * dxs[w][4 * f4 + 2][lane], outscale * dxs[w][4 * f4 + 3][lane]);
 }
+#undef PA_UNIT_LOAD
+#undef PA_UNIT_STORE
 
 template <int P, int DT, int HD>
 bool scan_t(const char* name, hipStream_t s, const TiledPlan& pl, bool rev, const bf16_t* X, const bf16_t* Yp, const TileDesc* tab,
