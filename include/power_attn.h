@@ -104,7 +104,7 @@ typedef struct {
                                a_ij = s_ij^p exp(b_i - b_j),
                            N_i = sum_j a_ij v_j, Z_i = sum_j a_ij. */
     int   d_tile;       /* tile width of the tiled symmetric-power embedding (Sec. 4.1.1).  0: the kernel family's
-                           own (8 for p = 2, 4 for p = 3 and p = 4).  A value > 0 asks for the PA_IMPL_TILED kernels
+                           own (8 for p = 2, 4 for p = 3, 2 for p = 4).  A value > 0 asks for the PA_IMPL_TILED kernels
                            with that width (PA_ERR_UNSUPPORTED if they do not take the problem); the result does
                            not depend on it beyond rounding. */
 } pa_problem;

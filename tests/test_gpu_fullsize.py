@@ -130,21 +130,39 @@ def test_chunk_size_invariance_on_device():
             assert err <= 2 * TOL["bf16"], (key, err)
 
 
-def test_p4_config4_shape_reduced_batch():
-    """Config 4 as stated (bf16 fwd+bwd, p=4, d=32, chunk 128, T=16384), one of its 16 heads - the chunked
-    form of this degree runs on the vector-ALU family, whose state of one head is already 128 x 52360 x 33
-    floats.  Covered: O and Z of every row by the definition, 12 sampled rows of dQ, 12 sampled columns of
-    dK and dV.  Not covered here: the other 15 heads (B2 H8), which test_config4_attention_form_full_shape
-    runs in the attention form."""
-    w = dict(inputs.WORKLOADS["cfg4_bf16_p4_T16384_d32_c128"])
-    Q, K, V, G = (a.astype(np.float64) for a in inputs.make_qkvg(1, 1, w["T"], w["d"], seed=1004, dtype="bf16"))
-    print("case cfg4 one head", flush=True)
-    got = run_fwd_bwd(Q, K, V, G, 4, w["chunk"], "bf16")
+def test_config4_as_stated_full_shape():
+    """Config 4 as stated, all of it: bf16 fwd+bwd, p=4, B2 H8 T16384 d32, chunk 128, as bench.py runs it (the
+    tiled matrix-core kernels of degree 4, chunk states kept between the passes).  One head, every output
+    (O, Z, dQ, dK, dV), against the definition in float64; eight more heads spread over the batch, sampled rows
+    of O, Z, dQ by the definition; sampled columns of dK, dV on the fully checked head."""
+    name = "cfg4_bf16_p4_T16384_d32_c128"
+    w = inputs.WORKLOADS[name]
+    Q, K, V, G = inputs.make_workload(name)
+    print("case", name, "as stated", flush=True)
+    got = run_fwd_bwd(Q, K, V, G, w["p"], w["chunk"], "bf16", keep_state=True)
     for k, a in got.items():
         assert np.isfinite(a).all(), k
+    b, h = 1, 5
+    q, k, v, g = (a[b, h].astype(np.float64) for a in (Q, K, V, G))
+    O_ref, Z_ref = orc.fwd_quadratic(q, k, v, w["p"])
+    dQ_ref, dK_ref, dV_ref = orc.bwd_quadratic(q, k, v, g, w["p"])
+    assert_close({key: a[b, h] for key, a in got.items()}, dict(O=O_ref, Z=Z_ref, dQ=dQ_ref, dK=dK_ref, dV=dV_ref),
+                 "bf16", f"{name} head (1,5) by the definition")
+    heads = [(1, 5), (0, 0), (0, 3), (0, 7), (1, 0), (1, 2), (1, 7), (0, 5), (1, 4)]
+    _check_sampled(name, got, Q, K, V, G, w, heads, n_rows=6, n_cols=12, ref_head=((b, h), (O_ref, Z_ref)))
+
+
+def test_config4_tile_width_four_one_head():
+    """The same head shape with the tile width the automatic choice does not take (d_tile = 4, 330 tiles of
+    256 rows): one head, every output by the definition."""
+    w = dict(inputs.WORKLOADS["cfg4_bf16_p4_T16384_d32_c128"])
+    Q, K, V, G = (a.astype(np.float64) for a in inputs.make_qkvg(1, 1, w["T"], w["d"], seed=1004, dtype="bf16"))
+    print("case cfg4 one head, d_tile 4", flush=True)
+    got = run_fwd_bwd(Q, K, V, G, 4, w["chunk"], "bf16", d_tile=4)
     O_ref, Z_ref = orc.fwd_quadratic(Q[0, 0], K[0, 0], V[0, 0], 4)
-    assert_close({k: got[k][0, 0] for k in ("O", "Z")}, dict(O=O_ref, Z=Z_ref), "bf16", "cfg4 chunk 128, one head, by the definition")
-    _check_sampled("cfg4", got, Q, K, V, G, dict(w, B=1, H=1), [(0, 0)], n_rows=12, n_cols=12, ref_head=((0, 0), (O_ref, Z_ref)))
+    dQ_ref, dK_ref, dV_ref = orc.bwd_quadratic(Q[0, 0], K[0, 0], V[0, 0], G[0, 0], 4)
+    assert_close({key: a[0, 0] for key, a in got.items()}, dict(O=O_ref, Z=Z_ref, dQ=dQ_ref, dK=dK_ref, dV=dV_ref),
+                 "bf16", "cfg4 head shape, d_tile 4, by the definition")
 
 
 def test_d128_config5_shape_reduced_batch():

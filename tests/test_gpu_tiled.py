@@ -54,10 +54,11 @@ def test_tiled_shapes(p, dt, d, B, H, T, chunk, scale, keep):
 
 def test_automatic_choice_runs_the_tiled_kernels_for_degree_four():
     """The chunked form of p = 4, d = 32 with no family named: the state rows reported are those of the tiled
-    embedding (330 tiles of 256 rows), i.e. the matrix-core kernels run, not the vector-ALU family."""
+    embedding (3876 tiles of 16 rows at the default tile width 2), i.e. the matrix-core kernels run, not the
+    vector-ALU family."""
     from paper_2507_04239_amd import binding
     prob = binding.make_problem(1, 2, 512, 32, 32, 4, 128, True, 1.0, "bf16", "auto")
-    assert binding.power_attn_state_rows(prob) == 330 * 256
+    assert binding.power_attn_state_rows(prob) == 3876 * 16
     Q, K, V, G = inputs.make_qkvg(1, 2, 512, 32, seed=5200, dtype="bf16")
     got = run_fwd_bwd(Q, K, V, G, 4, 128, "bf16")
     O, Z = orc.fwd_bhtd(Q, K, V, 4, 128, True, 1.0)

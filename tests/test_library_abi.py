@@ -98,6 +98,46 @@ def test_automatic_chunk_choice():
     assert rc(mk(1, 1, 100, 16, 16, 2, -1)) == 0                 # invalid
 
 
+def test_tiled_kernels_host_logic():
+    """Which problems the tiled matrix-core kernels (degree and tile width as parameters) take, the state rows
+    of their embedding C(d / d_tile + p - 1, p) d_tile^p (Sec. 4.1.1), and when the automatic choice runs them."""
+    import math
+    from paper_2507_04239_amd import binding
+    mk, ok, rows = binding.make_problem, binding.power_attn_supported, binding.power_attn_state_rows
+
+    def tspow_rows(d, p, dt):
+        return math.comb(d // dt + p - 1, p) * dt ** p
+
+    for (p, dt, d) in [(2, 4, 32), (2, 8, 32), (2, 16, 32), (3, 4, 32), (4, 2, 32), (4, 4, 32),
+                       (2, 4, 64), (2, 8, 64), (2, 16, 64), (3, 4, 64)]:
+        pr = mk(1, 2, 1024, d, d, p, 128, normalize=(p % 2 == 0), impl="tiled", d_tile=dt)
+        assert ok(pr, True) and ok(pr, False), (p, dt, d)
+        assert rows(pr) == tspow_rows(d, p, dt), (p, dt, d)
+    # the default widths: 8, 4, 2 for p = 2, 3, 4
+    assert rows(mk(1, 2, 1024, 32, 32, 2, 128, impl="tiled")) == tspow_rows(32, 2, 8)
+    assert rows(mk(1, 2, 1024, 32, 32, 3, 128, normalize=False, impl="tiled")) == tspow_rows(32, 3, 4) == 7680
+    assert rows(mk(1, 2, 1024, 32, 32, 4, 128, impl="tiled")) == tspow_rows(32, 4, 2) == 62016
+    # config 4 as stated with no family named: the tiled kernels, not the vector-ALU family (52360 rows there)
+    assert rows(mk(2, 8, 16384, 32, 32, 4, 128)) == 62016
+    assert rows(mk(2, 8, 16384, 32, 32, 4, 128, d_tile=4)) == 84480
+    assert rows(mk(2, 8, 16384, 32, 32, 4, 128, impl="generic")) == 52360
+    # a tile width is a request for these kernels: p = 2, d = 64 otherwise runs the d_tile = 8 family of its own
+    assert rows(mk(1, 12, 65536, 64, 64, 2, 128)) == 2304
+    assert rows(mk(1, 12, 65536, 64, 64, 2, 128, d_tile=4)) == tspow_rows(64, 2, 4) == 2176
+    assert rows(mk(1, 12, 65536, 64, 64, 2, 128, d_tile=16)) == 2560
+    # not taken: widths that are not built, one chunk, chunks that are not a multiple of 128, gates, float32, d = 128
+    assert not ok(mk(1, 2, 1024, 32, 32, 4, 128, d_tile=8), True)
+    assert not ok(mk(1, 2, 1024, 32, 32, 4, 128, d_tile=3), True)
+    assert not ok(mk(1, 2, 1024, 32, 32, 4, 1024, impl="tiled"), True)
+    assert not ok(mk(1, 2, 1024, 32, 32, 4, 64, impl="tiled"), True)
+    assert not ok(mk(1, 2, 1024, 32, 32, 4, 128, impl="tiled", gated=True), True)
+    assert not ok(mk(1, 2, 1024, 32, 32, 4, 128, impl="tiled", dtype="f32"), True)
+    assert not ok(mk(1, 2, 1024, 128, 128, 2, 128, impl="tiled"), True)
+    assert ok(mk(1, 2, 1024, 32, 32, 4, 128, gated=True), True)           # automatic: the vector-ALU family takes it
+    assert rows(mk(1, 2, 1024, 32, 32, 4, 128, gated=True)) == 52360
+    assert not ok(mk(1, 2, 1024, 32, 32, 4, 128, d_tile=-1), True)        # invalid
+
+
 def test_support_matrix_host_logic():
     """Which problems the matrix-core kernels take (host logic only, nothing is launched)."""
     from paper_2507_04239_amd import binding
