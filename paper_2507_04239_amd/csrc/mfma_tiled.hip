@@ -21,7 +21,9 @@
 // [feature][token], touched by their owner only: plain read-add-write).
 //
 // States: per (head, chunk) `nunit` units of 64 rows x VP = d + 16 value columns, bf16, row-major; column d
-// carries the normaliser (the values are extended by a one, App. E.4's l), the remaining 15 are zero.
+// carries the normaliser (the values are extended by a one, App. E.4's l), the remaining 15 are zero.  In
+// memory a row keeps only its first SP = d + 4 columns (the kernels are bound by the bytes of the states); the
+// columns beyond live in LDS only, as zeros.
 // MFMA: v_mfma_f32_16x16x32_bf16, and v_mfma_f32_16x16x16_bf16 for the 16 columns beyond d where the
 // contraction runs over the value columns.  Operand layouts as in mfma_common.hpp.
 #include "mfma_common.hpp"
@@ -71,6 +73,7 @@ __device__ __forceinline__ bf16x8 col_frag(const Tile64<W>& t, int s, int cb, in
 }
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 __device__ __forceinline__ f32x4 mfma16k16(uint2 a, uint2 b, f32x4 c) {
     union {
         uint2 u;
@@ -335,7 +338,7 @@ __global__ __launch_bounds__(256) void k_tiled_scan(const bf16_t* __restrict__ X
                                                     const TileDesc* __restrict__ tab, bf16_t* __restrict__ st, int T, int cs,
                                                     int nunit, float xscale) {
     using E = Emb<P, DT>;
-    constexpr int VP = HD + 16, NVB = VP / 16;
+    constexpr int VP = HD + 16, NVB = VP / 16, SP = HD + 4;
     __shared__ float xs[64][HD + 1];
     __shared__ __attribute__((aligned(16))) Tile64<VP> yt;
     __shared__ __attribute__((aligned(16))) Tile64<64> phis[4];
@@ -374,7 +377,7 @@ __global__ __launch_bounds__(256) void k_tiled_scan(const bf16_t* __restrict__ X
         if (sl % spc == 0) {
             // the running sum is the state entering this chunk (REV: the state gradient of the chunks after it)
             const int ci = sl / spc, c = REV ? nchunk - 1 - ci : ci;
-            bf16_t* dst = st + (((size_t)bh * nchunk + c) * nunit + unit) * 64 * VP;
+            bf16_t* dst = st + (((size_t)bh * nchunk + c) * nunit + unit) * 64 * SP;
 #pragma unroll
             for (int nb = 0; nb < 4; ++nb)
 #pragma unroll
@@ -382,7 +385,8 @@ __global__ __launch_bounds__(256) void k_tiled_scan(const bf16_t* __restrict__ X
                     bf16x4 o;
 #pragma unroll
                     for (int r = 0; r < 4; ++r) o[r] = (__bf16)(acc[vb][nb][r] * mult[nb]);
-                    *(bf16x4*)(dst + (size_t)(16 * nb + r16) * VP + g * (VP / 4) + 4 * vb) = o;
+                    const int col = g * (VP / 4) + 4 * vb;
+                    if (col < SP) *(bf16x4*)(dst + (size_t)(16 * nb + r16) * SP + col) = o;
                 }
         }
         if (sl == nstep) break;
@@ -436,37 +440,43 @@ __global__ __launch_bounds__(256) void k_tiled_scan(const bf16_t* __restrict__ X
 // Also serves dV: the state gradient read out with phi(k).
 constexpr int NPF = 4;   // units in flight per workgroup
 
-// unit u (64 x VP bf16, contiguous) of the state at sbase -> registers; PPT pieces of 16 bytes per thread
+// unit u (64 rows x SP bf16, contiguous) of the state at sbase -> registers; PPT pieces of 8 bytes per thread
 // (loads are unconditional, on clamped indices: an array that is assigned under a condition is kept in scratch
-// memory by the compiler, and the load then waits to be stored there)
+// memory by the compiler, and the load then waits to be stored there; threads past the last piece repeat it)
 #define PA_UNIT_LOAD(REGS, U)                                                                                    \
     _Pragma("unroll") for (int q_ = 0; q_ < PPT; ++q_) {                                                         \
         const int id_ = min(tid + 128 * q_, PIECES - 1);                                                         \
-        REGS[q_] = *(const u32x4*)(sbase + ((size_t)min((U), nunit_real - 1) * PIECES + id_) * 8);               \
+        REGS[q_] = *(const u32x2*)(sbase + ((size_t)min((U), nunit_real - 1) * PIECES + id_) * 4);               \
     }
 #define PA_UNIT_STORE(DST, REGS)                                                                                 \
     _Pragma("unroll") for (int q_ = 0; q_ < PPT; ++q_) {                                                         \
         const int id_ = min(tid + 128 * q_, PIECES - 1);                                                         \
-        *(u32x4*)&DST.r[id_ / (VP / 8)][8 * (id_ % (VP / 8))] = REGS[q_];                                        \
+        *(u32x2*)&DST.r[id_ / (SP / 4)][4 * (id_ % (SP / 4))] = REGS[q_];                                        \
     }
+// columns SP .. VP - 1 of an LDS state tile are zero and never written again
+#define PA_UNIT_ZERO_PAD(DST)                                                                                    \
+    for (int id_ = tid; id_ < 64 * ((VP - SP) / 4); id_ += 128)                                                  \
+        *(u32x2*)&DST.r[id_ / ((VP - SP) / 4)][SP + 4 * (id_ % ((VP - SP) / 4))] = (u32x2){0u, 0u};
 
 template <int P, int DT, int HD>
 __global__ __launch_bounds__(128) void k_tiled_readout(const bf16_t* __restrict__ X, const TileDesc* __restrict__ tab,
                                                        const bf16_t* __restrict__ st, float* __restrict__ part,
                                                        float* __restrict__ zpart, int T, int cs, int nunit, int nunit_real,
                                                        float xscale) {
-    constexpr int VP = HD + 16, NVB = VP / 16, PIECES = 64 * (VP / 8), PPT = (PIECES + 127) / 128;
+    constexpr int VP = HD + 16, NVB = VP / 16, SP = HD + 4, PIECES = 64 * (SP / 4), PPT = (PIECES + 127) / 128;
     __shared__ float xs[128][HD + 1];
     __shared__ __attribute__((aligned(16))) Tile64<VP> stt[2];
     __shared__ __attribute__((aligned(16))) Tile64<64> phis[2];
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6), r16 = lane & 15, g = lane >> 4;
     const int bh = blockIdx.y, tok0 = blockIdx.x * 128, nchunk = T / cs, chunk = tok0 / cs;
     const size_t head = (size_t)bh * T;
-    const bf16_t* sbase = st + ((size_t)bh * nchunk + chunk) * nunit * 64 * VP;
+    const bf16_t* sbase = st + ((size_t)bh * nchunk + chunk) * nunit * 64 * SP;
 
-    u32x4 pre[NPF][PPT];
+    u32x2 pre[NPF][PPT];
 #pragma unroll
     for (int j = 0; j < NPF - 1; ++j) PA_UNIT_LOAD(pre[j], j)
+    PA_UNIT_ZERO_PAD(stt[0])
+    PA_UNIT_ZERO_PAD(stt[1])
     stage_x<HD, 128>(xs, X + (head + tok0) * HD, 128, xscale, tid);
     f32x4 acc[NVB][4];
 #pragma unroll
@@ -527,7 +537,7 @@ __global__ __launch_bounds__(128) void k_tiled_dphi(const bf16_t* __restrict__ X
                                                     const TileDesc* __restrict__ tab, const bf16_t* __restrict__ st,
                                                     float* __restrict__ part, int T, int cs, int nunit, int nunit_real,
                                                     float xscale, float outscale) {
-    constexpr int VP = HD + 16, NK = HD / 32, PIECES = 64 * (VP / 8), PPT = (PIECES + 127) / 128, AP = 16 + 4;
+    constexpr int VP = HD + 16, NK = HD / 32, SP = HD + 4, PIECES = 64 * (SP / 4), PPT = (PIECES + 127) / 128, AP = 16 + 4;
     __shared__ float xs[128][HD + 1];
     __shared__ __attribute__((aligned(16))) Tile64<VP> stt;   // one slot (LDS decides how many workgroups share a CU): two barriers per unit
     __shared__ __attribute__((aligned(16))) float dph[2][64][AP];
@@ -535,11 +545,12 @@ __global__ __launch_bounds__(128) void k_tiled_dphi(const bf16_t* __restrict__ X
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6), r16 = lane & 15, g = lane >> 4;
     const int bh = blockIdx.y, tok0 = blockIdx.x * 128, nchunk = T / cs, chunk = tok0 / cs;
     const size_t head = (size_t)bh * T;
-    const bf16_t* sbase = st + ((size_t)bh * nchunk + chunk) * nunit * 64 * VP;
+    const bf16_t* sbase = st + ((size_t)bh * nchunk + chunk) * nunit * 64 * SP;
 
-    u32x4 pre[NPF][PPT];
+    u32x2 pre[NPF][PPT];
 #pragma unroll
     for (int j = 0; j < NPF - 1; ++j) PA_UNIT_LOAD(pre[j], j)
+    PA_UNIT_ZERO_PAD(stt)
     stage_x<HD, 128>(xs, X + (head + tok0) * HD, 128, xscale, tid);
 #pragma unroll
     for (int f = 0; f < HD; ++f) dxs[w][f][lane] = 0.f;
@@ -603,6 +614,7 @@ __global__ __launch_bounds__(128) void k_tiled_dphi(const bf16_t* __restrict__ X
 }
 #undef PA_UNIT_LOAD
 #undef PA_UNIT_STORE
+#undef PA_UNIT_ZERO_PAD
 
 template <int P, int DT, int HD>
 bool scan_t(const char* name, hipStream_t s, const TiledPlan& pl, bool rev, const bf16_t* X, const bf16_t* Yp, const TileDesc* tab,
@@ -665,7 +677,7 @@ TiledPlan tiled_plan(int p, int d, int dt) {
     pl.nunit_real = rows >= 64 ? pl.ntile * (rows / 64) : (pl.ntile + 64 / rows - 1) / (64 / rows);
     pl.nunit = (pl.nunit_real + 3) / 4 * 4;
     pl.nentry = rows >= 64 ? (pl.nunit + rows / 64 - 1) / (rows / 64) : pl.nunit * (64 / rows);
-    pl.state_elems = (size_t)pl.nunit * 64 * pl.vp;
+    pl.state_elems = (size_t)pl.nunit * 64 * (d + 4);   // rows are stored without their zero columns
     return pl;
 }
 

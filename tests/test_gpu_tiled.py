@@ -64,3 +64,14 @@ def test_automatic_choice_runs_the_tiled_kernels_for_degree_four():
     O, Z = orc.fwd_bhtd(Q, K, V, 4, 128, True, 1.0)
     dQ, dK, dV = orc.bwd_bhtd(Q, K, V, G, 4, 128, True, 1.0)
     assert_close(got, dict(O=O, Z=Z, dQ=dQ, dK=dK, dV=dV), "bf16", "auto p=4 d=32")
+
+
+def test_tiled_ragged_last_chunk():
+    """A sequence that is not a multiple of the chunk runs padded with zero rows, as in the other chunked
+    matrix-core kernels: p = 4, T = 1000 at chunk 128 (a last chunk of 104 tokens), kept states."""
+    p, d, T, chunk = 4, 32, 1000, 128
+    Q, K, V, G = inputs.make_qkvg(1, 2, T, d, seed=5300, dtype="bf16")
+    got = run_fwd_bwd(Q, K, V, G, p, chunk, "bf16", impl="tiled", keep_state=True)
+    O, Z = orc.fwd_bhtd(Q, K, V, p, chunk, True, 1.0)
+    dQ, dK, dV = orc.bwd_bhtd(Q, K, V, G, p, chunk, True, 1.0)
+    assert_close(got, dict(O=O, Z=Z, dQ=dQ, dK=dK, dV=dV), "bf16", "tiled ragged p=4 T=1000")
