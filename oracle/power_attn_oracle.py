@@ -234,9 +234,11 @@ def bwd_quadratic(Q, K, V, G, p: int, normalize: bool = True, scale: float = 1.0
     return dQ, dK, dV
 
 
-def bwd_dq_row(Q, K, V, G, i: int, p: int, normalize: bool = True, scale: float = 1.0):
-    """dQ_i alone, O(i d): needs only row i of the forward pass."""
-    O_i, Z_i = fwd_row(Q, K, V, i, p, normalize, scale)
+def bwd_dq_row(Q, K, V, G, i: int, p: int, normalize: bool = True, scale: float = 1.0, saved=None):
+    """dQ_i alone, O(i d): needs only row i of the forward pass.  saved = (O_i, Z_i): evaluate at these
+    saved forward results instead of recomputing them (a backward pass is handed O and Z as inputs; this is
+    how a test measures what rounding the saved output to its storage type does to a row)."""
+    O_i, Z_i = fwd_row(Q, K, V, i, p, normalize, scale) if saved is None else (np.asarray(saved[0], dtype=F64), float(saved[1]))
     g = np.asarray(G[i], dtype=F64)
     if normalize:
         if Z_i == 0.0:

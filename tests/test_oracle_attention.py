@@ -235,6 +235,31 @@ def test_chunked_and_sampled_backward_agree_with_quadratic(p, normalize):
         np.testing.assert_allclose(dv, want[2][i], rtol=1e-9, atol=1e-12)
 
 
+def test_dq_row_at_saved_forward_results():
+    """bwd_dq_row(saved=(O_i, Z_i)): with the exact forward results it is the default; with Z_i doubled and
+    O_i kept, Ghat and gz halve and so does the row (the row is linear in 1 / Z_i at fixed O_i); with O_i moved
+    by delta the row moves by -(G_i . delta) / Z_i times the gradient of Z_i, i.e. of sum_j s_ij^p (pinned
+    against finite differences of that sum taken with the forward row sampler)."""
+    T, d, v, p = 20, 4, 3, 4
+    Q, K, V = _rand(T, d, v, seed=900)
+    G = np.random.default_rng(901).standard_normal((T, v))
+    i = 13
+    O_i, Z_i = orc.fwd_row(Q, K, V, i, p)
+    base = orc.bwd_dq_row(Q, K, V, G, i, p)
+    np.testing.assert_allclose(orc.bwd_dq_row(Q, K, V, G, i, p, saved=(O_i, Z_i)), base, rtol=1e-13)
+    np.testing.assert_allclose(orc.bwd_dq_row(Q, K, V, G, i, p, saved=(O_i, 2.0 * Z_i)), 0.5 * base, rtol=1e-12)
+    delta = np.array([0.3, -0.2, 0.1])
+    moved = orc.bwd_dq_row(Q, K, V, G, i, p, saved=(O_i + delta, Z_i))
+    dZ = np.zeros(d)
+    h = 1e-6
+    for a in range(d):
+        Qp, Qm = Q.copy(), Q.copy()
+        Qp[i, a] += h
+        Qm[i, a] -= h
+        dZ[a] = (orc.fwd_row(Qp, K, V, i, p)[1] - orc.fwd_row(Qm, K, V, i, p)[1]) / (2 * h)
+    np.testing.assert_allclose(moved - base, -(G[i] @ delta) / Z_i * dZ, rtol=1e-6, atol=1e-9)
+
+
 def test_bhtd_wrappers_loop_over_heads():
     rng = np.random.default_rng(8)
     Q, K, V, G = (rng.standard_normal((2, 3, 10, 4)) * 0.5 for _ in range(4))
