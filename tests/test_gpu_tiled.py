@@ -40,6 +40,8 @@ CASES = [
     (3, 4, 32, 1, 2, 1024, 512, 0.7, False),
     (2, 8, 64, 1, 2, 1024, 256, 1.0, True),
     (3, 4, 64, 1, 1, 512, 128, 1.2, True),
+    (4, 2, 32, 1, 2, 640, 128, 1.0, False),     # 2.5 blocks of the in-chunk kernels' 256 queries
+    (2, 8, 32, 3, 5, 256, 128, 1.0, True),      # two chunks, odd head count
 ]
 
 
@@ -78,3 +80,14 @@ def test_tiled_ragged_last_chunk():
     O, Z = orc.fwd_bhtd(Q, K, V, p, None, True, 1.0)
     dQ, dK, dV = orc.bwd_bhtd(Q, K, V, G, p, None, True, 1.0)
     assert_close(got, dict(O=O, Z=Z, dQ=dQ, dK=dK, dV=dV), "bf16", "tiled ragged p=4 T=1000")
+
+
+@pytest.mark.parametrize("p,dt", [(2, 8), (4, 4)])
+def test_tiled_unnormalised_even_degree(p, dt):
+    """normalize = 0 with an even degree: O is the numerator, Z is still returned, the backward pass has no
+    normaliser terms."""
+    Q, K, V, G = inputs.make_qkvg(1, 2, 512, 32, seed=5400 + p, dtype="bf16")
+    got = run_fwd_bwd(Q, K, V, G, p, 128, "bf16", normalize=False, impl="tiled", d_tile=dt)
+    O, Z = orc.fwd_bhtd(Q, K, V, p, None, False, 1.0)
+    dQ, dK, dV = orc.bwd_bhtd(Q, K, V, G, p, None, False, 1.0)
+    assert_close(got, dict(O=O, Z=Z, dQ=dQ, dK=dK, dV=dV), "bf16", f"tiled un-normalised p={p}")
