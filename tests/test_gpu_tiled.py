@@ -42,6 +42,9 @@ CASES = [
     (3, 4, 64, 1, 1, 512, 128, 1.2, True),
     (4, 2, 32, 1, 2, 640, 128, 1.0, False),     # 2.5 blocks of the in-chunk kernels' 256 queries
     (2, 8, 32, 3, 5, 256, 128, 1.0, True),      # two chunks, odd head count
+    (3, 4, 64, 1, 2, 2048, 256, 1.0, True),     # 816 tiles, 16 chunks
+    (2, 16, 64, 2, 2, 2048, 128, 0.9, False),   # 256-row tiles
+    (4, 4, 32, 1, 1, 4096, 128, 1.0, True),     # 32 chunks
 ]
 
 
