@@ -26,6 +26,9 @@
 // columns beyond live in LDS only, as zeros.
 // MFMA: v_mfma_f32_16x16x32_bf16, and v_mfma_f32_16x16x16_bf16 for the 16 columns beyond d where the
 // contraction runs over the value columns.  Operand layouts as in mfma_common.hpp.
+#include <cmath>
+#include <type_traits>
+
 #include "mfma_common.hpp"
 
 namespace pa {
@@ -93,9 +96,27 @@ __device__ __forceinline__ void wave_sync() {
 }
 
 // ---- the embedding, one thread per token ----------------------------------------------------------------
-// x: the token's features (float32, LDS).  td: the tile (uniform over the wave).
-template <int P, int DT>
-__device__ __forceinline__ void right_feats(const float* x, const TileDesc& td, float (&uR)[Emb<P, DT>::NR]) {
+// A token's features as they wait in LDS for the thread that owns the token: float32, or - from head size 64
+// on, where LDS decides how many workgroups share a CU - the bf16 values as they came.
+struct RowF32 {
+    const float* p;
+    __device__ __forceinline__ float operator[](int i) const { return p[i]; }
+};
+struct RowBF16 {
+    const bf16_t* p;
+    __device__ __forceinline__ float operator[](int i) const { return bf16_to_f32(p[i]); }
+};
+template <int HD>
+struct XStore {
+    static constexpr bool BF = HD >= 64;
+    typedef typename std::conditional<BF, bf16_t, float>::type elem;
+    typedef typename std::conditional<BF, RowBF16, RowF32>::type row;
+    static constexpr int PITCH = BF ? HD + 2 : HD + 1;   // an odd number of dwords: the lanes' rows start in different banks
+};
+
+// x: the token's features.  td: the tile (uniform over the wave).
+template <int P, int DT, typename X>
+__device__ __forceinline__ void right_feats(const X x, const TileDesc& td, float (&uR)[Emb<P, DT>::NR]) {
     using E = Emb<P, DT>;
     if constexpr (E::PR == 1) {
 #pragma unroll
@@ -114,15 +135,15 @@ __device__ __forceinline__ void right_feats(const float* x, const TileDesc& td, 
     }
 }
 // alpha may be a run-time value (uniform over the wave): features are fetched from LDS by address
-template <int P, int DT>
-__device__ __forceinline__ float left_feat(const float* x, const TileDesc& td, int alpha) {
+template <int P, int DT, typename X>
+__device__ __forceinline__ float left_feat(const X x, const TileDesc& td, int alpha) {
     using E = Emb<P, DT>;
     if constexpr (E::PL == 1) return x[DT * td.t[0] + alpha];
     else return x[DT * td.t[0] + alpha / DT] * x[DT * td.t[1] + alpha % DT];
 }
 
-template <int P, int DT>
-__device__ __forceinline__ void unit_phi(const float* x, const TileDesc* __restrict__ tab, int unit, float (&phi)[64]) {
+template <int P, int DT, typename X>
+__device__ __forceinline__ void unit_phi(const X x, const TileDesc* __restrict__ tab, int unit, float (&phi)[64]) {
     using E = Emb<P, DT>;
     if constexpr (E::R >= 64) {
         const TileDesc td = tab[unit / E::UPT];
@@ -156,8 +177,8 @@ __device__ __forceinline__ void dx_add(float* dx, int f, float v) { dx[64 * f] +
 
 // chain rule through one side: du[i] = dL/du for the N = DT^PS values of the side whose first position is
 // `pos`; alpha0: index of du[0] within the side (non-zero only for a slice of the left side)
-template <int DT, int PS, int N>
-__device__ __forceinline__ void side_chain(const float* x, const TileDesc& td, int pos, int alpha0, const float (&du)[N], float* dx) {
+template <int DT, int PS, int N, typename X>
+__device__ __forceinline__ void side_chain(const X x, const TileDesc& td, int pos, int alpha0, const float (&du)[N], float* dx) {
     if constexpr (PS == 1) {
 #pragma unroll
         for (int i = 0; i < N; ++i) dx_add(dx, DT * td.t[pos] + alpha0 + i, du[i]);
@@ -207,7 +228,8 @@ struct UnitJacobian {
     TileDesc td;
     int a0;
 
-    __device__ __forceinline__ void begin(const float* x, const TileDesc* __restrict__ tab, int unit) {
+    template <typename X>
+    __device__ __forceinline__ void begin(const X x, const TileDesc* __restrict__ tab, int unit) {
         if constexpr (SLICE) {
             td = tab[unit / E::UPT];
             a0 = (unit % E::UPT) * E::NA;
@@ -216,7 +238,8 @@ struct UnitJacobian {
             for (int b = 0; b < E::NR; ++b) dR[b] = 0.f;
         }
     }
-    __device__ __forceinline__ void block(const float* x, const TileDesc* __restrict__ tab, int unit, int nb, const float (&A)[16],
+    template <typename X>
+    __device__ __forceinline__ void block(const X x, const TileDesc* __restrict__ tab, int unit, int nb, const float (&A)[16],
                                           float* dx) {
         if constexpr (!SLICE) {
             td = tab[unit * E::TPU + nb];
@@ -240,22 +263,28 @@ struct UnitJacobian {
         side_chain<DT, E::PL, APB>(x, td, 0, a0 + (SLICE ? nb * APB : 0), dL, dx);
         if constexpr (!SLICE) side_chain<DT, E::PR, E::NR>(x, td, E::PL, 0, dR, dx);
     }
-    __device__ __forceinline__ void finish(const float* x, float* dx) {
+    template <typename X>
+    __device__ __forceinline__ void finish(const X x, float* dx) {
         if constexpr (SLICE) side_chain<DT, E::PR, E::NR>(x, td, E::PL, 0, dR, dx);
     }
 };
 
-// 64 token rows of X (bf16, [.][HD]) -> xs[token][HD + 1] float32, times xscale
+// ntok token rows of X (bf16, [.][HD]) -> xs[token][.], float32 or bf16 as XStore<HD> says
 template <int HD, int NT>
-__device__ __forceinline__ void stage_x(float (*xs)[HD + 1], const bf16_t* __restrict__ Xrows, int ntok, float xscale, int tid) {
+__device__ __forceinline__ void stage_x(typename XStore<HD>::elem (*xs)[XStore<HD>::PITCH], const bf16_t* __restrict__ Xrows, int ntok, int tid) {
     for (int id = tid; id < ntok * (HD / 8); id += NT) {
         const int row = id / (HD / 8), c8 = id % (HD / 8);
         const uint4 u = *(const uint4*)(Xrows + (size_t)row * HD + 8 * c8);
-        float* dst = &xs[row][8 * c8];
-        dst[0] = xscale * bf_lo(u.x); dst[1] = xscale * bf_hi(u.x);
-        dst[2] = xscale * bf_lo(u.y); dst[3] = xscale * bf_hi(u.y);
-        dst[4] = xscale * bf_lo(u.z); dst[5] = xscale * bf_hi(u.z);
-        dst[6] = xscale * bf_lo(u.w); dst[7] = xscale * bf_hi(u.w);
+        if constexpr (XStore<HD>::BF) {
+            uint32_t* dst = (uint32_t*)&xs[row][8 * c8];   // rows start on a dword, not on 16 bytes
+            dst[0] = u.x; dst[1] = u.y; dst[2] = u.z; dst[3] = u.w;
+        } else {
+            float* dst = &xs[row][8 * c8];
+            dst[0] = bf_lo(u.x); dst[1] = bf_hi(u.x);
+            dst[2] = bf_lo(u.y); dst[3] = bf_hi(u.y);
+            dst[4] = bf_lo(u.z); dst[5] = bf_hi(u.z);
+            dst[6] = bf_lo(u.w); dst[7] = bf_hi(u.w);
+        }
     }
 }
 
@@ -332,14 +361,15 @@ __global__ __launch_bounds__(256) void k_tiled_pack(const bf16_t* __restrict__ Y
 // with VP / 4 consecutive value columns of one state row).  Before the tokens of chunk c are added, the
 // running sum - the state entering chunk c - is stored (REV: the walk runs from the last chunk down and the
 // stored sum is the state gradient of the chunks after c).  X: the rows phi is formed from (K; REV: Q, times
-// xscale), Yp: the extended value rows ([V, 1]; REV: [ghat, gz]).
+// oscale, which goes onto the stored state), Yp: the extended value rows ([V, 1]; REV: [ghat, gz]).
 template <int P, int DT, int HD, bool REV>
-__global__ __launch_bounds__(256) void k_tiled_scan(const bf16_t* __restrict__ X, const bf16_t* __restrict__ Yp,
+__global__ __launch_bounds__(256, 2) void k_tiled_scan(const bf16_t* __restrict__ X, const bf16_t* __restrict__ Yp,
                                                     const TileDesc* __restrict__ tab, bf16_t* __restrict__ st, int T, int cs,
-                                                    int nunit, float xscale) {
+                                                    int nunit, float oscale) {
     using E = Emb<P, DT>;
     constexpr int VP = HD + 16, NVB = VP / 16, SP = HD + 4;
-    __shared__ float xs[64][HD + 1];
+    typedef XStore<HD> XS;
+    __shared__ __attribute__((aligned(16))) typename XS::elem xs[64][XS::PITCH];
     __shared__ __attribute__((aligned(16))) Tile64<VP> yt;
     __shared__ __attribute__((aligned(16))) Tile64<64> phis[4];
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6), r16 = lane & 15, g = lane >> 4;
@@ -348,7 +378,7 @@ __global__ __launch_bounds__(256) void k_tiled_scan(const bf16_t* __restrict__ X
 
     float mult[4];
 #pragma unroll
-    for (int nb = 0; nb < 4; ++nb) mult[nb] = tab[E::R >= 64 ? unit / E::UPT : unit * E::TPU + (16 * nb) / E::R].mult;
+    for (int nb = 0; nb < 4; ++nb) mult[nb] = oscale * tab[E::R >= 64 ? unit / E::UPT : unit * E::TPU + (16 * nb) / E::R].mult;
     f32x4 acc[NVB][4];
 #pragma unroll
     for (int vb = 0; vb < NVB; ++vb)
@@ -395,12 +425,17 @@ __global__ __launch_bounds__(256) void k_tiled_scan(const bf16_t* __restrict__ X
 #pragma unroll
         for (int q = 0; q < XP; ++q) {
             const int id = min(tid + 256 * q, 64 * (HD / 8) - 1);
-            float* dst = &xs[id / (HD / 8)][8 * (id % (HD / 8))];
             const u32x4 u = xr[q];
-            dst[0] = xscale * bf_lo(u[0]); dst[1] = xscale * bf_hi(u[0]);
-            dst[2] = xscale * bf_lo(u[1]); dst[3] = xscale * bf_hi(u[1]);
-            dst[4] = xscale * bf_lo(u[2]); dst[5] = xscale * bf_hi(u[2]);
-            dst[6] = xscale * bf_lo(u[3]); dst[7] = xscale * bf_hi(u[3]);
+            if constexpr (XS::BF) {
+                uint32_t* dst = (uint32_t*)&xs[id / (HD / 8)][8 * (id % (HD / 8))];
+                dst[0] = u[0]; dst[1] = u[1]; dst[2] = u[2]; dst[3] = u[3];
+            } else {
+                float* dst = &xs[id / (HD / 8)][8 * (id % (HD / 8))];
+                dst[0] = bf_lo(u[0]); dst[1] = bf_hi(u[0]);
+                dst[2] = bf_lo(u[1]); dst[3] = bf_hi(u[1]);
+                dst[4] = bf_lo(u[2]); dst[5] = bf_hi(u[2]);
+                dst[6] = bf_lo(u[3]); dst[7] = bf_hi(u[3]);
+            }
         }
 #pragma unroll
         for (int q = 0; q < YP; ++q) {
@@ -411,7 +446,7 @@ __global__ __launch_bounds__(256) void k_tiled_scan(const bf16_t* __restrict__ X
         PA_STEP_FETCH(min(sl + 1, nstep - 1))
         {
             float phi[64];
-            unit_phi<P, DT>(&xs[lane][0], tab, unit, phi);
+            unit_phi<P, DT>(typename XS::row{&xs[lane][0]}, tab, unit, phi);
             put_phi(phis[w], lane, phi);
         }
         wave_sync();
@@ -438,7 +473,17 @@ __global__ __launch_bounds__(256) void k_tiled_scan(const bf16_t* __restrict__ X
 // streams that chunk's state, unit by unit: NPF units are on their way from memory in registers while one is
 // being worked on from a two-slot LDS ring.  zpart (may be null) receives the normaliser column's share.
 // Also serves dV: the state gradient read out with phi(k).
-constexpr int NPF = 4;   // units in flight per workgroup
+// Workgroups are dealt to the 8 XCDs round-robin by their linear id, each XCD with an L2 of its own.  The m
+// 128-token blocks of one chunk stream the same state, so they are given ids 8 apart: same XCD, about the
+// same time.  (Identity when the grid is not a multiple of 8 m blocks.)
+__device__ __forceinline__ int token_block(int bx, int nblk, int m) {
+    if (m <= 1 || nblk % (8 * m) != 0) return bx;
+    const int base = bx - bx % (8 * m), r = bx % (8 * m);
+    return (base / m + r % 8) * m + r / 8;
+}
+
+template <int HD>
+constexpr int units_in_flight() { return HD >= 128 ? 2 : 4; }   // per workgroup, in registers
 
 // unit u (64 rows x SP bf16, contiguous) of the state at sbase -> registers; PPT pieces of 8 bytes per thread
 // (loads are unconditional, on clamped indices: an array that is assigned under a condition is kept in scratch
@@ -462,13 +507,16 @@ template <int P, int DT, int HD>
 __global__ __launch_bounds__(128) void k_tiled_readout(const bf16_t* __restrict__ X, const TileDesc* __restrict__ tab,
                                                        const bf16_t* __restrict__ st, float* __restrict__ part,
                                                        float* __restrict__ zpart, int T, int cs, int nunit, int nunit_real,
-                                                       float xscale) {
+                                                       float oscale) {
     constexpr int VP = HD + 16, NVB = VP / 16, SP = HD + 4, PIECES = 64 * (SP / 4), PPT = (PIECES + 127) / 128;
-    __shared__ float xs[128][HD + 1];
-    __shared__ __attribute__((aligned(16))) Tile64<VP> stt[2];
+    constexpr int NPF = units_in_flight<HD>();
+    typedef XStore<HD> XS;
+    __shared__ __attribute__((aligned(16))) typename XS::elem xs[128][XS::PITCH];
+    constexpr int SLOTS = HD >= 128 ? 1 : 2;   // LDS decides how many workgroups share a CU: one slot costs a second barrier per unit
+    __shared__ __attribute__((aligned(16))) Tile64<VP> stt[SLOTS];
     __shared__ __attribute__((aligned(16))) Tile64<64> phis[2];
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6), r16 = lane & 15, g = lane >> 4;
-    const int bh = blockIdx.y, tok0 = blockIdx.x * 128, nchunk = T / cs, chunk = tok0 / cs;
+    const int bh = blockIdx.y, tok0 = token_block(blockIdx.x, gridDim.x, cs / 128) * 128, nchunk = T / cs, chunk = tok0 / cs;
     const size_t head = (size_t)bh * T;
     const bf16_t* sbase = st + ((size_t)bh * nchunk + chunk) * nunit * 64 * SP;
 
@@ -476,8 +524,8 @@ __global__ __launch_bounds__(128) void k_tiled_readout(const bf16_t* __restrict_
 #pragma unroll
     for (int j = 0; j < NPF - 1; ++j) PA_UNIT_LOAD(pre[j], j)
     PA_UNIT_ZERO_PAD(stt[0])
-    PA_UNIT_ZERO_PAD(stt[1])
-    stage_x<HD, 128>(xs, X + (head + tok0) * HD, 128, xscale, tid);
+    if (SLOTS > 1) PA_UNIT_ZERO_PAD(stt[SLOTS - 1])
+    stage_x<HD, 128>(xs, X + (head + tok0) * HD, 128, tid);
     f32x4 acc[NVB][4];
 #pragma unroll
     for (int vb = 0; vb < NVB; ++vb)
@@ -490,12 +538,13 @@ __global__ __launch_bounds__(128) void k_tiled_readout(const bf16_t* __restrict_
             const int u = u0 + j;
             PA_UNIT_LOAD(pre[(j + NPF - 1) % NPF], u + NPF - 1)
             if (u >= nunit_real) continue;
-            Tile64<VP>& cur = stt[j & 1];
+            Tile64<VP>& cur = stt[j & (SLOTS - 1)];
+            if (SLOTS == 1) __syncthreads();
             PA_UNIT_STORE(cur, pre[j])
             __syncthreads();
             {
                 float phi[64];
-                unit_phi<P, DT>(&xs[64 * w + lane][0], tab, u, phi);
+                unit_phi<P, DT>(typename XS::row{&xs[64 * w + lane][0]}, tab, u, phi);
                 put_phi(phis[w], lane, phi);
             }
             wave_sync();
@@ -522,13 +571,13 @@ __global__ __launch_bounds__(128) void k_tiled_readout(const bf16_t* __restrict_
         const size_t row = head + tok0 + 64 * w + 16 * ib + r16;
 #pragma unroll
         for (int vb = 0; vb < HD / 16; ++vb)
-            *(float4*)(part + row * HD + 16 * vb + 4 * g) =
-                make_float4(acc[vb][ib][0], acc[vb][ib][1], acc[vb][ib][2], acc[vb][ib][3]);
-        if (zpart != nullptr && g == 0) zpart[row] = acc[HD / 16][ib][0];
+            *(float4*)(part + row * HD + 16 * vb + 4 * g) = make_float4(oscale * acc[vb][ib][0], oscale * acc[vb][ib][1],
+                                                                        oscale * acc[vb][ib][2], oscale * acc[vb][ib][3]);
+        if (zpart != nullptr && g == 0) zpart[row] = oscale * acc[HD / 16][ib][0];
     }
 }
 
-// ---- d phi and the Jacobian: part[t][:] = outscale J_phi(x_t)^T (S_chunk(t) y'_t) --------------------------
+// ---- d phi and the Jacobian: part[t][:] = oscale J_phi(x_t)^T (S_chunk(t) y'_t) ----------------------------
 // Same shape as the read-out.  Per block of 16 state rows: A = S y'^T on the matrix cores (contraction over
 // the VP value columns; y' = [ghat, gz] for dQ, [v, 1] for dK, held as operand fragments in registers), laid
 // down in LDS as [token][row], then the Jacobian by the thread that owns the token.
@@ -536,14 +585,16 @@ template <int P, int DT, int HD>
 __global__ __launch_bounds__(128) void k_tiled_dphi(const bf16_t* __restrict__ X, const bf16_t* __restrict__ Yp,
                                                     const TileDesc* __restrict__ tab, const bf16_t* __restrict__ st,
                                                     float* __restrict__ part, int T, int cs, int nunit, int nunit_real,
-                                                    float xscale, float outscale) {
+                                                    float oscale) {
     constexpr int VP = HD + 16, NK = HD / 32, SP = HD + 4, PIECES = 64 * (SP / 4), PPT = (PIECES + 127) / 128, AP = 16 + 4;
-    __shared__ float xs[128][HD + 1];
+    constexpr int NPF = units_in_flight<HD>();
+    typedef XStore<HD> XS;
+    __shared__ __attribute__((aligned(16))) typename XS::elem xs[128][XS::PITCH];
     __shared__ __attribute__((aligned(16))) Tile64<VP> stt;   // one slot (LDS decides how many workgroups share a CU): two barriers per unit
     __shared__ __attribute__((aligned(16))) float dph[2][64][AP];
     __shared__ float dxs[2][HD][64];
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6), r16 = lane & 15, g = lane >> 4;
-    const int bh = blockIdx.y, tok0 = blockIdx.x * 128, nchunk = T / cs, chunk = tok0 / cs;
+    const int bh = blockIdx.y, tok0 = token_block(blockIdx.x, gridDim.x, cs / 128) * 128, nchunk = T / cs, chunk = tok0 / cs;
     const size_t head = (size_t)bh * T;
     const bf16_t* sbase = st + ((size_t)bh * nchunk + chunk) * nunit * 64 * SP;
 
@@ -551,7 +602,7 @@ __global__ __launch_bounds__(128) void k_tiled_dphi(const bf16_t* __restrict__ X
 #pragma unroll
     for (int j = 0; j < NPF - 1; ++j) PA_UNIT_LOAD(pre[j], j)
     PA_UNIT_ZERO_PAD(stt)
-    stage_x<HD, 128>(xs, X + (head + tok0) * HD, 128, xscale, tid);
+    stage_x<HD, 128>(xs, X + (head + tok0) * HD, 128, tid);
 #pragma unroll
     for (int f = 0; f < HD; ++f) dxs[w][f][lane] = 0.f;
     Frag yf[4][NK];
@@ -563,7 +614,7 @@ __global__ __launch_bounds__(128) void k_tiled_dphi(const bf16_t* __restrict__ X
         for (int ks = 0; ks < NK; ++ks) yf[ib][ks].u = *(const uint4*)(yrow + 32 * ks + 8 * g);
         ytail[ib] = *(const uint2*)(yrow + HD + 4 * g);
     }
-    const float* xrow = &xs[64 * w + lane][0];
+    const typename XS::row xrow{&xs[64 * w + lane][0]};
     float* dxcol = &dxs[w][0][lane];
 
     for (int u0 = 0; u0 < nunit_real; u0 += NPF) {
@@ -609,8 +660,8 @@ __global__ __launch_bounds__(128) void k_tiled_dphi(const bf16_t* __restrict__ X
     float* out = part + (head + tok0 + 64 * w + lane) * HD;
 #pragma unroll
     for (int f4 = 0; f4 < HD / 4; ++f4)
-        *(float4*)(out + 4 * f4) = make_float4(outscale * dxs[w][4 * f4][lane], outscale * dxs[w][4 * f4 + 1][lane],
-                                               outscale * dxs[w][4 * f4 + 2][lane], outscale * dxs[w][4 * f4 + 3][lane]);
+        *(float4*)(out + 4 * f4) = make_float4(oscale * dxs[w][4 * f4][lane], oscale * dxs[w][4 * f4 + 1][lane],
+                                               oscale * dxs[w][4 * f4 + 2][lane], oscale * dxs[w][4 * f4 + 3][lane]);
 }
 #undef PA_UNIT_LOAD
 #undef PA_UNIT_STORE
@@ -621,8 +672,9 @@ bool scan_t(const char* name, hipStream_t s, const TiledPlan& pl, bool rev, cons
             bf16_t* st, int BH, int T, int cs, float xscale) {
     LaunchScope ls(name, s);
     const dim3 grid(pl.nunit / 4, BH);
-    if (rev) hipLaunchKernelGGL((k_tiled_scan<P, DT, HD, true>), grid, dim3(256), 0, s, X, Yp, tab, st, T, cs, pl.nunit, xscale);
-    else hipLaunchKernelGGL((k_tiled_scan<P, DT, HD, false>), grid, dim3(256), 0, s, X, Yp, tab, st, T, cs, pl.nunit, xscale);
+    const float oscale = powf(xscale, (float)P);   // phi(s x) = s^p phi(x)
+    if (rev) hipLaunchKernelGGL((k_tiled_scan<P, DT, HD, true>), grid, dim3(256), 0, s, X, Yp, tab, st, T, cs, pl.nunit, oscale);
+    else hipLaunchKernelGGL((k_tiled_scan<P, DT, HD, false>), grid, dim3(256), 0, s, X, Yp, tab, st, T, cs, pl.nunit, oscale);
     return launch_ok();
 }
 template <int P, int DT, int HD>
@@ -630,7 +682,7 @@ bool readout_t(const char* name, hipStream_t s, const TiledPlan& pl, const bf16_
                float* part, float* zpart, int BH, int T, int cs, float xscale) {
     LaunchScope ls(name, s);
     hipLaunchKernelGGL((k_tiled_readout<P, DT, HD>), dim3(T / 128, BH), dim3(128), 0, s, X, tab, st, part, zpart, T, cs, pl.nunit,
-                       pl.nunit_real, xscale);
+                       pl.nunit_real, powf(xscale, (float)P));
     return launch_ok();
 }
 template <int P, int DT, int HD>
@@ -638,7 +690,7 @@ bool dphi_t(const char* name, hipStream_t s, const TiledPlan& pl, const bf16_t* 
             const bf16_t* st, float* part, int BH, int T, int cs, float xscale, float outscale) {
     LaunchScope ls(name, s);
     hipLaunchKernelGGL((k_tiled_dphi<P, DT, HD>), dim3(T / 128, BH), dim3(128), 0, s, X, Yp, tab, st, part, T, cs, pl.nunit,
-                       pl.nunit_real, xscale, outscale);
+                       pl.nunit_real, outscale * powf(xscale, (float)(P - 1)));   // J_phi(s x) = s^(p-1) J_phi(x)
     return launch_ok();
 }
 
@@ -647,7 +699,8 @@ bool dphi_t(const char* name, hipStream_t s, const TiledPlan& pl, const bf16_t* 
 // every (degree, tile width, head size) the kernels are built for
 #define PA_TILED_SHAPES(X) \
     X(2, 4, 32) X(2, 8, 32) X(2, 16, 32) X(3, 4, 32) X(4, 2, 32) X(4, 4, 32) \
-    X(2, 4, 64) X(2, 8, 64) X(2, 16, 64) X(3, 4, 64)
+    X(2, 4, 64) X(2, 8, 64) X(2, 16, 64) X(3, 4, 64) \
+    X(2, 8, 128)
 
 bool tiled_shape_ok(int p, int d, int dt) {
 #define PA_X(PP, DD, HH) \
@@ -692,6 +745,7 @@ bool launch_tiled_pack(hipStream_t s, int hd, const bf16_t* Y, const float* col,
     const long long n = rows * ((hd + 16) / 8);
     if (hd == 32) hipLaunchKernelGGL((k_tiled_pack<32>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, Y, col, Yp, rows);
     else if (hd == 64) hipLaunchKernelGGL((k_tiled_pack<64>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, Y, col, Yp, rows);
+    else if (hd == 128) hipLaunchKernelGGL((k_tiled_pack<128>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, Y, col, Yp, rows);
     else return false;
     return launch_ok();
 }

@@ -17,6 +17,7 @@ pytestmark = pytest.mark.gpu
 SHAPES = [
     (2, 4, 32), (2, 8, 32), (2, 16, 32), (3, 4, 32), (4, 2, 32), (4, 4, 32),
     (2, 4, 64), (2, 8, 64), (2, 16, 64), (3, 4, 64),
+    (2, 8, 128),
 ]
 
 
@@ -45,6 +46,8 @@ CASES = [
     (3, 4, 64, 1, 2, 2048, 256, 1.0, True),     # 816 tiles, 16 chunks
     (2, 16, 64, 2, 2, 2048, 128, 0.9, False),   # 256-row tiles
     (4, 4, 32, 1, 1, 4096, 128, 1.0, True),     # 32 chunks
+    (2, 8, 128, 1, 2, 2048, 256, 0.8, True),    # d = 128: 136 tiles, two 128-token blocks per chunk
+    (2, 8, 128, 2, 1, 4096, 256, 1.0, False),   # 16 blocks per head: the blocks of a chunk are dealt 8 apart
 ]
 
 
