@@ -69,9 +69,10 @@ typedef enum {
                              of 128, not gated */
     PA_IMPL_TILED = 4     /* the chunked bf16 MFMA kernels with the degree and the tile width of the embedding
                              (Sec. 4.1.1) as parameters, chunk states in memory: d = v = 32 with (p, d_tile) in
-                             {(2,4), (2,8), (2,16), (3,4), (4,2), (4,4)}, d = v = 64 with {(2,4), (2,8), (2,16), (3,4)};
-                             chunk a multiple of 128 that divides T, at least two chunks, not gated.  What AUTO runs for
-                             the chunked form of p = 3 and p = 4 */
+                             {(2,4), (2,8), (2,16), (3,4), (4,2), (4,4)}, d = v = 64 with {(2,4), (2,8), (2,16), (3,4)},
+                             d = v = 128 with (2,8); chunk a multiple of 128 that divides T, at least two chunks, not
+                             gated.  What AUTO runs for the chunked form of p = 3 and p = 4, of d = 32, and of p = 2
+                             at d = 128 */
 } pa_impl;
 
 typedef struct {

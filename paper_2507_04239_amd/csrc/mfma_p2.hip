@@ -109,10 +109,12 @@ bool attn_ok(const pa_problem& pr) {
 // One chunk: the attention-form kernels.  (The chunked kernels can run p = 2, d = 64 as one chunk
 // too; that path remains for gated sequences that are a multiple of 128 but not of the block.)
 bool use_attn(const pa_problem& pr) { return attn_ok(pr) && pr.impl != PA_IMPL_RESIDENT && pr.impl != PA_IMPL_TILED; }
+bool use_tiled(const pa_problem& pr);
 // The resident-state kernels run when asked for by name, and wherever they are the only matrix-core kernels
-// for the chunked form (d = 128)
+// for the chunked form
 bool use_resident(const pa_problem& pr) {
-    return pr.impl != PA_IMPL_TILED && resident_ok(pr) && (pr.impl == PA_IMPL_RESIDENT || (!chunked_ok(pr) && !attn_ok(pr)));
+    if (pr.impl == PA_IMPL_TILED || !resident_ok(pr)) return false;
+    return pr.impl == PA_IMPL_RESIDENT || (!chunked_ok(pr) && !attn_ok(pr) && !use_tiled(pr));
 }
 
 // tiled kernels (any degree and tile width, chunk states in memory): workspace of the forward pass, the backward
@@ -177,12 +179,13 @@ AttnLayout make_attn_layout(const pa_problem& pr, bool backward) {
 }
 
 // The tiled kernels run when asked for by name or for a tile width, and wherever no other matrix-core kernel takes the
-// chunked form of the problem (degrees 3 and 4, d = 32)
+// chunked form of the problem (degrees 3 and 4, d = 32) or they are the faster ones (d = 128: measured against the
+// resident-state walk, which has to cut the state into slabs there)
 bool use_tiled(const pa_problem& pr) {
     if (!tiled_ok(pr)) return false;
     if (pr.impl == PA_IMPL_TILED) return true;
     if (pr.impl == PA_IMPL_RESIDENT) return false;
-    return pr.d_tile > 0 || (!chunked_ok(pr) && !attn_ok(pr) && !resident_ok(pr));
+    return pr.d_tile > 0 || (!chunked_ok(pr) && !attn_ok(pr));
 }
 
 }  // namespace

@@ -202,7 +202,7 @@ def test_d128_config5_shape_reduced_batch():
 
 def test_config5_as_stated_full_shape():
     """Config 5 as stated, all of it: bf16 fwd+bwd, p=2, B8 H16 T32768 d128, chunk 256, as bench.py runs it (the
-    resident-state matrix-core kernels, states kept between the passes).  One head, every output, against the
+    tiled matrix-core kernels, chunk states in memory and kept between the passes).  One head, every output, against the
     chunked float64 oracle; eight more heads spread over the batch, sampled rows of O, Z, dQ by the definition;
     sampled columns of dK, dV on the fully checked head."""
     name = "cfg5_bf16_p2_T32768_d128_c256"

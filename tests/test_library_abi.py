@@ -125,14 +125,17 @@ def test_tiled_kernels_host_logic():
     assert rows(mk(1, 12, 65536, 64, 64, 2, 128)) == 2304
     assert rows(mk(1, 12, 65536, 64, 64, 2, 128, d_tile=4)) == tspow_rows(64, 2, 4) == 2176
     assert rows(mk(1, 12, 65536, 64, 64, 2, 128, d_tile=16)) == 2560
-    # not taken: widths that are not built, one chunk, chunks that are not a multiple of 128, gates, float32, d = 128
+    # not taken: widths that are not built, one chunk, chunks that are not a multiple of 128, gates, float32, d = 128 beyond p = 2 with width 8
     assert not ok(mk(1, 2, 1024, 32, 32, 4, 128, d_tile=8), True)
     assert not ok(mk(1, 2, 1024, 32, 32, 4, 128, d_tile=3), True)
     assert not ok(mk(1, 2, 1024, 32, 32, 4, 1024, impl="tiled"), True)
     assert not ok(mk(1, 2, 1024, 32, 32, 4, 64, impl="tiled"), True)
     assert not ok(mk(1, 2, 1024, 32, 32, 4, 128, impl="tiled", gated=True), True)
     assert not ok(mk(1, 2, 1024, 32, 32, 4, 128, impl="tiled", dtype="f32"), True)
-    assert not ok(mk(1, 2, 1024, 128, 128, 2, 128, impl="tiled"), True)
+    assert ok(mk(1, 2, 1024, 128, 128, 2, 128, impl="tiled"), True)
+    assert rows(mk(1, 2, 1024, 128, 128, 2, 128, impl="tiled")) == tspow_rows(128, 2, 8) == 8704
+    assert not ok(mk(1, 2, 1024, 128, 128, 2, 128, d_tile=4), True)
+    assert not ok(mk(1, 2, 1024, 128, 128, 3, 128, impl="tiled", normalize=False), True)
     assert ok(mk(1, 2, 1024, 32, 32, 4, 128, gated=True), True)           # automatic: the vector-ALU family takes it
     assert rows(mk(1, 2, 1024, 32, 32, 4, 128, gated=True)) == 52360
     assert not ok(mk(1, 2, 1024, 32, 32, 4, 128, d_tile=-1), True)        # invalid
@@ -146,10 +149,11 @@ def test_support_matrix_host_logic():
     assert ok(mk(1, 2, 1024, 64, 64, 2, 128, impl="mfma"), True)
     assert rows(mk(1, 2, 1024, 64, 64, 2, 128, impl="mfma")) == 36 * 64            # tiled embedding, d_tile = 8
     assert not ok(mk(1, 2, 1024, 64, 64, 2, 64, impl="mfma"), True)
-    # d = 128 chunked: the resident-state kernels (136 tiles of 64 rows), also when asked for by name at d = 64
+    # d = 128 chunked: the tiled kernels (136 tiles of 64 rows); the resident-state kernels when asked for by name
     assert ok(mk(1, 2, 1024, 128, 128, 2, 256, impl="mfma"), True)
     assert rows(mk(1, 2, 1024, 128, 128, 2, 256, impl="mfma")) == 136 * 64
     assert ok(mk(1, 2, 1024, 64, 64, 2, 128, impl="resident"), True)
+    assert ok(mk(1, 2, 1024, 128, 128, 2, 256, impl="resident"), True)
     assert not ok(mk(1, 2, 1024, 64, 64, 2, 64, impl="resident"), True)            # chunk a multiple of 128
     assert not ok(mk(1, 2, 1024, 32, 32, 4, 128, impl="resident"), True)           # p = 2 only
     assert not ok(mk(1, 2, 1024, 64, 64, 2, 128, impl="resident", gated=True), True)
