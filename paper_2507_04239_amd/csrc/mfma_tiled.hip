@@ -490,17 +490,17 @@ constexpr int units_in_flight() { return HD >= 128 ? 2 : 4; }   // per workgroup
 // memory by the compiler, and the load then waits to be stored there; threads past the last piece repeat it)
 #define PA_UNIT_LOAD(REGS, U)                                                                                    \
     _Pragma("unroll") for (int q_ = 0; q_ < PPT; ++q_) {                                                         \
-        const int id_ = min(tid + 128 * q_, PIECES - 1);                                                         \
+        const int id_ = min(tid + NT * q_, PIECES - 1);                                                         \
         REGS[q_] = *(const u32x2*)(sbase + ((size_t)min((U), nunit_real - 1) * PIECES + id_) * 4);               \
     }
 #define PA_UNIT_STORE(DST, REGS)                                                                                 \
     _Pragma("unroll") for (int q_ = 0; q_ < PPT; ++q_) {                                                         \
-        const int id_ = min(tid + 128 * q_, PIECES - 1);                                                         \
+        const int id_ = min(tid + NT * q_, PIECES - 1);                                                         \
         *(u32x2*)&DST.r[id_ / (SP / 4)][4 * (id_ % (SP / 4))] = REGS[q_];                                        \
     }
 // columns SP .. VP - 1 of an LDS state tile are zero and never written again
 #define PA_UNIT_ZERO_PAD(DST)                                                                                    \
-    for (int id_ = tid; id_ < 64 * ((VP - SP) / 4); id_ += 128)                                                  \
+    for (int id_ = tid; id_ < 64 * ((VP - SP) / 4); id_ += NT)                                                  \
         *(u32x2*)&DST.r[id_ / ((VP - SP) / 4)][SP + 4 * (id_ % ((VP - SP) / 4))] = (u32x2){0u, 0u};
 
 template <int P, int DT, int HD>
@@ -508,7 +508,7 @@ __global__ __launch_bounds__(128) void k_tiled_readout(const bf16_t* __restrict_
                                                        const bf16_t* __restrict__ st, float* __restrict__ part,
                                                        float* __restrict__ zpart, int T, int cs, int nunit, int nunit_real,
                                                        float oscale) {
-    constexpr int VP = HD + 16, NVB = VP / 16, SP = HD + 4, PIECES = 64 * (SP / 4), PPT = (PIECES + 127) / 128;
+    constexpr int NT = 128, VP = HD + 16, NVB = VP / 16, SP = HD + 4, PIECES = 64 * (SP / 4), PPT = (PIECES + NT - 1) / NT;
     constexpr int NPF = units_in_flight<HD>();
     typedef XStore<HD> XS;
     __shared__ __attribute__((aligned(16))) typename XS::elem xs[128][XS::PITCH];
@@ -580,20 +580,32 @@ __global__ __launch_bounds__(128) void k_tiled_readout(const bf16_t* __restrict_
 // ---- d phi and the Jacobian: part[t][:] = oscale J_phi(x_t)^T (S_chunk(t) y'_t) ----------------------------
 // Same shape as the read-out.  Per block of 16 state rows: A = S y'^T on the matrix cores (contraction over
 // the VP value columns; y' = [ghat, gz] for dQ, [v, 1] for dK, held as operand fragments in registers), laid
-// down in LDS as [token][row], then the Jacobian by the thread that owns the token.
+// down in LDS as [token][row], then the Jacobian by a thread that owns the token.
+// At d = 128 (p = 2, d_tile 8) two waves share a group of 64 tokens: the float32 accumulators of 128 tokens
+// (64 KB) leave room for one workgroup per CU, and two waves would keep only two of its four SIMDs busy.  Wave
+// h of a pair takes the unit's rows with left index alpha in [4h, 4h + 4) and lands the sums whose feature
+// index within the tile is in that same range, on either side: the two waves then never touch the same
+// accumulator.  The right side's sums run over all alpha, so each wave passes the half it does not land to its
+// partner through LDS; they are added one unit late, between the two barriers that the next unit needs anyway.
+template <int HD>
+constexpr int dphi_waves_per_group() { return HD >= 128 ? 2 : 1; }
+
 template <int P, int DT, int HD>
-__global__ __launch_bounds__(128) void k_tiled_dphi(const bf16_t* __restrict__ X, const bf16_t* __restrict__ Yp,
-                                                    const TileDesc* __restrict__ tab, const bf16_t* __restrict__ st,
-                                                    float* __restrict__ part, int T, int cs, int nunit, int nunit_real,
-                                                    float oscale) {
-    constexpr int VP = HD + 16, NK = HD / 32, SP = HD + 4, PIECES = 64 * (SP / 4), PPT = (PIECES + 127) / 128, AP = 16 + 4;
+__global__ __launch_bounds__(128 * dphi_waves_per_group<HD>()) void k_tiled_dphi(
+    const bf16_t* __restrict__ X, const bf16_t* __restrict__ Yp, const TileDesc* __restrict__ tab, const bf16_t* __restrict__ st,
+    float* __restrict__ part, int T, int cs, int nunit, int nunit_real, float oscale) {
+    constexpr int WPG = dphi_waves_per_group<HD>(), NT = 128 * WPG, NBW = 4 / WPG;
+    constexpr int VP = HD + 16, NK = HD / 32, SP = HD + 4, PIECES = 64 * (SP / 4), PPT = (PIECES + NT - 1) / NT, AP = 16 + 4;
     constexpr int NPF = units_in_flight<HD>();
     typedef XStore<HD> XS;
     __shared__ __attribute__((aligned(16))) typename XS::elem xs[128][XS::PITCH];
     __shared__ __attribute__((aligned(16))) Tile64<VP> stt;   // one slot (LDS decides how many workgroups share a CU): two barriers per unit
-    __shared__ __attribute__((aligned(16))) float dph[2][64][AP];
+    __shared__ __attribute__((aligned(16))) float dph[2 * WPG][64][AP];
     __shared__ float dxs[2][HD][64];
+    __shared__ float handed[WPG > 1 ? 4 : 1][4][64];   // [wave that wrote it][i][token]
+    static_assert(WPG == 1 || (P == 2 && DT == 8), "the split of a unit between two waves is laid out for one 8 x 8 tile per unit");
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6), r16 = lane & 15, g = lane >> 4;
+    const int grp = w / WPG, part_w = w % WPG;   // token group of the wave, and which blocks of a unit it takes
     const int bh = blockIdx.y, tok0 = token_block(blockIdx.x, gridDim.x, cs / 128) * 128, nchunk = T / cs, chunk = tok0 / cs;
     const size_t head = (size_t)bh * T;
     const bf16_t* sbase = st + ((size_t)bh * nchunk + chunk) * nunit * 64 * SP;
@@ -602,20 +614,22 @@ __global__ __launch_bounds__(128) void k_tiled_dphi(const bf16_t* __restrict__ X
 #pragma unroll
     for (int j = 0; j < NPF - 1; ++j) PA_UNIT_LOAD(pre[j], j)
     PA_UNIT_ZERO_PAD(stt)
-    stage_x<HD, 128>(xs, X + (head + tok0) * HD, 128, tid);
+    stage_x<HD, NT>(xs, X + (head + tok0) * HD, 128, tid);
 #pragma unroll
-    for (int f = 0; f < HD; ++f) dxs[w][f][lane] = 0.f;
+    for (int f = 0; f < HD / WPG; ++f) dxs[grp][part_w * (HD / WPG) + f][lane] = 0.f;   // seen by the other wave after the loop's first barrier
     Frag yf[4][NK];
     uint2 ytail[4];
 #pragma unroll
     for (int ib = 0; ib < 4; ++ib) {
-        const bf16_t* yrow = Yp + (head + tok0 + 64 * w + 16 * ib + r16) * VP;
+        const bf16_t* yrow = Yp + (head + tok0 + 64 * grp + 16 * ib + r16) * VP;
 #pragma unroll
         for (int ks = 0; ks < NK; ++ks) yf[ib][ks].u = *(const uint4*)(yrow + 32 * ks + 8 * g);
         ytail[ib] = *(const uint2*)(yrow + HD + 4 * g);
     }
-    const typename XS::row xrow{&xs[64 * w + lane][0]};
-    float* dxcol = &dxs[w][0][lane];
+    const typename XS::row xrow{&xs[64 * grp + lane][0]};
+    float* dxcol = &dxs[grp][0][lane];
+    float kept[4] = {0.f, 0.f, 0.f, 0.f};   // WPG > 1: the right side's sums of the last unit that this wave lands
+    int kept_f = -1;                        // their first feature (-1: none yet)
 
     for (int u0 = 0; u0 < nunit_real; u0 += NPF) {
 #pragma unroll
@@ -626,11 +640,18 @@ __global__ __launch_bounds__(128) void k_tiled_dphi(const bf16_t* __restrict__ X
             Tile64<VP>& cur = stt;
             __syncthreads();
             PA_UNIT_STORE(cur, pre[j])
+            if constexpr (WPG > 1) {
+                if (kept_f >= 0) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) dx_add(dxcol, kept_f + i, kept[i] + handed[w ^ 1][i][lane]);
+                }
+            }
             __syncthreads();
             UnitJacobian<P, DT> jac;
             jac.begin(xrow, tab, u);
 #pragma unroll
-            for (int nb = 0; nb < 4; ++nb) {
+            for (int k = 0; k < NBW; ++k) {
+                const int nb = part_w * NBW + k;
                 Frag sf[NK];
 #pragma unroll
                 for (int ks = 0; ks < NK; ++ks) sf[ks].u = *(const uint4*)&cur.r[16 * nb + r16][32 * ks + 8 * g];
@@ -653,15 +674,34 @@ __global__ __launch_bounds__(128) void k_tiled_dphi(const bf16_t* __restrict__ X
                 wave_sync();
                 jac.block(xrow, tab, u, nb, A, dxcol);
             }
-            jac.finish(xrow, dxcol);
+            if constexpr (WPG > 1) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    kept[i] = part_w ? jac.dR[4 + i] : jac.dR[i];
+                    handed[w][i][lane] = part_w ? jac.dR[i] : jac.dR[4 + i];
+                }
+                kept_f = DT * jac.td.t[1] + 4 * part_w;
+            } else {
+                jac.finish(xrow, dxcol);
+            }
         }
     }
-    wave_sync();
-    float* out = part + (head + tok0 + 64 * w + lane) * HD;
+    if constexpr (WPG > 1) {
+        __syncthreads();
+        if (kept_f >= 0) {
 #pragma unroll
-    for (int f4 = 0; f4 < HD / 4; ++f4)
-        *(float4*)(out + 4 * f4) = make_float4(oscale * dxs[w][4 * f4][lane], oscale * dxs[w][4 * f4 + 1][lane],
-                                               oscale * dxs[w][4 * f4 + 2][lane], oscale * dxs[w][4 * f4 + 3][lane]);
+            for (int i = 0; i < 4; ++i) dx_add(dxcol, kept_f + i, kept[i] + handed[w ^ 1][i][lane]);
+        }
+        __syncthreads();
+    } else {
+        wave_sync();
+    }
+    float* out = part + (head + tok0 + 64 * grp + lane) * HD + part_w * (HD / WPG);
+    const float* mine = &dxs[grp][part_w * (HD / WPG)][lane];
+#pragma unroll
+    for (int f4 = 0; f4 < HD / WPG / 4; ++f4)
+        *(float4*)(out + 4 * f4) = make_float4(oscale * mine[64 * (4 * f4)], oscale * mine[64 * (4 * f4 + 1)],
+                                               oscale * mine[64 * (4 * f4 + 2)], oscale * mine[64 * (4 * f4 + 3)]);
 }
 #undef PA_UNIT_LOAD
 #undef PA_UNIT_STORE
@@ -689,7 +729,7 @@ template <int P, int DT, int HD>
 bool dphi_t(const char* name, hipStream_t s, const TiledPlan& pl, const bf16_t* X, const bf16_t* Yp, const TileDesc* tab,
             const bf16_t* st, float* part, int BH, int T, int cs, float xscale, float outscale) {
     LaunchScope ls(name, s);
-    hipLaunchKernelGGL((k_tiled_dphi<P, DT, HD>), dim3(T / 128, BH), dim3(128), 0, s, X, Yp, tab, st, part, T, cs, pl.nunit,
+    hipLaunchKernelGGL((k_tiled_dphi<P, DT, HD>), dim3(T / 128, BH), dim3(128 * dphi_waves_per_group<HD>()), 0, s, X, Yp, tab, st, part, T, cs, pl.nunit,
                        pl.nunit_real, outscale * powf(xscale, (float)(P - 1)));   // J_phi(s x) = s^(p-1) J_phi(x)
     return launch_ok();
 }
