@@ -356,24 +356,36 @@ __global__ __launch_bounds__(256) void k_tiled_pack(const bf16_t* __restrict__ Y
 }
 
 // ---- update-state and cumulative sum ----------------------------------------------------------------------
-// One workgroup walks a group of four units (256 state rows) of one head over the whole sequence; wave w owns
-// unit 4 group + w as float32 accumulators, transposed (value column x state row, so that a lane ends up
+// One workgroup walks a group of four units (256 state rows; eight at d = 128) of one head over the whole sequence;
+// wave w owns unit w of the group as float32 accumulators, transposed (value column x state row, so that a lane ends up
 // with VP / 4 consecutive value columns of one state row).  Before the tokens of chunk c are added, the
 // running sum - the state entering chunk c - is stored (REV: the walk runs from the last chunk down and the
 // stored sum is the state gradient of the chunks after c).  X: the rows phi is formed from (K; REV: Q, times
 // oscale, which goes onto the stored state), Yp: the extended value rows ([V, 1]; REV: [ghat, gz]).
+template <int HD>
+constexpr int scan_units() { return HD >= 128 ? 8 : 4; }   // units (waves) per workgroup: each re-reads the head's token rows
+
 template <int P, int DT, int HD, bool REV>
-__global__ __launch_bounds__(256, 2) void k_tiled_scan(const bf16_t* __restrict__ X, const bf16_t* __restrict__ Yp,
+__global__ __launch_bounds__(64 * scan_units<HD>(), 2) void k_tiled_scan(const bf16_t* __restrict__ X, const bf16_t* __restrict__ Yp,
                                                     const TileDesc* __restrict__ tab, bf16_t* __restrict__ st, int T, int cs,
                                                     int nunit, float oscale) {
     using E = Emb<P, DT>;
-    constexpr int VP = HD + 16, NVB = VP / 16, SP = HD + 4;
+    constexpr int UPW = scan_units<HD>(), NT = 64 * UPW, VP = HD + 16, NVB = VP / 16, SP = HD + 4;
     typedef XStore<HD> XS;
     __shared__ __attribute__((aligned(16))) typename XS::elem xs[64][XS::PITCH];
     __shared__ __attribute__((aligned(16))) Tile64<VP> yt;
-    __shared__ __attribute__((aligned(16))) Tile64<64> phis[4];
+    __shared__ __attribute__((aligned(16))) Tile64<64> phis[UPW];
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6), r16 = lane & 15, g = lane >> 4;
-    const int unit = blockIdx.x * 4 + w, bh = blockIdx.y, nchunk = T / cs;
+    // Every workgroup of a head streams that head's token rows.  Workgroups are dealt to the 8 XCDs round-robin
+    // by their linear id; with a multiple of 8 heads the ids are re-read so that a head's workgroups all sit on one
+    // XCD and its rows come out of that XCD's L2 (otherwise each L2 fetches every head, and falls behind).
+    int ugrp = blockIdx.x, bh = blockIdx.y;
+    if (gridDim.y % 8 == 0) {
+        const int lin = blockIdx.x + gridDim.x * blockIdx.y, slot = lin / 8;
+        bh = (slot / gridDim.x) * 8 + lin % 8;
+        ugrp = slot % gridDim.x;
+    }
+    const int unit = ugrp * UPW + w, nchunk = T / cs;
     const size_t head = (size_t)bh * T;
 
     float mult[4];
@@ -386,7 +398,7 @@ __global__ __launch_bounds__(256, 2) void k_tiled_scan(const bf16_t* __restrict_
         for (int nb = 0; nb < 4; ++nb) acc[vb][nb] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
     // the token rows of a step wait in registers while the step before them is being worked on
-    constexpr int XP = (64 * (HD / 8) + 255) / 256, YP = (64 * (VP / 8) + 255) / 256;
+    constexpr int XP = (64 * (HD / 8) + NT - 1) / NT, YP = (64 * (VP / 8) + NT - 1) / NT;
     u32x4 xr[XP], yr[YP];   // (a true vector type: copies of HIP's uint4 struct become memcpy calls that keep the array in scratch)
     const int spc = cs / 64, nstep = (nchunk - 1) * spc;    // the last chunk walked is never added
 #define PA_STEP_FETCH(SL)                                                                                        \
@@ -394,37 +406,59 @@ __global__ __launch_bounds__(256, 2) void k_tiled_scan(const bf16_t* __restrict_
         const int ci_ = (SL) / spc, c_ = REV ? nchunk - 1 - ci_ : ci_;                                           \
         const size_t tok0_ = head + (size_t)c_ * cs + 64 * ((SL) % spc);                                         \
         _Pragma("unroll") for (int q_ = 0; q_ < XP; ++q_) {                                                      \
-            const int id_ = min(tid + 256 * q_, 64 * (HD / 8) - 1);                                              \
+            const int id_ = min(tid + NT * q_, 64 * (HD / 8) - 1);                                              \
             xr[q_] = *(const u32x4*)(X + tok0_ * HD + (size_t)id_ * 8);                                          \
         }                                                                                                        \
         _Pragma("unroll") for (int q_ = 0; q_ < YP; ++q_) {                                                      \
-            const int id_ = min(tid + 256 * q_, 64 * (VP / 8) - 1);                                              \
+            const int id_ = min(tid + NT * q_, 64 * (VP / 8) - 1);                                              \
             yr[q_] = *(const u32x4*)(Yp + tok0_ * VP + (size_t)id_ * 8);                                         \
         }                                                                                                        \
     }
     PA_STEP_FETCH(0)   // (a sequence of one chunk never gets here: the launchers ask for at least two)
     for (int sl = 0; sl <= nstep; ++sl) {
         if (sl % spc == 0) {
-            // the running sum is the state entering this chunk (REV: the state gradient of the chunks after it)
+            // the running sum is the state entering this chunk (REV: the state gradient of the chunks after it).
+            // A lane holds 8-byte runs of 16 different rows; written as they are, every store instruction would
+            // touch 64 cache lines in part.  The unit's 64 x SP block is contiguous in memory, so it goes through
+            // the wave's phi tile (free between two steps) and leaves as whole 16-byte pieces, 1 KB per instruction.
             const int ci = sl / spc, c = REV ? nchunk - 1 - ci : ci;
             bf16_t* dst = st + (((size_t)bh * nchunk + c) * nunit + unit) * 64 * SP;
+            constexpr int PASSES = 64 * SP * 2 > (int)sizeof(Tile64<64>) ? 2 : 1, NBP = 4 / PASSES;   // blocks of 16 rows per pass
+            constexpr int PIECES = NBP * 16 * SP / 8;                                                  // of 16 bytes
+            static_assert(NBP * 16 * SP * 2 <= (int)sizeof(Tile64<64>) && (NBP * 16 * SP) % 8 == 0, "a pass fits the phi tile");
+            bf16_t* stage = (bf16_t*)&phis[w];
 #pragma unroll
-            for (int nb = 0; nb < 4; ++nb)
+            for (int ps = 0; ps < PASSES; ++ps) {
 #pragma unroll
-                for (int vb = 0; vb < NVB; ++vb) {
-                    bf16x4 o;
+                for (int nl = 0; nl < NBP; ++nl) {
+                    const int nb = ps * NBP + nl;
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) o[r] = (__bf16)(acc[vb][nb][r] * mult[nb]);
-                    const int col = g * (VP / 4) + 4 * vb;
-                    if (col < SP) *(bf16x4*)(dst + (size_t)(16 * nb + r16) * SP + col) = o;
+                    for (int vb = 0; vb < NVB; ++vb) {
+                        bf16x4 o;
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) o[r] = (__bf16)(acc[vb][nb][r] * mult[nb]);
+                        const int col = g * (VP / 4) + 4 * vb;
+                        if (col < SP) *(bf16x4*)(stage + (16 * nl + r16) * SP + col) = o;
+                    }
                 }
+                wave_sync();
+#pragma unroll
+                for (int k = 0; k < (PIECES + 63) / 64; ++k) {
+                    const int idx = lane + 64 * k;
+                    // (streaming stores: a state is not read again by this kernel, and left to age in L2 like other
+                    // lines it pushes out the token rows that the head's other workgroups are about to ask for)
+                    if (idx < PIECES)
+                        __builtin_nontemporal_store(*(const u32x4*)(stage + 8 * idx), (u32x4*)(dst + (size_t)ps * (NBP * 16 * SP) + 8 * idx));
+                }
+                wave_sync();
+            }
         }
         if (sl == nstep) break;
         __syncthreads();
         // (threads past the last piece repeat it: same data to the same place)
 #pragma unroll
         for (int q = 0; q < XP; ++q) {
-            const int id = min(tid + 256 * q, 64 * (HD / 8) - 1);
+            const int id = min(tid + NT * q, 64 * (HD / 8) - 1);
             const u32x4 u = xr[q];
             if constexpr (XS::BF) {
                 uint32_t* dst = (uint32_t*)&xs[id / (HD / 8)][8 * (id % (HD / 8))];
@@ -439,7 +473,7 @@ __global__ __launch_bounds__(256, 2) void k_tiled_scan(const bf16_t* __restrict_
         }
 #pragma unroll
         for (int q = 0; q < YP; ++q) {
-            const int id = min(tid + 256 * q, 64 * (VP / 8) - 1);
+            const int id = min(tid + NT * q, 64 * (VP / 8) - 1);
             *(u32x4*)&yt.r[id / (VP / 8)][8 * (id % (VP / 8))] = yr[q];
         }
         __syncthreads();
@@ -711,10 +745,11 @@ template <int P, int DT, int HD>
 bool scan_t(const char* name, hipStream_t s, const TiledPlan& pl, bool rev, const bf16_t* X, const bf16_t* Yp, const TileDesc* tab,
             bf16_t* st, int BH, int T, int cs, float xscale) {
     LaunchScope ls(name, s);
-    const dim3 grid(pl.nunit / 4, BH);
+    constexpr int UPW = scan_units<HD>();
+    const dim3 grid(pl.nunit / UPW, BH);
     const float oscale = powf(xscale, (float)P);   // phi(s x) = s^p phi(x)
-    if (rev) hipLaunchKernelGGL((k_tiled_scan<P, DT, HD, true>), grid, dim3(256), 0, s, X, Yp, tab, st, T, cs, pl.nunit, oscale);
-    else hipLaunchKernelGGL((k_tiled_scan<P, DT, HD, false>), grid, dim3(256), 0, s, X, Yp, tab, st, T, cs, pl.nunit, oscale);
+    if (rev) hipLaunchKernelGGL((k_tiled_scan<P, DT, HD, true>), grid, dim3(64 * UPW), 0, s, X, Yp, tab, st, T, cs, pl.nunit, oscale);
+    else hipLaunchKernelGGL((k_tiled_scan<P, DT, HD, false>), grid, dim3(64 * UPW), 0, s, X, Yp, tab, st, T, cs, pl.nunit, oscale);
     return launch_ok();
 }
 template <int P, int DT, int HD>
@@ -768,7 +803,8 @@ TiledPlan tiled_plan(int p, int d, int dt) {
     for (int i = 0; i < p; ++i) rows *= dt;
     pl.rows_per_tile = rows;
     pl.nunit_real = rows >= 64 ? pl.ntile * (rows / 64) : (pl.ntile + 64 / rows - 1) / (64 / rows);
-    pl.nunit = (pl.nunit_real + 3) / 4 * 4;
+    const int upw = d >= 128 ? 8 : 4;   // units per workgroup of the scan
+    pl.nunit = (pl.nunit_real + upw - 1) / upw * upw;
     pl.nentry = rows >= 64 ? (pl.nunit + rows / 64 - 1) / (rows / 64) : pl.nunit * (64 / rows);
     pl.state_elems = (size_t)pl.nunit * 64 * (d + 4);   // rows are stored without their zero columns
     return pl;
