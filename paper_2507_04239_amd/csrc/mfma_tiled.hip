@@ -24,8 +24,8 @@
 // carries the normaliser (the values are extended by a one, App. E.4's l), the remaining 15 are zero.  In
 // memory a row keeps only its first SP = d + 4 columns (the kernels are bound by the bytes of the states); the
 // columns beyond live in LDS only, as zeros.
-// MFMA: v_mfma_f32_16x16x32_bf16, and v_mfma_f32_16x16x16_bf16 for the 16 columns beyond d where the
-// contraction runs over the value columns.  Operand layouts as in mfma_common.hpp.
+// MFMA: v_mfma_f32_16x16x32_bf16 throughout; where the contraction runs over the value columns, the 16 columns
+// beyond d fill half of a k = 32 step, the other half is zero.  Operand layouts as in mfma_common.hpp.
 #include <cmath>
 #include <type_traits>
 
@@ -75,16 +75,16 @@ __device__ __forceinline__ bf16x8 col_frag(const Tile64<W>& t, int s, int cb, in
     return col_frag_at<W>(t, s, 16 * cb + 4 * (r16 & 3), r16, g);
 }
 
-typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+// A contraction over 16 columns, lane (r16, g) holding columns 4g .. 4g + 3 of its row: a k = 32 step whose slots
+// 8g + 4 .. 8g + 7 are zero on both sides.  (Not v_mfma_f32_16x16x16_bf16: chained behind 16x16x32 steps with its
+// result in other registers than its addend it read that addend too early - wrong values in 16 lanes, run to
+// run, that wait states between the two kinds made go away.)
 __device__ __forceinline__ f32x4 mfma16k16(uint2 a, uint2 b, f32x4 c) {
-    union {
-        uint2 u;
-        s16x4 v;
-    } fa, fb;
-    fa.u = a;
-    fb.u = b;
-    return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(fa.v, fb.v, c, 0, 0, 0);
+    Frag fa, fb;
+    fa.u = make_uint4(a.x, a.y, 0u, 0u);
+    fb.u = make_uint4(b.x, b.y, 0u, 0u);
+    return mfma16(fa.v, fb.v, c);
 }
 
 // LDS traffic of one wave is ordered; this keeps the compiler from moving accesses across the hand-over
@@ -517,7 +517,7 @@ __device__ __forceinline__ int token_block(int bx, int nblk, int m) {
 }
 
 template <int HD>
-constexpr int units_in_flight() { return HD >= 128 ? 2 : 4; }   // per workgroup, in registers
+constexpr int units_in_flight() { return 4; }   // per workgroup, in registers
 
 // unit u (64 rows x SP bf16, contiguous) of the state at sbase -> registers; PPT pieces of 8 bytes per thread
 // (loads are unconditional, on clamped indices: an array that is assigned under a condition is kept in scratch
@@ -538,7 +538,7 @@ constexpr int units_in_flight() { return HD >= 128 ? 2 : 4; }   // per workgroup
         *(u32x2*)&DST.r[id_ / ((VP - SP) / 4)][SP + 4 * (id_ % ((VP - SP) / 4))] = (u32x2){0u, 0u};
 
 template <int P, int DT, int HD>
-__global__ __launch_bounds__(128) void k_tiled_readout(const bf16_t* __restrict__ X, const TileDesc* __restrict__ tab,
+__global__ __launch_bounds__(128, HD >= 128 ? 1 : 2) void k_tiled_readout(const bf16_t* __restrict__ X, const TileDesc* __restrict__ tab,
                                                        const bf16_t* __restrict__ st, float* __restrict__ part,
                                                        float* __restrict__ zpart, int T, int cs, int nunit, int nunit_real,
                                                        float oscale) {
@@ -630,7 +630,7 @@ __global__ __launch_bounds__(128 * dphi_waves_per_group<HD>()) void k_tiled_dphi
     float* __restrict__ part, int T, int cs, int nunit, int nunit_real, float oscale) {
     constexpr int WPG = dphi_waves_per_group<HD>(), NT = 128 * WPG, NBW = 4 / WPG;
     constexpr int VP = HD + 16, NK = HD / 32, SP = HD + 4, PIECES = 64 * (SP / 4), PPT = (PIECES + NT - 1) / NT, AP = 16 + 4;
-    constexpr int NPF = units_in_flight<HD>();
+    constexpr int NPF = HD >= 128 ? 2 : units_in_flight<HD>();   // (measured: four in flight are no faster here)
     typedef XStore<HD> XS;
     __shared__ __attribute__((aligned(16))) typename XS::elem xs[128][XS::PITCH];
     __shared__ __attribute__((aligned(16))) Tile64<VP> stt;   // one slot (LDS decides how many workgroups share a CU): two barriers per unit
@@ -690,13 +690,14 @@ __global__ __launch_bounds__(128 * dphi_waves_per_group<HD>()) void k_tiled_dphi
 #pragma unroll
                 for (int ks = 0; ks < NK; ++ks) sf[ks].u = *(const uint4*)&cur.r[16 * nb + r16][32 * ks + 8 * g];
                 const uint2 stail = *(const uint2*)&cur.r[16 * nb + r16][HD + 4 * g];
+                f32x4 c[4];   // rows 16 nb + 4g + r, token 16 ib + r16
 #pragma unroll
                 for (int ib = 0; ib < 4; ++ib) {
-                    f32x4 c = {0.f, 0.f, 0.f, 0.f};   // rows 16 nb + 4g + r, token 16 ib + r16
+                    c[ib] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                    for (int ks = 0; ks < NK; ++ks) c = mfma16(sf[ks].v, yf[ib][ks].v, c);
-                    c = mfma16k16(stail, ytail[ib], c);
-                    *(float4*)&dph[w][16 * ib + r16][4 * g] = make_float4(c[0], c[1], c[2], c[3]);
+                    for (int ks = 0; ks < NK; ++ks) c[ib] = mfma16(sf[ks].v, yf[ib][ks].v, c[ib]);
+                    c[ib] = mfma16k16(stail, ytail[ib], c[ib]);
+                    *(float4*)&dph[w][16 * ib + r16][4 * g] = make_float4(c[ib][0], c[ib][1], c[ib][2], c[ib][3]);
                 }
                 wave_sync();
                 float A[16];
