@@ -131,7 +131,7 @@ __device__ __forceinline__ void ring_issue(ChunkSmem<RING_TILES>& sm, int slot, 
         const int instr = (8 / NW) * wr + q;
         const int unit = instr * 64 + (SWIZZLE ? (lane ^ ((instr & 1) << 2)) : lane);
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + unit * 8),
-                                         (__attribute__((address_space(3))) void*)&sm.ring[slot][instr * 64], 16, 0, 0);
+                                         (__attribute__((address_space(3))) void*)&sm.ring[slot][instr * 64], 16, 0, 2);   // (aux 2: streaming, each state byte is read once)
     }
 }
 

@@ -180,7 +180,7 @@ template <bool GAMMA>
 __device__ __forceinline__ void store_run(const StateOut& so, int k) {
     // state tile [a][v][b]: run k = (row block k >> 1 = a, column-block pair k & 1); Gamma: column block k
     const int off = GAMMA ? 16 * DH * k : (k >> 1) * (DH * 8) + (k & 1) * (32 * 8);
-    *(uint4*)(so.dst + off) = so.run[k];
+    __builtin_nontemporal_store((u32x4){so.run[k].x, so.run[k].y, so.run[k].z, so.run[k].w}, (u32x4*)(so.dst + off));
 }
 
 // PACED: one run of `so` is stored after each k-step.  A CU drains stores slowly (about 10 bytes
