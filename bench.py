@@ -249,6 +249,9 @@ def main():
     ap.add_argument("--forward-only", action="store_true", help="time the forward pass alone")
     ap.add_argument("--all-configs", action="store_true",
                     help="run the five benchmark configurations as stated, one JSON line each")
+    ap.add_argument("--sweep", action="store_true",
+                    help="time the workload at every chunk size (128 ... 1024, and the whole sequence) and tile width "
+                         "the library takes for it, plus its own choice (chunk 0); one JSON line with the table")
     ap.add_argument("--decode-batch", type=int, default=0,
                     help="instead of the training step: time the single-token decode step of the workload's head shape "
                          "on this many sequences (state resident in HBM)")
@@ -261,6 +264,8 @@ def main():
     if args.decode_batch > 0:
         name = args.workload or inputs.HEADLINE
         return decode_bench(args, name, dict(inputs.WORKLOADS[name]))
+    if args.sweep:
+        return sweep(args, args.workload or inputs.HEADLINE)
     if args.all_configs:
         # every benchmark configuration as stated, one JSON line each (the headline one carries the CPU baseline)
         for name in sorted(inputs.WORKLOADS, key=lambda n: inputs.WORKLOADS[n]["position"]):
@@ -269,6 +274,41 @@ def main():
         return
     name = args.workload or inputs.HEADLINE
     print(json.dumps(run_workload(args, name, cpu=not args.no_cpu_baseline)), flush=True)
+
+
+def sweep(args, name):
+    """Chunk size x tile width (Sec. 4.1.1, Fig. 6(c)'s study): every combination the library takes for the workload,
+    the attention form (one chunk) and the library's own choice, HIP-event median per step."""
+    import copy
+    from paper_2507_04239_amd import binding, inputs
+    w = inputs.WORKLOADS[name]
+    with_bwd = bool(w.get("backward", True)) and not args.forward_only
+    rows, seen = [], set()
+    sizes = (32, 64, 128, 256, 512, 1024) if w["dtype"] == "f32" else (128, 256, 512, 1024)   # (bf16 below 128: vector ALUs only)
+    chunks = [c for c in sizes if w["T"] % c == 0 and c < w["T"]] + [w["T"], 0]
+    for chunk in chunks:
+        for dt in (0, 2, 4, 8, 16):
+            prob = binding.make_problem(w["B"], w["H"], w["T"], w["d"], w["d"], w["p"], chunk, True, 1.0, w["dtype"], args.impl,
+                                        not args.recompute_states, args.gated, dt)
+            if not binding.power_attn_supported(prob, with_bwd):
+                continue
+            key = (binding.power_attn_resolved_chunk(prob), dt, binding.power_attn_state_rows(prob)) if chunk else ("auto", dt)
+            if key in seen or (chunk == 0 and dt) or (dt == {2: 8, 3: 4, 4: 2}.get(w["p"]) and (chunk, "tiled") in seen):
+                continue   # (the tile width named is the one the tiled kernels just ran with by default)
+            seen.add(key)
+            a = copy.copy(args)
+            a.chunk, a.d_tile, a.serial_kernels = chunk, dt, False
+            out = run_workload(a, name, cpu=False)
+            rows.append({"chunk_requested": chunk, "chunk": out["config"]["chunk"], "d_tile": dt,
+                         "state_rows": out["config"]["state_rows"], "step_ms_median": out["timing"]["step_ms_median"],
+                         "fwd_ms_median": out["timing"]["fwd_ms_median"], "kernels": sorted(out["kernels"])})
+            if dt == 0 and any(k.startswith("tiled") for k in out["kernels"]):
+                seen.add((chunk, "tiled"))
+            print(f"# chunk {chunk} d_tile {dt}: {rows[-1]['step_ms_median']:.3f} ms", file=sys.stderr, flush=True)
+    best = min((r for r in rows if r["chunk_requested"]), key=lambda r: r["step_ms_median"])
+    print(json.dumps({"metric": "power-attention step time over chunk size and tile width", "unit": "ms", "workload": name,
+                      "pass": "fwd+bwd" if with_bwd else "fwd", "impl": args.impl, "steps": args.steps, "warmup": args.warmup,
+                      "best": {k: best[k] for k in ("chunk", "d_tile", "step_ms_median")}, "sweep": rows}), flush=True)
 
 
 def event_times(step, steps):

@@ -87,9 +87,10 @@ int auto_chunk(const pa_problem& pr) {
     // the chunked kernels, on the sequence rounded up to whole chunks when it is ragged (see Padding)
     probe.chunk = pr.T % 256 == 0 || pr.T % 128 != 0 ? 256 : 128;
     probe.T = (pr.T + probe.chunk - 1) / probe.chunk * probe.chunk;
-    // (d = 128 has chunked matrix-core kernels too, the resident-state ones; measured at B8 H16 T32768 they take
-    // 231 ms a step against 166 ms for the attention form, so the choice there stays with the attention form)
-    if (may_mfma && pr.d == 64 && mfma_supported(probe, true) == PA_OK && !(attn && pr.T <= (pr.gated ? 2048 : 4096)))
+    // d = 128 (p = 2, the tiled kernels): measured at B8 H16 T32768, 118 ms a step chunked against 166 ms for the
+    // attention form, whose time grows with the square of T: the two meet near 23k tokens
+    const int attn_upto = pr.d == 64 ? (pr.gated ? 2048 : 4096) : 24575;
+    if (may_mfma && (pr.d == 64 || (pr.d == 128 && pr.p == 2)) && mfma_supported(probe, true) == PA_OK && !(attn && pr.T <= attn_upto))
         return probe.chunk;
     if (attn) return pr.T;
     double D = 1.0;   // C(d + p - 1, p)

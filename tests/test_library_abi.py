@@ -82,8 +82,11 @@ def test_automatic_chunk_choice():
     assert rc(mk(4, 12, 4096, 64, 64, 2, 0, gated=True)) == 256
     assert rc(mk(4, 12, 2048, 64, 64, 2, 0, gated=True)) == 2048
     assert rc(mk(4, 12, 512, 64, 64, 2, 0)) == 512
-    # d = 128: matrix-core kernels exist for the attention form only
-    assert rc(mk(8, 16, 32768, 128, 128, 2, 0)) == 32768
+    # d = 128, p = 2: the tiled chunked kernels from about 24k tokens on (not gated: they take no gates)
+    assert rc(mk(8, 16, 32768, 128, 128, 2, 0)) == 256
+    assert rc(mk(8, 16, 16384, 128, 128, 2, 0)) == 16384
+    assert rc(mk(8, 16, 32768, 128, 128, 2, 0, gated=True)) == 32768
+    assert rc(mk(8, 16, 32768, 128, 128, 4, 0)) == 32768
     # p = 4, d = 32: the state is 52360 x 33 per head, the attention form stays cheaper far beyond 16k tokens
     assert rc(mk(2, 8, 16384, 32, 32, 4, 0, dtype="bf16")) == 16384
     # float32, small head: state 136 x 17; chunked from a few hundred tokens on
