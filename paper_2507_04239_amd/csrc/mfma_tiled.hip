@@ -288,10 +288,11 @@ __device__ __forceinline__ void stage_x(typename XStore<HD>::elem (*xs)[XStore<H
     }
 }
 
-// phi[64] -> one row of a [token][row] tile, rounded to bf16
+// phi[64] (its 8-row pieces I0 .. I1 - 1) -> one row of a [token][row] tile, rounded to bf16
+template <int I0 = 0, int I1 = 8>
 __device__ __forceinline__ void put_phi(Tile64<64>& t, int token, const float (&phi)[64]) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = I0; i < I1; ++i) {
         Frag f;
 #pragma unroll
         for (int j = 0; j < 8; ++j) f.v[j] = (__bf16)phi[8 * i + j];
@@ -537,19 +538,27 @@ constexpr int units_in_flight() { return 4; }   // per workgroup, in registers
     for (int id_ = tid; id_ < 64 * ((VP - SP) / 4); id_ += NT)                                                  \
         *(u32x2*)&DST.r[id_ / ((VP - SP) / 4)][SP + 4 * (id_ % ((VP - SP) / 4))] = (u32x2){0u, 0u};
 
+// At d = 128 two waves share a group of 64 tokens (LDS leaves room for two workgroups per CU, and two waves each
+// would leave every SIMD with a single wave, nothing to run under its MFMAs): each forms half of the rows of
+// phi and takes half of the value columns' accumulators.
+template <int HD>
+constexpr int readout_waves_per_group() { return HD >= 128 ? 2 : 1; }
+
 template <int P, int DT, int HD>
-__global__ __launch_bounds__(128, HD >= 128 ? 1 : 2) void k_tiled_readout(const bf16_t* __restrict__ X, const TileDesc* __restrict__ tab,
-                                                       const bf16_t* __restrict__ st, float* __restrict__ part,
-                                                       float* __restrict__ zpart, int T, int cs, int nunit, int nunit_real,
-                                                       float oscale) {
-    constexpr int NT = 128, VP = HD + 16, NVB = VP / 16, SP = HD + 4, PIECES = 64 * (SP / 4), PPT = (PIECES + NT - 1) / NT;
+__global__ __launch_bounds__(128 * readout_waves_per_group<HD>(), 2) void k_tiled_readout(
+    const bf16_t* __restrict__ X, const TileDesc* __restrict__ tab, const bf16_t* __restrict__ st, float* __restrict__ part,
+    float* __restrict__ zpart, int T, int cs, int nunit, int nunit_real, float oscale) {
+    constexpr int WPG = readout_waves_per_group<HD>(), NT = 128 * WPG;
+    constexpr int VP = HD + 16, NVB = VP / 16, NVW = (NVB + WPG - 1) / WPG, SP = HD + 4, PIECES = 64 * (SP / 4), PPT = (PIECES + NT - 1) / NT;
     constexpr int NPF = units_in_flight<HD>();
     typedef XStore<HD> XS;
     __shared__ __attribute__((aligned(16))) typename XS::elem xs[128][XS::PITCH];
     constexpr int SLOTS = HD >= 128 ? 1 : 2;   // LDS decides how many workgroups share a CU: one slot costs a second barrier per unit
+    static_assert(WPG == 1 || SLOTS == 1, "waves that share phi meet at the second barrier of a unit");
     __shared__ __attribute__((aligned(16))) Tile64<VP> stt[SLOTS];
     __shared__ __attribute__((aligned(16))) Tile64<64> phis[2];
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6), r16 = lane & 15, g = lane >> 4;
+    const int grp = w / WPG, part_w = w % WPG, vb0 = part_w * NVW;   // token group; first block of value columns of this wave
     const int bh = blockIdx.y, tok0 = token_block(blockIdx.x, gridDim.x, cs / 128) * 128, nchunk = T / cs, chunk = tok0 / cs;
     const size_t head = (size_t)bh * T;
     const bf16_t* sbase = st + ((size_t)bh * nchunk + chunk) * nunit * 64 * SP;
@@ -559,10 +568,10 @@ __global__ __launch_bounds__(128, HD >= 128 ? 1 : 2) void k_tiled_readout(const 
     for (int j = 0; j < NPF - 1; ++j) PA_UNIT_LOAD(pre[j], j)
     PA_UNIT_ZERO_PAD(stt[0])
     if (SLOTS > 1) PA_UNIT_ZERO_PAD(stt[SLOTS - 1])
-    stage_x<HD, 128>(xs, X + (head + tok0) * HD, 128, tid);
-    f32x4 acc[NVB][4];
+    stage_x<HD, NT>(xs, X + (head + tok0) * HD, 128, tid);
+    f32x4 acc[NVW][4];
 #pragma unroll
-    for (int vb = 0; vb < NVB; ++vb)
+    for (int vb = 0; vb < NVW; ++vb)
 #pragma unroll
         for (int ib = 0; ib < 4; ++ib) acc[vb][ib] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
@@ -575,39 +584,56 @@ __global__ __launch_bounds__(128, HD >= 128 ? 1 : 2) void k_tiled_readout(const 
             Tile64<VP>& cur = stt[j & (SLOTS - 1)];
             if (SLOTS == 1) __syncthreads();
             PA_UNIT_STORE(cur, pre[j])
-            __syncthreads();
-            {
+            if constexpr (WPG == 1) {
+                __syncthreads();
                 float phi[64];
-                unit_phi<P, DT>(typename XS::row{&xs[64 * w + lane][0]}, tab, u, phi);
-                put_phi(phis[w], lane, phi);
+                unit_phi<P, DT>(typename XS::row{&xs[64 * grp + lane][0]}, tab, u, phi);
+                put_phi(phis[grp], lane, phi);
+                wave_sync();
+            } else {
+                // (each branch uses half of phi; what it does not store is never computed)
+                if (part_w == 0) {
+                    float phi[64];
+                    unit_phi<P, DT>(typename XS::row{&xs[64 * grp + lane][0]}, tab, u, phi);
+                    put_phi<0, 4>(phis[grp], lane, phi);
+                } else {
+                    float phi[64];
+                    unit_phi<P, DT>(typename XS::row{&xs[64 * grp + lane][0]}, tab, u, phi);
+                    put_phi<4, 8>(phis[grp], lane, phi);
+                }
+                __syncthreads();
             }
-            wave_sync();
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
                 Frag qf[4];
 #pragma unroll
                 for (int ib = 0; ib < 4; ++ib) {
-                    qf[ib].h[0] = *(const uint2*)&phis[w].r[16 * ib + r16][32 * s + 4 * g];
-                    qf[ib].h[1] = *(const uint2*)&phis[w].r[16 * ib + r16][32 * s + 16 + 4 * g];
+                    qf[ib].h[0] = *(const uint2*)&phis[grp].r[16 * ib + r16][32 * s + 4 * g];
+                    qf[ib].h[1] = *(const uint2*)&phis[grp].r[16 * ib + r16][32 * s + 16 + 4 * g];
                 }
 #pragma unroll
-                for (int vb = 0; vb < NVB; ++vb) {
-                    const bf16x8 sf = col_frag<VP>(cur, s, vb, r16, g);
+                for (int vb = 0; vb < NVW; ++vb) {
+                    if (WPG > 1 && vb0 + vb >= NVB) continue;   // (uniform: the last wave of a group has a block less)
+                    const bf16x8 sf = col_frag<VP>(cur, s, vb0 + vb, r16, g);
 #pragma unroll
                     for (int ib = 0; ib < 4; ++ib) acc[vb][ib] = mfma16(sf, qf[ib].v, acc[vb][ib]);
                 }
             }
-            wave_sync();
+            if constexpr (WPG == 1) wave_sync();
         }
     }
 #pragma unroll
     for (int ib = 0; ib < 4; ++ib) {
-        const size_t row = head + tok0 + 64 * w + 16 * ib + r16;
+        const size_t row = head + tok0 + 64 * grp + 16 * ib + r16;
 #pragma unroll
-        for (int vb = 0; vb < HD / 16; ++vb)
-            *(float4*)(part + row * HD + 16 * vb + 4 * g) = make_float4(oscale * acc[vb][ib][0], oscale * acc[vb][ib][1],
-                                                                        oscale * acc[vb][ib][2], oscale * acc[vb][ib][3]);
-        if (zpart != nullptr && g == 0) zpart[row] = oscale * acc[HD / 16][ib][0];
+        for (int vb = 0; vb < NVW; ++vb) {
+            const int cb = vb0 + vb;   // block of 16 value columns; block HD / 16 holds the normaliser's column
+            if (cb < HD / 16)
+                *(float4*)(part + row * HD + 16 * cb + 4 * g) = make_float4(oscale * acc[vb][ib][0], oscale * acc[vb][ib][1],
+                                                                            oscale * acc[vb][ib][2], oscale * acc[vb][ib][3]);
+            else if (cb == HD / 16 && zpart != nullptr && g == 0)
+                zpart[row] = oscale * acc[vb][ib][0];
+        }
     }
 }
 
@@ -757,7 +783,7 @@ template <int P, int DT, int HD>
 bool readout_t(const char* name, hipStream_t s, const TiledPlan& pl, const bf16_t* X, const TileDesc* tab, const bf16_t* st,
                float* part, float* zpart, int BH, int T, int cs, float xscale) {
     LaunchScope ls(name, s);
-    hipLaunchKernelGGL((k_tiled_readout<P, DT, HD>), dim3(T / 128, BH), dim3(128), 0, s, X, tab, st, part, zpart, T, cs, pl.nunit,
+    hipLaunchKernelGGL((k_tiled_readout<P, DT, HD>), dim3(T / 128, BH), dim3(128 * readout_waves_per_group<HD>()), 0, s, X, tab, st, part, zpart, T, cs, pl.nunit,
                        pl.nunit_real, powf(xscale, (float)P));
     return launch_ok();
 }
