@@ -638,31 +638,53 @@ __global__ __launch_bounds__(128 * readout_waves_per_group<HD>(), 2) void k_tile
 }
 
 // ---- d phi and the Jacobian: part[t][:] = oscale J_phi(x_t)^T (S_chunk(t) y'_t) ----------------------------
-// Same shape as the read-out.  Per block of 16 state rows: A = S y'^T on the matrix cores (contraction over
-// the VP value columns; y' = [ghat, gz] for dQ, [v, 1] for dK, held as operand fragments in registers), laid
-// down in LDS as [token][row], then the Jacobian by a thread that owns the token.
+// A workgroup takes 128 tokens of one chunk.  Per block of 16 state rows: A = S y'^T on the matrix cores
+// (contraction over the VP value columns; y' = [ghat, gz] for dQ, [v, 1] for dK, held as operand fragments in
+// registers), laid down in LDS as [token][row], then the Jacobian by a thread that owns the token.
+// The state's operand fragments are rows of the stored state (lane (r16, g): row r16 of the block, 8 columns
+// from 8g), so every wave loads them straight from memory, NPF units ahead, and no state passes through LDS:
+// the waves of a workgroup read the same bytes (from L2 the second time) and do not wait for each other.
 // At d = 128 (p = 2, d_tile 8) two waves share a group of 64 tokens: the float32 accumulators of 128 tokens
 // (64 KB) leave room for one workgroup per CU, and two waves would keep only two of its four SIMDs busy.  Wave
 // h of a pair takes the unit's rows with left index alpha in [4h, 4h + 4) and lands the sums whose feature
 // index within the tile is in that same range, on either side: the two waves then never touch the same
 // accumulator.  The right side's sums run over all alpha, so each wave passes the half it does not land to its
-// partner through LDS; they are added one unit late, between the two barriers that the next unit needs anyway.
+// partner through LDS (two buffers taken in turn, one barrier per unit) and adds what it receives one unit late.
 template <int HD>
 constexpr int dphi_waves_per_group() { return HD >= 128 ? 2 : 1; }
+
+typedef u32x4 __attribute__((aligned(4))) u32x4_dword_aligned;   // rows of SP = d + 4 columns start on 8 bytes
+
+template <int NBW, int NK>
+struct StateFrags {
+    u32x4 sf[NBW][NK];
+    u32x2 tail[NBW];
+};
+// unit u of the state at sbase, the blocks nb0 .. nb0 + NBW - 1: this lane's operand fragments
+template <int NBW, int NK, int HD>
+__device__ __forceinline__ void load_frags(StateFrags<NBW, NK>& f, const bf16_t* __restrict__ sbase, int u, int nb0, int r16, int g) {
+    constexpr int SP = HD + 4;
+#pragma unroll
+    for (int k = 0; k < NBW; ++k) {
+        const bf16_t* row = sbase + ((size_t)u * 64 + 16 * (nb0 + k) + r16) * SP;
+#pragma unroll
+        for (int ks = 0; ks < NK; ++ks) f.sf[k][ks] = *(const u32x4_dword_aligned*)(row + 32 * ks + 8 * g);
+        f.tail[k] = *(const u32x2*)(row + HD);   // columns d .. d + 3; what lies beyond them in a k-step is zero
+    }
+}
 
 template <int P, int DT, int HD>
 __global__ __launch_bounds__(128 * dphi_waves_per_group<HD>()) void k_tiled_dphi(
     const bf16_t* __restrict__ X, const bf16_t* __restrict__ Yp, const TileDesc* __restrict__ tab, const bf16_t* __restrict__ st,
     float* __restrict__ part, int T, int cs, int nunit, int nunit_real, float oscale) {
     constexpr int WPG = dphi_waves_per_group<HD>(), NT = 128 * WPG, NBW = 4 / WPG;
-    constexpr int VP = HD + 16, NK = HD / 32, SP = HD + 4, PIECES = 64 * (SP / 4), PPT = (PIECES + NT - 1) / NT, AP = 16 + 4;
-    constexpr int NPF = HD >= 128 ? 2 : units_in_flight<HD>();   // (measured: four in flight are no faster here)
+    constexpr int VP = HD + 16, NK = HD / 32, SP = HD + 4, AP = 16 + 4;
+    constexpr int NPF = 3;   // units on their way from memory, per wave
     typedef XStore<HD> XS;
     __shared__ __attribute__((aligned(16))) typename XS::elem xs[128][XS::PITCH];
-    __shared__ __attribute__((aligned(16))) Tile64<VP> stt;   // one slot (LDS decides how many workgroups share a CU): two barriers per unit
     __shared__ __attribute__((aligned(16))) float dph[2 * WPG][64][AP];
     __shared__ float dxs[2][HD][64];
-    __shared__ float handed[WPG > 1 ? 4 : 1][4][64];   // [wave that wrote it][i][token]
+    __shared__ float handed[WPG > 1 ? 2 : 1][WPG > 1 ? 4 : 1][4][64];   // [unit parity][wave that wrote it][i][token]
     static_assert(WPG == 1 || (P == 2 && DT == 8), "the split of a unit between two waves is laid out for one 8 x 8 tile per unit");
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6), r16 = lane & 15, g = lane >> 4;
     const int grp = w / WPG, part_w = w % WPG;   // token group of the wave, and which blocks of a unit it takes
@@ -670,13 +692,12 @@ __global__ __launch_bounds__(128 * dphi_waves_per_group<HD>()) void k_tiled_dphi
     const size_t head = (size_t)bh * T;
     const bf16_t* sbase = st + ((size_t)bh * nchunk + chunk) * nunit * 64 * SP;
 
-    u32x2 pre[NPF][PPT];
+    StateFrags<NBW, NK> fr[NPF];
 #pragma unroll
-    for (int j = 0; j < NPF - 1; ++j) PA_UNIT_LOAD(pre[j], j)
-    PA_UNIT_ZERO_PAD(stt)
+    for (int j = 0; j < NPF - 1; ++j) load_frags<NBW, NK, HD>(fr[j], sbase, min(j, nunit_real - 1), part_w * NBW, r16, g);
     stage_x<HD, NT>(xs, X + (head + tok0) * HD, 128, tid);
 #pragma unroll
-    for (int f = 0; f < HD / WPG; ++f) dxs[grp][part_w * (HD / WPG) + f][lane] = 0.f;   // seen by the other wave after the loop's first barrier
+    for (int f = 0; f < HD / WPG; ++f) dxs[grp][part_w * (HD / WPG) + f][lane] = 0.f;
     Frag yf[4][NK];
     uint2 ytail[4];
 #pragma unroll
@@ -684,46 +705,45 @@ __global__ __launch_bounds__(128 * dphi_waves_per_group<HD>()) void k_tiled_dphi
         const bf16_t* yrow = Yp + (head + tok0 + 64 * grp + 16 * ib + r16) * VP;
 #pragma unroll
         for (int ks = 0; ks < NK; ++ks) yf[ib][ks].u = *(const uint4*)(yrow + 32 * ks + 8 * g);
-        ytail[ib] = *(const uint2*)(yrow + HD + 4 * g);
+        ytail[ib] = *(const uint2*)(yrow + HD);   // pairs with the state's tail: columns d .. d + 3 in the first four k-slots
     }
     const typename XS::row xrow{&xs[64 * grp + lane][0]};
     float* dxcol = &dxs[grp][0][lane];
     float kept[4] = {0.f, 0.f, 0.f, 0.f};   // WPG > 1: the right side's sums of the last unit that this wave lands
     int kept_f = -1;                        // their first feature (-1: none yet)
+    __syncthreads();                        // token rows and cleared accumulators in place
 
     for (int u0 = 0; u0 < nunit_real; u0 += NPF) {
 #pragma unroll
         for (int j = 0; j < NPF; ++j) {
             const int u = u0 + j;
-            PA_UNIT_LOAD(pre[(j + NPF - 1) % NPF], u + NPF - 1)
+            load_frags<NBW, NK, HD>(fr[(j + NPF - 1) % NPF], sbase, min(u + NPF - 1, nunit_real - 1), part_w * NBW, r16, g);
             if (u >= nunit_real) continue;
-            Tile64<VP>& cur = stt;
-            __syncthreads();
-            PA_UNIT_STORE(cur, pre[j])
+            const StateFrags<NBW, NK>& cur = fr[j];
             if constexpr (WPG > 1) {
                 if (kept_f >= 0) {
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) dx_add(dxcol, kept_f + i, kept[i] + handed[w ^ 1][i][lane]);
+                    for (int i = 0; i < 4; ++i) dx_add(dxcol, kept_f + i, kept[i] + handed[(u - 1) & 1][w ^ 1][i][lane]);
                 }
             }
-            __syncthreads();
             UnitJacobian<P, DT> jac;
             jac.begin(xrow, tab, u);
 #pragma unroll
             for (int k = 0; k < NBW; ++k) {
                 const int nb = part_w * NBW + k;
-                Frag sf[NK];
-#pragma unroll
-                for (int ks = 0; ks < NK; ++ks) sf[ks].u = *(const uint4*)&cur.r[16 * nb + r16][32 * ks + 8 * g];
-                const uint2 stail = *(const uint2*)&cur.r[16 * nb + r16][HD + 4 * g];
-                f32x4 c[4];   // rows 16 nb + 4g + r, token 16 ib + r16
+                // only the lanes g = 0 carry the tail's four columns; the other k-slots of that step are zero
+                const uint2 stail = g == 0 ? make_uint2(cur.tail[k][0], cur.tail[k][1]) : make_uint2(0u, 0u);
 #pragma unroll
                 for (int ib = 0; ib < 4; ++ib) {
-                    c[ib] = (f32x4){0.f, 0.f, 0.f, 0.f};
+                    f32x4 c = {0.f, 0.f, 0.f, 0.f};   // rows 16 nb + 4g + r, token 16 ib + r16
 #pragma unroll
-                    for (int ks = 0; ks < NK; ++ks) c[ib] = mfma16(sf[ks].v, yf[ib][ks].v, c[ib]);
-                    c[ib] = mfma16k16(stail, ytail[ib], c[ib]);
-                    *(float4*)&dph[w][16 * ib + r16][4 * g] = make_float4(c[ib][0], c[ib][1], c[ib][2], c[ib][3]);
+                    for (int ks = 0; ks < NK; ++ks) {
+                        Frag sfk;
+                        sfk.q = cur.sf[k][ks];
+                        c = mfma16(sfk.v, yf[ib][ks].v, c);
+                    }
+                    c = mfma16k16(stail, ytail[ib], c);
+                    *(float4*)&dph[w][16 * ib + r16][4 * g] = make_float4(c[0], c[1], c[2], c[3]);
                 }
                 wave_sync();
                 float A[16];
@@ -739,19 +759,19 @@ __global__ __launch_bounds__(128 * dphi_waves_per_group<HD>()) void k_tiled_dphi
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     kept[i] = part_w ? jac.dR[4 + i] : jac.dR[i];
-                    handed[w][i][lane] = part_w ? jac.dR[i] : jac.dR[4 + i];
+                    handed[u & 1][w][i][lane] = part_w ? jac.dR[i] : jac.dR[4 + i];
                 }
                 kept_f = DT * jac.td.t[1] + 4 * part_w;
+                __syncthreads();   // the partner's half of this unit is in place; the buffer is written again two units on
             } else {
                 jac.finish(xrow, dxcol);
             }
         }
     }
     if constexpr (WPG > 1) {
-        __syncthreads();
         if (kept_f >= 0) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) dx_add(dxcol, kept_f + i, kept[i] + handed[w ^ 1][i][lane]);
+            for (int i = 0; i < 4; ++i) dx_add(dxcol, kept_f + i, kept[i] + handed[(nunit_real - 1) & 1][w ^ 1][i][lane]);
         }
         __syncthreads();
     } else {
