@@ -106,9 +106,11 @@ struct RowBF16 {
     const bf16_t* p;
     __device__ __forceinline__ float operator[](int i) const { return bf16_to_f32(p[i]); }
 };
-template <int HD>
+// (float32 where LDS has the room: phi is formed from every feature for every unit; d phi reads few of them per unit
+// and takes the smaller rows, NARROW, for one more workgroup per CU)
+template <int HD, bool NARROW = false>
 struct XStore {
-    static constexpr bool BF = HD >= 64;
+    static constexpr bool BF = NARROW || HD >= 64;
     typedef typename std::conditional<BF, bf16_t, float>::type elem;
     typedef typename std::conditional<BF, RowBF16, RowF32>::type row;
     static constexpr int PITCH = BF ? HD + 2 : HD + 1;   // an odd number of dwords: the lanes' rows start in different banks
@@ -270,12 +272,14 @@ struct UnitJacobian {
 };
 
 // ntok token rows of X (bf16, [.][HD]) -> xs[token][.], float32 or bf16 as XStore<HD> says
-template <int HD, int NT>
-__device__ __forceinline__ void stage_x(typename XStore<HD>::elem (*xs)[XStore<HD>::PITCH], const bf16_t* __restrict__ Xrows, int ntok, int tid) {
+template <int HD, bool NARROW>
+using XRows = typename XStore<HD, NARROW>::elem (*)[XStore<HD, NARROW>::PITCH];
+template <int HD, int NT, bool NARROW = false>
+__device__ __forceinline__ void stage_x(XRows<HD, NARROW> xs, const bf16_t* __restrict__ Xrows, int ntok, int tid) {
     for (int id = tid; id < ntok * (HD / 8); id += NT) {
         const int row = id / (HD / 8), c8 = id % (HD / 8);
         const uint4 u = *(const uint4*)(Xrows + (size_t)row * HD + 8 * c8);
-        if constexpr (XStore<HD>::BF) {
+        if constexpr (XStore<HD, NARROW>::BF) {
             uint32_t* dst = (uint32_t*)&xs[row][8 * c8];   // rows start on a dword, not on 16 bytes
             dst[0] = u.x; dst[1] = u.y; dst[2] = u.z; dst[3] = u.w;
         } else {
@@ -680,7 +684,7 @@ __global__ __launch_bounds__(128 * dphi_waves_per_group<HD>()) void k_tiled_dphi
     constexpr int WPG = dphi_waves_per_group<HD>(), NT = 128 * WPG, NBW = 4 / WPG;
     constexpr int VP = HD + 16, NK = HD / 32, SP = HD + 4, AP = 16 + 4;
     constexpr int NPF = 3;   // units on their way from memory, per wave
-    typedef XStore<HD> XS;
+    typedef XStore<HD, true> XS;
     __shared__ __attribute__((aligned(16))) typename XS::elem xs[128][XS::PITCH];
     __shared__ __attribute__((aligned(16))) float dph[2 * WPG][64][AP];
     __shared__ float dxs[2][HD][64];
@@ -695,7 +699,7 @@ __global__ __launch_bounds__(128 * dphi_waves_per_group<HD>()) void k_tiled_dphi
     StateFrags<NBW, NK> fr[NPF];
 #pragma unroll
     for (int j = 0; j < NPF - 1; ++j) load_frags<NBW, NK, HD>(fr[j], sbase, min(j, nunit_real - 1), part_w * NBW, r16, g);
-    stage_x<HD, NT>(xs, X + (head + tok0) * HD, 128, tid);
+    stage_x<HD, NT, true>(xs, X + (head + tok0) * HD, 128, tid);
 #pragma unroll
     for (int f = 0; f < HD / WPG; ++f) dxs[grp][part_w * (HD / WPG) + f][lane] = 0.f;
     Frag yf[4][NK];
