@@ -48,6 +48,9 @@ CASES = [
     (4, 4, 32, 1, 1, 4096, 128, 1.0, True),     # 32 chunks
     (2, 8, 128, 1, 2, 2048, 256, 0.8, True),    # d = 128: 136 tiles, two 128-token blocks per chunk
     (2, 8, 128, 2, 1, 4096, 256, 1.0, False),   # 16 blocks per head: the blocks of a chunk are dealt 8 apart
+    (2, 8, 128, 2, 4, 512, 256, 1.0, True),     # a multiple of 8 heads: the scan keeps a head's workgroups on one XCD
+    (4, 2, 32, 4, 4, 256, 128, 0.9, False),     # ... 16 heads, 243 workgroups each
+    (3, 4, 64, 8, 1, 384, 128, 1.0, True),      # ... 8 heads, three chunks
 ]
 
 
