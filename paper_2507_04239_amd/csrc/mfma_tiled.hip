@@ -22,10 +22,12 @@
 //
 // States: per (head, chunk) `nunit` units of 64 rows x VP = d + 16 value columns, bf16, row-major; column d
 // carries the normaliser (the values are extended by a one, App. E.4's l), the remaining 15 are zero.  In
-// memory a row keeps only its first SP = d + 4 columns (the kernels are bound by the bytes of the states); the
-// columns beyond live in LDS only, as zeros.
-// MFMA: v_mfma_f32_16x16x32_bf16 throughout; where the contraction runs over the value columns, the 16 columns
-// beyond d fill half of a k = 32 step, the other half is zero.  Operand layouts as in mfma_common.hpp.
+// memory a row keeps only its first SP = d + 4 columns; the columns beyond exist in the read-out's LDS tile
+// only, as zeros.  The read-out (contraction over the rows) passes a unit through LDS for the transposing read;
+// d phi (contraction over the columns) takes its operand fragments, runs of 8 columns of one row, straight
+// from memory.
+// MFMA: v_mfma_f32_16x16x32_bf16 throughout; where the contraction runs over the value columns, the columns
+// beyond d fill part of a k = 32 step, the rest is zero.  Operand layouts as in mfma_common.hpp.
 #include <cmath>
 #include <type_traits>
 
