@@ -100,3 +100,18 @@ def test_tiled_unnormalised_even_degree(p, dt):
     O, Z = orc.fwd_bhtd(Q, K, V, p, None, False, 1.0)
     dQ, dK, dV = orc.bwd_bhtd(Q, K, V, G, p, None, False, 1.0)
     assert_close(got, dict(O=O, Z=Z, dQ=dQ, dK=dK, dV=dV), "bf16", f"tiled un-normalised p={p}")
+
+
+@pytest.mark.parametrize("p,dt,d", [(2, 8, 32), (2, 16, 32), (4, 2, 32), (3, 4, 64), (2, 8, 128)])
+def test_tiled_runs_are_bit_identical(p, dt, d):
+    """No kernel of the family uses atomics or an order that depends on timing: two runs on the same inputs give
+    the same bits.  (A d phi kernel that chained two kinds of MFMA instruction once returned values that differed
+    from run to run in 16 lanes of a wave; this is the check that would have caught it without an oracle.)"""
+    norm = p % 2 == 0
+    Q, K, V, G = inputs.make_qkvg(1, 2, 512, d, seed=5400 + 10 * p + dt + d, dtype="bf16")
+    print("case", (p, dt, d), flush=True)
+    first = run_fwd_bwd(Q, K, V, G, p, 128, "bf16", normalize=norm, impl="tiled", d_tile=dt)
+    for _ in range(3):
+        again = run_fwd_bwd(Q, K, V, G, p, 128, "bf16", normalize=norm, impl="tiled", d_tile=dt)
+        for k in first:
+            assert np.array_equal(first[k], again[k]), (k, (p, dt, d))
