@@ -49,10 +49,17 @@ struct Emb {
     static_assert(R % 16 == 0 && (R >= 64 ? 64 % NR == 0 : 64 % R == 0), "tile shape");
 };
 
-// 64 rows x (W + 8) bf16; pitch (W + 8) / 2 dwords = 4 (mod 8) for W = 48, 64, 80, 144
+// 64 rows x W columns of bf16 in LDS.  What decides the pitch is the transposing read: each of 16 rows is read by 4
+// lanes, 8 dwords in a row; with 64 banks and 32 lanes at a time that is free of conflicts when the pitch is an odd
+// multiple of 8 dwords, which the widths of the state and value tiles (48, 80, 144) are as they stand (measured
+// against 8 columns of padding: bank-conflict cycles of the scan 21 -> 11 %, of the read-out 31 -> 26 %, times
+// unchanged).  The phi tile (64) is also written 16 bytes per token and read row-wise, and does best on all
+// three with 8 columns of padding.
 template <int W>
 struct Tile64 {
-    bf16_t r[64][W + 8];
+    static constexpr int PITCH = W == 64 ? W + 8 : W;
+    static_assert(W == 64 || (W / 2) % 16 == 8, "pitch: an odd multiple of 8 dwords");
+    bf16_t r[64][PITCH];
 };
 
 typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
@@ -68,7 +75,7 @@ __device__ __forceinline__ bf16x8 col_frag_at(const Tile64<W>& t, int s, int col
         bf16x4 h[2];
     } f;
     f.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)p);
-    f.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p + 16 * (W + 8)));
+    f.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p + 16 * Tile64<W>::PITCH));
     return f.v;
 }
 // columns 16 cb .. 16 cb + 15 in order
