@@ -64,18 +64,19 @@ struct Tile64 {
 
 typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
 
-// Operand of a contraction over the tile's 64 rows: k-slots = rows 32 s + 4g .. + 3 and 32 s + 16 + 4g .. + 3,
-// lane r16 = column c0 + r16 % 4 of the four columns its pointer lane r16 / 4 names.  (The transposing read
+// Operand of a contraction over the tile's 64 rows: k-slots = rows 32 s + 8g .. + 7 (so that the other operand,
+// read row-wise, is one 16-byte read per lane), lane r16 = column c0 + r16 % 4 of the four columns its pointer
+// lane r16 / 4 names.  (The transposing read
 // hands lane n of a 16-lane group column n of the 4 x 16 block whose row j the lanes 4j .. 4j+3 point at.)
 template <int W>
 __device__ __forceinline__ bf16x8 col_frag_at(const Tile64<W>& t, int s, int col4, int r16, int g) {
-    const bf16_t* p = &t.r[32 * s + 4 * g + (r16 >> 2)][col4];
+    const bf16_t* p = &t.r[32 * s + 8 * g + (r16 >> 2)][col4];
     union {
         bf16x8 v;
         bf16x4 h[2];
     } f;
     f.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)p);
-    f.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p + 16 * Tile64<W>::PITCH));
+    f.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p + 4 * Tile64<W>::PITCH));
     return f.v;
 }
 // columns 16 cb .. 16 cb + 15 in order
@@ -621,8 +622,7 @@ __global__ __launch_bounds__(128 * readout_waves_per_group<HD>(), 2) void k_tile
                 Frag qf[4];
 #pragma unroll
                 for (int ib = 0; ib < 4; ++ib) {
-                    qf[ib].h[0] = *(const uint2*)&phis[grp].r[16 * ib + r16][32 * s + 4 * g];
-                    qf[ib].h[1] = *(const uint2*)&phis[grp].r[16 * ib + r16][32 * s + 16 + 4 * g];
+                    qf[ib].u = *(const uint4*)&phis[grp].r[16 * ib + r16][32 * s + 8 * g];
                 }
 #pragma unroll
                 for (int vb = 0; vb < NVW; ++vb) {
