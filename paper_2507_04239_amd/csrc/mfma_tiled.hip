@@ -184,13 +184,41 @@ __device__ __forceinline__ void unit_phi(const X x, const TileDesc* __restrict__
     }
 }
 
-// dx[f] += v for the token whose accumulators start at dx (stride 64 floats between features)
-__device__ __forceinline__ void dx_add(float* dx, int f, float v) { dx[64 * f] += v; }
+// Where a token's d accumulators of d phi live; add(f, v): dx[f] += v, f uniform over the wave.
+// LDS: [feature][token], the token's column (stride 64 floats between features), touched by its owner only.
+struct DxLds {
+    float* col;
+    __device__ __forceinline__ void add(int f, float v) { col[64 * f] += v; }
+    __device__ __forceinline__ float get(int f) const { return col[64 * f]; }
+};
+// Registers, indexed relative to a scalar (a vector type keeps a dynamically indexed array out of scratch memory):
+// all 32 features of a token,
+typedef float f32x32 __attribute__((ext_vector_type(32)));
+struct DxRegs32 {
+    f32x32 v;
+    __device__ __forceinline__ void clear() { v = 0.f; }
+    __device__ __forceinline__ void add(int f, float x) { v[f] += x; }
+    __device__ __forceinline__ float get(int f) const { return v[f]; }
+};
+// or, for one of two waves that share a token at d = 128, the 64 features f with f % 8 in [4h, 4h + 4): slot
+// 4 (f / 8) + f % 4
+struct DxRegsHalf {
+    f32x32 lo, hi;
+    __device__ __forceinline__ void clear() { lo = 0.f; hi = 0.f; }
+    __device__ __forceinline__ void add(int f, float x) {
+        const int i = 4 * (f >> 3) + (f & 3);
+        if (i < 32) lo[i] += x;
+        else hi[i - 32] += x;
+    }
+    __device__ __forceinline__ float slot(int i) const { return i < 32 ? lo[i] : hi[i - 32]; }
+};
+template <typename DX>
+__device__ __forceinline__ void dx_add(DX& dx, int f, float v) { dx.add(f, v); }
 
 // chain rule through one side: du[i] = dL/du for the N = DT^PS values of the side whose first position is
 // `pos`; alpha0: index of du[0] within the side (non-zero only for a slice of the left side)
-template <int DT, int PS, int N, typename X>
-__device__ __forceinline__ void side_chain(const X x, const TileDesc& td, int pos, int alpha0, const float (&du)[N], float* dx) {
+template <int DT, int PS, int N, typename X, typename DX>
+__device__ __forceinline__ void side_chain(const X x, const TileDesc& td, int pos, int alpha0, const float (&du)[N], DX& dx) {
     if constexpr (PS == 1) {
 #pragma unroll
         for (int i = 0; i < N; ++i) dx_add(dx, DT * td.t[pos] + alpha0 + i, du[i]);
@@ -250,9 +278,9 @@ struct UnitJacobian {
             for (int b = 0; b < E::NR; ++b) dR[b] = 0.f;
         }
     }
-    template <typename X>
+    template <typename X, typename DX>
     __device__ __forceinline__ void block(const X x, const TileDesc* __restrict__ tab, int unit, int nb, const float (&A)[16],
-                                          float* dx) {
+                                          DX& dx) {
         if constexpr (!SLICE) {
             td = tab[unit * E::TPU + nb];
             a0 = 0;
@@ -275,8 +303,8 @@ struct UnitJacobian {
         side_chain<DT, E::PL, APB>(x, td, 0, a0 + (SLICE ? nb * APB : 0), dL, dx);
         if constexpr (!SLICE) side_chain<DT, E::PR, E::NR>(x, td, E::PL, 0, dR, dx);
     }
-    template <typename X>
-    __device__ __forceinline__ void finish(const X x, float* dx) {
+    template <typename X, typename DX>
+    __device__ __forceinline__ void finish(const X x, DX& dx) {
         if constexpr (SLICE) side_chain<DT, E::PR, E::NR>(x, td, E::PL, 0, dR, dx);
     }
 };
@@ -696,7 +724,12 @@ __global__ __launch_bounds__(128 * dphi_waves_per_group<HD>()) void k_tiled_dphi
     typedef XStore<HD, true> XS;
     __shared__ __attribute__((aligned(16))) typename XS::elem xs[128][XS::PITCH];
     __shared__ __attribute__((aligned(16))) float dph[2 * WPG][64][AP];
-    __shared__ float dxs[2][HD][64];
+    // the accumulators: registers at d = 32 (all features of the thread's token), LDS beyond (64 more registers do
+    // not fit beside the operands at d = 64; at d = 128, with the half of the features that a wave lands in
+    // registers, LDS would allow two workgroups per CU but the kernel ran at 32 ms instead of 22)
+    constexpr bool DXREG = HD == 32;
+    typedef typename std::conditional<HD == 32, DxRegs32, typename std::conditional<DXREG, DxRegsHalf, DxLds>::type>::type DX;
+    __shared__ float dxs[DXREG ? 1 : 2][DXREG ? 1 : HD][64];
     __shared__ float handed[WPG > 1 ? 2 : 1][WPG > 1 ? 4 : 1][4][64];   // [unit parity][wave that wrote it][i][token]
     static_assert(WPG == 1 || (P == 2 && DT == 8), "the split of a unit between two waves is laid out for one 8 x 8 tile per unit");
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6), r16 = lane & 15, g = lane >> 4;
@@ -709,8 +742,14 @@ __global__ __launch_bounds__(128 * dphi_waves_per_group<HD>()) void k_tiled_dphi
 #pragma unroll
     for (int j = 0; j < NPF - 1; ++j) load_frags<NBW, NK, HD>(fr[j], sbase, min(j, nunit_real - 1), part_w * NBW, r16, g);
     stage_x<HD, NT, true>(xs, X + (head + tok0) * HD, 128, tid);
+    DX dx;
+    if constexpr (DXREG) {
+        dx.clear();
+    } else {
+        dx.col = &dxs[grp][0][lane];
 #pragma unroll
-    for (int f = 0; f < HD / WPG; ++f) dxs[grp][part_w * (HD / WPG) + f][lane] = 0.f;
+        for (int f = 0; f < HD / WPG; ++f) dxs[grp][part_w * (HD / WPG) + f][lane] = 0.f;
+    }
     Frag yf[4][NK];
     uint2 ytail[4];
 #pragma unroll
@@ -721,7 +760,6 @@ __global__ __launch_bounds__(128 * dphi_waves_per_group<HD>()) void k_tiled_dphi
         ytail[ib] = *(const uint2*)(yrow + HD);   // pairs with the state's tail: columns d .. d + 3 in the first four k-slots
     }
     const typename XS::row xrow{&xs[64 * grp + lane][0]};
-    float* dxcol = &dxs[grp][0][lane];
     float kept[4] = {0.f, 0.f, 0.f, 0.f};   // WPG > 1: the right side's sums of the last unit that this wave lands
     int kept_f = -1;                        // their first feature (-1: none yet)
     __syncthreads();                        // token rows and cleared accumulators in place
@@ -736,7 +774,7 @@ __global__ __launch_bounds__(128 * dphi_waves_per_group<HD>()) void k_tiled_dphi
             if constexpr (WPG > 1) {
                 if (kept_f >= 0) {
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) dx_add(dxcol, kept_f + i, kept[i] + handed[(u - 1) & 1][w ^ 1][i][lane]);
+                    for (int i = 0; i < 4; ++i) dx_add(dx, kept_f + i, kept[i] + handed[(u - 1) & 1][w ^ 1][i][lane]);
                 }
             }
             UnitJacobian<P, DT> jac;
@@ -766,7 +804,7 @@ __global__ __launch_bounds__(128 * dphi_waves_per_group<HD>()) void k_tiled_dphi
                     A[4 * i] = a4.x; A[4 * i + 1] = a4.y; A[4 * i + 2] = a4.z; A[4 * i + 3] = a4.w;
                 }
                 wave_sync();
-                jac.block(xrow, tab, u, nb, A, dxcol);
+                jac.block(xrow, tab, u, nb, A, dx);
             }
             if constexpr (WPG > 1) {
 #pragma unroll
@@ -777,25 +815,37 @@ __global__ __launch_bounds__(128 * dphi_waves_per_group<HD>()) void k_tiled_dphi
                 kept_f = DT * jac.td.t[1] + 4 * part_w;
                 __syncthreads();   // the partner's half of this unit is in place; the buffer is written again two units on
             } else {
-                jac.finish(xrow, dxcol);
+                jac.finish(xrow, dx);
             }
         }
     }
     if constexpr (WPG > 1) {
         if (kept_f >= 0) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) dx_add(dxcol, kept_f + i, kept[i] + handed[(nunit_real - 1) & 1][w ^ 1][i][lane]);
+            for (int i = 0; i < 4; ++i) dx_add(dx, kept_f + i, kept[i] + handed[(nunit_real - 1) & 1][w ^ 1][i][lane]);
         }
         __syncthreads();
     } else {
         wave_sync();
     }
-    float* out = part + (head + tok0 + 64 * grp + lane) * HD + part_w * (HD / WPG);
-    const float* mine = &dxs[grp][part_w * (HD / WPG)][lane];
+    if constexpr (HD == 32) {
+        float* out = part + (head + tok0 + 64 * grp + lane) * HD;
 #pragma unroll
-    for (int f4 = 0; f4 < HD / WPG / 4; ++f4)
-        *(float4*)(out + 4 * f4) = make_float4(oscale * mine[64 * (4 * f4)], oscale * mine[64 * (4 * f4 + 1)],
-                                               oscale * mine[64 * (4 * f4 + 2)], oscale * mine[64 * (4 * f4 + 3)]);
+        for (int f4 = 0; f4 < HD / 4; ++f4)
+            *(float4*)(out + 4 * f4) = make_float4(oscale * dx.v[4 * f4], oscale * dx.v[4 * f4 + 1], oscale * dx.v[4 * f4 + 2], oscale * dx.v[4 * f4 + 3]);
+    } else if constexpr (DXREG) {
+        float* out = part + (head + tok0 + 64 * grp + lane) * HD + 4 * part_w;   // features 8 a + 4 h + i of the token
+#pragma unroll
+        for (int a = 0; a < HD / 8; ++a)
+            *(float4*)(out + 8 * a) = make_float4(oscale * dx.slot(4 * a), oscale * dx.slot(4 * a + 1), oscale * dx.slot(4 * a + 2), oscale * dx.slot(4 * a + 3));
+    } else {
+        float* out = part + (head + tok0 + 64 * grp + lane) * HD + part_w * (HD / WPG);
+        const float* mine = &dxs[grp][part_w * (HD / WPG)][lane];
+#pragma unroll
+        for (int f4 = 0; f4 < HD / WPG / 4; ++f4)
+            *(float4*)(out + 4 * f4) = make_float4(oscale * mine[64 * (4 * f4)], oscale * mine[64 * (4 * f4 + 1)],
+                                                   oscale * mine[64 * (4 * f4 + 2)], oscale * mine[64 * (4 * f4 + 3)]);
+    }
 }
 #undef PA_UNIT_LOAD
 #undef PA_UNIT_STORE
