@@ -593,7 +593,7 @@ __global__ __launch_bounds__(128 * readout_waves_per_group<HD>(), 2) void k_tile
     constexpr int WPG = readout_waves_per_group<HD>(), NT = 128 * WPG;
     constexpr int VP = HD + 16, NVB = VP / 16, NVW = (NVB + WPG - 1) / WPG, SP = HD + 4, PIECES = 64 * (SP / 4), PPT = (PIECES + NT - 1) / NT;
     constexpr int NPF = units_in_flight<HD>();
-    typedef XStore<HD> XS;
+    typedef XStore<HD, true> XS;   // (bf16 rows: at d = 32 they make room for a fourth workgroup per CU)
     __shared__ __attribute__((aligned(16))) typename XS::elem xs[128][XS::PITCH];
     constexpr int SLOTS = HD >= 128 ? 1 : 2;   // LDS decides how many workgroups share a CU: one slot costs a second barrier per unit
     static_assert(WPG == 1 || SLOTS == 1, "waves that share phi meet at the second barrier of a unit");
@@ -610,7 +610,7 @@ __global__ __launch_bounds__(128 * readout_waves_per_group<HD>(), 2) void k_tile
     for (int j = 0; j < NPF - 1; ++j) PA_UNIT_LOAD(pre[j], j)
     PA_UNIT_ZERO_PAD(stt[0])
     if (SLOTS > 1) PA_UNIT_ZERO_PAD(stt[SLOTS - 1])
-    stage_x<HD, NT>(xs, X + (head + tok0) * HD, 128, tid);
+    stage_x<HD, NT, true>(xs, X + (head + tok0) * HD, 128, tid);
     f32x4 acc[NVW][4];
 #pragma unroll
     for (int vb = 0; vb < NVW; ++vb)
