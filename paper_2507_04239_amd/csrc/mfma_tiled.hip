@@ -106,24 +106,18 @@ __device__ __forceinline__ void wave_sync() {
 }
 
 // ---- the embedding, one thread per token ----------------------------------------------------------------
-// A token's features as they wait in LDS for the thread that owns the token: float32, or - from head size 64
-// on, where LDS decides how many workgroups share a CU - the bf16 values as they came.
-struct RowF32 {
-    const float* p;
-    __device__ __forceinline__ float operator[](int i) const { return p[i]; }
-};
+// A token's features as they wait in LDS for the thread that owns the token.
 struct RowBF16 {
     const bf16_t* p;
     __device__ __forceinline__ float operator[](int i) const { return bf16_to_f32(p[i]); }
 };
-// (float32 where LDS has the room: phi is formed from every feature for every unit; d phi reads few of them per unit
-// and takes the smaller rows, NARROW, for one more workgroup per CU)
-template <int HD, bool NARROW = false>
+// A token's features in LDS: bf16 as they come (rows of float32 were tried where LDS has the room: slower, they
+// cost a workgroup per CU at d = 32)
+template <int HD>
 struct XStore {
-    static constexpr bool BF = NARROW || HD >= 64;
-    typedef typename std::conditional<BF, bf16_t, float>::type elem;
-    typedef typename std::conditional<BF, RowBF16, RowF32>::type row;
-    static constexpr int PITCH = BF ? HD + 2 : HD + 1;   // an odd number of dwords: the lanes' rows start in different banks
+    typedef bf16_t elem;
+    typedef RowBF16 row;
+    static constexpr int PITCH = HD + 2;   // an odd number of dwords: the lanes' rows start in different banks
 };
 
 // x: the token's features.  td: the tile (uniform over the wave).
@@ -309,24 +303,14 @@ struct UnitJacobian {
     }
 };
 
-// ntok token rows of X (bf16, [.][HD]) -> xs[token][.], float32 or bf16 as XStore<HD> says
-template <int HD, bool NARROW>
-using XRows = typename XStore<HD, NARROW>::elem (*)[XStore<HD, NARROW>::PITCH];
-template <int HD, int NT, bool NARROW = false>
-__device__ __forceinline__ void stage_x(XRows<HD, NARROW> xs, const bf16_t* __restrict__ Xrows, int ntok, int tid) {
+// ntok token rows of X (bf16, [.][HD]) -> xs[token][.]
+template <int HD, int NT>
+__device__ __forceinline__ void stage_x(bf16_t (*xs)[XStore<HD>::PITCH], const bf16_t* __restrict__ Xrows, int ntok, int tid) {
     for (int id = tid; id < ntok * (HD / 8); id += NT) {
         const int row = id / (HD / 8), c8 = id % (HD / 8);
         const uint4 u = *(const uint4*)(Xrows + (size_t)row * HD + 8 * c8);
-        if constexpr (XStore<HD, NARROW>::BF) {
-            uint32_t* dst = (uint32_t*)&xs[row][8 * c8];   // rows start on a dword, not on 16 bytes
-            dst[0] = u.x; dst[1] = u.y; dst[2] = u.z; dst[3] = u.w;
-        } else {
-            float* dst = &xs[row][8 * c8];
-            dst[0] = bf_lo(u.x); dst[1] = bf_hi(u.x);
-            dst[2] = bf_lo(u.y); dst[3] = bf_hi(u.y);
-            dst[4] = bf_lo(u.z); dst[5] = bf_hi(u.z);
-            dst[6] = bf_lo(u.w); dst[7] = bf_hi(u.w);
-        }
+        uint32_t* dst = (uint32_t*)&xs[row][8 * c8];   // rows start on a dword, not on 16 bytes
+        dst[0] = u.x; dst[1] = u.y; dst[2] = u.z; dst[3] = u.w;
     }
 }
 
@@ -503,16 +487,8 @@ __global__ __launch_bounds__(64 * scan_units<HD>(), 2) void k_tiled_scan(const b
         for (int q = 0; q < XP; ++q) {
             const int id = min(tid + NT * q, 64 * (HD / 8) - 1);
             const u32x4 u = xr[q];
-            if constexpr (XS::BF) {
-                uint32_t* dst = (uint32_t*)&xs[id / (HD / 8)][8 * (id % (HD / 8))];
-                dst[0] = u[0]; dst[1] = u[1]; dst[2] = u[2]; dst[3] = u[3];
-            } else {
-                float* dst = &xs[id / (HD / 8)][8 * (id % (HD / 8))];
-                dst[0] = bf_lo(u[0]); dst[1] = bf_hi(u[0]);
-                dst[2] = bf_lo(u[1]); dst[3] = bf_hi(u[1]);
-                dst[4] = bf_lo(u[2]); dst[5] = bf_hi(u[2]);
-                dst[6] = bf_lo(u[3]); dst[7] = bf_hi(u[3]);
-            }
+            uint32_t* dst = (uint32_t*)&xs[id / (HD / 8)][8 * (id % (HD / 8))];
+            dst[0] = u[0]; dst[1] = u[1]; dst[2] = u[2]; dst[3] = u[3];
         }
 #pragma unroll
         for (int q = 0; q < YP; ++q) {
@@ -593,7 +569,7 @@ __global__ __launch_bounds__(128 * readout_waves_per_group<HD>(), 2) void k_tile
     constexpr int WPG = readout_waves_per_group<HD>(), NT = 128 * WPG;
     constexpr int VP = HD + 16, NVB = VP / 16, NVW = (NVB + WPG - 1) / WPG, SP = HD + 4, PIECES = 64 * (SP / 4), PPT = (PIECES + NT - 1) / NT;
     constexpr int NPF = units_in_flight<HD>();
-    typedef XStore<HD, true> XS;   // (bf16 rows: at d = 32 they make room for a fourth workgroup per CU)
+    typedef XStore<HD> XS;
     __shared__ __attribute__((aligned(16))) typename XS::elem xs[128][XS::PITCH];
     constexpr int SLOTS = HD >= 128 ? 1 : 2;   // LDS decides how many workgroups share a CU: one slot costs a second barrier per unit
     static_assert(WPG == 1 || SLOTS == 1, "waves that share phi meet at the second barrier of a unit");
@@ -610,7 +586,7 @@ __global__ __launch_bounds__(128 * readout_waves_per_group<HD>(), 2) void k_tile
     for (int j = 0; j < NPF - 1; ++j) PA_UNIT_LOAD(pre[j], j)
     PA_UNIT_ZERO_PAD(stt[0])
     if (SLOTS > 1) PA_UNIT_ZERO_PAD(stt[SLOTS - 1])
-    stage_x<HD, NT, true>(xs, X + (head + tok0) * HD, 128, tid);
+    stage_x<HD, NT>(xs, X + (head + tok0) * HD, 128, tid);
     f32x4 acc[NVW][4];
 #pragma unroll
     for (int vb = 0; vb < NVW; ++vb)
@@ -721,7 +697,7 @@ __global__ __launch_bounds__(128 * dphi_waves_per_group<HD>()) void k_tiled_dphi
     constexpr int WPG = dphi_waves_per_group<HD>(), NT = 128 * WPG, NBW = 4 / WPG;
     constexpr int VP = HD + 16, NK = HD / 32, SP = HD + 4, AP = 16 + 4;
     constexpr int NPF = 3;   // units on their way from memory, per wave
-    typedef XStore<HD, true> XS;
+    typedef XStore<HD> XS;
     __shared__ __attribute__((aligned(16))) typename XS::elem xs[128][XS::PITCH];
     __shared__ __attribute__((aligned(16))) float dph[2 * WPG][64][AP];
     // the accumulators: registers at d = 32 (all features of the thread's token), LDS beyond (64 more registers do
@@ -741,7 +717,7 @@ __global__ __launch_bounds__(128 * dphi_waves_per_group<HD>()) void k_tiled_dphi
     StateFrags<NBW, NK> fr[NPF];
 #pragma unroll
     for (int j = 0; j < NPF - 1; ++j) load_frags<NBW, NK, HD>(fr[j], sbase, min(j, nunit_real - 1), part_w * NBW, r16, g);
-    stage_x<HD, NT, true>(xs, X + (head + tok0) * HD, 128, tid);
+    stage_x<HD, NT>(xs, X + (head + tok0) * HD, 128, tid);
     DX dx;
     if constexpr (DXREG) {
         dx.clear();
