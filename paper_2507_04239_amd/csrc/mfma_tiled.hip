@@ -183,28 +183,14 @@ __device__ __forceinline__ void unit_phi(const X x, const TileDesc* __restrict__
 struct DxLds {
     float* col;
     __device__ __forceinline__ void add(int f, float v) { col[64 * f] += v; }
-    __device__ __forceinline__ float get(int f) const { return col[64 * f]; }
 };
 // Registers, indexed relative to a scalar (a vector type keeps a dynamically indexed array out of scratch memory):
-// all 32 features of a token,
+// all 32 features of a token.
 typedef float f32x32 __attribute__((ext_vector_type(32)));
 struct DxRegs32 {
     f32x32 v;
     __device__ __forceinline__ void clear() { v = 0.f; }
     __device__ __forceinline__ void add(int f, float x) { v[f] += x; }
-    __device__ __forceinline__ float get(int f) const { return v[f]; }
-};
-// or, for one of two waves that share a token at d = 128, the 64 features f with f % 8 in [4h, 4h + 4): slot
-// 4 (f / 8) + f % 4
-struct DxRegsHalf {
-    f32x32 lo, hi;
-    __device__ __forceinline__ void clear() { lo = 0.f; hi = 0.f; }
-    __device__ __forceinline__ void add(int f, float x) {
-        const int i = 4 * (f >> 3) + (f & 3);
-        if (i < 32) lo[i] += x;
-        else hi[i - 32] += x;
-    }
-    __device__ __forceinline__ float slot(int i) const { return i < 32 ? lo[i] : hi[i - 32]; }
 };
 template <typename DX>
 __device__ __forceinline__ void dx_add(DX& dx, int f, float v) { dx.add(f, v); }
@@ -704,7 +690,7 @@ __global__ __launch_bounds__(128 * dphi_waves_per_group<HD>()) void k_tiled_dphi
     // not fit beside the operands at d = 64; at d = 128, with the half of the features that a wave lands in
     // registers, LDS would allow two workgroups per CU but the kernel ran at 32 ms instead of 22)
     constexpr bool DXREG = HD == 32;
-    typedef typename std::conditional<HD == 32, DxRegs32, typename std::conditional<DXREG, DxRegsHalf, DxLds>::type>::type DX;
+    typedef typename std::conditional<DXREG, DxRegs32, DxLds>::type DX;
     __shared__ float dxs[DXREG ? 1 : 2][DXREG ? 1 : HD][64];
     __shared__ float handed[WPG > 1 ? 2 : 1][WPG > 1 ? 4 : 1][4][64];   // [unit parity][wave that wrote it][i][token]
     static_assert(WPG == 1 || (P == 2 && DT == 8), "the split of a unit between two waves is laid out for one 8 x 8 tile per unit");
@@ -804,16 +790,11 @@ __global__ __launch_bounds__(128 * dphi_waves_per_group<HD>()) void k_tiled_dphi
     } else {
         wave_sync();
     }
-    if constexpr (HD == 32) {
+    if constexpr (DXREG) {
         float* out = part + (head + tok0 + 64 * grp + lane) * HD;
 #pragma unroll
         for (int f4 = 0; f4 < HD / 4; ++f4)
             *(float4*)(out + 4 * f4) = make_float4(oscale * dx.v[4 * f4], oscale * dx.v[4 * f4 + 1], oscale * dx.v[4 * f4 + 2], oscale * dx.v[4 * f4 + 3]);
-    } else if constexpr (DXREG) {
-        float* out = part + (head + tok0 + 64 * grp + lane) * HD + 4 * part_w;   // features 8 a + 4 h + i of the token
-#pragma unroll
-        for (int a = 0; a < HD / 8; ++a)
-            *(float4*)(out + 8 * a) = make_float4(oscale * dx.slot(4 * a), oscale * dx.slot(4 * a + 1), oscale * dx.slot(4 * a + 2), oscale * dx.slot(4 * a + 3));
     } else {
         float* out = part + (head + tok0 + 64 * grp + lane) * HD + part_w * (HD / WPG);
         const float* mine = &dxs[grp][part_w * (HD / WPG)][lane];
