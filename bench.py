@@ -229,7 +229,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default=None, help="name from paper_2507_04239_amd.inputs.WORKLOADS")
+    ap.add_argument("--workload", default=None, help="name from paper_2507_04239_amd.inputs.WORKLOADS (the paper's five configurations) or EXTRA_WORKLOADS")
     ap.add_argument("--chunk", type=int, default=None,
                     help="chunk size instead of the workload's own; 0 lets the library choose (attention form or chunked)")
     ap.add_argument("--impl", default="auto", choices=["auto", "generic", "mfma", "resident", "tiled"])
@@ -281,15 +281,15 @@ def sweep(args, name):
     the attention form (one chunk) and the library's own choice, HIP-event median per step."""
     import copy
     from paper_2507_04239_amd import binding, inputs
-    w = inputs.WORKLOADS[name]
+    w = inputs.WORKLOADS[name] if name in inputs.WORKLOADS else inputs.EXTRA_WORKLOADS[name]
     with_bwd = bool(w.get("backward", True)) and not args.forward_only
     rows, seen = [], set()
     sizes = (32, 64, 128, 256, 512, 1024) if w["dtype"] == "f32" else (128, 256, 512, 1024)   # (bf16 below 128: vector ALUs only)
     chunks = [c for c in sizes if w["T"] % c == 0 and c < w["T"]] + [w["T"], 0]
     for chunk in chunks:
         for dt in (0, 2, 4, 8, 16):
-            prob = binding.make_problem(w["B"], w["H"], w["T"], w["d"], w["d"], w["p"], chunk, True, 1.0, w["dtype"], args.impl,
-                                        not args.recompute_states, args.gated, dt)
+            prob = binding.make_problem(w["B"], w["H"], w["T"], w["d"], w["d"], w["p"], chunk, w.get("normalize", True), 1.0, w["dtype"],
+                                        args.impl, not args.recompute_states, args.gated, dt)
             if not binding.power_attn_supported(prob, with_bwd):
                 continue
             key = (binding.power_attn_resolved_chunk(prob), dt, binding.power_attn_state_rows(prob)) if chunk else ("auto", dt)
@@ -328,7 +328,8 @@ def run_workload(args, name, cpu):
     import torch
     from paper_2507_04239_amd import binding, inputs, power_attn_bwd, power_attn_fwd
 
-    w = dict(inputs.WORKLOADS[name])
+    w = dict(inputs.WORKLOADS[name] if name in inputs.WORKLOADS else inputs.EXTRA_WORKLOADS[name])
+    norm = bool(w.get("normalize", True))
     oracle_chunk = w["chunk"]
     if args.chunk is not None:
         w["chunk"] = args.chunk
@@ -342,7 +343,7 @@ def run_workload(args, name, cpu):
     tl = None
     if args.gated:
         tl = torch.from_numpy(inputs.make_log_gates(w["B"], w["H"], w["T"], 1500 + w["position"])).to(dev)
-    prob = binding.make_problem(w["B"], w["H"], w["T"], w["d"], w["d"], p, chunk, True, 1.0, w["dtype"], args.impl, keep,
+    prob = binding.make_problem(w["B"], w["H"], w["T"], w["d"], w["d"], p, chunk, norm, 1.0, w["dtype"], args.impl, keep,
                                 args.gated, args.d_tile)
     w["chunk"] = binding.power_attn_resolved_chunk(prob)      # what the library runs (differs when 0 was asked for)
     ws_bytes = max(binding.power_attn_workspace_bytes(prob, True), binding.power_attn_workspace_bytes(prob, False))
@@ -354,12 +355,12 @@ def run_workload(args, name, cpu):
     with_bwd = bool(w.get("backward", True)) and not args.forward_only    # configs 1 and 2 are forward-only
 
     def fwd():
-        power_attn_fwd(tq, tk, tv, p, chunk, impl=args.impl, workspace=ws, out=O, out_z=Z, keep_state=keep, log_g=tl,
-                       d_tile=args.d_tile)
+        power_attn_fwd(tq, tk, tv, p, chunk, normalize=norm, impl=args.impl, workspace=ws, out=O, out_z=Z, keep_state=keep,
+                       log_g=tl, d_tile=args.d_tile)
 
     def bwd():
-        power_attn_bwd(tq, tk, tv, O, Z, tg, p, chunk, impl=args.impl, workspace=ws, out=grads, keep_state=keep, log_g=tl,
-                       d_tile=args.d_tile)
+        power_attn_bwd(tq, tk, tv, O, Z, tg, p, chunk, normalize=norm, impl=args.impl, workspace=ws, out=grads, keep_state=keep,
+                       log_g=tl, d_tile=args.d_tile)
 
     def step():
         fwd()
@@ -440,7 +441,7 @@ def run_workload(args, name, cpu):
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": w["dtype"], "data": "synthetic",
         "config": {"workload": name, "B": w["B"], "H": w["H"], "T": w["T"], "d": w["d"], "p": p, "chunk": w["chunk"],
-                   "chunk_requested": chunk, "normalize": True, "pass": "fwd+bwd" if with_bwd else "fwd", "impl": args.impl, "d_tile": args.d_tile, "keep_state": keep, "serial_kernels": args.serial_kernels, "gated": args.gated,
+                   "chunk_requested": chunk, "normalize": norm, "pass": "fwd+bwd" if with_bwd else "fwd", "impl": args.impl, "d_tile": args.d_tile, "keep_state": keep, "serial_kernels": args.serial_kernels, "gated": args.gated,
                    "state_rows": binding.power_attn_state_rows(prob)},
         "timing": timing,
         "step_algorithmic_tflop": total_alg / 1e12,

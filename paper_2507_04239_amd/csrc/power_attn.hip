@@ -90,7 +90,9 @@ int auto_chunk(const pa_problem& pr) {
     // d = 128 (p = 2, the tiled kernels): measured at B8 H16 T32768, 118 ms a step chunked against 166 ms for the
     // attention form, whose time grows with the square of T: the two meet near 23k tokens
     const int attn_upto = pr.d == 64 ? (pr.gated ? 2048 : 4096) : 24575;
-    if (may_mfma && (pr.d == 64 || (pr.d == 128 && pr.p == 2)) && mfma_supported(probe, true) == PA_OK && !(attn && pr.T <= attn_upto))
+    // (p = 2 only: for the higher degrees the attention form stays ahead at every length measured - p = 3, d = 64,
+    // T = 16384: 1.3 ms against 6.0 ms chunked; p = 4, d = 32, T = 16384: 2.5 ms against 24 ms)
+    if (may_mfma && pr.p == 2 && (pr.d == 64 || pr.d == 128) && mfma_supported(probe, true) == PA_OK && !(attn && pr.T <= attn_upto))
         return probe.chunk;
     if (attn) return pr.T;
     double D = 1.0;   // C(d + p - 1, p)

@@ -21,6 +21,12 @@ WORKLOADS = {
     "cfg5_bf16_p2_T32768_d128_c256": dict(position=5, B=8, H=16, T=32768, d=128, p=2, chunk=256, dtype="bf16", backward=True),
 }
 HEADLINE = "cfg3_bf16_p2_T65536_d64_c128"
+# Not one of the paper's benchmark configurations: a shape for timing the degree the paper names beside 2 and 4
+# (p = 3, d_tile = 4, Sec. 4.1.1).  Odd degree: un-normalised.  bench.py takes it by name; --all-configs does not run it.
+EXTRA_WORKLOADS = {
+    "extra_bf16_p3_T16384_d64_c128": dict(position=6, B=1, H=4, T=16384, d=64, p=3, chunk=128, dtype="bf16", backward=True,
+                                          normalize=False),
+}
 
 
 def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
@@ -71,7 +77,7 @@ def make_qkvg(B: int, H: int, T: int, d: int, seed: int, dtype: str = "bf16", v:
 
 def make_workload(name: str, with_grad: bool | None = None):
     """Inputs of a named workload; the seed is 1000 + its position."""
-    w = WORKLOADS[name]
+    w = WORKLOADS[name] if name in WORKLOADS else EXTRA_WORKLOADS[name]
     wg = w["backward"] if with_grad is None else with_grad
     return make_qkvg(w["B"], w["H"], w["T"], w["d"], 1000 + w["position"], w["dtype"], with_grad=wg)
 

@@ -87,6 +87,8 @@ def test_automatic_chunk_choice():
     assert rc(mk(8, 16, 16384, 128, 128, 2, 0)) == 16384
     assert rc(mk(8, 16, 32768, 128, 128, 2, 0, gated=True)) == 32768
     assert rc(mk(8, 16, 32768, 128, 128, 4, 0)) == 32768
+    # p = 3, d = 64: chunked matrix-core kernels exist (tiled), the attention form is the faster one at these lengths
+    assert rc(mk(1, 4, 16384, 64, 64, 3, 0, normalize=False)) == 16384
     # p = 4, d = 32: the state is 52360 x 33 per head, the attention form stays cheaper far beyond 16k tokens
     assert rc(mk(2, 8, 16384, 32, 32, 4, 0, dtype="bf16")) == 16384
     # float32, small head: state 136 x 17; chunked from a few hundred tokens on
