@@ -87,12 +87,15 @@ int auto_chunk(const pa_problem& pr) {
     // the chunked kernels, on the sequence rounded up to whole chunks when it is ragged (see Padding)
     probe.chunk = pr.T % 256 == 0 || pr.T % 128 != 0 ? 256 : 128;
     probe.T = (pr.T + probe.chunk - 1) / probe.chunk * probe.chunk;
-    // d = 128 (p = 2, the tiled kernels): measured at B8 H16 T32768, 118 ms a step chunked against 166 ms for the
-    // attention form, whose time grows with the square of T: the two meet near 23k tokens
-    const int attn_upto = pr.d == 64 ? (pr.gated ? 2048 : 4096) : 24575;
-    // (p = 2 only: for the higher degrees the attention form stays ahead at every length measured - p = 3, d = 64,
-    // T = 16384: 1.3 ms against 6.0 ms chunked; p = 4, d = 32, T = 16384: 2.5 ms against 24 ms)
-    if (may_mfma && pr.p == 2 && (pr.d == 64 || pr.d == 128) && mfma_supported(probe, true) == PA_OK && !(attn && pr.T <= attn_upto))
+    // p = 2 at the other head sizes runs chunked on the tiled kernels.  d = 128: measured at B8 H16 T32768, 110 ms a
+    // step chunked against 166 ms for the attention form, whose time grows with the square of T: the two meet near
+    // 23k tokens.  d = 32 (B4 H8): 0.24 against 0.15 ms at T = 2048, 0.75 against 1.20 ms at 8192, 2.2 against 6.5 ms
+    // at 32768.  For the higher degrees the attention form stays ahead at every length measured (p = 3, d = 64:
+    // 1.3 against 6.0 ms at T = 16384, 39 against 61 ms at 131072; p = 4, d = 32: 2.5 against 24 ms at 16384, 50
+    // against 101 ms at 131072).
+    const int attn_upto = pr.d == 128 ? 24575 : (pr.gated ? 2048 : 4096);
+    if (may_mfma && pr.p == 2 && (pr.d == 32 || pr.d == 64 || pr.d == 128) && mfma_supported(probe, true) == PA_OK &&
+        !(attn && pr.T <= attn_upto))
         return probe.chunk;
     if (attn) return pr.T;
     double D = 1.0;   // C(d + p - 1, p)

@@ -115,3 +115,26 @@ def test_tiled_runs_are_bit_identical(p, dt, d):
         again = run_fwd_bwd(Q, K, V, G, p, 128, "bf16", normalize=norm, impl="tiled", d_tile=dt)
         for k in first:
             assert np.array_equal(first[k], again[k]), (k, (p, dt, d))
+
+
+@pytest.mark.parametrize("d,T", [(32, 4096 + 512 + 37), (128, 24576 + 256 + 5)])
+def test_automatic_chunk_runs_the_tiled_kernels_on_long_sequences(d, T):
+    """chunk = 0 at p = 2, d = 32 and d = 128, at a length beyond the attention form's reach that no chunk divides:
+    chunk 256 on the tiled kernels, on the sequence padded with zero rows; sampled rows of O and dQ by the
+    definition, every output finite."""
+    from paper_2507_04239_amd import binding
+    from gpu_util import TOL, rel_l2
+    prob = binding.make_problem(1, 1, T, d, d, 2, 0)
+    assert binding.power_attn_resolved_chunk(prob) == 256
+    assert binding.power_attn_state_rows(prob) == (d // 8) * (d // 8 + 1) // 2 * 64
+    Q, K, V, G = inputs.make_qkvg(1, 1, T, d, seed=5300 + d, dtype="bf16")
+    print("case", (d, T), flush=True)
+    got = run_fwd_bwd(Q, K, V, G, 2, 0, "bf16")
+    q, k, v, g = (a[0, 0].astype(np.float64) for a in (Q, K, V, G))
+    rows = [0, 255, 256, 2047, 4096, T - 300, T - 2, T - 1]
+    o_ref = np.stack([orc.fwd_row(q, k, v, i, 2)[0] for i in rows])
+    dq_ref = np.stack([orc.bwd_dq_row(q, k, v, g, i, 2) for i in rows])
+    assert rel_l2(got["O"][0, 0][rows], o_ref) <= TOL["bf16"]
+    assert rel_l2(got["dQ"][0, 0][rows], dq_ref) <= TOL["bf16"]
+    for name in ("O", "Z", "dQ", "dK", "dV"):
+        assert np.isfinite(got[name]).all(), name

@@ -87,6 +87,10 @@ def test_automatic_chunk_choice():
     assert rc(mk(8, 16, 16384, 128, 128, 2, 0)) == 16384
     assert rc(mk(8, 16, 32768, 128, 128, 2, 0, gated=True)) == 32768
     assert rc(mk(8, 16, 32768, 128, 128, 4, 0)) == 32768
+    # d = 32, p = 2: the tiled chunked kernels beyond 4096 tokens
+    assert rc(mk(4, 8, 8192, 32, 32, 2, 0)) == 256
+    assert rc(mk(4, 8, 4096, 32, 32, 2, 0)) == 4096
+    assert rc(mk(4, 8, 8192, 32, 32, 2, 0, gated=True)) == 8192     # (they take no gates)
     # p = 3, d = 64: chunked matrix-core kernels exist (tiled), the attention form is the faster one at these lengths
     assert rc(mk(1, 4, 16384, 64, 64, 3, 0, normalize=False)) == 16384
     # p = 4, d = 32: the state is 52360 x 33 per head, the attention form stays cheaper far beyond 16k tokens
