@@ -263,7 +263,7 @@ def main():
     from paper_2507_04239_amd import inputs
     if args.decode_batch > 0:
         name = args.workload or inputs.HEADLINE
-        return decode_bench(args, name, dict(inputs.WORKLOADS[name]))
+        return decode_bench(args, name, dict(inputs.WORKLOADS[name] if name in inputs.WORKLOADS else inputs.EXTRA_WORKLOADS[name]))
     if args.sweep:
         return sweep(args, args.workload or inputs.HEADLINE)
     if args.all_configs:
