@@ -508,9 +508,9 @@ __global__ __launch_bounds__(64 * scan_units<HD>(), 2) void k_tiled_scan(const b
 }
 
 // ---- query-state: part[t][:] = S_chunk(t)^T phi(x_t) -------------------------------------------------------
-// A workgroup of two waves takes 128 tokens of one chunk (64 per wave, O^T accumulators in registers) and
-// streams that chunk's state, unit by unit: NPF units are on their way from memory in registers while one is
-// being worked on from a two-slot LDS ring.  zpart (may be null) receives the normaliser column's share.
+// A workgroup takes 128 tokens of one chunk (two waves of 64 tokens, O^T accumulators in registers; two waves
+// per 64 tokens at d = 128, see below) and streams that chunk's state, unit by unit: NPF units are on their way
+// from memory in registers while one is being worked on from LDS (two slots taken in turn, one from d = 128 on).  zpart (may be null) receives the normaliser column's share.
 // Also serves dV: the state gradient read out with phi(k).
 // Workgroups are dealt to the 8 XCDs round-robin by their linear id, each XCD with an L2 of its own.  The m
 // 128-token blocks of one chunk stream the same state, so they are given ids 8 apart: same XCD, about the
@@ -852,8 +852,8 @@ bool tiled_shape_ok(int p, int d, int dt) {
     return false;
 }
 
-// 8 for p = 2 and 4 for p = 3 (the widths Sec. 4.1.1 names); p = 4 at d = 32: 2 (62016 state rows against 84480 with 4,
-// and the kernels are bound by the bytes of the states: measured 31.8 against 37.9 ms per step on B2 H8 T16384)
+// 8 for p = 2 and 4 for p = 3 (the widths Sec. 4.1.1 names); p = 4 at d = 32: 2 (62016 state rows against 84480 with 4:
+// measured 24 against 28 ms per step on B2 H8 T16384)
 int tiled_default_dt(int p) { return p == 2 ? 8 : p == 3 ? 4 : 2; }
 
 TiledPlan tiled_plan(int p, int d, int dt) {
